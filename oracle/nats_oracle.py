@@ -1,0 +1,232 @@
+"""CPU oracle for the NAtS-L hybrid attention operator (TEST INFRASTRUCTURE ONLY).
+
+Plain, slow, fp64 numpy.  Nothing in the product path may import this file;
+only tests, the smoke check and the benchmark's cpu-baseline leg do.  It shares
+no code with the HIP kernels.
+
+What it computes, per (batch, head) independently, for tokens t = 0..L-1 with
+q_t, k_t in R^{d_k}, v_t in R^{d_v}, decay alpha_t, write strength beta_t and a
+hard routing mask m_t (1 = softmax token, 0 = linear token):
+
+  * linear branch  -- the Gated DeltaNet recurrence of Section 4.3 (Eq. 19),
+    written only for linear tokens (Section 4.1, the state-update rule that
+    skips non-linear tokens, Eq. 14) while the decay alpha_t is applied at every
+    token (Eq. 20); every query reads the state: o_t = S_t q_t (Eq. 5, Eq. 10).
+  * softmax branch -- Eq. 11 with the column mask of Eq. 12: query i attends
+    to key j iff j is a softmax token and i >= j.
+  * merge          -- plain sum (Section 4.1) or the RMS-normalised weighted sum
+    of Eq. 21 with caller-supplied weights.
+
+Readings taken where the paper is silent (all listed in the design notes):
+routing is applied per token; the state is S[d_v, d_k] and acts as S q; decay
+is applied before the write; an empty softmax key set gives output 0 and
+lse = -inf; RMSNorm has no gain and Norm(0) = 0.
+
+Parity pins: every function below is pinned by tests/test_oracle_pins.py
+(library softmax attention, closed forms of the delta rule, explicit
+transition-matrix products, Fig. 1c's support pattern, brute force).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- #
+# mask bookkeeping (integer, exactly one correct answer)
+# --------------------------------------------------------------------------- #
+def compaction(mask):
+    """cnt[t] = number of softmax tokens among 0..t; idx[c] = position of the c-th one.
+
+    Column sets t_nla / t_la of Eq. 12-13 as index lists.
+    """
+    m = (np.asarray(mask).reshape(-1) != 0)
+    cnt = np.zeros(m.shape[0], dtype=np.int32)
+    idx = []
+    running = 0
+    for t in range(m.shape[0]):
+        if m[t]:
+            idx.append(t)
+            running += 1
+        cnt[t] = running
+    return cnt, np.asarray(idx, dtype=np.int32), running
+
+
+# --------------------------------------------------------------------------- #
+# linear branch: token-recurrent Gated DeltaNet (Eq. 19 + Eq. 14 + Eq. 20)
+# --------------------------------------------------------------------------- #
+def gdn_recurrent(q, k, v, alpha, beta, mask, S0=None, la_scale=1.0, decay_on_softmax=True):
+    """Returns (o_la [L,d_v], S_final [d_v,d_k]).
+
+    decay_on_softmax=False is the ablation that freezes the state on softmax
+    tokens (Table 4, the variant without linear-attention decay); the method itself uses True.
+    """
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    alpha = np.asarray(alpha, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    L, d_k = k.shape
+    d_v = v.shape[1]
+    S = np.zeros((d_v, d_k)) if S0 is None else np.array(S0, dtype=np.float64)
+    o = np.zeros((L, d_v))
+    for t in range(L):
+        linear = (mask[t] == 0)
+        if linear or decay_on_softmax:
+            S = alpha[t] * S                       # decay at every token (Eq. 20)
+        if linear:                                 # write only linear tokens (Eq. 14)
+            pred = S @ k[t]                        # what the decayed state returns for k_t
+            S = S + beta[t] * np.outer(v[t] - pred, k[t])   # Eq. 19 expanded
+        o[t] = la_scale * (S @ q[t])               # Eq. 5
+    return o, S
+
+
+# --------------------------------------------------------------------------- #
+# softmax branch: brute force over the softmax-token columns (Eq. 11-12)
+# --------------------------------------------------------------------------- #
+def softmax_branch(q, k, v, mask, scale):
+    """Returns (o_nla [L,d_v], lse [L]); rows with no visible key give 0 / -inf."""
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    L = q.shape[0]
+    o = np.zeros((L, v.shape[1]))
+    lse = np.full(L, -np.inf)
+    for t in range(L):
+        J = np.flatnonzero(np.asarray(mask[:t + 1]) != 0)   # softmax columns j <= t
+        if J.size == 0:
+            continue
+        s = scale * (k[J] @ q[t])
+        smax = s.max()
+        e = np.exp(s - smax)
+        z = e.sum()
+        o[t] = (e / z) @ v[J]
+        lse[t] = smax + np.log(z)
+    return o, lse
+
+
+# --------------------------------------------------------------------------- #
+# merge of the two branch outputs (Section 4.1 sum; Eq. 21)
+# --------------------------------------------------------------------------- #
+def rms_norm_rows(x, eps):
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+
+
+def combine(o_la, o_nla, mode=0, w_nla=None, w_la=None, eps=1e-6):
+    if mode == 0:
+        return o_la + o_nla
+    L = o_la.shape[0]
+    w_nla = np.full(L, 0.5) if w_nla is None else np.asarray(w_nla, dtype=np.float64)
+    w_la = np.full(L, 0.5) if w_la is None else np.asarray(w_la, dtype=np.float64)
+    return w_nla[:, None] * rms_norm_rows(o_nla, eps) + w_la[:, None] * rms_norm_rows(o_la, eps)
+
+
+# --------------------------------------------------------------------------- #
+# whole operator for one (batch, head), and over [B,H,...]
+# --------------------------------------------------------------------------- #
+def hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
+                w_nla=None, w_la=None, eps=1e-6, S0=None):
+    d_k = np.asarray(q).shape[-1]
+    scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
+    o_la, S = gdn_recurrent(q, k, v, alpha, beta, mask, S0=S0, la_scale=la_scale)
+    o_nla, lse = softmax_branch(q, k, v, mask, scale)
+    o = combine(o_la, o_nla, mode, w_nla, w_la, eps)
+    cnt, idx, n_s = compaction(mask)
+    return {"O": o, "O_la": o_la, "O_nla": o_nla, "lse": lse, "S": S,
+            "cnt": cnt, "idx": idx, "n_s": n_s}
+
+
+def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
+               w_nla=None, w_la=None, eps=1e-6, S0=None):
+    """All (b,h) of [B,H,L,d] inputs; returns dict of stacked fp64 arrays (idx as nested lists)."""
+    B, H, L, _ = np.asarray(Q).shape
+    d_v = np.asarray(V).shape[-1]
+    out = {"O": np.zeros((B, H, L, d_v)), "O_la": np.zeros((B, H, L, d_v)),
+           "O_nla": np.zeros((B, H, L, d_v)), "lse": np.zeros((B, H, L)),
+           "S": np.zeros((B, H, d_v, np.asarray(K).shape[-1])),
+           "cnt": np.zeros((B, H, L), dtype=np.int32), "n_s": np.zeros((B, H), dtype=np.int32),
+           "idx": [[None] * H for _ in range(B)]}
+    for b in range(B):
+        for h in range(H):
+            r = hybrid_head(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask[b, h],
+                            softmax_scale, la_scale, mode,
+                            None if w_nla is None else w_nla[b, h],
+                            None if w_la is None else w_la[b, h], eps,
+                            None if S0 is None else S0[b, h])
+            for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
+                out[key][b, h] = r[key]
+            out["idx"][b][h] = r["idx"]
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# one decode step for one (batch, head) (Section 4.1, per-token generation)
+# --------------------------------------------------------------------------- #
+def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
+                softmax_scale=None, la_scale=1.0, mode=0, w_nla=0.5, w_la=0.5, eps=1e-6):
+    """One token.  S [d_v,d_k] fp64; k_cache/v_cache [cap,d] with cache_len live rows.
+
+    Returns (o [d_v], S_new, k_cache, v_cache, cache_len_new, overflow).  A softmax
+    token is appended to the cache before attending (it sees itself: Eq. 12, i >= j);
+    a linear token is written into the state.  If the cache is full the token is
+    not stored and overflow=True; the output then covers the existing rows only.
+    """
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    scale = (1.0 / np.sqrt(q.shape[0])) if softmax_scale is None else softmax_scale
+    S = float(alpha) * np.array(S, dtype=np.float64)
+    overflow = False
+    if m == 0:
+        S = S + float(beta) * np.outer(v - S @ k, k)
+    else:
+        if cache_len < k_cache.shape[0]:
+            k_cache = np.array(k_cache, dtype=np.float64)
+            v_cache = np.array(v_cache, dtype=np.float64)
+            k_cache[cache_len] = k
+            v_cache[cache_len] = v
+            cache_len = cache_len + 1
+        else:
+            overflow = True
+    o_la = la_scale * (S @ q)
+    if cache_len > 0:
+        s = scale * (np.asarray(k_cache[:cache_len], dtype=np.float64) @ q)
+        e = np.exp(s - s.max())
+        o_nla = (e / e.sum()) @ np.asarray(v_cache[:cache_len], dtype=np.float64)
+    else:
+        o_nla = np.zeros_like(o_la)
+    if mode == 0:
+        o = o_la + o_nla
+    else:
+        o = (w_nla * rms_norm_rows(o_nla[None], eps)[0] + w_la * rms_norm_rows(o_la[None], eps)[0])
+    return o, S, k_cache, v_cache, cache_len, overflow
+
+
+# --------------------------------------------------------------------------- #
+# second, independent form of the linear branch: chunkwise (Eq. 6-7 shape)
+# --------------------------------------------------------------------------- #
+def gdn_chunkwise(q, k, v, alpha, beta, mask, C, S0=None, la_scale=1.0):
+    """Chunkwise-parallel form of the same recurrence (Section 3, Eq. 6-7).
+
+    With b'_t = beta_t * (1 - m_t) and, inside a chunk, g_r = sum_{i<=r} log alpha_i:
+      D[r,i] = exp(g_r - g_i) (i <= r),  A = strict_lower(diag(b') (K K^T . D)),
+      T = (I + A)^{-1},  U~ = T diag(b') V,  W = T diag(b' exp(g)) K,
+      U = U~ - W S0^T,  O = diag(exp(g)) Q S0^T + ((Q K^T) . D) U,
+      S1 = exp(g_C) S0 + U^T diag(exp(g_C - g)) K.
+    Used only to pin "chunkwise == token-recurrent" and independence of C.
+    """
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    alpha = np.asarray(alpha, dtype=np.float64)
+    bp = np.asarray(beta, dtype=np.float64) * (np.asarray(mask) == 0)
+    L, d_k = k.shape
+    d_v = v.shape[1]
+    assert L % C == 0
+    S = np.zeros((d_v, d_k)) if S0 is None else np.array(S0, dtype=np.float64)
+    o = np.zeros((L, d_v))
+    for c0 in range(0, L, C):
+        sl = slice(c0, c0 + C)
+        Kc, Vc, Qc = k[sl], v[sl], q[sl]
+        g = np.cumsum(np.log(alpha[sl]))
+        D = np.tril(np.exp(g[:, None] - g[None, :]))
+        A = np.tril(bp[sl][:, None] * (Kc @ Kc.T) * D, -1)
+        T = np.linalg.inv(np.eye(C) + A)
+        Ut = T @ (bp[sl][:, None] * Vc)
+        W = T @ ((bp[sl] * np.exp(g))[:, None] * Kc)
+        U = Ut - W @ S.T
+        o[sl] = la_scale * (np.exp(g)[:, None] * (Qc @ S.T) + ((Qc @ Kc.T) * D) @ U)
+        S = np.exp(g[-1]) * S + U.T @ (np.exp(g[-1] - g)[:, None] * Kc)
+    return o, S
