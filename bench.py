@@ -1,0 +1,139 @@
+"""Benchmark of the NAtS-L hybrid-attention forward on one MI355X.
+
+One step = one pass of the whole hot path (mask scan + K/V compaction, linear branch,
+softmax branch over the compacted keys, merge) over one batch of seeded synthetic input
+already resident in HBM.  Workload: B=2, H=16, L=8192, d=128, C=64, bf16, 5% softmax tokens.
+Prints one JSON line: whole-job tokens/s (tokens = B*L), the roofline of the dominant kernel
+(HIP-event timing of each kernel inside the timed region) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "alu_f32": (157.3, "TFLOP/s")}
+
+
+def kernel_work(name, cfg, sum_cnt):
+    """Algorithmic work of one launch of each kernel at this workload -> (bound, amount, unit-scale).
+
+    bytes for HBM-bound kernels, FLOP for arithmetic-bound ones (counts documented in the design doc)."""
+    BH, L, d = cfg.B * cfg.H, cfg.L, cfg.d
+    n_tok = BH * L
+    esz = 2 if cfg.dtype == "bf16" else 4
+    if name == "scan_compact":      # mask in, cnt + idx out, gathered K/V rows in and out
+        n_soft = int(round(cfg.p_softmax * n_tok))
+        return "hbm", n_tok * (1 + 4) + n_soft * (4 + 4 * d * esz)
+    if name == "gdn_recurrent":     # per row-token: decay d, S.k 2d, rank-1 2d, S.q 2d (fp32 VALU)
+        return "alu_f32", n_tok * d * (7 * d)
+    if name == "softmax_fp32":      # QK^T and PV: 4 d FLOP per visible (query, key) pair (fp32 VALU)
+        return "alu_f32", 4 * d * sum_cnt
+    if name == "gdn_chunk_prep":    # KK^T, QK^T, T.K, T.V: 4 x 2 C d FLOP per token + solve
+        return "mfma_bf16", n_tok * (8 * cfg.C * d + cfg.C * cfg.C // 3)
+    if name == "gdn_chunk_scan":    # W S^T, Q S^T, U^T K: 3 x 2 d^2, and P U: 2 C d, per token
+        return "mfma_bf16", n_tok * (6 * d * d + 2 * cfg.C * d)
+    if name == "flash_softmax":
+        return "mfma_bf16", 4 * d * sum_cnt
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2602_03681_amd as nats
+    from paper_2602_03681_amd import binding as nb
+    from nats_inputs import CONFIGS, make_config_inputs
+
+    cfg = CONFIGS["cfg2_headline_bf16"]
+    x = make_config_inputs(cfg)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    g = {k: torch.from_numpy(v).to(dev) for k, v in x.items()}
+    Q, K, V = (g[k].to(torch.bfloat16) for k in ("Q", "K", "V"))
+    alpha, beta, mask = g["alpha"], g["beta"], g["mask"]
+    params = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16)
+    ws = torch.empty(nb.fwd_workspace_bytes(params), dtype=torch.uint8, device=dev)
+    O = torch.empty_like(Q)
+    sum_cnt = int(np.cumsum(x["mask"] != 0, axis=-1, dtype=np.int64).sum())
+
+    def step():
+        nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, out=O, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        nb.profile_begin(64 * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernels = {} if args.no_kernel_events else nb.profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = cfg.B * cfg.L
+    value = tokens / (ms_per_step * 1e-3)
+
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
+        work = kernel_work(dom, cfg, sum_cnt)
+        if work is not None:
+            bound, amount = work
+            peak, unit = PEAK[bound]
+            achieved = amount / (kernels[dom]["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+            roofline = {"kernel": dom, "bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
+                        "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                        "frac": round(achieved / peak, 5), "traffic": None,
+                        "avg_kernel_ms": round(kernels[dom]["avg_ms"], 4)}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import c_oracle
+        heads = 8       # first 8 heads of batch 0, all L tokens: each (b,h) is an independent unit
+        xs = {k: np.ascontiguousarray(v[:1, :heads]) for k, v in x.items()}
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 20:
+            c0 = time.perf_counter()
+            c_oracle.fwd(**xs, want=())
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        head_tok_per_s = reps * heads * cfg.L / t_cpu
+        cpu_baseline = {"value": round(head_tok_per_s / cfg.H, 1), "unit": "tokens/s",
+                        "cores": c_oracle.threads(), "kind": "oracle",
+                        "sample": f"{heads} of {cfg.B * cfg.H} (batch, head) pairs, all {cfg.L} tokens, "
+                                  f"{reps} repetitions; rate scaled by 1/H to whole tokens"}
+
+    out = {"metric": "hybrid_attn_fwd_tokens_per_s", "value": round(value, 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": "cfg2_headline_bf16: B=2 H=16 L=8192 d=128 C=64 bf16, mask~Bernoulli(0.05)",
+                      "global_batch": cfg.B, "seq_len": cfg.L, "heads": cfg.H, "d_head": cfg.d,
+                      "parallelism": "single GPU"},
+           "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kernels.items()},
+           "roofline": roofline, "cpu_baseline": cpu_baseline}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/* nats.h -- C ABI of the NAtS-L hybrid attention operator for AMD MI355X (gfx950).
+ *
+ * One layer of token-level hybrid attention (paper Section 4.1 and 4.3): a hard
+ * per-token routing mask m (1 = softmax token, 0 = linear token) sends each
+ * key/value either into a Gated DeltaNet state (Eq. 19; written only for linear
+ * tokens, Eq. 14; decayed at every token, Eq. 20) or into the softmax key set
+ * (Eq. 11 under the column mask of Eq. 12).  Every query reads both, and the
+ * two outputs are merged by a plain sum (Section 4.1) or by Eq. 21.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, frees nothing and never synchronises: all work is
+ *     enqueued on the given HIP stream (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns immediately.
+ *   - Arguments are validated on the host before anything is launched; a bad
+ *     argument returns a negative nats_status and launches nothing.
+ *     nats_last_error() then describes the problem (thread-local string).
+ *   - Tensors are dense, row-major, in the layouts written below; data pointers
+ *     must be 16-byte aligned; outputs must not alias inputs.
+ *   - Data-dependent sizes (the number of softmax tokens per head) stay on the
+ *     device; nothing is read back to the host.
+ *   - Results are deterministic: no floating-point atomics.
+ */
+#ifndef NATS_H_
+#define NATS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nats_status {
+    NATS_OK = 0,
+    NATS_ERR_NULL = -1,        /* a required pointer is NULL */
+    NATS_ERR_SHAPE = -2,       /* a size is out of range (e.g. L % C != 0) */
+    NATS_ERR_DTYPE = -3,       /* unknown dtype code */
+    NATS_ERR_ALIGN = -4,       /* a data pointer is not 16-byte aligned */
+    NATS_ERR_WORKSPACE = -5,   /* workspace missing or smaller than *_workspace_bytes() */
+    NATS_ERR_UNSUPPORTED = -6, /* legal request this build has no kernel for */
+    NATS_ERR_HIP = -7          /* a HIP launch failed; message holds hipGetErrorString */
+} nats_status;
+
+typedef enum nats_dtype { NATS_F32 = 0, NATS_BF16 = 1 } nats_dtype;
+
+/* Arithmetic used inside the kernels.
+ *   NATS_MATH_AUTO : f32 tensors -> fp32 kernels; bf16 tensors -> chunkwise bf16 MFMA kernels
+ *                    with fp32 state and accumulation.
+ *   NATS_MATH_FP32 : fp32 arithmetic for either tensor dtype (token-recurrent state update,
+ *                    fp32 dot products); slower, used for tight-tolerance work. */
+typedef enum nats_math { NATS_MATH_AUTO = 0, NATS_MATH_FP32 = 1 } nats_math;
+
+/* ------------------------------------------------------------------------- *
+ * Prefill / training forward
+ * ------------------------------------------------------------------------- */
+typedef struct nats_fwd_params {
+    int32_t B, H;          /* batch, heads (each (b,h) has its own mask: Section 4.3)          */
+    int32_t L;             /* tokens; must be a positive multiple of C                          */
+    int32_t d;             /* head dim, d_k = d_v = d, 64 or 128                                */
+    int32_t C;             /* chunk size of the chunkwise linear branch (Eq. 6-7); 64           */
+    int32_t dtype;         /* nats_dtype of Q, K, V, O                                          */
+    float softmax_scale;   /* logits = scale * q.k ; <= 0 selects 1/sqrt(d)                     */
+    float la_scale;        /* o_la = la_scale * S q (Eq. 5 has none); <= 0 selects 1            */
+    int32_t combine_mode;  /* 0: O = O_la + O_nla (Section 4.1).  1: Eq. 21,
+                              O = w_nla * RMSNorm(O_nla) + w_la * RMSNorm(O_la), no gain        */
+    float rms_eps;         /* RMSNorm epsilon for combine_mode 1; <= 0 selects 1e-6             */
+    int32_t math;          /* nats_math                                                         */
+} nats_fwd_params;
+
+/* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */
+typedef struct nats_fwd_extra {
+    const float* w_nla;         /* in  [B,H,L] weights of Eq. 21 (NULL -> 0.5)                   */
+    const float* w_la;          /* in  [B,H,L]                    (NULL -> 0.5)                   */
+    const float* initial_state; /* in  [B,H,d,d] f32 state S[d_v][d_k] before token 0 (NULL -> 0)*/
+    float* final_state;         /* out [B,H,d,d] f32 state after token L-1                       */
+    void* Kc;                   /* out [B,H,cap,d] softmax-token keys in order of position:      */
+    void* Vc;                   /* out [B,H,cap,d] the decode KV cache (rows >= cap are dropped) */
+    int32_t cap;                /* rows per (b,h) in Kc / Vc                                     */
+    int32_t* n_s;               /* out [B,H]   number of softmax tokens                          */
+    int32_t* idx;               /* out [B,H,L] idx[c] = position of the c-th softmax token;
+                                   entries c >= n_s are left untouched                           */
+    int32_t* cnt;               /* out [B,H,L] cnt[t] = number of softmax tokens among 0..t      */
+    float* O_la;                /* out [B,H,L,d] f32 linear-branch output (Eq. 10)               */
+    float* O_nla;               /* out [B,H,L,d] f32 softmax-branch output (Eq. 11)              */
+    float* lse;                 /* out [B,H,L] f32 log-sum-exp of the visible logits; -inf where
+                                   no softmax token is visible (then O_nla = 0)                  */
+} nats_fwd_extra;
+
+/* Bytes of device workspace nats_hybrid_attn_fwd{,_ex} needs for these params
+ * (0 if the params are invalid).  Host-only; touches no device. */
+size_t nats_hybrid_attn_fwd_workspace_bytes(const nats_fwd_params* p);
+
+/* O = merge(GDN branch, softmax branch) as defined above.
+ *   Q, K, V : in  [B,H,L,d]  dtype p->dtype.  The paper L2-normalises q,k for the linear
+ *             branch (Section 4.3); the caller does that, the library uses them as given.
+ *   alpha   : in  [B,H,L] f32 decay in (0,1]           (Eq. 19)
+ *   beta    : in  [B,H,L] f32 write strength in [0,1]  (Eq. 19)
+ *   mask    : in  [B,H,L] u8, non-zero = softmax token (Eq. 12-13 at token granularity)
+ *   O       : out [B,H,L,d] dtype p->dtype
+ *   workspace, workspace_bytes : device scratch of at least *_workspace_bytes(p); contents
+ *             are undefined afterwards; two calls in flight must not share it.
+ * Returns NATS_OK once everything is enqueued. */
+nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Same, with the optional inputs (Eq. 21 weights, initial state) and optional outputs
+ * (final state, compacted KV cache and its integer bookkeeping, per-branch outputs)
+ * that tests and the prefill -> decode hand-off need.  extra may be NULL. */
+nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                    const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                    const nats_fwd_extra* extra, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ * Single-token decode (Section 4.1, per-token generation, with per-token routing)
+ * ------------------------------------------------------------------------- */
+typedef struct nats_dec_params {
+    int32_t B, H;
+    int32_t d;             /* 64 or 128                                                         */
+    int32_t cap;           /* rows per (b,h) in the KV cache                                    */
+    int32_t dtype;         /* nats_dtype of q, k, v, o and of the KV cache                      */
+    float softmax_scale;   /* as in nats_fwd_params                                             */
+    float la_scale;
+    int32_t combine_mode;
+    float rms_eps;
+} nats_dec_params;
+
+/* For every (b,h):  S <- alpha S;  linear token: S <- S + beta (v - S k) k^T;  softmax token:
+ * (k,v) appended to the cache first (it sees itself, Eq. 12 i >= j);  then
+ * o = merge(la_scale * S q, softmax(scale * q.K_cache^T) V_cache).
+ *   state     : in/out [B,H,d,d] f32, S[d_v][d_k], updated in place
+ *   k_cache, v_cache : in/out [B,H,cap,d]; row cache_len[b,h] is written for a softmax token
+ *   cache_len : in/out [B,H] i32, incremented for a softmax token
+ *   q, k, v   : in  [B,H,d];  alpha, beta : in [B,H] f32;  mask : in [B,H] u8
+ *   w_nla, w_la : in [B,H] f32 or NULL (0.5), used by combine_mode 1
+ *   o         : out [B,H,d]
+ *   err_flags : out [B,H] i32 or NULL; set to 1 where a softmax token found its cache full
+ *               (the token is then not stored and o covers the existing rows), else 0.
+ * Needs no workspace. */
+nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void* k_cache, void* v_cache,
+                                    int32_t* cache_len, const void* q, const void* k, const void* v,
+                                    const float* alpha, const float* beta, const uint8_t* mask,
+                                    const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
+                                    void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ * Optional per-kernel timing (for benchmarks; off by default)
+ * ------------------------------------------------------------------------- */
+/* Creates max_records hipEvent pairs and turns recording on: until nats_profile_end, every kernel
+ * the forward / decode calls launch is bracketed by an event pair on the call's stream (records
+ * beyond max_records are dropped).  This is the one place the library creates HIP objects. */
+nats_status nats_profile_begin(int max_records);
+
+/* Turns recording off, waits for the recorded events, and aggregates per kernel name:
+ * names[i*32 .. i*32+31] (NUL-terminated), total_ms[i], launches[i] for up to max_kernels kernels.
+ * All three arrays are HOST memory owned by the caller.  Destroys the events.
+ * Returns the number of distinct kernels written, or a negative nats_status. */
+int nats_profile_end(char* names, float* total_ms, int32_t* launches, int max_kernels);
+
+/* Host-side message for the last non-OK status returned on this thread ("" if none). */
+const char* nats_last_error(void);
+
+/* ABI version of this header: major * 100 + minor. */
+int nats_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NATS_H_ */

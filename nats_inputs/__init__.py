@@ -19,7 +19,7 @@ Draw order is fixed: Q, K, V, alpha, beta, mask, (run positions).
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import Dict, Optional
 
 import numpy as np
@@ -80,16 +80,33 @@ def _sigmoid(x: np.ndarray) -> np.ndarray:
 
 
 def _unit_rows(x: np.ndarray) -> np.ndarray:
-    return x / np.linalg.norm(x, axis=-1, keepdims=True)
+    x /= np.sqrt(np.einsum("...i,...i->...", x, x))[..., None]
+    return x
+
+
+def _normal32(rng: np.random.Generator, shape) -> np.ndarray:
+    """N(0,1) float32 by Box-Muller on float32 uniforms, in fixed-size blocks (numpy's own
+    float32 normal sampler is ~20x slower per element, which matters at 10^8 elements)."""
+    n = int(np.prod(shape))
+    out = np.empty(n + (n & 1), dtype=np.float32)
+    block = 1 << 22
+    for lo in range(0, out.size, block):
+        m = min(block, out.size - lo) // 2
+        u1 = 1.0 - rng.random(m, dtype=np.float32)          # (0, 1]
+        u2 = rng.random(m, dtype=np.float32)
+        r = np.sqrt(-2.0 * np.log(u1))
+        ang = np.float32(2.0 * np.pi) * u2
+        out[lo:lo + m] = r * np.cos(ang)
+        out[lo + m:lo + 2 * m] = r * np.sin(ang)
+    return out[:n].reshape(shape)
 
 
 def _qkv_gates(rng: np.random.Generator, lead: tuple, d: int, dtype: str):
-    q = _unit_rows(rng.standard_normal(lead + (d,)))
-    k = _unit_rows(rng.standard_normal(lead + (d,)))
-    v = rng.standard_normal(lead + (d,))
+    q = _unit_rows(_normal32(rng, lead + (d,)))
+    k = _unit_rows(_normal32(rng, lead + (d,)))
+    v = _normal32(rng, lead + (d,))
     alpha = _sigmoid(2.0 + 0.5 * rng.standard_normal(lead))
     beta = _sigmoid(rng.standard_normal(lead))
-    q, k, v = (a.astype(np.float32) for a in (q, k, v))
     if dtype == "bf16":
         q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
     return q, k, v, alpha.astype(np.float32), beta.astype(np.float32)
@@ -153,13 +170,14 @@ def make_decode_inputs(cfg: DecodeConfig, steps: Optional[int] = None) -> Dict[s
     state = (cfg.state_std * rng.standard_normal((B, H, d, d))).astype(np.float32)
     lens = rng.integers(cfg.len_lo, cfg.len_hi + 1, size=(B,))
     cache_len = np.repeat(lens[:, None], H, axis=1).astype(np.int32)
-    k_cache = _unit_rows(rng.standard_normal((B, H, cap, d))).astype(np.float32)
-    v_cache = rng.standard_normal((B, H, cap, d)).astype(np.float32)
+    k_cache = np.zeros((B, H, cap, d), dtype=np.float32)
+    v_cache = np.zeros((B, H, cap, d), dtype=np.float32)
+    for b in range(B):                      # only the live rows are drawn; the rest stay zero
+        n = int(lens[b])
+        k_cache[b, :, :n] = _unit_rows(_normal32(rng, (H, n, d)))
+        v_cache[b, :, :n] = _normal32(rng, (H, n, d))
     if cfg.dtype == "bf16":
         k_cache, v_cache = round_to_bf16(k_cache), round_to_bf16(v_cache)
-    live = np.arange(cap)[None, None, :] < cache_len[:, :, None]
-    k_cache *= live[..., None]
-    v_cache *= live[..., None]
     q, k, v, alpha, beta = _qkv_gates(rng, (steps, B, H), d, cfg.dtype)
     mask = (rng.random((steps, B, H)) < cfg.p_softmax).astype(np.uint8)
     return {"state": state, "k_cache": k_cache, "v_cache": v_cache, "cache_len": cache_len,

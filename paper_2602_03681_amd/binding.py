@@ -1,0 +1,259 @@
+"""ctypes binding of the C ABI declared in include/nats.h.
+
+Argument marshalling only: tensors must already live on the GPU; this module
+passes their device pointers and torch's current HIP stream to libnats.so, and
+allocates outputs / workspace with torch.  No step of the operator is computed
+here, and there is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libnats.so")
+_lib = None
+
+NATS_F32, NATS_BF16 = 0, 1
+NATS_MATH_AUTO, NATS_MATH_FP32 = 0, 1
+
+
+class NatsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"nats status {status}: {message}")
+        self.status = status
+
+
+class FwdParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
+                ("math", ctypes.c_int32)]
+
+
+class FwdExtra(ctypes.Structure):
+    _fields_ = [("w_nla", ctypes.c_void_p), ("w_la", ctypes.c_void_p), ("initial_state", ctypes.c_void_p),
+                ("final_state", ctypes.c_void_p), ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
+                ("cap", ctypes.c_int32), ("n_s", ctypes.c_void_p), ("idx", ctypes.c_void_p),
+                ("cnt", ctypes.c_void_p), ("O_la", ctypes.c_void_p), ("O_nla", ctypes.c_void_p),
+                ("lse", ctypes.c_void_p)]
+
+
+class DecParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("cap", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("la_scale", ctypes.c_float),
+                ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float)]
+
+
+EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
+           "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
+           "nats_profile_end")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libnats.so (built in-tree by paper_2602_03681_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2602_03681_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.nats_hybrid_attn_fwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.nats_hybrid_attn_fwd_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams)]
+    lib.nats_hybrid_attn_fwd.restype = ctypes.c_int
+    lib.nats_hybrid_attn_fwd.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.nats_hybrid_attn_fwd_ex.restype = ctypes.c_int
+    lib.nats_hybrid_attn_fwd_ex.argtypes = ([ctypes.POINTER(FwdParams)] + [vp] * 7
+                                            + [ctypes.POINTER(FwdExtra), vp, ctypes.c_size_t, vp])
+    lib.nats_hybrid_attn_decode.restype = ctypes.c_int
+    lib.nats_hybrid_attn_decode.argtypes = [ctypes.POINTER(DecParams)] + [vp] * 15
+    lib.nats_last_error.restype = ctypes.c_char_p
+    lib.nats_abi_version.restype = ctypes.c_int
+    lib.nats_profile_begin.restype = ctypes.c_int
+    lib.nats_profile_begin.argtypes = [ctypes.c_int]
+    lib.nats_profile_end.restype = ctypes.c_int
+    lib.nats_profile_end.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_float),
+                                     ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise NatsError(status, load_library().nats_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NATS_F32
+    if t.dtype == torch.bfloat16:
+        return NATS_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _require(t: Optional[torch.Tensor], name: str, shape: Sequence[int], dtype: torch.dtype):
+    if t is None:
+        return
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous {dtype} of shape {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
+def _stream_ptr() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
+                    math=NATS_MATH_AUTO) -> FwdParams:
+    return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math)
+
+
+def fwd_workspace_bytes(params: FwdParams) -> int:
+    return int(load_library().nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params)))
+
+
+_EX_OUTPUTS = ("final_state", "Kc", "Vc", "n_s", "idx", "cnt", "O_la", "O_nla", "lse")
+
+
+def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
+                       la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
+                       math: int = NATS_MATH_AUTO, w_nla=None, w_la=None, initial_state=None,
+                       want: Sequence[str] = (), cap: Optional[int] = None, out=None,
+                       workspace=None) -> Dict[str, torch.Tensor]:
+    """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
+    (any of final_state, Kc, Vc, n_s, idx, cnt, O_la, O_nla, lse); the result dict always holds "O"."""
+    lib = load_library()
+    B, H, L, d = Q.shape
+    dt = Q.dtype
+    for name, t in (("Q", Q), ("K", K), ("V", V)):
+        _require(t, name, (B, H, L, d), dt)
+    _require(alpha, "alpha", (B, H, L), torch.float32)
+    _require(beta, "beta", (B, H, L), torch.float32)
+    _require(mask, "mask", (B, H, L), torch.uint8)
+    _require(w_nla, "w_nla", (B, H, L), torch.float32)
+    _require(w_la, "w_la", (B, H, L), torch.float32)
+    _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math)
+    need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
+    if need == 0:
+        _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    dev = Q.device
+    O = torch.empty_like(Q) if out is None else out
+    _require(O, "out", (B, H, L, d), dt)
+    want = set(want)
+    unknown = want - set(_EX_OUTPUTS)
+    if unknown:
+        raise ValueError(f"unknown outputs {sorted(unknown)}")
+    if ("Kc" in want) != ("Vc" in want):
+        raise ValueError("Kc and Vc come together")
+    cap = L if cap is None else cap
+    res: Dict[str, torch.Tensor] = {"O": O}
+    if "final_state" in want: res["final_state"] = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    if "Kc" in want:
+        res["Kc"] = torch.zeros((B, H, cap, d), dtype=dt, device=dev)
+        res["Vc"] = torch.zeros((B, H, cap, d), dtype=dt, device=dev)
+    if "n_s" in want: res["n_s"] = torch.empty((B, H), dtype=torch.int32, device=dev)
+    if "idx" in want: res["idx"] = torch.full((B, H, L), -1, dtype=torch.int32, device=dev)
+    if "cnt" in want: res["cnt"] = torch.empty((B, H, L), dtype=torch.int32, device=dev)
+    if "O_la" in want: res["O_la"] = torch.empty((B, H, L, d), dtype=torch.float32, device=dev)
+    if "O_nla" in want: res["O_nla"] = torch.empty((B, H, L, d), dtype=torch.float32, device=dev)
+    if "lse" in want: res["lse"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    g = lambda k: res[k].data_ptr() if k in res else None
+    extra = FwdExtra(w_nla.data_ptr() if w_nla is not None else None,
+                     w_la.data_ptr() if w_la is not None else None,
+                     initial_state.data_ptr() if initial_state is not None else None,
+                     g("final_state"), g("Kc"), g("Vc"), cap if "Kc" in want else 0, g("n_s"), g("idx"),
+                     g("cnt"), g("O_la"), g("O_nla"), g("lse"))
+    _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
+                                       _ptr(mask), _ptr(O), ctypes.byref(extra), _ptr(workspace),
+                                       workspace.numel(), _stream_ptr()))
+    return res
+
+
+def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
+                    la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
+                    math: int = NATS_MATH_AUTO, out=None, workspace=None) -> torch.Tensor:
+    """nats_hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C) -> O."""
+    lib = load_library()
+    B, H, L, d = Q.shape
+    dt = Q.dtype
+    for name, t in (("Q", Q), ("K", K), ("V", V)):
+        _require(t, name, (B, H, L, d), dt)
+    _require(alpha, "alpha", (B, H, L), torch.float32)
+    _require(beta, "beta", (B, H, L), torch.float32)
+    _require(mask, "mask", (B, H, L), torch.uint8)
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math)
+    if workspace is None:
+        workspace = torch.empty(max(fwd_workspace_bytes(params), 16), dtype=torch.uint8, device=Q.device)
+    O = torch.empty_like(Q) if out is None else out
+    _require(O, "out", (B, H, L, d), dt)
+    _check(lib.nats_hybrid_attn_fwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
+                                    _ptr(mask), _ptr(O), _ptr(workspace), workspace.numel(), _stream_ptr()))
+    return O
+
+
+def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, *,
+                       softmax_scale: float = 0.0, la_scale: float = 0.0, combine_mode: int = 0,
+                       rms_eps: float = 0.0, w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
+    """nats_hybrid_attn_decode: one token per (b,h); state, caches and cache_len are updated in place."""
+    lib = load_library()
+    B, H, cap, d = k_cache.shape
+    dt = k_cache.dtype
+    _require(state, "state", (B, H, d, d), torch.float32)
+    _require(k_cache, "k_cache", (B, H, cap, d), dt)
+    _require(v_cache, "v_cache", (B, H, cap, d), dt)
+    _require(cache_len, "cache_len", (B, H), torch.int32)
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        _require(t, name, (B, H, d), dt)
+    for name, t in (("alpha", alpha), ("beta", beta), ("w_nla", w_nla), ("w_la", w_la)):
+        _require(t, name, (B, H), torch.float32)
+    _require(mask, "mask", (B, H), torch.uint8)
+    _require(err_flags, "err_flags", (B, H), torch.int32)
+    o = torch.empty_like(q) if out is None else out
+    _require(o, "out", (B, H, d), dt)
+    params = DecParams(B, H, d, cap, _dtype_code(k_cache), softmax_scale, la_scale, combine_mode, rms_eps)
+    _check(lib.nats_hybrid_attn_decode(ctypes.byref(params), _ptr(state), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(cache_len), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta),
+                                       _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
+                                       _stream_ptr()))
+    return o
+
+
+def profile_begin(max_records: int = 4096) -> None:
+    """nats_profile_begin: bracket every kernel of the following calls with HIP events."""
+    _check(load_library().nats_profile_begin(max_records))
+
+
+def profile_end(max_kernels: int = 16) -> Dict[str, Dict[str, float]]:
+    """nats_profile_end: {kernel name: {"total_ms", "launches", "avg_ms"}}."""
+    names = ctypes.create_string_buffer(32 * max_kernels)
+    ms = (ctypes.c_float * max_kernels)()
+    cnt = (ctypes.c_int32 * max_kernels)()
+    n = load_library().nats_profile_end(names, ms, cnt, max_kernels)
+    if n < 0:
+        _check(n)
+    out = {}
+    for i in range(n):
+        name = names.raw[32 * i:32 * i + 32].split(b"\0", 1)[0].decode()
+        out[name] = {"total_ms": float(ms[i]), "launches": int(cnt[i]), "avg_ms": float(ms[i]) / max(int(cnt[i]), 1)}
+    return out
+
+
+decode = hybrid_attn_decode

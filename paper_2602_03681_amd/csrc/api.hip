@@ -1,0 +1,264 @@
+// C ABI of the NAtS-L hybrid attention library: host-side validation, workspace
+// carve-up and kernel sequencing.  Declarations and argument semantics: nats.h.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "nats_common.h"
+
+namespace nats {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+nats_status check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: HIP launch failed: %s", what, hipGetErrorString(e));
+        return NATS_ERR_HIP;
+    }
+    return NATS_OK;
+}
+
+// ---- optional per-kernel timing -----------------------------------------------------------
+struct ProfRecord { const char* name; hipEvent_t start, stop; };
+static std::mutex g_prof_mu;
+static std::vector<ProfRecord> g_prof;
+static int g_prof_used = 0;
+static bool g_prof_on = false;
+
+ProfScope::ProfScope(const char* name, hipStream_t st) : slot(-1), stream(st) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof_on || g_prof_used >= (int)g_prof.size()) return;
+    slot = g_prof_used++;
+    g_prof[slot].name = name;
+    (void)hipEventRecord(g_prof[slot].start, stream);
+}
+ProfScope::~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].stop, stream);
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
+    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
+    if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {
+        set_error("dtype %d is neither NATS_F32 nor NATS_BF16", p->dtype);
+        return NATS_ERR_DTYPE;
+    }
+    if (p->B <= 0 || p->H <= 0 || p->L <= 0 || p->C <= 0) {
+        set_error("B, H, L, C must be positive (got %d, %d, %d, %d)", p->B, p->H, p->L, p->C);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
+    if (p->L % p->C != 0) { set_error("L (%d) must be a multiple of C (%d)", p->L, p->C); return NATS_ERR_SHAPE; }
+    if ((long long)p->B * p->H > 65535) { set_error("B*H must not exceed 65535"); return NATS_ERR_SHAPE; }
+    if ((long long)p->B * p->H * p->L > (1ll << 31) - 1) {
+        set_error("B*H*L must fit in 31 bits");
+        return NATS_ERR_SHAPE;
+    }
+    if (p->C != 64) { set_error("chunk size C=%d has no kernel in this build (64 only)", p->C); return NATS_ERR_UNSUPPORTED; }
+    if (p->combine_mode != 0 && p->combine_mode != 1) {
+        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->math != NATS_MATH_AUTO && p->math != NATS_MATH_FP32) {
+        set_error("math must be NATS_MATH_AUTO or NATS_MATH_FP32 (got %d)", p->math);
+        return NATS_ERR_SHAPE;
+    }
+    pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
+    pl->dtype = p->dtype;
+    pl->math = p->math;
+    pl->softmax_scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+    pl->la_scale = p->la_scale > 0.f ? p->la_scale : 1.0f;
+    pl->rms_eps = p->rms_eps > 0.f ? p->rms_eps : 1e-6f;
+    pl->combine_mode = p->combine_mode;
+
+    const size_t esz = p->dtype == NATS_BF16 ? 2 : 4;
+    const size_t n_tok = (size_t)pl->BH * pl->L;
+    size_t off = 0;
+    pl->off_cnt = off; off = align_up(off + n_tok * 4, 256);
+    pl->off_idx = off; off = align_up(off + n_tok * 4, 256);
+    pl->off_ns = off;  off = align_up(off + (size_t)pl->BH * 4, 256);
+    pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
+    pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
+    pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
+    pl->total = off;
+    return NATS_OK;
+}
+
+}  // namespace nats
+
+using namespace nats;
+
+extern "C" {
+
+const char* nats_last_error(void) { return g_err; }
+
+int nats_abi_version(void) { return 100; }
+
+nats_status nats_profile_begin(int max_records) {
+    if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof.empty()) { set_error("profiling is already on"); return NATS_ERR_UNSUPPORTED; }
+    g_prof.resize(max_records);
+    for (auto& r : g_prof) {
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
+            set_error("hipEventCreate failed");
+            g_prof.clear();
+            return NATS_ERR_HIP;
+        }
+    }
+    g_prof_used = 0;
+    g_prof_on = true;
+    return NATS_OK;
+}
+
+int nats_profile_end(char* names, float* total_ms, int32_t* launches, int max_kernels) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = false;
+    int n = 0;
+    if (names && total_ms && launches) {
+        for (int i = 0; i < g_prof_used; ++i) {
+            float ms = 0.f;
+            if (hipEventSynchronize(g_prof[i].stop) != hipSuccess ||
+                hipEventElapsedTime(&ms, g_prof[i].start, g_prof[i].stop) != hipSuccess)
+                continue;
+            int k = 0;
+            while (k < n && strncmp(names + 32 * k, g_prof[i].name, 31) != 0) ++k;
+            if (k == n) {
+                if (n >= max_kernels) continue;
+                strncpy(names + 32 * n, g_prof[i].name, 31);
+                names[32 * n + 31] = 0;
+                total_ms[n] = 0.f;
+                launches[n] = 0;
+                ++n;
+            }
+            total_ms[k] += ms;
+            launches[k] += 1;
+        }
+    }
+    for (auto& r : g_prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    g_prof.clear();
+    g_prof_used = 0;
+    return n;
+}
+
+size_t nats_hybrid_attn_fwd_workspace_bytes(const nats_fwd_params* p) {
+    FwdPlan pl;
+    if (validate_fwd_params(p, &pl) != NATS_OK) return 0;
+    return pl.total;
+}
+
+nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                    const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                    const nats_fwd_extra* extra, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+    FwdPlan pl;
+    nats_status st = validate_fwd_params(p, &pl);
+    if (st != NATS_OK) return st;
+    if (!Q || !K || !V || !alpha || !beta || !mask || !O) {
+        set_error("Q, K, V, alpha, beta, mask and O must all be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    if (workspace == nullptr || workspace_bytes < pl.total) {
+        set_error("workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, pl.total);
+        return NATS_ERR_WORKSPACE;
+    }
+    nats_fwd_extra ex;
+    memset(&ex, 0, sizeof(ex));
+    if (extra) ex = *extra;
+    if ((ex.Kc == nullptr) != (ex.Vc == nullptr)) { set_error("extra.Kc and extra.Vc must be given together"); return NATS_ERR_NULL; }
+    if (ex.Kc != nullptr && ex.cap <= 0) { set_error("extra.cap must be positive when Kc/Vc are given"); return NATS_ERR_SHAPE; }
+    const void* ptrs[] = {Q, K, V, alpha, beta, mask, O, workspace, ex.w_nla, ex.w_la, ex.initial_state,
+                          ex.final_state, ex.Kc, ex.Vc, ex.n_s, ex.idx, ex.cnt, ex.O_la, ex.O_nla, ex.lse};
+    for (const void* ptr : ptrs)
+        if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    if (O == Q || O == K || O == V) { set_error("O must not alias Q, K or V"); return NATS_ERR_SHAPE; }
+
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    int32_t* cnt = reinterpret_cast<int32_t*>(ws + pl.off_cnt);
+    int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
+    int32_t* n_s = reinterpret_cast<int32_t*>(ws + pl.off_ns);
+    void* Kc = ws + pl.off_kc;
+    void* Vc = ws + pl.off_vc;
+    // the per-branch fp32 output lives in the caller's buffer when one is given
+    float* O_la = ex.O_la ? ex.O_la : reinterpret_cast<float*>(ws + pl.off_ola);
+    // integer bookkeeping goes straight to the caller's arrays when given
+    if (ex.cnt) cnt = ex.cnt;
+    if (ex.idx) idx = ex.idx;
+    if (ex.n_s) n_s = ex.n_s;
+
+    {
+        ProfScope ps("scan_compact", stream);
+        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap, stream);
+    }
+    if (st != NATS_OK) return st;
+    // Both tensor dtypes currently run the fp32-arithmetic kernels.
+    {
+        ProfScope ps("gdn_recurrent", stream);
+        st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la, stream);
+    }
+    if (st != NATS_OK) return st;
+    {
+        ProfScope ps("softmax_fp32", stream);
+        st = launch_softmax_fp32(pl, Q, Kc, Vc, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
+    }
+    return st;
+}
+
+nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return nats_hybrid_attn_fwd_ex(p, Q, K, V, alpha, beta, mask, O, nullptr, workspace, workspace_bytes,
+                                   hip_stream);
+}
+
+nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void* k_cache, void* v_cache,
+                                    int32_t* cache_len, const void* q, const void* k, const void* v,
+                                    const float* alpha, const float* beta, const uint8_t* mask,
+                                    const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
+                                    void* hip_stream) {
+    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
+    if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {
+        set_error("dtype %d is neither NATS_F32 nor NATS_BF16", p->dtype);
+        return NATS_ERR_DTYPE;
+    }
+    if (p->B <= 0 || p->H <= 0 || p->cap <= 0) {
+        set_error("B, H, cap must be positive (got %d, %d, %d)", p->B, p->H, p->cap);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
+    if (p->combine_mode != 0 && p->combine_mode != 1) {
+        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+        return NATS_ERR_SHAPE;
+    }
+    if (!state || !k_cache || !v_cache || !cache_len || !q || !k || !v || !alpha || !beta || !mask || !o) {
+        set_error("state, caches, cache_len, q, k, v, alpha, beta, mask and o must all be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    const void* ptrs[] = {state, k_cache, v_cache, q, k, v, o};
+    for (const void* ptr : ptrs)
+        if (!aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+    const float la_scale = p->la_scale > 0.f ? p->la_scale : 1.0f;
+    const float eps = p->rms_eps > 0.f ? p->rms_eps : 1e-6f;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("decode", stream);
+    return launch_decode(*p, scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
+                         mask, w_nla, w_la, o, err_flags, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,230 @@
+// Single-token decode step (Section 4.1, per-token generation; per-token routing):
+//   S <- alpha S ;  linear token: S <- S + beta (v - S k) k^T  (Eq. 19, Eq. 20)
+//   softmax token: (k, v) appended to the KV cache of softmax tokens, and attended (Eq. 12, i >= j)
+//   o = merge( la_scale * S q ,  softmax(scale * q . Kcache^T) Vcache )     (Section 4.1 / Eq. 21)
+// One block per (batch, head).  HBM-bound: the fp32 state is streamed once (read +
+// write, 8 d^2 bytes) and the live cache rows once (4 d len bytes for bf16).
+//
+//  phase A  state: LPR = D/4 lanes hold one row of S as a float4 each; all row passes of a
+//           thread are loaded up front so the loads overlap; S k and S q are reduced across
+//           the LPR lanes with xor shuffles.
+//  phase B  cache: LPK = D/(16/sizeof T) lanes share one key row (16 bytes per lane); the
+//           256 threads form NSG key groups that stride over the cache with their own
+//           running max / sum / accumulator, merged through LDS at the end.  The new
+//           token is folded in from registers (no read-back of the row just written).
+#include <math.h>
+
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int DEC_THREADS = 256;
+
+template <int W>
+__device__ __forceinline__ float group_sum(float x) {
+#pragma unroll
+    for (int off = 1; off < W; off <<= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
+    float* __restrict__ state, T* __restrict__ k_cache, T* __restrict__ v_cache,
+    int32_t* __restrict__ cache_len, const T* __restrict__ q, const T* __restrict__ k,
+    const T* __restrict__ v, const float* __restrict__ alpha, const float* __restrict__ beta,
+    const uint8_t* __restrict__ mask, const float* __restrict__ w_nla, const float* __restrict__ w_la,
+    T* __restrict__ o, int32_t* __restrict__ err_flags, int cap, float scale, float la_scale,
+    int combine_mode, float eps) {
+    constexpr int LPR = D / 4;                    // lanes per state row
+    constexpr int ROWS_PER_PASS = DEC_THREADS / LPR;
+    constexpr int PASSES = D / ROWS_PER_PASS;     // 16 (D=128) or 4 (D=64)
+    constexpr int EPL = Vec16<T>::N;              // elements per lane of a cache row
+    constexpr int LPK = D / EPL;                  // lanes per key
+    constexpr int NSG = DEC_THREADS / LPK;        // key groups in the block
+    constexpr int UNROLL = 4;
+
+    __shared__ float s_q[D], s_k[D], s_v[D], s_ola[D];
+    __shared__ float s_m[NSG], s_l[NSG];
+    __shared__ float s_acc[NSG][D];
+
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    for (int c = tid; c < D; c += DEC_THREADS) {
+        s_q[c] = to_float(q[(size_t)bh * D + c]);
+        s_k[c] = to_float(k[(size_t)bh * D + c]);
+        s_v[c] = to_float(v[(size_t)bh * D + c]);
+    }
+    const float a = alpha[bh];
+    const bool is_softmax = mask[bh] != 0;
+    const float b = is_softmax ? 0.f : beta[bh];
+    const int n_old = cache_len[bh];
+    const bool append = is_softmax && n_old < cap;
+    __syncthreads();
+
+    // ---- phase A: state update and o_la = la_scale * S q --------------------------------
+    {
+        const int lr = tid % LPR, r0 = tid / LPR;
+        float* Sb = state + (size_t)bh * D * D;
+        float4 S4[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+            S4[p] = *reinterpret_cast<const float4*>(Sb + (size_t)(p * ROWS_PER_PASS + r0) * D + lr * 4);
+        const float4 k4 = *reinterpret_cast<const float4*>(&s_k[lr * 4]);
+        const float4 q4 = *reinterpret_cast<const float4*>(&s_q[lr * 4]);
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = p * ROWS_PER_PASS + r0;
+            float4 s = S4[p];
+            s.x *= a; s.y *= a; s.z *= a; s.w *= a;
+            if (b != 0.f) {
+                const float pred = group_sum<LPR>(s.x * k4.x + s.y * k4.y + s.z * k4.z + s.w * k4.w);
+                const float delta = b * (s_v[row] - pred);
+                s.x += delta * k4.x; s.y += delta * k4.y; s.z += delta * k4.z; s.w += delta * k4.w;
+            }
+            const float oq = group_sum<LPR>(s.x * q4.x + s.y * q4.y + s.z * q4.z + s.w * q4.w);
+            if (lr == 0) s_ola[row] = la_scale * oq;
+            *reinterpret_cast<float4*>(Sb + (size_t)row * D + lr * 4) = s;
+        }
+    }
+
+    // ---- phase B: softmax over the cache (+ the new token) ---------------------------------
+    const int lk = tid % LPK, sg = tid / LPK;
+    float qf[EPL], acc[EPL];
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) { qf[j] = s_q[lk * EPL + j] * scale; acc[j] = 0.f; }
+    float m_run = -INFINITY, l_run = 0.f;
+    const T* Kb = k_cache + (size_t)bh * cap * D + lk * EPL;
+    const T* Vb = v_cache + (size_t)bh * cap * D + lk * EPL;
+
+    for (int c0 = sg; c0 < n_old; c0 += NSG * UNROLL) {
+        float kf[UNROLL][EPL], vf[UNROLL][EPL], s[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int c = c0 + u * NSG;
+            if (c < n_old) {
+                Vec16<T>::load(Kb + (size_t)c * D, kf[u]);
+                Vec16<T>::load(Vb + (size_t)c * D, vf[u]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) { kf[u][j] = 0.f; vf[u][j] = 0.f; }
+            }
+        }
+        float bm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) dot += qf[j] * kf[u][j];
+            dot = group_sum<LPK>(dot);
+            s[u] = (c0 + u * NSG < n_old) ? dot : -INFINITY;
+            bm = fmaxf(bm, s[u]);
+        }
+        const float m_new = fmaxf(m_run, bm);   // finite: key c0 is live
+        const float corr = expf(m_run - m_new);
+        l_run *= corr;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[j] *= corr;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const float p = expf(s[u] - m_new);
+            l_run += p;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) acc[j] += p * vf[u][j];
+        }
+        m_run = m_new;
+    }
+    if (append && sg == 0) {   // the new softmax token attends to itself
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) dot += qf[j] * s_k[lk * EPL + j];
+        dot = group_sum<LPK>(dot);
+        const float m_new = fmaxf(m_run, dot);
+        const float corr = expf(m_run - m_new);
+        const float p = expf(dot - m_new);
+        l_run = l_run * corr + p;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[j] = acc[j] * corr + p * s_v[lk * EPL + j];
+        m_run = m_new;
+    }
+    if (lk == 0) { s_m[sg] = m_run; s_l[sg] = l_run; }
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) s_acc[sg][lk * EPL + j] = acc[j];
+    __syncthreads();
+
+    // ---- append the new token to the cache -------------------------------------------------
+    if (append) {
+        for (int c = tid; c < D; c += DEC_THREADS) {
+            k_cache[((size_t)bh * cap + n_old) * D + c] = k[(size_t)bh * D + c];
+            v_cache[((size_t)bh * cap + n_old) * D + c] = v[(size_t)bh * D + c];
+        }
+        if (tid == 0) cache_len[bh] = n_old + 1;
+    }
+    if (tid == 0 && err_flags != nullptr) err_flags[bh] = (is_softmax && !append) ? 1 : 0;
+
+    // ---- merge the key groups, then the two branches (threads 0..D-1, one output each) --------
+    // D <= 128 <= 2 wavefronts; row statistics for Eq. 21 go through LDS.
+    __shared__ float s_red[4];
+    float o_nla = 0.f, o_la = 0.f;
+    if (tid < D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int g = 0; g < NSG; ++g) M = fmaxf(M, s_m[g]);
+        float num = 0.f, den = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int g = 0; g < NSG; ++g) {
+                const float wgt = expf(s_m[g] - M);   // groups that saw no key have m = -inf -> 0
+                num += wgt * s_acc[g][tid];
+                den += wgt * s_l[g];
+            }
+            o_nla = num / den;
+        }
+        o_la = s_ola[tid];
+    }
+    if (combine_mode == 0) {
+        if (tid < D) o[(size_t)bh * D + tid] = from_float<T>(o_la + o_nla);
+    } else {
+        float x = (tid < D) ? o_la * o_la : 0.f, y = (tid < D) ? o_nla * o_nla : 0.f;
+        x = group_sum<64>(x); y = group_sum<64>(y);
+        if ((tid & 63) == 0 && tid < 128) { s_red[(tid >> 6) * 2] = x; s_red[(tid >> 6) * 2 + 1] = y; }
+        __syncthreads();
+        if (tid < D) {
+            const float ss_la = s_red[0] + (D > 64 ? s_red[2] : 0.f);
+            const float ss_nla = s_red[1] + (D > 64 ? s_red[3] : 0.f);
+            const float wn = (w_nla ? w_nla[bh] : 0.5f) / sqrtf(ss_nla / D + eps);
+            const float wl = (w_la ? w_la[bh] : 0.5f) / sqrtf(ss_la / D + eps);
+            o[(size_t)bh * D + tid] = from_float<T>(wn * o_nla + wl * o_la);
+        }
+    }
+}
+
+template <typename T>
+static void launch_dec(const nats_dec_params& p, float scale, float la_scale, float eps, float* state,
+                       void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
+                       const void* v, const float* alpha, const float* beta, const uint8_t* mask,
+                       const float* w_nla, const float* w_la, void* o, int32_t* err_flags, hipStream_t st) {
+    dim3 grid(p.B * p.H);
+    if (p.d == 64)
+        hipLaunchKernelGGL((decode_kernel<T, 64>), grid, dim3(DEC_THREADS), 0, st, state, (T*)k_cache,
+                           (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
+                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
+    else
+        hipLaunchKernelGGL((decode_kernel<T, 128>), grid, dim3(DEC_THREADS), 0, st, state, (T*)k_cache,
+                           (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
+                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
+}
+
+nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
+                          float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
+                          const void* k, const void* v, const float* alpha, const float* beta,
+                          const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
+                          int32_t* err_flags, hipStream_t st) {
+    if (p.dtype == NATS_BF16)
+        launch_dec<bf16_t>(p, softmax_scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v,
+                           alpha, beta, mask, w_nla, w_la, o, err_flags, st);
+    else
+        launch_dec<float>(p, softmax_scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v,
+                          alpha, beta, mask, w_nla, w_la, o, err_flags, st);
+    return check_launch("decode");
+}
+
+}  // namespace nats

@@ -1,0 +1,136 @@
+// Linear branch in fp32 arithmetic: the token-recurrent Gated DeltaNet update of
+// Section 4.3 (Eq. 19), written for linear tokens only (Eq. 14), decayed at every
+// token (Eq. 20), read by every query, o_t = la_scale * S_t q_t (Eq. 5 / Eq. 10):
+//     S <- alpha_t S ;  if m_t == 0:  S <- S + beta_t (v_t - S k_t) k_t^T ;  o_t = S q_t.
+// Rows of S (index d_v) evolve independently, so one thread owns one row of S in
+// registers; k_t, q_t, alpha_t, beta_t are the same for all rows and are staged
+// through LDS a tile of tokens at a time (broadcast reads).
+//
+// This is the NATS_MATH_FP32 path (tight-tolerance fp32 workloads); the bf16
+// throughput path is the chunkwise MFMA kernel.  VALU-bound: 6 d FLOP per row-token.
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int REC_ROWS = 64;  // state rows (threads) per block: one wavefront
+constexpr int REC_TT = 32;    // tokens staged per tile
+
+template <typename T, int D>
+__global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
+    const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la, int L,
+    float la_scale) {
+    __shared__ __align__(16) float s_k[REC_TT][D];
+    __shared__ __align__(16) float s_q[REC_TT][D];
+    __shared__ float s_v[REC_TT][REC_ROWS];
+    __shared__ float s_a[REC_TT], s_b[REC_TT];
+
+    const int bh = blockIdx.y;
+    const int row = blockIdx.x * REC_ROWS + threadIdx.x;  // d_v index owned by this thread
+    const int tid = threadIdx.x;
+    const size_t base = (size_t)bh * L;
+
+    float S[D];
+    if (S0 != nullptr) {
+        const float* src = S0 + ((size_t)bh * D + row) * D;
+#pragma unroll
+        for (int c = 0; c < D; c += 4) {
+            float4 x = *reinterpret_cast<const float4*>(src + c);
+            S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < D; ++c) S[c] = 0.f;
+    }
+
+    constexpr int EPL = Vec16<T>::N;
+    for (int t0 = 0; t0 < L; t0 += REC_TT) {
+        __syncthreads();
+        // stage k, q (all D columns) and this block's slice of v for REC_TT tokens
+        for (int e = tid * EPL; e < REC_TT * D; e += REC_ROWS * EPL) {
+            const int i = e / D, c = e % D;
+            float tmp[EPL];
+            Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_k[i][c + j] = tmp[j];
+            Vec16<T>::load(Q + (base + t0 + i) * D + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_q[i][c + j] = tmp[j];
+        }
+        for (int e = tid * EPL; e < REC_TT * REC_ROWS; e += REC_ROWS * EPL) {
+            const int i = e / REC_ROWS, c = e % REC_ROWS;
+            float tmp[EPL];
+            Vec16<T>::load(V + (base + t0 + i) * D + blockIdx.x * REC_ROWS + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
+        }
+        if (tid < REC_TT) {
+            s_a[tid] = alpha[base + t0 + tid];
+            s_b[tid] = mask[base + t0 + tid] ? 0.f : beta[base + t0 + tid];  // softmax tokens never write
+        }
+        __syncthreads();
+
+        for (int i = 0; i < REC_TT; ++i) {
+            const float a = s_a[i], b = s_b[i];
+            float o = 0.f;
+            if (b != 0.f) {  // uniform across the block
+                float pred = 0.f;
+#pragma unroll
+                for (int c = 0; c < D; c += 4) {
+                    const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                    S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
+                    pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
+                }
+                const float delta = b * (s_v[i][tid] - pred);
+#pragma unroll
+                for (int c = 0; c < D; c += 4) {
+                    const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                    const float4 q4 = *reinterpret_cast<const float4*>(&s_q[i][c]);
+                    S[c] += delta * k4.x; S[c + 1] += delta * k4.y;
+                    S[c + 2] += delta * k4.z; S[c + 3] += delta * k4.w;
+                    o += S[c] * q4.x + S[c + 1] * q4.y + S[c + 2] * q4.z + S[c + 3] * q4.w;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < D; c += 4) {
+                    const float4 q4 = *reinterpret_cast<const float4*>(&s_q[i][c]);
+                    S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
+                    o += S[c] * q4.x + S[c + 1] * q4.y + S[c + 2] * q4.z + S[c + 3] * q4.w;
+                }
+            }
+            O_la[(base + t0 + i) * D + row] = la_scale * o;
+        }
+    }
+    if (S_final != nullptr) {
+        float* dst = S_final + ((size_t)bh * D + row) * D;
+#pragma unroll
+        for (int c = 0; c < D; c += 4)
+            *reinterpret_cast<float4*>(dst + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+    }
+}
+
+template <typename T>
+static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const void* V, const float* alpha,
+                       const float* beta, const uint8_t* mask, const float* S0, float* S_final,
+                       float* O_la, hipStream_t st) {
+    dim3 grid(pl.d / REC_ROWS, pl.BH);
+    if (pl.d == 64)
+        hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, pl.L, pl.la_scale);
+    else
+        hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, pl.L, pl.la_scale);
+}
+
+nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask,
+                                 const float* S0, float* S_final, float* O_la, hipStream_t st) {
+    if (pl.dtype == NATS_BF16)
+        launch_rec<bf16_t>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, st);
+    else
+        launch_rec<float>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, st);
+    return check_launch("gdn_recurrent");
+}
+
+}  // namespace nats

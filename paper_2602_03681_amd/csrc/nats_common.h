@@ -1,0 +1,117 @@
+// Shared device/host helpers for the NAtS-L gfx950 kernels (internal header).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nats.h"
+
+namespace nats {
+
+// ---- element types ------------------------------------------------------------------
+// bf16 is carried as its raw 16 bits; conversions are written out so that the rounding
+// (round-to-nearest-even) is the same everywhere and independent of library headers.
+struct bf16_t {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ T from_float(float f);
+template <>
+__device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float f) { return bf16_t{f32_to_bf16_bits(f)}; }
+
+// 16-byte global load of consecutive elements, widened to float.  N = 16 / sizeof(T).
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<float> {
+    static constexpr int N = 4;
+    __device__ __forceinline__ static void load(const float* p, float* out) {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+    __device__ __forceinline__ static void store(float* p, const float* in) {
+        *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+    }
+};
+template <>
+struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    __device__ __forceinline__ static void load(const bf16_t* p, float* out) {
+        uint4 v = *reinterpret_cast<const uint4*>(p);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ __forceinline__ static void store(bf16_t* p, const float* in) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16_bits(in[2 * i]) | ((uint32_t)f32_to_bf16_bits(in[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// number of non-zero bytes in a 32-bit word
+__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
+    uint32_t t = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w;
+    return __popc(t & 0x80808080u);
+}
+
+// ---- host side ------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+nats_status check_launch(const char* what);
+
+// Brackets one kernel launch with a hipEvent pair while nats_profile_begin/end recording is on.
+struct ProfScope {
+    ProfScope(const char* name, hipStream_t st);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Resolved forward problem handed to the kernel launchers.
+struct FwdPlan {
+    int B, H, L, d, C, BH;
+    int dtype;
+    int math;
+    float softmax_scale, la_scale, rms_eps;
+    int combine_mode;
+    // workspace carve-up (byte offsets)
+    size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
+};
+
+// kernel launchers (one per .hip file); every pointer is a device pointer
+nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
+                                int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
+                                void* Kc_user, void* Vc_user, int cap_user, hipStream_t st);
+nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask,
+                                 const float* S0, float* S_final, float* O_la, hipStream_t st);
+nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
+                                const int32_t* cnt, const float* O_la, const float* w_nla,
+                                const float* w_la, void* O, float* O_nla_out, float* lse_out,
+                                hipStream_t st);
+nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
+                          float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
+                          const void* k, const void* v, const float* alpha, const float* beta,
+                          const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
+                          int32_t* err_flags, hipStream_t st);
+
+}  // namespace nats

@@ -1,0 +1,120 @@
+// Mask scan + K/V compaction (paper Section 4.1: the softmax branch loads only the
+// tokens routed to it; Eq. 12 gives the column set).  For every (batch, head):
+//   cnt[t] = #softmax tokens among 0..t,  idx[c] = position of the c-th one,
+//   n_s = cnt[L-1],  Kc[c] = K[idx[c]],  Vc[c] = V[idx[c]].
+// Integer work, exactly one correct answer.  HBM-bound.
+//
+// Grid (ceil(L / SEG), B*H).  A block owns SEG consecutive tokens.  Its base
+// count is recomputed from the mask bytes in front of the segment (at most L
+// bytes, read 16 at a time and served by L2), so blocks need no ordering and
+// no inter-block communication.
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_SEG = SCAN_THREADS * 4;  // tokens per block, 4 per thread
+
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
+    const uint8_t* __restrict__ mask, const T* __restrict__ K, const T* __restrict__ V, int L, int d,
+    int32_t* __restrict__ cnt, int32_t* __restrict__ idx, int32_t* __restrict__ n_s, T* __restrict__ Kc,
+    T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user) {
+    __shared__ int s_wave[SCAN_THREADS / 64];
+    __shared__ int s_pos[SCAN_SEG];
+    const int bh = blockIdx.y;
+    const int seg0 = blockIdx.x * SCAN_SEG;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint8_t* m = mask + (size_t)bh * L;
+
+    // ---- 1. softmax tokens in front of this segment -----------------------------------
+    int before = 0;
+    {
+        const uint4* m16 = reinterpret_cast<const uint4*>(m);  // seg0 is a multiple of 1024
+        for (int i = tid; i < seg0 / 16; i += SCAN_THREADS) {
+            uint4 w = m16[i];
+            before += nonzero_bytes(w.x) + nonzero_bytes(w.y) + nonzero_bytes(w.z) + nonzero_bytes(w.w);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off);
+        if (lane == 0) s_wave[wave] = before;
+        __syncthreads();
+        before = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        __syncthreads();
+    }
+
+    // ---- 2. scan of the segment: 4 tokens per thread ------------------------------------
+    const int t0 = seg0 + tid * 4;
+    uint32_t w = 0;
+    if (t0 < L) w = *reinterpret_cast<const uint32_t*>(m + t0);  // L % 4 == 0: a word is all in or all out
+    const int mine = nonzero_bytes(w);
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int wave_base = 0, seg_total = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_THREADS / 64; ++i) {
+        if (i < wave) wave_base += s_wave[i];
+        seg_total += s_wave[i];
+    }
+    int local = wave_base + incl - mine;  // softmax tokens of this segment before t0
+    if (t0 < L) {
+        int c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if ((w >> (8 * j)) & 0xffu) {
+                s_pos[local] = t0 + j;
+                idx[(size_t)bh * L + before + local] = t0 + j;
+                ++local;
+            }
+            c[j] = before + local;
+        }
+        *reinterpret_cast<int4*>(cnt + (size_t)bh * L + t0) = make_int4(c[0], c[1], c[2], c[3]);
+    }
+    if (seg0 + SCAN_SEG >= L && tid == 0) n_s[bh] = before + seg_total;
+    __syncthreads();
+
+    // ---- 3. gather the K / V rows of this segment's softmax tokens ------------------------
+    constexpr int EPL = 16 / (int)sizeof(T);  // elements per 16-byte lane access
+    const int lpr = d / EPL;                  // lanes per row (8..32, divides 256)
+    const int rows_per_pass = SCAN_THREADS / lpr;
+    const int part = tid % lpr;
+    for (int r = tid / lpr; r < seg_total; r += rows_per_pass) {
+        const int t = s_pos[r];
+        const int c = before + r;
+        const size_t src = ((size_t)bh * L + t) * d + part * EPL;
+        const uint4 kv = *reinterpret_cast<const uint4*>(K + src);
+        const uint4 vv = *reinterpret_cast<const uint4*>(V + src);
+        const size_t dst = ((size_t)bh * L + c) * d + part * EPL;
+        *reinterpret_cast<uint4*>(Kc + dst) = kv;
+        *reinterpret_cast<uint4*>(Vc + dst) = vv;
+        if (Kc_user != nullptr && c < cap_user) {
+            const size_t du = ((size_t)bh * cap_user + c) * d + part * EPL;
+            *reinterpret_cast<uint4*>(Kc_user + du) = kv;
+            *reinterpret_cast<uint4*>(Vc_user + du) = vv;
+        }
+    }
+}
+
+nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
+                                int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
+                                void* Kc_user, void* Vc_user, int cap_user, hipStream_t st) {
+    dim3 grid((pl.L + SCAN_SEG - 1) / SCAN_SEG, pl.BH);
+    if (pl.dtype == NATS_BF16) {
+        hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, mask,
+                           (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
+                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user);
+    } else {
+        hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, mask,
+                           (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
+                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user);
+    }
+    return check_launch("scan_compact");
+}
+
+}  // namespace nats

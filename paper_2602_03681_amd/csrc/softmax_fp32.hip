@@ -1,0 +1,182 @@
+// Softmax branch over the compacted keys, fp32 arithmetic, with the merge epilogue.
+//   o_nla[t] = softmax_{c < cnt[t]}(scale * q_t . Kc[c]) Vc        (Eq. 11 under the mask of Eq. 12:
+//   the keys visible to query t are exactly the first cnt[t] rows of the compacted cache)
+//   O[t] = O_la[t] + o_nla[t]                                       (Section 4.1), or
+//   O[t] = w_nla RMSNorm(o_nla[t]) + w_la RMSNorm(O_la[t])          (Eq. 21)
+// Rows with cnt[t] == 0 give o_nla = 0, lse = -inf.
+//
+// A block owns 64 consecutive queries; 4 adjacent lanes share one query row and
+// each keeps a quarter of q and of the output accumulator in registers.  Key/value
+// tiles of SM_BN compacted rows are staged in LDS as fp32; all lanes with the same
+// quarter read the same LDS address (broadcast).  Online max/sum in blocks of 8 keys.
+//
+// This is the NATS_MATH_FP32 path; the bf16 throughput path is the MFMA flash kernel.
+#include <math.h>
+
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int SM_BM = 64;       // queries per block
+constexpr int SM_THREADS = 256; // 4 lanes per query
+constexpr int SM_BN = 32;       // compacted keys per LDS tile
+constexpr int SM_KB = 8;        // keys per online-softmax step
+
+template <typename T, int D>
+__global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
+    const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc,
+    const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
+    const float* __restrict__ w_la, T* __restrict__ O, float* __restrict__ O_nla_out,
+    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps) {
+    constexpr int DP = D / 4;       // elements of a row per lane
+    constexpr int DPP = DP + 4;     // padded quarter stride (floats): quarters land in different banks
+    constexpr int EPL = Vec16<T>::N;
+    __shared__ __align__(16) float s_k[SM_BN][4 * DPP];
+    __shared__ __align__(16) float s_v[SM_BN][4 * DPP];
+
+    const int bh = blockIdx.y;
+    const int q0 = blockIdx.x * SM_BM;
+    const int tid = threadIdx.x;
+    const int r = tid >> 2, part = tid & 3;
+    const int t = q0 + r;
+    const size_t row_off = ((size_t)bh * L + t) * D + part * DP;
+
+    float q[DP], acc[DP];
+#pragma unroll
+    for (int c = 0; c < DP; c += EPL) Vec16<T>::load(Q + row_off + c, q + c);
+#pragma unroll
+    for (int c = 0; c < DP; ++c) { q[c] *= scale; acc[c] = 0.f; }
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int my_cnt = cnt[(size_t)bh * L + t];
+    const int n_hi = cnt[(size_t)bh * L + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
+
+    for (int c0 = 0; c0 < n_hi; c0 += SM_BN) {
+        __syncthreads();
+        for (int e = tid * EPL; e < SM_BN * D; e += SM_THREADS * EPL) {
+            const int i = e / D, c = e % D;
+            float tk[EPL], tv[EPL];
+            if (c0 + i < n_hi) {
+                const size_t src = ((size_t)bh * L + c0 + i) * D + c;
+                Vec16<T>::load(Kc + src, tk);
+                Vec16<T>::load(Vc + src, tv);
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) { tk[j] = 0.f; tv[j] = 0.f; }
+            }
+            const int pq = c / DP, pc = c % DP;   // EPL divides DP: a 16-byte group stays in one quarter
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                s_k[i][pq * DPP + pc + j] = tk[j];
+                s_v[i][pq * DPP + pc + j] = tv[j];
+            }
+        }
+        __syncthreads();
+
+        if (c0 < my_cnt) {
+            for (int kb = 0; kb < SM_BN; kb += SM_KB) {
+                if (c0 + kb >= my_cnt) break;
+                float s[SM_KB];
+#pragma unroll
+                for (int j = 0; j < SM_KB; ++j) {
+                    const float* kr = &s_k[kb + j][part * DPP];
+                    float dot = 0.f;
+#pragma unroll
+                    for (int c = 0; c < DP; c += 4) {
+                        const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
+                        dot += q[c] * k4.x + q[c + 1] * k4.y + q[c + 2] * k4.z + q[c + 3] * k4.w;
+                    }
+                    dot += __shfl_xor(dot, 1);
+                    dot += __shfl_xor(dot, 2);
+                    s[j] = (c0 + kb + j < my_cnt) ? dot : -INFINITY;
+                }
+                float bm = s[0];
+#pragma unroll
+                for (int j = 1; j < SM_KB; ++j) bm = fmaxf(bm, s[j]);
+                const float m_new = fmaxf(m_run, bm);      // finite: key c0+kb is visible
+                const float corr = expf(m_run - m_new);    // exp(-inf) = 0 on the first step
+                float p[SM_KB], psum = 0.f;
+#pragma unroll
+                for (int j = 0; j < SM_KB; ++j) { p[j] = expf(s[j] - m_new); psum += p[j]; }
+                l_run = l_run * corr + psum;
+                m_run = m_new;
+#pragma unroll
+                for (int c = 0; c < DP; ++c) acc[c] *= corr;
+#pragma unroll
+                for (int j = 0; j < SM_KB; ++j) {
+                    const float* vr = &s_v[kb + j][part * DPP];
+#pragma unroll
+                    for (int c = 0; c < DP; c += 4) {
+                        const float4 v4 = *reinterpret_cast<const float4*>(vr + c);
+                        acc[c] += p[j] * v4.x; acc[c + 1] += p[j] * v4.y;
+                        acc[c + 2] += p[j] * v4.z; acc[c + 3] += p[j] * v4.w;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: normalise, optional branch outputs, merge, store -----------------------
+    const float inv_l = (l_run > 0.f) ? 1.f / l_run : 0.f;
+#pragma unroll
+    for (int c = 0; c < DP; ++c) acc[c] *= inv_l;
+    if (lse_out != nullptr && part == 0)
+        lse_out[(size_t)bh * L + t] = (l_run > 0.f) ? m_run + logf(l_run) : -INFINITY;
+    if (O_nla_out != nullptr) {
+#pragma unroll
+        for (int c = 0; c < DP; c += 4)
+            *reinterpret_cast<float4*>(O_nla_out + row_off + c) =
+                make_float4(acc[c], acc[c + 1], acc[c + 2], acc[c + 3]);
+    }
+    float la[DP];
+#pragma unroll
+    for (int c = 0; c < DP; c += 4) {
+        const float4 x = *reinterpret_cast<const float4*>(O_la + row_off + c);
+        la[c] = x.x; la[c + 1] = x.y; la[c + 2] = x.z; la[c + 3] = x.w;
+    }
+    float out[DP];
+    if (combine_mode == 0) {
+#pragma unroll
+        for (int c = 0; c < DP; ++c) out[c] = la[c] + acc[c];
+    } else {
+        float ss_la = 0.f, ss_nla = 0.f;
+#pragma unroll
+        for (int c = 0; c < DP; ++c) { ss_la += la[c] * la[c]; ss_nla += acc[c] * acc[c]; }
+        ss_la += __shfl_xor(ss_la, 1); ss_la += __shfl_xor(ss_la, 2);
+        ss_nla += __shfl_xor(ss_nla, 1); ss_nla += __shfl_xor(ss_nla, 2);
+        const float wn = (w_nla ? w_nla[(size_t)bh * L + t] : 0.5f) / sqrtf(ss_nla / D + eps);
+        const float wl = (w_la ? w_la[(size_t)bh * L + t] : 0.5f) / sqrtf(ss_la / D + eps);
+#pragma unroll
+        for (int c = 0; c < DP; ++c) out[c] = wn * acc[c] + wl * la[c];
+    }
+#pragma unroll
+    for (int c = 0; c < DP; c += EPL) Vec16<T>::store(O + row_off + c, out + c);
+}
+
+template <typename T>
+static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const int32_t* cnt,
+                      const float* O_la, const float* w_nla, const float* w_la, void* O, float* O_nla_out,
+                      float* lse_out, hipStream_t st) {
+    dim3 grid(pl.L / SM_BM, pl.BH);
+    if (pl.d == 64)
+        hipLaunchKernelGGL((softmax_fp32_kernel<T, 64>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
+                           (const T*)Kc, (const T*)Vc, cnt, O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+    else
+        hipLaunchKernelGGL((softmax_fp32_kernel<T, 128>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
+                           (const T*)Kc, (const T*)Vc, cnt, O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+}
+
+nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
+                                const int32_t* cnt, const float* O_la, const float* w_nla,
+                                const float* w_la, void* O, float* O_nla_out, float* lse_out,
+                                hipStream_t st) {
+    if (pl.dtype == NATS_BF16)
+        launch_sm<bf16_t>(pl, Q, Kc, Vc, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+    else
+        launch_sm<float>(pl, Q, Kc, Vc, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+    return check_launch("softmax_fp32");
+}
+
+}  // namespace nats

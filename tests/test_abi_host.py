@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+function nats.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_03681_amd import binding as nb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nats.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_UNSUP = 0, -1, -2, -3, -4, -5, -6
+FAKE = 0x10000  # an aligned non-NULL "device pointer"; validation fails before it is ever used
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(nb.library_path()):
+        from paper_2602_03681_amd.build import build_library
+        build_library()
+    return nb.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nats_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(nb.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_abi_version(lib):
+    assert lib.nats_abi_version() == 100
+
+
+def good_params(**over):
+    kw = dict(B=1, H=2, L=256, d=64, C=64, dtype_code=nb.NATS_F32)
+    kw.update(over)
+    return nb.make_fwd_params(**kw)
+
+
+def test_workspace_bytes(lib):
+    p = good_params()
+    n = nb.fwd_workspace_bytes(p)
+    # at least cnt + idx + compacted K,V + fp32 linear-branch output
+    assert n >= 2 * 512 * 4 + 2 * 512 * 64 * 4 + 512 * 64 * 4
+    assert nb.fwd_workspace_bytes(good_params(L=100)) == 0          # L % C != 0
+    assert nb.fwd_workspace_bytes(good_params(d=48)) == 0
+    big = nb.fwd_workspace_bytes(good_params(B=2, H=16, L=8192, d=128, dtype_code=nb.NATS_BF16))
+    assert big > n
+
+
+def call_fwd(lib, p, ptrs=None, ws=FAKE, ws_bytes=1 << 40, extra=None):
+    ptrs = [FAKE] * 7 if ptrs is None else ptrs
+    return lib.nats_hybrid_attn_fwd_ex(ctypes.byref(p), *ptrs, extra, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(L=100), E_SHAPE), (dict(L=0), E_SHAPE), (dict(B=0), E_SHAPE), (dict(d=96), E_SHAPE),
+    (dict(dtype_code=7), E_DTYPE), (dict(C=32, L=256), E_UNSUP), (dict(combine_mode=3), E_SHAPE),
+    (dict(math=9), E_SHAPE), (dict(B=70000, H=1), E_SHAPE),
+])
+def test_bad_params_are_rejected(lib, over, code):
+    assert call_fwd(lib, good_params(**over)) == code
+    assert lib.nats_last_error() != b""
+
+
+def test_null_misaligned_and_workspace_errors(lib):
+    p = good_params()
+    assert lib.nats_hybrid_attn_fwd_ex(None, *([FAKE] * 7), None, FAKE, 1 << 40, None) == E_NULL
+    for i in range(7):
+        ptrs = [FAKE] * 7
+        ptrs[i] = None
+        assert call_fwd(lib, p, ptrs) == E_NULL
+    ptrs = [FAKE] * 7
+    ptrs[2] = FAKE + 4
+    assert call_fwd(lib, p, ptrs) == E_ALIGN
+    assert b"aligned" in lib.nats_last_error()
+    assert call_fwd(lib, p, ws=None) == E_WS
+    assert call_fwd(lib, p, ws_bytes=nb.fwd_workspace_bytes(p) - 1) == E_WS
+    assert b"needed" in lib.nats_last_error()
+    # O aliasing an input
+    assert call_fwd(lib, p, [FAKE, FAKE + 16, FAKE + 32, FAKE + 48, FAKE + 64, FAKE + 80, FAKE]) == E_SHAPE
+    # Kc without Vc
+    ex = nb.FwdExtra()
+    ex.Kc = FAKE
+    assert call_fwd(lib, p, [FAKE + 16 * i for i in range(7)], extra=ctypes.byref(ex)) == E_NULL
+
+
+def test_plain_fwd_goes_through_the_same_validation(lib):
+    p = good_params(L=100)
+    assert lib.nats_hybrid_attn_fwd(ctypes.byref(p), *([FAKE] * 7), FAKE, 1 << 40, None) == E_SHAPE
+
+
+def test_decode_validation(lib):
+    def call(p, ptrs=None):
+        ptrs = [FAKE + 16 * i for i in range(14)] if ptrs is None else ptrs
+        return lib.nats_hybrid_attn_decode(ctypes.byref(p), *ptrs, None)
+    good = nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0.0, 0.0, 0, 0.0)
+    assert call(nb.DecParams(4, 2, 100, 512, nb.NATS_BF16, 0, 0, 0, 0)) == E_SHAPE
+    assert call(nb.DecParams(4, 2, 128, 0, nb.NATS_BF16, 0, 0, 0, 0)) == E_SHAPE
+    assert call(nb.DecParams(4, 2, 128, 512, 5, 0, 0, 0, 0)) == E_DTYPE
+    assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 2, 0)) == E_SHAPE
+    ptrs = [FAKE + 16 * i for i in range(14)]
+    ptrs[0] = None
+    assert call(good, ptrs) == E_NULL
+    ptrs = [FAKE + 16 * i for i in range(14)]
+    ptrs[4] = FAKE + 2
+    assert call(good, ptrs) == E_ALIGN
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(nb, "_lib", None)
+    monkeypatch.setattr(nb, "_LIB_PATH", str(tmp_path / "libnats.so"))
+    with pytest.raises(FileNotFoundError):
+        nb.load_library()
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros((1, 1, 64, 64))
+    a = torch.zeros((1, 1, 64))
+    m = torch.zeros((1, 1, 64), dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        nb.hybrid_attn_fwd(x, x, x, a, a, m)

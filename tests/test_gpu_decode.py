@@ -1,0 +1,109 @@
+"""GPU parity of the single-token decode step against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_03681_amd as nats
+from nats_inputs import CONFIGS, DecodeConfig, make_decode_inputs, make_fwd_inputs
+from oracle import c_oracle
+
+from gpu_util import TOL, host, oracle_fwd, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode_chain(cfg, steps, n_check_b, dtype, **kw):
+    """GPU runs all B sequences for `steps` steps; the oracle follows the first n_check_b of them."""
+    x = make_decode_inputs(cfg, steps=steps)
+    g = to_dev(x, dtype)
+    state = g["state"].clone()
+    kc, vc, clen = g["k_cache"].clone(), g["v_cache"].clone(), g["cache_len"].clone()
+    err = torch.zeros((cfg.B, cfg.H), dtype=torch.int32, device="cuda")
+    nb_ = n_check_b
+    S_ref = x["state"][:nb_].astype(np.float64)
+    kc_ref = np.ascontiguousarray(x["k_cache"][:nb_]); vc_ref = np.ascontiguousarray(x["v_cache"][:nb_])
+    clen_ref = np.ascontiguousarray(x["cache_len"][:nb_])
+    worst = 0.0
+    okw = {k: v for k, v in kw.items()}
+    for s in range(steps):
+        o = nats.hybrid_attn_decode(state, kc, vc, clen, g["q"][s], g["k"][s], g["v"][s], g["alpha"][s],
+                                    g["beta"][s], g["mask"][s], err_flags=err, **kw)
+        o_ref, ovf = c_oracle.decode(S_ref, kc_ref, vc_ref, clen_ref, x["q"][s, :nb_], x["k"][s, :nb_],
+                                     x["v"][s, :nb_], x["alpha"][s, :nb_], x["beta"][s, :nb_],
+                                     x["mask"][s, :nb_],
+                                     softmax_scale=okw.get("softmax_scale") or None,
+                                     la_scale=okw.get("la_scale") or 1.0, mode=okw.get("combine_mode", 0),
+                                     eps=okw.get("rms_eps") or 1e-6)
+        e = rel_err(host(o)[:nb_], o_ref)
+        worst = max(worst, e)
+        assert e <= TOL[dtype], f"step {s}: {e:.3e}"
+        np.testing.assert_array_equal(host(err)[:nb_], ovf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(clen)[:nb_], clen_ref)
+    assert rel_err(host(state)[:nb_], S_ref) <= TOL[dtype]
+    # the caches hold input rows verbatim
+    np.testing.assert_array_equal(host(kc)[:nb_], kc_ref)
+    np.testing.assert_array_equal(host(vc)[:nb_], vc_ref)
+    # every sequence, not only the checked ones, advanced its cache length by its number of softmax tokens
+    np.testing.assert_array_equal(host(clen), x["cache_len"] + x["mask"].astype(np.int32).sum(0))
+    return worst
+
+
+def test_cfg4_decode_256_steps():
+    cfg = CONFIGS["cfg4_decode_bf16"]
+    worst = run_decode_chain(cfg, cfg.steps, n_check_b=4, dtype="bf16")
+    print("cfg4 worst step err", worst)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64)])
+def test_decode_small_variants(dtype, d):
+    cfg = DecodeConfig("small", 3, 2, d, dtype, 0.3, seed=31 + d, len_lo=1, len_hi=70, steps=24)
+    run_decode_chain(cfg, 24, n_check_b=3, dtype=dtype)
+    run_decode_chain(cfg, 8, n_check_b=3, dtype=dtype, combine_mode=1, softmax_scale=float(np.sqrt(d)),
+                     la_scale=0.7, rms_eps=1e-5)
+
+
+def test_decode_empty_cache_and_overflow():
+    """cache_len = 0 with a linear token -> o = o_la only; a softmax token on a full cache raises the flag."""
+    B, H, d, cap = 1, 2, 64, 3
+    rng = np.random.default_rng(5)
+    f = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32)).cuda()
+    state = f(B, H, d, d) * 0.1
+    kc, vc = f(B, H, cap, d), f(B, H, cap, d)
+    clen = torch.tensor([[0, cap]], dtype=torch.int32, device="cuda")
+    q, k, v = f(B, H, d), f(B, H, d), f(B, H, d)
+    alpha = torch.full((B, H), 0.9, device="cuda"); beta = torch.full((B, H), 0.5, device="cuda")
+    mask = torch.tensor([[0, 1]], dtype=torch.uint8, device="cuda")
+    err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    S_ref = host(state).astype(np.float64); kc_ref, vc_ref = host(kc).copy(), host(vc).copy()
+    clen_ref = host(clen).copy()
+    o = nats.hybrid_attn_decode(state, kc, vc, clen, q, k, v, alpha, beta, mask, err_flags=err)
+    o_ref, ovf = c_oracle.decode(S_ref, kc_ref, vc_ref, clen_ref, host(q), host(k), host(v), host(alpha),
+                                 host(beta), host(mask))
+    assert rel_err(host(o), o_ref) <= TOL["f32"]
+    np.testing.assert_array_equal(host(err), [[0, 1]])
+    np.testing.assert_array_equal(ovf, [[0, 1]])
+    np.testing.assert_array_equal(host(clen), [[0, cap]])
+    np.testing.assert_array_equal(host(kc), kc_ref)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_then_decode_matches_longer_prefill(dtype):
+    """fwd_ex(L) hands over (final_state, Kc, Vc, n_s); decoding tokens L..L+n-1 must give the rows of fwd(L+n)."""
+    B, H, L, n, d = 2, 2, 192, 16, 128
+    x = make_fwd_inputs(B, H, L + 64, d, dtype, 0.15, seed=21)
+    ref = oracle_fwd(x, want=())
+    xp = {k: np.ascontiguousarray(v[:, :, :L]) for k, v in x.items()}
+    g = to_dev(xp, dtype)
+    cap = L + n
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64,
+                                want=("final_state", "Kc", "Vc", "n_s"), cap=cap)
+    state, kc, vc, clen = r["final_state"], r["Kc"], r["Vc"], r["n_s"]
+    gf = to_dev(x, dtype)
+    for t in range(L, L + n):
+        o = nats.hybrid_attn_decode(state, kc, vc, clen, gf["Q"][:, :, t].contiguous(),
+                                    gf["K"][:, :, t].contiguous(), gf["V"][:, :, t].contiguous(),
+                                    gf["alpha"][:, :, t].contiguous(), gf["beta"][:, :, t].contiguous(),
+                                    gf["mask"][:, :, t].contiguous())
+        e = rel_err(host(o), ref["O"][:, :, t])
+        assert e <= TOL[dtype], f"token {t}: {e:.3e}"
