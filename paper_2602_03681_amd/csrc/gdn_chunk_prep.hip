@@ -1,0 +1,237 @@
+// Chunkwise Gated DeltaNet, step 1 of 2: everything inside a chunk that does not depend
+// on the running state (Section 3, Eq. 6-7 applied to the update rule of Eq. 19, with
+// Eq. 14 / Eq. 20 folded in as  b'_t = beta_t (1 - m_t)  and decay at every token).
+//
+// For one chunk of C = 64 tokens, with g_r = sum_{i<=r} log alpha_i (inside the chunk):
+//   D[r,i]  = exp(g_r - g_i)                       (i <= r)
+//   A       = strict_lower( diag(b') (K K^T . D) )
+//   T       = (I + A)^{-1}                         (unit lower triangular, fp32 forward substitution)
+//   W       = T diag(b' exp(g)) K                  -> stored negated, fp16 [tok][d_k]
+//   U~      = T diag(b') V                         -> stored transposed, fp16 [d_v][tok]
+//   P       = (Q K^T) . D  (i <= r)                -> fp16 [tok r][tok i]
+//   Kd^T    = (diag(exp(g_C - g)) K)^T             -> fp16 [d_k][tok]
+//   gam     = exp(g)                               -> fp32 [tok]
+// so that the state-carrying kernel only needs
+//   U = U~ - W S0^T,  O = diag(gam) Q S0^T + P U,  S1 = exp(g_C) S0 + U^T Kd.
+//
+// One block per chunk (grid: chunks x B*H), 4 wavefronts.  All matrix products run on
+// MFMA with fp16 operands / fp32 accumulation; products are arranged (transposed where
+// needed) so that every result tile is stored as 4 consecutive fp16 along the layout the
+// consumer reads.  MFMA-bound in its products, latency-bound in the 64-step substitution.
+#include <math.h>
+
+#include "mfma_util.h"
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int PREP_THREADS = 256;
+constexpr int CH = 64;        // chunk size
+constexpr int AS_STRIDE = 68; // fp32 row stride of the A matrix in LDS
+
+template <int D>
+constexpr size_t prep_lds_bytes() {
+    return (size_t)(2 * CH * (D + LDS_PAD) + 2 * D * (CH + LDS_PAD)) * sizeof(half_t) +
+           (size_t)(CH * AS_STRIDE + 4 * CH) * sizeof(float);
+}
+
+template <int D>
+__global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
+    int L, half_t* __restrict__ Wneg, half_t* __restrict__ KdT, half_t* __restrict__ UtT,
+    half_t* __restrict__ P, float* __restrict__ gam) {
+    constexpr int RS = D + LDS_PAD;   // row stride, row-major [tok][d] tiles
+    constexpr int TS = CH + LDS_PAD;  // row stride, transposed [d][tok] tiles
+    extern __shared__ __align__(16) unsigned char smem[];
+    half_t* Ks = reinterpret_cast<half_t*>(smem);  // [64][RS]  K, fp16
+    half_t* Qs = Ks + CH * RS;                     // [64][RS]  Q
+    half_t* KsT = Qs + CH * RS;                    // [D][TS]   K^T
+    half_t* VsT = KsT + D * TS;                    // [D][TS]   V^T
+    float* As = reinterpret_cast<float*>(VsT + D * TS);  // [64][AS_STRIDE]
+    float* s_g = As + CH * AS_STRIDE;
+    float* s_gam = s_g + CH;
+    float* s_bp = s_gam + CH;
+    float* s_gdec = s_bp + CH;
+    half_t* Tp = Ks;   // [64][TS]  T diag(b' gam)  (reuses Ks once K K^T is done)
+    half_t* Tpp = Qs;  // [64][TS]  T diag(b')
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int n_chunks = L / CH;
+    const size_t gc = (size_t)blockIdx.y * n_chunks + blockIdx.x;  // global chunk id
+    const size_t tok0 = (size_t)blockIdx.y * L + (size_t)blockIdx.x * CH;
+
+    // ---- gates: cumulative log-decay and write strengths -------------------------------
+    if (wave == 0) {
+        const float a = alpha[tok0 + lane];
+        float g = logf(fmaxf(a, 1e-30f));
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float up = __shfl_up(g, off);
+            if (lane >= off) g += up;
+        }
+        const float gC = __shfl(g, 63);
+        s_g[lane] = g;
+        s_gam[lane] = expf(g);
+        s_gdec[lane] = expf(gC - g);
+        s_bp[lane] = mask[tok0 + lane] ? 0.f : beta[tok0 + lane];
+    }
+    // ---- tiles: K (row-major and transposed), Q (row-major), V (transposed) ----------------
+    // consecutive lanes take consecutive tokens so that the 2-byte transposed writes of a
+    // wavefront fall into consecutive LDS addresses
+    for (int e = tid; e < CH * D / 8; e += PREP_THREADS) {
+        const int row = e & 63, c8 = e >> 6;
+        const size_t src = (tok0 + row) * D + c8 * 8;
+        const half8 hk = bf16x8_to_half8(*reinterpret_cast<const uint4*>(K + src));
+        const half8 hq = bf16x8_to_half8(*reinterpret_cast<const uint4*>(Q + src));
+        const half8 hv = bf16x8_to_half8(*reinterpret_cast<const uint4*>(V + src));
+        *reinterpret_cast<half8*>(Ks + row * RS + c8 * 8) = hk;
+        *reinterpret_cast<half8*>(Qs + row * RS + c8 * 8) = hq;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            KsT[(c8 * 8 + j) * TS + row] = hk[j];
+            VsT[(c8 * 8 + j) * TS + row] = hv[j];
+        }
+    }
+    __syncthreads();
+
+    // ---- K K^T -> A (LDS, fp32) and (Q K^T . D) -> P (global), lower 16x16 tiles ----------
+    {
+        // 16x16 tile jobs (a, b), one hex digit per job: the 10 lower tiles, then the two
+        // upper tiles (0,1) and (2,3) that only need zeros
+        constexpr uint64_t JA = 0x203333222110ull;  // a of job 0 in the lowest digit
+        constexpr uint64_t JB = 0x313210210100ull;
+        half_t* Pc = P + gc * (CH * CH);
+        for (int job = wave; job < 12; job += 4) {
+            const int a = (int)((JA >> (4 * job)) & 15), b = (int)((JB >> (4 * job)) & 15);
+            if (a < b) {  // an upper tile the consumer's 32-wide contraction step still reads: zeros
+                half4 z = {0, 0, 0, 0};
+                *reinterpret_cast<half4*>(Pc + (16 * a + l16) * CH + 16 * b + 4 * lq) = z;
+                continue;
+            }
+            f32x4 accK = {0.f, 0.f, 0.f, 0.f}, accP = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < D / 32; ++ks) {
+                const int ko = 32 * ks + 8 * lq;
+                const half8 fa = lds_read8(Ks + (16 * a + l16) * RS + ko);
+                const half8 fb = lds_read8(Ks + (16 * b + l16) * RS + ko);
+                const half8 fq = lds_read8(Qs + (16 * a + l16) * RS + ko);
+                accK = mfma16(fa, fb, accK);  // rows: tokens of block a, cols: tokens of block b
+                accP = mfma16(fb, fq, accP);  // rows: key tokens i of block b, cols: query tokens r of block a
+            }
+            {   // A[r][i], r = 16a + 4 lq + j, i = 16b + l16
+                const int i = 16 * b + l16;
+                const float gi = s_g[i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 16 * a + 4 * lq + j;
+                    As[r * AS_STRIDE + i] = (i < r) ? s_bp[r] * accK[j] * expf(s_g[r] - gi) : 0.f;
+                }
+            }
+            {   // P[r][i], r = 16a + l16, i = 16b + 4 lq + j
+                const int r = 16 * a + l16;
+                const float gr = s_g[r];
+                f32x4 pv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = 16 * b + 4 * lq + j;
+                    pv[j] = (i <= r) ? accP[j] * expf(gr - s_g[i]) : 0.f;
+                }
+                *reinterpret_cast<half4*>(Pc + r * CH + 16 * b + 4 * lq) = to_half4(pv);
+            }
+        }
+    }
+    __syncthreads();
+
+    if (wave == 0) {
+        // ---- T = (I + A)^{-1}: lane j owns column j; row r needs rows < r -------------------
+        float col[CH];
+#pragma unroll
+        for (int r = 0; r < CH; ++r) col[r] = 0.f;
+#pragma unroll
+        for (int r = 0; r < CH; ++r) {
+            float acc = 0.f;
+#pragma unroll
+            for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {   // A[r][i] is 0 for i >= r, col[i] is 0 there too
+                const float4 a4 = *reinterpret_cast<const float4*>(As + r * AS_STRIDE + 4 * i4);
+                acc += a4.x * col[4 * i4] + a4.y * col[4 * i4 + 1] + a4.z * col[4 * i4 + 2] +
+                       a4.w * col[4 * i4 + 3];
+            }
+            col[r] = ((r == lane) ? 1.f : 0.f) - acc;
+        }
+        const float bpj = s_bp[lane], bgj = s_bp[lane] * s_gam[lane];
+#pragma unroll
+        for (int r = 0; r < CH; ++r) {
+            Tpp[r * TS + lane] = f32_to_half_sat(col[r] * bpj);
+            Tp[r * TS + lane] = f32_to_half_sat(col[r] * bgj);
+        }
+    } else {
+        // ---- Kd^T = K^T diag(exp(g_C - g)) and gam, straight to global -----------------------
+        half_t* Kd = KdT + gc * (size_t)(D * CH);
+        for (int e = tid - 64; e < D * CH / 8; e += PREP_THREADS - 64) {
+            const int dk = e >> 3, t8 = e & 7;
+            half8 h = lds_read8(KsT + dk * TS + t8 * 8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * s_gdec[t8 * 8 + j]);
+            *reinterpret_cast<half8*>(Kd + dk * CH + t8 * 8) = h;
+        }
+        if (wave == 1) gam[gc * CH + lane] = s_gam[lane];
+    }
+    __syncthreads();
+
+    // ---- W^T = K^T (T diag(b' gam))^T  and  U~ = (T diag(b')) V ------------------------------
+    {
+        half_t* Wc = Wneg + gc * (size_t)(CH * D);
+        half_t* Uc = UtT + gc * (size_t)(D * CH);
+#pragma unroll
+        for (int mi = 0; mi < D / 64; ++mi) {
+            const int m = wave * (D / 64) + mi;  // 16-wide tile index along d_k (W) / d_v (U~)
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {        // 16-token tile; T is lower triangular: k-steps 0..n/2
+                f32x4 accW = {0.f, 0.f, 0.f, 0.f}, accU = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks <= n / 2; ++ks) {
+                    const int ko = 32 * ks + 8 * lq;
+                    const half8 fk = lds_read8(KsT + (16 * m + l16) * TS + ko);
+                    const half8 fv = lds_read8(VsT + (16 * m + l16) * TS + ko);
+                    const half8 ft = lds_read8(Tp + (16 * n + l16) * TS + ko);
+                    const half8 ftt = lds_read8(Tpp + (16 * n + l16) * TS + ko);
+                    accW = mfma16(fk, ft, accW);   // rows d_k = 16m + 4lq + j, col token r = 16n + l16
+                    accU = mfma16(ftt, fv, accU);  // rows token r = 16n + 4lq + j, col d_v = 16m + l16
+                }
+                f32x4 neg = {-accW[0], -accW[1], -accW[2], -accW[3]};
+                *reinterpret_cast<half4*>(Wc + (16 * n + l16) * D + 16 * m + 4 * lq) = to_half4(neg);
+                *reinterpret_cast<half4*>(Uc + (16 * m + l16) * CH + 16 * n + 4 * lq) = to_half4(accU);
+            }
+        }
+    }
+}
+
+// workspace arrays of the chunkwise path, per chunk: Wneg [64][D], KdT [D][64], UtT [D][64],
+// P [64][64] (fp16) and gam [64] (fp32)
+nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
+                                  const float* alpha, const float* beta, const uint8_t* mask, void* Wneg,
+                                  void* KdT, void* UtT, void* P, float* gam, hipStream_t st) {
+    dim3 grid(pl.L / CH, pl.BH);
+    if (pl.d == 64) {
+        auto kern = gdn_chunk_prep_kernel<64>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)prep_lds_bytes<64>()) != hipSuccess)
+            return check_launch("gdn_chunk_prep (LDS attribute)");
+        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<64>(), st, (const bf16_t*)Q,
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)Wneg,
+                           (half_t*)KdT, (half_t*)UtT, (half_t*)P, gam);
+    } else {
+        auto kern = gdn_chunk_prep_kernel<128>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)prep_lds_bytes<128>()) != hipSuccess)
+            return check_launch("gdn_chunk_prep (LDS attribute)");
+        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<128>(), st, (const bf16_t*)Q,
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)Wneg,
+                           (half_t*)KdT, (half_t*)UtT, (half_t*)P, gam);
+    }
+    return check_launch("gdn_chunk_prep");
+}
+
+}  // namespace nats

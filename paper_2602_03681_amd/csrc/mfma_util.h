@@ -1,0 +1,57 @@
+// MFMA fragment helpers for gfx950 (wave64), internal header.
+//
+// v_mfma_f32_16x16x32_f16 lane layout (lane l of 64):
+//   A fragment: row  m = l % 16, contraction slots k = 8*(l/16) + j, j = 0..7
+//   B fragment: col  n = l % 16, contraction slots k = 8*(l/16) + j
+//   C/D       : rows 4*(l/16) + j (j = 0..3), col l % 16
+// so both operands are read as 8 consecutive fp16 (16 bytes) from a buffer that is
+// contiguous along the contraction index, and a result tile hands every lane four
+// consecutive rows of one column.
+//
+// MFMA operands are fp16 with fp32 accumulation: bf16 tensors convert exactly
+// (8 significant bits, values clamped to the fp16 range), and intermediates rounded to
+// fp16 carry 2^-12 relative error instead of bf16's 2^-9, which the parity bar needs.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nats {
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(half8 a, half8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ half_t f32_to_half_sat(float f) {
+    return (half_t)__builtin_amdgcn_fmed3f(f, -65504.f, 65504.f);
+}
+
+// 8 consecutive bf16 (one 16-byte word) -> 8 fp16, exact inside the fp16 range
+__device__ __forceinline__ half8 bf16x8_to_half8(uint4 w) {
+    const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+    half8 h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[2 * i] = f32_to_half_sat(__uint_as_float(u[i] << 16));
+        h[2 * i + 1] = f32_to_half_sat(__uint_as_float(u[i] & 0xffff0000u));
+    }
+    return h;
+}
+
+__device__ __forceinline__ half8 lds_read8(const half_t* p) { return *reinterpret_cast<const half8*>(p); }
+__device__ __forceinline__ half4 lds_read4(const half_t* p) { return *reinterpret_cast<const half4*>(p); }
+
+__device__ __forceinline__ half4 to_half4(f32x4 v) {
+    half4 h;
+    h[0] = f32_to_half_sat(v[0]); h[1] = f32_to_half_sat(v[1]);
+    h[2] = f32_to_half_sat(v[2]); h[3] = f32_to_half_sat(v[3]);
+    return h;
+}
+
+constexpr int LDS_PAD = 8;  // fp16 elements added to every LDS row: 16-byte reads of 16 rows hit distinct banks
+
+}  // namespace nats
