@@ -49,6 +49,9 @@ ProfScope::~ProfScope() {
     if (slot >= 0) (void)hipEventRecord(g_prof[slot].stop, stream);
 }
 
+// bf16 tensors take the chunkwise MFMA kernels unless fp32 arithmetic is asked for
+static bool uses_chunk_path(const FwdPlan& pl) { return pl.dtype == NATS_BF16 && pl.math == NATS_MATH_AUTO; }
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
@@ -94,6 +97,14 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
+    pl->off_w = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = 0;
+    if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
+        pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
+        pl->off_kd = off;  off = align_up(off + n_tok * pl->d * 2, 256);
+        pl->off_ut = off;  off = align_up(off + n_tok * pl->d * 2, 256);
+        pl->off_p = off;   off = align_up(off + n_tok * pl->C * 2, 256);
+        pl->off_gam = off; off = align_up(off + n_tok * 4, 256);
+    }
     pl->total = off;
     return NATS_OK;
 }
@@ -206,8 +217,23 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap, stream);
     }
     if (st != NATS_OK) return st;
-    // Both tensor dtypes currently run the fp32-arithmetic kernels.
-    {
+    if (uses_chunk_path(pl)) {
+        void* Wneg = ws + pl.off_w;
+        void* KdT = ws + pl.off_kd;
+        void* UtT = ws + pl.off_ut;
+        void* P = ws + pl.off_p;
+        float* gam = reinterpret_cast<float*>(ws + pl.off_gam);
+        {
+            ProfScope ps("gdn_chunk_prep", stream);
+            st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, Wneg, KdT, UtT, P, gam, stream);
+        }
+        if (st != NATS_OK) return st;
+        {
+            ProfScope ps("gdn_chunk_scan", stream);
+            st = launch_gdn_chunk_scan(pl, Q, Wneg, KdT, UtT, P, gam, ex.initial_state, ex.final_state, O_la,
+                                       stream);
+        }
+    } else {
         ProfScope ps("gdn_recurrent", stream);
         st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la, stream);
     }
