@@ -96,13 +96,13 @@ struct FwdPlan {
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_kd, off_ut, off_p, off_gam;
+    size_t off_w, off_kd, off_ut, off_p, off_gam, off_vht;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
                                 int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
-                                void* Kc_user, void* Vc_user, int cap_user, hipStream_t st);
+                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, hipStream_t st);
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
                                  const float* S0, float* S_final, float* O_la, hipStream_t st);
@@ -116,6 +116,10 @@ nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                 hipStream_t st);
+nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
+                                 const int32_t* cnt, const float* O_la, const float* w_nla,
+                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
+                                 hipStream_t st);
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
                           float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
                           const void* k, const void* v, const float* alpha, const float* beta,

@@ -8,9 +8,14 @@
 // count is recomputed from the mask bytes in front of the segment (at most L
 // bytes, read 16 at a time and served by L2), so blocks need no ordering and
 // no inter-block communication.
+#include "mfma_util.h"
 #include "nats_common.h"
 
 namespace nats {
+
+// fp16 value of one stored element (the MFMA softmax kernel's V^T operand)
+__device__ __forceinline__ half_t elem_to_half(bf16_t x) { return f32_to_half_sat(to_float(x)); }
+__device__ __forceinline__ half_t elem_to_half(float x) { return f32_to_half_sat(x); }
 
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_SEG = SCAN_THREADS * 4;  // tokens per block, 4 per thread
@@ -19,7 +24,8 @@ template <typename T>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     const uint8_t* __restrict__ mask, const T* __restrict__ K, const T* __restrict__ V, int L, int d,
     int32_t* __restrict__ cnt, int32_t* __restrict__ idx, int32_t* __restrict__ n_s, T* __restrict__ Kc,
-    T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user) {
+    T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user,
+    half_t* __restrict__ VhT) {
     __shared__ int s_wave[SCAN_THREADS / 64];
     __shared__ int s_pos[SCAN_SEG];
     const int bh = blockIdx.y;
@@ -98,21 +104,37 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
             *reinterpret_cast<uint4*>(Kc_user + du) = kv;
             *reinterpret_cast<uint4*>(Vc_user + du) = vv;
         }
+        if (VhT != nullptr) {   // fp16 copy, transposed inside tiles of 64 compacted rows: [tile][d][64]
+            const T* ve = reinterpret_cast<const T*>(&vv);
+            half_t* tile = VhT + ((size_t)bh * L + (size_t)(c >> 6) * 64) * d;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) tile[(size_t)(part * EPL + j) * 64 + (c & 63)] = elem_to_half(ve[j]);
+        }
+    }
+    // the tail of the last V^T tile is multiplied by zero weights downstream: make it finite
+    if (VhT != nullptr && seg0 + SCAN_SEG >= L) {
+        const int n_total = before + seg_total;
+        const int pad = ((n_total + 63) & ~63) - n_total;
+        half_t* tile = VhT + ((size_t)bh * L + (size_t)(n_total >> 6) * 64) * d;
+        for (int e = tid; e < pad * d; e += SCAN_THREADS) {
+            const int dv = e / pad, cc = (n_total & 63) + e % pad;
+            tile[(size_t)dv * 64 + cc] = (half_t)0.f;
+        }
     }
 }
 
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
                                 int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
-                                void* Kc_user, void* Vc_user, int cap_user, hipStream_t st) {
+                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, hipStream_t st) {
     dim3 grid((pl.L + SCAN_SEG - 1) / SCAN_SEG, pl.BH);
     if (pl.dtype == NATS_BF16) {
         hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
-                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user);
+                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT);
     } else {
         hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
-                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user);
+                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT);
     }
     return check_launch("scan_compact");
 }
