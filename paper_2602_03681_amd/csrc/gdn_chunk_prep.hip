@@ -5,7 +5,7 @@
 // For one chunk of C = 64 tokens, with g_r = sum_{i<=r} log alpha_i (inside the chunk):
 //   D[r,i]  = exp(g_r - g_i)                       (i <= r)
 //   A       = strict_lower( diag(b') (K K^T . D) )
-//   T       = (I + A)^{-1}                         (unit lower triangular, fp32 forward substitution)
+//   T       = (I + A)^{-1}                         (unit lower triangular; fp32, blocks of 16)
 //   W       = T diag(b' exp(g)) K                  -> stored negated, fp16 [tok][d_k]
 //   U~      = T diag(b') V                         -> stored transposed, fp16 [d_v][tok]
 //   P       = (Q K^T) . D  (i <= r)                -> fp16 [tok r][tok i]
@@ -17,11 +17,16 @@
 // One block per chunk (grid: chunks x B*H), 4 wavefronts.  All matrix products run on
 // MFMA with fp16 operands / fp32 accumulation; products are arranged (transposed where
 // needed) so that every result tile is stored as 4 consecutive fp16 along the layout the
-// consumer reads.  MFMA-bound in its products, latency-bound in the 64-step substitution.
+// consumer reads.  The triangular inverse is blocked 16x16: substitution inside the four
+// diagonal blocks (one per wavefront), fp32 MFMA for the blocks below them.
 #include <math.h>
 
 #include "mfma_util.h"
 #include "nats_common.h"
+
+#ifndef NATS_MARK
+#define NATS_MARK(i) do {} while (0)   // phase timestamps, only in debug harness builds
+#endif
 
 namespace nats {
 
@@ -32,7 +37,7 @@ constexpr int AS_STRIDE = 68; // fp32 row stride of the A matrix in LDS
 template <int D>
 constexpr size_t prep_lds_bytes() {
     return (size_t)(2 * CH * (D + LDS_PAD) + 2 * D * (CH + LDS_PAD)) * sizeof(half_t) +
-           (size_t)(CH * AS_STRIDE + 4 * CH) * sizeof(float);
+           (size_t)(2 * CH * AS_STRIDE + 4 * CH + 4 * 256) * sizeof(float);
 }
 
 template <int D>
@@ -53,6 +58,8 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     float* s_gam = s_g + CH;
     float* s_bp = s_gam + CH;
     float* s_gdec = s_bp + CH;
+    float* Ts = s_gdec + CH;            // [64][AS_STRIDE]  T = (I + A)^{-1}, fp32
+    float* Xs = Ts + CH * AS_STRIDE;    // [4][16*16]       per-wavefront scratch of the block solve
     half_t* Tp = Ks;   // [64][TS]  T diag(b' gam)  (reuses Ks once K K^T is done)
     half_t* Tpp = Qs;  // [64][TS]  T diag(b')
 
@@ -62,6 +69,7 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     const size_t gc = (size_t)blockIdx.y * n_chunks + blockIdx.x;  // global chunk id
     const size_t tok0 = (size_t)blockIdx.y * L + (size_t)blockIdx.x * CH;
 
+    NATS_MARK(0);
     // ---- gates: cumulative log-decay and write strengths -------------------------------
     if (wave == 0) {
         const float a = alpha[tok0 + lane];
@@ -95,6 +103,7 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         }
     }
     __syncthreads();
+    NATS_MARK(1);
 
     // ---- K K^T -> A (LDS, fp32) and (Q K^T . D) -> P (global), lower 16x16 tiles ----------
     {
@@ -143,33 +152,77 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         }
     }
     __syncthreads();
+    NATS_MARK(2);
 
-    if (wave == 0) {
-        // ---- T = (I + A)^{-1}: lane j owns column j; row r needs rows < r -------------------
-        float col[CH];
+    // ---- T = (I + A)^{-1}, unit lower triangular, by 16x16 blocks in fp32 ------------------------
+    // (a) diagonal blocks: wavefront b inverts I + A_bb by forward substitution; lane j < 16 owns
+    //     column j, row r needs rows < r of the same column
+    if (lane < 16) {
+        const int b = wave;
+        float col[16];
 #pragma unroll
-        for (int r = 0; r < CH; ++r) col[r] = 0.f;
+        for (int r = 0; r < 16; ++r) col[r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < CH; ++r) {
+        for (int r = 0; r < 16; ++r) {
             float acc = 0.f;
 #pragma unroll
             for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {   // A[r][i] is 0 for i >= r, col[i] is 0 there too
-                const float4 a4 = *reinterpret_cast<const float4*>(As + r * AS_STRIDE + 4 * i4);
+                const float4 a4 = *reinterpret_cast<const float4*>(As + (16 * b + r) * AS_STRIDE + 16 * b + 4 * i4);
                 acc += a4.x * col[4 * i4] + a4.y * col[4 * i4 + 1] + a4.z * col[4 * i4 + 2] +
                        a4.w * col[4 * i4 + 3];
             }
             col[r] = ((r == lane) ? 1.f : 0.f) - acc;
         }
-        const float bpj = s_bp[lane], bgj = s_bp[lane] * s_gam[lane];
 #pragma unroll
-        for (int r = 0; r < CH; ++r) {
-            Tpp[r * TS + lane] = f32_to_half_sat(col[r] * bpj);
-            Tp[r * TS + lane] = f32_to_half_sat(col[r] * bgj);
+        for (int r = 0; r < 16; ++r) Ts[(16 * b + r) * AS_STRIDE + 16 * b + lane] = col[r];
+    }
+    __syncthreads();
+    NATS_MARK(3);
+    // (b) blocks below the diagonal: T_ab = -T_aa sum_{b <= k < a} A_ak T_kb.  Wavefront b owns block
+    //     column b and walks down it; products are 16x16x16 in fp32 MFMA (16x16x4 steps).  A result
+    //     tile is in row-quad layout while the next product wants it as a B operand (one row per
+    //     lane quad), so it takes one trip through a per-wavefront LDS scratch.
+    {
+        const int b = wave;
+        float* Xw = Xs + wave * 256;
+        for (int a = b + 1; a < 4; ++a) {
+            f32x4 X = {0.f, 0.f, 0.f, 0.f};
+            for (int k = b; k < a; ++k) {
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const float af = As[(16 * a + l16) * AS_STRIDE + 16 * k + 4 * s4 + lq];
+                    const float bf = Ts[(16 * k + 4 * s4 + lq) * AS_STRIDE + 16 * b + l16];
+                    X = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, X, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Xw[(4 * lq + j) * 16 + l16] = X[j];
+            __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
+            f32x4 Y = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const float af = Ts[(16 * a + l16) * AS_STRIDE + 16 * a + 4 * s4 + lq];
+                const float bf = Xw[(4 * s4 + lq) * 16 + l16];
+                Y = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, Y, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Ts[(16 * a + 4 * lq + j) * AS_STRIDE + 16 * b + l16] = -Y[j];
+            __builtin_amdgcn_wave_barrier();
         }
-    } else {
-        // ---- Kd^T = K^T diag(exp(g_C - g)) and gam, straight to global -----------------------
+    }
+    __syncthreads();
+    // (c) operand forms T diag(b' gam) and T diag(b'), fp16, row-major [r][i]
+    for (int e = tid; e < CH * CH; e += PREP_THREADS) {
+        const int r = e >> 6, i = e & 63;
+        const float t = (i <= r) ? Ts[r * AS_STRIDE + i] : 0.f;
+        const float bp = s_bp[i];
+        Tpp[r * TS + i] = f32_to_half_sat(t * bp);
+        Tp[r * TS + i] = f32_to_half_sat(t * bp * s_gam[i]);
+    }
+    // ---- Kd^T = K^T diag(exp(g_C - g)) and gam, straight to global -----------------------------
+    {
         half_t* Kd = KdT + gc * (size_t)(D * CH);
-        for (int e = tid - 64; e < D * CH / 8; e += PREP_THREADS - 64) {
+        for (int e = tid; e < D * CH / 8; e += PREP_THREADS) {
             const int dk = e >> 3, t8 = e & 7;
             half8 h = lds_read8(KsT + dk * TS + t8 * 8);
 #pragma unroll
@@ -178,7 +231,9 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         }
         if (wave == 1) gam[gc * CH + lane] = s_gam[lane];
     }
+    NATS_MARK(4);
     __syncthreads();
+    NATS_MARK(5);
 
     // ---- W^T = K^T (T diag(b' gam))^T  and  U~ = (T diag(b')) V ------------------------------
     {
@@ -206,6 +261,9 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
             }
         }
     }
+    NATS_MARK(6);
+    __syncthreads();
+    NATS_MARK(7);
 }
 
 // workspace arrays of the chunkwise path, per chunk: Wneg [64][D], KdT [D][64], UtT [D][64],

@@ -12,7 +12,8 @@
 // S[v][d_k] in LDS is the B operand of the two products that read it.  Every operand is laid
 // out so that fragments are 16-byte LDS reads along the contraction index and results are
 // written back as 4 consecutive fp16.  Per chunk: two block barriers on the dependent chain
-// (U ready, S ready) and one for the staged operands.
+// (U ready, S ready).  Operands are software-pipelined: chunk c is read from one of two LDS
+// buffers while chunk c+1 moves from registers to the other and chunk c+2 is being loaded.
 //
 // MFMA work per chunk and block: (2 d + 2 d + 2 C + 2 d) C BV FLOP; the path is bound by the
 // length of the dependent chain (L / C steps), not by MFMA throughput.
@@ -28,15 +29,70 @@ template <int D, int BV>
 struct ScanLds {
     static constexpr int RS = D + LDS_PAD;   // [tok][d] rows
     static constexpr int TS = CS + LDS_PAD;  // [x][tok] rows
+    // per-chunk operands, double buffered
     static constexpr int o_W = 0;                       // [64][RS]  -W
     static constexpr int o_Q = o_W + CS * RS;           // [64][RS]  Q (fp16)
     static constexpr int o_Kd = o_Q + CS * RS;          // [D][TS]   Kd^T
     static constexpr int o_P = o_Kd + D * TS;           // [64][TS]  P
     static constexpr int o_Ut = o_P + CS * TS;          // [BV][TS]  U~^T slice
-    static constexpr int o_S = o_Ut + BV * TS;          // [BV][RS]  state copy, fp16
+    static constexpr int n_stage = o_Ut + BV * TS;      // halves per buffer
+    // carried between the phases of a step
+    static constexpr int o_S = 2 * n_stage;             // [BV][RS]  state copy, fp16
     static constexpr int o_U = o_S + BV * RS;           // [BV][TS]  U^T, fp16
     static constexpr int n_half = o_U + BV * TS;
-    static constexpr size_t bytes = (size_t)n_half * sizeof(half_t) + CS * sizeof(float);
+    static constexpr size_t bytes = (size_t)n_half * sizeof(half_t) + 2 * CS * sizeof(float);
+};
+
+// One chunk's operands on their way from global memory to LDS, held in registers so that the
+// loads of chunk c+2 are in flight while chunk c is computed.
+template <int D, int BV>
+struct ScanStage {
+    static constexpr int NW = CS * D / 8 / SCAN_THREADS_G;   // 16-byte pieces per thread of a [64][D] tile
+    static constexpr int NP = CS * CS / 8 / SCAN_THREADS_G;  // ... of the [64][64] tile
+    static constexpr int NU = BV * CS / 8;                   // pieces of the U~^T slice (<= 256)
+    uint4 w[NW], q[NW], kd[NW], p[NP], ut;
+    float g;
+
+    __device__ __forceinline__ void load(const bf16_t* __restrict__ Q, const half_t* __restrict__ Wneg,
+                                         const half_t* __restrict__ KdT, const half_t* __restrict__ UtT,
+                                         const half_t* __restrict__ P, const float* __restrict__ gam,
+                                         size_t gc, size_t tok0, int v0, int tid) {
+        const uint4* Wc = reinterpret_cast<const uint4*>(Wneg + gc * (size_t)(CS * D));
+        const uint4* Qc = reinterpret_cast<const uint4*>(Q + tok0 * D);
+        const uint4* Kc = reinterpret_cast<const uint4*>(KdT + gc * (size_t)(D * CS));
+        const uint4* Pc = reinterpret_cast<const uint4*>(P + gc * (size_t)(CS * CS));
+        const uint4* Uc = reinterpret_cast<const uint4*>(UtT + gc * (size_t)(D * CS) + (size_t)v0 * CS);
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {   // the tiles are contiguous in global memory: piece e = tid + 256 i
+            w[i] = Wc[tid + SCAN_THREADS_G * i];
+            q[i] = Qc[tid + SCAN_THREADS_G * i];
+            kd[i] = Kc[tid + SCAN_THREADS_G * i];
+        }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) p[i] = Pc[tid + SCAN_THREADS_G * i];
+        if (tid < NU) ut = Uc[tid];
+        if (tid < CS) g = gam[gc * CS + tid];
+    }
+
+    __device__ __forceinline__ void store(half_t* buf, float* s_gam, int tid) const {
+        using Lds = ScanLds<D, BV>;
+        constexpr int RS = Lds::RS, TS = Lds::TS;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int e = tid + SCAN_THREADS_G * i;
+            const int row = e / (D / 8), c8 = e % (D / 8);
+            *reinterpret_cast<uint4*>(buf + Lds::o_W + row * RS + c8 * 8) = w[i];
+            *reinterpret_cast<half8*>(buf + Lds::o_Q + row * RS + c8 * 8) = bf16x8_to_half8(q[i]);
+            *reinterpret_cast<uint4*>(buf + Lds::o_Kd + (e >> 3) * TS + (e & 7) * 8) = kd[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int e = tid + SCAN_THREADS_G * i;
+            *reinterpret_cast<uint4*>(buf + Lds::o_P + (e >> 3) * TS + (e & 7) * 8) = p[i];
+        }
+        if (tid < NU) *reinterpret_cast<uint4*>(buf + Lds::o_Ut + (tid >> 3) * TS + (tid & 7) * 8) = ut;
+        if (tid < CS) s_gam[tid] = g;
+    }
 };
 
 template <int D, int BV>
@@ -52,20 +108,17 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     constexpr int KS_D = D / 32;      // contraction steps over d_k
     extern __shared__ __align__(16) unsigned char smem[];
     half_t* sh = reinterpret_cast<half_t*>(smem);
-    half_t* Ws = sh + Lds::o_W;
-    half_t* Qs = sh + Lds::o_Q;
-    half_t* Kds = sh + Lds::o_Kd;
-    half_t* Ps = sh + Lds::o_P;
-    half_t* Uts = sh + Lds::o_Ut;
     half_t* Ss = sh + Lds::o_S;
     half_t* Us = sh + Lds::o_U;
-    float* s_gam = reinterpret_cast<float*>(sh + Lds::n_half);
+    float* s_gam_all = reinterpret_cast<float*>(sh + Lds::n_half);   // [2][64]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
     const int bh = blockIdx.y;
     const int v0 = blockIdx.x * BV;
     const int n_chunks = L / CS;
+    const size_t gc0 = (size_t)bh * n_chunks;
+    const size_t tokb = (size_t)bh * L;
 
     // ---- state: S^T tiles (rows d_k, cols v) as accumulators ---------------------------------
     f32x4 accS[MS][NT];
@@ -83,41 +136,24 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + dk) = to_half4(accS[ms][nt]);
         }
 
-    for (int c = 0; c < n_chunks; ++c) {
-        const size_t gc = (size_t)bh * n_chunks + c;
-        const size_t tok0 = (size_t)bh * L + (size_t)c * CS;
-        // ---- stage this chunk's operands into LDS ------------------------------------------
-        {
-            const half_t* Wc = Wneg + gc * (size_t)(CS * D);
-            const bf16_t* Qc = Q + tok0 * D;
-            for (int e = tid; e < CS * D / 8; e += SCAN_THREADS_G) {
-                const int row = e / (D / 8), c8 = e % (D / 8);
-                *reinterpret_cast<uint4*>(Ws + row * RS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Wc + row * D + c8 * 8);
-                *reinterpret_cast<half8*>(Qs + row * RS + c8 * 8) =
-                    bf16x8_to_half8(*reinterpret_cast<const uint4*>(Qc + row * D + c8 * 8));
-            }
-            const half_t* Kc = KdT + gc * (size_t)(D * CS);
-            for (int e = tid; e < D * CS / 8; e += SCAN_THREADS_G) {
-                const int row = e >> 3, c8 = e & 7;
-                *reinterpret_cast<uint4*>(Kds + row * TS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Kc + row * CS + c8 * 8);
-            }
-            const half_t* Pc = P + gc * (size_t)(CS * CS);
-            for (int e = tid; e < CS * CS / 8; e += SCAN_THREADS_G) {
-                const int row = e >> 3, c8 = e & 7;
-                *reinterpret_cast<uint4*>(Ps + row * TS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Pc + row * CS + c8 * 8);
-            }
-            const half_t* Uc = UtT + gc * (size_t)(D * CS) + (size_t)v0 * CS;
-            for (int e = tid; e < BV * CS / 8; e += SCAN_THREADS_G) {
-                const int row = e >> 3, c8 = e & 7;
-                *reinterpret_cast<uint4*>(Uts + row * TS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Uc + row * CS + c8 * 8);
-            }
-            if (tid < CS) s_gam[tid] = gam[gc * CS + tid];
-        }
-        __syncthreads();
+    // ---- software pipeline: chunk c in LDS buffer c&1, chunks c+1 and c+2 in registers ----------
+    ScanStage<D, BV> st[2];
+    st[0].load(Q, Wneg, KdT, UtT, P, gam, gc0, tokb, v0, tid);
+    if (n_chunks > 1) st[1].load(Q, Wneg, KdT, UtT, P, gam, gc0 + 1, tokb + CS, v0, tid);
+    st[0].store(sh, s_gam_all, tid);
+    __syncthreads();
+
+    auto step = [&](int c, ScanStage<D, BV>& st_far, const ScanStage<D, BV>& st_near) {
+        half_t* buf = sh + (c & 1) * Lds::n_stage;
+        const half_t* Ws = buf + Lds::o_W;
+        const half_t* Qs = buf + Lds::o_Q;
+        const half_t* Kds = buf + Lds::o_Kd;
+        const half_t* Ps = buf + Lds::o_P;
+        const half_t* Uts = buf + Lds::o_Ut;
+        const float* s_gam = s_gam_all + (c & 1) * CS;
+        const size_t tok0 = tokb + (size_t)c * CS;
+        // chunk c+2: global -> registers (its previous content, chunk c, is already in LDS)
+        if (c + 2 < n_chunks) st_far.load(Q, Wneg, KdT, UtT, P, gam, gc0 + c + 2, tok0 + 2 * CS, v0, tid);
 
         // ---- phase 1: this wavefront's 16 tokens: U = U~ - W S0^T and O1 = Q S0^T -------------
         const int mt = wave;
@@ -149,6 +185,8 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             }
         }
         const float gam_C = s_gam[CS - 1];
+        // chunk c+1: registers -> the other LDS buffer (last read in step c-1, before its final barrier)
+        if (c + 1 < n_chunks) st_near.store(sh + ((c + 1) & 1) * Lds::n_stage, s_gam_all + ((c + 1) & 1) * CS, tid);
         __syncthreads();   // U complete; every wavefront has read the old state copy
 
         // ---- phase 2: O += P U ; S^T = gam_C S^T + Kd^T U ---------------------------------------
@@ -157,14 +195,6 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) fu[ks][nt] = lds_read8(Us + (16 * nt + l16) * TS + 32 * ks + 8 * lq);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            if (ks <= mt / 2) {   // P is lower triangular: tokens beyond this tile's rows contribute nothing
-                const half8 fp = lds_read8(Ps + (16 * mt + l16) * TS + 32 * ks + 8 * lq);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) accO[nt] = mfma16(fp, fu[ks][nt], accO[nt]);
-            }
-        }
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) {
 #pragma unroll
@@ -183,13 +213,26 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + 16 * (MS * wave + ms) + 4 * lq) =
                     to_half4(accS[ms][nt]);
         }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks <= mt / 2) {   // P is lower triangular: tokens beyond this tile's rows contribute nothing
+                const half8 fp = lds_read8(Ps + (16 * mt + l16) * TS + 32 * ks + 8 * lq);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) accO[nt] = mfma16(fp, fu[ks][nt], accO[nt]);
+            }
+        }
         // linear-branch output rows of this wavefront's tokens, columns of this block's slice
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 O_la[(tok0 + 16 * mt + 4 * lq + j) * D + v0 + 16 * nt + l16] = la_scale * accO[nt][j];
-        __syncthreads();   // new state copy visible; staged operands free to be overwritten
+        __syncthreads();   // new state copy visible; this step's operand buffer is free again
+    };
+
+    for (int c = 0; c < n_chunks; c += 2) {
+        step(c, st[0], st[1]);
+        if (c + 1 < n_chunks) step(c + 1, st[1], st[0]);
     }
 
     if (S_final != nullptr) {
