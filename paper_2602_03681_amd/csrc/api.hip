@@ -97,9 +97,10 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
-    pl->off_w = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = 0;
+    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = 0;
     if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
         pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
+        pl->off_qf = off;  off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_kd = off;  off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_ut = off;  off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_p = off;   off = align_up(off + n_tok * pl->C * 2, 256);
@@ -220,19 +221,20 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     }
     if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
-        void* Wneg = ws + pl.off_w;
-        void* KdT = ws + pl.off_kd;
-        void* UtT = ws + pl.off_ut;
-        void* P = ws + pl.off_p;
-        float* gam = reinterpret_cast<float*>(ws + pl.off_gam);
+        void* WF = ws + pl.off_w;
+        void* QF = ws + pl.off_qf;
+        void* KdF = ws + pl.off_kd;
+        void* UtF = ws + pl.off_ut;
+        void* PF = ws + pl.off_p;
+        float* gamC = reinterpret_cast<float*>(ws + pl.off_gam);
         {
             ProfScope ps("gdn_chunk_prep", stream);
-            st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, Wneg, KdT, UtT, P, gam, stream);
+            st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, WF, QF, KdF, UtF, PF, gamC, stream);
         }
         if (st != NATS_OK) return st;
         {
             ProfScope ps("gdn_chunk_scan", stream);
-            st = launch_gdn_chunk_scan(pl, Q, Wneg, KdT, UtT, P, gam, ex.initial_state, ex.final_state, O_la,
+            st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state, O_la,
                                        stream);
         }
     } else {

@@ -6,13 +6,24 @@
 //   D[r,i]  = exp(g_r - g_i)                       (i <= r)
 //   A       = strict_lower( diag(b') (K K^T . D) )
 //   T       = (I + A)^{-1}                         (unit lower triangular; fp32, blocks of 16)
-//   W       = T diag(b' exp(g)) K                  -> stored negated, fp16 [tok][d_k]
-//   U~      = T diag(b') V                         -> stored transposed, fp16 [d_v][tok]
-//   P       = (Q K^T) . D  (i <= r)                -> fp16 [tok r][tok i]
-//   Kd^T    = (diag(exp(g_C - g)) K)^T             -> fp16 [d_k][tok]
-//   gam     = exp(g)                               -> fp32 [tok]
+//   W       = T diag(b' exp(g)) K                  (stored negated)
+//   U~      = T diag(b') V
+//   P       = (Q K^T) . D  (i <= r, zero above the diagonal)
+//   Kd      = diag(exp(g_C - g)) K
+//   Qg      = diag(exp(g)) Q
+//   gam_C   = exp(g_C)
 // so that the state-carrying kernel only needs
-//   U = U~ - W S0^T,  O = diag(gam) Q S0^T + P U,  S1 = exp(g_C) S0 + U^T Kd.
+//   U = U~ - W S0^T,  O = Qg S0^T + P U,  S1 = gam_C S0 + U^T Kd.
+//
+// Output format ("fragment-major", fp16): every operand is written in the order in which the
+// wavefronts of the state-carrying kernel load their MFMA fragments, so that each of their
+// loads is one contiguous 1 KiB (64 lanes x 16 bytes).  With lane = 16 lq + l16 and w = 0..3:
+//   WF  [chunk][w][ks < d/32][lane][8] = -W [tok = 16w + l16][d_k = (d/4) lq + 8 ks + j]
+//   QF  same shape                     =  Qg[tok = 16w + l16][d_k = (d/4) lq + 8 ks + j]
+//   KdF [chunk][w][ms < d/64][ks < 2][lane][8] = Kd[tok = 16 lq + 8 ks + j][d_k = 16 (d/64 w + ms) + l16]
+//   PF  [chunk][w][ks < 2][lane][8]    =  P [r = 16w + l16][i = 16 lq + 8 ks + j]
+//   UtF [chunk][vt < d/16][w][lane][4] =  U~[tok = 16w + 4 lq + j][d_v = 16 vt + l16]
+//   gamC[chunk]                        (fp32)
 //
 // One block per chunk (grid: chunks x B*H), 4 wavefronts.  All matrix products run on
 // MFMA with fp16 operands / fp32 accumulation; products are arranged (transposed where
@@ -44,8 +55,8 @@ template <int D>
 __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
-    int L, half_t* __restrict__ Wneg, half_t* __restrict__ KdT, half_t* __restrict__ UtT,
-    half_t* __restrict__ P, float* __restrict__ gam) {
+    int L, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
+    half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC) {
     constexpr int RS = D + LDS_PAD;   // row stride, row-major [tok][d] tiles
     constexpr int TS = CH + LDS_PAD;  // row stride, transposed [d][tok] tiles
     extern __shared__ __align__(16) unsigned char smem[];
@@ -60,8 +71,9 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     float* s_gdec = s_bp + CH;
     float* Ts = s_gdec + CH;            // [64][AS_STRIDE]  T = (I + A)^{-1}, fp32
     float* Xs = Ts + CH * AS_STRIDE;    // [4][16*16]       per-wavefront scratch of the block solve
-    half_t* Tp = Ks;   // [64][TS]  T diag(b' gam)  (reuses Ks once K K^T is done)
-    half_t* Tpp = Qs;  // [64][TS]  T diag(b')
+    half_t* Tp = Ks;              // [64][TS]  T diag(b' gam)  (reuses Ks once K K^T is done)
+    half_t* Tpp = Qs;             // [64][TS]  T diag(b')      (reuses Qs once Qg is written)
+    const half_t* Qs2 = Qs;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
@@ -107,16 +119,17 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
 
     // ---- K K^T -> A (LDS, fp32) and (Q K^T . D) -> P (global), lower 16x16 tiles ----------
     {
-        // 16x16 tile jobs (a, b), one hex digit per job: the 10 lower tiles, then the two
-        // upper tiles (0,1) and (2,3) that only need zeros
-        constexpr uint64_t JA = 0x203333222110ull;  // a of job 0 in the lowest digit
-        constexpr uint64_t JB = 0x313210210100ull;
-        half_t* Pc = P + gc * (CH * CH);
-        for (int job = wave; job < 12; job += 4) {
+        // 16x16 tile jobs (a, b), one hex digit per job: the 10 lower tiles (products), then the 6
+        // upper tiles, which are stored as zeros (the consumer contracts over all 64 tokens)
+        constexpr uint64_t JA = 0x2110003333222110ull;  // a of job 0 in the lowest digit
+        constexpr uint64_t JB = 0x3323213210210100ull;
+        half_t* Pc = PF + gc * (CH * CH);
+        // P[r = 16a + l16][i = 16b + 4 lq + j] -> PF[w = a][ks = lq / 2][lane = 16 b + l16][4 (lq % 2) + j]
+        for (int job = wave; job < 16; job += 4) {
             const int a = (int)((JA >> (4 * job)) & 15), b = (int)((JB >> (4 * job)) & 15);
-            if (a < b) {  // an upper tile the consumer's 32-wide contraction step still reads: zeros
+            if (a < b) {  // upper tile: zeros
                 half4 z = {0, 0, 0, 0};
-                *reinterpret_cast<half4*>(Pc + (16 * a + l16) * CH + 16 * b + 4 * lq) = z;
+                *reinterpret_cast<half4*>(Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1)) = z;
                 continue;
             }
             f32x4 accK = {0.f, 0.f, 0.f, 0.f}, accP = {0.f, 0.f, 0.f, 0.f};
@@ -147,13 +160,38 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
                     const int i = 16 * b + 4 * lq + j;
                     pv[j] = (i <= r) ? accP[j] * expf(gr - s_g[i]) : 0.f;
                 }
-                *reinterpret_cast<half4*>(Pc + r * CH + 16 * b + 4 * lq) = to_half4(pv);
+                *reinterpret_cast<half4*>(Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1)) =
+                    to_half4(pv);
             }
         }
     }
     __syncthreads();
     NATS_MARK(2);
 
+    // ---- Kd and Qg in fragment order, straight to global (coalesced 16-byte stores) ---------------
+    {
+        constexpr int MS = D / 64, KS_D = D / 32;
+        half8* Kd = reinterpret_cast<half8*>(KdF + gc * (size_t)(D * CH));
+        for (int e = tid; e < D * CH / 8; e += PREP_THREADS) {   // e = ((w * MS + ms) * 2 + ks) * 64 + lane
+            const int ln = e & 63, ks = (e >> 6) & 1, wm = e >> 7;   // wm = w * MS + ms
+            const int dk = 16 * wm + (ln & 15), t0 = 16 * (ln >> 4) + 8 * ks;
+            half8 h = lds_read8(KsT + dk * TS + t0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * s_gdec[t0 + j]);
+            Kd[e] = h;
+        }
+        half8* Qg = reinterpret_cast<half8*>(QF + gc * (size_t)(CH * D));
+        for (int e = tid; e < CH * D / 8; e += PREP_THREADS) {   // e = (w * KS_D + ks) * 64 + lane
+            const int ln = e & 63, ks = (e >> 6) % KS_D, w = (e >> 6) / KS_D;
+            const int tok = 16 * w + (ln & 15), dk = (D / 4) * (ln >> 4) + 8 * ks;
+            half8 h = lds_read8(Qs2 + tok * RS + dk);
+            const float g = s_gam[tok];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * g);
+            Qg[e] = h;
+        }
+        if (tid == 0) gamC[gc] = s_gam[CH - 1];
+    }
     // ---- T = (I + A)^{-1}, unit lower triangular, by 16x16 blocks in fp32 ------------------------
     // (a) diagonal blocks: wavefront b inverts I + A_bb by forward substitution; lane j < 16 owns
     //     column j, row r needs rows < r of the same column
@@ -219,26 +257,15 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         Tpp[r * TS + i] = f32_to_half_sat(t * bp);
         Tp[r * TS + i] = f32_to_half_sat(t * bp * s_gam[i]);
     }
-    // ---- Kd^T = K^T diag(exp(g_C - g)) and gam, straight to global -----------------------------
-    {
-        half_t* Kd = KdT + gc * (size_t)(D * CH);
-        for (int e = tid; e < D * CH / 8; e += PREP_THREADS) {
-            const int dk = e >> 3, t8 = e & 7;
-            half8 h = lds_read8(KsT + dk * TS + t8 * 8);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * s_gdec[t8 * 8 + j]);
-            *reinterpret_cast<half8*>(Kd + dk * CH + t8 * 8) = h;
-        }
-        if (wave == 1) gam[gc * CH + lane] = s_gam[lane];
-    }
     NATS_MARK(4);
     __syncthreads();
     NATS_MARK(5);
 
     // ---- W^T = K^T (T diag(b' gam))^T  and  U~ = (T diag(b')) V ------------------------------
     {
-        half_t* Wc = Wneg + gc * (size_t)(CH * D);
-        half_t* Uc = UtT + gc * (size_t)(D * CH);
+        constexpr int KS_D = D / 32;
+        half_t* Wc = WF + gc * (size_t)(CH * D);
+        half_t* Uc = UtF + gc * (size_t)(D * CH);
 #pragma unroll
         for (int mi = 0; mi < D / 64; ++mi) {
             const int m = wave * (D / 64) + mi;  // 16-wide tile index along d_k (W) / d_v (U~)
@@ -256,8 +283,12 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
                     accU = mfma16(ftt, fv, accU);  // rows token r = 16n + 4lq + j, col d_v = 16m + l16
                 }
                 f32x4 neg = {-accW[0], -accW[1], -accW[2], -accW[3]};
-                *reinterpret_cast<half4*>(Wc + (16 * n + l16) * D + 16 * m + 4 * lq) = to_half4(neg);
-                *reinterpret_cast<half4*>(Uc + (16 * m + l16) * CH + 16 * n + 4 * lq) = to_half4(accU);
+                // -W[tok = 16n + l16][d_k = 16m + 4 lq + j] -> WF[w = n][ks'][lane = 16 lq' + l16][j0 + j]
+                const int dk0 = 16 * m + 4 * lq;
+                const int lq2 = dk0 / (D / 4), ks2 = (dk0 % (D / 4)) / 8, j0 = dk0 & 7;
+                *reinterpret_cast<half4*>(Wc + (((n * KS_D + ks2) * 64) + 16 * lq2 + l16) * 8 + j0) = to_half4(neg);
+                // U~[tok = 16n + 4 lq + j][d_v = 16m + l16] -> UtF[vt = m][w = n][lane][j]
+                *reinterpret_cast<half4*>(Uc + ((m * 4 + n) * 64 + lane) * 4) = to_half4(accU);
             }
         }
     }
@@ -266,11 +297,10 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     NATS_MARK(7);
 }
 
-// workspace arrays of the chunkwise path, per chunk: Wneg [64][D], KdT [D][64], UtT [D][64],
-// P [64][64] (fp16) and gam [64] (fp32)
+// per chunk: WF, QF, KdF, UtF (64 * d fp16 each), PF (64 * 64 fp16), gamC (1 fp32); layouts above
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
-                                  const float* alpha, const float* beta, const uint8_t* mask, void* Wneg,
-                                  void* KdT, void* UtT, void* P, float* gam, hipStream_t st) {
+                                  const float* alpha, const float* beta, const uint8_t* mask, void* WF,
+                                  void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st) {
     dim3 grid(pl.L / CH, pl.BH);
     if (pl.d == 64) {
         auto kern = gdn_chunk_prep_kernel<64>;
@@ -278,16 +308,16 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
                                 (int)prep_lds_bytes<64>()) != hipSuccess)
             return check_launch("gdn_chunk_prep (LDS attribute)");
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<64>(), st, (const bf16_t*)Q,
-                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)Wneg,
-                           (half_t*)KdT, (half_t*)UtT, (half_t*)P, gam);
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)prep_lds_bytes<128>()) != hipSuccess)
             return check_launch("gdn_chunk_prep (LDS attribute)");
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<128>(), st, (const bf16_t*)Q,
-                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)Wneg,
-                           (half_t*)KdT, (half_t*)UtT, (half_t*)P, gam);
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     }
     return check_launch("gdn_chunk_prep");
 }

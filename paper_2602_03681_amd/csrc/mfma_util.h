@@ -21,6 +21,7 @@ typedef _Float16 half_t;
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte word held in registers
 
 __device__ __forceinline__ f32x4 mfma16(half8 a, half8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
@@ -31,8 +32,7 @@ __device__ __forceinline__ half_t f32_to_half_sat(float f) {
 }
 
 // 8 consecutive bf16 (one 16-byte word) -> 8 fp16, exact inside the fp16 range
-__device__ __forceinline__ half8 bf16x8_to_half8(uint4 w) {
-    const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+__device__ __forceinline__ half8 bf16x8_to_half8(u32x4 u) {
     half8 h;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -41,6 +41,8 @@ __device__ __forceinline__ half8 bf16x8_to_half8(uint4 w) {
     }
     return h;
 }
+
+__device__ __forceinline__ half8 bf16x8_to_half8(uint4 w) { return bf16x8_to_half8(u32x4{w.x, w.y, w.z, w.w}); }
 
 __device__ __forceinline__ half8 lds_read8(const half_t* p) { return *reinterpret_cast<const half8*>(p); }
 __device__ __forceinline__ half4 lds_read4(const half_t* p) { return *reinterpret_cast<const half4*>(p); }

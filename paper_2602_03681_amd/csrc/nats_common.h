@@ -96,7 +96,7 @@ struct FwdPlan {
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_kd, off_ut, off_p, off_gam, off_vht;
+    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
@@ -107,10 +107,10 @@ nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K
                                  const float* alpha, const float* beta, const uint8_t* mask,
                                  const float* S0, float* S_final, float* O_la, hipStream_t st);
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
-                                  const float* alpha, const float* beta, const uint8_t* mask, void* Wneg,
-                                  void* KdT, void* UtT, void* P, float* gam, hipStream_t st);
-nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* Q, const void* Wneg, const void* KdT,
-                                  const void* UtT, const void* P, const float* gam, const float* S0,
+                                  const float* alpha, const float* beta, const uint8_t* mask, void* WF,
+                                  void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
+nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
+                                  const void* UtF, const void* PF, const float* gamC, const float* S0,
                                   float* S_final, float* O_la, hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
