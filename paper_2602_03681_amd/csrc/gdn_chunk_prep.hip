@@ -43,37 +43,62 @@ namespace nats {
 
 constexpr int PREP_THREADS = 256;
 constexpr int CH = 64;        // chunk size
-constexpr int AS_STRIDE = 68; // fp32 row stride of the A matrix in LDS
+constexpr int AS_STRIDE = 68; // fp32 row stride of the A and T matrices in LDS
+constexpr float LOG2E = 1.44269504088896341f;
 
+// LDS plan (bytes).  Regions are reused as their first tenants die, to keep a block under half
+// of the CU's 160 KiB so that two blocks overlap each other's latency-bound phases:
+//   R12 : K and Q tiles, fp16 [64][d+8] each           (until Qg is written)
+//         -> T fp32 [64][68] at 0, T' fp16 [64][72] at 25600   (triangular inverse, then operand form)
+//         -> V^T fp16 [d][72] at 0                      (last phase; V waits in registers until then)
+//   R3  : K^T fp16 [d][72]                              (whole kernel)
+//   R5  : A fp32 [64][68] -> T'' fp16 [64][72]
+//   Xs  : 4 x 16x16 fp32 scratch of the block inverse;  gates: 4 x 64 fp32
 template <int D>
-constexpr size_t prep_lds_bytes() {
-    return (size_t)(2 * CH * (D + LDS_PAD) + 2 * D * (CH + LDS_PAD)) * sizeof(half_t) +
-           (size_t)(2 * CH * AS_STRIDE + 4 * CH + 4 * 256) * sizeof(float);
+struct PrepLds {
+    static constexpr int RS = D + LDS_PAD, TS = CH + LDS_PAD;
+    static constexpr int kq_bytes = 2 * CH * RS * 2;
+    static constexpr int tp_off = 25600;
+    static constexpr int r12_bytes = (kq_bytes > tp_off + CH * TS * 2) ? kq_bytes : tp_off + CH * TS * 2;
+    static constexpr int o_kst = r12_bytes;
+    static constexpr int o_as = o_kst + D * TS * 2;
+    static constexpr int o_xs = o_as + CH * AS_STRIDE * 4;
+    static constexpr int o_gate = o_xs + 4 * 256 * 4;
+    static constexpr int bytes = o_gate + 4 * CH * 4;
+    static_assert(CH * AS_STRIDE * 4 <= tp_off, "T and T' overlap");
+    static_assert(D * TS * 2 <= tp_off, "V^T and T' overlap");
+};
+
+// Transposed tiles [d][tok] are written 2 bytes at a time by lanes that hold different d of the
+// same token; an xor swizzle of the 8-token group index with (d / 8) spreads those writes over
+// the banks.  Readers fetch 8 consecutive tokens (16 bytes) starting at a multiple of 8.
+__device__ __forceinline__ int swz_t(int drow, int tok, int TS) {
+    return drow * TS + ((((tok >> 3) ^ (drow >> 3)) & 7) << 3) + (tok & 7);
 }
 
 template <int D>
-__global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
+__global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     int L, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
     half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC) {
-    constexpr int RS = D + LDS_PAD;   // row stride, row-major [tok][d] tiles
-    constexpr int TS = CH + LDS_PAD;  // row stride, transposed [d][tok] tiles
+    using Lds = PrepLds<D>;
+    constexpr int RS = Lds::RS, TS = Lds::TS;
+    constexpr int NPC = CH * D / 8 / PREP_THREADS;   // 16-byte pieces of a [64][D] tile per thread
     extern __shared__ __align__(16) unsigned char smem[];
-    half_t* Ks = reinterpret_cast<half_t*>(smem);  // [64][RS]  K, fp16
-    half_t* Qs = Ks + CH * RS;                     // [64][RS]  Q
-    half_t* KsT = Qs + CH * RS;                    // [D][TS]   K^T
-    half_t* VsT = KsT + D * TS;                    // [D][TS]   V^T
-    float* As = reinterpret_cast<float*>(VsT + D * TS);  // [64][AS_STRIDE]
-    float* s_g = As + CH * AS_STRIDE;
-    float* s_gam = s_g + CH;
+    half_t* Ks = reinterpret_cast<half_t*>(smem);              // [64][RS]
+    half_t* Qs = Ks + CH * RS;                                 // [64][RS]
+    float* Ts = reinterpret_cast<float*>(smem);                // [64][AS_STRIDE]   (after Ks, Qs)
+    half_t* Tp = reinterpret_cast<half_t*>(smem + Lds::tp_off);  // [64][TS]  T diag(b' gam)
+    half_t* VsT = reinterpret_cast<half_t*>(smem);             // [D][TS]   (after T)
+    half_t* KsT = reinterpret_cast<half_t*>(smem + Lds::o_kst);  // [D][TS]
+    float* As = reinterpret_cast<float*>(smem + Lds::o_as);    // [64][AS_STRIDE]
+    half_t* Tpp = reinterpret_cast<half_t*>(smem + Lds::o_as); // [64][TS]  T diag(b')  (after A)
+    float* Xs = reinterpret_cast<float*>(smem + Lds::o_xs);    // [4][256]
+    float* s_g2 = reinterpret_cast<float*>(smem + Lds::o_gate);  // cumulative log2-decay
+    float* s_gam = s_g2 + CH;
     float* s_bp = s_gam + CH;
     float* s_gdec = s_bp + CH;
-    float* Ts = s_gdec + CH;            // [64][AS_STRIDE]  T = (I + A)^{-1}, fp32
-    float* Xs = Ts + CH * AS_STRIDE;    // [4][16*16]       per-wavefront scratch of the block solve
-    half_t* Tp = Ks;              // [64][TS]  T diag(b' gam)  (reuses Ks once K K^T is done)
-    half_t* Tpp = Qs;             // [64][TS]  T diag(b')      (reuses Qs once Qg is written)
-    const half_t* Qs2 = Qs;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
@@ -82,37 +107,44 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
     const size_t tok0 = (size_t)blockIdx.y * L + (size_t)blockIdx.x * CH;
 
     NATS_MARK(0);
+    // ---- tiles: coalesced 16-byte loads (a [64][D] tile is contiguous in global memory) --------
+    u32x4 rk[NPC], rq[NPC], rv[NPC];
+    {
+        const u32x4* Kg = reinterpret_cast<const u32x4*>(K + tok0 * D);
+        const u32x4* Qg = reinterpret_cast<const u32x4*>(Q + tok0 * D);
+        const u32x4* Vg = reinterpret_cast<const u32x4*>(V + tok0 * D);
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            rk[i] = Kg[tid + PREP_THREADS * i];
+            rq[i] = Qg[tid + PREP_THREADS * i];
+            rv[i] = Vg[tid + PREP_THREADS * i];
+        }
+    }
     // ---- gates: cumulative log-decay and write strengths -------------------------------
     if (wave == 0) {
         const float a = alpha[tok0 + lane];
-        float g = logf(fmaxf(a, 1e-30f));
+        float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const float up = __shfl_up(g, off);
             if (lane >= off) g += up;
         }
         const float gC = __shfl(g, 63);
-        s_g[lane] = g;
-        s_gam[lane] = expf(g);
-        s_gdec[lane] = expf(gC - g);
+        s_g2[lane] = g;
+        s_gam[lane] = __builtin_amdgcn_exp2f(g);
+        s_gdec[lane] = __builtin_amdgcn_exp2f(gC - g);
         s_bp[lane] = mask[tok0 + lane] ? 0.f : beta[tok0 + lane];
     }
-    // ---- tiles: K (row-major and transposed), Q (row-major), V (transposed) ----------------
-    // consecutive lanes take consecutive tokens so that the 2-byte transposed writes of a
-    // wavefront fall into consecutive LDS addresses
-    for (int e = tid; e < CH * D / 8; e += PREP_THREADS) {
-        const int row = e & 63, c8 = e >> 6;
-        const size_t src = (tok0 + row) * D + c8 * 8;
-        const half8 hk = bf16x8_to_half8(*reinterpret_cast<const uint4*>(K + src));
-        const half8 hq = bf16x8_to_half8(*reinterpret_cast<const uint4*>(Q + src));
-        const half8 hv = bf16x8_to_half8(*reinterpret_cast<const uint4*>(V + src));
-        *reinterpret_cast<half8*>(Ks + row * RS + c8 * 8) = hk;
-        *reinterpret_cast<half8*>(Qs + row * RS + c8 * 8) = hq;
+    // K row-major + transposed (swizzled), Q row-major; V stays in registers for now
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            KsT[(c8 * 8 + j) * TS + row] = hk[j];
-            VsT[(c8 * 8 + j) * TS + row] = hv[j];
-        }
+    for (int i = 0; i < NPC; ++i) {
+        const int e = tid + PREP_THREADS * i;
+        const int row = e / (D / 8), c8 = e % (D / 8);
+        const half8 hk = bf16x8_to_half8(rk[i]);
+        *reinterpret_cast<half8*>(Ks + row * RS + c8 * 8) = hk;
+        *reinterpret_cast<half8*>(Qs + row * RS + c8 * 8) = bf16x8_to_half8(rq[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) KsT[swz_t(c8 * 8 + j, row, TS)] = hk[j];
     }
     __syncthreads();
     NATS_MARK(1);
@@ -127,9 +159,10 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         // P[r = 16a + l16][i = 16b + 4 lq + j] -> PF[w = a][ks = lq / 2][lane = 16 b + l16][4 (lq % 2) + j]
         for (int job = wave; job < 16; job += 4) {
             const int a = (int)((JA >> (4 * job)) & 15), b = (int)((JB >> (4 * job)) & 15);
+            half_t* dst = Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1);
             if (a < b) {  // upper tile: zeros
                 half4 z = {0, 0, 0, 0};
-                *reinterpret_cast<half4*>(Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1)) = z;
+                *reinterpret_cast<half4*>(dst) = z;
                 continue;
             }
             f32x4 accK = {0.f, 0.f, 0.f, 0.f}, accP = {0.f, 0.f, 0.f, 0.f};
@@ -144,24 +177,24 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
             }
             {   // A[r][i], r = 16a + 4 lq + j, i = 16b + l16
                 const int i = 16 * b + l16;
-                const float gi = s_g[i];
+                const float gi = s_g2[i];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * a + 4 * lq + j;
-                    As[r * AS_STRIDE + i] = (i < r) ? s_bp[r] * accK[j] * expf(s_g[r] - gi) : 0.f;
+                    As[r * AS_STRIDE + i] =
+                        (i < r) ? s_bp[r] * accK[j] * __builtin_amdgcn_exp2f(s_g2[r] - gi) : 0.f;
                 }
             }
             {   // P[r][i], r = 16a + l16, i = 16b + 4 lq + j
                 const int r = 16 * a + l16;
-                const float gr = s_g[r];
+                const float gr = s_g2[r];
                 f32x4 pv;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int i = 16 * b + 4 * lq + j;
-                    pv[j] = (i <= r) ? accP[j] * expf(gr - s_g[i]) : 0.f;
+                    pv[j] = (i <= r) ? accP[j] * __builtin_amdgcn_exp2f(gr - s_g2[i]) : 0.f;
                 }
-                *reinterpret_cast<half4*>(Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1)) =
-                    to_half4(pv);
+                *reinterpret_cast<half4*>(dst) = to_half4(pv);
             }
         }
     }
@@ -170,12 +203,12 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
 
     // ---- Kd and Qg in fragment order, straight to global (coalesced 16-byte stores) ---------------
     {
-        constexpr int MS = D / 64, KS_D = D / 32;
+        constexpr int KS_D = D / 32;
         half8* Kd = reinterpret_cast<half8*>(KdF + gc * (size_t)(D * CH));
         for (int e = tid; e < D * CH / 8; e += PREP_THREADS) {   // e = ((w * MS + ms) * 2 + ks) * 64 + lane
             const int ln = e & 63, ks = (e >> 6) & 1, wm = e >> 7;   // wm = w * MS + ms
             const int dk = 16 * wm + (ln & 15), t0 = 16 * (ln >> 4) + 8 * ks;
-            half8 h = lds_read8(KsT + dk * TS + t0);
+            half8 h = lds_read8(KsT + swz_t(dk, t0, TS));
 #pragma unroll
             for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * s_gdec[t0 + j]);
             Kd[e] = h;
@@ -184,7 +217,7 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         for (int e = tid; e < CH * D / 8; e += PREP_THREADS) {   // e = (w * KS_D + ks) * 64 + lane
             const int ln = e & 63, ks = (e >> 6) % KS_D, w = (e >> 6) / KS_D;
             const int tok = 16 * w + (ln & 15), dk = (D / 4) * (ln >> 4) + 8 * ks;
-            half8 h = lds_read8(Qs2 + tok * RS + dk);
+            half8 h = lds_read8(Qs + tok * RS + dk);
             const float g = s_gam[tok];
 #pragma unroll
             for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * g);
@@ -192,6 +225,7 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         }
         if (tid == 0) gamC[gc] = s_gam[CH - 1];
     }
+    __syncthreads();   // K and Q tiles are dead from here on: their region becomes T
     // ---- T = (I + A)^{-1}, unit lower triangular, by 16x16 blocks in fp32 ------------------------
     // (a) diagonal blocks: wavefront b inverts I + A_bb by forward substitution; lane j < 16 owns
     //     column j, row r needs rows < r of the same column
@@ -248,7 +282,7 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
             __builtin_amdgcn_wave_barrier();
         }
     }
-    __syncthreads();
+    __syncthreads();   // T complete; A is dead from here on: its region becomes T''
     // (c) operand forms T diag(b' gam) and T diag(b'), fp16, row-major [r][i]
     for (int e = tid; e < CH * CH; e += PREP_THREADS) {
         const int r = e >> 6, i = e & 63;
@@ -256,6 +290,15 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
         const float bp = s_bp[i];
         Tpp[r * TS + i] = f32_to_half_sat(t * bp);
         Tp[r * TS + i] = f32_to_half_sat(t * bp * s_gam[i]);
+    }
+    __syncthreads();   // T is dead from here on: its region becomes V^T
+#pragma unroll
+    for (int i = 0; i < NPC; ++i) {
+        const int e = tid + PREP_THREADS * i;
+        const int row = e / (D / 8), c8 = e % (D / 8);
+        const half8 hv = bf16x8_to_half8(rv[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) VsT[swz_t(c8 * 8 + j, row, TS)] = hv[j];
     }
     NATS_MARK(4);
     __syncthreads();
@@ -275,8 +318,8 @@ __global__ __launch_bounds__(PREP_THREADS) void gdn_chunk_prep_kernel(
 #pragma unroll
                 for (int ks = 0; ks <= n / 2; ++ks) {
                     const int ko = 32 * ks + 8 * lq;
-                    const half8 fk = lds_read8(KsT + (16 * m + l16) * TS + ko);
-                    const half8 fv = lds_read8(VsT + (16 * m + l16) * TS + ko);
+                    const half8 fk = lds_read8(KsT + swz_t(16 * m + l16, ko, TS));
+                    const half8 fv = lds_read8(VsT + swz_t(16 * m + l16, ko, TS));
                     const half8 ft = lds_read8(Tp + (16 * n + l16) * TS + ko);
                     const half8 ftt = lds_read8(Tpp + (16 * n + l16) * TS + ko);
                     accW = mfma16(fk, ft, accW);   // rows d_k = 16m + 4lq + j, col token r = 16n + l16
@@ -305,17 +348,17 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
     if (pl.d == 64) {
         auto kern = gdn_chunk_prep_kernel<64>;
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)prep_lds_bytes<64>()) != hipSuccess)
+                                PrepLds<64>::bytes) != hipSuccess)
             return check_launch("gdn_chunk_prep (LDS attribute)");
-        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<64>(), st, (const bf16_t*)Q,
+        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<64>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)prep_lds_bytes<128>()) != hipSuccess)
+                                PrepLds<128>::bytes) != hipSuccess)
             return check_launch("gdn_chunk_prep (LDS attribute)");
-        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), prep_lds_bytes<128>(), st, (const bf16_t*)Q,
+        hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<128>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     }
