@@ -97,7 +97,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
-    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = 0;
+    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = 0;
     if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
         pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_qf = off;  off = align_up(off + n_tok * pl->d * 2, 256);
@@ -106,6 +106,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         pl->off_p = off;   off = align_up(off + n_tok * pl->C * 2, 256);
         pl->off_gam = off; off = align_up(off + n_tok * 4, 256);
         pl->off_vht = off; off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
+        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);  // fp16 linear-branch output
     }
     pl->total = off;
     return NATS_OK;
@@ -234,8 +235,8 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         if (st != NATS_OK) return st;
         {
             ProfScope ps("gdn_chunk_scan", stream);
-            st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state, O_la,
-                                       stream);
+            st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state,
+                                       ws + pl.off_olah, ex.O_la, stream);
         }
     } else {
         ProfScope ps("gdn_recurrent", stream);
@@ -244,8 +245,8 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
         ProfScope ps("flash_softmax", stream);
-        st = launch_flash_softmax(pl, Q, Kc, ws + pl.off_vht, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse,
-                                  stream);
+        st = launch_flash_softmax(pl, Q, Kc, ws + pl.off_vht, cnt, ws + pl.off_olah, ex.w_nla, ex.w_la, O, ex.O_nla,
+                                  ex.lse, stream);
     } else {
         ProfScope ps("softmax_fp32", stream);
         st = launch_softmax_fp32(pl, Q, Kc, Vc, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);

@@ -23,6 +23,10 @@
 #include "mfma_util.h"
 #include "nats_common.h"
 
+#ifndef NATS_MARK
+#define NATS_MARK(i) do {} while (0)   // phase timestamps, only in debug harness builds
+#endif
+
 namespace nats {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -32,10 +36,9 @@ constexpr int FL_NQ = 2;                 // 16-query MFMA columns per wavefront
 constexpr int FL_BM = 4 * 16 * FL_NQ;    // queries per block
 constexpr int FL_BN = 64;                // compacted keys per tile
 
-__device__ __forceinline__ f32x4 mfma16_bf16(uint4 a, uint4 b, f32x4 c) {
-    union { uint4 u; bf16x8_t v; } ua, ub;
-    ua.u = a; ub.u = b;
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua.v, ub.v, c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma16_bf16(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
 }
 
 __device__ __forceinline__ float quad_max(float x) {   // over lanes l, l^16, l^32, l^48
@@ -47,18 +50,36 @@ __device__ __forceinline__ float quad_sum(float x) {
     return x + __shfl_xor(x, 32);
 }
 
+template <int W>
+__device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned groups of W lanes
+#pragma unroll
+    for (int off = 1; off < W; off <<= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
 template <int D>
-__global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
+__global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
-    const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
+    const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, float* __restrict__ O_nla_out,
     float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps) {
-    constexpr int RS = D + LDS_PAD;      // K tile rows (bf16 elements)
+    constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
+    constexpr int OS = D + 4;            // output staging rows (fp32 elements)
     constexpr int KS_D = D / 32;
     constexpr int DT = D / 16;           // 16-row d_v tiles
-    __shared__ __align__(16) uint16_t Ks[FL_BN * RS];
-    __shared__ __align__(16) half_t Vs[D * TS];
+    // one LDS region, three tenants: the Q tile (prologue), the K and V^T tiles (main loop), the
+    // per-wavefront output staging (epilogue)
+    constexpr int TILE_BYTES = FL_BN * RS * 2 + D * TS * 2;
+    constexpr int Q_BYTES = FL_BM * RS * 2;
+    constexpr int O_BYTES = 4 * 16 * OS * 4;
+    constexpr int LDS_BYTES = TILE_BYTES > Q_BYTES ? (TILE_BYTES > O_BYTES ? TILE_BYTES : O_BYTES)
+                                                   : (Q_BYTES > O_BYTES ? Q_BYTES : O_BYTES);
+    __shared__ __align__(16) unsigned char smem[LDS_BYTES];
+    uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
+    half_t* Vs = reinterpret_cast<half_t*>(smem + FL_BN * RS * 2);
+    uint16_t* Qst = reinterpret_cast<uint16_t*>(smem);
+    float* Ot = reinterpret_cast<float*>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
@@ -67,26 +88,54 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
     const size_t tokbase = (size_t)bh * L;
     const float scale2 = scale * 1.44269504088896341f;   // logits in base-2 units
 
-    // ---- this wavefront's queries: fragments of Q^T (B operand) and visible-key counts ----------
-    uint4 qf[FL_NQ][KS_D];
-    int my_cnt[FL_NQ], q_row[FL_NQ];
+    NATS_MARK(0);
+    // ---- prologue: the block's Q rows, coalesced, through LDS into B-operand fragments ------------
+    constexpr int NQP = FL_BM * D / 8 / FL_THREADS;   // 16-byte pieces per thread of the Q tile
+    constexpr int NKP = FL_BN * D / 8 / FL_THREADS;   // ... of a K tile and of a V^T tile
+    const int q_last = min(q0 + FL_BM, L) - 1;
+    const int n_hi = cnt[tokbase + q_last];   // cnt is non-decreasing: bound for the whole block
+    const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
+    u32x4 kreg[NKP], vreg[NKP];               // next K / V^T tile on its way from global memory to LDS
+    auto load_tile = [&](int kt) __attribute__((always_inline)) {
+        const u32x4* Kt = reinterpret_cast<const u32x4*>(Kc + (tokbase + (size_t)kt * FL_BN) * D);
+        const u32x4* Vt = reinterpret_cast<const u32x4*>(VhT + (tokbase + (size_t)kt * FL_BN) * D);   // [D][64]
+#pragma unroll
+        for (int i = 0; i < NKP; ++i) {   // both tiles are contiguous in global memory
+            kreg[i] = Kt[tid + FL_THREADS * i];
+            vreg[i] = Vt[tid + FL_THREADS * i];
+        }
+    };
+    {
+        u32x4 qreg[NQP];
+#pragma unroll
+        for (int i = 0; i < NQP; ++i) {   // all loads in flight before the first use
+            const int e = tid + FL_THREADS * i;
+            const int row = e / (D / 8), c8 = e % (D / 8);
+            qreg[i] = (q0 + row < L) ? *reinterpret_cast<const u32x4*>(Q + (tokbase + q0 + row) * D + c8 * 8)
+                                     : u32x4{0u, 0u, 0u, 0u};
+        }
+        if (n_tiles > 0) load_tile(0);
+#pragma unroll
+        for (int i = 0; i < NQP; ++i) {
+            const int e = tid + FL_THREADS * i;
+            *reinterpret_cast<u32x4*>(Qst + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = qreg[i];
+        }
+    }
+    __syncthreads();
+    u32x4 qf[FL_NQ][KS_D];
+    int my_cnt[FL_NQ];
     int wave_hi = 0;
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
-        const int q = q0 + (wave * FL_NQ + nq) * 16 + l16;
-        q_row[nq] = q;
-        const bool live = q < L;
-        my_cnt[nq] = live ? cnt[tokbase + q] : 0;
+        const int ql = (wave * FL_NQ + nq) * 16 + l16;
+        my_cnt[nq] = (q0 + ql < L) ? cnt[tokbase + q0 + ql] : 0;
 #pragma unroll
         for (int ks = 0; ks < KS_D; ++ks)
-            qf[nq][ks] = live ? *reinterpret_cast<const uint4*>(Q + (tokbase + q) * D + 32 * ks + 8 * lq)
-                              : make_uint4(0, 0, 0, 0);
+            qf[nq][ks] = *reinterpret_cast<const u32x4*>(Qst + ql * RS + 32 * ks + 8 * lq);
         wave_hi = max(wave_hi, my_cnt[nq]);
     }
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) wave_hi = max(wave_hi, __shfl_xor(wave_hi, off));
-    const int q_last = min(q0 + FL_BM, L) - 1;
-    const int n_hi = cnt[tokbase + q_last];   // cnt is non-decreasing: bound for the whole block
 
     f32x4 accO[FL_NQ][DT];
     float m_run[FL_NQ], l_run[FL_NQ];
@@ -98,24 +147,17 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
         for (int t = 0; t < DT; ++t) accO[nq][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
+    NATS_MARK(1);
     for (int kt = 0; kt < n_tiles; ++kt) {
-        __syncthreads();
-        {   // stage K tile (bf16 rows) and V^T tile (fp16, [d_v][key]) -- straight 16-byte copies
-            const bf16_t* Kt = Kc + (tokbase + (size_t)kt * FL_BN) * D;
-            for (int e = tid; e < FL_BN * D / 8; e += FL_THREADS) {
-                const int row = e / (D / 8), c8 = e % (D / 8);
-                *reinterpret_cast<uint4*>(Ks + row * RS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Kt + row * D + c8 * 8);
-            }
-            const half_t* Vt = VhT + (tokbase + (size_t)kt * FL_BN) * D;   // tile kt: [D][64]
-            for (int e = tid; e < D * FL_BN / 8; e += FL_THREADS) {
-                const int row = e >> 3, c8 = e & 7;
-                *reinterpret_cast<uint4*>(Vs + row * TS + c8 * 8) =
-                    *reinterpret_cast<const uint4*>(Vt + row * FL_BN + c8 * 8);
-            }
+        __syncthreads();   // the previous tile (or the Q tile) is no longer read
+#pragma unroll
+        for (int i = 0; i < NKP; ++i) {   // registers -> LDS: K rows [key][d], V^T rows [d_v][key]
+            const int e = tid + FL_THREADS * i;
+            *reinterpret_cast<u32x4*>(Ks + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = kreg[i];
+            *reinterpret_cast<u32x4*>(Vs + (e >> 3) * TS + (e & 7) * 8) = vreg[i];
         }
         __syncthreads();
+        load_tile(kt + 1 < n_tiles ? kt + 1 : kt);   // next tile in flight during this tile's products
         if (kt * FL_BN >= wave_hi) continue;   // nothing visible to this wavefront in this tile (uniform)
 
         // ---- S^T = K Q^T for 64 keys x 16*FL_NQ queries ------------------------------------------
@@ -128,7 +170,7 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
         for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const uint4 fk = *reinterpret_cast<const uint4*>(Ks + (16 * m + l16) * RS + 32 * ks + 8 * lq);
+                const u32x4 fk = *reinterpret_cast<const u32x4*>(Ks + (16 * m + l16) * RS + 32 * ks + 8 * lq);
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accS[nq][m] = mfma16_bf16(fk, qf[nq][ks], accS[nq][m]);
             }
@@ -143,9 +185,9 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = kt * FL_BN + 16 * m + 4 * lq + j;
-                    const float s = (c < my_cnt[nq]) ? accS[nq][m][j] * scale2 : -INFINITY;
-                    accS[nq][m][j] = s;
-                    tmax = fmaxf(tmax, s);
+                    const float sv = (c < my_cnt[nq]) ? accS[nq][m][j] * scale2 : -INFINITY;
+                    accS[nq][m][j] = sv;
+                    tmax = fmaxf(tmax, sv);
                 }
             tmax = quad_max(tmax);
             const float m_new = fmaxf(m_run[nq], tmax);
@@ -156,9 +198,9 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
             for (int m = 0; m < 4; ++m)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float p = any ? __builtin_amdgcn_exp2f(accS[nq][m][j] - m_new) : 0.f;
-                    accS[nq][m][j] = p;
-                    psum += p;
+                    const float pv = any ? __builtin_amdgcn_exp2f(accS[nq][m][j] - m_new) : 0.f;
+                    accS[nq][m][j] = pv;
+                    psum += pv;
                 }
             psum = quad_sum(psum);
             l_run[nq] = l_run[nq] * corr + psum;
@@ -186,61 +228,81 @@ __global__ __launch_bounds__(FL_THREADS) void flash_softmax_kernel(
                 for (int nq = 0; nq < FL_NQ; ++nq) accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
             }
     }
+    NATS_MARK(2);
+    __syncthreads();   // tiles are dead: the region becomes the output staging
+    NATS_MARK(3);
 
-    // ---- epilogue: normalise, optional branch outputs, merge with the linear branch, store --------
+    // ---- epilogue: normalise; transpose each 16-query x D result through LDS so that every global
+    //      access below is a full row segment; merge with the linear branch; store ------------------
+    constexpr int LPR = D / 4;            // lanes per output row (float4 each)
+    constexpr int RPP = 64 / LPR;         // rows per pass of a wavefront
+    float* Ow = Ot + wave * 16 * OS;
+    half4 lah_all[FL_NQ][16 / RPP];       // the linear branch's rows, all loads issued up front
+#pragma unroll
+    for (int nq = 0; nq < FL_NQ; ++nq)
+#pragma unroll
+        for (int pass = 0; pass < 16 / RPP; ++pass) {
+            const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
+            lah_all[nq][pass] =
+                *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
+        }
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
-        const int q = q_row[nq];
-        if (q >= L) continue;
+        const int qbase = q0 + (wave * FL_NQ + nq) * 16;
         const float l = l_run[nq];
         const float inv_l = l > 0.f ? 1.f / l : 0.f;
-        if (lse_out != nullptr && lq == 0)
-            lse_out[tokbase + q] = l > 0.f ? (m_run[nq] + log2f(l)) * 0.69314718055994531f : -INFINITY;
-        float ss_la = 0.f, ss_nla = 0.f;
-        float4 la[DT];
+        if (lse_out != nullptr && lq == 0 && qbase + l16 < L)
+            lse_out[tokbase + qbase + l16] =
+                l > 0.f ? (m_run[nq] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f : -INFINITY;
 #pragma unroll
-        for (int t = 0; t < DT; ++t) {
-            accO[nq][t][0] *= inv_l; accO[nq][t][1] *= inv_l; accO[nq][t][2] *= inv_l; accO[nq][t][3] *= inv_l;
-            const size_t off = (tokbase + q) * D + 16 * t + 4 * lq;
-            la[t] = *reinterpret_cast<const float4*>(O_la + off);
-            if (O_nla_out != nullptr)
-                *reinterpret_cast<float4*>(O_nla_out + off) =
-                    make_float4(accO[nq][t][0], accO[nq][t][1], accO[nq][t][2], accO[nq][t][3]);
-            ss_la += la[t].x * la[t].x + la[t].y * la[t].y + la[t].z * la[t].z + la[t].w * la[t].w;
-            ss_nla += accO[nq][t][0] * accO[nq][t][0] + accO[nq][t][1] * accO[nq][t][1] +
-                      accO[nq][t][2] * accO[nq][t][2] + accO[nq][t][3] * accO[nq][t][3];
-        }
-        float wn = 1.f, wl = 1.f;
-        if (combine_mode != 0) {
-            ss_la = quad_sum(ss_la);
-            ss_nla = quad_sum(ss_nla);
-            wn = (w_nla ? w_nla[tokbase + q] : 0.5f) / sqrtf(ss_nla / D + eps);
-            wl = (w_la ? w_la[tokbase + q] : 0.5f) / sqrtf(ss_la / D + eps);
-        }
+        for (int t = 0; t < DT; ++t)
+            *reinterpret_cast<float4*>(Ow + l16 * OS + 16 * t + 4 * lq) =
+                make_float4(accO[nq][t][0] * inv_l, accO[nq][t][1] * inv_l, accO[nq][t][2] * inv_l,
+                            accO[nq][t][3] * inv_l);
+        __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
 #pragma unroll
-        for (int t = 0; t < DT; ++t) {
-            const float o0 = wn * accO[nq][t][0] + wl * la[t].x, o1 = wn * accO[nq][t][1] + wl * la[t].y;
-            const float o2 = wn * accO[nq][t][2] + wl * la[t].z, o3 = wn * accO[nq][t][3] + wl * la[t].w;
-            uint2 w;
-            w.x = (uint32_t)f32_to_bf16_bits(o0) | ((uint32_t)f32_to_bf16_bits(o1) << 16);
-            w.y = (uint32_t)f32_to_bf16_bits(o2) | ((uint32_t)f32_to_bf16_bits(o3) << 16);
-            *reinterpret_cast<uint2*>(O + (tokbase + q) * D + 16 * t + 4 * lq) = w;
+        for (int pass = 0; pass < 16 / RPP; ++pass) {
+            const int row = pass * RPP + lane / LPR, c4 = lane % LPR;
+            const int q = qbase + row;
+            const bool live = q < L;
+            const float4 x = *reinterpret_cast<const float4*>(Ow + row * OS + 4 * c4);
+            const size_t off = (tokbase + (live ? q : 0)) * D + 4 * c4;
+            const half4 lah = lah_all[nq][pass];
+            const float la0 = (float)lah[0], la1 = (float)lah[1], la2 = (float)lah[2], la3 = (float)lah[3];
+            if (O_nla_out != nullptr && live) *reinterpret_cast<float4*>(O_nla_out + off) = x;
+            float wn = 1.f, wl = 1.f;
+            if (combine_mode != 0) {
+                const float ss_nla = lane_group_sum<LPR>(x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w);
+                const float ss_la = lane_group_sum<LPR>(la0 * la0 + la1 * la1 + la2 * la2 + la3 * la3);
+                wn = (w_nla ? w_nla[tokbase + (live ? q : 0)] : 0.5f) / sqrtf(ss_nla / D + eps);
+                wl = (w_la ? w_la[tokbase + (live ? q : 0)] : 0.5f) / sqrtf(ss_la / D + eps);
+            }
+            if (live) {
+                uint2 w;
+                w.x = (uint32_t)f32_to_bf16_bits(wn * x.x + wl * la0) |
+                      ((uint32_t)f32_to_bf16_bits(wn * x.y + wl * la1) << 16);
+                w.y = (uint32_t)f32_to_bf16_bits(wn * x.z + wl * la2) |
+                      ((uint32_t)f32_to_bf16_bits(wn * x.w + wl * la3) << 16);
+                *reinterpret_cast<uint2*>(O + off) = w;
+            }
         }
+        __builtin_amdgcn_wave_barrier();
     }
+    NATS_MARK(4);
 }
 
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
-                                 const int32_t* cnt, const float* O_la, const float* w_nla,
+                                 const int32_t* cnt, const void* O_la, const float* w_nla,
                                  const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                  hipStream_t st) {
     dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
     if (pl.d == 64)
         hipLaunchKernelGGL((flash_softmax_kernel<64>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, O_la, w_nla, w_la, (bf16_t*)O,
+                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
                            O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
     else
         hipLaunchKernelGGL((flash_softmax_kernel<128>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, O_la, w_nla, w_la, (bf16_t*)O,
+                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
                            O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
     return check_launch("flash_softmax");
 }

@@ -88,8 +88,8 @@ template <int D, int BV>
 __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     const half_t* __restrict__ WF, const half_t* __restrict__ QF, const half_t* __restrict__ KdF,
     const half_t* __restrict__ UtF, const half_t* __restrict__ PF, const float* __restrict__ gamC,
-    const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la, int L, int BH,
-    float la_scale) {
+    const float* __restrict__ S0, float* __restrict__ S_final, half_t* __restrict__ O_la_h,
+    float* __restrict__ O_la_f32, int L, int BH, float la_scale) {
     using Lds = ScanLds<D, BV>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NT = BV / 16;       // 16-wide tiles along the d_v slice
@@ -202,12 +202,17 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) accO[nt] = mfma16(cur.p[ks], fu[ks][nt], accO[nt]);
         if (c == NATS_MARK_STEP) NATS_MARK(3);
-        // linear-branch output rows of this wavefront's tokens, columns of this block's slice
+        // linear-branch output rows of this wavefront's tokens, columns of this block's slice:
+        // fp16 for the softmax kernel's merge epilogue, fp32 on request
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                O_la[(tok0 + 16 * wave + 4 * lq + j) * D + v0 + 16 * nt + l16] = la_scale * accO[nt][j];
+            for (int j = 0; j < 4; ++j) {
+                const size_t off = (tok0 + 16 * wave + 4 * lq + j) * D + v0 + 16 * nt + l16;
+                const float o = la_scale * accO[nt][j];
+                O_la_h[off] = f32_to_half_sat(o);
+                if (O_la_f32 != nullptr) O_la_f32[off] = o;
+            }
         if (c == NATS_MARK_STEP) NATS_MARK(4);
         __syncthreads();   // new state copy visible; U copy free again
         if (c == NATS_MARK_STEP) NATS_MARK(5);
@@ -240,19 +245,20 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 template <int D, int BV>
 static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                  const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                 float* S_final, float* O_la, hipStream_t st) {
+                                 float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st) {
     dim3 grid(8 * ((pl.BH + 7) / 8) * (D / BV));   // see the block -> (bh, slice) map in the kernel
     hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV>), grid, dim3(SCAN_THREADS_G), 0, st, (const half_t*)WF,
                        (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF, (const half_t*)PF, gamC, S0,
-                       S_final, O_la, pl.L, pl.BH, pl.la_scale);
+                       S_final, (half_t*)O_la_h, O_la_f32, pl.L, pl.BH, pl.la_scale);
     return check_launch("gdn_chunk_scan");
 }
 
 nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                  float* S_final, float* O_la, hipStream_t st) {
-    if (pl.d == 64) return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la, st);
-    return launch_scan_t<128, 32>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la, st);
+                                  float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st) {
+    if (pl.d == 64)
+        return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
+    return launch_scan_t<128, 32>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
 }
 
 }  // namespace nats

@@ -96,7 +96,7 @@ struct FwdPlan {
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht;
+    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
@@ -111,13 +111,13 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
 nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                  float* S_final, float* O_la, hipStream_t st);
+                                  float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                 hipStream_t st);
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
-                                 const int32_t* cnt, const float* O_la, const float* w_nla,
+                                 const int32_t* cnt, const void* O_la, const float* w_nla,
                                  const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                  hipStream_t st);
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
