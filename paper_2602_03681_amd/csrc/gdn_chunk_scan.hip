@@ -7,14 +7,16 @@
 // The rows of S (index d_v) never mix, so a block owns a slice of BV values of d_v for one
 // (batch, head) and walks the chunks in order; the grid is (d / BV) * (B*H) blocks.
 //
-// The state lives transposed, S^T [d_k x BV], as fp32 MFMA accumulators spread over the 4
+// The state lives transposed, S^T [d_k x BV], as fp32 MFMA accumulators spread over four
 // wavefronts (each owns d_k/4 rows) and never leaves registers in fp32; an fp16 copy
-// S[v][d_k] in LDS is the B operand of the two products that read it, and the fp16 copy of U
-// is the B operand of the state update.  Phase 1 splits the chunk's tokens over the
-// wavefronts, phase 2 splits d_k, so every A operand is private to one wavefront: it is
-// loaded from global memory straight into MFMA fragment registers, one chunk ahead of use,
-// and LDS carries only the two exchanged copies.  Per chunk: two block barriers on the
-// dependent chain (U ready, S ready).
+// S[v][d_k] in LDS is the B operand of the products that read it, and the fp16 copy of U is
+// the B operand of the state update.  A block has two groups of four wavefronts: the first
+// carries the dependent chain (U, then S1), the second produces the output (Qg S0^T + P U) from
+// the same two LDS copies, so the output work fills the issue slots the chain leaves idle.
+// Phase 1 splits the chunk's tokens over a group's wavefronts, phase 2 splits d_k, so every A
+// operand is private to one wavefront: it is loaded from global memory straight into MFMA
+// fragment registers, three chunks ahead of use, and LDS carries only the two exchanged copies.
+// Per chunk: two block barriers (U ready, S ready).
 //
 // MFMA work per chunk and block: (2 d + 2 d + 2 C + 2 d) C BV FLOP; the path is bound by the
 // length of the dependent chain (L / C steps), not by MFMA throughput.
@@ -28,8 +30,8 @@
 
 namespace nats {
 
-constexpr int SCAN_THREADS_G = 256;
-constexpr int CS = 64;  // chunk size
+constexpr int SCAN_THREADS_G = 512;   // 8 wavefronts: 4 carry the state, 4 produce the output
+constexpr int CS = 64;                // chunk size
 
 template <int D, int BV>
 struct ScanLds {
@@ -38,49 +40,53 @@ struct ScanLds {
     static constexpr int o_S = 0;                       // [BV][RS]  state copy, fp16
     static constexpr int o_U = o_S + BV * RS;           // [BV][TS]  U^T, fp16
     static constexpr int n_half = o_U + BV * TS;
-    static constexpr size_t bytes = (size_t)n_half * sizeof(half_t);
 };
 
-// One chunk's operands for one wavefront, as MFMA fragments in registers.  Every A operand of a
-// step is private to a wavefront (phase 1 splits the tokens, phase 2 splits d_k), so fragments
-// are loaded straight from global memory and never staged in LDS; the preparation kernel wrote
-// them in fragment order, so each load below is one contiguous 1 KiB per wavefront.  The
-// contraction slots of a lane (quad lq, step ks, slot j) stand for
+// Operands of one chunk for one wavefront, as MFMA fragments in registers.  Every A operand of a
+// step is private to a wavefront (phase 1 splits the chunk's tokens, phase 2 splits d_k), so
+// fragments are loaded straight from global memory and never staged in LDS; the preparation
+// kernel wrote them in fragment order, so each load below is one contiguous 1 KiB per wavefront.
+// The contraction slots of a lane (quad lq, step ks, slot j) stand for
 //   d_k = (D/4) lq + 8 ks + j   in the products over d_k,   tok = 16 lq + 8 ks + j   over tokens,
 // and the B operands (fp16 copies of S and U in LDS) are read with the same maps.
 template <int D, int BV>
-struct ScanStage {
+struct ChainStage {   // wavefront w of the state-carrying group
     static constexpr int KS_D = D / 32, MS = D / 64, NT = BV / 16;
-    half8 w[KS_D];      // -W   rows tok = 16 wave + l16
-    half8 q[KS_D];      // Qg   same rows (gam folded in)
-    half8 kd[MS][2];    // Kd^T rows d_k = 16 (MS wave + ms) + l16
-    half8 p[2];         // P    rows r = 16 wave + l16
-    half4 ut[NT];       // U~   rows tok = 16 wave + 4 lq + j, col v = 16 nt + l16
+    half8 w[KS_D];      // -W   rows tok = 16 w + l16
+    half8 kd[MS][2];    // Kd^T rows d_k = 16 (MS w + ms) + l16
+    half4 ut[NT];       // U~   rows tok = 16 w + 4 lq + j, col v = 16 nt + l16
     float gC;           // decay of the whole chunk
-
-    __device__ __forceinline__ void load(const half_t* __restrict__ WF, const half_t* __restrict__ QF,
-                                         const half_t* __restrict__ KdF, const half_t* __restrict__ UtF,
-                                         const half_t* __restrict__ PF, const float* __restrict__ gamC,
-                                         size_t gc, int v0, int wave, int lane) {
-        const half8* W8 = reinterpret_cast<const half8*>(WF) + ((gc * 4 + wave) * KS_D) * 64 + lane;
-        const half8* Q8 = reinterpret_cast<const half8*>(QF) + ((gc * 4 + wave) * KS_D) * 64 + lane;
+    __device__ __forceinline__ void load(const half_t* __restrict__ WF, const half_t* __restrict__ KdF,
+                                         const half_t* __restrict__ UtF, const float* __restrict__ gamC,
+                                         size_t gc, int v0, int w4, int lane) {
+        const half8* W8 = reinterpret_cast<const half8*>(WF) + ((gc * 4 + w4) * KS_D) * 64 + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) {
-            w[ks] = W8[ks * 64];
-            q[ks] = Q8[ks * 64];
-        }
-        const half8* K8 = reinterpret_cast<const half8*>(KdF) + ((gc * 4 + wave) * MS * 2) * 64 + lane;
+        for (int ks = 0; ks < KS_D; ++ks) w[ks] = W8[ks * 64];
+        const half8* K8 = reinterpret_cast<const half8*>(KdF) + ((gc * 4 + w4) * MS * 2) * 64 + lane;
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) kd[ms][ks] = K8[(ms * 2 + ks) * 64];
-        const half8* P8 = reinterpret_cast<const half8*>(PF) + ((gc * 4 + wave) * 2) * 64 + lane;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) p[ks] = P8[ks * 64];
-        const half4* U4 = reinterpret_cast<const half4*>(UtF) + ((gc * (D / 16) + v0 / 16) * 4 + wave) * 64 + lane;
+        const half4* U4 = reinterpret_cast<const half4*>(UtF) + ((gc * (D / 16) + v0 / 16) * 4 + w4) * 64 + lane;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) ut[nt] = U4[nt * 4 * 64];
         gC = gamC[gc];
+    }
+};
+
+template <int D, int BV>
+struct OutStage {     // wavefront w of the output group
+    static constexpr int KS_D = D / 32;
+    half8 q[KS_D];      // Qg   rows tok = 16 w + l16
+    half8 p[2];         // P    rows r = 16 w + l16
+    __device__ __forceinline__ void load(const half_t* __restrict__ QF, const half_t* __restrict__ PF,
+                                         size_t gc, int w4, int lane) {
+        const half8* Q8 = reinterpret_cast<const half8*>(QF) + ((gc * 4 + w4) * KS_D) * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) q[ks] = Q8[ks * 64];
+        const half8* P8 = reinterpret_cast<const half8*>(PF) + ((gc * 4 + w4) * 2) * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) p[ks] = P8[ks * 64];
     }
 };
 
@@ -100,145 +106,189 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     half_t* Us = sh + Lds::o_U;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w4 = wave & 3;                 // index inside the group: token tile (phase 1), d_k quarter (phase 2)
+    const bool is_chain = wave < 4;          // wavefronts 0-3 carry the state, 4-7 produce the output
     const int l16 = lane & 15, lq = lane >> 4;
     // Block -> (batch*head, d_v slice).  Workgroups are dealt round-robin to the 8 XCDs, each with
-    // its own L2; the slices of one (batch, head) read the same W / Q / Kd / P, so they are given
-    // ids that are congruent modulo 8 and therefore share one L2.
+    // its own L2; the slices of one (batch, head) read the same operands, so they are given ids
+    // that are congruent modulo 8 and therefore share one L2.
     constexpr int NSL = D / BV;
+#ifdef NATS_DEBUG_PLAIN_MAP
+    const int xcd = 0, slot = blockIdx.x % NSL + NSL * 0;
+    const int bh = blockIdx.x / NSL + 0 * xcd;
+#else
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int bh = (slot / NSL) * 8 + xcd;
+#endif
     if (bh >= BH) return;
     const int v0 = (slot % NSL) * BV;
     const int n_chunks = L / CS;
     const size_t gc0 = (size_t)bh * n_chunks;
     const size_t tokb = (size_t)bh * L;
+    constexpr int PF_DIST = 3;
+    // Both groups run the same barrier sequence (two per chunk).  Loads are issued PF_DIST chunks
+    // ahead of use through PF_DIST + 1 rotating register stages; they are unconditional (the tail re-loads the
+    // last chunk) and the first steps are peeled, so that the compiler's load-wait counts
+    // stay exact and never include the loads issued after the one being waited for.
 
-    // ---- state: S^T tiles (rows d_k, cols v) as accumulators ---------------------------------
-    f32x4 accS[MS][NT];
-#pragma unroll
-    for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int dk = 16 * (MS * wave + ms) + 4 * lq, v = v0 + 16 * nt + l16;
-            if (S0 != nullptr) {
-                const float4 x = *reinterpret_cast<const float4*>(S0 + ((size_t)bh * D + v) * D + dk);
-                accS[ms][nt] = f32x4{x.x, x.y, x.z, x.w};
-            } else {
-                accS[ms][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + dk) = to_half4(accS[ms][nt]);
-        }
-
-    // ---- software pipeline over chunks: stage c in use, stages c+1 and c+2 in flight -------------
-    // (a load must be issued about two steps before its use to cover an HBM round trip)
-    ScanStage<D, BV> stA, stB, stC;
-    stA.load(WF, QF, KdF, UtF, PF, gamC, gc0, v0, wave, lane);
-    stB.load(WF, QF, KdF, UtF, PF, gamC, gc0 + (n_chunks > 1 ? 1 : 0), v0, wave, lane);
-    __syncthreads();   // initial state copy visible
-
-    // always_inline: the stages must stay in registers, which needs every call site inlined
-    auto step = [&](int c, const ScanStage<D, BV>& cur, ScanStage<D, BV>& nxt) __attribute__((always_inline)) {
-        const size_t tok0 = tokb + (size_t)c * CS;
-        if (c == NATS_MARK_STEP) NATS_MARK(0);
-#ifndef NATS_DEBUG_NO_PREFETCH
-#ifdef NATS_DEBUG_HOT_CHUNKS
-        nxt.load(WF, QF, KdF, UtF, PF, gamC, gc0 + ((c + 2) & 3), v0, wave, lane);
-#else
-        // unconditional (the last step re-loads its own chunk): a branch here would make the compiler
-        // wait for these loads together with the ones the MFMAs below really need
-        nxt.load(WF, QF, KdF, UtF, PF, gamC, gc0 + (c + 2 < n_chunks ? c + 2 : c), v0, wave, lane);
-#endif
-#endif
-        // ---- phase 1: this wavefront's 16 tokens: U = U~ - W S0^T and O1 = Q S0^T -------------
-        f32x4 accU[NT], accO[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            accU[nt] = f32x4{(float)cur.ut[nt][0], (float)cur.ut[nt][1], (float)cur.ut[nt][2], (float)cur.ut[nt][3]};
-            accO[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const half8 fs = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
-                accU[nt] = mfma16(cur.w[ks], fs, accU[nt]);
-                accO[nt] = mfma16(cur.q[ks], fs, accO[nt]);
-            }
-        }
-        // decay of the state, off the dependent chain (the fp16 copy in LDS is what phase 1 reads)
+    if (is_chain) {
+        // ---- state: S^T tiles (rows d_k, cols v) as fp32 accumulators; fp16 copy S[v][d_k] in LDS -----
+        f32x4 accS[MS][NT];
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                accS[ms][nt][0] *= cur.gC; accS[ms][nt][1] *= cur.gC;
-                accS[ms][nt][2] *= cur.gC; accS[ms][nt][3] *= cur.gC;
+                const int dk = 16 * (MS * w4 + ms) + 4 * lq, v = v0 + 16 * nt + l16;
+                if (S0 != nullptr) {
+                    const float4 x = *reinterpret_cast<const float4*>(S0 + ((size_t)bh * D + v) * D + dk);
+                    accS[ms][nt] = f32x4{x.x, x.y, x.z, x.w};
+                } else {
+                    accS[ms][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + dk) = to_half4(accS[ms][nt]);
             }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            *reinterpret_cast<half4*>(Us + (16 * nt + l16) * TS + 16 * wave + 4 * lq) = to_half4(accU[nt]);
-        if (c == NATS_MARK_STEP) NATS_MARK(1);
-        __syncthreads();   // U complete; every wavefront has read the old state copy
-        if (c == NATS_MARK_STEP) NATS_MARK(2);
+        ChainStage<D, BV> stA, stB, stC, stD;
+        stA.load(WF, KdF, UtF, gamC, gc0, v0, w4, lane);
+        stB.load(WF, KdF, UtF, gamC, gc0 + min(1, n_chunks - 1), v0, w4, lane);
+        stC.load(WF, KdF, UtF, gamC, gc0 + min(2, n_chunks - 1), v0, w4, lane);
+        __syncthreads();   // initial state copy visible
 
-        // ---- phase 2: S^T = gam_C S^T + Kd^T U ; O += P U -------------------------------------------
-        half8 fu[2][NT];
+        auto step = [&](int c, const ChainStage<D, BV>& cur, ChainStage<D, BV>& nxt) __attribute__((always_inline)) {
+            if (c == NATS_MARK_STEP) NATS_MARK(0);
+#ifndef NATS_DEBUG_NO_PREFETCH
+#ifdef NATS_DEBUG_HOT_CHUNKS
+            nxt.load(WF, KdF, UtF, gamC, gc0 + ((c + PF_DIST) & 3), v0, w4, lane);
+#else
+            nxt.load(WF, KdF, UtF, gamC, gc0 + min(c + PF_DIST, n_chunks - 1), v0, w4, lane);
+#endif
+#endif
+            // phase 1: U = U~ - W S0^T for this wavefront's 16 tokens
+            f32x4 accU[NT];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+            for (int nt = 0; nt < NT; ++nt)
+                accU[nt] = f32x4{(float)cur.ut[nt][0], (float)cur.ut[nt][1], (float)cur.ut[nt][2], (float)cur.ut[nt][3]};
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) fu[ks][nt] = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
+            for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
+                for (int nt = 0; nt < NT; ++nt) {
+                    const half8 fs = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
+                    accU[nt] = mfma16(cur.w[ks], fs, accU[nt]);
+                }
+            // decay of the state, off the dependent chain (phase 1 reads the fp16 copy in LDS)
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    accS[ms][nt][0] *= cur.gC; accS[ms][nt][1] *= cur.gC;
+                    accS[ms][nt][2] *= cur.gC; accS[ms][nt][3] *= cur.gC;
+                }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                *reinterpret_cast<half4*>(Us + (16 * nt + l16) * TS + 16 * w4 + 4 * lq) = to_half4(accU[nt]);
+            if (c == NATS_MARK_STEP) NATS_MARK(1);
+            __syncthreads();   // U complete; the old state copy has been read by everyone
+            if (c == NATS_MARK_STEP) NATS_MARK(2);
+            // phase 2: S^T = gam_C S^T + Kd^T U for this wavefront's quarter of d_k
+            half8 fu[2][NT];
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) accS[ms][nt] = mfma16(cur.kd[ms][ks], fu[ks][nt], accS[ms][nt]);
+                for (int nt = 0; nt < NT; ++nt) fu[ks][nt] = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) accS[ms][nt] = mfma16(cur.kd[ms][ks], fu[ks][nt], accS[ms][nt]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + 16 * (MS * w4 + ms) + 4 * lq) =
+                        to_half4(accS[ms][nt]);
+            }
+            if (c == NATS_MARK_STEP) NATS_MARK(3);
+            __syncthreads();   // new state copy visible; U copy free again
+            if (c == NATS_MARK_STEP) NATS_MARK(4);
+        };
+        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST)
+        step(0, stA, stD);
+        if (n_chunks > 1) step(1, stB, stA);
+        if (n_chunks > 2) step(2, stC, stB);
+        if (n_chunks > 3) step(3, stD, stC);
+        for (int c = 4; c < n_chunks; c += 4) {
+            step(c, stA, stD);
+            if (c + 1 < n_chunks) step(c + 1, stB, stA);
+            if (c + 2 < n_chunks) step(c + 2, stC, stB);
+            if (c + 3 < n_chunks) step(c + 3, stD, stC);
+        }
+        if (S_final != nullptr) {
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int dk = 16 * (MS * w4 + ms) + 4 * lq, v = v0 + 16 * nt + l16;
+                    *reinterpret_cast<float4*>(S_final + ((size_t)bh * D + v) * D + dk) =
+                        make_float4(accS[ms][nt][0], accS[ms][nt][1], accS[ms][nt][2], accS[ms][nt][3]);
+                }
+        }
+    } else {
+        OutStage<D, BV> stA, stB, stC, stD;
+        stA.load(QF, PF, gc0, w4, lane);
+        stB.load(QF, PF, gc0 + min(1, n_chunks - 1), w4, lane);
+        stC.load(QF, PF, gc0 + min(2, n_chunks - 1), w4, lane);
+        __syncthreads();   // initial state copy visible
+
+        auto step = [&](int c, const OutStage<D, BV>& cur, OutStage<D, BV>& nxt) __attribute__((always_inline)) {
+            const size_t tok0 = tokb + (size_t)c * CS;
+#ifndef NATS_DEBUG_NO_PREFETCH
+#ifdef NATS_DEBUG_HOT_CHUNKS
+            nxt.load(QF, PF, gc0 + ((c + PF_DIST) & 3), w4, lane);
+#else
+            nxt.load(QF, PF, gc0 + min(c + PF_DIST, n_chunks - 1), w4, lane);
+#endif
+#endif
+            // phase 1: Qg S0^T for this wavefront's 16 tokens
+            f32x4 accO[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) accO[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const half8 fs = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
+                    accO[nt] = mfma16(cur.q[ks], fs, accO[nt]);
+                }
+            __syncthreads();   // U complete
+            // phase 2: + P U, then the linear-branch output rows of these tokens, columns of this slice:
+            // fp16 for the softmax kernel's merge epilogue, fp32 on request
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const half8 fu = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
+                    accO[nt] = mfma16(cur.p[ks], fu, accO[nt]);
+                }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + 16 * (MS * wave + ms) + 4 * lq) =
-                    to_half4(accS[ms][nt]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const size_t off = (tok0 + 16 * w4 + 4 * lq + j) * D + v0 + 16 * nt + l16;
+                    const float o = la_scale * accO[nt][j];
+                    O_la_h[off] = f32_to_half_sat(o);
+                    if (O_la_f32 != nullptr) O_la_f32[off] = o;
+                }
+            __syncthreads();   // U copy free again
+        };
+        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST)
+        step(0, stA, stD);
+        if (n_chunks > 1) step(1, stB, stA);
+        if (n_chunks > 2) step(2, stC, stB);
+        if (n_chunks > 3) step(3, stD, stC);
+        for (int c = 4; c < n_chunks; c += 4) {
+            step(c, stA, stD);
+            if (c + 1 < n_chunks) step(c + 1, stB, stA);
+            if (c + 2 < n_chunks) step(c + 2, stC, stB);
+            if (c + 3 < n_chunks) step(c + 3, stD, stC);
         }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) accO[nt] = mfma16(cur.p[ks], fu[ks][nt], accO[nt]);
-        if (c == NATS_MARK_STEP) NATS_MARK(3);
-        // linear-branch output rows of this wavefront's tokens, columns of this block's slice:
-        // fp16 for the softmax kernel's merge epilogue, fp32 on request
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const size_t off = (tok0 + 16 * wave + 4 * lq + j) * D + v0 + 16 * nt + l16;
-                const float o = la_scale * accO[nt][j];
-                O_la_h[off] = f32_to_half_sat(o);
-                if (O_la_f32 != nullptr) O_la_f32[off] = o;
-            }
-        if (c == NATS_MARK_STEP) NATS_MARK(4);
-        __syncthreads();   // new state copy visible; U copy free again
-        if (c == NATS_MARK_STEP) NATS_MARK(5);
-    };
-
-    // step(c, stage holding chunk c, stage to refill with chunk c+2).  The first three steps are
-    // peeled so that the loop is entered with the same pattern of outstanding loads as its back
-    // edge carries (keeps the compiler's load waits exact).
-    step(0, stA, stC);
-    if (n_chunks > 1) step(1, stB, stA);
-    if (n_chunks > 2) step(2, stC, stB);
-    for (int c = 3; c < n_chunks; c += 3) {
-        step(c, stA, stC);
-        if (c + 1 < n_chunks) step(c + 1, stB, stA);
-        if (c + 2 < n_chunks) step(c + 2, stC, stB);
-    }
-
-    if (S_final != nullptr) {
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int dk = 16 * (MS * wave + ms) + 4 * lq, v = v0 + 16 * nt + l16;
-                *reinterpret_cast<float4*>(S_final + ((size_t)bh * D + v) * D + dk) =
-                    make_float4(accS[ms][nt][0], accS[ms][nt][1], accS[ms][nt][2], accS[ms][nt][3]);
-            }
     }
 }
 
@@ -258,7 +308,10 @@ nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void*
                                   float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st) {
     if (pl.d == 64)
         return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
-    return launch_scan_t<128, 32>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
+#ifndef NATS_SCAN_BV128
+#define NATS_SCAN_BV128 32
+#endif
+    return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
 }
 
 }  // namespace nats
