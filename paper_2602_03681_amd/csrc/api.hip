@@ -228,6 +228,18 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         void* UtF = ws + pl.off_ut;
         void* PF = ws + pl.off_p;
         float* gamC = reinterpret_cast<float*>(ws + pl.off_gam);
+        void* VhT = ws + pl.off_vht;
+        void* Oh = ws + pl.off_olah;   // fp16 hand-off between the two branches
+        // Plain-sum merge (Section 4.1): the softmax branch runs first and hands its output over in
+        // fp16; the kernel that carries the state adds it where the linear output is in registers.
+        // Eq. 21 needs whole rows of both branches: there the softmax kernel runs last and merges.
+        const bool merge_in_scan = pl.combine_mode == 0;
+        if (merge_in_scan) {
+            ProfScope ps("flash_softmax", stream);
+            st = launch_flash_softmax(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
+                                      stream);
+            if (st != NATS_OK) return st;
+        }
         {
             ProfScope ps("gdn_chunk_prep", stream);
             st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, WF, QF, KdF, UtF, PF, gamC, stream);
@@ -236,18 +248,20 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         {
             ProfScope ps("gdn_chunk_scan", stream);
             st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state,
-                                       ws + pl.off_olah, ex.O_la, stream);
+                                       merge_in_scan ? nullptr : Oh, ex.O_la, merge_in_scan ? Oh : nullptr, O,
+                                       stream);
+        }
+        if (st != NATS_OK) return st;
+        if (!merge_in_scan) {
+            ProfScope ps("flash_softmax", stream);
+            st = launch_flash_softmax(pl, Q, Kc, VhT, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
         }
     } else {
-        ProfScope ps("gdn_recurrent", stream);
-        st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la, stream);
-    }
-    if (st != NATS_OK) return st;
-    if (uses_chunk_path(pl)) {
-        ProfScope ps("flash_softmax", stream);
-        st = launch_flash_softmax(pl, Q, Kc, ws + pl.off_vht, cnt, ws + pl.off_olah, ex.w_nla, ex.w_la, O, ex.O_nla,
-                                  ex.lse, stream);
-    } else {
+        {
+            ProfScope ps("gdn_recurrent", stream);
+            st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la, stream);
+        }
+        if (st != NATS_OK) return st;
         ProfScope ps("softmax_fp32", stream);
         st = launch_softmax_fp32(pl, Q, Kc, Vc, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
     }

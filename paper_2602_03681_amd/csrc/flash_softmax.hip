@@ -57,12 +57,17 @@ __device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned
     return x;
 }
 
-template <int D>
+// MERGE = true : the epilogue reads the linear branch's output (fp16), merges and stores O.
+// MERGE = false: the epilogue stores the softmax branch's output as fp16 (O_nla_h); the kernel that
+//                carries the state merges and stores O.  This variant depends on nothing but the
+//                compaction, so it can run beside the linear branch's preparation.
+template <int D, bool MERGE>
 __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
-    const float* __restrict__ w_la, bf16_t* __restrict__ O, float* __restrict__ O_nla_out,
-    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps) {
+    const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
+    float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
+    float eps) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -238,14 +243,16 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     constexpr int RPP = 64 / LPR;         // rows per pass of a wavefront
     float* Ow = Ot + wave * 16 * OS;
     half4 lah_all[FL_NQ][16 / RPP];       // the linear branch's rows, all loads issued up front
+    if (MERGE) {
 #pragma unroll
-    for (int nq = 0; nq < FL_NQ; ++nq)
+        for (int nq = 0; nq < FL_NQ; ++nq)
 #pragma unroll
-        for (int pass = 0; pass < 16 / RPP; ++pass) {
-            const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
-            lah_all[nq][pass] =
-                *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
-        }
+            for (int pass = 0; pass < 16 / RPP; ++pass) {
+                const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
+                lah_all[nq][pass] =
+                    *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
+            }
+    }
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         const int qbase = q0 + (wave * FL_NQ + nq) * 16;
@@ -267,9 +274,13 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             const bool live = q < L;
             const float4 x = *reinterpret_cast<const float4*>(Ow + row * OS + 4 * c4);
             const size_t off = (tokbase + (live ? q : 0)) * D + 4 * c4;
+            if (O_nla_out != nullptr && live) *reinterpret_cast<float4*>(O_nla_out + off) = x;
+            if (!MERGE) {
+                if (live) *reinterpret_cast<half4*>(O_nla_h + off) = to_half4(f32x4{x.x, x.y, x.z, x.w});
+                continue;
+            }
             const half4 lah = lah_all[nq][pass];
             const float la0 = (float)lah[0], la1 = (float)lah[1], la2 = (float)lah[2], la3 = (float)lah[3];
-            if (O_nla_out != nullptr && live) *reinterpret_cast<float4*>(O_nla_out + off) = x;
             float wn = 1.f, wl = 1.f;
             if (combine_mode != 0) {
                 const float ss_nla = lane_group_sum<LPR>(x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w);
@@ -291,19 +302,28 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     NATS_MARK(4);
 }
 
+template <int D, bool MERGE>
+static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT, const int32_t* cnt,
+                      const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
+                      float* O_nla_out, float* lse_out, hipStream_t st) {
+    dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
+    hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                       (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
+                       (half_t*)O_nla_h, O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+}
+
+// O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
+                                 const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
                                  hipStream_t st) {
-    dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
-    if (pl.d == 64)
-        hipLaunchKernelGGL((flash_softmax_kernel<64>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
-                           O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
-    else
-        hipLaunchKernelGGL((flash_softmax_kernel<128>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
-                           O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+    if (O_nla_h == nullptr) {
+        if (pl.d == 64) launch_fl<64, true>(pl, Q, Kc, VhT, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
+        else launch_fl<128, true>(pl, Q, Kc, VhT, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
+    } else {
+        if (pl.d == 64) launch_fl<64, false>(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
+        else launch_fl<128, false>(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
+    }
     return check_launch("flash_softmax");
 }
 

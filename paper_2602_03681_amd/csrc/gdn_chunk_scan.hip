@@ -40,7 +40,13 @@ struct ScanLds {
     static constexpr int o_S = 0;                       // [BV][RS]  state copy, fp16
     static constexpr int o_U = o_S + BV * RS;           // [BV][TS]  U^T, fp16
     static constexpr int n_half = o_U + BV * TS;
+    static constexpr int OSTR = BV + 4;                 // fp32 row stride of the output staging tiles
+    static constexpr int n_ost = 4 * 16 * OSTR;         // [4 wavefronts][16 tok][OSTR]
 };
+
+template <int N> struct HalfVec;
+template <> struct HalfVec<8> { typedef half8 type; };
+template <> struct HalfVec<4> { typedef half4 type; };
 
 // Operands of one chunk for one wavefront, as MFMA fragments in registers.  Every A operand of a
 // step is private to a wavefront (phase 1 splits the chunk's tokens, phase 2 splits d_k), so
@@ -76,11 +82,15 @@ struct ChainStage {   // wavefront w of the state-carrying group
 
 template <int D, int BV>
 struct OutStage {     // wavefront w of the output group
-    static constexpr int KS_D = D / 32;
+    static constexpr int KS_D = D / 32, VPL = BV / 4;
+    typedef typename HalfVec<VPL>::type hvec;
     half8 q[KS_D];      // Qg   rows tok = 16 w + l16
     half8 p[2];         // P    rows r = 16 w + l16
+    hvec onla;          // softmax-branch output, row 16 w + lane / 4, columns v0 + VPL (lane % 4) ..
+    // onla_row: pointer to this lane's VPL values of row (16 w + lane / 4) of the chunk, or nullptr
     __device__ __forceinline__ void load(const half_t* __restrict__ QF, const half_t* __restrict__ PF,
-                                         size_t gc, int w4, int lane) {
+                                         const half_t* onla_row, size_t gc, int w4, int lane) {
+        if (onla_row != nullptr) onla = *reinterpret_cast<const hvec*>(onla_row);
         const half8* Q8 = reinterpret_cast<const half8*>(QF) + ((gc * 4 + w4) * KS_D) * 64 + lane;
 #pragma unroll
         for (int ks = 0; ks < KS_D; ++ks) q[ks] = Q8[ks * 64];
@@ -90,18 +100,24 @@ struct OutStage {     // wavefront w of the output group
     }
 };
 
-template <int D, int BV>
+// MERGE = false: the output group stores the linear branch's output as fp16 (O_la_h) for the softmax
+//                kernel's merge epilogue.
+// MERGE = true : it reads the softmax branch's output (O_nla_h, fp16), adds it and stores O (bf16):
+//                the plain-sum merge of Section 4.1, done where the linear output is in registers.
+template <int D, int BV, bool MERGE>
 __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     const half_t* __restrict__ WF, const half_t* __restrict__ QF, const half_t* __restrict__ KdF,
     const half_t* __restrict__ UtF, const half_t* __restrict__ PF, const float* __restrict__ gamC,
     const float* __restrict__ S0, float* __restrict__ S_final, half_t* __restrict__ O_la_h,
-    float* __restrict__ O_la_f32, int L, int BH, float la_scale) {
+    float* __restrict__ O_la_f32, const half_t* __restrict__ O_nla_h, bf16_t* __restrict__ O, int L, int BH,
+    float la_scale) {
     using Lds = ScanLds<D, BV>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NT = BV / 16;       // 16-wide tiles along the d_v slice
     constexpr int MS = D / 64;        // 16-row d_k tiles of S^T owned by one wavefront
     constexpr int KS_D = D / 32;      // contraction steps over d_k
     __shared__ __align__(16) half_t sh[Lds::n_half];
+    __shared__ __align__(16) float ost_all[MERGE ? Lds::n_ost : 4];
     half_t* Ss = sh + Lds::o_S;
     half_t* Us = sh + Lds::o_U;
 
@@ -231,19 +247,25 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 }
         }
     } else {
+        constexpr int VPL = BV / 4;   // merged output: a lane stores VPL consecutive d_v of one token
+        // this lane's piece of the softmax-branch output for chunk cc (row 16 w4 + lane / 4)
+        auto onla_ptr = [&](int cc) __attribute__((always_inline)) -> const half_t* {
+            return MERGE ? O_nla_h + (tokb + (size_t)cc * CS + 16 * w4 + (lane >> 2)) * D + v0 + VPL * (lane & 3)
+                         : nullptr;
+        };
         OutStage<D, BV> stA, stB, stC, stD;
-        stA.load(QF, PF, gc0, w4, lane);
-        stB.load(QF, PF, gc0 + min(1, n_chunks - 1), w4, lane);
-        stC.load(QF, PF, gc0 + min(2, n_chunks - 1), w4, lane);
+        stA.load(QF, PF, onla_ptr(0), gc0, w4, lane);
+        stB.load(QF, PF, onla_ptr(min(1, n_chunks - 1)), gc0 + min(1, n_chunks - 1), w4, lane);
+        stC.load(QF, PF, onla_ptr(min(2, n_chunks - 1)), gc0 + min(2, n_chunks - 1), w4, lane);
         __syncthreads();   // initial state copy visible
 
         auto step = [&](int c, const OutStage<D, BV>& cur, OutStage<D, BV>& nxt) __attribute__((always_inline)) {
             const size_t tok0 = tokb + (size_t)c * CS;
 #ifndef NATS_DEBUG_NO_PREFETCH
 #ifdef NATS_DEBUG_HOT_CHUNKS
-            nxt.load(QF, PF, gc0 + ((c + PF_DIST) & 3), w4, lane);
+            nxt.load(QF, PF, onla_ptr((c + PF_DIST) & 3), gc0 + ((c + PF_DIST) & 3), w4, lane);
 #else
-            nxt.load(QF, PF, gc0 + min(c + PF_DIST, n_chunks - 1), w4, lane);
+            nxt.load(QF, PF, onla_ptr(min(c + PF_DIST, n_chunks - 1)), gc0 + min(c + PF_DIST, n_chunks - 1), w4, lane);
 #endif
 #endif
             // phase 1: Qg S0^T for this wavefront's 16 tokens
@@ -267,15 +289,50 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                     const half8 fu = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
                     accO[nt] = mfma16(cur.p[ks], fu, accO[nt]);
                 }
+            if (MERGE) {
+                // transpose the 16 x BV result through LDS so that a lane owns VPL consecutive d_v of one
+                // token, add the softmax branch's row piece, store bf16 (one 2*VPL-byte access per lane)
+                constexpr int OSTR = Lds::OSTR;
+                float* Ost = ost_all + w4 * 16 * OSTR;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const size_t off = (tok0 + 16 * w4 + 4 * lq + j) * D + v0 + 16 * nt + l16;
-                    const float o = la_scale * accO[nt][j];
-                    O_la_h[off] = f32_to_half_sat(o);
-                    if (O_la_f32 != nullptr) O_la_f32[off] = o;
+                    for (int j = 0; j < 4; ++j) Ost[(4 * lq + j) * OSTR + 16 * nt + l16] = la_scale * accO[nt][j];
+                __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
+                const int row = lane >> 2, piece = lane & 3;
+                const size_t off = (tok0 + 16 * w4 + row) * D + v0 + VPL * piece;
+                float ola[VPL];
+#pragma unroll
+                for (int i = 0; i < VPL; i += 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(Ost + row * OSTR + VPL * piece + i);
+                    ola[i] = x.x; ola[i + 1] = x.y; ola[i + 2] = x.z; ola[i + 3] = x.w;
                 }
+                uint32_t packed[VPL / 2];
+#pragma unroll
+                for (int i = 0; i < VPL; i += 2)
+                    packed[i / 2] = (uint32_t)f32_to_bf16_bits(ola[i] + (float)cur.onla[i]) |
+                                    ((uint32_t)f32_to_bf16_bits(ola[i + 1] + (float)cur.onla[i + 1]) << 16);
+                if (VPL == 8)
+                    *reinterpret_cast<u32x4*>(O + off) = u32x4{packed[0], packed[1], packed[VPL / 2 - 2], packed[VPL / 2 - 1]};
+                else
+                    *reinterpret_cast<uint2*>(O + off) = make_uint2(packed[0], packed[1]);
+                if (O_la_f32 != nullptr) {
+#pragma unroll
+                    for (int i = 0; i < VPL; i += 4)
+                        *reinterpret_cast<float4*>(O_la_f32 + off + i) = make_float4(ola[i], ola[i + 1], ola[i + 2], ola[i + 3]);
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const size_t off = (tok0 + 16 * w4 + 4 * lq + j) * D + v0 + 16 * nt + l16;
+                        const float o = la_scale * accO[nt][j];
+                        O_la_h[off] = f32_to_half_sat(o);
+                        if (O_la_f32 != nullptr) O_la_f32[off] = o;
+                    }
+            }
             __syncthreads();   // U copy free again
         };
         // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST)
@@ -295,23 +352,35 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 template <int D, int BV>
 static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                  const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                 float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st) {
+                                 float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
+                                 hipStream_t st) {
     dim3 grid(8 * ((pl.BH + 7) / 8) * (D / BV));   // see the block -> (bh, slice) map in the kernel
-    hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV>), grid, dim3(SCAN_THREADS_G), 0, st, (const half_t*)WF,
-                       (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF, (const half_t*)PF, gamC, S0,
-                       S_final, (half_t*)O_la_h, O_la_f32, pl.L, pl.BH, pl.la_scale);
+    if (O_nla_h != nullptr)
+        hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, true>), grid, dim3(SCAN_THREADS_G), 0, st,
+                           (const half_t*)WF, (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF,
+                           (const half_t*)PF, gamC, S0, S_final, (half_t*)nullptr, O_la_f32,
+                           (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BH, pl.la_scale);
+    else
+        hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, false>), grid, dim3(SCAN_THREADS_G), 0, st,
+                           (const half_t*)WF, (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF,
+                           (const half_t*)PF, gamC, S0, S_final, (half_t*)O_la_h, O_la_f32,
+                           (const half_t*)nullptr, (bf16_t*)nullptr, pl.L, pl.BH, pl.la_scale);
     return check_launch("gdn_chunk_scan");
 }
 
+// O_nla_h == nullptr: writes O_la_h (fp16) for the softmax kernel to merge.  Otherwise merges
+// (plain sum) with O_nla_h and writes O.
 nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                  float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st) {
-    if (pl.d == 64)
-        return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
+                                  float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
+                                  hipStream_t st) {
 #ifndef NATS_SCAN_BV128
 #define NATS_SCAN_BV128 32
 #endif
-    return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, st);
+    if (pl.d == 64)
+        return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, O_nla_h, O, st);
+    return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
+                                               O_nla_h, O, st);
 }
 
 }  // namespace nats

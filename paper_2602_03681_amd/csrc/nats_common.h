@@ -111,14 +111,15 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
 nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                  float* S_final, void* O_la_h, float* O_la_f32, hipStream_t st);
+                                  float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
+                                  hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                 hipStream_t st);
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
+                                 const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
                                  hipStream_t st);
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
                           float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
