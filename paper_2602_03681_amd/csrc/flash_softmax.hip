@@ -11,8 +11,8 @@
 //   O^T [d_v x query] += V^T P^T   fp16 MFMA, A = V^T tile from LDS (written transposed, fp16, by the
 //                                  compaction kernel), B = P^T straight from the S^T accumulators:
 //                                  a result tile gives each lane 4 consecutive keys of one query, and two
-//                                  such tiles fill the 8 contraction slots of one lane (the V^T fragment
-//                                  is read with the same slot -> key map).
+//                                  such tiles fill the 8 contraction slots of one lane (the V^T tile's
+//                                  columns are stored in that slot order).
 // A query is one MFMA column, so its max / sum live in the 4 lanes {l, l+16, l+32, l+48}:
 // two xor-shuffles per reduction.  P is rounded to fp16 (2^-12), not bf16: with few visible
 // keys a single p v term dominates and bf16's 2^-9 would exceed the parity bar.
@@ -89,7 +89,8 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
     const int bh = blockIdx.y;
-    const int q0 = blockIdx.x * FL_BM;
+    // later query tiles see more keys: dispatch them first so that the long blocks do not form the tail
+    const int q0 = (gridDim.x - 1 - blockIdx.x) * FL_BM;
     const size_t tokbase = (size_t)bh * L;
     const float scale2 = scale * 1.44269504088896341f;   // logits in base-2 units
 
@@ -99,7 +100,11 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     constexpr int NKP = FL_BN * D / 8 / FL_THREADS;   // ... of a K tile and of a V^T tile
     const int q_last = min(q0 + FL_BM, L) - 1;
     const int n_hi = cnt[tokbase + q_last];   // cnt is non-decreasing: bound for the whole block
+#ifdef NATS_DEBUG_FLASH_NOTILES
+    const int n_tiles = 0 * n_hi;
+#else
     const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
+#endif
     u32x4 kreg[NKP], vreg[NKP];               // next K / V^T tile on its way from global memory to LDS
     auto load_tile = [&](int kt) __attribute__((always_inline)) {
         const u32x4* Kt = reinterpret_cast<const u32x4*>(Kc + (tokbase + (size_t)kt * FL_BN) * D);
@@ -226,9 +231,8 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
         for (int t = 0; t < DT; ++t)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
-                const half_t* vrow = Vs + (16 * t + l16) * TS + 32 * s2 + 4 * lq;
-                const half4 lo = lds_read4(vrow), hi = lds_read4(vrow + 16);
-                const half8 fv = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                // the tile's columns were stored in contraction-slot order by the compaction kernel
+                const half8 fv = lds_read8(Vs + (16 * t + l16) * TS + 32 * s2 + 8 * lq);
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
             }

@@ -13,6 +13,15 @@
 
 namespace nats {
 
+// Column of compacted row c inside its V^T tile of 64.  Within each group of 32 keys the columns are
+// stored in the order in which the softmax kernel's second MFMA consumes them: a lane quad lq holds
+// keys {4 lq + j} of the first 16-key result tile and {16 + 4 lq + j} of the second in its 8
+// contraction slots, so those 8 keys are made contiguous (one 16-byte LDS read per fragment).
+__device__ __forceinline__ int vht_col(int c) {
+    const int k32 = c & 31;
+    return (c & 32) + 8 * ((k32 & 15) >> 2) + 4 * (k32 >> 4) + (k32 & 3);
+}
+
 // fp16 value of one stored element (the MFMA softmax kernel's V^T operand)
 __device__ __forceinline__ half_t elem_to_half(bf16_t x) { return f32_to_half_sat(to_float(x)); }
 __device__ __forceinline__ half_t elem_to_half(float x) { return f32_to_half_sat(x); }
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
             const T* ve = reinterpret_cast<const T*>(&vv);
             half_t* tile = VhT + ((size_t)bh * L + (size_t)(c >> 6) * 64) * d;
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) tile[(size_t)(part * EPL + j) * 64 + (c & 63)] = elem_to_half(ve[j]);
+            for (int j = 0; j < EPL; ++j) tile[(size_t)(part * EPL + j) * 64 + vht_col(c)] = elem_to_half(ve[j]);
         }
     }
     // the tail of the last V^T tile is multiplied by zero weights downstream: make it finite
@@ -118,7 +127,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
         half_t* tile = VhT + ((size_t)bh * L + (size_t)(n_total >> 6) * 64) * d;
         for (int e = tid; e < pad * d; e += SCAN_THREADS) {
             const int dv = e / pad, cc = (n_total & 63) + e % pad;
-            tile[(size_t)dv * 64 + cc] = (half_t)0.f;
+            tile[(size_t)dv * 64 + vht_col(cc)] = (half_t)0.f;
         }
     }
 }
