@@ -44,6 +44,72 @@ def kernel_work(name, cfg, sum_cnt):
     return None
 
 
+def measured_traffic_bytes(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "fwd_cfg2_headline_bf16_hbm_traffic.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) >= 5 and cells[1] == kernel:
+                return float(cells[4]) * 1e6
+    except OSError:
+        pass
+    return None
+
+
+def bench_decode(args):
+    """Decode workload (B=64, H=16, d=128, bf16, cache length U{64..2048}): HBM-bound streaming of the
+    fp32 state (read + write) and the live cache rows, one launch per token."""
+    import numpy as np
+    import torch
+
+    import paper_2602_03681_amd as nats
+    from paper_2602_03681_amd import binding as nb
+    from nats_inputs import CONFIGS, make_decode_inputs
+
+    cfg = CONFIGS["cfg4_decode_bf16"]
+    steps = max(args.steps, 1)
+    x = make_decode_inputs(cfg, steps=steps + args.warmup)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    g = {}
+    for k, v in x.items():
+        if isinstance(v, np.ndarray):
+            t = torch.from_numpy(v).to(dev)
+            g[k] = t.to(torch.bfloat16) if k in ("q", "k", "v", "k_cache", "v_cache") else t
+    o = torch.empty((cfg.B, cfg.H, cfg.d), dtype=torch.bfloat16, device=dev)
+
+    def step(i):
+        nats.hybrid_attn_decode(g["state"], g["k_cache"], g["v_cache"], g["cache_len"], g["q"][i], g["k"][i],
+                                g["v"][i], g["alpha"][i], g["beta"][i], g["mask"][i], out=o)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    len0 = g["cache_len"].sum().item()
+    nb.profile_begin(4 * steps)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = nb.profile_end()
+    len1 = g["cache_len"].sum().item()
+    ms = (t1 - t0) * 1e3 / steps
+    bh, d = cfg.B * cfg.H, cfg.d
+    bytes_per_step = bh * 8 * d * d + 0.5 * (len0 + len1) * 4 * d      # state r+w (fp32) + live K,V rows (bf16)
+    achieved = bytes_per_step / (kern["decode"]["avg_ms"] * 1e-3) / 1e9
+    out = {"metric": "hybrid_attn_decode_tokens_per_s", "value": round(cfg.B / (ms * 1e-3), 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "cfg4_decode_bf16: B=64 H=16 d=128, cache length U{64..2048}, one token per step"},
+           "roofline": {"kernel": "decode", "bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0,
+                        "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
+                        "avg_kernel_ms": round(kern["decode"]["avg_ms"], 4)},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,9 +117,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 256 MiB device copy: the known-size dispatch against which "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    if args.decode:
+        return bench_decode(args)
 
     import numpy as np
     import torch
@@ -89,6 +162,11 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kernels = {} if args.no_kernel_events else nb.profile_end()
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens = cfg.B * cfg.L
     value = tokens / (ms_per_step * 1e-3)
@@ -103,7 +181,7 @@ def main():
             achieved = amount / (kernels[dom]["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
             roofline = {"kernel": dom, "bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
                         "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                        "frac": round(achieved / peak, 5), "traffic": None,
+                        "frac": round(achieved / peak, 5), "traffic": measured_traffic_bytes(dom),
                         "avg_kernel_ms": round(kernels[dom]["avg_ms"], 4)}
 
     cpu_baseline = None

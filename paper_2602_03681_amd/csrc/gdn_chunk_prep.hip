@@ -345,19 +345,30 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st) {
     dim3 grid(pl.L / CH, pl.BH);
+    // the LDS-size attribute is per function and device: set once per device, not per launch
+    static bool attr_done[2][64] = {};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    dev = (dev >= 0 && dev < 64) ? dev : 0;
     if (pl.d == 64) {
         auto kern = gdn_chunk_prep_kernel<64>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                PrepLds<64>::bytes) != hipSuccess)
-            return check_launch("gdn_chunk_prep (LDS attribute)");
+        if (!attr_done[0][dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    PrepLds<64>::bytes) != hipSuccess)
+                return check_launch("gdn_chunk_prep (LDS attribute)");
+            attr_done[0][dev] = true;
+        }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<64>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                PrepLds<128>::bytes) != hipSuccess)
-            return check_launch("gdn_chunk_prep (LDS attribute)");
+        if (!attr_done[1][dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    PrepLds<128>::bytes) != hipSuccess)
+                return check_launch("gdn_chunk_prep (LDS attribute)");
+            attr_done[1][dev] = true;
+        }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<128>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);

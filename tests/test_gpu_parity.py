@@ -157,6 +157,21 @@ def test_eq21_merge_and_initial_state(dtype):
     check_all(x, dtype, r, oracle_fwd(x, mode=1))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_odd_batch_head_count_and_ragged_tiles(dtype):
+    """B*H = 9 (not a multiple of the 8-way block interleave), L = 448 = 3.5 query tiles of 128,
+    softmax counts that are not multiples of the 64-row key tile."""
+    x = make_fwd_inputs(3, 3, 448, 128, dtype, 0.23, seed=16, n_runs=2, run_len=37)
+    r = run_ex(x, dtype)
+    check_all(x, dtype, r, oracle_fwd(x))
+    # plain entry point (no optional outputs) gives the same O
+    g = to_dev(x, dtype)
+    O = nats.hybrid_attn_fwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       r["O"].view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
 def test_single_chunk_and_small_cache_capacity():
     x = make_fwd_inputs(1, 2, 64, 64, "f32", 0.5, seed=13)
     r = run_ex(x, "f32", cap=5)                # cap < n_s: only the first 5 rows are handed out
