@@ -97,7 +97,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
-    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = 0;
+    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = pl->off_prog = 0;
     if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
         pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_qf = off;  off = align_up(off + n_tok * pl->d * 2, 256);
@@ -106,7 +106,8 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         pl->off_p = off;   off = align_up(off + n_tok * pl->C * 2, 256);
         pl->off_gam = off; off = align_up(off + n_tok * 4, 256);
         pl->off_vht = off; off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
-        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);  // fp16 linear-branch output
+        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);  // fp16 hand-off between the branches
+        pl->off_prog = off; off = align_up(off + (size_t)pl->BH * PROG_STRIDE * 4, 256);  // chunk progress per (b,h), one line each
     }
     pl->total = off;
     return NATS_OK;
@@ -218,7 +219,8 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     {
         ProfScope ps("scan_compact", stream);
         st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
-                                 uses_chunk_path(pl) ? ws + pl.off_vht : nullptr, stream);
+                                 uses_chunk_path(pl) ? ws + pl.off_vht : nullptr,
+                                 uses_chunk_path(pl) ? reinterpret_cast<int32_t*>(ws + pl.off_prog) : nullptr, stream);
     }
     if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
@@ -249,7 +251,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
             ProfScope ps("gdn_chunk_scan", stream);
             st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state,
                                        merge_in_scan ? nullptr : Oh, ex.O_la, merge_in_scan ? Oh : nullptr, O,
-                                       stream);
+                                       reinterpret_cast<int32_t*>(ws + pl.off_prog), stream);
         }
         if (st != NATS_OK) return st;
         if (!merge_in_scan) {

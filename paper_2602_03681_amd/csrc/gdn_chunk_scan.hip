@@ -20,6 +20,8 @@
 //
 // MFMA work per chunk and block: (2 d + 2 d + 2 C + 2 d) C BV FLOP; the path is bound by the
 // length of the dependent chain (L / C steps), not by MFMA throughput.
+#include <stdlib.h>
+
 #include "mfma_util.h"
 #include "nats_common.h"
 
@@ -32,6 +34,10 @@ namespace nats {
 
 constexpr int SCAN_THREADS_G = 512;   // 8 wavefronts: 4 carry the state, 4 produce the output
 constexpr int CS = 64;                // chunk size
+#ifndef PF_HELPER_AHEAD
+#define PF_HELPER_AHEAD 12
+#endif
+constexpr int PF_HELPER_FIRST = 4;    // first chunk a prefetch helper touches (earlier ones are already in flight)
 
 template <int D, int BV>
 struct ScanLds {
@@ -109,8 +115,8 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     const half_t* __restrict__ WF, const half_t* __restrict__ QF, const half_t* __restrict__ KdF,
     const half_t* __restrict__ UtF, const half_t* __restrict__ PF, const float* __restrict__ gamC,
     const float* __restrict__ S0, float* __restrict__ S_final, half_t* __restrict__ O_la_h,
-    float* __restrict__ O_la_f32, const half_t* __restrict__ O_nla_h, bf16_t* __restrict__ O, int L, int BH,
-    float la_scale) {
+    float* __restrict__ O_la_f32, const half_t* __restrict__ O_nla_h, bf16_t* __restrict__ O,
+    int32_t* __restrict__ progress, int n_compute, int L, int BH, float la_scale) {
     using Lds = ScanLds<D, BV>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NT = BV / 16;       // 16-wide tiles along the d_v slice
@@ -129,6 +135,47 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     // its own L2; the slices of one (batch, head) read the same operands, so they are given ids
     // that are congruent modulo 8 and therefore share one L2.
     constexpr int NSL = D / BV;
+    const int n_chunks = L / CS;
+    if ((int)blockIdx.x >= n_compute) {
+        // ---- prefetch helper: one block per (batch, head) on an otherwise idle CU of the same XCD.
+        // A CU can keep only so many cache-line misses in flight, so with HBM latency the compute
+        // blocks cannot pull their 60 KB per chunk fast enough by themselves.  The helper reads one
+        // word of every 64 bytes of the chunks they will need a few steps from now, so that their
+        // loads hit in L2.  It follows the published chunk counter and never blocks anyone: every
+        // wait is bounded, and the compute blocks never wait for a helper.
+        const int hid = (int)blockIdx.x - n_compute;
+        const int hbh = (hid >> 3) * 8 + (hid & 7);
+        if (hbh >= BH) return;
+        constexpr int AHEAD = PF_HELPER_AHEAD;       // chunks of lead over the consumer
+        constexpr int SEG = 64 / (int)sizeof(half_t);
+        const size_t hgc0 = (size_t)hbh * n_chunks;
+        float sink = 0.f;
+        for (int c = PF_HELPER_FIRST + wave; c < n_chunks; c += SCAN_THREADS_G / 64) {
+            int spins = 0, done = 0;
+            while (true) {
+                done = __hip_atomic_load(progress + hbh * PROG_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (c <= done + AHEAD || ++spins > 2000) break;
+                // sleep roughly one consumer step per chunk of excess lead: few polls per chunk
+                for (int e = min(c - done - AHEAD, 16); e > 0; --e) __builtin_amdgcn_s_sleep(24);
+            }
+            if (spins > 2000) break;                 // the consumer is not advancing: stop helping
+            if (c <= done + 2) continue;             // too late to be useful for this chunk
+            const size_t gc = hgc0 + c;
+            const half_t* bases[5] = {WF + gc * (size_t)(CS * D), QF + gc * (size_t)(CS * D),
+                                      KdF + gc * (size_t)(D * CS), UtF + gc * (size_t)(D * CS),
+                                      MERGE ? O_nla_h + ((size_t)hbh * L + (size_t)c * CS) * D : WF + gc * (size_t)(CS * D)};
+#pragma unroll
+            for (int a = 0; a < 5; ++a)
+#pragma unroll
+                for (int i = 0; i < CS * D / SEG / 64; ++i)
+                    sink += (float)bases[a][(size_t)(i * 64 + lane) * SEG];
+            const half_t* pb = PF + gc * (size_t)(CS * CS);
+#pragma unroll
+            for (int i = 0; i < CS * CS / SEG / 64; ++i) sink += (float)pb[(size_t)(i * 64 + lane) * SEG];
+        }
+        asm volatile("" ::"v"(sink));   // keeps the loads alive; the values are not used
+        return;
+    }
 #ifdef NATS_DEBUG_PLAIN_MAP
     const int xcd = 0, slot = blockIdx.x % NSL + NSL * 0;
     const int bh = blockIdx.x / NSL + 0 * xcd;
@@ -138,10 +185,10 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #endif
     if (bh >= BH) return;
     const int v0 = (slot % NSL) * BV;
-    const int n_chunks = L / CS;
     const size_t gc0 = (size_t)bh * n_chunks;
     const size_t tokb = (size_t)bh * L;
     constexpr int PF_DIST = 3;
+    const bool publisher = progress != nullptr && is_chain && v0 == 0 && tid == 0;   // reports progress
     // Both groups run the same barrier sequence (two per chunk).  Loads are issued PF_DIST chunks
     // ahead of use through PF_DIST + 1 rotating register stages; they are unconditional (the tail re-loads the
     // last chunk) and the first steps are peeled, so that the compiler's load-wait counts
@@ -171,6 +218,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 
         auto step = [&](int c, const ChainStage<D, BV>& cur, ChainStage<D, BV>& nxt) __attribute__((always_inline)) {
             if (c == NATS_MARK_STEP) NATS_MARK(0);
+            if (publisher) __hip_atomic_store(progress + bh * PROG_STRIDE, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifndef NATS_DEBUG_NO_PREFETCH
 #ifdef NATS_DEBUG_HOT_CHUNKS
             nxt.load(WF, KdF, UtF, gamC, gc0 + ((c + PF_DIST) & 3), v0, w4, lane);
@@ -353,18 +401,22 @@ template <int D, int BV>
 static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                  const void* UtF, const void* PF, const float* gamC, const float* S0,
                                  float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
-                                 hipStream_t st) {
-    dim3 grid(8 * ((pl.BH + 7) / 8) * (D / BV));   // see the block -> (bh, slice) map in the kernel
+                                 int32_t* progress, hipStream_t st) {
+    const int n_compute = 8 * ((pl.BH + 7) / 8) * (D / BV);   // see the block -> (bh, slice) map in the kernel
+    // prefetch helpers only where CUs would otherwise idle (one compute block fills a CU)
+    const int n_helper = 8 * ((pl.BH + 7) / 8);
+    const bool helpers = progress != nullptr && n_compute + n_helper <= 256 && getenv("NATS_NO_PREFETCH_HELPERS") == nullptr;
+    dim3 grid(n_compute + (helpers ? n_helper : 0));
     if (O_nla_h != nullptr)
         hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, true>), grid, dim3(SCAN_THREADS_G), 0, st,
                            (const half_t*)WF, (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF,
                            (const half_t*)PF, gamC, S0, S_final, (half_t*)nullptr, O_la_f32,
-                           (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BH, pl.la_scale);
+                           (const half_t*)O_nla_h, (bf16_t*)O, progress, n_compute, pl.L, pl.BH, pl.la_scale);
     else
         hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, false>), grid, dim3(SCAN_THREADS_G), 0, st,
                            (const half_t*)WF, (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF,
                            (const half_t*)PF, gamC, S0, S_final, (half_t*)O_la_h, O_la_f32,
-                           (const half_t*)nullptr, (bf16_t*)nullptr, pl.L, pl.BH, pl.la_scale);
+                           (const half_t*)nullptr, (bf16_t*)nullptr, progress, n_compute, pl.L, pl.BH, pl.la_scale);
     return check_launch("gdn_chunk_scan");
 }
 
@@ -373,14 +425,15 @@ static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* 
 nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
                                   float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
-                                  hipStream_t st) {
+                                  int32_t* progress, hipStream_t st) {
 #ifndef NATS_SCAN_BV128
 #define NATS_SCAN_BV128 32
 #endif
     if (pl.d == 64)
-        return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, O_nla_h, O, st);
+        return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, O_nla_h, O,
+                                     progress, st);
     return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
-                                               O_nla_h, O, st);
+                                               O_nla_h, O, progress, st);
 }
 
 }  // namespace nats
