@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy: the known-size dispatch against which "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--probes", action="store_true",
+                    help="also time an MFMA-issue probe and a 256 MiB copy and report them as measured_peaks")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -167,6 +169,29 @@ def main():
         dst = torch.empty_like(src)
         dst.copy_(src)          # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
+    measured_peaks = None
+    if args.probes:
+        scratch = torch.empty(4096, dtype=torch.float32, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        nb.probe_mfma(2000, scratch)
+        torch.cuda.synchronize()
+        e0.record()
+        flop = nb.probe_mfma(20000, scratch)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        measured_peaks = {"mfma_f16_16x16x32_TFLOPs": round(mfma_tflops, 1), "copy_256MiB_GBs": round(copy_gbs, 1)}
+        del src, dst
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens = cfg.B * cfg.L
     value = tokens / (ms_per_step * 1e-3)
@@ -177,6 +202,8 @@ def main():
         work = kernel_work(dom, cfg, sum_cnt)
         if work is not None:
             bound, amount = work
+            # the work of one step is spread evenly over that step's launches of the kernel
+            amount = amount * args.steps / max(kernels[dom]["launches"], 1)
             peak, unit = PEAK[bound]
             achieved = amount / (kernels[dom]["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
             roofline = {"kernel": dom, "bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
@@ -208,8 +235,13 @@ def main():
            "config": {"workload": "cfg2_headline_bf16: B=2 H=16 L=8192 d=128 C=64 bf16, mask~Bernoulli(0.05)",
                       "global_batch": cfg.B, "seq_len": cfg.L, "heads": cfg.H, "d_head": cfg.d,
                       "parallelism": "single GPU"},
-           "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kernels.items()},
+           "kernels_ms": {k: round(v["total_ms"] / args.steps, 4) for k, v in kernels.items()},
+           "kernel_launches_per_step": {k: v["launches"] // args.steps for k, v in kernels.items()},
            "roofline": roofline, "cpu_baseline": cpu_baseline}
+    if measured_peaks is not None:
+        out["measured_peaks"] = measured_peaks
+    flop_total = 4.0 * cfg.d * sum_cnt + (10.0 * cfg.C * cfg.d + 6.0 * cfg.d ** 2 + cfg.C ** 2 / 3.0) * cfg.B * cfg.H * cfg.L
+    out["algorithmic_TFLOPs"] = round(flop_total / (ms_per_step * 1e-3) / 1e12, 2)
     print(json.dumps(out))
 
 

@@ -159,6 +159,13 @@ nats_status nats_profile_begin(int max_records);
  * Returns the number of distinct kernels written, or a negative nats_status. */
 int nats_profile_end(char* names, float* total_ms, int32_t* launches, int max_kernels);
 
+/* Measurement helper, no part of the method: launches a kernel in which every wavefront of a
+ * chip-filling grid issues iters x 8 independent 16x16x32 fp16 MFMA (the instruction the bf16 path
+ * is built on) and nothing else.  out: DEVICE buffer of at least 2048 floats (scratch, overwritten).
+ * Returns the floating-point operations that launch performs (the caller times it on the stream),
+ * or a negative value on error (see nats_last_error). */
+double nats_probe_mfma(int iters, float* out, size_t out_floats, void* hip_stream);
+
 /* Host-side message for the last non-OK status returned on this thread ("" if none). */
 const char* nats_last_error(void);
 

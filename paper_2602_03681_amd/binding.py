@@ -50,7 +50,7 @@ class DecParams(ctypes.Structure):
 
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
-           "nats_profile_end")
+           "nats_profile_end", "nats_probe_mfma")
 
 
 def library_path() -> str:
@@ -79,6 +79,8 @@ def load_library():
     lib.nats_hybrid_attn_decode.argtypes = [ctypes.POINTER(DecParams)] + [vp] * 15
     lib.nats_last_error.restype = ctypes.c_char_p
     lib.nats_abi_version.restype = ctypes.c_int
+    lib.nats_probe_mfma.restype = ctypes.c_double
+    lib.nats_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.nats_profile_begin.restype = ctypes.c_int
     lib.nats_profile_begin.argtypes = [ctypes.c_int]
     lib.nats_profile_end.restype = ctypes.c_int
@@ -254,6 +256,15 @@ def profile_end(max_kernels: int = 16) -> Dict[str, Dict[str, float]]:
         name = names.raw[32 * i:32 * i + 32].split(b"\0", 1)[0].decode()
         out[name] = {"total_ms": float(ms[i]), "launches": int(cnt[i]), "avg_ms": float(ms[i]) / max(int(cnt[i]), 1)}
     return out
+
+
+def probe_mfma(iters: int, out) -> float:
+    """nats_probe_mfma: launch the MFMA-issue probe; `out` is a float32 device tensor of >= 2048 elements.
+    Returns the FLOP of the launch (time it on torch's current stream)."""
+    flop = load_library().nats_probe_mfma(int(iters), out.data_ptr(), out.numel(), _stream_ptr())
+    if flop < 0:
+        raise RuntimeError(load_library().nats_last_error().decode())
+    return float(flop)
 
 
 decode = hybrid_attn_decode
