@@ -98,13 +98,18 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     // ---- prologue: the block's Q rows, coalesced, through LDS into B-operand fragments ------------
     constexpr int NQP = FL_BM * D / 8 / FL_THREADS;   // 16-byte pieces per thread of the Q tile
     constexpr int NKP = FL_BN * D / 8 / FL_THREADS;   // ... of a K tile and of a V^T tile
+    // Every global load of the prologue is issued before the first use of any of them, so that the
+    // block pays one memory latency here, not one per dependent step: the per-query counts, the count
+    // that bounds the block, the Q tile and key tile 0 (which exists for every sequence: the
+    // compacted buffers have capacity L >= 64 rows; its contents are not used if nothing is visible).
     const int q_last = min(q0 + FL_BM, L) - 1;
+    int my_cnt[FL_NQ];
+#pragma unroll
+    for (int nq = 0; nq < FL_NQ; ++nq) {
+        const int ql = (wave * FL_NQ + nq) * 16 + l16;
+        my_cnt[nq] = cnt[tokbase + min(q0 + ql, L - 1)];
+    }
     const int n_hi = cnt[tokbase + q_last];   // cnt is non-decreasing: bound for the whole block
-#ifdef NATS_DEBUG_FLASH_NOTILES
-    const int n_tiles = 0 * n_hi;
-#else
-    const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
-#endif
     u32x4 kreg[NKP], vreg[NKP];               // next K / V^T tile on its way from global memory to LDS
     auto load_tile = [&](int kt) __attribute__((always_inline)) {
         const u32x4* Kt = reinterpret_cast<const u32x4*>(Kc + (tokbase + (size_t)kt * FL_BN) * D);
@@ -118,34 +123,41 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     {
         u32x4 qreg[NQP];
 #pragma unroll
-        for (int i = 0; i < NQP; ++i) {   // all loads in flight before the first use
+        for (int i = 0; i < NQP; ++i) {
             const int e = tid + FL_THREADS * i;
             const int row = e / (D / 8), c8 = e % (D / 8);
-            qreg[i] = (q0 + row < L) ? *reinterpret_cast<const u32x4*>(Q + (tokbase + q0 + row) * D + c8 * 8)
-                                     : u32x4{0u, 0u, 0u, 0u};
+            qreg[i] = *reinterpret_cast<const u32x4*>(Q + (tokbase + min(q0 + row, L - 1)) * D + c8 * 8);
         }
-        if (n_tiles > 0) load_tile(0);
+        load_tile(0);
 #pragma unroll
         for (int i = 0; i < NQP; ++i) {
             const int e = tid + FL_THREADS * i;
             *reinterpret_cast<u32x4*>(Qst + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = qreg[i];
         }
     }
+#ifdef NATS_DEBUG_FLASH_NOTILES
+    const int n_tiles = 0 * n_hi;
+#else
+    const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
+#endif
     __syncthreads();
     u32x4 qf[FL_NQ][KS_D];
-    int my_cnt[FL_NQ];
-    int wave_hi = 0;
+    int wave_hi = 0, wave_lo = 0x7fffffff;   // most and fewest keys visible to a query of this wavefront
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         const int ql = (wave * FL_NQ + nq) * 16 + l16;
-        my_cnt[nq] = (q0 + ql < L) ? cnt[tokbase + q0 + ql] : 0;
+        if (q0 + ql >= L) my_cnt[nq] = 0;   // rows past the end see nothing
 #pragma unroll
         for (int ks = 0; ks < KS_D; ++ks)
             qf[nq][ks] = *reinterpret_cast<const u32x4*>(Qst + ql * RS + 32 * ks + 8 * lq);
         wave_hi = max(wave_hi, my_cnt[nq]);
+        wave_lo = min(wave_lo, my_cnt[nq]);
     }
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) wave_hi = max(wave_hi, __shfl_xor(wave_hi, off));
+    for (int off = 1; off < 64; off <<= 1) {
+        wave_hi = max(wave_hi, __shfl_xor(wave_hi, off));
+        wave_lo = min(wave_lo, __shfl_xor(wave_lo, off));
+    }
 
     f32x4 accO[FL_NQ][DT];
     float m_run[FL_NQ], l_run[FL_NQ];
@@ -186,43 +198,57 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             }
 
         // ---- online softmax per query column; P^T fragments ------------------------------------------
+        // VALU work is what bounds this loop, so it is kept to one fused multiply-add, one exponential,
+        // one add and one conversion per logit: masking only in tiles that are not visible in full to
+        // every query of the wavefront; the running maximum is raised only when the tile's maximum
+        // exceeds it by more than 2^8 (the weights then stay below 2^8, exact enough in fp16 and far
+        // from overflow), so rescaling of the accumulators is rare and skipped by the whole wavefront.
+        const bool full_tile = (kt + 1) * FL_BN <= wave_lo;
         half8 pf[FL_NQ][2];
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
+            if (!full_tile) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int c = kt * FL_BN + 16 * m + 4 * lq + j;
+                        if (c >= my_cnt[nq]) accS[nq][m][j] = -INFINITY;
+                    }
+            }
             float tmax = -INFINITY;
 #pragma unroll
             for (int m = 0; m < 4; ++m)
+                tmax = fmaxf(fmaxf(tmax, fmaxf(accS[nq][m][0], accS[nq][m][1])), fmaxf(accS[nq][m][2], accS[nq][m][3]));
+            tmax = quad_max(tmax) * scale2;    // scale2 > 0: the maximum commutes with the scaling
+            const float m_old = m_run[nq];
+            const bool raise = tmax > m_old + 8.f;   // also true for the first visible key (m_old = -inf)
+            const float m_new = raise ? tmax : m_old;
+            const float m_sub = m_new > -INFINITY ? m_new : 0.f;   // nothing visible yet: weights exp2(-inf) = 0
+            if (__any(raise)) {
+                const float corr = raise ? __builtin_amdgcn_exp2f(m_old - m_new) : 1.f;   // exp2(-inf) = 0
+                l_run[nq] *= corr;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int c = kt * FL_BN + 16 * m + 4 * lq + j;
-                    const float sv = (c < my_cnt[nq]) ? accS[nq][m][j] * scale2 : -INFINITY;
-                    accS[nq][m][j] = sv;
-                    tmax = fmaxf(tmax, sv);
+                for (int t = 0; t < DT; ++t) {
+                    accO[nq][t][0] *= corr; accO[nq][t][1] *= corr; accO[nq][t][2] *= corr; accO[nq][t][3] *= corr;
                 }
-            tmax = quad_max(tmax);
-            const float m_new = fmaxf(m_run[nq], tmax);
-            const bool any = m_new > -INFINITY;
-            const float corr = any ? __builtin_amdgcn_exp2f(m_run[nq] - m_new) : 1.f;
+            }
+            m_run[nq] = m_new;
             float psum = 0.f;
 #pragma unroll
             for (int m = 0; m < 4; ++m)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float pv = any ? __builtin_amdgcn_exp2f(accS[nq][m][j] - m_new) : 0.f;
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(accS[nq][m][j], scale2, -m_sub));
                     accS[nq][m][j] = pv;
                     psum += pv;
                 }
-            psum = quad_sum(psum);
-            l_run[nq] = l_run[nq] * corr + psum;
-            m_run[nq] = m_new;
-#pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                accO[nq][t][0] *= corr; accO[nq][t][1] *= corr; accO[nq][t][2] *= corr; accO[nq][t][3] *= corr;
-            }
+            l_run[nq] += quad_sum(psum);
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {   // contraction step s2: slots 0-3 <- key tile 2 s2, 4-7 <- 2 s2 + 1
-                const half4 lo = to_half4(accS[nq][2 * s2]), hi = to_half4(accS[nq][2 * s2 + 1]);
-                pf[nq][s2] = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const f32x4 lo = accS[nq][2 * s2], hi = accS[nq][2 * s2 + 1];   // weights <= 2^8: no clamp needed
+                pf[nq][s2] = half8{(half_t)lo[0], (half_t)lo[1], (half_t)lo[2], (half_t)lo[3],
+                                   (half_t)hi[0], (half_t)hi[1], (half_t)hi[2], (half_t)hi[3]};
             }
         }
 
