@@ -26,6 +26,9 @@
 #ifndef NATS_MARK
 #define NATS_MARK(i) do {} while (0)   // phase timestamps, only in debug harness builds
 #endif
+#ifndef NATS_MARK_TILE
+#define NATS_MARK_TILE 3               // the key tile whose inner phases the debug harness times
+#endif
 
 namespace nats {
 
@@ -171,14 +174,18 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
 
     NATS_MARK(1);
     for (int kt = 0; kt < n_tiles; ++kt) {
+        if (kt == NATS_MARK_TILE) NATS_MARK(10);
         __syncthreads();   // the previous tile (or the Q tile) is no longer read
+        if (kt == NATS_MARK_TILE) NATS_MARK(11);
 #pragma unroll
         for (int i = 0; i < NKP; ++i) {   // registers -> LDS: K rows [key][d], V^T rows [d_v][key]
             const int e = tid + FL_THREADS * i;
             *reinterpret_cast<u32x4*>(Ks + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = kreg[i];
             *reinterpret_cast<u32x4*>(Vs + (e >> 3) * TS + (e & 7) * 8) = vreg[i];
         }
+        if (kt == NATS_MARK_TILE) NATS_MARK(12);
         __syncthreads();
+        if (kt == NATS_MARK_TILE) NATS_MARK(13);
         load_tile(kt + 1 < n_tiles ? kt + 1 : kt);   // next tile in flight during this tile's products
         if (kt * FL_BN >= wave_hi) continue;   // nothing visible to this wavefront in this tile (uniform)
 
@@ -197,6 +204,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
                 for (int nq = 0; nq < FL_NQ; ++nq) accS[nq][m] = mfma16_bf16(fk, qf[nq][ks], accS[nq][m]);
             }
 
+        if (kt == NATS_MARK_TILE) NATS_MARK(14);
         // ---- online softmax per query column; P^T fragments ------------------------------------------
         // VALU work is what bounds this loop, so it is kept to one fused multiply-add, one exponential,
         // one add and one conversion per logit: masking only in tiles that are not visible in full to
@@ -252,6 +260,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             }
         }
 
+        if (kt == NATS_MARK_TILE) NATS_MARK(15);
         // ---- O^T += V^T P^T -----------------------------------------------------------------------
 #pragma unroll
         for (int t = 0; t < DT; ++t)
@@ -262,6 +271,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
             }
+        if (kt == NATS_MARK_TILE) NATS_MARK(16);
     }
     NATS_MARK(2);
     __syncthreads();   // tiles are dead: the region becomes the output staging
@@ -320,10 +330,8 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             }
             if (live) {
                 uint2 w;
-                w.x = (uint32_t)f32_to_bf16_bits(wn * x.x + wl * la0) |
-                      ((uint32_t)f32_to_bf16_bits(wn * x.y + wl * la1) << 16);
-                w.y = (uint32_t)f32_to_bf16_bits(wn * x.z + wl * la2) |
-                      ((uint32_t)f32_to_bf16_bits(wn * x.w + wl * la3) << 16);
+                w.x = pack_bf16x2(wn * x.x + wl * la0, wn * x.y + wl * la1);
+                w.y = pack_bf16x2(wn * x.z + wl * la2, wn * x.w + wl * la3);
                 *reinterpret_cast<uint2*>(O + off) = w;
             }
         }

@@ -37,6 +37,9 @@ constexpr int CS = 64;                // chunk size
 #ifndef PF_HELPER_AHEAD
 #define PF_HELPER_AHEAD 12
 #endif
+#ifndef NATS_STORE_FENCED
+#define NATS_STORE_FENCED 0
+#endif
 constexpr int PF_HELPER_FIRST = 4;    // first chunk a prefetch helper touches (earlier ones are already in flight)
 
 template <int D, int BV>
@@ -71,18 +74,27 @@ struct ChainStage {   // wavefront w of the state-carrying group
     __device__ __forceinline__ void load(const half_t* __restrict__ WF, const half_t* __restrict__ KdF,
                                          const half_t* __restrict__ UtF, const float* __restrict__ gamC,
                                          size_t gc, int v0, int w4, int lane) {
-        const half8* W8 = reinterpret_cast<const half8*>(WF) + ((gc * 4 + w4) * KS_D) * 64 + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) w[ks] = W8[ks * 64];
-        const half8* K8 = reinterpret_cast<const half8*>(KdF) + ((gc * 4 + w4) * MS * 2) * 64 + lane;
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) kd[ms][ks] = K8[(ms * 2 + ks) * 64];
-        const half4* U4 = reinterpret_cast<const half4*>(UtF) + ((gc * (D / 16) + v0 / 16) * 4 + w4) * 64 + lane;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) ut[nt] = U4[nt * 4 * 64];
-        gC = gamC[gc];
+        for (int i = 0; i < N_PIECES; ++i) load_piece(i, WF, KdF, UtF, gamC, gc, v0, w4, lane);
+    }
+    // The loads of a stage one at a time, so that a step can spread them between its matrix
+    // instructions: pieces [0, KS_D) -W, [KS_D, KS_D + NT) U~, then the chunk decay, then Kd.
+    static constexpr int N_P1 = KS_D + NT + 1;          // pieces phase 1 of the step needs
+    static constexpr int N_PIECES = N_P1 + 2 * MS;
+    __device__ __forceinline__ void load_piece(int i, const half_t* __restrict__ WF, const half_t* __restrict__ KdF,
+                                               const half_t* __restrict__ UtF, const float* __restrict__ gamC,
+                                               size_t gc, int v0, int w4, int lane) {
+        if (i < KS_D) {
+            w[i] = (reinterpret_cast<const half8*>(WF) + ((gc * 4 + w4) * KS_D) * 64 + lane)[i * 64];
+        } else if (i < KS_D + NT) {
+            const int nt = i - KS_D;
+            ut[nt] = (reinterpret_cast<const half4*>(UtF) + ((gc * (D / 16) + v0 / 16) * 4 + w4) * 64 + lane)[nt * 4 * 64];
+        } else if (i == KS_D + NT) {
+            gC = gamC[gc];
+        } else {
+            const int m = i - N_P1;
+            kd[m / 2][m % 2] = (reinterpret_cast<const half8*>(KdF) + ((gc * 4 + w4) * MS * 2) * 64 + lane)[m * 64];
+        }
     }
 };
 
@@ -96,13 +108,20 @@ struct OutStage {     // wavefront w of the output group
     // onla_row: pointer to this lane's VPL values of row (16 w + lane / 4) of the chunk, or nullptr
     __device__ __forceinline__ void load(const half_t* __restrict__ QF, const half_t* __restrict__ PF,
                                          const half_t* onla_row, size_t gc, int w4, int lane) {
-        if (onla_row != nullptr) onla = *reinterpret_cast<const hvec*>(onla_row);
-        const half8* Q8 = reinterpret_cast<const half8*>(QF) + ((gc * 4 + w4) * KS_D) * 64 + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) q[ks] = Q8[ks * 64];
-        const half8* P8 = reinterpret_cast<const half8*>(PF) + ((gc * 4 + w4) * 2) * 64 + lane;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) p[ks] = P8[ks * 64];
+        for (int i = 0; i < N_PIECES; ++i) load_piece(i, QF, PF, onla_row, gc, w4, lane);
+    }
+    // one load at a time (see ChainStage): pieces [0, KS_D) Qg, then P, then the softmax-branch row piece
+    static constexpr int N_PIECES = KS_D + 3;
+    __device__ __forceinline__ void load_piece(int i, const half_t* __restrict__ QF, const half_t* __restrict__ PF,
+                                               const half_t* onla_row, size_t gc, int w4, int lane) {
+        if (i < KS_D) {
+            q[i] = (reinterpret_cast<const half8*>(QF) + ((gc * 4 + w4) * KS_D) * 64 + lane)[i * 64];
+        } else if (i < KS_D + 2) {
+            p[i - KS_D] = (reinterpret_cast<const half8*>(PF) + ((gc * 4 + w4) * 2) * 64 + lane)[(i - KS_D) * 64];
+        } else if (onla_row != nullptr) {
+            onla = *reinterpret_cast<const hvec*>(onla_row);
+        }
     }
 };
 
@@ -123,7 +142,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     constexpr int MS = D / 64;        // 16-row d_k tiles of S^T owned by one wavefront
     constexpr int KS_D = D / 32;      // contraction steps over d_k
     __shared__ __align__(16) half_t sh[Lds::n_half];
-    __shared__ __align__(16) float ost_all[MERGE ? Lds::n_ost : 4];
+    __shared__ __align__(16) float ost_all[Lds::n_ost];
     half_t* Ss = sh + Lds::o_S;
     half_t* Us = sh + Lds::o_U;
 
@@ -219,14 +238,27 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         auto step = [&](int c, const ChainStage<D, BV>& cur, ChainStage<D, BV>& nxt) __attribute__((always_inline)) {
             if (c == NATS_MARK_STEP) NATS_MARK(0);
             if (publisher) __hip_atomic_store(progress + bh * PROG_STRIDE, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // The loads for chunk c + PF_DIST are issued one at a time between the matrix instructions of
+            // this step: issued in a burst they queue in the CU's vector-memory path (about 16 cycles
+            // per 1 KiB load, shared with the output group) and stall the wavefront that carries the
+            // dependent chain for hundreds of cycles.
+            using CS_t = ChainStage<D, BV>;
+            const size_t gcn = gc0 + min(c + PF_DIST, n_chunks - 1);
+            int piece = 0;
+            auto one_load = [&]() __attribute__((always_inline)) {
 #ifndef NATS_DEBUG_NO_PREFETCH
-#ifdef NATS_DEBUG_HOT_CHUNKS
-            nxt.load(WF, KdF, UtF, gamC, gc0 + ((c + PF_DIST) & 3), v0, w4, lane);
-#else
-            nxt.load(WF, KdF, UtF, gamC, gc0 + min(c + PF_DIST, n_chunks - 1), v0, w4, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                if (piece < CS_t::N_PIECES) nxt.load_piece(piece, WF, KdF, UtF, gamC, gcn, v0, w4, lane);
+                ++piece;
+                __builtin_amdgcn_sched_barrier(0);
 #endif
-#endif
+            };
             // phase 1: U = U~ - W S0^T for this wavefront's 16 tokens
+            half8 fs[KS_D][NT];
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
             f32x4 accU[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
@@ -235,8 +267,8 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    const half8 fs = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
-                    accU[nt] = mfma16(cur.w[ks], fs, accU[nt]);
+                    accU[nt] = mfma16(cur.w[ks], fs[ks][nt], accU[nt]);
+                    if (piece < CS_t::N_P1) one_load();
                 }
             // decay of the state, off the dependent chain (phase 1 reads the fp16 copy in LDS)
 #pragma unroll
@@ -249,6 +281,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
                 *reinterpret_cast<half4*>(Us + (16 * nt + l16) * TS + 16 * w4 + 4 * lq) = to_half4(accU[nt]);
+            while (piece < CS_t::N_P1) one_load();
             if (c == NATS_MARK_STEP) NATS_MARK(1);
             __syncthreads();   // U complete; the old state copy has been read by everyone
             if (c == NATS_MARK_STEP) NATS_MARK(2);
@@ -263,12 +296,16 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) accS[ms][nt] = mfma16(cur.kd[ms][ks], fu[ks][nt], accS[ms][nt]);
+                    for (int nt = 0; nt < NT; ++nt) {
+                        accS[ms][nt] = mfma16(cur.kd[ms][ks], fu[ks][nt], accS[ms][nt]);
+                        one_load();
+                    }
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + 16 * (MS * w4 + ms) + 4 * lq) =
                         to_half4(accS[ms][nt]);
             }
+            while (piece < CS_t::N_PIECES) one_load();
             if (c == NATS_MARK_STEP) NATS_MARK(3);
             __syncthreads();   // new state copy visible; U copy free again
             if (c == NATS_MARK_STEP) NATS_MARK(4);
@@ -307,16 +344,71 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         stC.load(QF, PF, onla_ptr(min(2, n_chunks - 1)), gc0 + min(2, n_chunks - 1), w4, lane);
         __syncthreads();   // initial state copy visible
 
-        auto step = [&](int c, const OutStage<D, BV>& cur, OutStage<D, BV>& nxt) __attribute__((always_inline)) {
-            const size_t tok0 = tokb + (size_t)c * CS;
+        // The result rows of a chunk leave through a staging tile in LDS that is private to the
+        // wavefront (transposed there so that a lane owns VPL consecutive d_v of one token and every
+        // global access is a full row segment).  Between the two barriers of a step stand only the
+        // products that read U and the writes into that tile: the dependent chain waits at the second
+        // barrier.  Reading the tile back, the merge and the store of chunk c - 1 are spread between
+        // the matrix instructions of step c's first phase, like the loads for chunk c + PF_DIST.
+        constexpr int OSTR = Lds::OSTR;
+        float* Ost = ost_all + w4 * 16 * OSTR;
+        using OS_t = OutStage<D, BV>;
+        // st: the stage that holds chunk cprev's piece of the softmax-branch output
+        auto store_rows = [&](int cprev, const OS_t& st) __attribute__((always_inline)) {
+            const int row = lane >> 2, piece = lane & 3;
+            const size_t off = (tokb + (size_t)cprev * CS + 16 * w4 + row) * D + v0 + VPL * piece;
+            float ola[VPL];
+#pragma unroll
+            for (int i = 0; i < VPL; i += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(Ost + row * OSTR + VPL * piece + i);
+                ola[i] = x.x; ola[i + 1] = x.y; ola[i + 2] = x.z; ola[i + 3] = x.w;
+            }
+            if (O_la_f32 != nullptr) {
+#pragma unroll
+                for (int i = 0; i < VPL; i += 4)
+                    *reinterpret_cast<float4*>(O_la_f32 + off + i) = make_float4(ola[i], ola[i + 1], ola[i + 2], ola[i + 3]);
+            }
+            uint32_t packed[VPL / 2];
+            if (MERGE) {   // add the softmax branch's row piece, store bf16
+#pragma unroll
+                for (int i = 0; i < VPL; i += 2)
+                    packed[i / 2] = pack_bf16x2(ola[i] + (float)st.onla[i], ola[i + 1] + (float)st.onla[i + 1]);
+            } else {       // the linear branch's rows as fp16 for the softmax kernel's merge epilogue
+#pragma unroll
+                for (int i = 0; i < VPL; i += 2) {
+                    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+                    const half2_t h = half2_t{f32_to_half_sat(ola[i]), f32_to_half_sat(ola[i + 1])};
+                    packed[i / 2] = __builtin_bit_cast(uint32_t, h);
+                }
+            }
+            void* dst = MERGE ? static_cast<void*>(O + off) : static_cast<void*>(O_la_h + off);
+            if (VPL == 8)
+                *reinterpret_cast<u32x4*>(dst) = u32x4{packed[0], packed[1], packed[VPL / 2 - 2], packed[VPL / 2 - 1]};
+            else
+                *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
+        };
+
+        auto step = [&](int c, const OS_t& cur, OS_t& nxt) __attribute__((always_inline)) {
+#ifdef NATS_DEBUG_IDLE_OUTPUT
+            __syncthreads(); __syncthreads(); return;
+#endif
+            const int cn = min(c + PF_DIST, n_chunks - 1);
+            const half_t* onla_n = onla_ptr(cn);
+            int piece = 0;
+            auto one_load = [&]() __attribute__((always_inline)) {
 #ifndef NATS_DEBUG_NO_PREFETCH
-#ifdef NATS_DEBUG_HOT_CHUNKS
-            nxt.load(QF, PF, onla_ptr((c + PF_DIST) & 3), gc0 + ((c + PF_DIST) & 3), w4, lane);
-#else
-            nxt.load(QF, PF, onla_ptr(min(c + PF_DIST, n_chunks - 1)), gc0 + min(c + PF_DIST, n_chunks - 1), w4, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                if (piece < OS_t::N_PIECES) nxt.load_piece(piece, QF, PF, onla_n, gc0 + cn, w4, lane);
+                ++piece;
+                __builtin_amdgcn_sched_barrier(0);
 #endif
-#endif
+            };
             // phase 1: Qg S0^T for this wavefront's 16 tokens
+            half8 fs[KS_D][NT];
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
             f32x4 accO[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) accO[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -324,12 +416,22 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    const half8 fs = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
-                    accO[nt] = mfma16(cur.q[ks], fs, accO[nt]);
+                    accO[nt] = mfma16(cur.q[ks], fs[ks][nt], accO[nt]);
+                    if (ks == 0 && nt == NT - 1 && c > 0) {
+                        // rows of the previous chunk; nxt still holds that chunk's softmax-branch piece
+#if NATS_STORE_FENCED
+                        __builtin_amdgcn_sched_barrier(0);
+#endif
+                        store_rows(c - 1, nxt);
+#if NATS_STORE_FENCED
+                        __builtin_amdgcn_sched_barrier(0);
+#endif
+                    }
+                    if (ks > 0 || nt == NT - 1) one_load();
                 }
+            while (piece < OS_t::N_PIECES) one_load();
             __syncthreads();   // U complete
-            // phase 2: + P U, then the linear-branch output rows of these tokens, columns of this slice:
-            // fp16 for the softmax kernel's merge epilogue, fp32 on request
+            // phase 2: + P U, then the result tile into the staging rows
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -337,53 +439,13 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                     const half8 fu = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
                     accO[nt] = mfma16(cur.p[ks], fu, accO[nt]);
                 }
-            if (MERGE) {
-                // transpose the 16 x BV result through LDS so that a lane owns VPL consecutive d_v of one
-                // token, add the softmax branch's row piece, store bf16 (one 2*VPL-byte access per lane)
-                constexpr int OSTR = Lds::OSTR;
-                float* Ost = ost_all + w4 * 16 * OSTR;
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) Ost[(4 * lq + j) * OSTR + 16 * nt + l16] = la_scale * accO[nt][j];
-                __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
-                const int row = lane >> 2, piece = lane & 3;
-                const size_t off = (tok0 + 16 * w4 + row) * D + v0 + VPL * piece;
-                float ola[VPL];
-#pragma unroll
-                for (int i = 0; i < VPL; i += 4) {
-                    const float4 x = *reinterpret_cast<const float4*>(Ost + row * OSTR + VPL * piece + i);
-                    ola[i] = x.x; ola[i + 1] = x.y; ola[i + 2] = x.z; ola[i + 3] = x.w;
-                }
-                uint32_t packed[VPL / 2];
-#pragma unroll
-                for (int i = 0; i < VPL; i += 2)
-                    packed[i / 2] = (uint32_t)f32_to_bf16_bits(ola[i] + (float)cur.onla[i]) |
-                                    ((uint32_t)f32_to_bf16_bits(ola[i + 1] + (float)cur.onla[i + 1]) << 16);
-                if (VPL == 8)
-                    *reinterpret_cast<u32x4*>(O + off) = u32x4{packed[0], packed[1], packed[VPL / 2 - 2], packed[VPL / 2 - 1]};
-                else
-                    *reinterpret_cast<uint2*>(O + off) = make_uint2(packed[0], packed[1]);
-                if (O_la_f32 != nullptr) {
-#pragma unroll
-                    for (int i = 0; i < VPL; i += 4)
-                        *reinterpret_cast<float4*>(O_la_f32 + off + i) = make_float4(ola[i], ola[i + 1], ola[i + 2], ola[i + 3]);
-                }
-                __builtin_amdgcn_wave_barrier();
-            } else {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const size_t off = (tok0 + 16 * w4 + 4 * lq + j) * D + v0 + 16 * nt + l16;
-                        const float o = la_scale * accO[nt][j];
-                        O_la_h[off] = f32_to_half_sat(o);
-                        if (O_la_f32 != nullptr) O_la_f32[off] = o;
-                    }
-            }
+                for (int j = 0; j < 4; ++j) Ost[(4 * lq + j) * OSTR + 16 * nt + l16] = la_scale * accO[nt][j];
             __syncthreads();   // U copy free again
         };
-        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST)
+        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST, which held chunk c - 1)
         step(0, stA, stD);
         if (n_chunks > 1) step(1, stB, stA);
         if (n_chunks > 2) step(2, stC, stB);
@@ -394,6 +456,15 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             if (c + 2 < n_chunks) step(c + 2, stC, stB);
             if (c + 3 < n_chunks) step(c + 3, stD, stC);
         }
+#ifndef NATS_DEBUG_IDLE_OUTPUT
+        // rows of the last chunk
+        switch ((n_chunks - 1) & 3) {
+            case 0: store_rows(n_chunks - 1, stA); break;
+            case 1: store_rows(n_chunks - 1, stB); break;
+            case 2: store_rows(n_chunks - 1, stC); break;
+            default: store_rows(n_chunks - 1, stD); break;
+        }
+#endif
     }
 }
 
