@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy: the known-size dispatch against which "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a captured HIP graph (extra key graph_replay_ms_per_step)")
     ap.add_argument("--probes", action="store_true",
                     help="also time an MFMA-issue probe and a 256 MiB copy and report them as measured_peaks")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
@@ -164,6 +166,24 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kernels = {} if args.no_kernel_events else nb.profile_end()
+    graph_ms = None
+    if args.graph:
+        # the same step replayed from a HIP graph (launch gaps removed); reported beside the eager figure
+        gs = torch.cuda.Stream()
+        gs.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(gs):
+            with torch.cuda.graph(graph, stream=gs):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -240,6 +260,8 @@ def main():
            "roofline": roofline, "cpu_baseline": cpu_baseline}
     if measured_peaks is not None:
         out["measured_peaks"] = measured_peaks
+    if graph_ms is not None:
+        out["graph_replay_ms_per_step"] = round(graph_ms, 4)
     flop_total = 4.0 * cfg.d * sum_cnt + (10.0 * cfg.C * cfg.d + 6.0 * cfg.d ** 2 + cfg.C ** 2 / 3.0) * cfg.B * cfg.H * cfg.L
     out["algorithmic_TFLOPs"] = round(flop_total / (ms_per_step * 1e-3) / 1e12, 2)
     print(json.dumps(out))

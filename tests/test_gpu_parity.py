@@ -200,3 +200,61 @@ def test_runs_on_a_side_stream():
         O = nats.hybrid_attn_fwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64)
     s.synchronize()
     assert rel_err(host(O), oracle_fwd(x, want=())["O"]) <= TOL["f32"]
+
+
+def test_bf16_path_on_a_side_stream_twice():
+    """The bf16 path forks part of its work to a library-owned stream and joins it back: the result
+    must be complete when the caller's stream is, call after call."""
+    x = make_fwd_inputs(1, 3, 1024, 128, "bf16", 0.08, seed=16)
+    g = to_dev(x, "bf16")
+    ref = oracle_fwd(x, want=())["O"]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        O1 = nats.hybrid_attn_fwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64)
+        O2 = nats.hybrid_attn_fwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64)
+    s.synchronize()
+    assert rel_err(host(O1), ref, stored="bf16") <= TOL["bf16"]
+    assert torch.equal(O1, O2)
+
+
+def test_forward_in_a_hip_graph_replays():
+    """Capture one forward (caller-provided output and workspace, nothing allocated inside) into a
+    graph; every replay, with eager work and synchronisation in between and new inputs written in
+    place, must reproduce the eager result of the same inputs bit for bit."""
+    from paper_2602_03681_amd import binding as nb
+    B, H, L, d = 1, 2, 512, 128
+    xs = [make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=30 + i) for i in range(3)]
+    gs = [to_dev(x, "bf16") for x in xs]
+    cur = {k: v.clone() for k, v in gs[0].items()}
+    params = nb.make_fwd_params(B, H, L, d, 64, nb.NATS_BF16)
+    ws = torch.empty(nb.fwd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    O = torch.empty_like(cur["Q"])
+
+    def run():
+        nats.hybrid_attn_fwd(cur["Q"], cur["K"], cur["V"], cur["alpha"], cur["beta"], cur["mask"], 64,
+                             out=O, workspace=ws)
+
+    eager = []
+    for g in gs:                       # eager results (also creates the library's stream and events)
+        for k in cur:
+            cur[k].copy_(g[k])
+        run()
+        torch.cuda.synchronize()
+        eager.append(O.clone())
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(graph, stream=s):
+            run()
+    torch.cuda.synchronize()
+    for i in (1, 2, 0, 1):
+        for k in cur:
+            cur[k].copy_(gs[i][k])
+        O.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, eager[i]), f"replay with input set {i} differs from the eager result"
+    assert rel_err(host(eager[0]), oracle_fwd(xs[0], want=())["O"], stored="bf16") <= TOL["bf16"]
