@@ -9,9 +9,15 @@
  *
  * Conventions common to every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates nothing, frees nothing and never synchronises: all work is
- *     enqueued on the given HIP stream (a hipStream_t passed as void*, NULL =
- *     the default stream) and the call returns immediately.
+ *     allocates no memory, frees nothing and never synchronises the host: all
+ *     work is ordered after what the given HIP stream (a hipStream_t passed as
+ *     void*, NULL = the default stream) held at the call, is complete when that
+ *     stream reaches the end of what the call enqueued, and the call returns
+ *     immediately.  The forward may run part of its kernels on a second stream
+ *     that the library creates once per device (forked from and joined back
+ *     into the given stream with events; legal under stream capture, but the
+ *     first call on a device must not be made while capturing if the overlap
+ *     is wanted).  Two calls that overlap in time need different workspaces.
  *   - Arguments are validated on the host before anything is launched; a bad
  *     argument returns a negative nats_status and launches nothing.
  *     nats_last_error() then describes the problem (thread-local string).
