@@ -35,8 +35,11 @@ def kernel_work(name, cfg, sum_cnt):
         return "alu_f32", n_tok * d * (7 * d)
     if name == "softmax_fp32":      # QK^T and PV: 4 d FLOP per visible (query, key) pair (fp32 VALU)
         return "alu_f32", 4 * d * sum_cnt
-    if name == "gdn_chunk_prep":    # KK^T, QK^T, T.K, T.V: 4 x 2 C d FLOP per token + solve
-        return "mfma_bf16", n_tok * (8 * cfg.C * d + cfg.C * cfg.C // 3)
+    if name == "gdn_chunk_prep":
+        # HBM-bound in practice (its 4 products are 66 kFLOP per token against 1.9 kB moved per token).
+        # Algorithmic bytes: K, Q, V, alpha, beta, mask in; W, U~ (fp16) and P (C fp16 per token) out.
+        # The re-laid-out copies of Q and K it also writes are this design's choice and are not counted.
+        return "hbm", n_tok * (3 * d * esz + 9 + 2 * d * 2 + cfg.C * 2)
     if name == "gdn_chunk_scan":    # W S^T, Q S^T, U^T K: 3 x 2 d^2, and P U: 2 C d, per token
         return "mfma_bf16", n_tok * (6 * d * d + 2 * cfg.C * d)
     if name == "flash_softmax":
@@ -231,6 +234,20 @@ def main():
                         "frac": round(achieved / peak, 5), "traffic": measured_traffic_bytes(dom),
                         "avg_kernel_ms": round(kernels[dom]["avg_ms"], 4)}
 
+    # every kernel of the step against its own bound (kernels that ran side by side on two streams
+    # shared the chip while their events were open)
+    kernel_rooflines = {}
+    for name, k in kernels.items():
+        work = kernel_work(name, cfg, sum_cnt)
+        if work is None:
+            continue
+        bound, amount = work
+        amount = amount * args.steps / max(k["launches"], 1)
+        peak, unit = PEAK[bound]
+        ach = amount / (k["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        kernel_rooflines[name] = {"bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
+                                  "achieved": round(ach, 2), "unit": unit, "frac": round(ach / peak, 4)}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import c_oracle
@@ -257,7 +274,7 @@ def main():
                       "parallelism": "single GPU"},
            "kernels_ms": {k: round(v["total_ms"] / args.steps, 4) for k, v in kernels.items()},
            "kernel_launches_per_step": {k: v["launches"] // args.steps for k, v in kernels.items()},
-           "roofline": roofline, "cpu_baseline": cpu_baseline}
+           "roofline": roofline, "kernel_rooflines": kernel_rooflines, "cpu_baseline": cpu_baseline}
     if measured_peaks is not None:
         out["measured_peaks"] = measured_peaks
     if graph_ms is not None:

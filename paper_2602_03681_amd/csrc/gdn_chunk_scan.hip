@@ -37,9 +37,6 @@ constexpr int CS = 64;                // chunk size
 #ifndef PF_HELPER_AHEAD
 #define PF_HELPER_AHEAD 12
 #endif
-#ifndef NATS_STORE_FENCED
-#define NATS_STORE_FENCED 0
-#endif
 constexpr int PF_HELPER_FIRST = 4;    // first chunk a prefetch helper touches (earlier ones are already in flight)
 
 template <int D, int BV>
@@ -403,6 +400,12 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 __builtin_amdgcn_sched_barrier(0);
 #endif
             };
+            // rows of the previous chunk first: the chain group's reads of the state copy get the LDS
+            // to themselves for a few hundred cycles
+            if (c > 0) {
+                store_rows(c - 1, nxt);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // phase 1: Qg S0^T for this wavefront's 16 tokens
             half8 fs[KS_D][NT];
 #pragma unroll
@@ -417,16 +420,6 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     accO[nt] = mfma16(cur.q[ks], fs[ks][nt], accO[nt]);
-                    if (ks == 0 && nt == NT - 1 && c > 0) {
-                        // rows of the previous chunk; nxt still holds that chunk's softmax-branch piece
-#if NATS_STORE_FENCED
-                        __builtin_amdgcn_sched_barrier(0);
-#endif
-                        store_rows(c - 1, nxt);
-#if NATS_STORE_FENCED
-                        __builtin_amdgcn_sched_barrier(0);
-#endif
-                    }
                     if (ks > 0 || nt == NT - 1) one_load();
                 }
             while (piece < OS_t::N_PIECES) one_load();
