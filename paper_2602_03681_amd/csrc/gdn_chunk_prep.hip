@@ -64,7 +64,7 @@ struct PrepLds {
     static constexpr int o_as = o_kst + D * TS * 2;
     static constexpr int o_xs = o_as + CH * AS_STRIDE * 4;
     static constexpr int o_gate = o_xs + 4 * 256 * 4;
-    static constexpr int bytes = o_gate + 4 * CH * 4;
+    static constexpr int bytes = o_gate + 4 * CH * 4 + 2 * CH * 2;
     static_assert(CH * AS_STRIDE * 4 <= tp_off, "T and T' overlap");
     static_assert(D * TS * 2 <= tp_off, "V^T and T' overlap");
 };
@@ -99,6 +99,8 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     float* s_gam = s_g2 + CH;
     float* s_bp = s_gam + CH;
     float* s_gdec = s_bp + CH;
+    half_t* s_gdec_h = reinterpret_cast<half_t*>(s_gdec + CH);   // fp16 copies of gam_C / gam and gam
+    half_t* s_gam_h = s_gdec_h + CH;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
@@ -133,6 +135,8 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
         s_g2[lane] = g;
         s_gam[lane] = __builtin_amdgcn_exp2f(g);
         s_gdec[lane] = __builtin_amdgcn_exp2f(gC - g);
+        s_gdec_h[lane] = (half_t)s_gdec[lane];
+        s_gam_h[lane] = (half_t)s_gam[lane];
         s_bp[lane] = mask[tok0 + lane] ? 0.f : beta[tok0 + lane];
     }
     // K row-major + transposed (swizzled), Q row-major; V stays in registers for now
@@ -157,24 +161,36 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
         constexpr uint64_t JB = 0x3323213210210100ull;
         half_t* Pc = PF + gc * (CH * CH);
         // P[r = 16a + l16][i = 16b + 4 lq + j] -> PF[w = a][ks = lq / 2][lane = 16 b + l16][4 (lq % 2) + j]
-        for (int job = wave; job < 16; job += 4) {
-            const int a = (int)((JA >> (4 * job)) & 15), b = (int)((JB >> (4 * job)) & 15);
-            half_t* dst = Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1);
-            if (a < b) {  // upper tile: zeros
-                half4 z = {0, 0, 0, 0};
-                *reinterpret_cast<half4*>(dst) = z;
-                continue;
-            }
-            f32x4 accK = {0.f, 0.f, 0.f, 0.f}, accP = {0.f, 0.f, 0.f, 0.f};
+        // A wavefront's product jobs (job = wave, wave + 4, wave + 8 < 10) run as one straight-line
+        // sequence with separate accumulators, so that the LDS reads and MFMA chains of one job fill
+        // the latencies of the others; the third slot of wavefronts 2 and 3 repeats job 0 and is not stored.
+        constexpr int NJ = 3;
+        int ja[NJ], jb[NJ];
+        f32x4 accK[NJ], accP[NJ];
 #pragma unroll
-            for (int ks = 0; ks < D / 32; ++ks) {
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int job = (wave + 4 * jj < 10) ? wave + 4 * jj : 0;
+            ja[jj] = (int)((JA >> (4 * job)) & 15);
+            jb[jj] = (int)((JB >> (4 * job)) & 15);
+            accK[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+            accP[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks)
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj) {
                 const int ko = 32 * ks + 8 * lq;
-                const half8 fa = lds_read8(Ks + (16 * a + l16) * RS + ko);
-                const half8 fb = lds_read8(Ks + (16 * b + l16) * RS + ko);
-                const half8 fq = lds_read8(Qs + (16 * a + l16) * RS + ko);
-                accK = mfma16(fa, fb, accK);  // rows: tokens of block a, cols: tokens of block b
-                accP = mfma16(fb, fq, accP);  // rows: key tokens i of block b, cols: query tokens r of block a
+                const half8 fa = lds_read8(Ks + (16 * ja[jj] + l16) * RS + ko);
+                const half8 fb = lds_read8(Ks + (16 * jb[jj] + l16) * RS + ko);
+                const half8 fq = lds_read8(Qs + (16 * ja[jj] + l16) * RS + ko);
+                accK[jj] = mfma16(fa, fb, accK[jj]);  // rows: tokens of block a, cols: tokens of block b
+                accP[jj] = mfma16(fb, fq, accP[jj]);  // rows: key tokens i of block b, cols: query tokens r of block a
             }
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            if (wave + 4 * jj >= 10) continue;   // uniform per wavefront
+            const int a = ja[jj], b = jb[jj];
+            half_t* dst = Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1);
             {   // A[r][i], r = 16a + 4 lq + j, i = 16b + l16
                 const int i = 16 * b + l16;
                 const float gi = s_g2[i];
@@ -182,7 +198,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * a + 4 * lq + j;
                     As[r * AS_STRIDE + i] =
-                        (i < r) ? s_bp[r] * accK[j] * __builtin_amdgcn_exp2f(s_g2[r] - gi) : 0.f;
+                        (i < r) ? s_bp[r] * accK[jj][j] * __builtin_amdgcn_exp2f(s_g2[r] - gi) : 0.f;
                 }
             }
             {   // P[r][i], r = 16a + l16, i = 16b + 4 lq + j
@@ -192,10 +208,16 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int i = 16 * b + 4 * lq + j;
-                    pv[j] = (i <= r) ? accP[j] * __builtin_amdgcn_exp2f(gr - s_g2[i]) : 0.f;
+                    pv[j] = (i <= r) ? accP[jj][j] * __builtin_amdgcn_exp2f(gr - s_g2[i]) : 0.f;
                 }
                 *reinterpret_cast<half4*>(dst) = to_half4(pv);
             }
+        }
+        // the 6 upper tiles (jobs 10..15) of P are zeros
+        for (int job = 10 + wave; job < 16; job += 4) {
+            const int a = (int)((JA >> (4 * job)) & 15), b = (int)((JB >> (4 * job)) & 15);
+            half4 z = {0, 0, 0, 0};
+            *reinterpret_cast<half4*>(Pc + (((a * 2 + (lq >> 1)) * 64) + 16 * b + l16) * 8 + 4 * (lq & 1)) = z;
         }
     }
     __syncthreads();
@@ -205,12 +227,19 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     {
         constexpr int KS_D = D / 32;
         half8* Kd = reinterpret_cast<half8*>(KdF + gc * (size_t)(D * CH));
+        // scaling in packed fp16 (two elements per instruction): the factors gam_C / gam_r and gam_r are
+        // in (0, 1], so nothing overflows, and the second rounding costs 2^-12 relative
+        typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
         for (int e = tid; e < D * CH / 8; e += PREP_THREADS) {   // e = ((w * MS + ms) * 2 + ks) * 64 + lane
             const int ln = e & 63, ks = (e >> 6) & 1, wm = e >> 7;   // wm = w * MS + ms
             const int dk = 16 * wm + (ln & 15), t0 = 16 * (ln >> 4) + 8 * ks;
             half8 h = lds_read8(KsT + swz_t(dk, t0, TS));
+            const half8 sc = lds_read8(s_gdec_h + t0);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * s_gdec[t0 + j]);
+            for (int j = 0; j < 8; j += 2) {
+                const half2_t pr = half2_t{h[j], h[j + 1]} * half2_t{sc[j], sc[j + 1]};
+                h[j] = pr[0]; h[j + 1] = pr[1];
+            }
             Kd[e] = h;
         }
         half8* Qg = reinterpret_cast<half8*>(QF + gc * (size_t)(CH * D));
@@ -218,9 +247,12 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
             const int ln = e & 63, ks = (e >> 6) % KS_D, w = (e >> 6) / KS_D;
             const int tok = 16 * w + (ln & 15), dk = (D / 4) * (ln >> 4) + 8 * ks;
             half8 h = lds_read8(Qs + tok * RS + dk);
-            const float g = s_gam[tok];
+            const half_t g = s_gam_h[tok];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = (half_t)((float)h[j] * g);
+            for (int j = 0; j < 8; j += 2) {
+                const half2_t pr = half2_t{h[j], h[j + 1]} * half2_t{g, g};
+                h[j] = pr[0]; h[j + 1] = pr[1];
+            }
             Qg[e] = h;
         }
         if (tid == 0) gamC[gc] = s_gam[CH - 1];
