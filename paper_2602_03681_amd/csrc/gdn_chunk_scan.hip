@@ -41,11 +41,23 @@ constexpr int PF_HELPER_FIRST = 4;    // first chunk a prefetch helper touches (
 
 template <int D, int BV>
 struct ScanLds {
-    static constexpr int RS = D + LDS_PAD;   // [v][d_k] rows
-    static constexpr int TS = CS + LDS_PAD;  // [v][tok] rows
-    static constexpr int o_S = 0;                       // [BV][RS]  state copy, fp16
-    static constexpr int o_U = o_S + BV * RS;           // [BV][TS]  U^T, fp16
-    static constexpr int n_half = o_U + BV * TS;
+    // The fp16 copies of S and U are the B operands of every product here: a lane (l16, quad lq) reads 16
+    // bytes of row l16 at a column that depends on lq.  On gfx950 such reads run at the full LDS rate
+    // (about 200 B/clk measured, against 128) when the four quads' addresses are equal modulo 256
+    // bytes and the 16 rows of a quad fall on 16 different 16-byte slots modulo 256.  So each copy
+    // is stored as four planes, one per quad (d_k / (D/4) for S, tok / 16 for U), whose size is a
+    // multiple of 256 bytes and whose rows are an odd number of 16-byte slots long.
+    static constexpr int SP = D / 4 + LDS_PAD;          // halves per row of a state plane  [BV][SP]
+    static constexpr int UP = 16 + LDS_PAD;             // halves per row of a U plane      [BV][UP]
+    static constexpr int S_PLANE = BV * SP, U_PLANE = BV * UP;
+    static_assert((S_PLANE * 2) % 256 == 0 && (U_PLANE * 2) % 256 == 0, "planes must be 256-byte multiples");
+    static_assert(((SP * 2 / 16) & 1) == 1 && ((UP * 2 / 16) & 1) == 1, "rows must be an odd number of 16-byte slots");
+    static constexpr int o_S = 0;                       // state copy, fp16
+    static constexpr int o_U = o_S + 4 * S_PLANE;       // U^T, fp16
+    static constexpr int n_half = o_U + 4 * U_PLANE;
+    // element (row v, d_k) of the state copy / (row v, token) of the U copy, in halves from the copy's base
+    __device__ static __forceinline__ int s_at(int v, int dk) { return (dk / (D / 4)) * S_PLANE + v * SP + dk % (D / 4); }
+    __device__ static __forceinline__ int u_at(int v, int tok) { return (tok / 16) * U_PLANE + v * UP + tok % 16; }
     static constexpr int OSTR = BV + 4;                 // fp32 row stride of the output staging tiles
     static constexpr int n_ost = 4 * 16 * OSTR;         // [4 wavefronts][16 tok][OSTR]
 };
@@ -134,7 +146,6 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     float* __restrict__ O_la_f32, const half_t* __restrict__ O_nla_h, bf16_t* __restrict__ O,
     int32_t* __restrict__ progress, int n_compute, int L, int BH, float la_scale) {
     using Lds = ScanLds<D, BV>;
-    constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NT = BV / 16;       // 16-wide tiles along the d_v slice
     constexpr int MS = D / 64;        // 16-row d_k tiles of S^T owned by one wavefront
     constexpr int KS_D = D / 32;      // contraction steps over d_k
@@ -224,7 +235,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 } else {
                     accS[ms][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
-                *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + dk) = to_half4(accS[ms][nt]);
+                *reinterpret_cast<half4*>(Ss + Lds::s_at(16 * nt + l16, dk)) = to_half4(accS[ms][nt]);
             }
         ChainStage<D, BV> stA, stB, stC, stD;
         stA.load(WF, KdF, UtF, gamC, gc0, v0, w4, lane);
@@ -255,7 +266,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
+                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + Lds::s_at(16 * nt + l16, (D / 4) * lq + 8 * ks));
             f32x4 accU[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
@@ -277,7 +288,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                *reinterpret_cast<half4*>(Us + (16 * nt + l16) * TS + 16 * w4 + 4 * lq) = to_half4(accU[nt]);
+                *reinterpret_cast<half4*>(Us + Lds::u_at(16 * nt + l16, 16 * w4 + 4 * lq)) = to_half4(accU[nt]);
             while (piece < CS_t::N_P1) one_load();
             if (c == NATS_MARK_STEP) NATS_MARK(1);
             __syncthreads();   // U complete; the old state copy has been read by everyone
@@ -287,7 +298,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) fu[ks][nt] = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
+                for (int nt = 0; nt < NT; ++nt) fu[ks][nt] = lds_read8(Us + Lds::u_at(16 * nt + l16, 16 * lq + 8 * ks));
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms) {
 #pragma unroll
@@ -299,7 +310,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                     }
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    *reinterpret_cast<half4*>(Ss + (16 * nt + l16) * RS + 16 * (MS * w4 + ms) + 4 * lq) =
+                    *reinterpret_cast<half4*>(Ss + Lds::s_at(16 * nt + l16, 16 * (MS * w4 + ms) + 4 * lq)) =
                         to_half4(accS[ms][nt]);
             }
             while (piece < CS_t::N_PIECES) one_load();
@@ -411,7 +422,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS_D; ++ks)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + (16 * nt + l16) * RS + (D / 4) * lq + 8 * ks);
+                for (int nt = 0; nt < NT; ++nt) fs[ks][nt] = lds_read8(Ss + Lds::s_at(16 * nt + l16, (D / 4) * lq + 8 * ks));
             f32x4 accO[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) accO[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -429,7 +440,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    const half8 fu = lds_read8(Us + (16 * nt + l16) * TS + 16 * lq + 8 * ks);
+                    const half8 fu = lds_read8(Us + Lds::u_at(16 * nt + l16, 16 * lq + 8 * ks));
                     accO[nt] = mfma16(cur.p[ks], fu, accO[nt]);
                 }
 #pragma unroll
