@@ -30,6 +30,7 @@ def _load():
         _lib.nats_oracle_threads.restype = ctypes.c_int
         _lib.nats_oracle_fwd.restype = ctypes.c_int
         _lib.nats_oracle_decode.restype = ctypes.c_int
+        _lib.nats_oracle_fwd_chunk.restype = ctypes.c_int
     return _lib
 
 
@@ -46,8 +47,10 @@ def _f32(a):
 
 
 def fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0, w_nla=None, w_la=None,
-        eps=1e-6, S0=None, want=("O", "O_la", "O_nla", "lse", "S", "cnt", "idx", "n_s")):
-    """Inputs [B,H,L,d] / [B,H,L]; returns a dict of fp64 / int32 arrays shaped like the inputs."""
+        eps=1e-6, S0=None, chunk_routing=0, want=("O", "O_la", "O_nla", "lse", "S", "cnt", "idx", "n_s")):
+    """Inputs [B,H,L,d] / [B,H,L]; returns a dict of fp64 / int32 arrays shaped like the inputs.
+
+    chunk_routing = C > 0: mask is [B,H,L/C], one routing decision per chunk (nats_oracle_fwd_chunk)."""
     Q, K, V, alpha, beta = (_f32(a) for a in (Q, K, V, alpha, beta))
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     B, H, L, d = Q.shape
@@ -63,7 +66,14 @@ def fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0, w_
     if "cnt" in want: out["cnt"] = np.empty((B, H, L), dtype=np.int32)
     if "idx" in want: out["idx"] = np.full((B, H, L), -1, dtype=np.int32)
     if "n_s" in want: out["n_s"] = np.empty((B, H), dtype=np.int32)
-    rc = _load().nats_oracle_fwd(
+    lib = _load()
+    if chunk_routing:
+        assert mask.shape == (B, H, L // chunk_routing)
+        call = lambda *a: lib.nats_oracle_fwd_chunk(a[0], a[1], a[2], ctypes.c_int(chunk_routing), *a[3:])
+    else:
+        assert mask.shape == (B, H, L)
+        call = lib.nats_oracle_fwd
+    rc = call(
         ctypes.c_int(BH), ctypes.c_int(L), ctypes.c_int(d), _p(Q), _p(K), _p(V), _p(alpha), _p(beta),
         _p(mask), ctypes.c_double(scale), ctypes.c_double(la_scale), ctypes.c_int(mode), _p(w_nla),
         _p(w_la), ctypes.c_double(eps), _p(S0), _p(out["O"]), _p(out.get("O_la")), _p(out.get("O_nla")),

@@ -24,7 +24,10 @@ lse = -inf; RMSNorm has no gain and Norm(0) = 0.
 
 Parity pins: every function below is pinned by tests/test_oracle_pins.py
 (library softmax attention, closed forms of the delta rule, explicit
-transition-matrix products, Fig. 1c's support pattern, brute force).
+transition-matrix products, Fig. 1c's support pattern, brute force); the
+chunk-routed form at the end of the file by tests/test_oracle_chunk_routing.py
+(library attention with explicit masks, and its composition from the pinned
+per-token functions).
 """
 from __future__ import annotations
 
@@ -230,3 +233,81 @@ def gdn_chunkwise(q, k, v, alpha, beta, mask, C, S0=None, la_scale=1.0):
         o[sl] = la_scale * (np.exp(g)[:, None] * (Qc @ S.T) + ((Qc @ Kc.T) * D) @ U)
         S = np.exp(g[-1]) * S + U.T @ (np.exp(g[-1] - g)[:, None] * Kc)
     return o, S
+
+
+# --------------------------------------------------------------------------- #
+# chunk-level routing (Section 4.1 as the paper states it: the type is chosen per
+# chunk, after the whole chunk has been seen)
+# --------------------------------------------------------------------------- #
+def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
+                             w_nla=None, w_la=None, eps=1e-6, S0=None):
+    """One (batch, head) with one routing decision per chunk of C tokens (mask_c[c] = 1: softmax chunk).
+
+    Section 4.1: a chunk's type is known only once the whole chunk has been seen, so both
+    operations compute the intra-chunk part of every chunk, and afterwards the state of the
+    operation that was not chosen is rolled back (per-token generation paragraph):
+      * linear branch  -- inside every chunk the Gated DeltaNet recurrence (Eq. 19) runs on all of
+        its tokens, starting from the state at the chunk's start; after a linear chunk the state is
+        kept (Eq. 14), after a softmax chunk it is reset to the chunk-start state times the chunk's
+        decay (the writes are dropped, the decay of Eq. 20 stays);
+      * softmax branch -- query t attends to every token of earlier softmax chunks (column mask of
+        Eq. 12 at chunk granularity) and, causally, to the tokens j <= t of its own chunk whatever
+        its type.
+    cnt / idx / n_s describe the compaction of the tokens of softmax chunks.
+    """
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    alpha = np.asarray(alpha, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    mask_c = np.asarray(mask_c).reshape(-1) != 0
+    L, d_k = k.shape
+    d_v = v.shape[1]
+    assert L % C == 0 and mask_c.shape[0] == L // C
+    scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
+    S = np.zeros((d_v, d_k)) if S0 is None else np.array(S0, dtype=np.float64)
+    o_la = np.zeros((L, d_v))
+    o_nla = np.zeros((L, d_v))
+    lse = np.full(L, -np.inf)
+    earlier = []                                   # tokens of earlier softmax chunks
+    for c in range(L // C):
+        S_start, decay = S.copy(), 1.0
+        for t in range(c * C, (c + 1) * C):
+            S = alpha[t] * S
+            decay *= alpha[t]
+            S = S + beta[t] * np.outer(v[t] - S @ k[t], k[t])        # Eq. 19, every token of the chunk
+            o_la[t] = la_scale * (S @ q[t])
+            J = np.asarray(earlier + list(range(c * C, t + 1)), dtype=np.int64)
+            s = scale * (k[J] @ q[t])
+            smax = s.max()
+            e = np.exp(s - smax)
+            z = e.sum()
+            o_nla[t] = (e / z) @ v[J]
+            lse[t] = smax + np.log(z)
+        if mask_c[c]:
+            S = decay * S_start                    # softmax chunk: its writes are rolled back
+            earlier += list(range(c * C, (c + 1) * C))
+    o = combine(o_la, o_nla, mode, w_nla, w_la, eps)
+    cnt, idx, n_s = compaction(np.repeat(mask_c, C))
+    return {"O": o, "O_la": o_la, "O_nla": o_nla, "lse": lse, "S": S, "cnt": cnt, "idx": idx, "n_s": n_s}
+
+
+def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
+                            w_nla=None, w_la=None, eps=1e-6, S0=None):
+    """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; same result layout as hybrid_fwd."""
+    B, H, L, _ = np.asarray(Q).shape
+    d_v = np.asarray(V).shape[-1]
+    out = {"O": np.zeros((B, H, L, d_v)), "O_la": np.zeros((B, H, L, d_v)),
+           "O_nla": np.zeros((B, H, L, d_v)), "lse": np.zeros((B, H, L)),
+           "S": np.zeros((B, H, d_v, np.asarray(K).shape[-1])),
+           "cnt": np.zeros((B, H, L), dtype=np.int32), "n_s": np.zeros((B, H), dtype=np.int32),
+           "idx": [[None] * H for _ in range(B)]}
+    for b in range(B):
+        for h in range(H):
+            r = hybrid_head_chunk_routed(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask_c[b, h], C,
+                                         softmax_scale, la_scale, mode,
+                                         None if w_nla is None else w_nla[b, h],
+                                         None if w_la is None else w_la[b, h], eps,
+                                         None if S0 is None else S0[b, h])
+            for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
+                out[key][b, h] = r[key]
+            out["idx"][b][h] = r["idx"]
+    return out

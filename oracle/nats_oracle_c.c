@@ -220,3 +220,116 @@ int nats_oracle_decode(int BH, int d, int cap, double *state, float *k_cache, fl
     }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------
+ * Chunk-level routing (Section 4.1 as stated: one decision per chunk of C tokens,
+ * taken after the chunk has been seen).  Both operations compute the intra-chunk part
+ * of every chunk; afterwards the operation that was not chosen is rolled back:
+ *   linear branch : Eq. 19 on every token of the chunk from the chunk-start state; after a
+ *                   softmax chunk the state is reset to (chunk decay) x (chunk-start state)
+ *                   (writes dropped, Eq. 14; decay kept, Eq. 20)
+ *   softmax branch: keys = tokens of earlier softmax chunks (Eq. 12 per chunk) plus the
+ *                   tokens j <= t of the query's own chunk
+ * mask_c is [BH, L/C]; everything else as in nats_oracle_fwd (cnt, idx, n_s: compaction of
+ * the tokens of softmax chunks). */
+static void head_forward_chunk(int L, int d, int C, const float *q, const float *k, const float *v,
+                               const float *alpha, const float *beta, const uint8_t *mask_c,
+                               double scale, double la_scale, int mode, const float *w_nla,
+                               const float *w_la, double eps, double *S, double *O, double *O_la,
+                               double *O_nla, double *lse, int32_t *cnt, int32_t *idx, int32_t *n_s_out) {
+    double *pred = (double *)malloc(sizeof(double) * d);
+    double *ola = (double *)malloc(sizeof(double) * d);
+    double *onla = (double *)malloc(sizeof(double) * d);
+    double *score = (double *)malloc(sizeof(double) * (L > 0 ? L : 1));
+    int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (L > 0 ? L : 1));   /* visible key positions */
+    double *S_start = (double *)malloc(sizeof(double) * d * d);
+    int n_s = 0;                                   /* tokens of earlier softmax chunks */
+    for (int c0 = 0; c0 < L; c0 += C) {
+        const int soft = mask_c[c0 / C] != 0;
+        memcpy(S_start, S, sizeof(double) * d * d);
+        double decay = 1.0;
+        for (int t = c0; t < c0 + C; ++t) {
+            const float *qt = q + (size_t)t * d, *kt = k + (size_t)t * d, *vt = v + (size_t)t * d;
+            double a = alpha[t], b = beta[t];
+            decay *= a;
+            for (int i = 0; i < d * d; ++i) S[i] *= a;
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int j = 0; j < d; ++j) acc += S[r * d + j] * (double)kt[j];
+                pred[r] = acc;
+            }
+            for (int r = 0; r < d; ++r) {                           /* Eq. 19, every token of the chunk */
+                double delta = b * ((double)vt[r] - pred[r]);
+                for (int j = 0; j < d; ++j) S[r * d + j] += delta * (double)kt[j];
+            }
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int j = 0; j < d; ++j) acc += S[r * d + j] * (double)qt[j];
+                ola[r] = la_scale * acc;
+            }
+            /* visible keys: pos[0..n_s) from earlier softmax chunks, then c0..t of the own chunk */
+            const int n_vis = n_s + (t - c0 + 1);
+            double smax = -INFINITY, z = 0.0;
+            for (int cc = 0; cc < n_vis; ++cc) {
+                const int j = cc < n_s ? pos[cc] : c0 + (cc - n_s);
+                const float *kj = k + (size_t)j * d;
+                double acc = 0.0;
+                for (int i = 0; i < d; ++i) acc += (double)qt[i] * (double)kj[i];
+                score[cc] = scale * acc;
+                if (score[cc] > smax) smax = score[cc];
+            }
+            for (int cc = 0; cc < n_vis; ++cc) { score[cc] = exp(score[cc] - smax); z += score[cc]; }
+            for (int r = 0; r < d; ++r) onla[r] = 0.0;
+            for (int cc = 0; cc < n_vis; ++cc) {
+                const int j = cc < n_s ? pos[cc] : c0 + (cc - n_s);
+                const float *vj = v + (size_t)j * d;
+                double p = score[cc] / z;
+                for (int r = 0; r < d; ++r) onla[r] += p * (double)vj[r];
+            }
+            double *o = O + (size_t)t * d;
+            if (mode == 0) {
+                for (int r = 0; r < d; ++r) o[r] = ola[r] + onla[r];
+            } else {
+                double ms_la = 0.0, ms_nla = 0.0;
+                for (int r = 0; r < d; ++r) { ms_la += ola[r] * ola[r]; ms_nla += onla[r] * onla[r]; }
+                double inv_la = 1.0 / sqrt(ms_la / d + eps), inv_nla = 1.0 / sqrt(ms_nla / d + eps);
+                double wn = w_nla ? (double)w_nla[t] : 0.5, wl = w_la ? (double)w_la[t] : 0.5;
+                for (int r = 0; r < d; ++r) o[r] = wn * onla[r] * inv_nla + wl * ola[r] * inv_la;
+            }
+            if (O_la) memcpy(O_la + (size_t)t * d, ola, sizeof(double) * d);
+            if (O_nla) memcpy(O_nla + (size_t)t * d, onla, sizeof(double) * d);
+            if (lse) lse[t] = smax + log(z);
+            if (cnt) cnt[t] = n_s + (soft ? (t - c0 + 1) : 0);
+        }
+        if (soft) {
+            for (int i = 0; i < d * d; ++i) S[i] = decay * S_start[i];   /* writes rolled back */
+            for (int t = c0; t < c0 + C; ++t) pos[n_s++] = t;
+        }
+    }
+    if (idx) for (int c = 0; c < n_s; ++c) idx[c] = pos[c];
+    if (n_s_out) *n_s_out = n_s;
+    free(pred); free(ola); free(onla); free(score); free(pos); free(S_start);
+}
+
+int nats_oracle_fwd_chunk(int BH, int L, int d, int C, const float *Q, const float *K, const float *V,
+                          const float *alpha, const float *beta, const uint8_t *mask_c, double scale,
+                          double la_scale, int mode, const float *w_nla, const float *w_la, double eps,
+                          const double *S0, double *O, double *O_la, double *O_nla, double *lse,
+                          double *S_final, int32_t *cnt, int32_t *idx, int32_t *n_s) {
+    if (!Q || !K || !V || !alpha || !beta || !mask_c || !O || BH < 0 || L < 0 || d <= 0 || C <= 0 || L % C) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < BH; ++u) {
+        size_t ld = (size_t)L * d, off = (size_t)u * ld, offl = (size_t)u * L;
+        double *S = (double *)malloc(sizeof(double) * d * d);
+        if (S0) memcpy(S, S0 + (size_t)u * d * d, sizeof(double) * d * d);
+        else memset(S, 0, sizeof(double) * d * d);
+        head_forward_chunk(L, d, C, Q + off, K + off, V + off, alpha + offl, beta + offl,
+                           mask_c + (size_t)u * (L / C), scale, la_scale, mode, w_nla ? w_nla + offl : NULL,
+                           w_la ? w_la + offl : NULL, eps, S, O + off, O_la ? O_la + off : NULL,
+                           O_nla ? O_nla + off : NULL, lse ? lse + offl : NULL, cnt ? cnt + offl : NULL,
+                           idx ? idx + offl : NULL, n_s ? n_s + u : NULL);
+        if (S_final) memcpy(S_final + (size_t)u * d * d, S, sizeof(double) * d * d);
+        free(S);
+    }
+    return 0;
+}

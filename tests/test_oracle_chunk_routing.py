@@ -1,0 +1,119 @@
+"""Pins for the chunk-routed form of the oracle (Section 4.1: one routing decision per chunk,
+both operations compute the intra-chunk part, the unchosen one is rolled back).
+
+It is pinned to things other than itself:
+  * a library attention routine with explicit boolean masks (softmax branch);
+  * the per-token functions of the oracle, which have their own pins in test_oracle_pins.py:
+    the outputs of chunk c equal those of a per-token run over tokens 0 .. end of chunk c in which
+    the tokens of earlier softmax chunks are softmax tokens and the tokens of chunk c itself are
+    linear tokens (linear branch), respectively softmax tokens (softmax branch);
+  * special cases: all chunks linear (plain Gated DeltaNet + block-diagonal causal attention), all
+    chunks softmax (full causal attention + per-chunk DeltaNet from a decayed-away state).
+"""
+import numpy as np
+import pytest
+import torch
+
+from nats_inputs import make_fwd_inputs
+from oracle import c_oracle, nats_oracle as no
+
+
+def _inputs(L, d, seed, C, p=0.4):
+    x = make_fwd_inputs(1, 1, L, d, "f32", 0.1, seed=seed)
+    rng = np.random.default_rng(seed + 1000)
+    mc = (rng.random(L // C) < p).astype(np.uint8)
+    return {k: v[0, 0].astype(np.float64) for k, v in x.items() if k != "mask"}, mc
+
+
+def _sdpa(q, k, v, allowed, scale):
+    out = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None, None], torch.from_numpy(k)[None, None], torch.from_numpy(v)[None, None],
+        attn_mask=torch.from_numpy(allowed)[None, None], scale=scale)
+    return out[0, 0].numpy()
+
+
+@pytest.mark.parametrize("C", [4, 16])
+def test_softmax_branch_equals_library_attention_with_the_chunk_mask(C):
+    L, d = 64, 8
+    x, mc = _inputs(L, d, 3, C)
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, softmax_scale=0.7)
+    i, j = np.arange(L)[:, None], np.arange(L)[None, :]
+    allowed = ((mc[j // C] != 0) & (j // C < i // C)) | ((j // C == i // C) & (j <= i))
+    np.testing.assert_allclose(r["O_nla"], _sdpa(x["Q"], x["K"], x["V"], allowed, 0.7), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("C", [4, 16])
+def test_chunk_outputs_equal_per_token_runs_with_the_own_chunk_retyped(C):
+    L, d = 48, 8
+    x, mc = _inputs(L, d, 5, C)
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, softmax_scale=1.3,
+                                    la_scale=0.5)
+    tok = np.repeat(mc, C)
+    for c in range(L // C):
+        end = (c + 1) * C
+        m_lin = tok[:end].copy(); m_lin[c * C:] = 0      # own chunk written into the state
+        m_sm = tok[:end].copy(); m_sm[c * C:] = 1        # own chunk visible to the softmax branch
+        o_la, _ = no.gdn_recurrent(x["Q"][:end], x["K"][:end], x["V"][:end], x["alpha"][:end], x["beta"][:end],
+                                   m_lin, la_scale=0.5)
+        o_nla, lse = no.softmax_branch(x["Q"][:end], x["K"][:end], x["V"][:end], m_sm, 1.3)
+        np.testing.assert_allclose(r["O_la"][c * C:end], o_la[c * C:], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(r["O_nla"][c * C:end], o_nla[c * C:], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(r["lse"][c * C:end], lse[c * C:], rtol=0, atol=1e-12)
+    # the carried state is the per-token state with the chunk mask expanded to tokens
+    _, S = no.gdn_recurrent(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], tok)
+    np.testing.assert_allclose(r["S"], S, rtol=0, atol=1e-12)
+    cnt, idx, n_s = no.compaction(tok)
+    assert np.array_equal(r["cnt"], cnt) and np.array_equal(r["idx"], idx) and r["n_s"] == n_s
+
+
+def test_all_linear_chunks_is_plain_deltanet_plus_block_diagonal_attention():
+    L, d, C = 32, 8, 8
+    x, _ = _inputs(L, d, 7, C)
+    mc = np.zeros(L // C, dtype=np.uint8)
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C)
+    o_la, S = no.gdn_recurrent(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], np.zeros(L, dtype=np.uint8))
+    np.testing.assert_allclose(r["O_la"], o_la, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r["S"], S, rtol=0, atol=1e-12)
+    i, j = np.arange(L)[:, None], np.arange(L)[None, :]
+    allowed = (j // C == i // C) & (j <= i)
+    np.testing.assert_allclose(r["O_nla"], _sdpa(x["Q"], x["K"], x["V"], allowed, 1.0 / np.sqrt(d)), rtol=0, atol=1e-12)
+    assert r["n_s"] == 0
+
+
+def test_all_softmax_chunks_is_full_causal_attention_plus_per_chunk_deltanet():
+    L, d, C = 32, 8, 8
+    x, _ = _inputs(L, d, 9, C)
+    mc = np.ones(L // C, dtype=np.uint8)
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C)
+    out = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(x["Q"])[None, None], torch.from_numpy(x["K"])[None, None],
+        torch.from_numpy(x["V"])[None, None], is_causal=True)[0, 0].numpy()
+    np.testing.assert_allclose(r["O_nla"], out, rtol=0, atol=1e-12)
+    for c in range(L // C):     # every chunk starts from a state that holds no write
+        sl = slice(c * C, (c + 1) * C)
+        o_la, _ = no.gdn_recurrent(x["Q"][sl], x["K"][sl], x["V"][sl], x["alpha"][sl], x["beta"][sl],
+                                   np.zeros(C, dtype=np.uint8))
+        np.testing.assert_allclose(r["O_la"][sl], o_la, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r["S"], 0.0, atol=0)
+    assert r["n_s"] == L
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_c_oracle_matches_numpy_oracle_chunk_routed(mode):
+    B, H, L, d, C = 2, 2, 64, 16, 16
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=11)
+    rng = np.random.default_rng(12)
+    mc = (rng.random((B, H, L // C)) < 0.4).astype(np.uint8)
+    w = rng.random((2, B, H, L)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, d, d)) * 0.1
+    a = no.hybrid_fwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, mode=mode,
+                                   w_nla=w[0], w_la=w[1], S0=S0, la_scale=0.7)
+    b = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, mode=mode, w_nla=w[0], w_la=w[1], S0=S0,
+                     la_scale=0.7, chunk_routing=C)
+    for key in ("O", "O_la", "O_nla", "lse", "S"):
+        np.testing.assert_allclose(b[key], a[key], rtol=0, atol=1e-11)
+    assert np.array_equal(a["cnt"], b["cnt"]) and np.array_equal(a["n_s"], b["n_s"])
+    for bb in range(B):
+        for h in range(H):
+            n = a["n_s"][bb, h]
+            assert np.array_equal(b["idx"][bb, h, :n], a["idx"][bb][h])
