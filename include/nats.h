@@ -60,6 +60,19 @@ typedef enum nats_math { NATS_MATH_AUTO = 0, NATS_MATH_FP32 = 1 } nats_math;
 /* ------------------------------------------------------------------------- *
  * Prefill / training forward
  * ------------------------------------------------------------------------- */
+/* Granularity of the routing decision (Section 4.1).
+ *   NATS_ROUTE_TOKEN: mask is [B,H,L], one decision per token.  A softmax token is never written into
+ *       the linear state (it only decays it) and is a key of the softmax branch; a linear token is
+ *       written into the state and is no key.
+ *   NATS_ROUTE_CHUNK: mask is [B,H,L/C], one decision per chunk of C tokens, as the paper states it:
+ *       a chunk's type is known only after the chunk has been seen, so both operations compute
+ *       the intra-chunk part of every chunk.  Linear branch: Eq. 19 runs on all tokens of a chunk from
+ *       the state at its start; after a softmax chunk the state is set back to that state times the
+ *       chunk's decay (Eq. 14, Eq. 20).  Softmax branch: a query sees the tokens of earlier softmax
+ *       chunks (Eq. 12) and, causally, the tokens of its own chunk whatever its type.  n_s, idx, cnt,
+ *       Kc, Vc then describe the tokens of softmax chunks. */
+typedef enum nats_routing { NATS_ROUTE_TOKEN = 0, NATS_ROUTE_CHUNK = 1 } nats_routing;
+
 typedef struct nats_fwd_params {
     int32_t B, H;          /* batch, heads (each (b,h) has its own mask: Section 4.3)          */
     int32_t L;             /* tokens; must be a positive multiple of C                          */
@@ -72,6 +85,7 @@ typedef struct nats_fwd_params {
                               O = w_nla * RMSNorm(O_nla) + w_la * RMSNorm(O_la), no gain        */
     float rms_eps;         /* RMSNorm epsilon for combine_mode 1; <= 0 selects 1e-6             */
     int32_t math;          /* nats_math                                                         */
+    int32_t routing;       /* nats_routing: granularity of the routing mask                     */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */
@@ -102,7 +116,8 @@ size_t nats_hybrid_attn_fwd_workspace_bytes(const nats_fwd_params* p);
  *             branch (Section 4.3); the caller does that, the library uses them as given.
  *   alpha   : in  [B,H,L] f32 decay in (0,1]           (Eq. 19)
  *   beta    : in  [B,H,L] f32 write strength in [0,1]  (Eq. 19)
- *   mask    : in  [B,H,L] u8, non-zero = softmax token (Eq. 12-13 at token granularity)
+ *   mask    : in  [B,H,L] u8 (routing = NATS_ROUTE_TOKEN) or [B,H,L/C] u8 (NATS_ROUTE_CHUNK), non-zero =
+ *             softmax token / chunk (Eq. 12-13)
  *   O       : out [B,H,L,d] dtype p->dtype
  *   workspace, workspace_bytes : device scratch of at least *_workspace_bytes(p); contents
  *             are undefined afterwards; two calls in flight must not share it.

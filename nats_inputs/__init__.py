@@ -150,6 +150,30 @@ def make_fwd_inputs(B: int, H: int, L: int, d: int, dtype: str, p_softmax: float
     return {"Q": q, "K": k, "V": v, "alpha": alpha, "beta": beta, "mask": mask}
 
 
+def make_chunk_mask(B: int, H: int, n_chunks: int, p_softmax: float, seed: int,
+                    mask_kind: str = "bernoulli") -> np.ndarray:
+    """Routing mask with one decision per chunk, [B,H,n_chunks] uint8 (1 = softmax chunk).
+
+    mask_kind: "bernoulli", "all_softmax", "all_linear", "head_skew" (even heads none, odd heads half),
+    "alternate" (every other chunk).
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    u = rng.random((B, H, n_chunks))
+    if mask_kind == "bernoulli":
+        mask = u < p_softmax
+    elif mask_kind == "all_softmax":
+        mask = np.ones((B, H, n_chunks), dtype=bool)
+    elif mask_kind == "all_linear":
+        mask = np.zeros((B, H, n_chunks), dtype=bool)
+    elif mask_kind == "head_skew":
+        mask = u < np.where(np.arange(H) % 2 == 0, 0.0, 0.5)[None, :, None]
+    elif mask_kind == "alternate":
+        mask = np.broadcast_to((np.arange(n_chunks) % 2 == 1)[None, None, :], (B, H, n_chunks))
+    else:
+        raise ValueError(f"unknown mask_kind {mask_kind!r}")
+    return np.ascontiguousarray(mask, dtype=np.uint8)
+
+
 def make_config_inputs(cfg: FwdConfig) -> Dict[str, np.ndarray]:
     return make_fwd_inputs(cfg.B, cfg.H, cfg.L, cfg.d, cfg.dtype, cfg.p_softmax, cfg.seed,
                            n_runs=cfg.n_runs, run_len=cfg.run_len)

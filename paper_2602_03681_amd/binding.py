@@ -19,6 +19,7 @@ _lib = None
 
 NATS_F32, NATS_BF16 = 0, 1
 NATS_MATH_AUTO, NATS_MATH_FP32 = 0, 1
+NATS_ROUTE_TOKEN, NATS_ROUTE_CHUNK = 0, 1
 
 
 class NatsError(RuntimeError):
@@ -31,7 +32,7 @@ class FwdParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
-                ("math", ctypes.c_int32)]
+                ("math", ctypes.c_int32), ("routing", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -121,8 +122,8 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
-                    math=NATS_MATH_AUTO) -> FwdParams:
-    return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math)
+                    math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN) -> FwdParams:
+    return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing)
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -134,7 +135,8 @@ _EX_OUTPUTS = ("final_state", "Kc", "Vc", "n_s", "idx", "cnt", "O_la", "O_nla", 
 
 def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
                        la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
-                       math: int = NATS_MATH_AUTO, w_nla=None, w_la=None, initial_state=None,
+                       math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, w_nla=None, w_la=None,
+                       initial_state=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
                        workspace=None) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
@@ -146,11 +148,12 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
         _require(t, name, (B, H, L, d), dt)
     _require(alpha, "alpha", (B, H, L), torch.float32)
     _require(beta, "beta", (B, H, L), torch.float32)
-    _require(mask, "mask", (B, H, L), torch.uint8)
+    _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
     _require(w_nla, "w_nla", (B, H, L), torch.float32)
     _require(w_la, "w_la", (B, H, L), torch.float32)
     _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
-    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math)
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
+                             routing)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
@@ -191,7 +194,8 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
 
 def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
                     la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
-                    math: int = NATS_MATH_AUTO, out=None, workspace=None) -> torch.Tensor:
+                    math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, out=None,
+                    workspace=None) -> torch.Tensor:
     """nats_hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C) -> O."""
     lib = load_library()
     B, H, L, d = Q.shape
@@ -200,8 +204,9 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
         _require(t, name, (B, H, L, d), dt)
     _require(alpha, "alpha", (B, H, L), torch.float32)
     _require(beta, "beta", (B, H, L), torch.float32)
-    _require(mask, "mask", (B, H, L), torch.uint8)
-    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math)
+    _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
+                             routing)
     if workspace is None:
         workspace = torch.empty(max(fwd_workspace_bytes(params), 16), dtype=torch.uint8, device=Q.device)
     O = torch.empty_like(Q) if out is None else out

@@ -113,6 +113,11 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         set_error("math must be NATS_MATH_AUTO or NATS_MATH_FP32 (got %d)", p->math);
         return NATS_ERR_SHAPE;
     }
+    if (p->routing != NATS_ROUTE_TOKEN && p->routing != NATS_ROUTE_CHUNK) {
+        set_error("routing must be NATS_ROUTE_TOKEN or NATS_ROUTE_CHUNK (got %d)", p->routing);
+        return NATS_ERR_SHAPE;
+    }
+    pl->routing = p->routing;
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
     pl->dtype = p->dtype;
     pl->math = p->math;
@@ -131,6 +136,10 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
     pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = pl->off_prog = 0;
+    pl->off_snap = 0;
+    if (!uses_chunk_path(*pl) && pl->routing == NATS_ROUTE_CHUNK) {   // chunk-start state of the fp32 recurrence
+        pl->off_snap = off; off = align_up(off + (size_t)pl->BH * pl->d * pl->d * 4, 256);
+    }
     if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
         pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
         pl->off_qf = off;  off = align_up(off + n_tok * pl->d * 2, 256);
@@ -154,7 +163,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 100; }
+int nats_abi_version(void) { return 101; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -297,7 +306,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         const bool merge_in_scan = pl.combine_mode == 0;
         if (merge_in_scan) {
             ProfScope ps("flash_softmax", s_nla);
-            st = launch_flash_softmax(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
+            st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
                                       s_nla);
             if (st != NATS_OK) { join(); return st; }
         }
@@ -316,16 +325,18 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         if (st != NATS_OK) return st;
         if (!merge_in_scan) {
             ProfScope ps("flash_softmax", stream);
-            st = launch_flash_softmax(pl, Q, Kc, VhT, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
+            st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
         }
     } else {
         {
             ProfScope ps("gdn_recurrent", stream);
-            st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la, stream);
+            st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la,
+                                      pl.routing == NATS_ROUTE_CHUNK ? reinterpret_cast<float*>(ws + pl.off_snap) : nullptr,
+                                      stream);
         }
         if (st != NATS_OK) return st;
         ProfScope ps("softmax_fp32", stream);
-        st = launch_softmax_fp32(pl, Q, Kc, Vc, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
+        st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
     }
     return st;
 }

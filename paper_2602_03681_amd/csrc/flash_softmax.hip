@@ -76,6 +76,7 @@ __device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned
 template <int D, bool MERGE>
 __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
+    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, int chunk_routing,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
@@ -115,19 +116,38 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     // that bounds the block, the Q tile and key tile 0 (which exists for every sequence: the
     // compacted buffers have capacity L >= 64 rows; its contents are not used if nothing is visible).
     const int q_last = min(q0 + FL_BM, L) - 1;
+    // Compacted rows visible to a query: routing per token, the first cnt[t]; routing per chunk, those of
+    // earlier chunks, i.e. cnt at the last token before the query's chunk (the chunk's own tokens come
+    // from K and V after the compacted tiles, see below).
+    auto visible_rows = [&](int t) __attribute__((always_inline)) -> int {
+        if (!chunk_routing) return cnt[tokbase + t];
+        const int cs = t & ~(FL_BN - 1);
+        return cs > 0 ? cnt[tokbase + cs - 1] : 0;
+    };
     int my_cnt[FL_NQ];
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         const int ql = (wave * FL_NQ + nq) * 16 + l16;
-        my_cnt[nq] = cnt[tokbase + min(q0 + ql, L - 1)];
+        my_cnt[nq] = visible_rows(min(q0 + ql, L - 1));
     }
-    const int n_hi = cnt[tokbase + q_last];   // cnt is non-decreasing: bound for the whole block
+    const int n_hi = visible_rows(q_last);    // non-decreasing in t: bound for the whole block
     u32x4 kreg[NKP], vreg[NKP];               // next K / V^T tile on its way from global memory to LDS
     auto load_tile = [&](int kt) __attribute__((always_inline)) {
         const u32x4* Kt = reinterpret_cast<const u32x4*>(Kc + (tokbase + (size_t)kt * FL_BN) * D);
         const u32x4* Vt = reinterpret_cast<const u32x4*>(VhT + (tokbase + (size_t)kt * FL_BN) * D);   // [D][64]
 #pragma unroll
         for (int i = 0; i < NKP; ++i) {   // both tiles are contiguous in global memory
+            kreg[i] = Kt[tid + FL_THREADS * i];
+            vreg[i] = Vt[tid + FL_THREADS * i];
+        }
+    };
+    // routing per chunk: the dc-th chunk of this block's queries, rows of K and V as they are (V row-major)
+    auto load_own_chunk = [&](int dc) __attribute__((always_inline)) {
+        const size_t t0 = tokbase + min(q0 + dc * FL_BN, L - FL_BN);
+        const u32x4* Kt = reinterpret_cast<const u32x4*>(K + t0 * D);
+        const u32x4* Vt = reinterpret_cast<const u32x4*>(V + t0 * D);
+#pragma unroll
+        for (int i = 0; i < NKP; ++i) {
             kreg[i] = Kt[tid + FL_THREADS * i];
             vreg[i] = Vt[tid + FL_THREADS * i];
         }
@@ -140,7 +160,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             const int row = e / (D / 8), c8 = e % (D / 8);
             qreg[i] = *reinterpret_cast<const u32x4*>(Q + (tokbase + min(q0 + row, L - 1)) * D + c8 * 8);
         }
-        load_tile(0);
+        if (!chunk_routing) load_tile(0);
 #pragma unroll
         for (int i = 0; i < NQP; ++i) {
             const int e = tid + FL_THREADS * i;
@@ -152,6 +172,14 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
 #else
     const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
 #endif
+    // The tiles of this block in order: n_tiles compacted ones, then (routing per chunk) the chunks the
+    // block's own queries lie in.  Tile i + 1 is loaded while tile i is used.
+    const int n_own = chunk_routing ? (min(q0 + FL_BM, L) - q0) / FL_BN : 0;
+    const int n_all = n_tiles + n_own;
+    auto load_any = [&](int i) __attribute__((always_inline)) {
+        if (i < n_tiles) load_tile(i); else load_own_chunk(i - n_tiles);
+    };
+    if (chunk_routing) load_any(0);   // which kind tile 0 is depends on the counts just read
     __syncthreads();
     u32x4 qf[FL_NQ][KS_D];
     int wave_hi = 0, wave_lo = 0x7fffffff;   // most and fewest keys visible to a query of this wavefront
@@ -182,7 +210,9 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     }
 
     NATS_MARK(1);
-    for (int kt = 0; kt < n_tiles; ++kt) {
+    for (int kt = 0; kt < n_all; ++kt) {
+        const bool own = kt >= n_tiles;      // one of the block's own chunks (uniform)
+        const int dc = kt - n_tiles;
         if (kt == NATS_MARK_TILE) NATS_MARK(10);
         __syncthreads();   // the previous tile (or the Q tile) is no longer read
         if (kt == NATS_MARK_TILE) NATS_MARK(11);
@@ -190,13 +220,37 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
         for (int i = 0; i < NKP; ++i) {   // registers -> LDS: K rows [key][d], V^T rows [d_v][key]
             const int e = tid + FL_THREADS * i;
             *reinterpret_cast<u32x4*>(Ks + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = kreg[i];
-            *reinterpret_cast<u32x4*>(Vs + (e >> 3) * TS + (e & 7) * 8) = vreg[i];
+            if (!own) {
+                *reinterpret_cast<u32x4*>(Vs + (e >> 3) * TS + (e & 7) * 8) = vreg[i];
+            } else {   // a piece of row `key` of V: transposed here, columns in the order the compaction kernel uses
+                const int key = e / (D / 8), c8 = e % (D / 8);
+                const half8 hv = bf16x8_to_half8(vreg[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) Vs[(c8 * 8 + j) * TS + vht_col(key)] = hv[j];
+            }
         }
         if (kt == NATS_MARK_TILE) NATS_MARK(12);
         __syncthreads();
         if (kt == NATS_MARK_TILE) NATS_MARK(13);
-        load_tile(kt + 1 < n_tiles ? kt + 1 : kt);   // next tile in flight during this tile's products
-        if (kt * FL_BN >= wave_hi) continue;   // nothing visible to this wavefront in this tile (uniform)
+        load_any(kt + 1 < n_all ? kt + 1 : kt);   // next tile in flight during this tile's products
+        // keys of this tile visible to each of this lane's queries (may be <= 0 or >= 64)
+        int vis[FL_NQ];
+        bool full_tile, skip;
+        if (!own) {
+#pragma unroll
+            for (int nq = 0; nq < FL_NQ; ++nq) vis[nq] = my_cnt[nq] - kt * FL_BN;
+            full_tile = (kt + 1) * FL_BN <= wave_lo;
+            skip = kt * FL_BN >= wave_hi;     // nothing visible to this wavefront in this tile (uniform)
+        } else {
+#pragma unroll
+            for (int nq = 0; nq < FL_NQ; ++nq) {   // causal inside the chunk, the token itself included
+                const int ql = (wave * FL_NQ + nq) * 16 + l16;
+                vis[nq] = (q0 + ql < L) ? ql - dc * FL_BN + 1 : 0;
+            }
+            full_tile = false;
+            skip = (wave * FL_NQ * 16) / FL_BN != dc;   // this wavefront's queries lie in another chunk (uniform)
+        }
+        if (skip) continue;
 
         // ---- S^T = K Q^T for 64 keys x 16*FL_NQ queries ------------------------------------------
         f32x4 accS[FL_NQ][4];
@@ -220,7 +274,6 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
         // every query of the wavefront; the running maximum is raised only when the tile's maximum
         // exceeds it by more than 2^8 (the weights then stay below 2^8, exact enough in fp16 and far
         // from overflow), so rescaling of the accumulators is rare and skipped by the whole wavefront.
-        const bool full_tile = (kt + 1) * FL_BN <= wave_lo;
         half8 pf[FL_NQ][2];
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
@@ -229,8 +282,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
                 for (int m = 0; m < 4; ++m)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int c = kt * FL_BN + 16 * m + 4 * lq + j;
-                        if (c >= my_cnt[nq]) accS[nq][m][j] = -INFINITY;
+                        if (16 * m + 4 * lq + j >= vis[nq]) accS[nq][m][j] = -INFINITY;
                     }
             }
             float tmax = -INFINITY;
@@ -350,26 +402,28 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
 }
 
 template <int D, bool MERGE>
-static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT, const int32_t* cnt,
+static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT, const void* K,
+                      const void* V, const int32_t* cnt,
                       const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
     dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
     hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                       (const bf16_t*)Kc, (const half_t*)VhT, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
+                       (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V,
+                       pl.routing == NATS_ROUTE_CHUNK, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
                        (half_t*)O_nla_h, O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
 }
 
 // O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
-                                 const int32_t* cnt, const void* O_la, const float* w_nla,
+                                 const void* K, const void* V, const int32_t* cnt, const void* O_la, const float* w_nla,
                                  const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
                                  hipStream_t st) {
     if (O_nla_h == nullptr) {
-        if (pl.d == 64) launch_fl<64, true>(pl, Q, Kc, VhT, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
-        else launch_fl<128, true>(pl, Q, Kc, VhT, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
+        if (pl.d == 64) launch_fl<64, true>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
+        else launch_fl<128, true>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
     } else {
-        if (pl.d == 64) launch_fl<64, false>(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
-        else launch_fl<128, false>(pl, Q, Kc, VhT, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
+        if (pl.d == 64) launch_fl<64, false>(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
+        else launch_fl<128, false>(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
     }
     return check_launch("flash_softmax");
 }

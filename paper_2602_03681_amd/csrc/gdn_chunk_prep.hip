@@ -80,7 +80,7 @@ template <int D>
 __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
-    int L, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
+    int L, int chunk_mask, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
     half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC) {
     using Lds = PrepLds<D>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
@@ -134,10 +134,14 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
         const float gC = __shfl(g, 63);
         s_g2[lane] = g;
         s_gam[lane] = __builtin_amdgcn_exp2f(g);
-        s_gdec[lane] = __builtin_amdgcn_exp2f(gC - g);
+        // Routing per token: a softmax token writes nothing (b' = 0).  Routing per chunk: every token
+        // writes inside its chunk (the intra-chunk part is computed for every chunk), and a softmax
+        // chunk hands nothing on: its Kd is zero, so the state only takes the chunk's decay.
+        const bool soft_chunk = chunk_mask && mask[gc] != 0;
+        s_gdec[lane] = soft_chunk ? 0.f : __builtin_amdgcn_exp2f(gC - g);
         s_gdec_h[lane] = (half_t)s_gdec[lane];
         s_gam_h[lane] = (half_t)s_gam[lane];
-        s_bp[lane] = mask[tok0 + lane] ? 0.f : beta[tok0 + lane];
+        s_bp[lane] = (!chunk_mask && mask[tok0 + lane]) ? 0.f : beta[tok0 + lane];
     }
     // K row-major + transposed (swizzled), Q row-major; V stays in registers for now
 #pragma unroll
@@ -391,7 +395,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
             attr_done[0][dev] = true;
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<64>::bytes, st, (const bf16_t*)Q,
-                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
@@ -402,7 +406,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
             attr_done[1][dev] = true;
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<128>::bytes, st, (const bf16_t*)Q,
-                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, (half_t*)WF, (half_t*)QF,
+                           (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
                            (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
     }
     return check_launch("gdn_chunk_prep");

@@ -19,8 +19,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
-    const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la, int L,
-    float la_scale) {
+    const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
+    float* __restrict__ snap, int L, float la_scale) {
     __shared__ __align__(16) float s_k[REC_TT][D];
     __shared__ __align__(16) float s_q[REC_TT][D];
     __shared__ float s_v[REC_TT][REC_ROWS];
@@ -43,6 +43,14 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
 #pragma unroll
         for (int c = 0; c < D; ++c) S[c] = 0.f;
     }
+
+    // Routing per chunk (snap != nullptr; mask holds one byte per chunk of 64 tokens): every token
+    // of a chunk is written (the intra-chunk part is computed for every chunk); at the end of a softmax
+    // chunk the row goes back to its value at the chunk's start, kept in snap, times the chunk's decay.
+    const bool chunk_mask = snap != nullptr;
+    float* my_snap = chunk_mask ? snap + ((size_t)bh * D + row) * D : nullptr;
+    const uint8_t* mask_c = mask + (size_t)bh * (L / 64);
+    float chunk_decay = 1.f;
 
     constexpr int EPL = Vec16<T>::N;
     for (int t0 = 0; t0 < L; t0 += REC_TT) {
@@ -67,13 +75,21 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
         }
         if (tid < REC_TT) {
             s_a[tid] = alpha[base + t0 + tid];
-            s_b[tid] = mask[base + t0 + tid] ? 0.f : beta[base + t0 + tid];  // softmax tokens never write
+            // routing per token: softmax tokens never write
+            s_b[tid] = (!chunk_mask && mask[base + t0 + tid]) ? 0.f : beta[base + t0 + tid];
         }
         __syncthreads();
 
         for (int i = 0; i < REC_TT; ++i) {
             const float a = s_a[i], b = s_b[i];
             float o = 0.f;
+            if (chunk_mask && ((t0 + i) & 63) == 0) {   // chunk start (uniform)
+#pragma unroll
+                for (int c = 0; c < D; c += 4)
+                    *reinterpret_cast<float4*>(my_snap + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+                chunk_decay = 1.f;
+            }
+            chunk_decay *= a;
             if (b != 0.f) {  // uniform across the block
                 float pred = 0.f;
 #pragma unroll
@@ -100,6 +116,14 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
                 }
             }
             O_la[(base + t0 + i) * D + row] = la_scale * o;
+            if (chunk_mask && ((t0 + i) & 63) == 63 && mask_c[(t0 + i) >> 6]) {   // end of a softmax chunk
+#pragma unroll
+                for (int c = 0; c < D; c += 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(my_snap + c);
+                    S[c] = chunk_decay * x.x; S[c + 1] = chunk_decay * x.y;
+                    S[c + 2] = chunk_decay * x.z; S[c + 3] = chunk_decay * x.w;
+                }
+            }
         }
     }
     if (S_final != nullptr) {
@@ -113,23 +137,23 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
 template <typename T>
 static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const void* V, const float* alpha,
                        const float* beta, const uint8_t* mask, const float* S0, float* S_final,
-                       float* O_la, hipStream_t st) {
+                       float* O_la, float* snap, hipStream_t st) {
     dim3 grid(pl.d / REC_ROWS, pl.BH);
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, pl.L, pl.la_scale);
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, pl.L, pl.la_scale);
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
-                                 const float* S0, float* S_final, float* O_la, hipStream_t st) {
+                                 const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st) {
     if (pl.dtype == NATS_BF16)
-        launch_rec<bf16_t>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, st);
+        launch_rec<bf16_t>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, st);
     else
-        launch_rec<float>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, st);
+        launch_rec<float>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, st);
     return check_launch("gdn_recurrent");
 }
 

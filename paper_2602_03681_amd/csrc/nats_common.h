@@ -73,6 +73,15 @@ struct Vec16<bf16_t> {
     }
 };
 
+// Column of compacted row c inside its V^T tile of 64 keys.  Within each group of 32 keys the columns
+// are stored in the order in which the softmax kernel's second MFMA consumes them: a lane quad lq holds
+// keys {4 lq + j} of the first 16-key result tile and {16 + 4 lq + j} of the second in its 8
+// contraction slots, so those 8 keys are made contiguous (one 16-byte LDS read per fragment).
+__device__ __forceinline__ int vht_col(int c) {
+    const int k32 = c & 31;
+    return (c & 32) + 8 * ((k32 & 15) >> 2) + 4 * (k32 >> 4) + (k32 & 3);
+}
+
 // number of non-zero bytes in a 32-bit word
 __device__ __forceinline__ int nonzero_bytes(uint32_t w) {
     uint32_t t = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w;
@@ -104,10 +113,11 @@ struct FwdPlan {
     int math;
     float softmax_scale, la_scale, rms_eps;
     int combine_mode;
+    int routing;   // nats_routing
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah, off_prog;
+    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah, off_prog, off_snap;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
@@ -117,7 +127,7 @@ nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const vo
                                 hipStream_t st);
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
-                                 const float* S0, float* S_final, float* O_la, hipStream_t st);
+                                 const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st);
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
@@ -126,10 +136,12 @@ nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void*
                                   float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
                                   int32_t* progress, hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
+                                const void* K, const void* V,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                 hipStream_t st);
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
+                                 const void* K, const void* V,
                                  const int32_t* cnt, const void* O_la, const float* w_nla,
                                  const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
                                  hipStream_t st);

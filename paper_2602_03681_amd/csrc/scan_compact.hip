@@ -13,15 +13,6 @@
 
 namespace nats {
 
-// Column of compacted row c inside its V^T tile of 64.  Within each group of 32 keys the columns are
-// stored in the order in which the softmax kernel's second MFMA consumes them: a lane quad lq holds
-// keys {4 lq + j} of the first 16-key result tile and {16 + 4 lq + j} of the second in its 8
-// contraction slots, so those 8 keys are made contiguous (one 16-byte LDS read per fragment).
-__device__ __forceinline__ int vht_col(int c) {
-    const int k32 = c & 31;
-    return (c & 32) + 8 * ((k32 & 15) >> 2) + 4 * (k32 >> 4) + (k32 & 3);
-}
-
 // fp16 value of one stored element (the MFMA softmax kernel's V^T operand)
 __device__ __forceinline__ half_t elem_to_half(bf16_t x) { return f32_to_half_sat(to_float(x)); }
 __device__ __forceinline__ half_t elem_to_half(float x) { return f32_to_half_sat(x); }
@@ -34,21 +25,27 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     const uint8_t* __restrict__ mask, const T* __restrict__ K, const T* __restrict__ V, int L, int d,
     int32_t* __restrict__ cnt, int32_t* __restrict__ idx, int32_t* __restrict__ n_s, T* __restrict__ Kc,
     T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user,
-    half_t* __restrict__ VhT, int32_t* __restrict__ progress) {
+    half_t* __restrict__ VhT, int32_t* __restrict__ progress, int chunk_mask) {
     __shared__ int s_wave[SCAN_THREADS / 64];
     __shared__ int s_pos[SCAN_SEG];
     const int bh = blockIdx.y;
     const int seg0 = blockIdx.x * SCAN_SEG;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint8_t* m = mask + (size_t)bh * L;
+    // chunk_mask: one mask byte per chunk of 64 tokens (routing per chunk: every token of a softmax
+    // chunk is a softmax token); otherwise one byte per token
+    const uint8_t* m = mask + (size_t)bh * (chunk_mask ? L / 64 : L);
 
     // ---- 1. softmax tokens in front of this segment -----------------------------------
     int before = 0;
     {
-        const uint4* m16 = reinterpret_cast<const uint4*>(m);  // seg0 is a multiple of 1024
-        for (int i = tid; i < seg0 / 16; i += SCAN_THREADS) {
-            uint4 w = m16[i];
-            before += nonzero_bytes(w.x) + nonzero_bytes(w.y) + nonzero_bytes(w.z) + nonzero_bytes(w.w);
+        if (chunk_mask) {   // a few hundred bytes at most, at no particular alignment
+            for (int i = tid; i < seg0 / 64; i += SCAN_THREADS) before += m[i] ? 64 : 0;
+        } else {
+            const uint4* m16 = reinterpret_cast<const uint4*>(m);  // seg0 is a multiple of 1024
+            for (int i = tid; i < seg0 / 16; i += SCAN_THREADS) {
+                uint4 w = m16[i];
+                before += nonzero_bytes(w.x) + nonzero_bytes(w.y) + nonzero_bytes(w.z) + nonzero_bytes(w.w);
+            }
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off);
@@ -61,7 +58,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     // ---- 2. scan of the segment: 4 tokens per thread ------------------------------------
     const int t0 = seg0 + tid * 4;
     uint32_t w = 0;
-    if (t0 < L) w = *reinterpret_cast<const uint32_t*>(m + t0);  // L % 4 == 0: a word is all in or all out
+    if (t0 < L)   // L % 4 == 0: a word is all in or all out; its 4 tokens lie in one chunk
+        w = chunk_mask ? (m[t0 >> 6] ? 0x01010101u : 0u) : *reinterpret_cast<const uint32_t*>(m + t0);
     const int mine = nonzero_bytes(w);
     int incl = mine;
 #pragma unroll
@@ -142,11 +140,13 @@ nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const vo
     if (pl.dtype == NATS_BF16) {
         hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
-                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT, progress);
+                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT, progress,
+                           pl.routing == NATS_ROUTE_CHUNK);
     } else {
         hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
-                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT, progress);
+                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT, progress,
+                           pl.routing == NATS_ROUTE_CHUNK);
     }
     return check_launch("scan_compact");
 }

@@ -25,7 +25,7 @@ constexpr int SM_KB = 8;        // keys per online-softmax step
 template <typename T, int D>
 __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc,
-    const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
+    const T* __restrict__ K, const T* __restrict__ V, int chunk_routing, const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, T* __restrict__ O, float* __restrict__ O_nla_out,
     float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps) {
     constexpr int DP = D / 4;       // elements of a row per lane
@@ -48,18 +48,24 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     for (int c = 0; c < DP; ++c) { q[c] *= scale; acc[c] = 0.f; }
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int my_cnt = cnt[(size_t)bh * L + t];
-    const int n_hi = cnt[(size_t)bh * L + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
+    // Routing per token: the first cnt[t] compacted rows are visible.  Routing per chunk: a block is
+    // exactly one chunk (64 queries); its queries see the compacted rows of earlier chunks, cnt at the
+    // last token before the chunk, and then, causally, the chunk's own rows of K and V.
+    const size_t tokb = (size_t)bh * L;
+    const int my_cnt = chunk_routing ? (q0 > 0 ? cnt[tokb + q0 - 1] : 0) : cnt[tokb + t];
+    const int n_hi = chunk_routing ? my_cnt : cnt[tokb + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
 
-    for (int c0 = 0; c0 < n_hi; c0 += SM_BN) {
+    // One tile of SM_BN rows of (Ks, Vs) starting at row0, the first n_rows of which exist; this
+    // query sees the first `mine` of them.
+    auto tile = [&](const T* Ks, const T* Vs, int row0, int n_rows, int mine) {
         __syncthreads();
         for (int e = tid * EPL; e < SM_BN * D; e += SM_THREADS * EPL) {
             const int i = e / D, c = e % D;
             float tk[EPL], tv[EPL];
-            if (c0 + i < n_hi) {
-                const size_t src = ((size_t)bh * L + c0 + i) * D + c;
-                Vec16<T>::load(Kc + src, tk);
-                Vec16<T>::load(Vc + src, tv);
+            if (i < n_rows) {
+                const size_t src = (tokb + row0 + i) * D + c;
+                Vec16<T>::load(Ks + src, tk);
+                Vec16<T>::load(Vs + src, tv);
             } else {
 #pragma unroll
                 for (int j = 0; j < EPL; ++j) { tk[j] = 0.f; tv[j] = 0.f; }
@@ -73,48 +79,49 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         }
         __syncthreads();
 
-        if (c0 < my_cnt) {
-            for (int kb = 0; kb < SM_BN; kb += SM_KB) {
-                if (c0 + kb >= my_cnt) break;
-                float s[SM_KB];
+        for (int kb = 0; kb < SM_BN; kb += SM_KB) {
+            if (kb >= mine) break;
+            float s[SM_KB];
 #pragma unroll
-                for (int j = 0; j < SM_KB; ++j) {
-                    const float* kr = &s_k[kb + j][part * DPP];
-                    float dot = 0.f;
+            for (int j = 0; j < SM_KB; ++j) {
+                const float* kr = &s_k[kb + j][part * DPP];
+                float dot = 0.f;
 #pragma unroll
-                    for (int c = 0; c < DP; c += 4) {
-                        const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
-                        dot += q[c] * k4.x + q[c + 1] * k4.y + q[c + 2] * k4.z + q[c + 3] * k4.w;
-                    }
-                    dot += __shfl_xor(dot, 1);
-                    dot += __shfl_xor(dot, 2);
-                    s[j] = (c0 + kb + j < my_cnt) ? dot : -INFINITY;
+                for (int c = 0; c < DP; c += 4) {
+                    const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
+                    dot += q[c] * k4.x + q[c + 1] * k4.y + q[c + 2] * k4.z + q[c + 3] * k4.w;
                 }
-                float bm = s[0];
+                dot += __shfl_xor(dot, 1);
+                dot += __shfl_xor(dot, 2);
+                s[j] = (kb + j < mine) ? dot : -INFINITY;
+            }
+            float bm = s[0];
 #pragma unroll
-                for (int j = 1; j < SM_KB; ++j) bm = fmaxf(bm, s[j]);
-                const float m_new = fmaxf(m_run, bm);      // finite: key c0+kb is visible
-                const float corr = expf(m_run - m_new);    // exp(-inf) = 0 on the first step
-                float p[SM_KB], psum = 0.f;
+            for (int j = 1; j < SM_KB; ++j) bm = fmaxf(bm, s[j]);
+            const float m_new = fmaxf(m_run, bm);      // finite: row kb is visible
+            const float corr = expf(m_run - m_new);    // exp(-inf) = 0 on the first step
+            float p[SM_KB], psum = 0.f;
 #pragma unroll
-                for (int j = 0; j < SM_KB; ++j) { p[j] = expf(s[j] - m_new); psum += p[j]; }
-                l_run = l_run * corr + psum;
-                m_run = m_new;
+            for (int j = 0; j < SM_KB; ++j) { p[j] = expf(s[j] - m_new); psum += p[j]; }
+            l_run = l_run * corr + psum;
+            m_run = m_new;
 #pragma unroll
-                for (int c = 0; c < DP; ++c) acc[c] *= corr;
+            for (int c = 0; c < DP; ++c) acc[c] *= corr;
 #pragma unroll
-                for (int j = 0; j < SM_KB; ++j) {
-                    const float* vr = &s_v[kb + j][part * DPP];
+            for (int j = 0; j < SM_KB; ++j) {
+                const float* vr = &s_v[kb + j][part * DPP];
 #pragma unroll
-                    for (int c = 0; c < DP; c += 4) {
-                        const float4 v4 = *reinterpret_cast<const float4*>(vr + c);
-                        acc[c] += p[j] * v4.x; acc[c + 1] += p[j] * v4.y;
-                        acc[c + 2] += p[j] * v4.z; acc[c + 3] += p[j] * v4.w;
-                    }
+                for (int c = 0; c < DP; c += 4) {
+                    const float4 v4 = *reinterpret_cast<const float4*>(vr + c);
+                    acc[c] += p[j] * v4.x; acc[c + 1] += p[j] * v4.y;
+                    acc[c + 2] += p[j] * v4.z; acc[c + 3] += p[j] * v4.w;
                 }
             }
         }
-    }
+    };
+    for (int c0 = 0; c0 < n_hi; c0 += SM_BN) tile(Kc, Vc, c0, min(SM_BN, n_hi - c0), my_cnt - c0);
+    if (chunk_routing)   // the block's own chunk, rows q0 .. q0 + 63 of K and V: query row r sees rows <= r
+        for (int d0 = 0; d0 < SM_BM; d0 += SM_BN) tile(K, V, q0 + d0, SM_BN, r + 1 - d0);
 
     // ---- epilogue: normalise, optional branch outputs, merge, store -----------------------
     const float inv_l = (l_run > 0.f) ? 1.f / l_run : 0.f;
@@ -154,28 +161,31 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
 }
 
 template <typename T>
-static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const int32_t* cnt,
+static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* K,
+                      const void* V, const int32_t* cnt,
                       const float* O_la, const float* w_nla, const float* w_la, void* O, float* O_nla_out,
                       float* lse_out, hipStream_t st) {
     dim3 grid(pl.L / SM_BM, pl.BH);
     if (pl.d == 64)
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 64>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
-                           (const T*)Kc, (const T*)Vc, cnt, O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
+                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
+                           O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
                            pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
     else
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 128>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
-                           (const T*)Kc, (const T*)Vc, cnt, O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
+                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
+                           O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
                            pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
 }
 
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
-                                const int32_t* cnt, const float* O_la, const float* w_nla,
+                                const void* K, const void* V, const int32_t* cnt, const float* O_la, const float* w_nla,
                                 const float* w_la, void* O, float* O_nla_out, float* lse_out,
                                 hipStream_t st) {
     if (pl.dtype == NATS_BF16)
-        launch_sm<bf16_t>(pl, Q, Kc, Vc, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+        launch_sm<bf16_t>(pl, Q, Kc, Vc, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
     else
-        launch_sm<float>(pl, Q, Kc, Vc, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+        launch_sm<float>(pl, Q, Kc, Vc, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
     return check_launch("softmax_fp32");
 }
 

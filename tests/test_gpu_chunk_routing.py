@@ -1,0 +1,73 @@
+"""GPU parity for routing per chunk (Section 4.1 as stated: one decision per chunk, the intra-chunk part
+computed by both operations, the unchosen state rolled back): the HIP path through the C ABI against
+the chunk-routed CPU oracle, same bars as the per-token tests."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_03681_amd as nats
+from paper_2602_03681_amd import binding as nb
+from nats_inputs import make_chunk_mask, make_fwd_inputs
+
+from gpu_util import TOL, host, rel_err, stored, to_dev
+from oracle import c_oracle
+from test_gpu_parity import ALL_OUT, check_all
+
+pytestmark = pytest.mark.gpu
+C = 64
+
+
+def inputs(B, H, L, d, dtype, p, seed, kind="bernoulli"):
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.1, seed=seed)
+    x["mask"] = make_chunk_mask(B, H, L // C, p, seed + 7, kind)
+    return x
+
+
+def oracle(x, **kw):
+    return c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], chunk_routing=C, **kw)
+
+
+def run_ex(x, dtype, want=ALL_OUT, **kw):
+    g = to_dev(x, dtype)
+    extra_in = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
+                for k, v in kw.items() if k in ("w_nla", "w_la", "initial_state") and v is not None}
+    kw = {k: v for k, v in kw.items() if k not in ("w_nla", "w_la", "initial_state")}
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], C,
+                                routing=nb.NATS_ROUTE_CHUNK, want=want, **extra_in, **kw)
+    torch.cuda.synchronize()
+    return r
+
+
+@pytest.mark.parametrize("kind", ["bernoulli", "all_softmax", "all_linear", "head_skew", "alternate"])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+def test_chunk_routing_mask_patterns(dtype, d, kind):
+    x = inputs(2, 3, 512, d, dtype, 0.3, seed=40 + d, kind=kind)
+    check_all(x, dtype, run_ex(x, dtype), oracle(x))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chunk_routing_eq21_initial_state_and_scales(dtype):
+    x = inputs(1, 4, 384, 128, dtype, 0.35, seed=51)
+    rng = np.random.default_rng(52)
+    w = rng.random((2, 1, 4, 384)).astype(np.float32)
+    S0 = (rng.standard_normal((1, 4, 128, 128)) * 0.05).astype(np.float32)
+    kw = dict(combine_mode=1, softmax_scale=float(np.sqrt(128.0)), la_scale=0.5)
+    r = run_ex(x, dtype, w_nla=w[0], w_la=w[1], initial_state=S0, **kw)
+    ref = oracle(x, mode=1, softmax_scale=kw["softmax_scale"], la_scale=0.5, w_nla=w[0], w_la=w[1],
+                 S0=S0.astype(np.float64))
+    check_all(x, dtype, r, ref)
+
+
+def test_chunk_routing_fp32_math_on_bf16_tensors():
+    x = inputs(1, 2, 256, 64, "bf16", 0.4, seed=53)
+    check_all(x, "bf16", run_ex(x, "bf16", math=nb.NATS_MATH_FP32), oracle(x))
+
+
+def test_chunk_routing_long_sequence_ragged_query_tile_bf16():
+    """L = 64 * 21: the last block of the softmax kernel holds one chunk only; many compacted tiles."""
+    x = inputs(1, 5, 64 * 21, 128, "bf16", 0.5, seed=54)
+    g = to_dev(x, "bf16")
+    O = nats.hybrid_attn_fwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], C,
+                             routing=nb.NATS_ROUTE_CHUNK)
+    torch.cuda.synchronize()
+    assert rel_err(host(O), oracle(x, want=())["O"], stored("bf16")) <= TOL["bf16"]
