@@ -127,6 +127,8 @@ def main():
                     help="also time the step replayed from a captured HIP graph (extra key graph_replay_ms_per_step)")
     ap.add_argument("--probes", action="store_true",
                     help="also time an MFMA-issue probe and a 256 MiB copy and report them as measured_peaks")
+    ap.add_argument("--routing", choices=("token", "chunk"), default="token",
+                    help="granularity of the routing mask: per token (default, the headline workload) or per chunk")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,13 +151,25 @@ def main():
     g = {k: torch.from_numpy(v).to(dev) for k, v in x.items()}
     Q, K, V = (g[k].to(torch.bfloat16) for k in ("Q", "K", "V"))
     alpha, beta, mask = g["alpha"], g["beta"], g["mask"]
-    params = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16)
+    routing = nb.NATS_ROUTE_CHUNK if args.routing == "chunk" else nb.NATS_ROUTE_TOKEN
+    if routing == nb.NATS_ROUTE_CHUNK:
+        # same shapes and softmax share, one routing decision per chunk of 64 tokens (Section 4.1 as stated)
+        from nats_inputs import make_chunk_mask
+        mask_c = make_chunk_mask(cfg.B, cfg.H, cfg.L // cfg.C, cfg.p_softmax, cfg.seed + 1)
+        mask_c[:, :, 0] = 1
+        x["mask"] = mask_c
+        mask = torch.from_numpy(mask_c).to(dev)
+        tok = np.repeat(mask_c, cfg.C, axis=-1).astype(np.int64)
+        before = np.cumsum(tok, axis=-1) - tok * (np.arange(cfg.L) % cfg.C + 1)      # rows of earlier chunks
+        sum_cnt = int((before + np.arange(cfg.L) % cfg.C + 1).sum())                # + own chunk, causally
+    else:
+        sum_cnt = int(np.cumsum(x["mask"] != 0, axis=-1, dtype=np.int64).sum())
+    params = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, routing=routing)
     ws = torch.empty(nb.fwd_workspace_bytes(params), dtype=torch.uint8, device=dev)
     O = torch.empty_like(Q)
-    sum_cnt = int(np.cumsum(x["mask"] != 0, axis=-1, dtype=np.int64).sum())
 
     def step():
-        nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, out=O, workspace=ws)
+        nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, routing=routing, out=O, workspace=ws)
 
     for _ in range(args.warmup):
         step()
@@ -256,7 +270,7 @@ def main():
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 20:
             c0 = time.perf_counter()
-            c_oracle.fwd(**xs, want=())
+            c_oracle.fwd(**xs, want=(), chunk_routing=cfg.C if args.routing == "chunk" else 0)
             t_cpu += time.perf_counter() - c0
             reps += 1
         head_tok_per_s = reps * heads * cfg.L / t_cpu
@@ -269,7 +283,8 @@ def main():
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
-           "config": {"workload": "cfg2_headline_bf16: B=2 H=16 L=8192 d=128 C=64 bf16, mask~Bernoulli(0.05)",
+           "config": {"workload": "cfg2_headline_bf16: B=2 H=16 L=8192 d=128 C=64 bf16, mask~Bernoulli(0.05)"
+                                  + (" per chunk of 64 tokens (routing per chunk)" if args.routing == "chunk" else ""),
                       "global_batch": cfg.B, "seq_len": cfg.L, "heads": cfg.H, "d_head": cfg.d,
                       "parallelism": "single GPU"},
            "kernels_ms": {k: round(v["total_ms"] / args.steps, 4) for k, v in kernels.items()},
