@@ -73,10 +73,11 @@ __device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned
 // MERGE = false: the epilogue stores the softmax branch's output as fp16 (O_nla_h); the kernel that
 //                carries the state merges and stores O.  This variant depends on nothing but the
 //                compaction, so it can run beside the linear branch's preparation.
-template <int D, bool MERGE>
+// chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
+template <int D, bool MERGE, bool chunk_routing>
 __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
-    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, int chunk_routing,
+    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
@@ -407,10 +408,16 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
                       const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
     dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
-    hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
-                       (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V,
-                       pl.routing == NATS_ROUTE_CHUNK, cnt, (const half_t*)O_la, w_nla, w_la, (bf16_t*)O,
-                       (half_t*)O_nla_h, O_nla_out, lse_out, pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+    if (pl.routing == NATS_ROUTE_CHUNK)
+        hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                           (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
+                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+    else
+        hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                           (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
+                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps);
 }
 
 // O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.
