@@ -167,6 +167,43 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
                                     void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ * Generation with routing per chunk (Section 4.1, per-token generation)
+ * ------------------------------------------------------------------------- */
+/* The type of a chunk is known only after its last token, so inside an open chunk both operations
+ * are updated provisionally and one of them is rolled back when the chunk is settled:
+ *   every token:  S <- alpha S + beta (v - alpha S k) k^T  (Eq. 19) and (k, v) appended to the cache at
+ *                 row cache_len + chunk_pos;  o = merge(la_scale * S q, softmax over rows
+ *                 [0, cache_len + chunk_pos] of the cache)  -- the token sees earlier softmax chunks
+ *                 and, causally, its own chunk;
+ *   first token of a chunk (chunk_pos == 0): state_start <- S (before the update), chunk_decay <- 1;
+ *   nats_hybrid_attn_decode_commit, after the chunk: a softmax chunk keeps its rows (cache_len +=
+ *                 chunk_pos) and sets S <- chunk_decay * state_start (writes dropped, Eq. 14; decay
+ *                 kept, Eq. 20); a linear chunk keeps S and drops the rows; chunk_pos <- 0.
+ * All members are DEVICE pointers owned by the caller, updated in place. */
+typedef struct nats_dec_chunk_state {
+    float* state;         /* [B,H,d,d] f32 S[d_v][d_k], with the open chunk's provisional writes       */
+    float* state_start;   /* [B,H,d,d] f32 state at the start of the open chunk                         */
+    float* chunk_decay;   /* [B,H]     f32 product of alpha over the open chunk's tokens so far         */
+    int32_t* chunk_pos;   /* [B,H]     i32 tokens of the open chunk seen so far                         */
+    void* k_cache;        /* [B,H,cap,d] rows [0,cache_len) settled, [cache_len, +chunk_pos) provisional */
+    void* v_cache;
+    int32_t* cache_len;   /* [B,H]     i32 settled rows                                                 */
+} nats_dec_chunk_state;
+
+/* One token for every (b,h).  q, k, v [B,H,d]; alpha, beta [B,H]; w_nla, w_la [B,H] or NULL (0.5);
+ * o [B,H,d]; err_flags [B,H] or NULL: 1 where the cache was full (the token is then not stored and o
+ * covers the rows that are there).  The cache needs room for cache_len + C rows. */
+nats_status nats_hybrid_attn_decode_chunk(const nats_dec_params* p, const nats_dec_chunk_state* s, const void* q,
+                                          const void* k, const void* v, const float* alpha, const float* beta,
+                                          const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
+                                          void* hip_stream);
+
+/* Settles the open chunk of every (b,h) with its routing decision mask_c [B,H] u8 (non-zero = softmax
+ * chunk), as described above.  err_flags [B,H] or NULL: 1 where rows of a softmax chunk had not fitted. */
+nats_status nats_hybrid_attn_decode_commit(const nats_dec_params* p, const nats_dec_chunk_state* s,
+                                           const uint8_t* mask_c, int32_t* err_flags, void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
  * Optional per-kernel timing (for benchmarks; off by default)
  * ------------------------------------------------------------------------- */
 /* Creates max_records hipEvent pairs and turns recording on: until nats_profile_end, every kernel

@@ -311,3 +311,57 @@ def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None,
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]
     return out
+
+
+# --------------------------------------------------------------------------- #
+# generation with routing per chunk (Section 4.1, per-token generation): provisional
+# updates inside the open chunk, rollback of the unchosen operation when it is settled
+# --------------------------------------------------------------------------- #
+def decode_chunk_state(S, k_cache, v_cache, cache_len):
+    """State of one (batch, head) between tokens: settled rows [0, cache_len) of the caches."""
+    return {"S": np.array(S, dtype=np.float64), "S_start": np.array(S, dtype=np.float64), "decay": 1.0,
+            "pos": 0, "k_cache": np.array(k_cache, dtype=np.float64), "v_cache": np.array(v_cache, dtype=np.float64),
+            "cache_len": int(cache_len)}
+
+
+def decode_step_chunk_routed(st, q, k, v, alpha, beta, softmax_scale=None, la_scale=1.0, mode=0,
+                             w_nla=0.5, w_la=0.5, eps=1e-6):
+    """One token inside an open chunk.  Both operations take it: the state is updated by Eq. 19 and (k, v)
+    goes to the cache at row cache_len + pos; the output reads the state and every row up to that one
+    (earlier softmax chunks, and the own chunk causally).  Returns (o, overflow); st is updated in place.
+    A full cache leaves the token out of the cache (overflow=True)."""
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    scale = (1.0 / np.sqrt(q.shape[0])) if softmax_scale is None else softmax_scale
+    if st["pos"] == 0:
+        st["S_start"] = st["S"].copy()
+        st["decay"] = 1.0
+    S = float(alpha) * st["S"]
+    st["decay"] *= float(alpha)
+    S = S + float(beta) * np.outer(v - S @ k, k)
+    st["S"] = S
+    n = st["cache_len"] + st["pos"]
+    overflow = n >= st["k_cache"].shape[0]
+    if not overflow:
+        st["k_cache"][n] = k
+        st["v_cache"][n] = v
+        n += 1
+    st["pos"] += 1
+    o_la = la_scale * (S @ q)
+    if n > 0:
+        s = scale * (st["k_cache"][:n] @ q)
+        e = np.exp(s - s.max())
+        o_nla = (e / e.sum()) @ st["v_cache"][:n]
+    else:
+        o_nla = np.zeros_like(o_la)
+    if mode == 0:
+        return o_la + o_nla, overflow
+    return w_nla * rms_norm_rows(o_nla[None], eps)[0] + w_la * rms_norm_rows(o_la[None], eps)[0], overflow
+
+
+def decode_commit_chunk(st, m):
+    """Settles the open chunk: a softmax chunk (m != 0) keeps its cache rows and sets the state back to
+    (chunk decay) x (chunk-start state); a linear chunk keeps the state and drops the rows."""
+    if m:
+        st["cache_len"] = min(st["cache_len"] + st["pos"], st["k_cache"].shape[0])
+        st["S"] = st["decay"] * st["S_start"]
+    st["pos"] = 0

@@ -43,6 +43,12 @@ class FwdExtra(ctypes.Structure):
                 ("lse", ctypes.c_void_p)]
 
 
+class DecChunkState(ctypes.Structure):
+    _fields_ = [("state", ctypes.c_void_p), ("state_start", ctypes.c_void_p), ("chunk_decay", ctypes.c_void_p),
+                ("chunk_pos", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("cache_len", ctypes.c_void_p)]
+
+
 class DecParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("la_scale", ctypes.c_float),
@@ -51,7 +57,8 @@ class DecParams(ctypes.Structure):
 
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
-           "nats_profile_end", "nats_probe_mfma")
+           "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
+           "nats_hybrid_attn_decode_commit")
 
 
 def library_path() -> str:
@@ -241,6 +248,55 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
                                        _stream_ptr()))
     return o
+
+
+def _chunk_state(st: Dict[str, torch.Tensor]):
+    """st: dict of tensors state, state_start [B,H,d,d] f32; chunk_decay [B,H] f32; chunk_pos, cache_len [B,H]
+    i32; k_cache, v_cache [B,H,cap,d]."""
+    B, H, cap, d = st["k_cache"].shape
+    dt = st["k_cache"].dtype
+    _require(st["state"], "state", (B, H, d, d), torch.float32)
+    _require(st["state_start"], "state_start", (B, H, d, d), torch.float32)
+    _require(st["chunk_decay"], "chunk_decay", (B, H), torch.float32)
+    _require(st["chunk_pos"], "chunk_pos", (B, H), torch.int32)
+    _require(st["k_cache"], "k_cache", (B, H, cap, d), dt)
+    _require(st["v_cache"], "v_cache", (B, H, cap, d), dt)
+    _require(st["cache_len"], "cache_len", (B, H), torch.int32)
+    cs = DecChunkState(*(st[k].data_ptr() for k in ("state", "state_start", "chunk_decay", "chunk_pos", "k_cache",
+                                                    "v_cache", "cache_len")))
+    return cs, (B, H, cap, d, dt)
+
+
+def hybrid_attn_decode_chunk(st, q, k, v, alpha, beta, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
+                             combine_mode: int = 0, rms_eps: float = 0.0, w_nla=None, w_la=None, out=None,
+                             err_flags=None) -> torch.Tensor:
+    """nats_hybrid_attn_decode_chunk: one token per (b,h) under routing per chunk; `st` (see _chunk_state) is
+    updated in place."""
+    lib = load_library()
+    cs, (B, H, cap, d, dt) = _chunk_state(st)
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        _require(t, name, (B, H, d), dt)
+    for name, t in (("alpha", alpha), ("beta", beta), ("w_nla", w_nla), ("w_la", w_la)):
+        _require(t, name, (B, H), torch.float32)
+    _require(err_flags, "err_flags", (B, H), torch.int32)
+    o = torch.empty_like(q) if out is None else out
+    _require(o, "out", (B, H, d), dt)
+    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), softmax_scale, la_scale, combine_mode, rms_eps)
+    _check(lib.nats_hybrid_attn_decode_chunk(ctypes.byref(params), ctypes.byref(cs), _ptr(q), _ptr(k), _ptr(v),
+                                             _ptr(alpha), _ptr(beta), _ptr(w_nla), _ptr(w_la), _ptr(o),
+                                             _ptr(err_flags), _stream_ptr()))
+    return o
+
+
+def hybrid_attn_decode_commit(st, mask_c, *, err_flags=None) -> None:
+    """nats_hybrid_attn_decode_commit: settle the open chunk of every (b,h) with its routing decision."""
+    lib = load_library()
+    cs, (B, H, cap, d, dt) = _chunk_state(st)
+    _require(mask_c, "mask_c", (B, H), torch.uint8)
+    _require(err_flags, "err_flags", (B, H), torch.int32)
+    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), 0.0, 0.0, 0, 0.0)
+    _check(lib.nats_hybrid_attn_decode_commit(ctypes.byref(params), ctypes.byref(cs), _ptr(mask_c), _ptr(err_flags),
+                                              _stream_ptr()))
 
 
 def profile_begin(max_records: int = 4096) -> None:

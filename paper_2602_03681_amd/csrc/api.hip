@@ -383,4 +383,73 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
                          mask, w_nla, w_la, o, err_flags, stream);
 }
 
+static nats_status validate_dec_params(const nats_dec_params* p) {
+    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
+    if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {
+        set_error("dtype %d is neither NATS_F32 nor NATS_BF16", p->dtype);
+        return NATS_ERR_DTYPE;
+    }
+    if (p->B <= 0 || p->H <= 0 || p->cap <= 0) {
+        set_error("B, H, cap must be positive (got %d, %d, %d)", p->B, p->H, p->cap);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
+    if (p->combine_mode != 0 && p->combine_mode != 1) {
+        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+        return NATS_ERR_SHAPE;
+    }
+    return NATS_OK;
+}
+
+static nats_status validate_chunk_state(const nats_dec_chunk_state* s) {
+    if (s == nullptr) { set_error("chunk state is NULL"); return NATS_ERR_NULL; }
+    if (!s->state || !s->state_start || !s->chunk_decay || !s->chunk_pos || !s->k_cache || !s->v_cache ||
+        !s->cache_len) {
+        set_error("every pointer of the chunk state must be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    const void* ptrs[] = {s->state, s->state_start, s->k_cache, s->v_cache};
+    for (const void* ptr : ptrs)
+        if (!aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    return NATS_OK;
+}
+
+nats_status nats_hybrid_attn_decode_chunk(const nats_dec_params* p, const nats_dec_chunk_state* s, const void* q,
+                                          const void* k, const void* v, const float* alpha, const float* beta,
+                                          const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
+                                          void* hip_stream) {
+    nats_status st = validate_dec_params(p);
+    if (st != NATS_OK) return st;
+    st = validate_chunk_state(s);
+    if (st != NATS_OK) return st;
+    if (!q || !k || !v || !alpha || !beta || !o) {
+        set_error("q, k, v, alpha, beta and o must all be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    const void* ptrs[] = {q, k, v, o};
+    for (const void* ptr : ptrs)
+        if (!aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+    const float la_scale = p->la_scale > 0.f ? p->la_scale : 1.0f;
+    const float eps = p->rms_eps > 0.f ? p->rms_eps : 1e-6f;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("decode_chunk", stream);
+    return launch_decode_chunk(*p, scale, la_scale, eps, s->state, s->state_start, s->chunk_decay, s->chunk_pos,
+                               s->k_cache, s->v_cache, s->cache_len, q, k, v, alpha, beta, w_nla, w_la, o, err_flags,
+                               stream);
+}
+
+nats_status nats_hybrid_attn_decode_commit(const nats_dec_params* p, const nats_dec_chunk_state* s,
+                                           const uint8_t* mask_c, int32_t* err_flags, void* hip_stream) {
+    nats_status st = validate_dec_params(p);
+    if (st != NATS_OK) return st;
+    st = validate_chunk_state(s);
+    if (st != NATS_OK) return st;
+    if (!mask_c) { set_error("mask_c is NULL"); return NATS_ERR_NULL; }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("decode_commit", stream);
+    return launch_decode_commit(*p, s->state, s->state_start, s->chunk_decay, s->chunk_pos, s->cache_len, mask_c,
+                                err_flags, stream);
+}
+
 }  // extern "C"

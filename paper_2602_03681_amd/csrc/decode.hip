@@ -27,9 +27,15 @@ __device__ __forceinline__ float group_sum(float x) {
     return x;
 }
 
-template <typename T, int D>
+// CHUNK = false: routing per token (mask: the token's type).
+// CHUNK = true : routing per chunk, known only after the chunk (Section 4.1, per-token generation): every
+//   token is written into the state and appended to the cache provisionally (row cache_len +
+//   chunk_pos); at a chunk's first token the state is copied to state_start; chunk_decay collects the
+//   chunk's decay; cache_len stays, chunk_pos advances.  decode_commit_kernel settles the chunk.
+template <typename T, int D, bool CHUNK>
 __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
-    float* __restrict__ state, T* __restrict__ k_cache, T* __restrict__ v_cache,
+    float* __restrict__ state, float* __restrict__ state_start, float* __restrict__ chunk_decay,
+    int32_t* __restrict__ chunk_pos, T* __restrict__ k_cache, T* __restrict__ v_cache,
     int32_t* __restrict__ cache_len, const T* __restrict__ q, const T* __restrict__ k,
     const T* __restrict__ v, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ w_nla, const float* __restrict__ w_la,
@@ -54,9 +60,10 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
         s_v[c] = to_float(v[(size_t)bh * D + c]);
     }
     const float a = alpha[bh];
-    const bool is_softmax = mask[bh] != 0;
-    const float b = is_softmax ? 0.f : beta[bh];
-    const int n_old = cache_len[bh];
+    const int pos = CHUNK ? chunk_pos[bh] : 0;
+    const bool is_softmax = CHUNK ? true : mask[bh] != 0;     // CHUNK: every token goes to the cache ...
+    const float b = (!CHUNK && is_softmax) ? 0.f : beta[bh];  // ... and into the state
+    const int n_old = cache_len[bh] + pos;                    // rows present, provisional ones included
     const bool append = is_softmax && n_old < cap;
     __syncthreads();
 
@@ -70,6 +77,12 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
             S4[p] = *reinterpret_cast<const float4*>(Sb + (size_t)(p * ROWS_PER_PASS + r0) * D + lr * 4);
         const float4 k4 = *reinterpret_cast<const float4*>(&s_k[lr * 4]);
         const float4 q4 = *reinterpret_cast<const float4*>(&s_q[lr * 4]);
+        if (CHUNK && pos == 0) {   // first token of a chunk: keep the state it starts from
+            float* Sst = state_start + (size_t)bh * D * D;
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p)
+                *reinterpret_cast<float4*>(Sst + (size_t)(p * ROWS_PER_PASS + r0) * D + lr * 4) = S4[p];
+        }
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int row = p * ROWS_PER_PASS + r0;
@@ -156,7 +169,11 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
             k_cache[((size_t)bh * cap + n_old) * D + c] = k[(size_t)bh * D + c];
             v_cache[((size_t)bh * cap + n_old) * D + c] = v[(size_t)bh * D + c];
         }
-        if (tid == 0) cache_len[bh] = n_old + 1;
+        if (tid == 0 && !CHUNK) cache_len[bh] = n_old + 1;
+    }
+    if (CHUNK && tid == 0) {
+        chunk_pos[bh] = pos + 1;
+        chunk_decay[bh] = (pos == 0 ? 1.f : chunk_decay[bh]) * a;
     }
     if (tid == 0 && err_flags != nullptr) err_flags[bh] = (is_softmax && !append) ? 1 : 0;
 
@@ -197,18 +214,51 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     }
 }
 
-template <typename T>
+// After a chunk has been seen and its type decided (mask_c[b,h] != 0: softmax chunk): a softmax chunk keeps
+// its provisional cache rows and gives the state back as (chunk decay) x (chunk-start state); a linear
+// chunk keeps the state and drops the rows.  chunk_pos returns to 0.  err_flags (optional) is set where
+// rows of a softmax chunk did not fit into the cache (they were never stored).
+template <int D>
+__global__ __launch_bounds__(DEC_THREADS) void decode_commit_kernel(
+    float* __restrict__ state, const float* __restrict__ state_start, const float* __restrict__ chunk_decay,
+    int32_t* __restrict__ chunk_pos, int32_t* __restrict__ cache_len, const uint8_t* __restrict__ mask_c,
+    int32_t* __restrict__ err_flags, int cap) {
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int pos = chunk_pos[bh];
+    const bool soft = mask_c[bh] != 0;
+    const int n = cache_len[bh];
+    if (soft && pos > 0) {
+        const float dec = chunk_decay[bh];
+        float4* S = reinterpret_cast<float4*>(state + (size_t)bh * D * D);
+        const float4* S0 = reinterpret_cast<const float4*>(state_start + (size_t)bh * D * D);
+        for (int i = tid; i < D * D / 4; i += DEC_THREADS) {
+            const float4 x = S0[i];
+            S[i] = make_float4(dec * x.x, dec * x.y, dec * x.z, dec * x.w);
+        }
+    }
+    __syncthreads();   // every thread has read pos and n
+    if (tid == 0) {
+        if (soft) cache_len[bh] = min(n + pos, cap);
+        if (err_flags != nullptr) err_flags[bh] = (soft && n + pos > cap) ? 1 : 0;
+        chunk_pos[bh] = 0;
+    }
+}
+
+template <typename T, bool CHUNK>
 static void launch_dec(const nats_dec_params& p, float scale, float la_scale, float eps, float* state,
+                       float* state_start, float* chunk_decay, int32_t* chunk_pos,
                        void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
                        const void* v, const float* alpha, const float* beta, const uint8_t* mask,
                        const float* w_nla, const float* w_la, void* o, int32_t* err_flags, hipStream_t st) {
     dim3 grid(p.B * p.H);
     if (p.d == 64)
-        hipLaunchKernelGGL((decode_kernel<T, 64>), grid, dim3(DEC_THREADS), 0, st, state, (T*)k_cache,
+        hipLaunchKernelGGL((decode_kernel<T, 64, CHUNK>), grid, dim3(DEC_THREADS), 0, st, state, state_start,
+                           chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
                            w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
     else
-        hipLaunchKernelGGL((decode_kernel<T, 128>), grid, dim3(DEC_THREADS), 0, st, state, (T*)k_cache,
+        hipLaunchKernelGGL((decode_kernel<T, 128, CHUNK>), grid, dim3(DEC_THREADS), 0, st, state, state_start,
+                           chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
                            w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
 }
@@ -219,12 +269,39 @@ nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float l
                           const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
                           int32_t* err_flags, hipStream_t st) {
     if (p.dtype == NATS_BF16)
-        launch_dec<bf16_t>(p, softmax_scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v,
-                           alpha, beta, mask, w_nla, w_la, o, err_flags, st);
+        launch_dec<bf16_t, false>(p, softmax_scale, la_scale, eps, state, nullptr, nullptr, nullptr, k_cache, v_cache,
+                                  cache_len, q, k, v, alpha, beta, mask, w_nla, w_la, o, err_flags, st);
     else
-        launch_dec<float>(p, softmax_scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v,
-                          alpha, beta, mask, w_nla, w_la, o, err_flags, st);
+        launch_dec<float, false>(p, softmax_scale, la_scale, eps, state, nullptr, nullptr, nullptr, k_cache, v_cache,
+                                 cache_len, q, k, v, alpha, beta, mask, w_nla, w_la, o, err_flags, st);
     return check_launch("decode");
+}
+
+nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
+                                float* state, float* state_start, float* chunk_decay, int32_t* chunk_pos,
+                                void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
+                                const void* v, const float* alpha, const float* beta, const float* w_nla,
+                                const float* w_la, void* o, int32_t* err_flags, hipStream_t st) {
+    if (p.dtype == NATS_BF16)
+        launch_dec<bf16_t, true>(p, softmax_scale, la_scale, eps, state, state_start, chunk_decay, chunk_pos, k_cache,
+                                 v_cache, cache_len, q, k, v, alpha, beta, nullptr, w_nla, w_la, o, err_flags, st);
+    else
+        launch_dec<float, true>(p, softmax_scale, la_scale, eps, state, state_start, chunk_decay, chunk_pos, k_cache,
+                                v_cache, cache_len, q, k, v, alpha, beta, nullptr, w_nla, w_la, o, err_flags, st);
+    return check_launch("decode (routing per chunk)");
+}
+
+nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,
+                                 const float* chunk_decay, int32_t* chunk_pos, int32_t* cache_len,
+                                 const uint8_t* mask_c, int32_t* err_flags, hipStream_t st) {
+    dim3 grid(p.B * p.H);
+    if (p.d == 64)
+        hipLaunchKernelGGL(decode_commit_kernel<64>, grid, dim3(DEC_THREADS), 0, st, state, state_start, chunk_decay,
+                           chunk_pos, cache_len, mask_c, err_flags, p.cap);
+    else
+        hipLaunchKernelGGL(decode_commit_kernel<128>, grid, dim3(DEC_THREADS), 0, st, state, state_start, chunk_decay,
+                           chunk_pos, cache_len, mask_c, err_flags, p.cap);
+    return check_launch("decode_commit");
 }
 
 }  // namespace nats

@@ -116,6 +116,27 @@ def test_decode_validation(lib):
     assert call(good, ptrs) == E_ALIGN
 
 
+def test_chunk_routing_validation(lib):
+    # forward: routing must be one of the two enumerators
+    assert lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(good_params(routing=7))) == 0
+    assert lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK))) > 0
+    # generation with routing per chunk: params, state struct and pointers are checked before any launch
+    good = nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0.0, 0.0, 0, 0.0)
+    st = nb.DecChunkState(*[FAKE + 16 * i for i in range(7)])
+    args = [FAKE + 256 + 16 * i for i in range(9)]
+
+    def step(p, s, a=args):
+        return lib.nats_hybrid_attn_decode_chunk(ctypes.byref(p), None if s is None else ctypes.byref(s), *a, None)
+
+    assert step(nb.DecParams(4, 2, 100, 512, nb.NATS_BF16, 0, 0, 0, 0), st) == E_SHAPE
+    assert step(good, None) == E_NULL
+    assert step(good, nb.DecChunkState(*([None] + [FAKE + 16 * i for i in range(6)]))) == E_NULL
+    assert step(good, nb.DecChunkState(*([FAKE + 2] + [FAKE + 16 * i for i in range(6)]))) == E_ALIGN
+    assert step(good, st, [None] + args[1:]) == E_NULL
+    assert lib.nats_hybrid_attn_decode_commit(ctypes.byref(good), ctypes.byref(st), None, None, None) == E_NULL
+    assert lib.nats_hybrid_attn_decode_commit(ctypes.byref(good), None, FAKE, None, None) == E_NULL
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(nb, "_lib", None)
     monkeypatch.setattr(nb, "_LIB_PATH", str(tmp_path / "libnats.so"))

@@ -71,3 +71,80 @@ def test_chunk_routing_long_sequence_ragged_query_tile_bf16():
                              routing=nb.NATS_ROUTE_CHUNK)
     torch.cuda.synchronize()
     assert rel_err(host(O), oracle(x, want=())["O"], stored("bf16")) <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------------------------------------
+# generation: provisional updates inside the open chunk, commit per chunk
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_generation_with_commits_continues_the_forward(dtype, d):
+    """Prefill L0 tokens with the forward (routing per chunk), then generate 3 chunks token by token with
+    nats_hybrid_attn_decode_chunk and a commit per chunk: every output row must match the chunk-routed
+    oracle's forward over the whole sequence, the final state and the settled cache likewise."""
+    B, H, L0, n_new = 2, 2, 256, 192
+    L = L0 + n_new
+    x = inputs(B, H, L, d, dtype, 0.4, seed=60 + d)
+    ref = oracle(x)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    pre = {k: v[:, :, :L0] for k, v in x.items() if k != "mask"}
+    pre["mask"] = x["mask"][:, :, :L0 // C]
+    g = to_dev({k: np.ascontiguousarray(v) for k, v in pre.items()}, dtype)
+    cap = L
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], C,
+                                routing=nb.NATS_ROUTE_CHUNK, want=("final_state", "Kc", "Vc", "n_s"), cap=cap)
+    st = {"state": r["final_state"], "state_start": torch.zeros_like(r["final_state"]),
+          "chunk_decay": torch.ones((B, H), dtype=torch.float32, device="cuda"),
+          "chunk_pos": torch.zeros((B, H), dtype=torch.int32, device="cuda"),
+          "k_cache": r["Kc"], "v_cache": r["Vc"], "cache_len": r["n_s"].clone()}
+    full = to_dev(x, dtype)
+    err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    worst = 0.0
+    rms = np.sqrt(np.mean(ref["O"] ** 2))
+    for t in range(L0, L):
+        o = nats.hybrid_attn_decode_chunk(st, full["Q"][:, :, t].contiguous(), full["K"][:, :, t].contiguous(),
+                                          full["V"][:, :, t].contiguous(), full["alpha"][:, :, t].contiguous(),
+                                          full["beta"][:, :, t].contiguous(), err_flags=err)
+        assert int(err.sum()) == 0
+        diff = np.abs(host(o).astype(np.float64) - ref["O"][:, :, t])
+        if dtype == "bf16":
+            from gpu_util import bf16_half_ulp
+            diff = np.maximum(diff - bf16_half_ulp(ref["O"][:, :, t]), 0.0)
+        worst = max(worst, float(diff.max() / rms))
+        if (t + 1) % C == 0:
+            nats.hybrid_attn_decode_commit(st, full["mask"][:, :, t // C].contiguous(), err_flags=err)
+            assert int(err.sum()) == 0
+    torch.cuda.synchronize()
+    assert worst <= TOL[dtype], f"worst output error {worst:.3e}"
+    assert rel_err(host(st["state"]), ref["S"]) <= TOL[dtype]
+    np.testing.assert_array_equal(host(st["cache_len"]), ref["n_s"])
+    np.testing.assert_array_equal(host(st["chunk_pos"]), 0)
+    kc = host(st["k_cache"])
+    for b in range(B):
+        for h in range(H):
+            n = int(ref["n_s"][b, h])
+            np.testing.assert_array_equal(kc[b, h, :n], x["K"][b, h, ref["idx"][b, h, :n]])
+
+
+def test_generation_cache_overflow_is_flagged():
+    B, H, d = 1, 2, 64
+    cap = 70
+    x = inputs(B, H, 128, d, "f32", 1.0, seed=70, kind="all_softmax")
+    full = to_dev(x, "f32")
+    st = {"state": torch.zeros((B, H, d, d), device="cuda"), "state_start": torch.zeros((B, H, d, d), device="cuda"),
+          "chunk_decay": torch.ones((B, H), device="cuda"), "chunk_pos": torch.zeros((B, H), dtype=torch.int32, device="cuda"),
+          "k_cache": torch.zeros((B, H, cap, d), device="cuda"), "v_cache": torch.zeros((B, H, cap, d), device="cuda"),
+          "cache_len": torch.zeros((B, H), dtype=torch.int32, device="cuda")}
+    err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    flagged_at = None
+    for t in range(128):
+        nats.hybrid_attn_decode_chunk(st, *(full[k][:, :, t].contiguous() for k in ("Q", "K", "V", "alpha", "beta")),
+                                      err_flags=err)
+        if int(err.sum()) and flagged_at is None:
+            flagged_at = t
+        if (t + 1) % C == 0:
+            cerr = torch.zeros_like(err)
+            nats.hybrid_attn_decode_commit(st, full["mask"][:, :, t // C].contiguous(), err_flags=cerr)
+            if t + 1 == 128:
+                assert int(cerr.sum()) == B * H          # 128 rows do not fit into 70
+    assert flagged_at == cap                             # token index 70 is the first one without a row
+    np.testing.assert_array_equal(host(st["cache_len"]), cap)

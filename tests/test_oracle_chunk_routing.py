@@ -117,3 +117,29 @@ def test_c_oracle_matches_numpy_oracle_chunk_routed(mode):
         for h in range(H):
             n = a["n_s"][bb, h]
             assert np.array_equal(b["idx"][bb, h, :n], a["idx"][bb][h])
+
+
+def test_generation_with_reroll_continues_the_chunk_routed_forward():
+    """Prefill by the (pinned) chunk-routed forward, then token-by-token generation with provisional
+    updates and a commit per chunk must reproduce the rows of the forward over the longer sequence."""
+    L0, n_new, d, C = 32, 24, 8, 8
+    L = L0 + n_new
+    x, mc = _inputs(L, d, 21, C, p=0.5)
+    full = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, la_scale=0.8)
+    pre = no.hybrid_head_chunk_routed(x["Q"][:L0], x["K"][:L0], x["V"][:L0], x["alpha"][:L0], x["beta"][:L0],
+                                      mc[:L0 // C], C, la_scale=0.8)
+    cap = L
+    kc, vc = np.zeros((cap, d)), np.zeros((cap, d))
+    kc[:pre["n_s"]] = x["K"][pre["idx"]]
+    vc[:pre["n_s"]] = x["V"][pre["idx"]]
+    st = no.decode_chunk_state(pre["S"], kc, vc, pre["n_s"])
+    for t in range(L0, L):
+        o, ovf = no.decode_step_chunk_routed(st, x["Q"][t], x["K"][t], x["V"][t], x["alpha"][t], x["beta"][t],
+                                             la_scale=0.8)
+        assert not ovf
+        np.testing.assert_allclose(o, full["O"][t], rtol=0, atol=1e-12)
+        if (t + 1) % C == 0:
+            no.decode_commit_chunk(st, mc[t // C])
+    np.testing.assert_allclose(st["S"], full["S"], rtol=0, atol=1e-12)
+    assert st["cache_len"] == full["n_s"]
+    np.testing.assert_array_equal(st["k_cache"][:full["n_s"]], x["K"][full["idx"]])
