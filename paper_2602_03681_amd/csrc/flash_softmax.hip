@@ -168,11 +168,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             *reinterpret_cast<u32x4*>(Qst + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = qreg[i];
         }
     }
-#ifdef NATS_DEBUG_FLASH_NOTILES
-    const int n_tiles = 0 * n_hi;
-#else
     const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
-#endif
     // The tiles of this block in order: n_tiles compacted ones, then (routing per chunk) the chunks the
     // block's own queries lie in.  Tile i + 1 is loaded while tile i is used.
     const int n_own = chunk_routing ? (min(q0 + FL_BM, L) - q0) / FL_BN : 0;

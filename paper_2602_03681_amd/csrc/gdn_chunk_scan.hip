@@ -8,15 +8,17 @@
 // (batch, head) and walks the chunks in order; the grid is (d / BV) * (B*H) blocks.
 //
 // The state lives transposed, S^T [d_k x BV], as fp32 MFMA accumulators spread over four
-// wavefronts (each owns d_k/4 rows) and never leaves registers in fp32; an fp16 copy
-// S[v][d_k] in LDS is the B operand of the products that read it, and the fp16 copy of U is
-// the B operand of the state update.  A block has two groups of four wavefronts: the first
-// carries the dependent chain (U, then S1), the second produces the output (Qg S0^T + P U) from
-// the same two LDS copies, so the output work fills the issue slots the chain leaves idle.
-// Phase 1 splits the chunk's tokens over a group's wavefronts, phase 2 splits d_k, so every A
-// operand is private to one wavefront: it is loaded from global memory straight into MFMA
-// fragment registers, three chunks ahead of use, and LDS carries only the two exchanged copies.
-// Per chunk: two block barriers (U ready, S ready).
+// wavefronts (each owns d_k/4 rows) and never leaves registers in fp32; an fp16 copy of S in LDS
+// is the B operand of the products that read it, and the fp16 copy of U is the B operand of the
+// state update.  A block has two groups of four wavefronts: the first carries the dependent chain
+// (U, then S1), the second produces the output (Qg S0^T + P U) from the same two LDS copies and
+// merges / stores it one step later, so that only the products that read U stand between the two
+// barriers of a step.  Phase 1 splits the chunk's tokens over a group's wavefronts, phase 2 splits
+// d_k, so every A operand is private to one wavefront: it is loaded from global memory straight
+// into MFMA fragment registers, three chunks ahead of use and one load at a time between the
+// matrix instructions, and LDS carries only the two exchanged copies.  Where CUs would idle
+// anyway, one extra block per (batch, head) touches the operands a dozen chunks ahead so that those
+// loads hit in L2.  Per chunk: two block barriers (U ready, S ready).
 //
 // MFMA work per chunk and block: (2 d + 2 d + 2 C + 2 d) C BV FLOP; the path is bound by the
 // length of the dependent chain (L / C steps), not by MFMA throughput.
@@ -203,13 +205,8 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         asm volatile("" ::"v"(sink));   // keeps the loads alive; the values are not used
         return;
     }
-#ifdef NATS_DEBUG_PLAIN_MAP
-    const int xcd = 0, slot = blockIdx.x % NSL + NSL * 0;
-    const int bh = blockIdx.x / NSL + 0 * xcd;
-#else
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int bh = (slot / NSL) * 8 + xcd;
-#endif
     if (bh >= BH) return;
     const int v0 = (slot % NSL) * BV;
     const size_t gc0 = (size_t)bh * n_chunks;
@@ -254,12 +251,10 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             const size_t gcn = gc0 + min(c + PF_DIST, n_chunks - 1);
             int piece = 0;
             auto one_load = [&]() __attribute__((always_inline)) {
-#ifndef NATS_DEBUG_NO_PREFETCH
                 __builtin_amdgcn_sched_barrier(0);
                 if (piece < CS_t::N_PIECES) nxt.load_piece(piece, WF, KdF, UtF, gamC, gcn, v0, w4, lane);
                 ++piece;
                 __builtin_amdgcn_sched_barrier(0);
-#endif
             };
             // phase 1: U = U~ - W S0^T for this wavefront's 16 tokens
             half8 fs[KS_D][NT];
@@ -397,19 +392,14 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         };
 
         auto step = [&](int c, const OS_t& cur, OS_t& nxt) __attribute__((always_inline)) {
-#ifdef NATS_DEBUG_IDLE_OUTPUT
-            __syncthreads(); __syncthreads(); return;
-#endif
             const int cn = min(c + PF_DIST, n_chunks - 1);
             const half_t* onla_n = onla_ptr(cn);
             int piece = 0;
             auto one_load = [&]() __attribute__((always_inline)) {
-#ifndef NATS_DEBUG_NO_PREFETCH
                 __builtin_amdgcn_sched_barrier(0);
                 if (piece < OS_t::N_PIECES) nxt.load_piece(piece, QF, PF, onla_n, gc0 + cn, w4, lane);
                 ++piece;
                 __builtin_amdgcn_sched_barrier(0);
-#endif
             };
             // rows of the previous chunk first: the chain group's reads of the state copy get the LDS
             // to themselves for a few hundred cycles
@@ -460,7 +450,6 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             if (c + 2 < n_chunks) step(c + 2, stC, stB);
             if (c + 3 < n_chunks) step(c + 3, stD, stC);
         }
-#ifndef NATS_DEBUG_IDLE_OUTPUT
         // rows of the last chunk
         switch ((n_chunks - 1) & 3) {
             case 0: store_rows(n_chunks - 1, stA); break;
@@ -468,7 +457,6 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             case 2: store_rows(n_chunks - 1, stC); break;
             default: store_rows(n_chunks - 1, stD); break;
         }
-#endif
     }
 }
 
@@ -501,13 +489,10 @@ nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void*
                                   const void* UtF, const void* PF, const float* gamC, const float* S0,
                                   float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
                                   int32_t* progress, hipStream_t st) {
-#ifndef NATS_SCAN_BV128
-#define NATS_SCAN_BV128 32
-#endif
     if (pl.d == 64)
         return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, O_nla_h, O,
                                      progress, st);
-    return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
+    return launch_scan_t<128, 32>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
                                                O_nla_h, O, progress, st);
 }
 
