@@ -105,6 +105,9 @@ typedef struct nats_fwd_extra {
     float* O_nla;               /* out [B,H,L,d] f32 softmax-branch output (Eq. 11)              */
     float* lse;                 /* out [B,H,L] f32 log-sum-exp of the visible logits; -inf where
                                    no softmax token is visible (then O_nla = 0)                  */
+    const float* W_out;         /* in  [H,2,d] f32 or NULL.  With combine_mode 1: the weights of Eq. 21
+                                   are computed from Q by Eq. 22, [w_nla, w_la] = softmax([W_out[h,0] . q_t,
+                                   W_out[h,1] . q_t]); w_nla and w_la must then be NULL                  */
 } nats_fwd_extra;
 
 /* Bytes of device workspace nats_hybrid_attn_fwd{,_ex} needs for these params
@@ -165,6 +168,13 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
                                     const float* alpha, const float* beta, const uint8_t* mask,
                                     const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
                                     void* hip_stream);
+
+/* Weights of the merge by Eq. 22 as a call of its own (the forward does the same when W_out is given):
+ *   Q [B,H,L,d] dtype p->dtype (L = 1 for a generation step; only B, H, L, d, dtype of p are used),
+ *   W_out [H,2,d] f32  ->  w_nla, w_la [B,H,L] f32,  [w_nla, w_la] = softmax([W_out[h,0] . q, W_out[h,1] . q]).
+ * The paper maps "the attention q values" to the weights; the Q given here is used as it is. */
+nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const float* W_out, float* w_nla,
+                               float* w_la, void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
  * Generation with routing per chunk (Section 4.1, per-token generation)

@@ -120,6 +120,21 @@ def combine(o_la, o_nla, mode=0, w_nla=None, w_la=None, eps=1e-6):
     return w_nla[:, None] * rms_norm_rows(o_nla, eps) + w_la[:, None] * rms_norm_rows(o_la, eps)
 
 
+def eq22_weights(Q, W_out):
+    """Weights of the merge, Eq. 22: [w_nla, w_la] = softmax([W_nla q_t, W_la q_t]) per token and head.
+
+    Q [B,H,L,d]; W_out [H,2,d] (row 0: W_nla, row 1: W_la of the head).  Returns (w_nla, w_la) [B,H,L].
+    The paper takes "the attention q values"; the Q handed to the operator is used as it is.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    W = np.asarray(W_out, dtype=np.float64)
+    logits = np.einsum("bhld,hkd->bhlk", Q, W)
+    logits = logits - logits.max(axis=-1, keepdims=True)
+    e = np.exp(logits)
+    w = e / e.sum(axis=-1, keepdims=True)
+    return w[..., 0], w[..., 1]
+
+
 # --------------------------------------------------------------------------- #
 # whole operator for one (batch, head), and over [B,H,...]
 # --------------------------------------------------------------------------- #

@@ -40,7 +40,7 @@ class FwdExtra(ctypes.Structure):
                 ("final_state", ctypes.c_void_p), ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
                 ("cap", ctypes.c_int32), ("n_s", ctypes.c_void_p), ("idx", ctypes.c_void_p),
                 ("cnt", ctypes.c_void_p), ("O_la", ctypes.c_void_p), ("O_nla", ctypes.c_void_p),
-                ("lse", ctypes.c_void_p)]
+                ("lse", ctypes.c_void_p), ("W_out", ctypes.c_void_p)]
 
 
 class DecChunkState(ctypes.Structure):
@@ -58,7 +58,7 @@ class DecParams(ctypes.Structure):
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
-           "nats_hybrid_attn_decode_commit")
+           "nats_hybrid_attn_decode_commit", "nats_merge_weights")
 
 
 def library_path() -> str:
@@ -143,7 +143,7 @@ _EX_OUTPUTS = ("final_state", "Kc", "Vc", "n_s", "idx", "cnt", "O_la", "O_nla", 
 def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
                        la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
                        math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, w_nla=None, w_la=None,
-                       initial_state=None,
+                       W_out=None, initial_state=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
                        workspace=None) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
@@ -192,7 +192,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                      w_la.data_ptr() if w_la is not None else None,
                      initial_state.data_ptr() if initial_state is not None else None,
                      g("final_state"), g("Kc"), g("Vc"), cap if "Kc" in want else 0, g("n_s"), g("idx"),
-                     g("cnt"), g("O_la"), g("O_nla"), g("lse"))
+                     g("cnt"), g("O_la"), g("O_nla"), g("lse"), W_out.data_ptr() if W_out is not None else None)
     _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
                                        _ptr(mask), _ptr(O), ctypes.byref(extra), _ptr(workspace),
                                        workspace.numel(), _stream_ptr()))
@@ -248,6 +248,19 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
                                        _stream_ptr()))
     return o
+
+
+def merge_weights(Q, W_out):
+    """nats_merge_weights (Eq. 22): Q [B,H,L,d], W_out [H,2,d] f32 -> (w_nla, w_la) [B,H,L] f32."""
+    lib = load_library()
+    B, H, L, d = Q.shape
+    _require(Q, "Q", (B, H, L, d), Q.dtype)
+    _require(W_out, "W_out", (H, 2, d), torch.float32)
+    w_nla = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
+    w_la = torch.empty_like(w_nla)
+    params = make_fwd_params(B, H, L, d, 64, _dtype_code(Q))
+    _check(lib.nats_merge_weights(ctypes.byref(params), _ptr(Q), _ptr(W_out), _ptr(w_nla), _ptr(w_la), _stream_ptr()))
+    return w_nla, w_la
 
 
 def _chunk_state(st: Dict[str, torch.Tensor]):

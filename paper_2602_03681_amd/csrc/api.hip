@@ -137,6 +137,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
     pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = pl->off_prog = 0;
     pl->off_snap = 0;
+    pl->off_wout = off; off = align_up(off + 2 * n_tok * 4, 256);   // weights of Eq. 21 when computed by Eq. 22
     if (!uses_chunk_path(*pl) && pl->routing == NATS_ROUTE_CHUNK) {   // chunk-start state of the fp32 recurrence
         pl->off_snap = off; off = align_up(off + (size_t)pl->BH * pl->d * pl->d * 4, 256);
     }
@@ -163,7 +164,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 101; }
+int nats_abi_version(void) { return 102; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -238,8 +239,12 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (extra) ex = *extra;
     if ((ex.Kc == nullptr) != (ex.Vc == nullptr)) { set_error("extra.Kc and extra.Vc must be given together"); return NATS_ERR_NULL; }
     if (ex.Kc != nullptr && ex.cap <= 0) { set_error("extra.cap must be positive when Kc/Vc are given"); return NATS_ERR_SHAPE; }
+    if (ex.W_out != nullptr && (ex.w_nla != nullptr || ex.w_la != nullptr)) {
+        set_error("extra.W_out (weights by Eq. 22) and extra.w_nla / w_la (given weights) exclude each other");
+        return NATS_ERR_SHAPE;
+    }
     const void* ptrs[] = {Q, K, V, alpha, beta, mask, O, workspace, ex.w_nla, ex.w_la, ex.initial_state,
-                          ex.final_state, ex.Kc, ex.Vc, ex.n_s, ex.idx, ex.cnt, ex.O_la, ex.O_nla, ex.lse};
+                          ex.final_state, ex.Kc, ex.Vc, ex.n_s, ex.idx, ex.cnt, ex.O_la, ex.O_nla, ex.lse, ex.W_out};
     for (const void* ptr : ptrs)
         if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
     if (O == Q || O == K || O == V) { set_error("O must not alias Q, K or V"); return NATS_ERR_SHAPE; }
@@ -258,6 +263,14 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (ex.idx) idx = ex.idx;
     if (ex.n_s) n_s = ex.n_s;
 
+    if (ex.W_out != nullptr && pl.combine_mode == 1) {   // Eq. 22: the merge weights from Q
+        float* w = reinterpret_cast<float*>(ws + pl.off_wout);
+        ProfScope ps("merge_weights", stream);
+        st = launch_merge_weights(pl.B, pl.H, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BH * pl.L, stream);
+        if (st != NATS_OK) return st;
+        ex.w_nla = w;
+        ex.w_la = w + (size_t)pl.BH * pl.L;
+    }
     // With the plain-sum merge on the chunkwise path, the compaction and the softmax branch go to
     // the side stream (forked here, joined before the kernel that merges).
     const bool fork_ok = uses_chunk_path(pl) && pl.combine_mode == 0;
@@ -381,6 +394,25 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
     ProfScope ps("decode", stream);
     return launch_decode(*p, scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
                          mask, w_nla, w_la, o, err_flags, stream);
+}
+
+nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const float* W_out, float* w_nla,
+                               float* w_la, void* hip_stream) {
+    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
+    if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {
+        set_error("dtype %d is neither NATS_F32 nor NATS_BF16", p->dtype);
+        return NATS_ERR_DTYPE;
+    }
+    if (p->B <= 0 || p->H <= 0 || p->L <= 0) {
+        set_error("B, H, L must be positive (got %d, %d, %d)", p->B, p->H, p->L);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
+    if (!Q || !W_out || !w_nla || !w_la) { set_error("Q, W_out, w_nla and w_la must be non-NULL"); return NATS_ERR_NULL; }
+    if (!aligned16(Q) || !aligned16(W_out)) { set_error("Q and W_out must be 16-byte aligned"); return NATS_ERR_ALIGN; }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("merge_weights", stream);
+    return launch_merge_weights(p->B, p->H, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, stream);
 }
 
 static nats_status validate_dec_params(const nats_dec_params* p) {

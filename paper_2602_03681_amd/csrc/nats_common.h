@@ -117,7 +117,7 @@ struct FwdPlan {
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah, off_prog, off_snap;
+    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah, off_prog, off_snap, off_wout;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
@@ -155,6 +155,8 @@ nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, f
                                 void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
                                 const void* v, const float* alpha, const float* beta, const float* w_nla,
                                 const float* w_la, void* o, int32_t* err_flags, hipStream_t st);
+nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const void* Q, const float* W_out,
+                                 float* w_nla, float* w_la, hipStream_t st);
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,
                                  const float* chunk_decay, int32_t* chunk_pos, int32_t* cache_len,
                                  const uint8_t* mask_c, int32_t* err_flags, hipStream_t st);

@@ -37,7 +37,7 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 101   # 101: nats_fwd_params gained `routing`
+    assert lib.nats_abi_version() == 102   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`
 
 
 def good_params(**over):

@@ -258,3 +258,28 @@ def test_forward_in_a_hip_graph_replays():
         torch.cuda.synchronize()
         assert torch.equal(O, eager[i]), f"replay with input set {i} differs from the eager result"
     assert rel_err(host(eager[0]), oracle_fwd(xs[0], want=())["O"], stored="bf16") <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_eq22_merge_weights_kernel_and_forward(dtype, d):
+    """Eq. 22 on the device: the weights as a call of their own, and the forward given W_out against the
+    oracle's Eq. 21 with the oracle's Eq. 22 weights."""
+    from oracle import nats_oracle as no
+    B, H, L = 2, 3, 320
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.1, seed=80 + d)
+    rng = np.random.default_rng(81)
+    W = (rng.standard_normal((H, 2, d)) * 2.0).astype(np.float32)
+    w_ref = no.eq22_weights(x["Q"], W)
+    g = to_dev(x, dtype)
+    Wd = torch.from_numpy(W).cuda()
+    w_nla, w_la = nats.merge_weights(g["Q"], Wd)
+    torch.cuda.synchronize()
+    assert np.abs(host(w_nla) - w_ref[0]).max() <= 2e-6 and np.abs(host(w_la) - w_ref[1]).max() <= 2e-6
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, combine_mode=1,
+                                W_out=Wd)
+    torch.cuda.synchronize()
+    ref = oracle_fwd(x, mode=1, w_nla=w_ref[0], w_la=w_ref[1], want=())
+    assert rel_err(host(r["O"]), ref["O"], stored(dtype)) <= TOL[dtype]
+    with pytest.raises(nb.NatsError):   # given weights and W_out exclude each other
+        nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, combine_mode=1,
+                                W_out=Wd, w_nla=w_nla)

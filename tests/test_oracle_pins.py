@@ -354,3 +354,29 @@ def test_c_and_numpy_agree_on_generated_workload():
         for h in range(3):
             n = r_np["n_s"][b, h]
             np.testing.assert_array_equal(r_c["idx"][b, h, :n], r_np["idx"][b][h])
+
+
+# --- Eq. 22: the merge weights from the queries ---------------------------------------------- #
+def test_eq22_weights_against_library_softmax_and_closed_forms():
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((2, 3, 7, 16))
+    W = rng.standard_normal((3, 2, 16))
+    w_nla, w_la = npo.eq22_weights(Q, W)
+    logits = torch.einsum("bhld,hkd->bhlk", torch.from_numpy(Q), torch.from_numpy(W))
+    ref = torch.softmax(logits, dim=-1).numpy()
+    np.testing.assert_allclose(w_nla, ref[..., 0], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(w_la, ref[..., 1], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(w_nla + w_la, 1.0, rtol=0, atol=1e-15)
+    # equal weight vectors give 1/2 each; swapping the two rows swaps the two weights
+    Weq = np.repeat(W[:, :1], 2, axis=1)
+    a, b = npo.eq22_weights(Q, Weq)
+    np.testing.assert_allclose(a, 0.5, atol=1e-15)
+    np.testing.assert_allclose(b, 0.5, atol=1e-15)
+    a, b = npo.eq22_weights(Q, W[:, ::-1])
+    np.testing.assert_allclose(a, w_la, atol=1e-15)
+    np.testing.assert_allclose(b, w_nla, atol=1e-15)
+    # a head's weights depend on that head's rows of W only
+    W2 = W.copy(); W2[1, 0] += 1.0
+    a2, _ = npo.eq22_weights(Q, W2)
+    np.testing.assert_allclose(a2[:, 0], w_nla[:, 0], atol=0)
+    assert np.abs(a2[:, 1] - w_nla[:, 1]).max() > 1e-3
