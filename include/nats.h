@@ -169,6 +169,18 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
                                     const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
                                     void* hip_stream);
 
+/* Routing decision per chunk by the score layer (Section 4.1, Eq. 8-9): the layer's input features are
+ * mean-pooled over each chunk of C tokens, one linear layer maps the mean to a score per head and
+ * operation, and the operation with the higher score gets the chunk.
+ *   X      : in  [B,L,d_model] dtype (NATS_F32 or NATS_BF16); d_model a multiple of 8, at most 65536
+ *   W_s    : in  [H,2,d_model] f32; row 0 of a head scores softmax attention, row 1 the linear operation
+ *   scores : out [B,L/C,H,2] f32 or NULL
+ *   mask_c : out [B,H,L/C] u8, 1 = softmax chunk (score 0 >= score 1, decided on the fp32 scores), the
+ *            mask nats_hybrid_attn_fwd takes with routing = NATS_ROUTE_CHUNK
+ * L must be a multiple of C; H at most 32. */
+nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, int32_t H, int32_t dtype,
+                              const void* X, const float* W_s, float* scores, uint8_t* mask_c, void* hip_stream);
+
 /* Weights of the merge by Eq. 22 as a call of its own (the forward does the same when W_out is given):
  *   Q [B,H,L,d] dtype p->dtype (L = 1 for a generation step; only B, H, L, d, dtype of p are used),
  *   W_out [H,2,d] f32  ->  w_nla, w_la [B,H,L] f32,  [w_nla, w_la] = softmax([W_out[h,0] . q, W_out[h,1] . q]).

@@ -174,6 +174,17 @@ def make_chunk_mask(B: int, H: int, n_chunks: int, p_softmax: float, seed: int,
     return np.ascontiguousarray(mask, dtype=np.uint8)
 
 
+def make_score_inputs(B: int, L: int, d_model: int, H: int, dtype: str, seed: int) -> Dict[str, np.ndarray]:
+    """Inputs of the score layer: hidden states X [B,L,d_model] (unit variance, as after a normalisation
+    layer; representable in `dtype`) and the layer's weights W_s [H,2,d_model] float32 (variance 1/d_model)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    X = _normal32(rng, (B, L, d_model))
+    if dtype == "bf16":
+        X = round_to_bf16(X)
+    W_s = _normal32(rng, (H, 2, d_model)) / np.float32(np.sqrt(d_model))
+    return {"X": X, "W_s": np.ascontiguousarray(W_s, dtype=np.float32)}
+
+
 def make_config_inputs(cfg: FwdConfig) -> Dict[str, np.ndarray]:
     return make_fwd_inputs(cfg.B, cfg.H, cfg.L, cfg.d, cfg.dtype, cfg.p_softmax, cfg.seed,
                            n_runs=cfg.n_runs, run_len=cfg.run_len)

@@ -120,6 +120,21 @@ def combine(o_la, o_nla, mode=0, w_nla=None, w_la=None, eps=1e-6):
     return w_nla[:, None] * rms_norm_rows(o_nla, eps) + w_la[:, None] * rms_norm_rows(o_la, eps)
 
 
+def route_chunks(X, W_s, C):
+    """Score layer and routing decision, Eq. 8-9: mean-pool X [B,L,d_model] over chunks of C tokens, map the mean
+    with W_s [H,2,d_model] to one score per head and operation (0: softmax attention, 1: linear), give the
+    chunk to the operation with the highest score (the first one on a tie, as argmax does).
+
+    Returns (mask_c [B,H,L/C] uint8, scores [B,L/C,H,2])."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W_s, dtype=np.float64)
+    B, L, dm = X.shape
+    pooled = X.reshape(B, L // C, C, dm).mean(axis=2)
+    scores = np.einsum("bcd,hkd->bchk", pooled, W)
+    mask_c = (np.argmax(scores, axis=-1) == 0).astype(np.uint8).transpose(0, 2, 1)
+    return np.ascontiguousarray(mask_c), scores
+
+
 def eq22_weights(Q, W_out):
     """Weights of the merge, Eq. 22: [w_nla, w_la] = softmax([W_nla q_t, W_la q_t]) per token and head.
 

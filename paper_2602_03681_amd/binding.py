@@ -58,7 +58,7 @@ class DecParams(ctypes.Structure):
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
-           "nats_hybrid_attn_decode_commit", "nats_merge_weights")
+           "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks")
 
 
 def library_path() -> str:
@@ -85,6 +85,14 @@ def load_library():
                                             + [ctypes.POINTER(FwdExtra), vp, ctypes.c_size_t, vp])
     lib.nats_hybrid_attn_decode.restype = ctypes.c_int
     lib.nats_hybrid_attn_decode.argtypes = [ctypes.POINTER(DecParams)] + [vp] * 15
+    lib.nats_hybrid_attn_decode_chunk.restype = ctypes.c_int
+    lib.nats_hybrid_attn_decode_chunk.argtypes = [ctypes.POINTER(DecParams), ctypes.POINTER(DecChunkState)] + [vp] * 10
+    lib.nats_hybrid_attn_decode_commit.restype = ctypes.c_int
+    lib.nats_hybrid_attn_decode_commit.argtypes = [ctypes.POINTER(DecParams), ctypes.POINTER(DecChunkState)] + [vp] * 3
+    lib.nats_merge_weights.restype = ctypes.c_int
+    lib.nats_merge_weights.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 5
+    lib.nats_route_chunks.restype = ctypes.c_int
+    lib.nats_route_chunks.argtypes = [ctypes.c_int32] * 6 + [vp] * 5
     lib.nats_last_error.restype = ctypes.c_char_p
     lib.nats_abi_version.restype = ctypes.c_int
     lib.nats_probe_mfma.restype = ctypes.c_double
@@ -248,6 +256,21 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
                                        _stream_ptr()))
     return o
+
+
+def route_chunks(X, W_s, C: int = 64, want_scores: bool = True):
+    """nats_route_chunks (Eq. 8-9): X [B,L,d_model], W_s [H,2,d_model] f32 -> (mask_c [B,H,L/C] u8, scores
+    [B,L/C,H,2] f32 or None)."""
+    lib = load_library()
+    B, L, dm = X.shape
+    H = W_s.shape[0]
+    _require(X, "X", (B, L, dm), X.dtype)
+    _require(W_s, "W_s", (H, 2, dm), torch.float32)
+    mask_c = torch.empty((B, H, L // C), dtype=torch.uint8, device=X.device)
+    scores = torch.empty((B, L // C, H, 2), dtype=torch.float32, device=X.device) if want_scores else None
+    _check(lib.nats_route_chunks(B, L, C, dm, H, _dtype_code(X), _ptr(X), _ptr(W_s), _ptr(scores), _ptr(mask_c),
+                                 _stream_ptr()))
+    return mask_c, scores
 
 
 def merge_weights(Q, W_out):

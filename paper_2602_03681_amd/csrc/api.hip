@@ -415,6 +415,27 @@ nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const fl
     return launch_merge_weights(p->B, p->H, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, stream);
 }
 
+nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, int32_t H, int32_t dtype,
+                              const void* X, const float* W_s, float* scores, uint8_t* mask_c, void* hip_stream) {
+    if (dtype != NATS_F32 && dtype != NATS_BF16) { set_error("dtype %d is neither NATS_F32 nor NATS_BF16", dtype); return NATS_ERR_DTYPE; }
+    if (B <= 0 || L <= 0 || C <= 0 || H <= 0 || d_model <= 0) {
+        set_error("B, L, C, H, d_model must be positive (got %d, %d, %d, %d, %d)", B, L, C, H, d_model);
+        return NATS_ERR_SHAPE;
+    }
+    if (L % C != 0) { set_error("L (%d) must be a multiple of C (%d)", L, C); return NATS_ERR_SHAPE; }
+    if (H > 32) { set_error("H must not exceed 32 (got %d)", H); return NATS_ERR_SHAPE; }
+    if (d_model % 8 != 0 || d_model > 65536) {
+        set_error("d_model must be a multiple of 8 and at most 65536 (got %d)", d_model);
+        return NATS_ERR_SHAPE;
+    }
+    if ((long long)B * (L / C) > (1ll << 31) - 1) { set_error("B * L / C must fit in 31 bits"); return NATS_ERR_SHAPE; }
+    if (!X || !W_s || !mask_c) { set_error("X, W_s and mask_c must be non-NULL"); return NATS_ERR_NULL; }
+    if (!aligned16(X) || !aligned16(W_s)) { set_error("X and W_s must be 16-byte aligned"); return NATS_ERR_ALIGN; }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("route_chunks", stream);
+    return launch_route_chunks(B, L, C, d_model, H, dtype, X, W_s, scores, mask_c, stream);
+}
+
 static nats_status validate_dec_params(const nats_dec_params* p) {
     if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
     if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {

@@ -155,6 +155,8 @@ nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, f
                                 void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
                                 const void* v, const float* alpha, const float* beta, const float* w_nla,
                                 const float* w_la, void* o, int32_t* err_flags, hipStream_t st);
+nats_status launch_route_chunks(int B, int L, int C, int d_model, int H, int dtype, const void* X, const float* W_s,
+                                float* scores, uint8_t* mask_c, hipStream_t st);
 nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const void* Q, const float* W_out,
                                  float* w_nla, float* w_la, hipStream_t st);
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,

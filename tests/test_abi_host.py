@@ -137,6 +137,23 @@ def test_chunk_routing_validation(lib):
     assert lib.nats_hybrid_attn_decode_commit(ctypes.byref(good), None, FAKE, None, None) == E_NULL
 
 
+def test_route_chunks_and_merge_weights_validation(lib):
+    """Every rejected call returns before anything is launched (the pointers are fake)."""
+    rc = lambda *a: lib.nats_route_chunks(*a, None)
+    assert rc(2, 250, 64, 1536, 6, nb.NATS_BF16, FAKE, FAKE + 64, None, FAKE + 128) == E_SHAPE     # L % C
+    assert rc(2, 256, 64, 1537, 6, nb.NATS_BF16, FAKE, FAKE + 64, None, FAKE + 128) == E_SHAPE     # d_model % 8
+    assert rc(2, 256, 64, 65544, 6, nb.NATS_BF16, FAKE, FAKE + 64, None, FAKE + 128) == E_SHAPE    # d_model too large
+    assert rc(2, 256, 64, 1536, 40, nb.NATS_BF16, FAKE, FAKE + 64, None, FAKE + 128) == E_SHAPE    # H
+    assert rc(2, 256, 64, 1536, 6, 9, FAKE, FAKE + 64, None, FAKE + 128) == E_DTYPE
+    assert rc(2, 256, 64, 1536, 6, nb.NATS_BF16, None, FAKE + 64, None, FAKE + 128) == E_NULL
+    assert rc(2, 256, 64, 1536, 6, nb.NATS_BF16, FAKE + 4, FAKE + 64, None, FAKE + 128) == E_ALIGN
+    p = good_params()
+    mw = lambda *a: lib.nats_merge_weights(ctypes.byref(p), *a, None)
+    assert mw(None, FAKE, FAKE, FAKE) == E_NULL
+    assert mw(FAKE + 4, FAKE, FAKE, FAKE) == E_ALIGN
+    assert lib.nats_merge_weights(ctypes.byref(good_params(d=96)), FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(nb, "_lib", None)
     monkeypatch.setattr(nb, "_LIB_PATH", str(tmp_path / "libnats.so"))

@@ -148,3 +148,69 @@ def test_generation_cache_overflow_is_flagged():
                 assert int(cerr.sum()) == B * H          # 128 rows do not fit into 70
     assert flagged_at == cap                             # token index 70 is the first one without a row
     np.testing.assert_array_equal(host(st["cache_len"]), cap)
+
+
+# ---- the score layer on the device (Eq. 8-9) ------------------------------------------------------------
+
+def run_route(x, dtype):
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    X = torch.from_numpy(x["X"]).to(tdt).cuda()
+    W = torch.from_numpy(x["W_s"]).cuda()
+    mask_c, scores = nats.route_chunks(X, W, C)
+    torch.cuda.synchronize()
+    return mask_c, scores
+
+
+@pytest.mark.parametrize("B,L,dm,H", [(2, 512, 1536, 6), (1, 64, 8, 1), (3, 1024, 2048, 16), (1, 192, 4088, 32), (1, 128, 8200, 3), (4, 32960, 64, 5)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_route_chunks_scores_and_mask(dtype, B, L, dm, H):
+    from nats_inputs import make_score_inputs
+    from oracle import nats_oracle
+    x = make_score_inputs(B, L, dm, H, dtype, seed=31 + dm)
+    mask_c, scores = run_route(x, dtype)
+    ref_mask, ref_scores = nats_oracle.route_chunks(x["X"], x["W_s"], C)
+    s = host(scores)
+    assert s.shape == ref_scores.shape and tuple(mask_c.shape) == ref_mask.shape
+    assert rel_err(s, ref_scores) <= TOL["f32"]       # fp32 sums of exact inputs, whatever X is stored in
+    m = host(mask_c)
+    # the decision is taken in fp32 on the device: it is exactly the argmax of the device's own scores ...
+    own = (s[..., 0] >= s[..., 1]).astype(np.uint8).transpose(0, 2, 1)
+    assert np.array_equal(m, own)
+    # ... and equals the oracle's wherever the two scores are further apart than the fp32 error could bridge
+    margin = np.abs(ref_scores[..., 0] - ref_scores[..., 1]).transpose(0, 2, 1)
+    rms = np.sqrt(np.mean(ref_scores ** 2))
+    clear = margin > 2 * TOL["f32"] * rms
+    assert clear.mean() > 0.99
+    assert np.array_equal(m[clear], ref_mask[clear])
+
+
+def test_route_chunks_tie_goes_to_softmax_and_scores_are_optional():
+    from nats_inputs import make_score_inputs
+    x = make_score_inputs(2, 256, 512, 4, "bf16", seed=5)
+    x["W_s"][1] = 0.0                      # head 1: both scores are exactly zero
+    x["W_s"][2, 1] = x["W_s"][2, 0]        # head 2: both scores are the same sum
+    mask_c, scores = run_route(x, "bf16")
+    assert host(mask_c)[:, 1].all() and host(mask_c)[:, 2].all()
+    X = torch.from_numpy(x["X"]).to(torch.bfloat16).cuda()
+    m2, none = nats.route_chunks(X, torch.from_numpy(x["W_s"]).cuda(), C, want_scores=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(m2, mask_c)
+
+
+def test_route_chunks_feeds_the_forward():
+    """Mask produced on the device goes straight into the chunk-routed forward, no host round trip."""
+    from nats_inputs import make_score_inputs
+    from oracle import nats_oracle
+    B, H, L, d = 2, 4, 512, 64
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=77)
+    sx = make_score_inputs(B, L, H * d, H, "bf16", seed=78)
+    mask_c, _ = run_route(sx, "bf16")
+    ref_mask, _ = nats_oracle.route_chunks(sx["X"], sx["W_s"], C)
+    assert np.array_equal(host(mask_c), ref_mask)   # seed chosen with every margin clear of rounding
+    g = to_dev(x, "bf16")
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], mask_c, C,
+                                routing=nb.NATS_ROUTE_CHUNK, want=())
+    torch.cuda.synchronize()
+    x["mask"] = ref_mask
+    ref = oracle(x, want=("O",))
+    assert rel_err(host(r["O"]), ref["O"], stored("bf16")) <= TOL["bf16"]

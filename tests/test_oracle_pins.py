@@ -380,3 +380,26 @@ def test_eq22_weights_against_library_softmax_and_closed_forms():
     a2, _ = npo.eq22_weights(Q, W2)
     np.testing.assert_allclose(a2[:, 0], w_nla[:, 0], atol=0)
     assert np.abs(a2[:, 1] - w_nla[:, 1]).max() > 1e-3
+
+
+# --- Eq. 8-9: score layer and routing decision ------------------------------------------------ #
+def test_route_chunks_against_library_pooling_and_argmax():
+    rng = np.random.default_rng(6)
+    B, L, dm, H, C = 2, 48, 24, 3, 8
+    X = rng.standard_normal((B, L, dm))
+    W = rng.standard_normal((H, 2, dm))
+    mask_c, scores = npo.route_chunks(X, W, C)
+    pooled = torch.nn.functional.avg_pool1d(torch.from_numpy(X).transpose(1, 2), C).transpose(1, 2)   # [B, L/C, dm]
+    ref = torch.nn.functional.linear(pooled, torch.from_numpy(W).reshape(2 * H, dm)).reshape(B, L // C, H, 2).numpy()
+    np.testing.assert_allclose(scores, ref, rtol=0, atol=1e-13)
+    assert mask_c.shape == (B, H, L // C) and mask_c.dtype == np.uint8
+    np.testing.assert_array_equal(mask_c, (ref[..., 0] >= ref[..., 1]).transpose(0, 2, 1))
+    # a chunk of identical tokens scores like one of its tokens; scaling one operation's row flips the choice
+    Xc = np.repeat(X[:, ::C], C, axis=1)
+    _, s2 = npo.route_chunks(Xc, W, C)
+    np.testing.assert_allclose(s2, np.einsum("bcd,hkd->bchk", X[:, ::C], W), rtol=0, atol=1e-13)
+    W_flip = W.copy(); W_flip[:, 0] = W[:, 1]; W_flip[:, 1] = W[:, 0]
+    m_flip, _ = npo.route_chunks(X, W_flip, C)
+    assert np.array_equal(m_flip, 1 - mask_c)       # no ties in random data
+    m_tie, _ = npo.route_chunks(X, np.repeat(W[:, :1], 2, axis=1), C)
+    assert m_tie.min() == 1                          # a tie goes to operation 0, as argmax does
