@@ -81,7 +81,7 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
-    float eps) {
+    float eps, int BH) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -102,9 +102,18 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int bh = blockIdx.y;
-    // later query tiles see more keys: dispatch them first so that the long blocks do not form the tail
-    const int q0 = (gridDim.x - 1 - blockIdx.x) * FL_BM;
+    // One-dimensional grid over (batch, head) pairs (padded to a multiple of 8) and query tiles.  Later
+    // tiles see more keys and are dispatched first, so that the long blocks do not form the tail.
+    // Routing per token: tile-major, the blocks of one tile side by side, one per pair; a pair's blocks
+    // then always land on the same XCD and share its L2 for the compacted keys (measured 71 against 85
+    // microseconds on the headline shape).  Routing per chunk, where every block also streams its own
+    // 128 rows of K and V: pair-major, neighbouring blocks read neighbouring rows (136 against 149).
+    const int bh8 = (BH + 7) & ~7;
+    const int n_tiles_g = gridDim.x / bh8;
+    const int bh = chunk_routing ? blockIdx.x / n_tiles_g : blockIdx.x % bh8;
+    const int tile = n_tiles_g - 1 - (chunk_routing ? blockIdx.x % n_tiles_g : blockIdx.x / bh8);
+    if (bh >= BH) return;
+    const int q0 = tile * FL_BM;
     const size_t tokbase = (size_t)bh * L;
     const float scale2 = scale * 1.44269504088896341f;   // logits in base-2 units
 
@@ -403,17 +412,17 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
                       const void* V, const int32_t* cnt,
                       const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
-    dim3 grid((pl.L + FL_BM - 1) / FL_BM, pl.BH);
+    dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BH + 7) & ~7)));
     if (pl.routing == NATS_ROUTE_CHUNK)
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BH);
     else
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BH);
 }
 
 // O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.

@@ -25,7 +25,7 @@
 //   UtF [chunk][vt < d/16][w][lane][4] =  U~[tok = 16w + 4 lq + j][d_v = 16 vt + l16]
 //   gamC[chunk]                        (fp32)
 //
-// One block per chunk (grid: chunks x B*H), 4 wavefronts.  All matrix products run on
+// One block per chunk and (batch, head) (a one-dimensional grid, chunk-major), 4 wavefronts.  All matrix products run on
 // MFMA with fp16 operands / fp32 accumulation; products are arranged (transposed where
 // needed) so that every result tile is stored as 4 consecutive fp16 along the layout the
 // consumer reads.  The triangular inverse is blocked 16x16: substitution inside the four
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     int L, int chunk_mask, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
-    half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC) {
+    half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC, int BH) {
     using Lds = PrepLds<D>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NPC = CH * D / 8 / PREP_THREADS;   // 16-byte pieces of a [64][D] tile per thread
@@ -105,8 +105,14 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
     const int n_chunks = L / CH;
-    const size_t gc = (size_t)blockIdx.y * n_chunks + blockIdx.x;  // global chunk id
-    const size_t tok0 = (size_t)blockIdx.y * L + (size_t)blockIdx.x * CH;
+    // One-dimensional grid, chunk-major: all (batch, head) pairs of a chunk side by side (padded to a
+    // multiple of 8, so that a pair's blocks land on the XCD whose L2 the recurrence blocks of that pair
+    // use), the chunks front to back, the order in which the recurrence will want them.
+    const int bh8 = (BH + 7) & ~7;
+    const int chunk = blockIdx.x / bh8, bh = blockIdx.x % bh8;
+    if (bh >= BH) return;
+    const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
+    const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
 
     NATS_MARK(0);
     // ---- tiles: coalesced 16-byte loads (a [64][D] tile is contiguous in global memory) --------
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st) {
-    dim3 grid(pl.L / CH, pl.BH);
+    dim3 grid((unsigned)((pl.L / CH) * ((pl.BH + 7) & ~7)));
     // the LDS-size attribute is per function and device: set once per device, not per launch
     static bool attr_done[2][64] = {};
     int dev = 0;
@@ -396,7 +402,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<64>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
-                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
         if (!attr_done[1][dev]) {
@@ -407,7 +413,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<128>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
-                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC);
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH);
     }
     return check_launch("gdn_chunk_prep");
 }
