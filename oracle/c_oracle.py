@@ -47,10 +47,12 @@ def _f32(a):
 
 
 def fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0, w_nla=None, w_la=None,
-        eps=1e-6, S0=None, chunk_routing=0, want=("O", "O_la", "O_nla", "lse", "S", "cnt", "idx", "n_s")):
+        eps=1e-6, S0=None, chunk_routing=0, want=("O", "O_la", "O_nla", "lse", "S", "cnt", "idx", "n_s"),
+        linear_op=0, freeze_on_softmax=0):
     """Inputs [B,H,L,d] / [B,H,L]; returns a dict of fp64 / int32 arrays shaped like the inputs.
 
-    chunk_routing = C > 0: mask is [B,H,L/C], one routing decision per chunk (nats_oracle_fwd_chunk)."""
+    chunk_routing = C > 0: mask is [B,H,L/C], one routing decision per chunk (nats_oracle_fwd_chunk).
+    linear_op, freeze_on_softmax: the variants of nats_oracle_set_variant."""
     Q, K, V, alpha, beta = (_f32(a) for a in (Q, K, V, alpha, beta))
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     B, H, L, d = Q.shape
@@ -73,18 +75,22 @@ def fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0, w_
     else:
         assert mask.shape == (B, H, L)
         call = lib.nats_oracle_fwd
-    rc = call(
-        ctypes.c_int(BH), ctypes.c_int(L), ctypes.c_int(d), _p(Q), _p(K), _p(V), _p(alpha), _p(beta),
-        _p(mask), ctypes.c_double(scale), ctypes.c_double(la_scale), ctypes.c_int(mode), _p(w_nla),
-        _p(w_la), ctypes.c_double(eps), _p(S0), _p(out["O"]), _p(out.get("O_la")), _p(out.get("O_nla")),
-        _p(out.get("lse")), _p(out.get("S")), _p(out.get("cnt")), _p(out.get("idx")), _p(out.get("n_s")))
+    lib.nats_oracle_set_variant(ctypes.c_int(linear_op), ctypes.c_int(freeze_on_softmax))
+    try:
+        rc = call(
+            ctypes.c_int(BH), ctypes.c_int(L), ctypes.c_int(d), _p(Q), _p(K), _p(V), _p(alpha), _p(beta),
+            _p(mask), ctypes.c_double(scale), ctypes.c_double(la_scale), ctypes.c_int(mode), _p(w_nla),
+            _p(w_la), ctypes.c_double(eps), _p(S0), _p(out["O"]), _p(out.get("O_la")), _p(out.get("O_nla")),
+            _p(out.get("lse")), _p(out.get("S")), _p(out.get("cnt")), _p(out.get("idx")), _p(out.get("n_s")))
+    finally:
+        lib.nats_oracle_set_variant(ctypes.c_int(0), ctypes.c_int(0))
     if rc != 0:
         raise RuntimeError(f"nats_oracle_fwd returned {rc}")
     return out
 
 
 def decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, softmax_scale=None,
-           la_scale=1.0, mode=0, w_nla=None, w_la=None, eps=1e-6):
+           la_scale=1.0, mode=0, w_nla=None, w_la=None, eps=1e-6, linear_op=0, freeze_on_softmax=0):
     """In place on state (fp64 [B,H,d,d]), k_cache/v_cache (f32 [B,H,cap,d]), cache_len (i32 [B,H]).
 
     Returns (o fp64 [B,H,d], overflow i32 [B,H]).
@@ -97,11 +103,16 @@ def decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, softm
     scale = (1.0 / np.sqrt(d)) if softmax_scale is None else float(softmax_scale)
     o = np.empty((B, H, d))
     overflow = np.zeros((B, H), dtype=np.int32)
-    rc = _load().nats_oracle_decode(
-        ctypes.c_int(B * H), ctypes.c_int(d), ctypes.c_int(cap), _p(state), _p(k_cache), _p(v_cache),
-        _p(cache_len), _p(q), _p(k), _p(v), _p(alpha), _p(beta), _p(mask), ctypes.c_double(scale),
-        ctypes.c_double(la_scale), ctypes.c_int(mode), _p(_f32(w_nla)), _p(_f32(w_la)),
-        ctypes.c_double(eps), _p(o), _p(overflow))
+    lib = _load()
+    lib.nats_oracle_set_variant(ctypes.c_int(linear_op), ctypes.c_int(freeze_on_softmax))
+    try:
+        rc = lib.nats_oracle_decode(
+            ctypes.c_int(B * H), ctypes.c_int(d), ctypes.c_int(cap), _p(state), _p(k_cache), _p(v_cache),
+            _p(cache_len), _p(q), _p(k), _p(v), _p(alpha), _p(beta), _p(mask), ctypes.c_double(scale),
+            ctypes.c_double(la_scale), ctypes.c_int(mode), _p(_f32(w_nla)), _p(_f32(w_la)),
+            ctypes.c_double(eps), _p(o), _p(overflow))
+    finally:
+        lib.nats_oracle_set_variant(ctypes.c_int(0), ctypes.c_int(0))
     if rc != 0:
         raise RuntimeError(f"nats_oracle_decode returned {rc}")
     return o, overflow

@@ -57,11 +57,14 @@ def compaction(mask):
 # --------------------------------------------------------------------------- #
 # linear branch: token-recurrent Gated DeltaNet (Eq. 19 + Eq. 14 + Eq. 20)
 # --------------------------------------------------------------------------- #
-def gdn_recurrent(q, k, v, alpha, beta, mask, S0=None, la_scale=1.0, decay_on_softmax=True):
+def gdn_recurrent(q, k, v, alpha, beta, mask, S0=None, la_scale=1.0, decay_on_softmax=True, linear_op=0):
     """Returns (o_la [L,d_v], S_final [d_v,d_k]).
 
     decay_on_softmax=False is the ablation that freezes the state on softmax
     tokens (Table 4, the variant without linear-attention decay); the method itself uses True.
+    linear_op=1 replaces the delta rule by the gated linear attention of Mamba2,
+    S_t = alpha_t S_{t-1} + beta_t v_t k_t^T (appendix "Mixture of SoftmaxAttention and Mamba2
+    architecture": the linear operation is exchangeable; B = k, C = q, dt x = beta v, scalar decay).
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
     alpha = np.asarray(alpha, dtype=np.float64)
@@ -75,7 +78,7 @@ def gdn_recurrent(q, k, v, alpha, beta, mask, S0=None, la_scale=1.0, decay_on_so
         if linear or decay_on_softmax:
             S = alpha[t] * S                       # decay at every token (Eq. 20)
         if linear:                                 # write only linear tokens (Eq. 14)
-            pred = S @ k[t]                        # what the decayed state returns for k_t
+            pred = S @ k[t] if linear_op == 0 else 0.0   # what the decayed state returns for k_t (delta rule only)
             S = S + beta[t] * np.outer(v[t] - pred, k[t])   # Eq. 19 expanded
         o[t] = la_scale * (S @ q[t])               # Eq. 5
     return o, S
@@ -154,10 +157,11 @@ def eq22_weights(Q, W_out):
 # whole operator for one (batch, head), and over [B,H,...]
 # --------------------------------------------------------------------------- #
 def hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
-                w_nla=None, w_la=None, eps=1e-6, S0=None):
+                w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
     d_k = np.asarray(q).shape[-1]
     scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
-    o_la, S = gdn_recurrent(q, k, v, alpha, beta, mask, S0=S0, la_scale=la_scale)
+    o_la, S = gdn_recurrent(q, k, v, alpha, beta, mask, S0=S0, la_scale=la_scale,
+                            decay_on_softmax=decay_on_softmax, linear_op=linear_op)
     o_nla, lse = softmax_branch(q, k, v, mask, scale)
     o = combine(o_la, o_nla, mode, w_nla, w_la, eps)
     cnt, idx, n_s = compaction(mask)
@@ -166,7 +170,7 @@ def hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mo
 
 
 def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
-               w_nla=None, w_la=None, eps=1e-6, S0=None):
+               w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
     """All (b,h) of [B,H,L,d] inputs; returns dict of stacked fp64 arrays (idx as nested lists)."""
     B, H, L, _ = np.asarray(Q).shape
     d_v = np.asarray(V).shape[-1]
@@ -181,7 +185,7 @@ def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mod
                             softmax_scale, la_scale, mode,
                             None if w_nla is None else w_nla[b, h],
                             None if w_la is None else w_la[b, h], eps,
-                            None if S0 is None else S0[b, h])
+                            None if S0 is None else S0[b, h], linear_op, decay_on_softmax)
             for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]
@@ -192,7 +196,8 @@ def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mod
 # one decode step for one (batch, head) (Section 4.1, per-token generation)
 # --------------------------------------------------------------------------- #
 def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
-                softmax_scale=None, la_scale=1.0, mode=0, w_nla=0.5, w_la=0.5, eps=1e-6):
+                softmax_scale=None, la_scale=1.0, mode=0, w_nla=0.5, w_la=0.5, eps=1e-6, linear_op=0,
+                decay_on_softmax=True):
     """One token.  S [d_v,d_k] fp64; k_cache/v_cache [cap,d] with cache_len live rows.
 
     Returns (o [d_v], S_new, k_cache, v_cache, cache_len_new, overflow).  A softmax
@@ -202,10 +207,10 @@ def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
     scale = (1.0 / np.sqrt(q.shape[0])) if softmax_scale is None else softmax_scale
-    S = float(alpha) * np.array(S, dtype=np.float64)
+    S = (float(alpha) if (m == 0 or decay_on_softmax) else 1.0) * np.array(S, dtype=np.float64)
     overflow = False
     if m == 0:
-        S = S + float(beta) * np.outer(v - S @ k, k)
+        S = S + float(beta) * np.outer(v - (S @ k if linear_op == 0 else 0.0), k)
     else:
         if cache_len < k_cache.shape[0]:
             k_cache = np.array(k_cache, dtype=np.float64)
@@ -270,7 +275,7 @@ def gdn_chunkwise(q, k, v, alpha, beta, mask, C, S0=None, la_scale=1.0):
 # chunk, after the whole chunk has been seen)
 # --------------------------------------------------------------------------- #
 def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
-                             w_nla=None, w_la=None, eps=1e-6, S0=None):
+                             w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
     """One (batch, head) with one routing decision per chunk of C tokens (mask_c[c] = 1: softmax chunk).
 
     Section 4.1: a chunk's type is known only once the whole chunk has been seen, so both
@@ -284,6 +289,8 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
         Eq. 12 at chunk granularity) and, causally, to the tokens j <= t of its own chunk whatever
         its type.
     cnt / idx / n_s describe the compaction of the tokens of softmax chunks.
+    linear_op, decay_on_softmax: the variants of gdn_recurrent (without decay on softmax chunks the state
+    after such a chunk is the chunk-start state itself).
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
     alpha = np.asarray(alpha, dtype=np.float64)
@@ -303,7 +310,8 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
         for t in range(c * C, (c + 1) * C):
             S = alpha[t] * S
             decay *= alpha[t]
-            S = S + beta[t] * np.outer(v[t] - S @ k[t], k[t])        # Eq. 19, every token of the chunk
+            pred = S @ k[t] if linear_op == 0 else 0.0
+            S = S + beta[t] * np.outer(v[t] - pred, k[t])            # Eq. 19, every token of the chunk
             o_la[t] = la_scale * (S @ q[t])
             J = np.asarray(earlier + list(range(c * C, t + 1)), dtype=np.int64)
             s = scale * (k[J] @ q[t])
@@ -313,7 +321,7 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
             o_nla[t] = (e / z) @ v[J]
             lse[t] = smax + np.log(z)
         if mask_c[c]:
-            S = decay * S_start                    # softmax chunk: its writes are rolled back
+            S = (decay if decay_on_softmax else 1.0) * S_start   # softmax chunk: its writes are rolled back
             earlier += list(range(c * C, (c + 1) * C))
     o = combine(o_la, o_nla, mode, w_nla, w_la, eps)
     cnt, idx, n_s = compaction(np.repeat(mask_c, C))
@@ -321,7 +329,7 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
 
 
 def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
-                            w_nla=None, w_la=None, eps=1e-6, S0=None):
+                            w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
     """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; same result layout as hybrid_fwd."""
     B, H, L, _ = np.asarray(Q).shape
     d_v = np.asarray(V).shape[-1]
@@ -336,7 +344,7 @@ def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None,
                                          softmax_scale, la_scale, mode,
                                          None if w_nla is None else w_nla[b, h],
                                          None if w_la is None else w_la[b, h], eps,
-                                         None if S0 is None else S0[b, h])
+                                         None if S0 is None else S0[b, h], linear_op, decay_on_softmax)
             for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]
@@ -355,7 +363,7 @@ def decode_chunk_state(S, k_cache, v_cache, cache_len):
 
 
 def decode_step_chunk_routed(st, q, k, v, alpha, beta, softmax_scale=None, la_scale=1.0, mode=0,
-                             w_nla=0.5, w_la=0.5, eps=1e-6):
+                             w_nla=0.5, w_la=0.5, eps=1e-6, linear_op=0):
     """One token inside an open chunk.  Both operations take it: the state is updated by Eq. 19 and (k, v)
     goes to the cache at row cache_len + pos; the output reads the state and every row up to that one
     (earlier softmax chunks, and the own chunk causally).  Returns (o, overflow); st is updated in place.
@@ -367,7 +375,7 @@ def decode_step_chunk_routed(st, q, k, v, alpha, beta, softmax_scale=None, la_sc
         st["decay"] = 1.0
     S = float(alpha) * st["S"]
     st["decay"] *= float(alpha)
-    S = S + float(beta) * np.outer(v - S @ k, k)
+    S = S + float(beta) * np.outer(v - (S @ k if linear_op == 0 else 0.0), k)
     st["S"] = S
     n = st["cache_len"] + st["pos"]
     overflow = n >= st["k_cache"].shape[0]
@@ -388,10 +396,11 @@ def decode_step_chunk_routed(st, q, k, v, alpha, beta, softmax_scale=None, la_sc
     return w_nla * rms_norm_rows(o_nla[None], eps)[0] + w_la * rms_norm_rows(o_la[None], eps)[0], overflow
 
 
-def decode_commit_chunk(st, m):
+def decode_commit_chunk(st, m, decay_on_softmax=True):
     """Settles the open chunk: a softmax chunk (m != 0) keeps its cache rows and sets the state back to
-    (chunk decay) x (chunk-start state); a linear chunk keeps the state and drops the rows."""
+    (chunk decay) x (chunk-start state), or to the chunk-start state itself in the variant without decay on
+    softmax chunks; a linear chunk keeps the state and drops the rows."""
     if m:
         st["cache_len"] = min(st["cache_len"] + st["pos"], st["k_cache"].shape[0])
-        st["S"] = st["decay"] * st["S_start"]
+        st["S"] = (st["decay"] if decay_on_softmax else 1.0) * st["S_start"]
     st["pos"] = 0

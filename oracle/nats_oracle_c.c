@@ -26,6 +26,19 @@
 #include <omp.h>
 #endif
 
+/* Variants of the linear branch, set before a call and read by every function below (the defaults are the
+ * method as stated):
+ *   g_linear_op = 1        : the linear operation is the gated linear attention of Mamba2,
+ *                            S_t = alpha_t S_{t-1} + beta_t v_t k_t^T (no delta correction), the second linear
+ *                            operation of the appendix "Mixture of SoftmaxAttention and Mamba2 architecture"
+ *   g_freeze_on_softmax = 1: no decay where the state is not written (the ablation without linear-attention
+ *                            decay, Section 5 "Ablation Study" (ii), i.e. Eq. 20 switched off) */
+static int g_linear_op = 0, g_freeze_on_softmax = 0;
+void nats_oracle_set_variant(int linear_op, int freeze_on_softmax) {
+    g_linear_op = linear_op;
+    g_freeze_on_softmax = freeze_on_softmax;
+}
+
 int nats_oracle_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
@@ -49,13 +62,14 @@ static void head_forward(int L, int d, const float *q, const float *k, const flo
     for (int t = 0; t < L; ++t) {
         const float *qt = q + (size_t)t * d, *kt = k + (size_t)t * d, *vt = v + (size_t)t * d;
         /* ---- linear branch ---- */
-        double a = alpha[t];
+        double a = (mask[t] != 0 && g_freeze_on_softmax) ? 1.0 : alpha[t];
         for (int i = 0; i < d * d; ++i) S[i] *= a;                 /* Eq. 20: decay always */
         if (mask[t] == 0) {                                        /* Eq. 14: write linear tokens only */
             double b = beta[t];
             for (int r = 0; r < d; ++r) {
                 double acc = 0.0;
-                for (int c = 0; c < d; ++c) acc += S[r * d + c] * (double)kt[c];
+                if (g_linear_op == 0)
+                    for (int c = 0; c < d; ++c) acc += S[r * d + c] * (double)kt[c];
                 pred[r] = acc;
             }
             for (int r = 0; r < d; ++r) {                          /* Eq. 19 expanded */
@@ -159,7 +173,7 @@ int nats_oracle_decode(int BH, int d, int cap, double *state, float *k_cache, fl
         double *S = state + (size_t)u * d * d;
         float *kc = k_cache + (size_t)u * cap * d, *vc = v_cache + (size_t)u * cap * d;
         const float *qt = q + (size_t)u * d, *kt = k + (size_t)u * d, *vt = v + (size_t)u * d;
-        double a = alpha[u];
+        double a = (mask[u] != 0 && g_freeze_on_softmax) ? 1.0 : alpha[u];
         for (int i = 0; i < d * d; ++i) S[i] *= a;
         if (overflow) overflow[u] = 0;
         if (mask[u] == 0) {
@@ -167,7 +181,8 @@ int nats_oracle_decode(int BH, int d, int cap, double *state, float *k_cache, fl
             double *pred = (double *)malloc(sizeof(double) * d);
             for (int r = 0; r < d; ++r) {
                 double acc = 0.0;
-                for (int c = 0; c < d; ++c) acc += S[r * d + c] * (double)kt[c];
+                if (g_linear_op == 0)
+                    for (int c = 0; c < d; ++c) acc += S[r * d + c] * (double)kt[c];
                 pred[r] = acc;
             }
             for (int r = 0; r < d; ++r) {
@@ -255,7 +270,8 @@ static void head_forward_chunk(int L, int d, int C, const float *q, const float 
             for (int i = 0; i < d * d; ++i) S[i] *= a;
             for (int r = 0; r < d; ++r) {
                 double acc = 0.0;
-                for (int j = 0; j < d; ++j) acc += S[r * d + j] * (double)kt[j];
+                if (g_linear_op == 0)
+                    for (int j = 0; j < d; ++j) acc += S[r * d + j] * (double)kt[j];
                 pred[r] = acc;
             }
             for (int r = 0; r < d; ++r) {                           /* Eq. 19, every token of the chunk */
@@ -302,6 +318,7 @@ static void head_forward_chunk(int L, int d, int C, const float *q, const float 
             if (cnt) cnt[t] = n_s + (soft ? (t - c0 + 1) : 0);
         }
         if (soft) {
+            if (g_freeze_on_softmax) decay = 1.0;
             for (int i = 0; i < d * d; ++i) S[i] = decay * S_start[i];   /* writes rolled back */
             for (int t = c0; t < c0 + C; ++t) pos[n_s++] = t;
         }

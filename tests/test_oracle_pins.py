@@ -403,3 +403,85 @@ def test_route_chunks_against_library_pooling_and_argmax():
     assert np.array_equal(m_flip, 1 - mask_c)       # no ties in random data
     m_tie, _ = npo.route_chunks(X, np.repeat(W[:, :1], 2, axis=1), C)
     assert m_tie.min() == 1                          # a tie goes to operation 0, as argmax does
+
+
+# ---- variants of the linear branch: Mamba2-style gated linear attention, no decay on softmax tokens ----------
+
+def _variant_inputs(L=24, d=6, seed=3, p=0.3):
+    rng = np.random.default_rng(seed)
+    q, k, v = (rng.standard_normal((L, d)) for _ in range(3))
+    k /= np.linalg.norm(k, axis=1, keepdims=True)
+    alpha = 1 / (1 + np.exp(-rng.normal(2, 0.5, L)))
+    beta = 1 / (1 + np.exp(-rng.standard_normal(L)))
+    mask = (rng.random(L) < p).astype(np.uint8)
+    return q, k, v, alpha, beta, mask
+
+
+def test_gated_linear_op_is_masked_decayed_linear_attention():
+    """linear_op=1 in closed form: o_t = sum over linear j <= t of (prod_{j<i<=t} alpha_i) beta_j (k_j.q_t) v_j,
+    i.e. (Q K^T * decay * column mask) diag(beta) V: Eq. 10 with a decay mask, no delta correction."""
+    q, k, v, alpha, beta, mask = _variant_inputs()
+    L = len(alpha)
+    o, S = npo.gdn_recurrent(q, k, v, alpha, beta, mask, linear_op=1)
+    cum = np.cumsum(np.log(alpha))
+    A = np.zeros((L, L))
+    for t in range(L):
+        for j in range(t + 1):
+            if mask[j] == 0:
+                A[t, j] = np.exp(cum[t] - cum[j]) * beta[j] * (k[j] @ q[t])
+    np.testing.assert_allclose(o, A @ v, rtol=1e-10, atol=1e-12)
+    S_ref = sum(np.exp(cum[-1] - cum[j]) * beta[j] * np.outer(v[j], k[j]) for j in range(L) if mask[j] == 0)
+    np.testing.assert_allclose(S, S_ref, rtol=1e-10, atol=1e-12)
+    # the delta rule gives something else as soon as two written keys overlap
+    o_gdn, _ = npo.gdn_recurrent(q, k, v, alpha, beta, mask, linear_op=0)
+    assert np.abs(o_gdn - o).max() > 1e-3
+
+
+def test_no_decay_on_softmax_tokens_equals_alpha_one_there():
+    q, k, v, alpha, beta, mask = _variant_inputs(seed=4)
+    for op in (0, 1):
+        o1, S1 = npo.gdn_recurrent(q, k, v, alpha, beta, mask, decay_on_softmax=False, linear_op=op)
+        a2 = np.where(mask != 0, 1.0, alpha)
+        o2, S2 = npo.gdn_recurrent(q, k, v, a2, beta, mask, linear_op=op)
+        np.testing.assert_allclose(o1, o2, rtol=1e-12)
+        np.testing.assert_allclose(S1, S2, rtol=1e-12)
+        o3, _ = npo.gdn_recurrent(q, k, v, alpha, beta, mask, linear_op=op)
+        assert np.abs(o3 - o1).max() > 1e-3
+
+
+@pytest.mark.parametrize("op,freeze", [(1, 0), (0, 1), (1, 1)])
+def test_c_oracle_variants_match_numpy(op, freeze):
+    from oracle import c_oracle
+    from nats_inputs import make_chunk_mask, make_fwd_inputs
+    x = make_fwd_inputs(1, 2, 128, 8, "f32", 0.2, seed=12)
+    r = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], linear_op=op, freeze_on_softmax=freeze)
+    ref = npo.hybrid_fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], linear_op=op,
+                        decay_on_softmax=not freeze)
+    np.testing.assert_allclose(r["O"], ref["O"], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(r["S"], ref["S"], rtol=1e-9, atol=1e-11)
+    # routing per chunk
+    mc = make_chunk_mask(1, 2, 2, 0.5, 5, "alternate")
+    r = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, chunk_routing=64, linear_op=op,
+                     freeze_on_softmax=freeze)
+    ref = npo.hybrid_fwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, 64, linear_op=op,
+                                     decay_on_softmax=not freeze)
+    np.testing.assert_allclose(r["O"], ref["O"], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(r["S"], ref["S"], rtol=1e-9, atol=1e-11)
+    # the defaults are untouched by a variant call before them
+    r0 = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"])
+    ref0 = npo.hybrid_fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"])
+    np.testing.assert_allclose(r0["O"], ref0["O"], rtol=1e-9, atol=1e-11)
+
+
+def test_chunk_routed_variants_carry_the_per_token_state():
+    """Whatever the variant, the state handed from chunk to chunk under routing per chunk is the per-token
+    state for the chunk mask expanded to tokens (the fact the kernels rely on)."""
+    from nats_inputs import make_fwd_inputs
+    x = make_fwd_inputs(1, 1, 192, 8, "f32", 0.2, seed=13)
+    mc = np.array([0, 1, 0], dtype=np.uint8)
+    for op, keep in ((1, True), (0, False), (1, False)):
+        r = npo.hybrid_head_chunk_routed(x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0], x["alpha"][0, 0], x["beta"][0, 0],
+                                        mc, 64, linear_op=op, decay_on_softmax=keep)
+        _, S = npo.gdn_recurrent(x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0], x["alpha"][0, 0], x["beta"][0, 0],
+                                np.repeat(mc, 64), decay_on_softmax=keep, linear_op=op)
+        np.testing.assert_allclose(r["S"], S, rtol=1e-10, atol=1e-12)
