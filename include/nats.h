@@ -73,6 +73,13 @@ typedef enum nats_math { NATS_MATH_AUTO = 0, NATS_MATH_FP32 = 1 } nats_math;
  *       Kc, Vc then describe the tokens of softmax chunks. */
 typedef enum nats_routing { NATS_ROUTE_TOKEN = 0, NATS_ROUTE_CHUNK = 1 } nats_routing;
 
+/* The linear operation (the search space's linear member is exchangeable: Section 4.3 uses Gated DeltaNet,
+ * the appendix "Mixture of SoftmaxAttention and Mamba2 architecture" Mamba2):
+ *   NATS_LINEAR_GDN  : S <- alpha S;  S <- S + beta (v - S k) k^T          (Eq. 19, the delta rule)
+ *   NATS_LINEAR_GATED: S <- alpha S;  S <- S + beta v k^T                  (Mamba2's recurrence with scalar
+ *                      decay per head: B = k, C = q, dt x = beta v; no correction by the state)  */
+typedef enum nats_linear_op { NATS_LINEAR_GDN = 0, NATS_LINEAR_GATED = 1 } nats_linear_op;
+
 typedef struct nats_fwd_params {
     int32_t B, H;          /* batch, heads (each (b,h) has its own mask: Section 4.3)          */
     int32_t L;             /* tokens; must be a positive multiple of C                          */
@@ -86,6 +93,10 @@ typedef struct nats_fwd_params {
     float rms_eps;         /* RMSNorm epsilon for combine_mode 1; <= 0 selects 1e-6             */
     int32_t math;          /* nats_math                                                         */
     int32_t routing;       /* nats_routing: granularity of the routing mask                     */
+    int32_t linear_op;     /* nats_linear_op                                                    */
+    int32_t freeze_on_softmax; /* 0: the decay acts on the state at every token (Eq. 20).  1: the ablation
+                              without linear-attention decay (Section 5, Ablation Study (ii)): softmax
+                              tokens, or softmax chunks as a whole, leave the carried state unchanged  */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */
@@ -149,6 +160,8 @@ typedef struct nats_dec_params {
     float la_scale;
     int32_t combine_mode;
     float rms_eps;
+    int32_t linear_op;         /* as in nats_fwd_params */
+    int32_t freeze_on_softmax; /* as in nats_fwd_params (routing per chunk: applied by the commit) */
 } nats_dec_params;
 
 /* For every (b,h):  S <- alpha S;  linear token: S <- S + beta (v - S k) k^T;  softmax token:

@@ -20,6 +20,7 @@ _lib = None
 NATS_F32, NATS_BF16 = 0, 1
 NATS_MATH_AUTO, NATS_MATH_FP32 = 0, 1
 NATS_ROUTE_TOKEN, NATS_ROUTE_CHUNK = 0, 1
+NATS_LINEAR_GDN, NATS_LINEAR_GATED = 0, 1
 
 
 class NatsError(RuntimeError):
@@ -32,7 +33,8 @@ class FwdParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
-                ("math", ctypes.c_int32), ("routing", ctypes.c_int32)]
+                ("math", ctypes.c_int32), ("routing", ctypes.c_int32), ("linear_op", ctypes.c_int32),
+                ("freeze_on_softmax", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -52,7 +54,8 @@ class DecChunkState(ctypes.Structure):
 class DecParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("la_scale", ctypes.c_float),
-                ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float)]
+                ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("linear_op", ctypes.c_int32),
+                ("freeze_on_softmax", ctypes.c_int32)]
 
 
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
@@ -137,8 +140,10 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
-                    math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN) -> FwdParams:
-    return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing)
+                    math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN, linear_op=NATS_LINEAR_GDN,
+                    freeze_on_softmax=0) -> FwdParams:
+    return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing,
+                     linear_op, int(freeze_on_softmax))
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -150,7 +155,8 @@ _EX_OUTPUTS = ("final_state", "Kc", "Vc", "n_s", "idx", "cnt", "O_la", "O_nla", 
 
 def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
                        la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
-                       math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, w_nla=None, w_la=None,
+                       math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, linear_op: int = NATS_LINEAR_GDN,
+                       freeze_on_softmax: bool = False, w_nla=None, w_la=None,
                        W_out=None, initial_state=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
                        workspace=None) -> Dict[str, torch.Tensor]:
@@ -168,7 +174,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
     _require(w_la, "w_la", (B, H, L), torch.float32)
     _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing)
+                             routing, linear_op, freeze_on_softmax)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
@@ -209,7 +215,8 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
 
 def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: float = 0.0,
                     la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
-                    math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, out=None,
+                    math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, linear_op: int = NATS_LINEAR_GDN,
+                    freeze_on_softmax: bool = False, out=None,
                     workspace=None) -> torch.Tensor:
     """nats_hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C) -> O."""
     lib = load_library()
@@ -221,7 +228,7 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
     _require(beta, "beta", (B, H, L), torch.float32)
     _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing)
+                             routing, linear_op, freeze_on_softmax)
     if workspace is None:
         workspace = torch.empty(max(fwd_workspace_bytes(params), 16), dtype=torch.uint8, device=Q.device)
     O = torch.empty_like(Q) if out is None else out
@@ -233,7 +240,8 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
 
 def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, *,
                        softmax_scale: float = 0.0, la_scale: float = 0.0, combine_mode: int = 0,
-                       rms_eps: float = 0.0, w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
+                       rms_eps: float = 0.0, linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False,
+                       w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
     """nats_hybrid_attn_decode: one token per (b,h); state, caches and cache_len are updated in place."""
     lib = load_library()
     B, H, cap, d = k_cache.shape
@@ -250,7 +258,8 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
     _require(err_flags, "err_flags", (B, H), torch.int32)
     o = torch.empty_like(q) if out is None else out
     _require(o, "out", (B, H, d), dt)
-    params = DecParams(B, H, d, cap, _dtype_code(k_cache), softmax_scale, la_scale, combine_mode, rms_eps)
+    params = DecParams(B, H, d, cap, _dtype_code(k_cache), softmax_scale, la_scale, combine_mode, rms_eps, linear_op,
+                       int(freeze_on_softmax))
     _check(lib.nats_hybrid_attn_decode(ctypes.byref(params), _ptr(state), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(cache_len), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta),
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
@@ -304,8 +313,8 @@ def _chunk_state(st: Dict[str, torch.Tensor]):
 
 
 def hybrid_attn_decode_chunk(st, q, k, v, alpha, beta, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
-                             combine_mode: int = 0, rms_eps: float = 0.0, w_nla=None, w_la=None, out=None,
-                             err_flags=None) -> torch.Tensor:
+                             combine_mode: int = 0, rms_eps: float = 0.0, linear_op: int = NATS_LINEAR_GDN,
+                             w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
     """nats_hybrid_attn_decode_chunk: one token per (b,h) under routing per chunk; `st` (see _chunk_state) is
     updated in place."""
     lib = load_library()
@@ -317,20 +326,21 @@ def hybrid_attn_decode_chunk(st, q, k, v, alpha, beta, *, softmax_scale: float =
     _require(err_flags, "err_flags", (B, H), torch.int32)
     o = torch.empty_like(q) if out is None else out
     _require(o, "out", (B, H, d), dt)
-    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), softmax_scale, la_scale, combine_mode, rms_eps)
+    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), softmax_scale, la_scale, combine_mode, rms_eps,
+                       linear_op, 0)
     _check(lib.nats_hybrid_attn_decode_chunk(ctypes.byref(params), ctypes.byref(cs), _ptr(q), _ptr(k), _ptr(v),
                                              _ptr(alpha), _ptr(beta), _ptr(w_nla), _ptr(w_la), _ptr(o),
                                              _ptr(err_flags), _stream_ptr()))
     return o
 
 
-def hybrid_attn_decode_commit(st, mask_c, *, err_flags=None) -> None:
+def hybrid_attn_decode_commit(st, mask_c, *, freeze_on_softmax: bool = False, err_flags=None) -> None:
     """nats_hybrid_attn_decode_commit: settle the open chunk of every (b,h) with its routing decision."""
     lib = load_library()
     cs, (B, H, cap, d, dt) = _chunk_state(st)
     _require(mask_c, "mask_c", (B, H), torch.uint8)
     _require(err_flags, "err_flags", (B, H), torch.int32)
-    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), 0.0, 0.0, 0, 0.0)
+    params = DecParams(B, H, d, cap, _dtype_code(st["k_cache"]), 0.0, 0.0, 0, 0.0, 0, int(freeze_on_softmax))
     _check(lib.nats_hybrid_attn_decode_commit(ctypes.byref(params), ctypes.byref(cs), _ptr(mask_c), _ptr(err_flags),
                                               _stream_ptr()))
 

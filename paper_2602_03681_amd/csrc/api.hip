@@ -117,7 +117,17 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         set_error("routing must be NATS_ROUTE_TOKEN or NATS_ROUTE_CHUNK (got %d)", p->routing);
         return NATS_ERR_SHAPE;
     }
+    if (p->linear_op != NATS_LINEAR_GDN && p->linear_op != NATS_LINEAR_GATED) {
+        set_error("linear_op must be NATS_LINEAR_GDN or NATS_LINEAR_GATED (got %d)", p->linear_op);
+        return NATS_ERR_SHAPE;
+    }
+    if (p->freeze_on_softmax != 0 && p->freeze_on_softmax != 1) {
+        set_error("freeze_on_softmax must be 0 or 1 (got %d)", p->freeze_on_softmax);
+        return NATS_ERR_SHAPE;
+    }
     pl->routing = p->routing;
+    pl->linear_op = p->linear_op;
+    pl->freeze_on_softmax = p->freeze_on_softmax;
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
     pl->dtype = p->dtype;
     pl->math = p->math;
@@ -164,7 +174,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 102; }
+int nats_abi_version(void) { return 103; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -380,6 +390,12 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
         set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
         return NATS_ERR_SHAPE;
     }
+    if ((p->linear_op != NATS_LINEAR_GDN && p->linear_op != NATS_LINEAR_GATED) ||
+        (p->freeze_on_softmax != 0 && p->freeze_on_softmax != 1)) {
+        set_error("linear_op must be a nats_linear_op and freeze_on_softmax 0 or 1 (got %d, %d)", p->linear_op,
+                  p->freeze_on_softmax);
+        return NATS_ERR_SHAPE;
+    }
     if (!state || !k_cache || !v_cache || !cache_len || !q || !k || !v || !alpha || !beta || !mask || !o) {
         set_error("state, caches, cache_len, q, k, v, alpha, beta, mask and o must all be non-NULL");
         return NATS_ERR_NULL;
@@ -449,6 +465,12 @@ static nats_status validate_dec_params(const nats_dec_params* p) {
     if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
     if (p->combine_mode != 0 && p->combine_mode != 1) {
         set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+        return NATS_ERR_SHAPE;
+    }
+    if ((p->linear_op != NATS_LINEAR_GDN && p->linear_op != NATS_LINEAR_GATED) ||
+        (p->freeze_on_softmax != 0 && p->freeze_on_softmax != 1)) {
+        set_error("linear_op must be a nats_linear_op and freeze_on_softmax 0 or 1 (got %d, %d)", p->linear_op,
+                  p->freeze_on_softmax);
         return NATS_ERR_SHAPE;
     }
     return NATS_OK;

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     const T* __restrict__ v, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ w_nla, const float* __restrict__ w_la,
     T* __restrict__ o, int32_t* __restrict__ err_flags, int cap, float scale, float la_scale,
-    int combine_mode, float eps) {
+    int combine_mode, float eps, int linear_op, int freeze_on_softmax) {
     constexpr int LPR = D / 4;                    // lanes per state row
     constexpr int ROWS_PER_PASS = DEC_THREADS / LPR;
     constexpr int PASSES = D / ROWS_PER_PASS;     // 16 (D=128) or 4 (D=64)
@@ -59,9 +59,10 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
         s_k[c] = to_float(k[(size_t)bh * D + c]);
         s_v[c] = to_float(v[(size_t)bh * D + c]);
     }
-    const float a = alpha[bh];
     const int pos = CHUNK ? chunk_pos[bh] : 0;
     const bool is_softmax = CHUNK ? true : mask[bh] != 0;     // CHUNK: every token goes to the cache ...
+    // variant without decay on softmax tokens: alpha counts as 1 there (routing per chunk: the commit decides)
+    const float a = (!CHUNK && is_softmax && freeze_on_softmax) ? 1.f : alpha[bh];
     const float b = (!CHUNK && is_softmax) ? 0.f : beta[bh];  // ... and into the state
     const int n_old = cache_len[bh] + pos;                    // rows present, provisional ones included
     const bool append = is_softmax && n_old < cap;
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
             s.x *= a; s.y *= a; s.z *= a; s.w *= a;
             if (b != 0.f) {
                 const float pred = group_sum<LPR>(s.x * k4.x + s.y * k4.y + s.z * k4.z + s.w * k4.w);
-                const float delta = b * (s_v[row] - pred);
+                const float delta = b * (s_v[row] - (linear_op == 0 ? pred : 0.f));   // no correction without the delta rule
                 s.x += delta * k4.x; s.y += delta * k4.y; s.z += delta * k4.z; s.w += delta * k4.w;
             }
             const float oq = group_sum<LPR>(s.x * q4.x + s.y * q4.y + s.z * q4.z + s.w * q4.w);
@@ -222,13 +223,13 @@ template <int D>
 __global__ __launch_bounds__(DEC_THREADS) void decode_commit_kernel(
     float* __restrict__ state, const float* __restrict__ state_start, const float* __restrict__ chunk_decay,
     int32_t* __restrict__ chunk_pos, int32_t* __restrict__ cache_len, const uint8_t* __restrict__ mask_c,
-    int32_t* __restrict__ err_flags, int cap) {
+    int32_t* __restrict__ err_flags, int cap, int freeze_on_softmax) {
     const int bh = blockIdx.x, tid = threadIdx.x;
     const int pos = chunk_pos[bh];
     const bool soft = mask_c[bh] != 0;
     const int n = cache_len[bh];
     if (soft && pos > 0) {
-        const float dec = chunk_decay[bh];
+        const float dec = freeze_on_softmax ? 1.f : chunk_decay[bh];   // variant: the state as the chunk found it
         float4* S = reinterpret_cast<float4*>(state + (size_t)bh * D * D);
         const float4* S0 = reinterpret_cast<const float4*>(state_start + (size_t)bh * D * D);
         for (int i = tid; i < D * D / 4; i += DEC_THREADS) {
@@ -255,12 +256,14 @@ static void launch_dec(const nats_dec_params& p, float scale, float la_scale, fl
         hipLaunchKernelGGL((decode_kernel<T, 64, CHUNK>), grid, dim3(DEC_THREADS), 0, st, state, state_start,
                            chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
-                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
+                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps,
+                           p.linear_op, p.freeze_on_softmax);
     else
         hipLaunchKernelGGL((decode_kernel<T, 128, CHUNK>), grid, dim3(DEC_THREADS), 0, st, state, state_start,
                            chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
-                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps);
+                           w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps,
+                           p.linear_op, p.freeze_on_softmax);
 }
 
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
@@ -297,10 +300,10 @@ nats_status launch_decode_commit(const nats_dec_params& p, float* state, const f
     dim3 grid(p.B * p.H);
     if (p.d == 64)
         hipLaunchKernelGGL(decode_commit_kernel<64>, grid, dim3(DEC_THREADS), 0, st, state, state_start, chunk_decay,
-                           chunk_pos, cache_len, mask_c, err_flags, p.cap);
+                           chunk_pos, cache_len, mask_c, err_flags, p.cap, p.freeze_on_softmax);
     else
         hipLaunchKernelGGL(decode_commit_kernel<128>, grid, dim3(DEC_THREADS), 0, st, state, state_start, chunk_decay,
-                           chunk_pos, cache_len, mask_c, err_flags, p.cap);
+                           chunk_pos, cache_len, mask_c, err_flags, p.cap, p.freeze_on_softmax);
     return check_launch("decode_commit");
 }
 

@@ -81,7 +81,8 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     int L, int chunk_mask, half_t* __restrict__ WF, half_t* __restrict__ QF, half_t* __restrict__ KdF,
-    half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC, int BH) {
+    half_t* __restrict__ UtF, half_t* __restrict__ PF, float* __restrict__ gamC, int BH, int linear_op,
+    int freeze_on_softmax) {
     using Lds = PrepLds<D>;
     constexpr int RS = Lds::RS, TS = Lds::TS;
     constexpr int NPC = CH * D / 8 / PREP_THREADS;   // 16-byte pieces of a [64][D] tile per thread
@@ -130,7 +131,8 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     }
     // ---- gates: cumulative log-decay and write strengths -------------------------------
     if (wave == 0) {
-        const float a = alpha[tok0 + lane];
+        // variant without decay on softmax tokens (routing per token): their alpha counts as 1
+        const float a = (freeze_on_softmax && !chunk_mask && mask[tok0 + lane]) ? 1.f : alpha[tok0 + lane];
         float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -207,8 +209,9 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * a + 4 * lq + j;
+                    // gated linear attention (no delta rule): A = 0, so T = (I + A)^-1 = I below
                     As[r * AS_STRIDE + i] =
-                        (i < r) ? s_bp[r] * accK[jj][j] * __builtin_amdgcn_exp2f(s_g2[r] - gi) : 0.f;
+                        (i < r && linear_op == 0) ? s_bp[r] * accK[jj][j] * __builtin_amdgcn_exp2f(s_g2[r] - gi) : 0.f;
                 }
             }
             {   // P[r][i], r = 16a + l16, i = 16b + 4 lq + j
@@ -265,7 +268,9 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
             }
             Qg[e] = h;
         }
-        if (tid == 0) gamC[gc] = s_gam[CH - 1];
+        // the decay the recurrence applies to the state it carries over this chunk (1 for a softmax chunk in
+        // the variant without decay there: inside the chunk the decays still act on the provisional state)
+        if (tid == 0) gamC[gc] = (freeze_on_softmax && chunk_mask && mask[gc] != 0) ? 1.f : s_gam[CH - 1];
     }
     __syncthreads();   // K and Q tiles are dead from here on: their region becomes T
     // ---- T = (I + A)^{-1}, unit lower triangular, by 16x16 blocks in fp32 ------------------------
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
         const float t = (i <= r) ? Ts[r * AS_STRIDE + i] : 0.f;
         const float bp = s_bp[i];
         Tpp[r * TS + i] = f32_to_half_sat(t * bp);
-        Tp[r * TS + i] = f32_to_half_sat(t * bp * s_gam[i]);
+        Tp[r * TS + i] = linear_op == 0 ? f32_to_half_sat(t * bp * s_gam[i]) : (half_t)0.f;   // W = 0 without the delta rule
     }
     __syncthreads();   // T is dead from here on: its region becomes V^T
 #pragma unroll
@@ -402,7 +407,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<64>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
-                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH);
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
     } else {
         auto kern = gdn_chunk_prep_kernel<128>;
         if (!attr_done[1][dev]) {
@@ -413,7 +418,7 @@ nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* 
         }
         hipLaunchKernelGGL(kern, grid, dim3(PREP_THREADS), PrepLds<128>::bytes, st, (const bf16_t*)Q,
                            (const bf16_t*)K, (const bf16_t*)V, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)WF, (half_t*)QF,
-                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH);
+                           (half_t*)KdF, (half_t*)UtF, (half_t*)PF, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
     }
     return check_launch("gdn_chunk_prep");
 }

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
-    float* __restrict__ snap, int L, float la_scale) {
+    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax) {
     __shared__ __align__(16) float s_k[REC_TT][D];
     __shared__ __align__(16) float s_q[REC_TT][D];
     __shared__ float s_v[REC_TT][REC_ROWS];
@@ -74,7 +74,8 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
             for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
         }
         if (tid < REC_TT) {
-            s_a[tid] = alpha[base + t0 + tid];
+            // variant without decay on softmax tokens (routing per token): their alpha counts as 1
+            s_a[tid] = (freeze_on_softmax && !chunk_mask && mask[base + t0 + tid]) ? 1.f : alpha[base + t0 + tid];
             // routing per token: softmax tokens never write
             s_b[tid] = (!chunk_mask && mask[base + t0 + tid]) ? 0.f : beta[base + t0 + tid];
         }
@@ -98,7 +99,8 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
                     S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
                     pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
                 }
-                const float delta = b * (s_v[i][tid] - pred);
+                // gated linear attention (linear_op != 0) writes beta v k^T as it is: no correction by the state
+                const float delta = b * (s_v[i][tid] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
                 for (int c = 0; c < D; c += 4) {
                     const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
@@ -117,6 +119,7 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
             }
             O_la[(base + t0 + i) * D + row] = la_scale * o;
             if (chunk_mask && ((t0 + i) & 63) == 63 && mask_c[(t0 + i) >> 6]) {   // end of a softmax chunk
+                if (freeze_on_softmax) chunk_decay = 1.f;   // variant: a softmax chunk leaves the state as it found it
 #pragma unroll
                 for (int c = 0; c < D; c += 4) {
                     const float4 x = *reinterpret_cast<const float4*>(my_snap + c);
@@ -141,10 +144,12 @@ static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const vo
     dim3 grid(pl.d / REC_ROWS, pl.BH);
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale);
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
+                           pl.linear_op, pl.freeze_on_softmax);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale);
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
+                           pl.linear_op, pl.freeze_on_softmax);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,

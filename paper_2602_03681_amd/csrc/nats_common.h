@@ -114,6 +114,7 @@ struct FwdPlan {
     float softmax_scale, la_scale, rms_eps;
     int combine_mode;
     int routing;   // nats_routing
+    int linear_op, freeze_on_softmax;   // variants of the linear branch, see nats_fwd_params
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands

@@ -1,0 +1,119 @@
+"""GPU parity for the variants of the linear branch: Mamba2-style gated linear attention (appendix
+"Mixture of SoftmaxAttention and Mamba2 architecture") and the ablation without decay on softmax tokens /
+chunks (Section 5, Ablation Study (ii)), through the C ABI against the CPU oracle, same bars as the method
+itself: forward with routing per token and per chunk on both arithmetic paths, and generation."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_03681_amd as nats
+from paper_2602_03681_amd import binding as nb
+from nats_inputs import DecodeConfig, make_chunk_mask, make_decode_inputs, make_fwd_inputs
+from oracle import c_oracle
+from oracle import nats_oracle as npo
+
+from gpu_util import TOL, host, rel_err, stored, to_dev
+from test_gpu_parity import ALL_OUT, check_all
+
+pytestmark = pytest.mark.gpu
+VARIANTS = [(nb.NATS_LINEAR_GATED, 0), (nb.NATS_LINEAR_GDN, 1), (nb.NATS_LINEAR_GATED, 1)]
+
+
+def fwd_both(x, dtype, op, freeze, chunk=False, **kw):
+    g = to_dev(x, dtype)
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, want=ALL_OUT,
+                                routing=nb.NATS_ROUTE_CHUNK if chunk else nb.NATS_ROUTE_TOKEN, linear_op=op,
+                                freeze_on_softmax=bool(freeze), **kw)
+    torch.cuda.synchronize()
+    ref = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], chunk_routing=64 if chunk else 0,
+                       linear_op=op, freeze_on_softmax=freeze)
+    return r, ref
+
+
+@pytest.mark.parametrize("op,freeze", VARIANTS)
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+def test_variants_routing_per_token(dtype, d, op, freeze):
+    x = make_fwd_inputs(2, 3, 1088 if dtype == "bf16" else 320, d, dtype, 0.15, seed=41 + d + op)
+    r, ref = fwd_both(x, dtype, op, freeze)
+    check_all(x, dtype, r, ref)
+    # the variant is not a no-op on these inputs
+    base = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], want=())
+    assert rel_err(base["O"], ref["O"]) > 10 * TOL[dtype]
+
+
+@pytest.mark.parametrize("op,freeze", VARIANTS)
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64)])
+def test_variants_routing_per_chunk(dtype, d, op, freeze):
+    L = 1024 if dtype == "bf16" else 320
+    x = make_fwd_inputs(2, 2, L, d, dtype, 0.1, seed=51 + d + op)
+    x["mask"] = make_chunk_mask(2, 2, L // 64, 0.4, 60 + d, "bernoulli")
+    r, ref = fwd_both(x, dtype, op, freeze, chunk=True)
+    check_all(x, dtype, r, ref)
+
+
+def test_variants_fp32_arithmetic_on_bf16_tensors_and_eq21():
+    x = make_fwd_inputs(1, 2, 256, 64, "bf16", 0.2, seed=71)
+    rng = np.random.default_rng(7)
+    w = rng.random((2, 1, 2, 256)).astype(np.float32)
+    g = to_dev(x, "bf16")
+    for math in (nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32):
+        r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, want=(), math=math,
+                                    combine_mode=1, w_nla=torch.from_numpy(w[0]).cuda(), w_la=torch.from_numpy(w[1]).cuda(),
+                                    linear_op=nb.NATS_LINEAR_GATED, freeze_on_softmax=True)
+        torch.cuda.synchronize()
+        ref = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], mode=1, w_nla=w[0], w_la=w[1],
+                           linear_op=1, freeze_on_softmax=1, want=())
+        assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("op,freeze", VARIANTS)
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_variants_decode_steps(dtype, d, op, freeze):
+    cfg = DecodeConfig("small", 3, 2, d, dtype, 0.3, seed=81 + d + op, len_lo=1, len_hi=70, steps=24)
+    x = make_decode_inputs(cfg, steps=cfg.steps)
+    g = to_dev(x, dtype)
+    state, kc, vc, clen = g["state"].clone(), g["k_cache"].clone(), g["v_cache"].clone(), g["cache_len"].clone()
+    S_ref = x["state"].astype(np.float64)
+    kc_ref, vc_ref, clen_ref = x["k_cache"].copy(), x["v_cache"].copy(), x["cache_len"].copy()
+    for s in range(cfg.steps):
+        o = nats.hybrid_attn_decode(state, kc, vc, clen, g["q"][s], g["k"][s], g["v"][s], g["alpha"][s], g["beta"][s],
+                                    g["mask"][s], linear_op=op, freeze_on_softmax=bool(freeze))
+        o_ref, _ = c_oracle.decode(S_ref, kc_ref, vc_ref, clen_ref, x["q"][s], x["k"][s], x["v"][s], x["alpha"][s],
+                                   x["beta"][s], x["mask"][s], linear_op=op, freeze_on_softmax=freeze)
+        assert rel_err(host(o), o_ref, stored(dtype)) <= TOL[dtype], f"step {s}"
+    torch.cuda.synchronize()
+    assert rel_err(host(state), S_ref) <= TOL[dtype]
+    np.testing.assert_array_equal(host(clen), clen_ref)
+
+
+@pytest.mark.parametrize("op,freeze", [(nb.NATS_LINEAR_GATED, 1), (nb.NATS_LINEAR_GDN, 1)])
+def test_variants_generation_per_chunk_with_commits(op, freeze):
+    """Two chunks generated token by token under routing per chunk (one softmax, one linear), every token and
+    the state after each commit against the numpy oracle's generation functions."""
+    B, H, d, cap, C = 1, 2, 64, 192, 64
+    x = make_fwd_inputs(B, H, 2 * C, d, "f32", 0.0, seed=93)
+    g = to_dev(x, "f32")
+    st = {"state": torch.zeros((B, H, d, d), device="cuda"), "state_start": torch.zeros((B, H, d, d), device="cuda"),
+          "chunk_decay": torch.ones((B, H), device="cuda"), "chunk_pos": torch.zeros((B, H), dtype=torch.int32, device="cuda"),
+          "k_cache": torch.zeros((B, H, cap, d), device="cuda"), "v_cache": torch.zeros((B, H, cap, d), device="cuda"),
+          "cache_len": torch.zeros((B, H), dtype=torch.int32, device="cuda")}
+    ref = [[npo.decode_chunk_state(np.zeros((d, d)), np.zeros((cap, d)), np.zeros((cap, d)), 0) for _ in range(H)]
+           for _ in range(B)]
+    decisions = [np.array([[1, 0]], dtype=np.uint8), np.array([[0, 1]], dtype=np.uint8)]
+    for c in range(2):
+        for t in range(c * C, (c + 1) * C):
+            o = nats.hybrid_attn_decode_chunk(st, g["Q"][:, :, t].contiguous(), g["K"][:, :, t].contiguous(),
+                                              g["V"][:, :, t].contiguous(), g["alpha"][:, :, t].contiguous(),
+                                              g["beta"][:, :, t].contiguous(), linear_op=op)
+            for b in range(B):
+                for h in range(H):
+                    o_ref, _ = npo.decode_step_chunk_routed(ref[b][h], x["Q"][b, h, t], x["K"][b, h, t], x["V"][b, h, t],
+                                                            x["alpha"][b, h, t], x["beta"][b, h, t], linear_op=op)
+                    assert rel_err(host(o)[b, h], o_ref) <= TOL["f32"], (c, t, b, h)
+        nats.hybrid_attn_decode_commit(st, torch.from_numpy(decisions[c]).cuda(), freeze_on_softmax=bool(freeze))
+        torch.cuda.synchronize()
+        for b in range(B):
+            for h in range(H):
+                npo.decode_commit_chunk(ref[b][h], int(decisions[c][b, h]), decay_on_softmax=not freeze)
+                assert rel_err(host(st["state"])[b, h], ref[b][h]["S"]) <= TOL["f32"]
+                assert int(host(st["cache_len"])[b, h]) == ref[b][h]["cache_len"]
