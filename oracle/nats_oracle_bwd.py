@@ -1,0 +1,124 @@
+"""CPU oracle for the backward pass of the NAtS-L hybrid attention operator (TEST INFRASTRUCTURE ONLY).
+
+Plain fp64 numpy, token by token: the adjoint of the forward oracle's own loops (nats_oracle.py), written
+out by hand.  Nothing in the product path may import this file; it shares no code with the HIP kernels.
+
+Given dO = dLoss/dO for the plain-sum merge O = O_la + O_nla (Section 4.1), per (batch, head):
+
+  * linear branch   -- reverse of the recurrence  S <- alpha S;  S <- S + beta (v - S k) k^T  (Eq. 19, written
+    for linear tokens only, Eq. 14; decay at every token, Eq. 20);  o = la_scale S q.  Gives dq, dk, dv,
+    dalpha, dbeta and the gradient of the initial state.  k and v of a softmax token get nothing from this
+    branch (Section 4.2: the gradient is zero for an operation a token is inactive for).
+  * softmax branch  -- the usual attention backward over the softmax columns j <= i, and the column sums
+    of Eq. 15:  dM_ij = P_ij (dP_ij - do_i . o_i),  g_j = sum_i dM_ij,  which Eq. 16 adds up per chunk into
+    the gradient of the softmax score.
+
+Parity pins: tests/test_oracle_bwd_pins.py checks every output against automatic differentiation of an
+independently written forward (plain PyTorch fp64 on the CPU), the column sums against the derivative with
+respect to an explicit multiplicative mask, special cases against a library attention routine, and single
+entries against central finite differences of the forward oracle.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0=None, la_scale=1.0, linear_op=0, decay_on_softmax=True):
+    """Adjoint of nats_oracle.gdn_recurrent.  do [L,d_v].
+
+    Returns dict(dq, dk, dv [L,d], dalpha, dbeta [L], dS0 [d_v,d_k])."""
+    q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
+    alpha = np.asarray(alpha, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    L, d_k = k.shape
+    d_v = v.shape[1]
+    S = np.zeros((d_v, d_k)) if S0 is None else np.array(S0, dtype=np.float64)
+    # forward, keeping what the reverse sweep needs: the state before each token, after its decay, after its write
+    S_prev, S_dec, S_new, resid = [], [], [], []
+    for t in range(L):
+        linear = (mask[t] == 0)
+        S_prev.append(S)
+        a = alpha[t] if (linear or decay_on_softmax) else 1.0
+        S = a * S
+        S_dec.append(S)
+        r = np.zeros(d_v)
+        if linear:
+            r = v[t] - (S @ k[t] if linear_op == 0 else 0.0)
+            S = S + beta[t] * np.outer(r, k[t])
+        resid.append(r)
+        S_new.append(S)
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    dalpha, dbeta = np.zeros(L), np.zeros(L)
+    dS = np.zeros((d_v, d_k))                       # dLoss/dS after token t, from the tokens behind it
+    for t in range(L - 1, -1, -1):
+        linear = (mask[t] == 0)
+        # o_t = la_scale S_t q_t
+        dq[t] = la_scale * (S_new[t].T @ do[t])
+        dS = dS + la_scale * np.outer(do[t], q[t])
+        if linear:                                  # S_t = Sd + beta r k^T,  r = v - Sd k (delta rule) or v
+            r = resid[t]
+            dSk = dS @ k[t]                         # [d_v]
+            dbeta[t] = r @ dSk
+            dr = beta[t] * dSk
+            dk[t] = beta[t] * (dS.T @ r)
+            dv[t] = dr
+            if linear_op == 0:
+                dk[t] -= S_dec[t].T @ dr
+                dS = dS - np.outer(dr, k[t])
+        if linear or decay_on_softmax:              # Sd = alpha S_{t-1}
+            dalpha[t] = np.sum(dS * S_prev[t])
+            dS = alpha[t] * dS
+    return {"dq": dq, "dk": dk, "dv": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS}
+
+
+def softmax_branch_bwd(q, k, v, mask, scale, do):
+    """Adjoint of nats_oracle.softmax_branch, plus g [L]: the column sums of Eq. 15 (zero at linear tokens).
+
+    Returns dict(dq, dk, dv, g)."""
+    q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
+    L = q.shape[0]
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    g = np.zeros(L)
+    for i in range(L):
+        J = np.flatnonzero(np.asarray(mask[:i + 1]) != 0)
+        if J.size == 0:
+            continue
+        s = scale * (k[J] @ q[i])
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        o = p @ v[J]
+        dp = v[J] @ do[i]                           # dLoss/dP_ij
+        dm = p * (dp - do[i] @ o)                   # Eq. 15; also dLoss/ds_ij
+        g[J] += dm
+        dv[J] += np.outer(p, do[i])
+        dq[i] = scale * (dm @ k[J])
+        dk[J] += scale * np.outer(dm, q[i])
+    return {"dq": dq, "dk": dk, "dv": dv, "g": g}
+
+
+def hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
+                    decay_on_softmax=True):
+    """Backward of nats_oracle.hybrid_head with the plain-sum merge: dO goes to both branches as it is."""
+    d_k = np.asarray(q).shape[-1]
+    scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
+    la = gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, la_scale, linear_op, decay_on_softmax)
+    nla = softmax_branch_bwd(q, k, v, mask, scale, do)
+    return {"dQ": la["dq"] + nla["dq"], "dK": la["dk"] + nla["dk"], "dV": la["dv"] + nla["dv"],
+            "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_nla": nla["g"]}
+
+
+def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
+               decay_on_softmax=True):
+    """All (b,h) of [B,H,L,d] inputs; returns a dict of stacked fp64 arrays."""
+    B, H, L, d = np.asarray(Q).shape
+    out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
+           "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
+           "g_nla": np.zeros((B, H, L))}
+    for b in range(B):
+        for h in range(H):
+            r = hybrid_head_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask[b, h], dO[b, h],
+                                softmax_scale, la_scale, None if S0 is None else S0[b, h], linear_op,
+                                decay_on_softmax)
+            for key in out:
+                out[key][b, h] = r[key]
+    return out

@@ -1,0 +1,135 @@
+"""Pins of the backward oracle (oracle/nats_oracle_bwd.py) to things other than itself: automatic
+differentiation of an independently written forward (plain PyTorch fp64, CPU), a library attention routine,
+the derivative with respect to an explicit multiplicative mask (Eq. 15), and central finite differences of
+the forward oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import nats_oracle as npo
+from oracle import nats_oracle_bwd as nbw
+
+
+def inputs(L=20, d=5, seed=0, p=0.3):
+    rng = np.random.default_rng(seed)
+    q, k, v, do = (rng.standard_normal((L, d)) for _ in range(4))
+    k /= np.linalg.norm(k, axis=1, keepdims=True)
+    alpha = 1 / (1 + np.exp(-rng.normal(2, 0.5, L)))
+    beta = 1 / (1 + np.exp(-rng.standard_normal(L)))
+    mask = (rng.random(L) < p).astype(np.uint8)
+    mask[0] = 1
+    S0 = 0.1 * rng.standard_normal((d, d))
+    return q, k, v, alpha, beta, mask, do, S0
+
+
+def torch_forward(q, k, v, alpha, beta, mask, S0, scale, la_scale, linear_op, decay_on_softmax, M=None):
+    """The operator's definition written with torch ops (autograd does the rest): Eq. 19 / 14 / 20 token by
+    token, Eq. 11-12 as a dense masked softmax.  M: optional multiplicative mask on exp(A) (Eq. 11)."""
+    L = q.shape[0]
+    S = S0
+    o_la = []
+    for t in range(L):
+        lin = mask[t] == 0
+        if lin or decay_on_softmax:
+            S = alpha[t] * S
+        if lin:
+            r = v[t] - (S @ k[t] if linear_op == 0 else 0.0)
+            S = S + beta[t] * torch.outer(r, k[t])
+        o_la.append(la_scale * (S @ q[t]))
+    o_la = torch.stack(o_la)
+    A = scale * (q @ k.T)
+    vis = torch.tril(torch.ones(L, L, dtype=torch.bool)) & torch.from_numpy(mask != 0)[None, :]
+    E = torch.where(vis, torch.exp(A - A.detach().max()), torch.zeros_like(A))
+    if M is not None:
+        E = E * M
+    Z = E.sum(1, keepdim=True)
+    P = torch.where(Z > 0, E / torch.where(Z > 0, Z, torch.ones_like(Z)), torch.zeros_like(E))
+    return o_la + P @ v, S
+
+
+@pytest.mark.parametrize("linear_op,decay_on_softmax", [(0, True), (1, True), (0, False), (1, False)])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_backward_against_autograd(seed, linear_op, decay_on_softmax):
+    q, k, v, alpha, beta, mask, do, S0 = inputs(seed=seed)
+    scale, la_scale = 0.7, 1.3
+    t = {n: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+         for n, a in dict(q=q, k=k, v=v, alpha=alpha, beta=beta, S0=S0).items()}
+    O, _ = torch_forward(t["q"], t["k"], t["v"], t["alpha"], t["beta"], mask, t["S0"], scale, la_scale, linear_op,
+                         decay_on_softmax)
+    (O * torch.tensor(do)).sum().backward()
+    r = nbw.hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=scale, la_scale=la_scale, S0=S0,
+                            linear_op=linear_op, decay_on_softmax=decay_on_softmax)
+    for name, key in (("q", "dQ"), ("k", "dK"), ("v", "dV"), ("alpha", "dalpha"), ("beta", "dbeta"), ("S0", "dS0")):
+        np.testing.assert_allclose(r[key], t[name].grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=key)
+    # the forward written here is the forward oracle's (so the gradients belong to the right function)
+    ref = npo.hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=scale, la_scale=la_scale, S0=S0,
+                          linear_op=linear_op, decay_on_softmax=decay_on_softmax)
+    np.testing.assert_allclose(O.detach().numpy(), ref["O"], rtol=1e-10, atol=1e-12)
+    # Section 4.2: k, v of a softmax token get nothing from the linear branch, alpha, beta of it only the decay
+    la = nbw.gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, la_scale, linear_op, decay_on_softmax)
+    soft = mask != 0
+    assert np.all(la["dk"][soft] == 0) and np.all(la["dv"][soft] == 0) and np.all(la["dbeta"][soft] == 0)
+    if not decay_on_softmax:
+        assert np.all(la["dalpha"][soft] == 0)
+
+
+def test_column_sums_are_the_derivative_of_a_multiplicative_mask():
+    """Eq. 15: dM_ij = P_ij (dP_ij - do_i . o_i) is dLoss/dM_ij for O = (e^A * M / rowsum(e^A * M)) V at M = 1;
+    g_j of the oracle is its column sum (Eq. 16 adds the columns of a chunk)."""
+    q, k, v, alpha, beta, mask, do, S0 = inputs(L=16, d=4, seed=3, p=0.5)
+    tq, tk, tv = (torch.tensor(a, dtype=torch.float64) for a in (q, k, v))
+    M = torch.ones(16, 16, dtype=torch.float64, requires_grad=True)
+    O, _ = torch_forward(tq, tk, tv, torch.tensor(alpha), torch.tensor(beta), mask, torch.zeros(4, 4, dtype=torch.float64),
+                         0.5, 0.0, 0, True, M=M)
+    (O * torch.tensor(do)).sum().backward()
+    r = nbw.softmax_branch_bwd(q, k, v, mask, 0.5, do)
+    dM = M.grad.numpy()
+    np.testing.assert_allclose(r["g"], dM.sum(0), rtol=1e-9, atol=1e-12)
+    assert np.all(r["g"][mask == 0] == 0)
+    # each row of dM sums to zero (softmax normalisation): so does the total of g
+    assert abs(r["g"].sum()) < 1e-10
+
+
+def test_all_softmax_reduces_to_library_attention_backward():
+    q, k, v, alpha, beta, mask, do, S0 = inputs(L=24, d=8, seed=5)
+    mask[:] = 1
+    tq, tk, tv = (torch.tensor(a[None, None], dtype=torch.float64, requires_grad=True) for a in (q, k, v))
+    O = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=0.4)
+    (O * torch.tensor(do)[None, None]).sum().backward()
+    r = nbw.hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=0.4)
+    np.testing.assert_allclose(r["dQ"], tq.grad[0, 0].numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(r["dK"], tk.grad[0, 0].numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(r["dV"], tv.grad[0, 0].numpy(), rtol=1e-9, atol=1e-11)
+    assert np.all(r["dbeta"] == 0)       # nothing is ever written
+
+
+def test_single_entries_against_finite_differences():
+    q, k, v, alpha, beta, mask, do, S0 = inputs(L=12, d=4, seed=7)
+    r = nbw.hybrid_head_bwd(q, k, v, alpha, beta, mask, do, S0=S0)
+
+    def loss(**over):
+        a = dict(q=q, k=k, v=v, alpha=alpha, beta=beta)
+        a.update(over)
+        return float(np.sum(npo.hybrid_head(a["q"], a["k"], a["v"], a["alpha"], a["beta"], mask, S0=S0)["O"] * do))
+
+    h = 1e-6
+    for name, key, pos in (("q", "dQ", (5, 2)), ("k", "dK", (3, 1)), ("k", "dK", (0, 0)), ("v", "dV", (7, 3)),
+                           ("alpha", "dalpha", (4,)), ("beta", "dbeta", (6,)), ("alpha", "dalpha", (0,))):
+        base = dict(q=q, k=k, v=v, alpha=alpha, beta=beta)[name]
+        up, dn = base.copy(), base.copy()
+        up[pos] += h
+        dn[pos] -= h
+        fd = (loss(**{name: up}) - loss(**{name: dn})) / (2 * h)
+        assert abs(fd - r[key][pos]) <= 1e-6 * max(1.0, abs(fd)), (name, pos, fd, r[key][pos])
+
+
+def test_batched_wrapper_stacks_heads():
+    rng = np.random.default_rng(9)
+    B, H, L, d = 2, 2, 10, 4
+    Q, K, V, dO = (rng.standard_normal((B, H, L, d)) for _ in range(4))
+    alpha, beta = rng.random((B, H, L)) * 0.5 + 0.5, rng.random((B, H, L))
+    mask = (rng.random((B, H, L)) < 0.3).astype(np.uint8)
+    r = nbw.hybrid_bwd(Q, K, V, alpha, beta, mask, dO)
+    one = nbw.hybrid_head_bwd(Q[1, 0], K[1, 0], V[1, 0], alpha[1, 0], beta[1, 0], mask[1, 0], dO[1, 0])
+    for key in ("dQ", "dK", "dV", "dalpha", "dbeta", "g_nla"):
+        np.testing.assert_array_equal(r[key][1, 0], one[key])
