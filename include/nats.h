@@ -149,6 +149,37 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
                                     void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ * Backward pass (Section 4.2), routing per token, plain-sum merge, fp32 arithmetic
+ * ------------------------------------------------------------------------- */
+typedef struct nats_bwd_extra {
+    const float* initial_state; /* in  [B,H,d,d] f32, the state the forward started from (NULL -> 0)         */
+    float* d_initial_state;     /* out [B,H,d,d] f32, gradient of that state                                 */
+    float* g_nla;               /* out [B,H,L] f32: g_j = sum_i dM_ij of Eq. 15 for softmax tokens j, 0 for
+                                   linear tokens; Eq. 16 (the gradient of a chunk's softmax score) is the sum
+                                   of g over the chunk's tokens                                              */
+} nats_bwd_extra;
+
+size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
+
+/* Gradients of nats_hybrid_attn_fwd's O = O_la + O_nla with respect to its inputs, given dO = dLoss/dO:
+ * the adjoint of the recurrence of Eq. 19 / 14 / 20 (or of the gated operation) for the linear branch, and the
+ * attention backward over the softmax columns of Eq. 12 with the mask gradients of Eq. 15.  k and v of a
+ * softmax token get nothing from the linear branch and vice versa (Section 4.2).
+ *   Q, K, V, alpha, beta, mask : as in the forward (p->routing must be NATS_ROUTE_TOKEN, p->combine_mode 0;
+ *             p->math is not looked at: every product and sum here is fp32)
+ *   dO      : in  [B,H,L,d] dtype p->dtype
+ *   dQ, dK, dV : out [B,H,L,d] f32 (whatever p->dtype);  dalpha, dbeta : out [B,H,L] f32
+ *   extra   : optional, may be NULL
+ *   workspace : at least nats_hybrid_attn_bwd_workspace_bytes(p); nothing is kept from the forward call, the
+ *             backward recomputes what it needs (the state is checkpointed once per 64 tokens)
+ * Sums over (batch, head)-internal blocks are taken in a fixed order: results are deterministic. */
+nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask, const void* dO,
+                                 float* dQ, float* dK, float* dV, float* dalpha, float* dbeta,
+                                 const nats_bwd_extra* extra, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
  * Single-token decode (Section 4.1, per-token generation, with per-token routing)
  * ------------------------------------------------------------------------- */
 typedef struct nats_dec_params {

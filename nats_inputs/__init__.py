@@ -185,6 +185,13 @@ def make_score_inputs(B: int, L: int, d_model: int, H: int, dtype: str, seed: in
     return {"X": X, "W_s": np.ascontiguousarray(W_s, dtype=np.float32)}
 
 
+def make_grad_output(B: int, H: int, L: int, d: int, dtype: str, seed: int) -> np.ndarray:
+    """dO [B,H,L,d] for the backward pass: N(0,1), representable in `dtype`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dO = _normal32(rng, (B, H, L, d))
+    return round_to_bf16(dO) if dtype == "bf16" else dO
+
+
 def make_config_inputs(cfg: FwdConfig) -> Dict[str, np.ndarray]:
     return make_fwd_inputs(cfg.B, cfg.H, cfg.L, cfg.d, cfg.dtype, cfg.p_softmax, cfg.seed,
                            n_runs=cfg.n_runs, run_len=cfg.run_len)

@@ -45,6 +45,10 @@ class FwdExtra(ctypes.Structure):
                 ("lse", ctypes.c_void_p), ("W_out", ctypes.c_void_p)]
 
 
+class BwdExtra(ctypes.Structure):
+    _fields_ = [("initial_state", ctypes.c_void_p), ("d_initial_state", ctypes.c_void_p), ("g_nla", ctypes.c_void_p)]
+
+
 class DecChunkState(ctypes.Structure):
     _fields_ = [("state", ctypes.c_void_p), ("state_start", ctypes.c_void_p), ("chunk_decay", ctypes.c_void_p),
                 ("chunk_pos", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
@@ -61,7 +65,8 @@ class DecParams(ctypes.Structure):
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
-           "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks")
+           "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks",
+           "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd")
 
 
 def library_path() -> str:
@@ -96,6 +101,11 @@ def load_library():
     lib.nats_merge_weights.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 5
     lib.nats_route_chunks.restype = ctypes.c_int
     lib.nats_route_chunks.argtypes = [ctypes.c_int32] * 6 + [vp] * 5
+    lib.nats_hybrid_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.nats_hybrid_attn_bwd_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams)]
+    lib.nats_hybrid_attn_bwd.restype = ctypes.c_int
+    lib.nats_hybrid_attn_bwd.argtypes = ([ctypes.POINTER(FwdParams)] + [vp] * 12 + [ctypes.POINTER(BwdExtra), vp,
+                                          ctypes.c_size_t, vp])
     lib.nats_last_error.restype = ctypes.c_char_p
     lib.nats_abi_version.restype = ctypes.c_int
     lib.nats_probe_mfma.restype = ctypes.c_double
@@ -236,6 +246,45 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
     _check(lib.nats_hybrid_attn_fwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
                                     _ptr(mask), _ptr(O), _ptr(workspace), workspace.numel(), _stream_ptr()))
     return O
+
+
+def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
+                    linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False, initial_state=None,
+                    want=(), workspace=None) -> Dict[str, torch.Tensor]:
+    """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla (routing per token) given dO.  Returns dQ, dK, dV
+    [B,H,L,d] f32, dalpha, dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla [B,H,L]."""
+    lib = load_library()
+    B, H, L, d = Q.shape
+    dt = Q.dtype
+    for name, t in (("Q", Q), ("K", K), ("V", V), ("dO", dO)):
+        _require(t, name, (B, H, L, d), dt)
+    _require(alpha, "alpha", (B, H, L), torch.float32)
+    _require(beta, "beta", (B, H, L), torch.float32)
+    _require(mask, "mask", (B, H, L), torch.uint8)
+    _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
+    unknown = set(want) - {"d_initial_state", "g_nla"}
+    if unknown:
+        raise ValueError(f"unknown outputs {sorted(unknown)}")
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, NATS_MATH_AUTO,
+                             NATS_ROUTE_TOKEN, linear_op, freeze_on_softmax)
+    need = int(lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(params)))
+    if need == 0:   # let the library say what is wrong with the parameters
+        _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), *([None] * 12), None, None, 0, None))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    dev = Q.device
+    res = {k: torch.empty((B, H, L, d), dtype=torch.float32, device=dev) for k in ("dQ", "dK", "dV")}
+    res["dalpha"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    res["dbeta"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    if "d_initial_state" in want: res["d_initial_state"] = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    if "g_nla" in want: res["g_nla"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    g = lambda k: res[k].data_ptr() if k in res else None
+    extra = BwdExtra(initial_state.data_ptr() if initial_state is not None else None, g("d_initial_state"), g("g_nla"))
+    _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta), _ptr(mask),
+                                    _ptr(dO), _ptr(res["dQ"]), _ptr(res["dK"]), _ptr(res["dV"]), _ptr(res["dalpha"]),
+                                    _ptr(res["dbeta"]), ctypes.byref(extra), _ptr(workspace), workspace.numel(),
+                                    _stream_ptr()))
+    return res
 
 
 def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, *,

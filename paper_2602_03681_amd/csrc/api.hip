@@ -166,6 +166,39 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     return NATS_OK;
 }
 
+// Workspace of the backward pass, behind the forward's integer bookkeeping and compacted cache (the same
+// offsets): branch output and lse of the softmax branch, D_i, checkpoints of the state, the scratch rows of
+// the reverse sweep and the partial sums of its blocks.
+struct BwdPlan {
+    size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, total;
+};
+static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
+    const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / 64;
+    size_t off = align_up(pl.off_ola, 256);   // first byte behind cnt, idx, n_s, Kc, Vc
+    bp->off_onla = off;    off = align_up(off + n_tok * pl.d * 4, 256);
+    bp->off_lse = off;     off = align_up(off + n_tok * 4, 256);
+    bp->off_dvec = off;    off = align_up(off + n_tok * 4, 256);
+    bp->off_ckpt = off;    off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
+    bp->off_scratch = off; off = align_up(off + (size_t)pl.BH * ns * 64 * 64 * pl.d * 4, 256);
+    bp->off_dqp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
+    bp->off_dkp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
+    bp->off_dap = off;     off = align_up(off + ns * n_tok * 4, 256);
+    bp->off_dbp = off;     off = align_up(off + ns * n_tok * 4, 256);
+    bp->total = off;
+}
+
+static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, BwdPlan* bp) {
+    nats_status st = validate_fwd_params(p, pl);
+    if (st != NATS_OK) return st;
+    if (pl->routing != NATS_ROUTE_TOKEN || pl->combine_mode != 0) {
+        set_error("the backward pass covers routing per token with the plain-sum merge (routing %d, combine_mode %d given)",
+                  pl->routing, pl->combine_mode);
+        return NATS_ERR_UNSUPPORTED;
+    }
+    plan_bwd(*pl, bp);
+    return NATS_OK;
+}
+
 }  // namespace nats
 
 using namespace nats;
@@ -174,7 +207,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 103; }
+int nats_abi_version(void) { return 104; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -355,13 +388,103 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
             ProfScope ps("gdn_recurrent", stream);
             st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la,
                                       pl.routing == NATS_ROUTE_CHUNK ? reinterpret_cast<float*>(ws + pl.off_snap) : nullptr,
-                                      stream);
+                                      nullptr, stream);
         }
         if (st != NATS_OK) return st;
         ProfScope ps("softmax_fp32", stream);
         st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
     }
     return st;
+}
+
+size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p) {
+    FwdPlan pl;
+    BwdPlan bp;
+    if (validate_bwd_params(p, &pl, &bp) != NATS_OK) return 0;
+    return bp.total;
+}
+
+nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask, const void* dO,
+                                 float* dQ, float* dK, float* dV, float* dalpha, float* dbeta,
+                                 const nats_bwd_extra* extra, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+    FwdPlan pl;
+    BwdPlan bp;
+    nats_status st = validate_bwd_params(p, &pl, &bp);
+    if (st != NATS_OK) return st;
+    if (!Q || !K || !V || !alpha || !beta || !mask || !dO || !dQ || !dK || !dV || !dalpha || !dbeta) {
+        set_error("Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha and dbeta must all be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    if (workspace == nullptr || workspace_bytes < bp.total) {
+        set_error("workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, bp.total);
+        return NATS_ERR_WORKSPACE;
+    }
+    nats_bwd_extra ex;
+    memset(&ex, 0, sizeof(ex));
+    if (extra) ex = *extra;
+    const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
+                          ex.d_initial_state, ex.g_nla};
+    for (const void* ptr : ptrs)
+        if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
+    for (const void* o : outs)
+        if (o == Q || o == K || o == V || o == dO || o == alpha || o == beta) {
+            set_error("a gradient output must not alias an input");
+            return NATS_ERR_SHAPE;
+        }
+
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    int32_t* cnt = reinterpret_cast<int32_t*>(ws + pl.off_cnt);
+    int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
+    int32_t* n_s = reinterpret_cast<int32_t*>(ws + pl.off_ns);
+    void* Kc = ws + pl.off_kc;
+    void* Vc = ws + pl.off_vc;
+    float* O_nla = reinterpret_cast<float*>(ws + bp.off_onla);
+    float* lse = reinterpret_cast<float*>(ws + bp.off_lse);
+    float* Dvec = reinterpret_cast<float*>(ws + bp.off_dvec);
+    float* ckpt = reinterpret_cast<float*>(ws + bp.off_ckpt);
+    float* scratch = reinterpret_cast<float*>(ws + bp.off_scratch);
+    float* dqp = reinterpret_cast<float*>(ws + bp.off_dqp);
+    float* dkp = reinterpret_cast<float*>(ws + bp.off_dkp);
+    float* dap = reinterpret_cast<float*>(ws + bp.off_dap);
+    float* dbp = reinterpret_cast<float*>(ws + bp.off_dbp);
+    {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
+        ProfScope ps("scan_compact", stream);
+        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, nullptr, nullptr, stream);
+        if (st != NATS_OK) return st;
+    }
+    {
+        ProfScope ps("softmax_fp32", stream);
+        st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
+        if (st != NATS_OK) return st;
+    }
+    {   // dQ = the softmax branch's share (written); also D_i
+        ProfScope ps("softmax_bwd_dq", stream);
+        st = launch_softmax_bwd_dq(pl, Q, Kc, Vc, dO, cnt, O_nla, lse, Dvec, dQ, stream);
+        if (st != NATS_OK) return st;
+    }
+    {   // the linear branch forwards once more, leaving a checkpoint of the state per chunk
+        ProfScope ps("gdn_recurrent", stream);
+        st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, nullptr, nullptr, nullptr, ckpt, stream);
+        if (st != NATS_OK) return st;
+    }
+    {
+        ProfScope ps("gdn_recurrent_bwd", stream);
+        st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
+                                      ex.d_initial_state, stream);
+        if (st != NATS_OK) return st;
+    }
+    {   // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
+        ProfScope ps("bwd_combine", stream);
+        st = launch_bwd_combine(pl, dqp, dkp, dap, dbp, dQ, dK, dalpha, dbeta, ex.g_nla, stream);
+        if (st != NATS_OK) return st;
+    }
+    // rows of the softmax tokens in dK, dV (their linear share is zero) and g_nla
+    ProfScope ps("softmax_bwd_dkv", stream);
+    return launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla, stream);
 }
 
 nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,

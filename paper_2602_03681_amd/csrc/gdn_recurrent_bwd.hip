@@ -1,0 +1,291 @@
+// Backward of the linear branch in fp32 arithmetic (Section 4.2): the reverse sweep of
+//     Sd = a_t S_{t-1};   linear token:  r = v_t - Sd k_t,  S_t = Sd + b_t r k_t^T   (Eq. 19, delta rule; the
+//     gated operation has r = v_t);   softmax token: S_t = Sd (Eq. 14);   o_t = la_scale S_t q_t
+// with dS the gradient of the state after token t (from the tokens behind it) and do_t given:
+//     dq_t  = la_scale S_t^T do_t ;              dS += la_scale do_t q_t^T
+//     linear token:  A = dS k_t ;  dbeta_t = r . A ;  dr = b_t A ;  dv_t = dr ;
+//                    dk_t = b_t dS^T r - Sd^T dr ;  dS -= dr k_t^T          (the last two terms: delta rule only)
+//     dalpha_t = <dS, S_{t-1}> = <dS, Sd> / a_t ;  dS <- a_t dS
+// Rows of S (index d_v) never mix, so, as in the forward kernel, one thread owns one row: of dS in
+// registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
+// pass: it leaves one checkpoint per chunk of 64 tokens, and a block walks the chunks from the back, first
+// re-running the chunk forwards from its checkpoint and parking the 64 rows Sd in a scratch area (2 MB per
+// block for d = 128, written and read once, laid out so that a wavefront's accesses are contiguous), then
+// sweeping it backwards.  dq_t, dk_t (vectors over d_k) and dalpha_t, dbeta_t add up over all rows: a block
+// (64 rows) reduces its share through LDS, in a fixed order, and writes one partial per block; a small kernel
+// adds the partials (d / 64 of them) and finishes the outputs.  No floating-point atomics.
+//
+// VALU- and latency-bound (one wavefront per block, d / 64 blocks per (batch, head)): this is the path for
+// checking gradients and for small problems, the counterpart of the fp32 forward path.
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int RB_ROWS = 64;   // state rows (threads) per block: one wavefront
+constexpr int RB_TT = 16;     // tokens staged per tile
+constexpr int RB_CH = 64;     // tokens between checkpoints
+
+template <typename T, int D>
+__global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
+    const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
+    const float* __restrict__ ckpt, float* __restrict__ scratch, float* __restrict__ dq_part,
+    float* __restrict__ dk_part, float* __restrict__ dalpha_part, float* __restrict__ dbeta_part,
+    float* __restrict__ dV, float* __restrict__ dS0, int L, int BH, float la_scale, int linear_op,
+    int freeze_on_softmax) {
+    constexpr int EPL = Vec16<T>::N;
+    constexpr int RSTR = D + 1;   // row stride of the reduction tile: rows and columns both hit distinct banks
+    __shared__ __align__(16) float s_k[RB_TT][D];
+    __shared__ __align__(16) float s_q[RB_TT][D];
+    __shared__ float s_v[RB_TT][RB_ROWS], s_do[RB_TT][RB_ROWS];
+    __shared__ float s_a[RB_TT], s_b[RB_TT];
+    __shared__ uint8_t s_dec[RB_TT];           // 1: the decay acts at this token
+    __shared__ uint8_t s_lin[RB_TT];           // 1: linear token (the state is written)
+    __shared__ float s_red[RB_ROWS * RSTR];
+
+    const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
+    const int row = slice * RB_ROWS + tid;
+    const size_t base = (size_t)bh * L;
+    const int n_chunks = L / RB_CH;
+    const size_t n_tok = (size_t)BH * L;
+    // this block's scratch: [token of the chunk][d_k / 4][row][4]
+    float* my_scr = scratch + ((size_t)bh * gridDim.x + slice) * (size_t)(RB_CH * D * RB_ROWS);
+    float* dq_p = dq_part + (size_t)slice * n_tok * D;
+    float* dk_p = dk_part + (size_t)slice * n_tok * D;
+    float* da_p = dalpha_part + (size_t)slice * n_tok;
+    float* db_p = dbeta_part + (size_t)slice * n_tok;
+
+    // stages tokens [t0, t0 + RB_TT): k, v and the gates always, q and do for the backward sweep
+    auto stage = [&](int t0, bool with_q) {
+        __syncthreads();
+        for (int e = tid * EPL; e < RB_TT * D; e += RB_ROWS * EPL) {
+            const int i = e / D, c = e % D;
+            float tmp[EPL];
+            Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_k[i][c + j] = tmp[j];
+            if (with_q) {
+                Vec16<T>::load(Q + (base + t0 + i) * D + c, tmp);
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) s_q[i][c + j] = tmp[j];
+            }
+        }
+        for (int e = tid * EPL; e < RB_TT * RB_ROWS; e += RB_ROWS * EPL) {
+            const int i = e / RB_ROWS, c = e % RB_ROWS;
+            float tmp[EPL];
+            Vec16<T>::load(V + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
+            if (with_q) {
+                Vec16<T>::load(dO + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) s_do[i][c + j] = tmp[j];
+            }
+        }
+        if (tid < RB_TT) {
+            const bool soft = mask[base + t0 + tid] != 0;
+            const bool dec = !(soft && freeze_on_softmax);
+            s_dec[tid] = dec ? 1 : 0;
+            s_lin[tid] = soft ? 0 : 1;
+            s_a[tid] = dec ? alpha[base + t0 + tid] : 1.f;
+            s_b[tid] = soft ? 0.f : beta[base + t0 + tid];
+        }
+        __syncthreads();
+    };
+
+    float dS[D];
+#pragma unroll
+    for (int c = 0; c < D; ++c) dS[c] = 0.f;
+
+    for (int chunk = n_chunks - 1; chunk >= 0; --chunk) {
+        const int tc0 = chunk * RB_CH;
+        // ---- forwards through the chunk from its checkpoint: park Sd of every token ----------------
+        {
+            float S[D];
+            const float* src = ckpt + (((size_t)bh * n_chunks + chunk) * D + row) * D;
+#pragma unroll
+            for (int c = 0; c < D; c += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(src + c);
+                S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
+            }
+            for (int tt = 0; tt < RB_CH; tt += RB_TT) {
+                stage(tc0 + tt, false);
+                for (int i = 0; i < RB_TT; ++i) {
+                    const float a = s_a[i], b = s_b[i];
+                    float* dst = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;
+                    float pred = 0.f;
+#pragma unroll
+                    for (int c = 0; c < D; c += 4) {
+                        const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                        S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
+                        *reinterpret_cast<float4*>(dst + (c / 4) * (RB_ROWS * 4)) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+                        pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
+                    }
+                    if (s_lin[i]) {   // uniform across the block
+                        const float delta = b * (s_v[i][tid] - (linear_op == 0 ? pred : 0.f));
+#pragma unroll
+                        for (int c = 0; c < D; c += 4) {
+                            const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                            S[c] += delta * k4.x; S[c + 1] += delta * k4.y; S[c + 2] += delta * k4.z; S[c + 3] += delta * k4.w;
+                        }
+                    }
+                }
+            }
+        }
+        // ---- backwards through the chunk ------------------------------------------------------------
+        for (int tt = RB_CH - RB_TT; tt >= 0; tt -= RB_TT) {
+            stage(tc0 + tt, true);   // its leading barrier also orders the scratch stores before the loads below
+            for (int i = RB_TT - 1; i >= 0; --i) {
+                const int t = tc0 + tt + i;
+                const float a = s_a[i], b = s_b[i], go = la_scale * s_do[i][tid];
+                const float* src = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;
+                float Sd[D];
+                float pred = 0.f;
+#pragma unroll
+                for (int c = 0; c < D; c += 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RB_ROWS * 4));
+                    const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                    Sd[c] = x.x; Sd[c + 1] = x.y; Sd[c + 2] = x.z; Sd[c + 3] = x.w;
+                    pred += x.x * k4.x + x.y * k4.y + x.z * k4.z + x.w * k4.w;
+                }
+                const bool lin = s_lin[i] != 0;   // uniform across the block
+                const float r = lin ? s_v[i][tid] - (linear_op == 0 ? pred : 0.f) : 0.f;
+                // dq_t: this row's share la_scale do S_t, S_t = Sd + b r k;   dS += la_scale do q^T;   A = dS k
+                float A = 0.f;
+                const float br = b * r;
+#pragma unroll
+                for (int c = 0; c < D; ++c) {
+                    const float kc = s_k[i][c];
+                    s_red[tid * RSTR + c] = go * (Sd[c] + br * kc);
+                    dS[c] += go * s_q[i][c];
+                    A += dS[c] * kc;
+                }
+                __syncthreads();
+                for (int c = tid; c < D; c += RB_ROWS) {
+                    float sum = 0.f;
+                    for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
+                    dq_p[(base + t) * D + c] = sum;
+                }
+                __syncthreads();
+                float dbeta_p = 0.f, dr = 0.f;
+                if (lin) {
+                    dbeta_p = r * A;
+                    dr = b * A;
+                    const float drd = linear_op == 0 ? dr : 0.f;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) {
+                        const float kc = s_k[i][c];
+                        s_red[tid * RSTR + c] = br * dS[c] - drd * Sd[c];
+                        dS[c] -= drd * kc;
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < D; ++c) s_red[tid * RSTR + c] = 0.f;
+                }
+                __syncthreads();
+                for (int c = tid; c < D; c += RB_ROWS) {
+                    float sum = 0.f;
+                    for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
+                    dk_p[(base + t) * D + c] = sum;
+                }
+                dV[(base + t) * D + row] = dr;
+                float dalpha_p = 0.f;
+                if (s_dec[i]) {   // uniform
+#pragma unroll
+                    for (int c = 0; c < D; ++c) { dalpha_p += dS[c] * Sd[c]; dS[c] *= a; }
+                    dalpha_p /= fmaxf(a, 1e-30f);   // S_{t-1} = Sd / a
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    dalpha_p += __shfl_xor(dalpha_p, off);
+                    dbeta_p += __shfl_xor(dbeta_p, off);
+                }
+                if (tid == 0) { da_p[base + t] = dalpha_p; db_p[base + t] = dbeta_p; }
+                __syncthreads();   // the reduction tile is free again
+            }
+        }
+    }
+    if (dS0 != nullptr) {
+        float* dst = dS0 + ((size_t)bh * D + row) * D;
+#pragma unroll
+        for (int c = 0; c < D; c += 4) *reinterpret_cast<float4*>(dst + c) = make_float4(dS[c], dS[c + 1], dS[c + 2], dS[c + 3]);
+    }
+}
+
+// dQ += sum of the blocks' partials (it already holds the softmax branch's share); dK, dalpha, dbeta = the sums;
+// g_nla (optional) is cleared for the kernel that fills in the softmax tokens' entries afterwards.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_combine_kernel(
+    const float* __restrict__ dq_part, const float* __restrict__ dk_part, const float* __restrict__ dalpha_part,
+    const float* __restrict__ dbeta_part, float* __restrict__ dQ, float* __restrict__ dK,
+    float* __restrict__ dalpha, float* __restrict__ dbeta, float* __restrict__ g_nla, size_t n_tok) {
+    constexpr int NS = D / RB_ROWS;
+    const size_t n4 = n_tok * D / 4;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256) {
+        float4 q = reinterpret_cast<const float4*>(dQ)[e];
+        float4 k = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const float4 a = reinterpret_cast<const float4*>(dq_part + (size_t)s * n_tok * D)[e];
+            const float4 b = reinterpret_cast<const float4*>(dk_part + (size_t)s * n_tok * D)[e];
+            q.x += a.x; q.y += a.y; q.z += a.z; q.w += a.w;
+            k.x += b.x; k.y += b.y; k.z += b.z; k.w += b.w;
+        }
+        reinterpret_cast<float4*>(dQ)[e] = q;
+        reinterpret_cast<float4*>(dK)[e] = k;
+    }
+    for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < n_tok; t += (size_t)gridDim.x * 256) {
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) { a += dalpha_part[(size_t)s * n_tok + t]; b += dbeta_part[(size_t)s * n_tok + t]; }
+        dalpha[t] = a;
+        dbeta[t] = b;
+        if (g_nla != nullptr) g_nla[t] = 0.f;
+    }
+}
+
+template <typename T>
+static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO, const float* alpha,
+                      const float* beta, const uint8_t* mask, const float* ckpt, float* scratch, float* dq_part,
+                      float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
+    dim3 grid(pl.d / RB_ROWS, pl.BH);
+    if (pl.d == 64)
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RB_ROWS), 0, st, (const T*)Q, (const T*)K,
+                           (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
+                           dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
+    else
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RB_ROWS), 0, st, (const T*)Q, (const T*)K,
+                           (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
+                           dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
+}
+
+// scratch: BH * (d / 64) * 64 * d * 64 floats;  dq_part, dk_part: (d / 64) * BH * L * d floats;
+// dalpha_part, dbeta_part: (d / 64) * BH * L floats;  dV [B,H,L,d] f32 is written for every token
+nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
+                                     const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
+                                     float* scratch, float* dq_part, float* dk_part, float* dalpha_part,
+                                     float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
+    if (pl.dtype == NATS_BF16)
+        launch_rb<bf16_t>(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,
+                          dV, dS0, st);
+    else
+        launch_rb<float>(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,
+                         dV, dS0, st);
+    return check_launch("gdn_recurrent_bwd");
+}
+
+nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,
+                               const float* dbeta_part, float* dQ, float* dK, float* dalpha, float* dbeta,
+                               float* g_nla, hipStream_t st) {
+    const size_t n_tok = (size_t)pl.BH * pl.L;
+    const unsigned blocks = (unsigned)((n_tok * pl.d / 4 + 255) / 256 < 4096 ? (n_tok * pl.d / 4 + 255) / 256 : 4096);
+    if (pl.d == 64)
+        hipLaunchKernelGGL(bwd_combine_kernel<64>, dim3(blocks), dim3(256), 0, st, dq_part, dk_part, dalpha_part,
+                           dbeta_part, dQ, dK, dalpha, dbeta, g_nla, n_tok);
+    else
+        hipLaunchKernelGGL(bwd_combine_kernel<128>, dim3(blocks), dim3(256), 0, st, dq_part, dk_part, dalpha_part,
+                           dbeta_part, dQ, dK, dalpha, dbeta, g_nla, n_tok);
+    return check_launch("bwd_combine");
+}
+
+}  // namespace nats

@@ -128,7 +128,8 @@ nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const vo
                                 hipStream_t st);
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
-                                 const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st);
+                                 const float* S0, float* S_final, float* O_la, float* snap, float* ckpt,
+                                 hipStream_t st);   // O_la may be NULL; ckpt [BH][L/64][d][d]: state before every chunk
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
@@ -163,5 +164,20 @@ nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const vo
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,
                                  const float* chunk_decay, int32_t* chunk_pos, int32_t* cache_len,
                                  const uint8_t* mask_c, int32_t* err_flags, hipStream_t st);
+
+// ---- backward pass (fp32 arithmetic) ----
+nats_status launch_softmax_bwd_dq(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
+                                  const int32_t* cnt, const float* O_nla, const float* lse, float* Dvec, float* dQ,
+                                  hipStream_t st);
+nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
+                                   const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* lse,
+                                   const float* Dvec, float* dK, float* dV, float* g_nla, hipStream_t st);
+nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
+                                     const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
+                                     float* scratch, float* dq_part, float* dk_part, float* dalpha_part,
+                                     float* dbeta_part, float* dV, float* dS0, hipStream_t st);
+nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,
+                               const float* dbeta_part, float* dQ, float* dK, float* dalpha, float* dbeta,
+                               float* g_nla, hipStream_t st);
 
 }  // namespace nats

@@ -135,6 +135,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
             *reinterpret_cast<float4*>(O_nla_out + row_off + c) =
                 make_float4(acc[c], acc[c + 1], acc[c + 2], acc[c + 3]);
     }
+    if (O == nullptr) return;   // the caller wanted the branch output and lse only (backward pass)
     float la[DP];
 #pragma unroll
     for (int c = 0; c < DP; c += 4) {

@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 103   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`
+    assert lib.nats_abi_version() == 104   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points
 
 
 def good_params(**over):
@@ -156,6 +156,32 @@ def test_route_chunks_and_merge_weights_validation(lib):
     assert mw(None, FAKE, FAKE, FAKE) == E_NULL
     assert mw(FAKE + 4, FAKE, FAKE, FAKE) == E_ALIGN
     assert lib.nats_merge_weights(ctypes.byref(good_params(d=96)), FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
+
+
+def test_backward_validation(lib):
+    p = good_params()
+    need = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(p))
+    assert need > nb.fwd_workspace_bytes(p) // 2
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK))) == 0
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(combine_mode=1))) == 0
+
+    def call(prm, ptrs=None, ws=FAKE, ws_bytes=1 << 40):
+        ptrs = [FAKE + 16 * i for i in range(12)] if ptrs is None else ptrs
+        return lib.nats_hybrid_attn_bwd(ctypes.byref(prm), *ptrs, None, ws, ws_bytes, None)
+
+    assert call(good_params(routing=nb.NATS_ROUTE_CHUNK)) == E_UNSUP
+    assert call(good_params(combine_mode=1)) == E_UNSUP
+    assert call(good_params(L=100)) == E_SHAPE
+    ptrs = [FAKE + 16 * i for i in range(12)]
+    ptrs[6] = None                                     # dO
+    assert call(p, ptrs) == E_NULL
+    ptrs = [FAKE + 16 * i for i in range(12)]
+    ptrs[8] = FAKE + 4                                 # dK
+    assert call(p, ptrs) == E_ALIGN
+    ptrs = [FAKE + 16 * i for i in range(12)]
+    ptrs[7] = ptrs[0]                                  # dQ aliases Q
+    assert call(p, ptrs) == E_SHAPE
+    assert call(p, ws_bytes=need - 1) == E_WS
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

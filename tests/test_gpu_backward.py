@@ -1,0 +1,97 @@
+"""GPU parity of the backward pass (Section 4.2; fp32 arithmetic, routing per token, plain-sum merge) against
+the backward oracle, through the C ABI.  Every gradient tensor is held to max|err| / RMS(oracle) <= 1e-4 (the
+outputs are fp32 whatever the input dtype)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_03681_amd as nats
+from paper_2602_03681_amd import binding as nb
+from nats_inputs import make_fwd_inputs, make_grad_output
+from oracle import nats_oracle_bwd as nbw
+
+from gpu_util import host, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL_BWD = 1e-4
+KEYS = (("dQ", "dQ"), ("dK", "dK"), ("dV", "dV"), ("dalpha", "dalpha"), ("dbeta", "dbeta"))
+
+
+def run_bwd(x, dO, dtype, want=("d_initial_state", "g_nla"), S0=None, **kw):
+    g = to_dev(x, dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    r = nats.hybrid_attn_bwd(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"],
+                             torch.from_numpy(dO).to(tdt).cuda(), want=want,
+                             initial_state=None if S0 is None else torch.from_numpy(S0.astype(np.float32)).cuda(), **kw)
+    torch.cuda.synchronize()
+    return r
+
+
+def check(r, ref, extra=()):
+    errs = {}
+    for got, want in KEYS + tuple(extra):
+        a, b = host(r[got]), ref[want]
+        if np.all(b == 0):
+            assert np.all(a == 0), got          # e.g. dbeta when nothing is ever written
+            continue
+        errs[got] = rel_err(a, b)
+    for k, e in errs.items():
+        assert e <= TOL_BWD, f"{k}: {e:.3e} (all: {errs})"
+    return errs
+
+
+@pytest.mark.parametrize("dtype,B,H,L,d,p", [("f32", 1, 2, 320, 64, 0.15), ("f32", 2, 2, 256, 128, 0.1),
+                                             ("bf16", 1, 3, 1088, 64, 0.08), ("bf16", 1, 2, 448, 128, 0.2),
+                                             ("f32", 1, 1, 64, 64, 0.5)])
+def test_backward_matches_the_oracle(dtype, B, H, L, d, p):
+    x = make_fwd_inputs(B, H, L, d, dtype, p, seed=200 + L + d)
+    dO = make_grad_output(B, H, L, d, dtype, seed=300 + L)
+    S0 = (0.05 * np.random.default_rng(L).standard_normal((B, H, d, d))).astype(np.float32)
+    r = run_bwd(x, dO, dtype, S0=S0)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, S0=S0)
+    errs = check(r, ref, extra=(("d_initial_state", "dS0"), ("g_nla", "g_nla")))
+    print(dtype, L, d, errs)
+    # Section 4.2: nothing for the operation a token is inactive for
+    soft = x["mask"] != 0
+    assert np.all(host(r["dbeta"])[soft] == 0)
+    assert np.all(host(r["g_nla"])[~soft] == 0)
+
+
+@pytest.mark.parametrize("linear_op,freeze", [(nb.NATS_LINEAR_GATED, False), (nb.NATS_LINEAR_GDN, True),
+                                              (nb.NATS_LINEAR_GATED, True)])
+def test_backward_variants_and_scales(linear_op, freeze):
+    B, H, L, d = 1, 2, 256, 64
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.2, seed=410 + linear_op)
+    dO = make_grad_output(B, H, L, d, "f32", seed=411)
+    r = run_bwd(x, dO, "f32", softmax_scale=0.3, la_scale=1.7, linear_op=linear_op, freeze_on_softmax=freeze)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, softmax_scale=0.3, la_scale=1.7,
+                         linear_op=linear_op, decay_on_softmax=not freeze)
+    check(r, ref, extra=(("d_initial_state", "dS0"), ("g_nla", "g_nla")))
+    if freeze:   # no decay on softmax tokens: their alpha has no effect at all
+        assert np.all(host(r["dalpha"])[x["mask"] != 0] == 0)
+
+
+@pytest.mark.parametrize("kind", ["all_softmax", "all_linear"])
+def test_backward_degenerate_masks(kind):
+    B, H, L, d = 1, 2, 192, 64
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=420)
+    x["mask"][:] = 1 if kind == "all_softmax" else 0
+    dO = make_grad_output(B, H, L, d, "f32", seed=421)
+    r = run_bwd(x, dO, "f32")
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO)
+    check(r, ref, extra=(("g_nla", "g_nla"),) if kind == "all_softmax" else ())
+    if kind == "all_linear":
+        assert np.all(host(r["g_nla"]) == 0)
+
+
+def test_backward_is_deterministic_and_reuses_a_poisoned_workspace():
+    B, H, L, d = 1, 2, 256, 128
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=430)
+    dO = make_grad_output(B, H, L, d, "bf16", seed=431)
+    prm = nb.make_fwd_params(B, H, L, d, 64, nb.NATS_BF16)
+    n = int(nb.load_library().nats_hybrid_attn_bwd_workspace_bytes(__import__("ctypes").byref(prm)))
+    ws = torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda")
+    r1 = run_bwd(x, dO, "bf16", workspace=ws)
+    r2 = run_bwd(x, dO, "bf16")
+    for k in ("dQ", "dK", "dV", "dalpha", "dbeta", "g_nla", "d_initial_state"):
+        assert torch.equal(r1[k], r2[k]), k
