@@ -113,6 +113,58 @@ def bench_decode(args):
     print(json.dumps(out))
 
 
+def bench_backward(args):
+    """Backward pass on workload 2's shapes (fp32 arithmetic; the recurrence's reverse sweep dominates): a step
+    is one nats_hybrid_attn_bwd call.  Roofline: plain fp32 vector arithmetic of the reverse sweep."""
+    import torch
+
+    import paper_2602_03681_amd as nats
+    from paper_2602_03681_amd import binding as nb
+    from nats_inputs import CONFIGS, make_config_inputs, make_grad_output
+
+    cfg = CONFIGS["cfg2_headline_bf16"]
+    x = make_config_inputs(cfg)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    g = {k: torch.from_numpy(v).to(dev) for k, v in x.items()}
+    Q, K, V = (g[k].to(torch.bfloat16) for k in ("Q", "K", "V"))
+    dO = torch.from_numpy(make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 1)).to(dev).to(torch.bfloat16)
+    import ctypes
+    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16)
+    ws = torch.empty(int(nb.load_library().nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(prm))), dtype=torch.uint8,
+                     device=dev)
+
+    def step():
+        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws)
+
+    steps = max(1, min(args.steps, 5))
+    for _ in range(max(1, min(args.warmup, 2))):
+        step()
+    torch.cuda.synchronize()
+    nb.profile_begin(16 * steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern = nb.profile_end()
+    n_tok = cfg.B * cfg.H * cfg.L
+    dom = max(kern, key=lambda k: kern[k]["total_ms"])
+    # reverse sweep: about 25 d_k flops per state row and token (re-run of the chunk, then the adjoint)
+    flops = 25.0 * n_tok * cfg.d * cfg.d
+    achieved = flops / (kern["gdn_recurrent_bwd"]["avg_ms"] * 1e-3) / 1e12
+    out = {"metric": "hybrid_attn_bwd_tokens_per_s", "value": round(cfg.B * cfg.L / (ms * 1e-3), 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 arithmetic, fp32 gradients)"},
+           "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,
+           "roofline": {"kernel": "gdn_recurrent_bwd", "bound": "alu", "achieved": round(achieved, 3), "peak": 157.3,
+                        "unit": "TFLOP/s", "frac": round(achieved / 157.3, 5), "traffic": None,
+                        "avg_kernel_ms": round(kern["gdn_recurrent_bwd"]["avg_ms"], 4)},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,12 +182,15 @@ def main():
     ap.add_argument("--routing", choices=("token", "chunk"), default="token",
                     help="granularity of the routing mask: per token (default, the headline workload) or per chunk")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
+    ap.add_argument("--backward", action="store_true", help="measure the backward pass (fp32 arithmetic) instead")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
 
     if args.decode:
         return bench_decode(args)
+    if args.backward:
+        return bench_backward(args)
 
     import numpy as np
     import torch

@@ -388,7 +388,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
             ProfScope ps("gdn_recurrent", stream);
             st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, ex.final_state, O_la,
                                       pl.routing == NATS_ROUTE_CHUNK ? reinterpret_cast<float*>(ws + pl.off_snap) : nullptr,
-                                      nullptr, stream);
+                                      stream);
         }
         if (st != NATS_OK) return st;
         ProfScope ps("softmax_fp32", stream);
@@ -467,8 +467,8 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         if (st != NATS_OK) return st;
     }
     {   // the linear branch forwards once more, leaving a checkpoint of the state per chunk
-        ProfScope ps("gdn_recurrent", stream);
-        st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, nullptr, nullptr, nullptr, ckpt, stream);
+        ProfScope ps("gdn_checkpoints", stream);
+        st = launch_gdn_checkpoints(pl, K, V, alpha, beta, mask, ex.initial_state, ckpt, stream);
         if (st != NATS_OK) return st;
     }
     {

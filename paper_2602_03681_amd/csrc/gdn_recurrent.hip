@@ -20,8 +20,7 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
-    float* __restrict__ snap, float* __restrict__ ckpt, int L, float la_scale, int linear_op,
-    int freeze_on_softmax) {
+    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax) {
     __shared__ __align__(16) float s_k[REC_TT][D];
     __shared__ __align__(16) float s_q[REC_TT][D];
     __shared__ float s_v[REC_TT][REC_ROWS];
@@ -85,13 +84,6 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
         for (int i = 0; i < REC_TT; ++i) {
             const float a = s_a[i], b = s_b[i];
             float o = 0.f;
-            // for the backward pass: the row as it stands before every chunk of 64 tokens, [bh][chunk][row][D]
-            if (ckpt != nullptr && ((t0 + i) & 63) == 0) {
-                float* dst = ckpt + (((size_t)bh * (L / 64) + ((t0 + i) >> 6)) * D + row) * D;
-#pragma unroll
-                for (int c = 0; c < D; c += 4)
-                    *reinterpret_cast<float4*>(dst + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
-            }
             if (chunk_mask && ((t0 + i) & 63) == 0) {   // chunk start (uniform)
 #pragma unroll
                 for (int c = 0; c < D; c += 4)
@@ -125,7 +117,7 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
                     o += S[c] * q4.x + S[c + 1] * q4.y + S[c + 2] * q4.z + S[c + 3] * q4.w;
                 }
             }
-            if (O_la != nullptr) O_la[(base + t0 + i) * D + row] = la_scale * o;
+            O_la[(base + t0 + i) * D + row] = la_scale * o;
             if (chunk_mask && ((t0 + i) & 63) == 63 && mask_c[(t0 + i) >> 6]) {   // end of a softmax chunk
                 if (freeze_on_softmax) chunk_decay = 1.f;   // variant: a softmax chunk leaves the state as it found it
 #pragma unroll
@@ -148,26 +140,25 @@ __global__ __launch_bounds__(REC_ROWS) void gdn_recurrent_kernel(
 template <typename T>
 static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const void* V, const float* alpha,
                        const float* beta, const uint8_t* mask, const float* S0, float* S_final,
-                       float* O_la, float* snap, float* ckpt, hipStream_t st) {
+                       float* O_la, float* snap, hipStream_t st) {
     dim3 grid(pl.d / REC_ROWS, pl.BH);
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, ckpt, pl.L, pl.la_scale,
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
                            pl.linear_op, pl.freeze_on_softmax);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_ROWS), 0, st, (const T*)Q,
-                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, ckpt, pl.L, pl.la_scale,
+                           (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
                            pl.linear_op, pl.freeze_on_softmax);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
-                                 const float* S0, float* S_final, float* O_la, float* snap, float* ckpt,
-                                 hipStream_t st) {
+                                 const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st) {
     if (pl.dtype == NATS_BF16)
-        launch_rec<bf16_t>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, ckpt, st);
+        launch_rec<bf16_t>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, st);
     else
-        launch_rec<float>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, ckpt, st);
+        launch_rec<float>(pl, Q, K, V, alpha, beta, mask, S0, S_final, O_la, snap, st);
     return check_launch("gdn_recurrent");
 }
 

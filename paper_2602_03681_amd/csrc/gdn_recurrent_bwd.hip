@@ -6,8 +6,8 @@
 //     linear token:  A = dS k_t ;  dbeta_t = r . A ;  dr = b_t A ;  dv_t = dr ;
 //                    dk_t = b_t dS^T r - Sd^T dr ;  dS -= dr k_t^T          (the last two terms: delta rule only)
 //     dalpha_t = <dS, S_{t-1}> = <dS, Sd> / a_t ;  dS <- a_t dS
-// Rows of S (index d_v) never mix, so, as in the forward kernel, one thread owns one row: of dS in
-// registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
+// Rows of S (index d_v) never mix: four adjacent lanes own one row (a quarter of its d_k columns each): of dS
+// in registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
 // pass: it leaves one checkpoint per chunk of 64 tokens, and a block walks the chunks from the back, first
 // re-running the chunk forwards from its checkpoint and parking the 64 rows Sd in a scratch area (2 MB per
 // block for d = 128, written and read once, laid out so that a wavefront's accesses are contiguous), then
@@ -15,18 +15,19 @@
 // (64 rows) reduces its share through LDS, in a fixed order, and writes one partial per block; a small kernel
 // adds the partials (d / 64 of them) and finishes the outputs.  No floating-point atomics.
 //
-// VALU- and latency-bound (one wavefront per block, d / 64 blocks per (batch, head)): this is the path for
+// VALU- and latency-bound (d / 64 blocks of four wavefronts per (batch, head)): this is the path for
 // checking gradients and for small problems, the counterpart of the fp32 forward path.
 #include "nats_common.h"
 
 namespace nats {
 
-constexpr int RB_ROWS = 64;   // state rows (threads) per block: one wavefront
-constexpr int RB_TT = 16;     // tokens staged per tile
-constexpr int RB_CH = 64;     // tokens between checkpoints
+constexpr int RB_ROWS = 64;       // state rows per block
+constexpr int RB_THREADS = 256;   // 4 adjacent lanes share a row, each owns a quarter of its d_k columns
+constexpr int RB_TT = 16;         // tokens staged per tile
+constexpr int RB_CH = 64;         // tokens between checkpoints
 
 template <typename T, int D>
-__global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
+__global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ ckpt, float* __restrict__ scratch, float* __restrict__ dq_part,
@@ -34,21 +35,26 @@ __global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
     float* __restrict__ dV, float* __restrict__ dS0, int L, int BH, float la_scale, int linear_op,
     int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
-    constexpr int RSTR = D + 1;   // row stride of the reduction tile: rows and columns both hit distinct banks
-    __shared__ __align__(16) float s_k[RB_TT][D];
-    __shared__ __align__(16) float s_q[RB_TT][D];
+    constexpr int DP = D / 4;       // columns of a row per lane
+    constexpr int DPP = DP + 4;     // padded quarter stride: the four quarters land in different banks
+    constexpr int RSTR = D + 1;     // row stride of the reduction tile: rows and columns both hit distinct banks
+    __shared__ __align__(16) float s_k[RB_TT][4 * DPP];
+    __shared__ __align__(16) float s_q[RB_TT][4 * DPP];
     __shared__ float s_v[RB_TT][RB_ROWS], s_do[RB_TT][RB_ROWS];
     __shared__ float s_a[RB_TT], s_b[RB_TT];
     __shared__ uint8_t s_dec[RB_TT];           // 1: the decay acts at this token
     __shared__ uint8_t s_lin[RB_TT];           // 1: linear token (the state is written)
     __shared__ float s_red[RB_ROWS * RSTR];
+    __shared__ float s_sc[2][RB_THREADS / 64];
 
     const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
-    const int row = slice * RB_ROWS + tid;
+    const int r = tid >> 2, part = tid & 3, lane = tid & 63, wave = tid >> 6;
+    const int row = slice * RB_ROWS + r;
     const size_t base = (size_t)bh * L;
     const int n_chunks = L / RB_CH;
     const size_t n_tok = (size_t)BH * L;
-    // this block's scratch: [token of the chunk][d_k / 4][row][4]
+    // this block's scratch: [token of the chunk][group of 4 columns inside a quarter][row][quarter][4], so that
+    // the threads of the block, in order, touch consecutive 16 bytes
     float* my_scr = scratch + ((size_t)bh * gridDim.x + slice) * (size_t)(RB_CH * D * RB_ROWS);
     float* dq_p = dq_part + (size_t)slice * n_tok * D;
     float* dk_p = dk_part + (size_t)slice * n_tok * D;
@@ -58,19 +64,20 @@ __global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
     // stages tokens [t0, t0 + RB_TT): k, v and the gates always, q and do for the backward sweep
     auto stage = [&](int t0, bool with_q) {
         __syncthreads();
-        for (int e = tid * EPL; e < RB_TT * D; e += RB_ROWS * EPL) {
+        for (int e = tid * EPL; e < RB_TT * D; e += RB_THREADS * EPL) {
             const int i = e / D, c = e % D;
+            const int pq = c / DP, pc = c % DP;   // EPL divides DP: a 16-byte group stays inside one quarter
             float tmp[EPL];
             Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) s_k[i][c + j] = tmp[j];
+            for (int j = 0; j < EPL; ++j) s_k[i][pq * DPP + pc + j] = tmp[j];
             if (with_q) {
                 Vec16<T>::load(Q + (base + t0 + i) * D + c, tmp);
 #pragma unroll
-                for (int j = 0; j < EPL; ++j) s_q[i][c + j] = tmp[j];
+                for (int j = 0; j < EPL; ++j) s_q[i][pq * DPP + pc + j] = tmp[j];
             }
         }
-        for (int e = tid * EPL; e < RB_TT * RB_ROWS; e += RB_ROWS * EPL) {
+        for (int e = tid * EPL; e < RB_TT * RB_ROWS; e += RB_THREADS * EPL) {
             const int i = e / RB_ROWS, c = e % RB_ROWS;
             float tmp[EPL];
             Vec16<T>::load(V + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
@@ -92,19 +99,30 @@ __global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
         }
         __syncthreads();
     };
+    auto row_sum = [](float x) { x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); return x; };   // over a row's 4 lanes
+    // column sums of the reduction tile (rows in a fixed order) into dst[c], c = 0..D-1
+    auto reduce_tile = [&](float* dst) {
+        __syncthreads();
+        for (int c = tid; c < D; c += RB_THREADS) {
+            float sum = 0.f;
+            for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
+            dst[c] = sum;
+        }
+        __syncthreads();
+    };
 
-    float dS[D];
+    float dS[DP];
 #pragma unroll
-    for (int c = 0; c < D; ++c) dS[c] = 0.f;
+    for (int c = 0; c < DP; ++c) dS[c] = 0.f;
 
     for (int chunk = n_chunks - 1; chunk >= 0; --chunk) {
         const int tc0 = chunk * RB_CH;
         // ---- forwards through the chunk from its checkpoint: park Sd of every token ----------------
         {
-            float S[D];
-            const float* src = ckpt + (((size_t)bh * n_chunks + chunk) * D + row) * D;
+            float S[DP];
+            const float* src = ckpt + (((size_t)bh * n_chunks + chunk) * D + row) * D + part * DP;
 #pragma unroll
-            for (int c = 0; c < D; c += 4) {
+            for (int c = 0; c < DP; c += 4) {
                 const float4 x = *reinterpret_cast<const float4*>(src + c);
                 S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
             }
@@ -112,20 +130,22 @@ __global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
                 stage(tc0 + tt, false);
                 for (int i = 0; i < RB_TT; ++i) {
                     const float a = s_a[i], b = s_b[i];
+                    const float* kr = &s_k[i][part * DPP];
                     float* dst = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;
                     float pred = 0.f;
 #pragma unroll
-                    for (int c = 0; c < D; c += 4) {
-                        const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                    for (int c = 0; c < DP; c += 4) {
+                        const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
                         S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
-                        *reinterpret_cast<float4*>(dst + (c / 4) * (RB_ROWS * 4)) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+                        *reinterpret_cast<float4*>(dst + (c / 4) * (RB_THREADS * 4)) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
                         pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
                     }
                     if (s_lin[i]) {   // uniform across the block
-                        const float delta = b * (s_v[i][tid] - (linear_op == 0 ? pred : 0.f));
+                        pred = row_sum(pred);
+                        const float delta = b * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
-                        for (int c = 0; c < D; c += 4) {
-                            const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                        for (int c = 0; c < DP; c += 4) {
+                            const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
                             S[c] += delta * k4.x; S[c + 1] += delta * k4.y; S[c + 2] += delta * k4.z; S[c + 3] += delta * k4.w;
                         }
                     }
@@ -134,81 +154,162 @@ __global__ __launch_bounds__(RB_ROWS) void gdn_recurrent_bwd_kernel(
         }
         // ---- backwards through the chunk ------------------------------------------------------------
         for (int tt = RB_CH - RB_TT; tt >= 0; tt -= RB_TT) {
-            stage(tc0 + tt, true);   // its leading barrier also orders the scratch stores before the loads below
+            stage(tc0 + tt, true);
             for (int i = RB_TT - 1; i >= 0; --i) {
                 const int t = tc0 + tt + i;
-                const float a = s_a[i], b = s_b[i], go = la_scale * s_do[i][tid];
-                const float* src = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;
-                float Sd[D];
+                const float a = s_a[i], b = s_b[i], go = la_scale * s_do[i][r];
+                const bool lin = s_lin[i] != 0;   // uniform across the block
+                const float* kr = &s_k[i][part * DPP];
+                const float* qr = &s_q[i][part * DPP];
+                const float* src = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;   // this thread's own stores
+                float Sd[DP];
                 float pred = 0.f;
 #pragma unroll
-                for (int c = 0; c < D; c += 4) {
-                    const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RB_ROWS * 4));
-                    const float4 k4 = *reinterpret_cast<const float4*>(&s_k[i][c]);
+                for (int c = 0; c < DP; c += 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RB_THREADS * 4));
+                    const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
                     Sd[c] = x.x; Sd[c + 1] = x.y; Sd[c + 2] = x.z; Sd[c + 3] = x.w;
                     pred += x.x * k4.x + x.y * k4.y + x.z * k4.z + x.w * k4.w;
                 }
-                const bool lin = s_lin[i] != 0;   // uniform across the block
-                const float r = lin ? s_v[i][tid] - (linear_op == 0 ? pred : 0.f) : 0.f;
+                pred = row_sum(pred);
+                const float rv = lin ? s_v[i][r] - (linear_op == 0 ? pred : 0.f) : 0.f;
                 // dq_t: this row's share la_scale do S_t, S_t = Sd + b r k;   dS += la_scale do q^T;   A = dS k
                 float A = 0.f;
-                const float br = b * r;
+                const float br = b * rv;
 #pragma unroll
-                for (int c = 0; c < D; ++c) {
-                    const float kc = s_k[i][c];
-                    s_red[tid * RSTR + c] = go * (Sd[c] + br * kc);
-                    dS[c] += go * s_q[i][c];
+                for (int c = 0; c < DP; ++c) {
+                    const float kc = kr[c];
+                    s_red[r * RSTR + part * DP + c] = go * (Sd[c] + br * kc);
+                    dS[c] += go * qr[c];
                     A += dS[c] * kc;
                 }
-                __syncthreads();
-                for (int c = tid; c < D; c += RB_ROWS) {
-                    float sum = 0.f;
-                    for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
-                    dq_p[(base + t) * D + c] = sum;
-                }
-                __syncthreads();
+                A = row_sum(A);
+                reduce_tile(dq_p + (base + t) * D);
                 float dbeta_p = 0.f, dr = 0.f;
                 if (lin) {
-                    dbeta_p = r * A;
+                    dbeta_p = rv * A;
                     dr = b * A;
                     const float drd = linear_op == 0 ? dr : 0.f;
 #pragma unroll
-                    for (int c = 0; c < D; ++c) {
-                        const float kc = s_k[i][c];
-                        s_red[tid * RSTR + c] = br * dS[c] - drd * Sd[c];
-                        dS[c] -= drd * kc;
+                    for (int c = 0; c < DP; ++c) {
+                        s_red[r * RSTR + part * DP + c] = br * dS[c] - drd * Sd[c];
+                        dS[c] -= drd * kr[c];
                     }
                 } else {
 #pragma unroll
-                    for (int c = 0; c < D; ++c) s_red[tid * RSTR + c] = 0.f;
+                    for (int c = 0; c < DP; ++c) s_red[r * RSTR + part * DP + c] = 0.f;
                 }
-                __syncthreads();
-                for (int c = tid; c < D; c += RB_ROWS) {
-                    float sum = 0.f;
-                    for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
-                    dk_p[(base + t) * D + c] = sum;
-                }
-                dV[(base + t) * D + row] = dr;
+                reduce_tile(dk_p + (base + t) * D);
+                if (part == 0) dV[(base + t) * D + row] = dr;
                 float dalpha_p = 0.f;
                 if (s_dec[i]) {   // uniform
 #pragma unroll
-                    for (int c = 0; c < D; ++c) { dalpha_p += dS[c] * Sd[c]; dS[c] *= a; }
-                    dalpha_p /= fmaxf(a, 1e-30f);   // S_{t-1} = Sd / a
+                    for (int c = 0; c < DP; ++c) { dalpha_p += dS[c] * Sd[c]; dS[c] *= a; }
+                    dalpha_p = row_sum(dalpha_p) / fmaxf(a, 1e-30f);   // S_{t-1} = Sd / a
                 }
+                // the two scalars: one value per row (its lane 0), rows of a wavefront, then the wavefronts in order
+                float xa = part == 0 ? dalpha_p : 0.f, xb = part == 0 ? dbeta_p : 0.f;
 #pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    dalpha_p += __shfl_xor(dalpha_p, off);
-                    dbeta_p += __shfl_xor(dbeta_p, off);
+                for (int off = 32; off > 0; off >>= 1) { xa += __shfl_xor(xa, off); xb += __shfl_xor(xb, off); }
+                if (lane == 0) { s_sc[0][wave] = xa; s_sc[1][wave] = xb; }
+                __syncthreads();
+                if (tid == 0) {
+                    float sa = 0.f, sb = 0.f;
+#pragma unroll
+                    for (int w = 0; w < RB_THREADS / 64; ++w) { sa += s_sc[0][w]; sb += s_sc[1][w]; }
+                    da_p[base + t] = sa;
+                    db_p[base + t] = sb;
                 }
-                if (tid == 0) { da_p[base + t] = dalpha_p; db_p[base + t] = dbeta_p; }
-                __syncthreads();   // the reduction tile is free again
             }
         }
     }
     if (dS0 != nullptr) {
-        float* dst = dS0 + ((size_t)bh * D + row) * D;
+        float* dst = dS0 + ((size_t)bh * D + row) * D + part * DP;
 #pragma unroll
-        for (int c = 0; c < D; c += 4) *reinterpret_cast<float4*>(dst + c) = make_float4(dS[c], dS[c + 1], dS[c + 2], dS[c + 3]);
+        for (int c = 0; c < DP; c += 4) *reinterpret_cast<float4*>(dst + c) = make_float4(dS[c], dS[c + 1], dS[c + 2], dS[c + 3]);
+    }
+}
+
+// The forward recurrence once more, only to leave the checkpoints the reverse sweep starts from: the row of the
+// state before every chunk of 64 tokens, ckpt[bh][chunk][row][d_k].  Same thread layout as the kernel above.
+template <typename T, int D>
+__global__ __launch_bounds__(RB_THREADS) void gdn_checkpoint_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ alpha, const float* __restrict__ beta,
+    const uint8_t* __restrict__ mask, const float* __restrict__ S0, float* __restrict__ ckpt, int L, int linear_op,
+    int freeze_on_softmax) {
+    constexpr int EPL = Vec16<T>::N;
+    constexpr int DP = D / 4, DPP = DP + 4;
+    constexpr int TT = 32;
+    __shared__ __align__(16) float s_k[TT][4 * DPP];
+    __shared__ float s_v[TT][RB_ROWS];
+    __shared__ float s_a[TT], s_b[TT];
+    __shared__ uint8_t s_lin[TT];
+    const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
+    const int r = tid >> 2, part = tid & 3;
+    const int row = slice * RB_ROWS + r;
+    const size_t base = (size_t)bh * L;
+    const int n_chunks = L / RB_CH;
+    float S[DP];
+    if (S0 != nullptr) {
+        const float* src = S0 + ((size_t)bh * D + row) * D + part * DP;
+#pragma unroll
+        for (int c = 0; c < DP; c += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(src + c);
+            S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < DP; ++c) S[c] = 0.f;
+    }
+    for (int t0 = 0; t0 < L; t0 += TT) {
+        __syncthreads();
+        for (int e = tid * EPL; e < TT * D; e += RB_THREADS * EPL) {
+            const int i = e / D, c = e % D;
+            float tmp[EPL];
+            Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_k[i][(c / DP) * DPP + c % DP + j] = tmp[j];
+        }
+        for (int e = tid * EPL; e < TT * RB_ROWS; e += RB_THREADS * EPL) {
+            const int i = e / RB_ROWS, c = e % RB_ROWS;
+            float tmp[EPL];
+            Vec16<T>::load(V + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
+        }
+        if (tid < TT) {
+            const bool soft = mask[base + t0 + tid] != 0;
+            s_lin[tid] = soft ? 0 : 1;
+            s_a[tid] = (soft && freeze_on_softmax) ? 1.f : alpha[base + t0 + tid];
+            s_b[tid] = soft ? 0.f : beta[base + t0 + tid];
+        }
+        __syncthreads();
+        for (int i = 0; i < TT; ++i) {
+            if (((t0 + i) & (RB_CH - 1)) == 0) {
+                float* dst = ckpt + (((size_t)bh * n_chunks + (t0 + i) / RB_CH) * D + row) * D + part * DP;
+#pragma unroll
+                for (int c = 0; c < DP; c += 4) *reinterpret_cast<float4*>(dst + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+            }
+            const float a = s_a[i];
+            const float* kr = &s_k[i][part * DPP];
+            float pred = 0.f;
+#pragma unroll
+            for (int c = 0; c < DP; c += 4) {
+                const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
+                S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
+                pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
+            }
+            if (s_lin[i]) {   // uniform across the block
+                pred += __shfl_xor(pred, 1);
+                pred += __shfl_xor(pred, 2);
+                const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
+#pragma unroll
+                for (int c = 0; c < DP; c += 4) {
+                    const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
+                    S[c] += delta * k4.x; S[c + 1] += delta * k4.y; S[c + 2] += delta * k4.z; S[c + 3] += delta * k4.w;
+                }
+            }
+        }
     }
 }
 
@@ -250,11 +351,11 @@ static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const voi
                       float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
     dim3 grid(pl.d / RB_ROWS, pl.BH);
     if (pl.d == 64)
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RB_ROWS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RB_THREADS), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
     else
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RB_ROWS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RB_THREADS), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
 }
@@ -272,6 +373,19 @@ nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const voi
         launch_rb<float>(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,
                          dV, dS0, st);
     return check_launch("gdn_recurrent_bwd");
+}
+
+// ckpt [BH][L/64][d][d] f32: the state before every chunk of 64 tokens (S0 may be NULL: zero)
+nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
+                                   const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st) {
+    dim3 grid(pl.d / RB_ROWS, pl.BH);
+#define NATS_CK_LAUNCH(TT, DD)                                                                                        \
+    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(RB_THREADS), 0, st, (const TT*)K, (const TT*)V, alpha, \
+                       beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax)
+    if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_CK_LAUNCH(bf16_t, 64); else NATS_CK_LAUNCH(bf16_t, 128); }
+    else { if (pl.d == 64) NATS_CK_LAUNCH(float, 64); else NATS_CK_LAUNCH(float, 128); }
+#undef NATS_CK_LAUNCH
+    return check_launch("gdn_checkpoints");
 }
 
 nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,

@@ -128,8 +128,7 @@ nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const vo
                                 hipStream_t st);
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
-                                 const float* S0, float* S_final, float* O_la, float* snap, float* ckpt,
-                                 hipStream_t st);   // O_la may be NULL; ckpt [BH][L/64][d][d]: state before every chunk
+                                 const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st);
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
@@ -176,6 +175,8 @@ nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const voi
                                      const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
                                      float* scratch, float* dq_part, float* dk_part, float* dalpha_part,
                                      float* dbeta_part, float* dV, float* dS0, hipStream_t st);
+nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
+                                   const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st);
 nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,
                                const float* dbeta_part, float* dQ, float* dK, float* dalpha, float* dbeta,
                                float* g_nla, hipStream_t st);
