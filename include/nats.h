@@ -119,6 +119,10 @@ typedef struct nats_fwd_extra {
     const float* W_out;         /* in  [H,2,d] f32 or NULL.  With combine_mode 1: the weights of Eq. 21
                                    are computed from Q by Eq. 22, [w_nla, w_la] = softmax([W_out[h,0] . q_t,
                                    W_out[h,1] . q_t]); w_nla and w_la must then be NULL                  */
+    const void* Q_nla;          /* in  [B,H,L,d] dtype or NULL: queries and keys of the softmax branch when  */
+    const void* K_nla;          /* in  they differ from the linear branch's (Section 4.3: L2-normalised q, k for
+                                   the linear operation, RMS-normalised and possibly rotated ones for softmax
+                                   attention; V is shared).  Both or neither.  Kc then holds rows of K_nla.   */
 } nats_fwd_extra;
 
 /* Bytes of device workspace nats_hybrid_attn_fwd{,_ex} needs for these params
@@ -193,6 +197,8 @@ typedef struct nats_dec_params {
     float rms_eps;
     int32_t linear_op;         /* as in nats_fwd_params */
     int32_t freeze_on_softmax; /* as in nats_fwd_params (routing per chunk: applied by the commit) */
+    const void* q_nla;         /* [B,H,d] dtype or NULL: the softmax branch's own query and key of this token  */
+    const void* k_nla;         /* (see nats_fwd_extra.Q_nla); both or neither; k_nla is what the cache receives */
 } nats_dec_params;
 
 /* For every (b,h):  S <- alpha S;  linear token: S <- S + beta (v - S k) k^T;  softmax token:

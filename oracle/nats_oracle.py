@@ -157,12 +157,16 @@ def eq22_weights(Q, W_out):
 # whole operator for one (batch, head), and over [B,H,...]
 # --------------------------------------------------------------------------- #
 def hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
-                w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
+                w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
+                q_nla=None, k_nla=None):
+    """q_nla, k_nla: the softmax branch's own queries and keys (Section 4.3: the two families share the
+    projections but the linear one takes L2-normalised q, k and the softmax one RMS-normalised, possibly
+    rotated ones); None: both branches use q, k."""
     d_k = np.asarray(q).shape[-1]
     scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
     o_la, S = gdn_recurrent(q, k, v, alpha, beta, mask, S0=S0, la_scale=la_scale,
                             decay_on_softmax=decay_on_softmax, linear_op=linear_op)
-    o_nla, lse = softmax_branch(q, k, v, mask, scale)
+    o_nla, lse = softmax_branch(q if q_nla is None else q_nla, k if k_nla is None else k_nla, v, mask, scale)
     o = combine(o_la, o_nla, mode, w_nla, w_la, eps)
     cnt, idx, n_s = compaction(mask)
     return {"O": o, "O_la": o_la, "O_nla": o_nla, "lse": lse, "S": S,
@@ -170,7 +174,7 @@ def hybrid_head(q, k, v, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mo
 
 
 def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mode=0,
-               w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
+               w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True, Q_nla=None, K_nla=None):
     """All (b,h) of [B,H,L,d] inputs; returns dict of stacked fp64 arrays (idx as nested lists)."""
     B, H, L, _ = np.asarray(Q).shape
     d_v = np.asarray(V).shape[-1]
@@ -185,7 +189,8 @@ def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mod
                             softmax_scale, la_scale, mode,
                             None if w_nla is None else w_nla[b, h],
                             None if w_la is None else w_la[b, h], eps,
-                            None if S0 is None else S0[b, h], linear_op, decay_on_softmax)
+                            None if S0 is None else S0[b, h], linear_op, decay_on_softmax,
+                            None if Q_nla is None else Q_nla[b, h], None if K_nla is None else K_nla[b, h])
             for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]
@@ -197,7 +202,7 @@ def hybrid_fwd(Q, K, V, alpha, beta, mask, softmax_scale=None, la_scale=1.0, mod
 # --------------------------------------------------------------------------- #
 def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
                 softmax_scale=None, la_scale=1.0, mode=0, w_nla=0.5, w_la=0.5, eps=1e-6, linear_op=0,
-                decay_on_softmax=True):
+                decay_on_softmax=True, q_nla=None, k_nla=None):
     """One token.  S [d_v,d_k] fp64; k_cache/v_cache [cap,d] with cache_len live rows.
 
     Returns (o [d_v], S_new, k_cache, v_cache, cache_len_new, overflow).  A softmax
@@ -206,6 +211,8 @@ def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
     not stored and overflow=True; the output then covers the existing rows only.
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    qn = q if q_nla is None else np.asarray(q_nla, dtype=np.float64)   # the softmax branch's own query and key
+    kn = k if k_nla is None else np.asarray(k_nla, dtype=np.float64)
     scale = (1.0 / np.sqrt(q.shape[0])) if softmax_scale is None else softmax_scale
     S = (float(alpha) if (m == 0 or decay_on_softmax) else 1.0) * np.array(S, dtype=np.float64)
     overflow = False
@@ -215,14 +222,14 @@ def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
         if cache_len < k_cache.shape[0]:
             k_cache = np.array(k_cache, dtype=np.float64)
             v_cache = np.array(v_cache, dtype=np.float64)
-            k_cache[cache_len] = k
+            k_cache[cache_len] = kn
             v_cache[cache_len] = v
             cache_len = cache_len + 1
         else:
             overflow = True
     o_la = la_scale * (S @ q)
     if cache_len > 0:
-        s = scale * (np.asarray(k_cache[:cache_len], dtype=np.float64) @ q)
+        s = scale * (np.asarray(k_cache[:cache_len], dtype=np.float64) @ qn)
         e = np.exp(s - s.max())
         o_nla = (e / e.sum()) @ np.asarray(v_cache[:cache_len], dtype=np.float64)
     else:
@@ -275,7 +282,8 @@ def gdn_chunkwise(q, k, v, alpha, beta, mask, C, S0=None, la_scale=1.0):
 # chunk, after the whole chunk has been seen)
 # --------------------------------------------------------------------------- #
 def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
-                             w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
+                             w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
+                             q_nla=None, k_nla=None):
     """One (batch, head) with one routing decision per chunk of C tokens (mask_c[c] = 1: softmax chunk).
 
     Section 4.1: a chunk's type is known only once the whole chunk has been seen, so both
@@ -293,6 +301,8 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
     after such a chunk is the chunk-start state itself).
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    qn = q if q_nla is None else np.asarray(q_nla, dtype=np.float64)   # the softmax branch's own queries and keys
+    kn = k if k_nla is None else np.asarray(k_nla, dtype=np.float64)
     alpha = np.asarray(alpha, dtype=np.float64)
     beta = np.asarray(beta, dtype=np.float64)
     mask_c = np.asarray(mask_c).reshape(-1) != 0
@@ -314,7 +324,7 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
             S = S + beta[t] * np.outer(v[t] - pred, k[t])            # Eq. 19, every token of the chunk
             o_la[t] = la_scale * (S @ q[t])
             J = np.asarray(earlier + list(range(c * C, t + 1)), dtype=np.int64)
-            s = scale * (k[J] @ q[t])
+            s = scale * (kn[J] @ qn[t])
             smax = s.max()
             e = np.exp(s - smax)
             z = e.sum()
@@ -329,7 +339,8 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
 
 
 def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
-                            w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True):
+                            w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
+                            Q_nla=None, K_nla=None):
     """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; same result layout as hybrid_fwd."""
     B, H, L, _ = np.asarray(Q).shape
     d_v = np.asarray(V).shape[-1]
@@ -344,7 +355,8 @@ def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None,
                                          softmax_scale, la_scale, mode,
                                          None if w_nla is None else w_nla[b, h],
                                          None if w_la is None else w_la[b, h], eps,
-                                         None if S0 is None else S0[b, h], linear_op, decay_on_softmax)
+                                         None if S0 is None else S0[b, h], linear_op, decay_on_softmax,
+                                         None if Q_nla is None else Q_nla[b, h], None if K_nla is None else K_nla[b, h])
             for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]

@@ -42,7 +42,8 @@ class FwdExtra(ctypes.Structure):
                 ("final_state", ctypes.c_void_p), ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
                 ("cap", ctypes.c_int32), ("n_s", ctypes.c_void_p), ("idx", ctypes.c_void_p),
                 ("cnt", ctypes.c_void_p), ("O_la", ctypes.c_void_p), ("O_nla", ctypes.c_void_p),
-                ("lse", ctypes.c_void_p), ("W_out", ctypes.c_void_p)]
+                ("lse", ctypes.c_void_p), ("W_out", ctypes.c_void_p), ("Q_nla", ctypes.c_void_p),
+                ("K_nla", ctypes.c_void_p)]
 
 
 class BwdExtra(ctypes.Structure):
@@ -59,7 +60,7 @@ class DecParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("la_scale", ctypes.c_float),
                 ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("linear_op", ctypes.c_int32),
-                ("freeze_on_softmax", ctypes.c_int32)]
+                ("freeze_on_softmax", ctypes.c_int32), ("q_nla", ctypes.c_void_p), ("k_nla", ctypes.c_void_p)]
 
 
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
@@ -167,7 +168,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                        la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
                        math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, linear_op: int = NATS_LINEAR_GDN,
                        freeze_on_softmax: bool = False, w_nla=None, w_la=None,
-                       W_out=None, initial_state=None,
+                       W_out=None, initial_state=None, Q_nla=None, K_nla=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
                        workspace=None) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
@@ -183,6 +184,8 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
     _require(w_nla, "w_nla", (B, H, L), torch.float32)
     _require(w_la, "w_la", (B, H, L), torch.float32)
     _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
+    _require(Q_nla, "Q_nla", (B, H, L, d), dt)
+    _require(K_nla, "K_nla", (B, H, L, d), dt)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
                              routing, linear_op, freeze_on_softmax)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
@@ -216,7 +219,8 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                      w_la.data_ptr() if w_la is not None else None,
                      initial_state.data_ptr() if initial_state is not None else None,
                      g("final_state"), g("Kc"), g("Vc"), cap if "Kc" in want else 0, g("n_s"), g("idx"),
-                     g("cnt"), g("O_la"), g("O_nla"), g("lse"), W_out.data_ptr() if W_out is not None else None)
+                     g("cnt"), g("O_la"), g("O_nla"), g("lse"), W_out.data_ptr() if W_out is not None else None,
+                     Q_nla.data_ptr() if Q_nla is not None else None, K_nla.data_ptr() if K_nla is not None else None)
     _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
                                        _ptr(mask), _ptr(O), ctypes.byref(extra), _ptr(workspace),
                                        workspace.numel(), _stream_ptr()))
@@ -290,7 +294,7 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
 def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, *,
                        softmax_scale: float = 0.0, la_scale: float = 0.0, combine_mode: int = 0,
                        rms_eps: float = 0.0, linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False,
-                       w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
+                       q_nla=None, k_nla=None, w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
     """nats_hybrid_attn_decode: one token per (b,h); state, caches and cache_len are updated in place."""
     lib = load_library()
     B, H, cap, d = k_cache.shape
@@ -307,8 +311,11 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
     _require(err_flags, "err_flags", (B, H), torch.int32)
     o = torch.empty_like(q) if out is None else out
     _require(o, "out", (B, H, d), dt)
+    _require(q_nla, "q_nla", (B, H, d), dt)
+    _require(k_nla, "k_nla", (B, H, d), dt)
     params = DecParams(B, H, d, cap, _dtype_code(k_cache), softmax_scale, la_scale, combine_mode, rms_eps, linear_op,
-                       int(freeze_on_softmax))
+                       int(freeze_on_softmax), q_nla.data_ptr() if q_nla is not None else None,
+                       k_nla.data_ptr() if k_nla is not None else None)
     _check(lib.nats_hybrid_attn_decode(ctypes.byref(params), _ptr(state), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(cache_len), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta),
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),

@@ -207,7 +207,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 104; }
+int nats_abi_version(void) { return 105; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -286,11 +286,16 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         set_error("extra.W_out (weights by Eq. 22) and extra.w_nla / w_la (given weights) exclude each other");
         return NATS_ERR_SHAPE;
     }
+    if ((ex.Q_nla == nullptr) != (ex.K_nla == nullptr)) { set_error("extra.Q_nla and extra.K_nla must be given together"); return NATS_ERR_NULL; }
     const void* ptrs[] = {Q, K, V, alpha, beta, mask, O, workspace, ex.w_nla, ex.w_la, ex.initial_state,
-                          ex.final_state, ex.Kc, ex.Vc, ex.n_s, ex.idx, ex.cnt, ex.O_la, ex.O_nla, ex.lse, ex.W_out};
+                          ex.final_state, ex.Kc, ex.Vc, ex.n_s, ex.idx, ex.cnt, ex.O_la, ex.O_nla, ex.lse, ex.W_out,
+                          ex.Q_nla, ex.K_nla};
     for (const void* ptr : ptrs)
         if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
-    if (O == Q || O == K || O == V) { set_error("O must not alias Q, K or V"); return NATS_ERR_SHAPE; }
+    if (O == Q || O == K || O == V || O == ex.Q_nla || O == ex.K_nla) { set_error("O must not alias Q, K or V"); return NATS_ERR_SHAPE; }
+    // queries and keys of the softmax branch (the linear branch always takes Q, K)
+    const void* Qs = ex.Q_nla != nullptr ? ex.Q_nla : Q;
+    const void* Ks = ex.K_nla != nullptr ? ex.K_nla : K;
 
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
@@ -342,7 +347,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     };
     {
         ProfScope ps("scan_compact", s_nla);
-        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
+        st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
                                  uses_chunk_path(pl) ? ws + pl.off_vht : nullptr,
                                  uses_chunk_path(pl) ? reinterpret_cast<int32_t*>(ws + pl.off_prog) : nullptr, s_nla);
     }
@@ -362,7 +367,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         const bool merge_in_scan = pl.combine_mode == 0;
         if (merge_in_scan) {
             ProfScope ps("flash_softmax", s_nla);
-            st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
+            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
                                       s_nla);
             if (st != NATS_OK) { join(); return st; }
         }
@@ -381,7 +386,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         if (st != NATS_OK) return st;
         if (!merge_in_scan) {
             ProfScope ps("flash_softmax", stream);
-            st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
+            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
         }
     } else {
         {
@@ -392,7 +397,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         }
         if (st != NATS_OK) return st;
         ProfScope ps("softmax_fp32", stream);
-        st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
+        st = launch_softmax_fp32(pl, Qs, Kc, Vc, Ks, V, cnt, O_la, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
     }
     return st;
 }
@@ -494,31 +499,15 @@ nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const 
                                    hip_stream);
 }
 
+static nats_status validate_dec_params(const nats_dec_params* p);
+
 nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void* k_cache, void* v_cache,
                                     int32_t* cache_len, const void* q, const void* k, const void* v,
                                     const float* alpha, const float* beta, const uint8_t* mask,
                                     const float* w_nla, const float* w_la, void* o, int32_t* err_flags,
                                     void* hip_stream) {
-    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
-    if (p->dtype != NATS_F32 && p->dtype != NATS_BF16) {
-        set_error("dtype %d is neither NATS_F32 nor NATS_BF16", p->dtype);
-        return NATS_ERR_DTYPE;
-    }
-    if (p->B <= 0 || p->H <= 0 || p->cap <= 0) {
-        set_error("B, H, cap must be positive (got %d, %d, %d)", p->B, p->H, p->cap);
-        return NATS_ERR_SHAPE;
-    }
-    if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
-    if (p->combine_mode != 0 && p->combine_mode != 1) {
-        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
-        return NATS_ERR_SHAPE;
-    }
-    if ((p->linear_op != NATS_LINEAR_GDN && p->linear_op != NATS_LINEAR_GATED) ||
-        (p->freeze_on_softmax != 0 && p->freeze_on_softmax != 1)) {
-        set_error("linear_op must be a nats_linear_op and freeze_on_softmax 0 or 1 (got %d, %d)", p->linear_op,
-                  p->freeze_on_softmax);
-        return NATS_ERR_SHAPE;
-    }
+    const nats_status vst = validate_dec_params(p);
+    if (vst != NATS_OK) return vst;
     if (!state || !k_cache || !v_cache || !cache_len || !q || !k || !v || !alpha || !beta || !mask || !o) {
         set_error("state, caches, cache_len, q, k, v, alpha, beta, mask and o must all be non-NULL");
         return NATS_ERR_NULL;
@@ -596,6 +585,8 @@ static nats_status validate_dec_params(const nats_dec_params* p) {
                   p->freeze_on_softmax);
         return NATS_ERR_SHAPE;
     }
+    if ((p->q_nla == nullptr) != (p->k_nla == nullptr)) { set_error("q_nla and k_nla must be given together"); return NATS_ERR_NULL; }
+    if (!aligned16(p->q_nla) || !aligned16(p->k_nla)) { set_error("q_nla and k_nla must be 16-byte aligned"); return NATS_ERR_ALIGN; }
     return NATS_OK;
 }
 

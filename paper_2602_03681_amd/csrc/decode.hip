@@ -40,7 +40,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     const T* __restrict__ v, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ w_nla, const float* __restrict__ w_la,
     T* __restrict__ o, int32_t* __restrict__ err_flags, int cap, float scale, float la_scale,
-    int combine_mode, float eps, int linear_op, int freeze_on_softmax) {
+    int combine_mode, float eps, int linear_op, int freeze_on_softmax, const T* __restrict__ q_nla,
+    const T* __restrict__ k_nla) {
     constexpr int LPR = D / 4;                    // lanes per state row
     constexpr int ROWS_PER_PASS = DEC_THREADS / LPR;
     constexpr int PASSES = D / ROWS_PER_PASS;     // 16 (D=128) or 4 (D=64)
@@ -50,6 +51,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     constexpr int UNROLL = 4;
 
     __shared__ float s_q[D], s_k[D], s_v[D], s_ola[D];
+    __shared__ float s_qn[D], s_kn[D];            // query and key of the softmax branch (q, k unless given apart)
     __shared__ float s_m[NSG], s_l[NSG];
     __shared__ float s_acc[NSG][D];
 
@@ -57,6 +59,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     for (int c = tid; c < D; c += DEC_THREADS) {
         s_q[c] = to_float(q[(size_t)bh * D + c]);
         s_k[c] = to_float(k[(size_t)bh * D + c]);
+        s_qn[c] = to_float((q_nla != nullptr ? q_nla : q)[(size_t)bh * D + c]);
+        s_kn[c] = to_float((k_nla != nullptr ? k_nla : k)[(size_t)bh * D + c]);
         s_v[c] = to_float(v[(size_t)bh * D + c]);
     }
     const int pos = CHUNK ? chunk_pos[bh] : 0;
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     const int lk = tid % LPK, sg = tid / LPK;
     float qf[EPL], acc[EPL];
 #pragma unroll
-    for (int j = 0; j < EPL; ++j) { qf[j] = s_q[lk * EPL + j] * scale; acc[j] = 0.f; }
+    for (int j = 0; j < EPL; ++j) { qf[j] = s_qn[lk * EPL + j] * scale; acc[j] = 0.f; }
     float m_run = -INFINITY, l_run = 0.f;
     const T* Kb = k_cache + (size_t)bh * cap * D + lk * EPL;
     const T* Vb = v_cache + (size_t)bh * cap * D + lk * EPL;
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     if (append && sg == 0) {   // the new softmax token attends to itself
         float dot = 0.f;
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) dot += qf[j] * s_k[lk * EPL + j];
+        for (int j = 0; j < EPL; ++j) dot += qf[j] * s_kn[lk * EPL + j];
         dot = group_sum<LPK>(dot);
         const float m_new = fmaxf(m_run, dot);
         const float corr = expf(m_run - m_new);
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     // ---- append the new token to the cache -------------------------------------------------
     if (append) {
         for (int c = tid; c < D; c += DEC_THREADS) {
-            k_cache[((size_t)bh * cap + n_old) * D + c] = k[(size_t)bh * D + c];
+            k_cache[((size_t)bh * cap + n_old) * D + c] = (k_nla != nullptr ? k_nla : k)[(size_t)bh * D + c];
             v_cache[((size_t)bh * cap + n_old) * D + c] = v[(size_t)bh * D + c];
         }
         if (tid == 0 && !CHUNK) cache_len[bh] = n_old + 1;
@@ -257,13 +261,13 @@ static void launch_dec(const nats_dec_params& p, float scale, float la_scale, fl
                            chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
                            w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps,
-                           p.linear_op, p.freeze_on_softmax);
+                           p.linear_op, p.freeze_on_softmax, (const T*)p.q_nla, (const T*)p.k_nla);
     else
         hipLaunchKernelGGL((decode_kernel<T, 128, CHUNK>), grid, dim3(DEC_THREADS), 0, st, state, state_start,
                            chunk_decay, chunk_pos, (T*)k_cache,
                            (T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v, alpha, beta, mask,
                            w_nla, w_la, (T*)o, err_flags, p.cap, scale, la_scale, p.combine_mode, eps,
-                           p.linear_op, p.freeze_on_softmax);
+                           p.linear_op, p.freeze_on_softmax, (const T*)p.q_nla, (const T*)p.k_nla);
 }
 
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,

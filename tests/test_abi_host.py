@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 104   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points
+    assert lib.nats_abi_version() == 105   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla
 
 
 def good_params(**over):
@@ -94,6 +94,10 @@ def test_null_misaligned_and_workspace_errors(lib):
     ex = nb.FwdExtra()
     ex.Kc = FAKE
     assert call_fwd(lib, p, [FAKE + 16 * i for i in range(7)], extra=ctypes.byref(ex)) == E_NULL
+    # Q_nla without K_nla
+    ex = nb.FwdExtra()
+    ex.Q_nla = FAKE + 4096
+    assert call_fwd(lib, p, [FAKE + 16 * i for i in range(7)], extra=ctypes.byref(ex)) == E_NULL
 
 
 def test_plain_fwd_goes_through_the_same_validation(lib):
@@ -112,6 +116,7 @@ def test_decode_validation(lib):
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 2, 0)) == E_SHAPE
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 5, 0)) == E_SHAPE     # linear_op
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 1, 2)) == E_SHAPE     # freeze_on_softmax
+    assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 0, 0, FAKE, None)) == E_NULL   # q_nla alone
     ptrs = [FAKE + 16 * i for i in range(14)]
     ptrs[0] = None
     assert call(good, ptrs) == E_NULL

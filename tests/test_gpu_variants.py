@@ -117,3 +117,75 @@ def test_variants_generation_per_chunk_with_commits(op, freeze):
                 npo.decode_commit_chunk(ref[b][h], int(decisions[c][b, h]), decay_on_softmax=not freeze)
                 assert rel_err(host(st["state"])[b, h], ref[b][h]["S"]) <= TOL["f32"]
                 assert int(host(st["cache_len"])[b, h]) == ref[b][h]["cache_len"]
+
+
+# ---- queries and keys of the softmax branch given apart (Section 4.3: L2-normalised q, k for the linear
+#      operation, RMS-normalised / rotated ones for softmax attention; V shared) ---------------------------
+
+def nla_inputs(shape, dtype, seed):
+    from nats_inputs import round_to_bf16
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(shape).astype(np.float32)
+    b = rng.standard_normal(shape).astype(np.float32)
+    return (round_to_bf16(a), round_to_bf16(b)) if dtype == "bf16" else (a, b)
+
+
+@pytest.mark.parametrize("chunk", [False, True])
+@pytest.mark.parametrize("dtype,d,L", [("f32", 64, 256), ("bf16", 128, 512), ("bf16", 64, 320)])
+def test_separate_softmax_queries_and_keys_forward(dtype, d, L, chunk):
+    B, H = 1, 2
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=111 + d)
+    if chunk:
+        x["mask"] = make_chunk_mask(B, H, L // 64, 0.4, 112, "bernoulli")
+    Qn, Kn = nla_inputs((B, H, L, d), dtype, 113)
+    g = to_dev(x, dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, want=ALL_OUT,
+                                routing=nb.NATS_ROUTE_CHUNK if chunk else nb.NATS_ROUTE_TOKEN,
+                                Q_nla=torch.from_numpy(Qn).to(tdt).cuda(), K_nla=torch.from_numpy(Kn).to(tdt).cuda())
+    torch.cuda.synchronize()
+    if chunk:
+        ref = npo.hybrid_fwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, Q_nla=Qn, K_nla=Kn)
+    else:
+        ref = npo.hybrid_fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], Q_nla=Qn, K_nla=Kn)
+    for key, rk, st in (("O", "O", stored(dtype)), ("O_la", "O_la", None), ("O_nla", "O_nla", None), ("final_state", "S", None)):
+        assert rel_err(host(r[key]), ref[rk], st) <= TOL[dtype], key
+    np.testing.assert_array_equal(host(r["n_s"]), ref["n_s"])
+    Kc = host(r["Kc"])
+    for h in range(H):   # the compacted cache holds the softmax branch's keys
+        n = int(ref["n_s"][0, h])
+        np.testing.assert_array_equal(Kc[0, h, :n], Kn[0, h, np.asarray(ref["idx"][0][h][:n], dtype=np.int64)])
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_separate_softmax_queries_and_keys_decode(dtype, d):
+    cfg = DecodeConfig("small", 2, 2, d, dtype, 0.4, seed=121 + d, len_lo=1, len_hi=40, steps=12)
+    x = make_decode_inputs(cfg, steps=cfg.steps)
+    g = to_dev(x, dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    qn, kn = nla_inputs((cfg.steps, cfg.B, cfg.H, d), dtype, 122)
+    gq, gk = torch.from_numpy(qn).to(tdt).cuda(), torch.from_numpy(kn).to(tdt).cuda()
+    state, kc, vc, clen = g["state"].clone(), g["k_cache"].clone(), g["v_cache"].clone(), g["cache_len"].clone()
+    ref = [[dict(S=x["state"][b, h].astype(np.float64), kc=x["k_cache"][b, h].astype(np.float64),
+                 vc=x["v_cache"][b, h].astype(np.float64), n=int(x["cache_len"][b, h])) for h in range(cfg.H)]
+           for b in range(cfg.B)]
+    for s in range(cfg.steps):
+        o = nats.hybrid_attn_decode(state, kc, vc, clen, g["q"][s], g["k"][s], g["v"][s], g["alpha"][s], g["beta"][s],
+                                    g["mask"][s], q_nla=gq[s].contiguous(), k_nla=gk[s].contiguous())
+        oh = host(o)
+        for b in range(cfg.B):
+            for h in range(cfg.H):
+                st = ref[b][h]
+                o_ref, st["S"], st["kc"], st["vc"], st["n"], _ = npo.decode_step(
+                    st["S"], st["kc"], st["vc"], st["n"], x["q"][s, b, h], x["k"][s, b, h], x["v"][s, b, h],
+                    x["alpha"][s, b, h], x["beta"][s, b, h], x["mask"][s, b, h], q_nla=qn[s, b, h], k_nla=kn[s, b, h])
+                rms = max(float(np.sqrt(np.mean(o_ref ** 2))), 1e-6)
+                diff = np.abs(oh[b, h] - o_ref)
+                if dtype == "bf16":
+                    from gpu_util import bf16_half_ulp
+                    diff = np.maximum(diff - bf16_half_ulp(o_ref), 0.0)
+                assert diff.max() / rms <= TOL[dtype], (s, b, h)
+    torch.cuda.synchronize()
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            assert int(host(clen)[b, h]) == ref[b][h]["n"]

@@ -143,3 +143,19 @@ def test_generation_with_reroll_continues_the_chunk_routed_forward():
     np.testing.assert_allclose(st["S"], full["S"], rtol=0, atol=1e-12)
     assert st["cache_len"] == full["n_s"]
     np.testing.assert_array_equal(st["k_cache"][:full["n_s"]], x["K"][full["idx"]])
+
+
+def test_chunk_routed_separate_softmax_queries_and_keys():
+    """With q_nla, k_nla the softmax branch of the chunk-routed operator is that of (q_nla, k_nla, v), the
+    linear branch that of (q, k, v)."""
+    import numpy as np
+    from nats_inputs import make_fwd_inputs
+    from oracle import nats_oracle as no2
+    x = make_fwd_inputs(1, 1, 128, 8, "f32", 0.0, seed=31)
+    rng = np.random.default_rng(32)
+    q, k, v, a, b = x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0], x["alpha"][0, 0], x["beta"][0, 0]
+    qn, kn = rng.standard_normal(q.shape), rng.standard_normal(k.shape)
+    mc = np.array([1, 0], dtype=np.uint8)
+    r = no2.hybrid_head_chunk_routed(q, k, v, a, b, mc, 64, q_nla=qn, k_nla=kn)
+    np.testing.assert_allclose(r["O_la"], no2.hybrid_head_chunk_routed(q, k, v, a, b, mc, 64)["O_la"], rtol=1e-12)
+    np.testing.assert_allclose(r["O_nla"], no2.hybrid_head_chunk_routed(qn, kn, v, a, b, mc, 64)["O_nla"], rtol=1e-12)

@@ -485,3 +485,26 @@ def test_chunk_routed_variants_carry_the_per_token_state():
         _, S = npo.gdn_recurrent(x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0], x["alpha"][0, 0], x["beta"][0, 0],
                                 np.repeat(mc, 64), decay_on_softmax=keep, linear_op=op)
         np.testing.assert_allclose(r["S"], S, rtol=1e-10, atol=1e-12)
+
+
+def test_separate_softmax_queries_and_keys():
+    """q_nla, k_nla replace q, k in the softmax branch only: O = O_la(q, k) + O_nla(q_nla, k_nla), each term
+    being what the single-input operator gives for that pair; the decode step continues the same sequence."""
+    x = make_fwd_inputs(1, 1, 48, 8, "f32", 0.3, seed=21)
+    rng = np.random.default_rng(22)
+    q, k, v = x["Q"][0, 0], x["K"][0, 0], x["V"][0, 0]
+    a, b, m = x["alpha"][0, 0], x["beta"][0, 0], x["mask"][0, 0]
+    qn, kn = rng.standard_normal(q.shape), rng.standard_normal(k.shape)
+    r = npo.hybrid_head(q, k, v, a, b, m, q_nla=qn, k_nla=kn)
+    np.testing.assert_allclose(r["O_la"], npo.hybrid_head(q, k, v, a, b, m)["O_la"], rtol=1e-12)
+    np.testing.assert_allclose(r["O_nla"], npo.hybrid_head(qn, kn, v, a, b, m)["O_nla"], rtol=1e-12)
+    np.testing.assert_allclose(r["O"], r["O_la"] + r["O_nla"], rtol=1e-12)
+    # generation: prefix by the forward, then one token at a time
+    L0 = 32
+    pre = npo.hybrid_head(q[:L0], k[:L0], v[:L0], a[:L0], b[:L0], m[:L0], q_nla=qn[:L0], k_nla=kn[:L0])
+    S, n = pre["S"], int(pre["n_s"])
+    kc, vc = np.zeros((48, 8)), np.zeros((48, 8))
+    kc[:n], vc[:n] = kn[pre["idx"][:n]], v[pre["idx"][:n]]
+    for t in range(L0, 48):
+        o, S, kc, vc, n, _ = npo.decode_step(S, kc, vc, n, q[t], k[t], v[t], a[t], b[t], m[t], q_nla=qn[t], k_nla=kn[t])
+        np.testing.assert_allclose(o, r["O"][t], rtol=1e-9, atol=1e-11)
