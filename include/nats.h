@@ -80,6 +80,10 @@ typedef enum nats_routing { NATS_ROUTE_TOKEN = 0, NATS_ROUTE_CHUNK = 1 } nats_ro
  *                      decay per head: B = k, C = q, dt x = beta v; no correction by the state)  */
 typedef enum nats_linear_op { NATS_LINEAR_GDN = 0, NATS_LINEAR_GATED = 1 } nats_linear_op;
 
+/* What turns the two logits W_out q of Eq. 22 into the weights of Eq. 21: the softmax over the pair (the
+ * method), or, as in the ablation "(iv)" of Section 5, a sigmoid of each logit, or the logits themselves. */
+typedef enum nats_weight_act { NATS_WEIGHTS_SOFTMAX = 0, NATS_WEIGHTS_SIGMOID = 1, NATS_WEIGHTS_LINEAR = 2 } nats_weight_act;
+
 typedef struct nats_fwd_params {
     int32_t B, H;          /* batch, heads (each (b,h) has its own mask: Section 4.3)          */
     int32_t L;             /* tokens; must be a positive multiple of C                          */
@@ -89,7 +93,9 @@ typedef struct nats_fwd_params {
     float softmax_scale;   /* logits = scale * q.k ; <= 0 selects 1/sqrt(d)                     */
     float la_scale;        /* o_la = la_scale * S q (Eq. 5 has none); <= 0 selects 1            */
     int32_t combine_mode;  /* 0: O = O_la + O_nla (Section 4.1).  1: Eq. 21,
-                              O = w_nla * RMSNorm(O_nla) + w_la * RMSNorm(O_la), no gain        */
+                              O = w_nla * RMSNorm(O_nla) + w_la * RMSNorm(O_la), no gain.
+                              2: the ablation with one normalisation (Section 5, (iii)):
+                              O = RMSNorm(w_nla * O_nla + w_la * O_la), weights NULL -> 1       */
     float rms_eps;         /* RMSNorm epsilon for combine_mode 1; <= 0 selects 1e-6             */
     int32_t math;          /* nats_math                                                         */
     int32_t routing;       /* nats_routing: granularity of the routing mask                     */
@@ -97,6 +103,7 @@ typedef struct nats_fwd_params {
     int32_t freeze_on_softmax; /* 0: the decay acts on the state at every token (Eq. 20).  1: the ablation
                               without linear-attention decay (Section 5, Ablation Study (ii)): softmax
                               tokens, or softmax chunks as a whole, leave the carried state unchanged  */
+    int32_t weight_act;    /* nats_weight_act, used where the weights come from W_out                     */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */
@@ -232,7 +239,7 @@ nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, 
                               const void* X, const float* W_s, float* scores, uint8_t* mask_c, void* hip_stream);
 
 /* Weights of the merge by Eq. 22 as a call of its own (the forward does the same when W_out is given):
- *   Q [B,H,L,d] dtype p->dtype (L = 1 for a generation step; only B, H, L, d, dtype of p are used),
+ *   Q [B,H,L,d] dtype p->dtype (L = 1 for a generation step; only B, H, L, d, dtype, weight_act of p are used),
  *   W_out [H,2,d] f32  ->  w_nla, w_la [B,H,L] f32,  [w_nla, w_la] = softmax([W_out[h,0] . q, W_out[h,1] . q]).
  * The paper maps "the attention q values" to the weights; the Q given here is used as it is. */
 nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const float* W_out, float* w_nla,

@@ -115,9 +115,15 @@ def rms_norm_rows(x, eps):
 
 
 def combine(o_la, o_nla, mode=0, w_nla=None, w_la=None, eps=1e-6):
+    """mode 0: sum (Section 4.1); 1: Eq. 21; 2: the ablation with a single normalisation (Section 5, (iii)),
+    RMSNorm(w_nla o_nla + w_la o_la) with weights 1 unless given."""
     if mode == 0:
         return o_la + o_nla
     L = o_la.shape[0]
+    if mode == 2:
+        wn = np.ones(L) if w_nla is None else np.asarray(w_nla, dtype=np.float64)
+        wl = np.ones(L) if w_la is None else np.asarray(w_la, dtype=np.float64)
+        return rms_norm_rows(wn[:, None] * o_nla + wl[:, None] * o_la, eps)
     w_nla = np.full(L, 0.5) if w_nla is None else np.asarray(w_nla, dtype=np.float64)
     w_la = np.full(L, 0.5) if w_la is None else np.asarray(w_la, dtype=np.float64)
     return w_nla[:, None] * rms_norm_rows(o_nla, eps) + w_la[:, None] * rms_norm_rows(o_la, eps)
@@ -138,8 +144,9 @@ def route_chunks(X, W_s, C):
     return np.ascontiguousarray(mask_c), scores
 
 
-def eq22_weights(Q, W_out):
+def eq22_weights(Q, W_out, act=0):
     """Weights of the merge, Eq. 22: [w_nla, w_la] = softmax([W_nla q_t, W_la q_t]) per token and head.
+    act = 1 / 2: the ablation (iv) of Section 5, a sigmoid of each logit / the logits themselves.
 
     Q [B,H,L,d]; W_out [H,2,d] (row 0: W_nla, row 1: W_la of the head).  Returns (w_nla, w_la) [B,H,L].
     The paper takes "the attention q values"; the Q handed to the operator is used as it is.
@@ -147,6 +154,11 @@ def eq22_weights(Q, W_out):
     Q = np.asarray(Q, dtype=np.float64)
     W = np.asarray(W_out, dtype=np.float64)
     logits = np.einsum("bhld,hkd->bhlk", Q, W)
+    if act == 1:
+        w = 1.0 / (1.0 + np.exp(-logits))
+        return w[..., 0], w[..., 1]
+    if act == 2:
+        return logits[..., 0], logits[..., 1]
     logits = logits - logits.max(axis=-1, keepdims=True)
     e = np.exp(logits)
     w = e / e.sum(axis=-1, keepdims=True)
@@ -236,6 +248,8 @@ def decode_step(S, k_cache, v_cache, cache_len, q, k, v, alpha, beta, m,
         o_nla = np.zeros_like(o_la)
     if mode == 0:
         o = o_la + o_nla
+    elif mode == 2:
+        o = rms_norm_rows((w_nla * o_nla + w_la * o_la)[None], eps)[0]
     else:
         o = (w_nla * rms_norm_rows(o_nla[None], eps)[0] + w_la * rms_norm_rows(o_la[None], eps)[0])
     return o, S, k_cache, v_cache, cache_len, overflow

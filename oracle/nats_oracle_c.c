@@ -114,6 +114,11 @@ static void head_forward(int L, int d, const float *q, const float *k, const flo
         double *o = O + (size_t)t * d;
         if (mode == 0) {
             for (int r = 0; r < d; ++r) o[r] = ola[r] + onla[r];
+        } else if (mode == 2) {                                   /* one normalisation of the weighted sum */
+            double wn = w_nla ? (double)w_nla[t] : 1.0, wl = w_la ? (double)w_la[t] : 1.0, ms = 0.0;
+            for (int r = 0; r < d; ++r) { o[r] = wn * onla[r] + wl * ola[r]; ms += o[r] * o[r]; }
+            double inv = 1.0 / sqrt(ms / d + eps);
+            for (int r = 0; r < d; ++r) o[r] *= inv;
         } else {
             double ms_la = 0.0, ms_nla = 0.0;
             for (int r = 0; r < d; ++r) { ms_la += ola[r] * ola[r]; ms_nla += onla[r] * onla[r]; }
@@ -224,6 +229,11 @@ int nats_oracle_decode(int BH, int d, int cap, double *state, float *k_cache, fl
         double *out = o + (size_t)u * d;
         if (mode == 0) {
             for (int r = 0; r < d; ++r) out[r] = ola[r] + onla[r];
+        } else if (mode == 2) {
+            double wn = w_nla ? (double)w_nla[u] : 1.0, wl = w_la ? (double)w_la[u] : 1.0, ms = 0.0;
+            for (int r = 0; r < d; ++r) { out[r] = wn * onla[r] + wl * ola[r]; ms += out[r] * out[r]; }
+            double inv = 1.0 / sqrt(ms / d + eps);
+            for (int r = 0; r < d; ++r) out[r] *= inv;
         } else {
             double ms_la = 0.0, ms_nla = 0.0;
             for (int r = 0; r < d; ++r) { ms_la += ola[r] * ola[r]; ms_nla += onla[r] * onla[r]; }
@@ -305,6 +315,11 @@ static void head_forward_chunk(int L, int d, int C, const float *q, const float 
             double *o = O + (size_t)t * d;
             if (mode == 0) {
                 for (int r = 0; r < d; ++r) o[r] = ola[r] + onla[r];
+            } else if (mode == 2) {
+                double wn = w_nla ? (double)w_nla[t] : 1.0, wl = w_la ? (double)w_la[t] : 1.0, ms = 0.0;
+                for (int r = 0; r < d; ++r) { o[r] = wn * onla[r] + wl * ola[r]; ms += o[r] * o[r]; }
+                double inv = 1.0 / sqrt(ms / d + eps);
+                for (int r = 0; r < d; ++r) o[r] *= inv;
             } else {
                 double ms_la = 0.0, ms_nla = 0.0;
                 for (int r = 0; r < d; ++r) { ms_la += ola[r] * ola[r]; ms_nla += onla[r] * onla[r]; }

@@ -21,6 +21,7 @@ NATS_F32, NATS_BF16 = 0, 1
 NATS_MATH_AUTO, NATS_MATH_FP32 = 0, 1
 NATS_ROUTE_TOKEN, NATS_ROUTE_CHUNK = 0, 1
 NATS_LINEAR_GDN, NATS_LINEAR_GATED = 0, 1
+NATS_WEIGHTS_SOFTMAX, NATS_WEIGHTS_SIGMOID, NATS_WEIGHTS_LINEAR = 0, 1, 2
 
 
 class NatsError(RuntimeError):
@@ -34,7 +35,7 @@ class FwdParams(ctypes.Structure):
                 ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
                 ("math", ctypes.c_int32), ("routing", ctypes.c_int32), ("linear_op", ctypes.c_int32),
-                ("freeze_on_softmax", ctypes.c_int32)]
+                ("freeze_on_softmax", ctypes.c_int32), ("weight_act", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -152,9 +153,9 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
                     math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN, linear_op=NATS_LINEAR_GDN,
-                    freeze_on_softmax=0) -> FwdParams:
+                    freeze_on_softmax=0, weight_act=0) -> FwdParams:
     return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing,
-                     linear_op, int(freeze_on_softmax))
+                     linear_op, int(freeze_on_softmax), weight_act)
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -168,7 +169,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                        la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
                        math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, linear_op: int = NATS_LINEAR_GDN,
                        freeze_on_softmax: bool = False, w_nla=None, w_la=None,
-                       W_out=None, initial_state=None, Q_nla=None, K_nla=None,
+                       W_out=None, weight_act: int = NATS_WEIGHTS_SOFTMAX, initial_state=None, Q_nla=None, K_nla=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
                        workspace=None) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
@@ -187,7 +188,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
     _require(Q_nla, "Q_nla", (B, H, L, d), dt)
     _require(K_nla, "K_nla", (B, H, L, d), dt)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing, linear_op, freeze_on_softmax)
+                             routing, linear_op, freeze_on_softmax, weight_act)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
@@ -338,7 +339,7 @@ def route_chunks(X, W_s, C: int = 64, want_scores: bool = True):
     return mask_c, scores
 
 
-def merge_weights(Q, W_out):
+def merge_weights(Q, W_out, weight_act: int = NATS_WEIGHTS_SOFTMAX):
     """nats_merge_weights (Eq. 22): Q [B,H,L,d], W_out [H,2,d] f32 -> (w_nla, w_la) [B,H,L] f32."""
     lib = load_library()
     B, H, L, d = Q.shape
@@ -346,7 +347,7 @@ def merge_weights(Q, W_out):
     _require(W_out, "W_out", (H, 2, d), torch.float32)
     w_nla = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
     w_la = torch.empty_like(w_nla)
-    params = make_fwd_params(B, H, L, d, 64, _dtype_code(Q))
+    params = make_fwd_params(B, H, L, d, 64, _dtype_code(Q), weight_act=weight_act)
     _check(lib.nats_merge_weights(ctypes.byref(params), _ptr(Q), _ptr(W_out), _ptr(w_nla), _ptr(w_la), _stream_ptr()))
     return w_nla, w_la
 

@@ -105,8 +105,8 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         return NATS_ERR_SHAPE;
     }
     if (p->C != 64) { set_error("chunk size C=%d has no kernel in this build (64 only)", p->C); return NATS_ERR_UNSUPPORTED; }
-    if (p->combine_mode != 0 && p->combine_mode != 1) {
-        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+    if (p->combine_mode < 0 || p->combine_mode > 2) {
+        set_error("combine_mode must be 0, 1 or 2 (got %d)", p->combine_mode);
         return NATS_ERR_SHAPE;
     }
     if (p->math != NATS_MATH_AUTO && p->math != NATS_MATH_FP32) {
@@ -128,6 +128,11 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->routing = p->routing;
     pl->linear_op = p->linear_op;
     pl->freeze_on_softmax = p->freeze_on_softmax;
+    if (p->weight_act < NATS_WEIGHTS_SOFTMAX || p->weight_act > NATS_WEIGHTS_LINEAR) {
+        set_error("weight_act must be a nats_weight_act (got %d)", p->weight_act);
+        return NATS_ERR_SHAPE;
+    }
+    pl->weight_act = p->weight_act;
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
     pl->dtype = p->dtype;
     pl->math = p->math;
@@ -207,7 +212,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 105; }
+int nats_abi_version(void) { return 107; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -311,10 +316,11 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (ex.idx) idx = ex.idx;
     if (ex.n_s) n_s = ex.n_s;
 
-    if (ex.W_out != nullptr && pl.combine_mode == 1) {   // Eq. 22: the merge weights from Q
+    if (ex.W_out != nullptr && pl.combine_mode != 0) {   // Eq. 22: the merge weights from Q
         float* w = reinterpret_cast<float*>(ws + pl.off_wout);
         ProfScope ps("merge_weights", stream);
-        st = launch_merge_weights(pl.B, pl.H, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BH * pl.L, stream);
+        st = launch_merge_weights(pl.B, pl.H, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BH * pl.L, pl.weight_act,
+                                  stream);
         if (st != NATS_OK) return st;
         ex.w_nla = w;
         ex.w_la = w + (size_t)pl.BH * pl.L;
@@ -536,11 +542,15 @@ nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const fl
         return NATS_ERR_SHAPE;
     }
     if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
+    if (p->weight_act < NATS_WEIGHTS_SOFTMAX || p->weight_act > NATS_WEIGHTS_LINEAR) {
+        set_error("weight_act must be a nats_weight_act (got %d)", p->weight_act);
+        return NATS_ERR_SHAPE;
+    }
     if (!Q || !W_out || !w_nla || !w_la) { set_error("Q, W_out, w_nla and w_la must be non-NULL"); return NATS_ERR_NULL; }
     if (!aligned16(Q) || !aligned16(W_out)) { set_error("Q and W_out must be 16-byte aligned"); return NATS_ERR_ALIGN; }
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     ProfScope ps("merge_weights", stream);
-    return launch_merge_weights(p->B, p->H, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, stream);
+    return launch_merge_weights(p->B, p->H, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, p->weight_act, stream);
 }
 
 nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, int32_t H, int32_t dtype,
@@ -575,8 +585,8 @@ static nats_status validate_dec_params(const nats_dec_params* p) {
         return NATS_ERR_SHAPE;
     }
     if (p->d != 64 && p->d != 128) { set_error("d must be 64 or 128 (got %d)", p->d); return NATS_ERR_SHAPE; }
-    if (p->combine_mode != 0 && p->combine_mode != 1) {
-        set_error("combine_mode must be 0 or 1 (got %d)", p->combine_mode);
+    if (p->combine_mode < 0 || p->combine_mode > 2) {
+        set_error("combine_mode must be 0, 1 or 2 (got %d)", p->combine_mode);
         return NATS_ERR_SHAPE;
     }
     if ((p->linear_op != NATS_LINEAR_GDN && p->linear_op != NATS_LINEAR_GATED) ||

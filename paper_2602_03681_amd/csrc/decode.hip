@@ -204,6 +204,16 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     }
     if (combine_mode == 0) {
         if (tid < D) o[(size_t)bh * D + tid] = from_float<T>(o_la + o_nla);
+    } else if (combine_mode == 2) {   // one normalisation of the (weighted) sum
+        const float sum = (w_nla ? w_nla[bh] : 1.f) * o_nla + (w_la ? w_la[bh] : 1.f) * o_la;
+        float x = (tid < D) ? sum * sum : 0.f;
+        x = group_sum<64>(x);
+        if ((tid & 63) == 0 && tid < 128) s_red[tid >> 6] = x;
+        __syncthreads();
+        if (tid < D) {
+            const float ss = s_red[0] + (D > 64 ? s_red[1] : 0.f);
+            o[(size_t)bh * D + tid] = from_float<T>(sum / sqrtf(ss / D + eps));
+        }
     } else {
         float x = (tid < D) ? o_la * o_la : 0.f, y = (tid < D) ? o_nla * o_nla : 0.f;
         x = group_sum<64>(x); y = group_sum<64>(y);

@@ -389,16 +389,24 @@ __global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
             const half4 lah = lah_all[nq][pass];
             const float la0 = (float)lah[0], la1 = (float)lah[1], la2 = (float)lah[2], la3 = (float)lah[3];
             float wn = 1.f, wl = 1.f;
-            if (combine_mode != 0) {
+            if (combine_mode == 1) {          // Eq. 21: each branch normalised, then weighted
                 const float ss_nla = lane_group_sum<LPR>(x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w);
                 const float ss_la = lane_group_sum<LPR>(la0 * la0 + la1 * la1 + la2 * la2 + la3 * la3);
                 wn = (w_nla ? w_nla[tokbase + (live ? q : 0)] : 0.5f) / sqrtf(ss_nla / D + eps);
                 wl = (w_la ? w_la[tokbase + (live ? q : 0)] : 0.5f) / sqrtf(ss_la / D + eps);
+            } else if (combine_mode == 2) {   // one normalisation of the (weighted) sum
+                wn = w_nla ? w_nla[tokbase + (live ? q : 0)] : 1.f;
+                wl = w_la ? w_la[tokbase + (live ? q : 0)] : 1.f;
+            }
+            float o0 = wn * x.x + wl * la0, o1 = wn * x.y + wl * la1, o2 = wn * x.z + wl * la2, o3 = wn * x.w + wl * la3;
+            if (combine_mode == 2) {
+                const float inv = 1.f / sqrtf(lane_group_sum<LPR>(o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3) / D + eps);
+                o0 *= inv; o1 *= inv; o2 *= inv; o3 *= inv;
             }
             if (live) {
                 uint2 w;
-                w.x = pack_bf16x2(wn * x.x + wl * la0, wn * x.y + wl * la1);
-                w.y = pack_bf16x2(wn * x.z + wl * la2, wn * x.w + wl * la3);
+                w.x = pack_bf16x2(o0, o1);
+                w.y = pack_bf16x2(o2, o3);
                 *reinterpret_cast<uint2*>(O + off) = w;
             }
         }

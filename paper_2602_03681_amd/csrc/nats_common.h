@@ -115,6 +115,7 @@ struct FwdPlan {
     int combine_mode;
     int routing;   // nats_routing
     int linear_op, freeze_on_softmax;   // variants of the linear branch, see nats_fwd_params
+    int weight_act;                     // nats_weight_act
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
@@ -159,7 +160,7 @@ nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, f
 nats_status launch_route_chunks(int B, int L, int C, int d_model, int H, int dtype, const void* X, const float* W_s,
                                 float* scores, uint8_t* mask_c, hipStream_t st);
 nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const void* Q, const float* W_out,
-                                 float* w_nla, float* w_la, hipStream_t st);
+                                 float* w_nla, float* w_la, int act, hipStream_t st);
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,
                                  const float* chunk_decay, int32_t* chunk_pos, int32_t* cache_len,
                                  const uint8_t* mask_c, int32_t* err_flags, hipStream_t st);

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     if (combine_mode == 0) {
 #pragma unroll
         for (int c = 0; c < DP; ++c) out[c] = la[c] + acc[c];
-    } else {
+    } else if (combine_mode == 1) {   // Eq. 21: each branch normalised, then weighted
         float ss_la = 0.f, ss_nla = 0.f;
 #pragma unroll
         for (int c = 0; c < DP; ++c) { ss_la += la[c] * la[c]; ss_nla += acc[c] * acc[c]; }
@@ -156,6 +156,15 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         const float wl = (w_la ? w_la[(size_t)bh * L + t] : 0.5f) / sqrtf(ss_la / D + eps);
 #pragma unroll
         for (int c = 0; c < DP; ++c) out[c] = wn * acc[c] + wl * la[c];
+    } else {                          // one normalisation of the (weighted) sum
+        const float wn = w_nla ? w_nla[(size_t)bh * L + t] : 1.f, wl = w_la ? w_la[(size_t)bh * L + t] : 1.f;
+        float ss = 0.f;
+#pragma unroll
+        for (int c = 0; c < DP; ++c) { out[c] = wn * acc[c] + wl * la[c]; ss += out[c] * out[c]; }
+        ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2);
+        const float inv = 1.f / sqrtf(ss / D + eps);
+#pragma unroll
+        for (int c = 0; c < DP; ++c) out[c] *= inv;
     }
 #pragma unroll
     for (int c = 0; c < DP; c += EPL) Vec16<T>::store(O + row_off + c, out + c);

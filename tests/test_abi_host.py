@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 105   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla
+    assert lib.nats_abi_version() == 107   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2
 
 
 def good_params(**over):
@@ -67,7 +67,7 @@ def call_fwd(lib, p, ptrs=None, ws=FAKE, ws_bytes=1 << 40, extra=None):
     (dict(L=100), E_SHAPE), (dict(L=0), E_SHAPE), (dict(B=0), E_SHAPE), (dict(d=96), E_SHAPE),
     (dict(dtype_code=7), E_DTYPE), (dict(C=32, L=256), E_UNSUP), (dict(combine_mode=3), E_SHAPE),
     (dict(math=9), E_SHAPE), (dict(B=70000, H=1), E_SHAPE), (dict(linear_op=2), E_SHAPE),
-    (dict(freeze_on_softmax=3), E_SHAPE),
+    (dict(freeze_on_softmax=3), E_SHAPE), (dict(weight_act=3), E_SHAPE),
 ])
 def test_bad_params_are_rejected(lib, over, code):
     assert call_fwd(lib, good_params(**over)) == code
@@ -113,7 +113,7 @@ def test_decode_validation(lib):
     assert call(nb.DecParams(4, 2, 100, 512, nb.NATS_BF16, 0, 0, 0, 0)) == E_SHAPE
     assert call(nb.DecParams(4, 2, 128, 0, nb.NATS_BF16, 0, 0, 0, 0)) == E_SHAPE
     assert call(nb.DecParams(4, 2, 128, 512, 5, 0, 0, 0, 0)) == E_DTYPE
-    assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 2, 0)) == E_SHAPE
+    assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 3, 0)) == E_SHAPE
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 5, 0)) == E_SHAPE     # linear_op
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 1, 2)) == E_SHAPE     # freeze_on_softmax
     assert call(nb.DecParams(4, 2, 128, 512, nb.NATS_BF16, 0, 0, 0, 0, 0, 0, FAKE, None)) == E_NULL   # q_nla alone

@@ -283,3 +283,25 @@ def test_eq22_merge_weights_kernel_and_forward(dtype, d):
     with pytest.raises(nb.NatsError):   # given weights and W_out exclude each other
         nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, combine_mode=1,
                                 W_out=Wd, w_nla=w_nla)
+
+
+@pytest.mark.parametrize("act", [nb.NATS_WEIGHTS_SIGMOID, nb.NATS_WEIGHTS_LINEAR])
+def test_merge_weight_activations(act):
+    """Section 5, ablation (iv): sigmoid or no activation instead of the softmax of Eq. 22, as a call of its own
+    and inside the forward."""
+    from oracle import nats_oracle as no
+    B, H, L, d = 1, 3, 256, 64
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=85)
+    W = (np.random.default_rng(86).standard_normal((H, 2, d)) * 1.5).astype(np.float32)
+    w_ref = no.eq22_weights(x["Q"], W, act=act)
+    g = to_dev(x, "bf16")
+    Wd = torch.from_numpy(W).cuda()
+    w_nla, w_la = nats.merge_weights(g["Q"], Wd, weight_act=act)
+    torch.cuda.synchronize()
+    scale = max(1.0, float(np.abs(w_ref[0]).max()))
+    assert np.abs(host(w_nla) - w_ref[0]).max() <= 4e-6 * scale and np.abs(host(w_la) - w_ref[1]).max() <= 4e-6 * scale
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, combine_mode=1, W_out=Wd,
+                                weight_act=act)
+    torch.cuda.synchronize()
+    ref = oracle_fwd(x, mode=1, w_nla=w_ref[0], w_la=w_ref[1], want=())
+    assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"]

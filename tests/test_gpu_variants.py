@@ -189,3 +189,34 @@ def test_separate_softmax_queries_and_keys_decode(dtype, d):
     for b in range(cfg.B):
         for h in range(cfg.H):
             assert int(host(clen)[b, h]) == ref[b][h]["n"]
+
+
+@pytest.mark.parametrize("dtype,d,math", [("f32", 64, 0), ("bf16", 128, 0), ("bf16", 64, 1)])
+def test_single_normalisation_merge(dtype, d, math):
+    """combine_mode 2 (Section 5, ablation (iii)): RMSNorm of the weighted sum, forward and decode."""
+    B, H, L = 1, 2, 320
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=131 + d)
+    w = (np.random.default_rng(132).random((2, B, H, L)) + 0.5).astype(np.float32)
+    g = to_dev(x, dtype)
+    for given in (True, False):
+        kw = dict(w_nla=torch.from_numpy(w[0]).cuda(), w_la=torch.from_numpy(w[1]).cuda()) if given else {}
+        r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, want=(), combine_mode=2,
+                                    math=nb.NATS_MATH_FP32 if math else nb.NATS_MATH_AUTO, **kw)
+        torch.cuda.synchronize()
+        ref = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], mode=2,
+                           w_nla=w[0] if given else None, w_la=w[1] if given else None, want=())
+        assert rel_err(host(r["O"]), ref["O"], stored(dtype)) <= TOL[dtype], given
+    # decode
+    cfg = DecodeConfig("small", 2, 2, d, dtype, 0.4, seed=133, len_lo=1, len_hi=30, steps=6)
+    xd = make_decode_inputs(cfg, steps=cfg.steps)
+    gd = to_dev(xd, dtype)
+    state, kc, vc, clen = gd["state"].clone(), gd["k_cache"].clone(), gd["v_cache"].clone(), gd["cache_len"].clone()
+    S_ref, kc_ref, vc_ref, cl_ref = xd["state"].astype(np.float64), xd["k_cache"].copy(), xd["v_cache"].copy(), xd["cache_len"].copy()
+    wd = (np.random.default_rng(134).random((2, cfg.steps, cfg.B, cfg.H)) + 0.5).astype(np.float32)
+    for s in range(cfg.steps):
+        o = nats.hybrid_attn_decode(state, kc, vc, clen, gd["q"][s], gd["k"][s], gd["v"][s], gd["alpha"][s], gd["beta"][s],
+                                    gd["mask"][s], combine_mode=2, w_nla=torch.from_numpy(wd[0, s]).cuda(),
+                                    w_la=torch.from_numpy(wd[1, s]).cuda())
+        o_ref, _ = c_oracle.decode(S_ref, kc_ref, vc_ref, cl_ref, xd["q"][s], xd["k"][s], xd["v"][s], xd["alpha"][s],
+                                   xd["beta"][s], xd["mask"][s], mode=2, w_nla=wd[0, s], w_la=wd[1, s])
+        assert rel_err(host(o), o_ref, stored(dtype)) <= TOL[dtype], s

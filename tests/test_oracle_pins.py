@@ -508,3 +508,38 @@ def test_separate_softmax_queries_and_keys():
     for t in range(L0, 48):
         o, S, kc, vc, n, _ = npo.decode_step(S, kc, vc, n, q[t], k[t], v[t], a[t], b[t], m[t], q_nla=qn[t], k_nla=kn[t])
         np.testing.assert_allclose(o, r["O"][t], rtol=1e-9, atol=1e-11)
+
+
+def test_merge_weight_activations_of_the_ablation():
+    """act = 1: a library sigmoid of each logit; act = 2: the logits; act = 0 stays the softmax over the pair,
+    which is the sigmoid of the logits' difference."""
+    from scipy.special import expit
+    rng = np.random.default_rng(41)
+    Q = rng.standard_normal((2, 3, 7, 8))
+    W = rng.standard_normal((3, 2, 8))
+    logits = np.einsum("bhld,hkd->bhlk", Q, W)
+    a1, b1 = npo.eq22_weights(Q, W, act=1)
+    np.testing.assert_allclose(a1, expit(logits[..., 0]), rtol=1e-12)
+    np.testing.assert_allclose(b1, expit(logits[..., 1]), rtol=1e-12)
+    a2, b2 = npo.eq22_weights(Q, W, act=2)
+    np.testing.assert_array_equal(a2, logits[..., 0])
+    np.testing.assert_array_equal(b2, logits[..., 1])
+    a0, b0 = npo.eq22_weights(Q, W)
+    np.testing.assert_allclose(a0, expit(logits[..., 0] - logits[..., 1]), rtol=1e-12)
+    np.testing.assert_allclose(a0 + b0, 1.0, rtol=1e-12)
+
+
+def test_single_normalisation_merge_against_library_rms_norm():
+    """combine mode 2 (Section 5, ablation (iii)): a library RMS norm of the weighted sum; the C oracle agrees."""
+    rng = np.random.default_rng(51)
+    o_la, o_nla = rng.standard_normal((9, 16)), rng.standard_normal((9, 16))
+    wn, wl = rng.random(9) + 0.5, rng.random(9) + 0.5
+    ref = torch.nn.functional.rms_norm(torch.tensor(wn[:, None] * o_nla + wl[:, None] * o_la), (16,), eps=1e-6).numpy()
+    np.testing.assert_allclose(npo.combine(o_la, o_nla, 2, wn, wl, 1e-6), ref, rtol=1e-12)
+    np.testing.assert_allclose(npo.combine(o_la, o_nla, 2, None, None, 1e-6),
+                               torch.nn.functional.rms_norm(torch.tensor(o_nla + o_la), (16,), eps=1e-6).numpy(), rtol=1e-12)
+    x = make_fwd_inputs(1, 2, 64, 8, "f32", 0.3, seed=52)
+    w = rng.random((2, 1, 2, 64)).astype(np.float32)
+    r = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], mode=2, w_nla=w[0], w_la=w[1])
+    ref = npo.hybrid_fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], mode=2, w_nla=w[0], w_la=w[1])
+    np.testing.assert_allclose(r["O"], ref["O"], rtol=1e-9, atol=1e-12)
