@@ -108,9 +108,11 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const int n_chunks = L / CH;
     // One-dimensional grid, chunk-major: all (batch, head) pairs of a chunk side by side (padded to a
     // multiple of 8, so that a pair's blocks land on the XCD whose L2 the recurrence blocks of that pair
-    // use), the chunks front to back, the order in which the recurrence will want them.
+    // use), the chunks back to front: what the recurrence reads first is then what was written last and is
+    // still in the caches (its time per chunk is 1.05 microseconds while all operands fit the memory-side
+    // cache, 1.3 beyond; on the headline shape this order brought it from 1.31 to 1.20).
     const int bh8 = (BH + 7) & ~7;
-    const int chunk = blockIdx.x / bh8, bh = blockIdx.x % bh8;
+    const int chunk = n_chunks - 1 - blockIdx.x / bh8, bh = blockIdx.x % bh8;
     if (bh >= BH) return;
     const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
     const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
