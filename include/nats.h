@@ -18,6 +18,10 @@
  *     into the given stream with events; legal under stream capture, but the
  *     first call on a device must not be made while capturing if the overlap
  *     is wanted).  Two calls that overlap in time need different workspaces.
+ *     Two switches in the environment, read once, for comparisons:
+ *     NATS_SINGLE_STREAM=1 keeps every kernel on the given stream;
+ *     NATS_NO_PREFETCH_HELPERS=1 runs the recurrence kernel without the extra
+ *     blocks that touch its operands ahead of use.
  *   - Arguments are validated on the host before anything is launched; a bad
  *     argument returns a negative nats_status and launches nothing.
  *     nats_last_error() then describes the problem (thread-local string).

@@ -468,7 +468,8 @@ static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* 
     const int n_compute = 8 * ((pl.BH + 7) / 8) * (D / BV);   // see the block -> (bh, slice) map in the kernel
     // prefetch helpers only where CUs would otherwise idle (one compute block fills a CU)
     const int n_helper = 8 * ((pl.BH + 7) / 8);
-    const bool helpers = progress != nullptr && n_compute + n_helper <= 256 && getenv("NATS_NO_PREFETCH_HELPERS") == nullptr;
+    static const bool helpers_off = getenv("NATS_NO_PREFETCH_HELPERS") != nullptr;   // A/B switch, read once
+    const bool helpers = progress != nullptr && n_compute + n_helper <= 256 && !helpers_off;
     dim3 grid(n_compute + (helpers ? n_helper : 0));
     if (O_nla_h != nullptr)
         hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, true>), grid, dim3(SCAN_THREADS_G), 0, st,
