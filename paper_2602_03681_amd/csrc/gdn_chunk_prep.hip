@@ -76,6 +76,11 @@ __device__ __forceinline__ int swz_t(int drow, int tok, int TS) {
     return drow * TS + ((((tok >> 3) ^ (drow >> 3)) & 7) << 3) + (tok & 7);
 }
 
+#ifndef NATS_PREP_CPB
+#define NATS_PREP_CPB 2
+#endif
+constexpr int PREP_CPB = NATS_PREP_CPB;   // chunks per block
+
 template <int D>
 __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -103,34 +108,52 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
     half_t* s_gdec_h = reinterpret_cast<half_t*>(s_gdec + CH);   // fp16 copies of gam_C / gam and gam
     half_t* s_gam_h = s_gdec_h + CH;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, lq = lane >> 4;
+    const int tid0 = threadIdx.x;
     const int n_chunks = L / CH;
     // One-dimensional grid, chunk-major: all (batch, head) pairs of a chunk side by side (padded to a
     // multiple of 8, so that a pair's blocks land on the XCD whose L2 the recurrence blocks of that pair
     // use), the chunks back to front: what the recurrence reads first is then what was written last and is
     // still in the caches (its time per chunk is 1.05 microseconds while all operands fit the memory-side
     // cache, 1.3 beyond; on the headline shape this order brought it from 1.31 to 1.20).
+    // A block takes PREP_CPB chunks of one pair, one after the other, and issues the global loads of the next
+    // chunk while it works on the current one (K and Q as soon as their registers are free, V later): with
+    // two blocks per CU (LDS) there are not enough wavefronts to hide that latency otherwise.
     const int bh8 = (BH + 7) & ~7;
-    const int chunk = n_chunks - 1 - blockIdx.x / bh8, bh = blockIdx.x % bh8;
+    const int bh = blockIdx.x % bh8;
     if (bh >= BH) return;
-    const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
-    const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
+    int chunk = n_chunks - 1 - (blockIdx.x / bh8) * PREP_CPB;
+    // The thread's indices are re-derived inside the chunk loop from a value the compiler cannot see through:
+    // otherwise it hoists every LDS address of the body out of the loop and runs out of registers.
+    int tid = tid0;
 
     NATS_MARK(0);
     // ---- tiles: coalesced 16-byte loads (a [64][D] tile is contiguous in global memory) --------
     u32x4 rk[NPC], rq[NPC], rv[NPC];
-    {
-        const u32x4* Kg = reinterpret_cast<const u32x4*>(K + tok0 * D);
-        const u32x4* Qg = reinterpret_cast<const u32x4*>(Q + tok0 * D);
-        const u32x4* Vg = reinterpret_cast<const u32x4*>(V + tok0 * D);
+    auto load_kq = [&](int c) __attribute__((always_inline)) {
+        const size_t t0 = (size_t)bh * L + (size_t)c * CH;
+        const u32x4* Kg = reinterpret_cast<const u32x4*>(K + t0 * D);
+        const u32x4* Qg = reinterpret_cast<const u32x4*>(Q + t0 * D);
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             rk[i] = Kg[tid + PREP_THREADS * i];
             rq[i] = Qg[tid + PREP_THREADS * i];
-            rv[i] = Vg[tid + PREP_THREADS * i];
         }
-    }
+    };
+    auto load_v = [&](int c) __attribute__((always_inline)) {
+        const u32x4* Vg = reinterpret_cast<const u32x4*>(V + ((size_t)bh * L + (size_t)c * CH) * D);
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) rv[i] = Vg[tid + PREP_THREADS * i];
+    };
+    load_kq(chunk);
+    load_v(chunk);
+#pragma unroll 1
+    for (int it = 0; it < PREP_CPB && chunk >= 0; ++it, --chunk) {
+    const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
+    const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
+    const bool more = it + 1 < PREP_CPB && chunk > 0;   // another chunk follows in this block (uniform)
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
     // ---- gates: cumulative log-decay and write strengths -------------------------------
     if (wave == 0) {
         // variant without decay on softmax tokens (routing per token): their alpha counts as 1
@@ -164,6 +187,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) KsT[swz_t(c8 * 8 + j, row, TS)] = hk[j];
     }
+    if (more) load_kq(chunk - 1);
     __syncthreads();
     NATS_MARK(1);
 
@@ -349,6 +373,7 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) VsT[swz_t(c8 * 8 + j, row, TS)] = hv[j];
     }
+    if (more) load_v(chunk - 1);
     NATS_MARK(4);
     __syncthreads();
     NATS_MARK(5);
@@ -385,15 +410,16 @@ __global__ __launch_bounds__(PREP_THREADS, 2) void gdn_chunk_prep_kernel(
         }
     }
     NATS_MARK(6);
-    __syncthreads();
+    __syncthreads();   // also: the LDS regions are free for the block's next chunk
     NATS_MARK(7);
+    }
 }
 
 // per chunk: WF, QF, KdF, UtF (64 * d fp16 each), PF (64 * 64 fp16), gamC (1 fp32); layouts above
 nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                   const float* alpha, const float* beta, const uint8_t* mask, void* WF,
                                   void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st) {
-    dim3 grid((unsigned)((pl.L / CH) * ((pl.BH + 7) & ~7)));
+    dim3 grid((unsigned)(((pl.L / CH + PREP_CPB - 1) / PREP_CPB) * ((pl.BH + 7) & ~7)));
     // the LDS-size attribute is per function and device: set once per device, not per launch
     static bool attr_done[2][64] = {};
     int dev = 0;
