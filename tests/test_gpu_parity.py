@@ -305,3 +305,27 @@ def test_merge_weight_activations(act):
     torch.cuda.synchronize()
     ref = oracle_fwd(x, mode=1, w_nla=w_ref[0], w_la=w_ref[1], want=())
     assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_more_pairs_than_the_chip_has_cus(d):
+    """B*H = 80: the recurrence kernel's grid (320 blocks) exceeds the CU count, so it runs without its prefetch
+    helper blocks and in more than one wave of blocks; the padded pair count of the one-dimensional grids
+    (80 is a multiple of 8, 75 below is not) changes nothing."""
+    for B, H in ((5, 16), (5, 15)):
+        x = make_fwd_inputs(B, H, 256, d, "bf16", 0.1, seed=95 + H)
+        r = run_ex(x, "bf16", want=("final_state", "n_s"))
+        ref = oracle_fwd(x, want=("S", "n_s"))
+        assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"]
+        assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"]
+        np.testing.assert_array_equal(host(r["n_s"]), ref["n_s"])
+
+
+def test_one_chunk_and_long_thin_shapes_bf16():
+    """L = 64 (a single chunk, a single query tile) and a long single head."""
+    for B, H, L, d in ((2, 2, 64, 128), (1, 1, 16384, 64)):
+        x = make_fwd_inputs(B, H, L, d, "bf16", 0.05, seed=97 + d)
+        r = run_ex(x, "bf16", want=("final_state",))
+        ref = oracle_fwd(x, want=("S",))
+        assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"], (L, d)
+        assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (L, d)
