@@ -40,8 +40,11 @@ def kernel_work(name, cfg, sum_cnt):
         # Algorithmic bytes: K, Q, V, alpha, beta, mask in; W, U~ (fp16) and P (C fp16 per token) out.
         # The re-laid-out copies of Q and K it also writes are this design's choice and are not counted.
         return "hbm", n_tok * (3 * d * esz + 9 + 2 * d * 2 + cfg.C * 2)
-    if name == "gdn_chunk_scan":    # W S^T, Q S^T, U^T K: 3 x 2 d^2, and P U: 2 C d, per token
-        return "mfma_bf16", n_tok * (6 * d * d + 2 * cfg.C * d)
+    if name == "gdn_chunk_scan":
+        # Its products (W S^T, Q S^T, U^T K: 3 x 2 d^2, and P U: 2 C d FLOP per token) would take a fifth of the
+        # time its operands take to stream at the HBM peak, so HBM is the roofline that bounds it: per token
+        # W, U~, Kd, Qg (fp16) and P (C fp16) in, the softmax branch's output (fp16) in, O out.
+        return "hbm", n_tok * (4 * d * 2 + cfg.C * 2 + d * 2 + d * esz) + (n_tok // cfg.C) * 4
     if name == "flash_softmax":
         return "mfma_bf16", 4 * d * sum_cnt
     return None
@@ -303,8 +306,7 @@ def main():
                         "frac": round(achieved / peak, 5), "traffic": measured_traffic_bytes(dom),
                         "avg_kernel_ms": round(kernels[dom]["avg_ms"], 4)}
 
-    # every kernel of the step against its own bound (kernels that ran side by side on two streams
-    # shared the chip while their events were open)
+    # every kernel of the step against its own bound
     kernel_rooflines = {}
     for name, k in kernels.items():
         work = kernel_work(name, cfg, sum_cnt)

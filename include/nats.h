@@ -13,13 +13,9 @@
  *     work is ordered after what the given HIP stream (a hipStream_t passed as
  *     void*, NULL = the default stream) held at the call, is complete when that
  *     stream reaches the end of what the call enqueued, and the call returns
- *     immediately.  The forward may run part of its kernels on a second stream
- *     that the library creates once per device (forked from and joined back
- *     into the given stream with events; legal under stream capture, but the
- *     first call on a device must not be made while capturing if the overlap
- *     is wanted).  Two calls that overlap in time need different workspaces.
- *     Two switches in the environment, read once, for comparisons:
- *     NATS_SINGLE_STREAM=1 keeps every kernel on the given stream;
+ *     immediately.  Every kernel of a call runs on the given stream (legal
+ *     under stream capture).  Two calls that overlap in time need different
+ *     workspaces.  One switch in the environment, read once, for comparisons:
  *     NATS_NO_PREFETCH_HELPERS=1 runs the recurrence kernel without the extra
  *     blocks that touch its operands ahead of use.
  *   - Arguments are validated on the host before anything is launched; a bad

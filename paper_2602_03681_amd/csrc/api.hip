@@ -22,38 +22,6 @@ void set_error(const char* fmt, ...) {
     va_end(ap);
 }
 
-// A second stream per device with the events to fork to it and join it back.  With the plain-sum
-// merge the compaction and the softmax branch depend on nothing the linear branch's preparation
-// computes: they run beside it and join before the kernel that merges.  Created on first use, kept
-// until the process ends; the mutex makes one call's record / wait pairs atomic.
-struct SideQueue {
-    bool tried = false, ok = false;
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-};
-static SideQueue g_side[64];
-static std::mutex g_side_mutex;
-
-// caller_stream: the stream of the call; while it is being captured into a graph no HIP object is
-// created (a first call under capture runs on one stream)
-static SideQueue* side_queue_locked(hipStream_t caller_stream) {
-    static const bool off = getenv("NATS_SINGLE_STREAM") != nullptr;   // A/B switch
-    int dev = 0;
-    if (off || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    SideQueue& q = g_side[dev];
-    if (!q.tried) {
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(caller_stream, &cap) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-        if (cap != hipStreamCaptureStatusNone) return nullptr;
-        q.tried = true;
-        q.ok = hipStreamCreateWithFlags(&q.stream, hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&q.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&q.join, hipEventDisableTiming) == hipSuccess;
-        if (!q.ok) (void)hipGetLastError();   // fall back to one stream
-    }
-    return q.ok ? &q : nullptr;
-}
-
 nats_status check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -325,39 +293,16 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         ex.w_nla = w;
         ex.w_la = w + (size_t)pl.BH * pl.L;
     }
-    // With the plain-sum merge on the chunkwise path, the compaction and the softmax branch go to
-    // the side stream (forked here, joined before the kernel that merges).
-    const bool fork_ok = uses_chunk_path(pl) && pl.combine_mode == 0;
-    std::unique_lock<std::mutex> side_lock(g_side_mutex, std::defer_lock);
-    SideQueue* side = nullptr;
-    if (fork_ok) {
-        side_lock.lock();
-        side = side_queue_locked(stream);
-        if (side != nullptr && (hipEventRecord(side->fork, stream) != hipSuccess ||
-                                hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)) {
-            (void)hipGetLastError();
-            side = nullptr;   // nothing was forked yet: carry on with one stream
-        }
-        if (side == nullptr) side_lock.unlock();
-    }
-    hipStream_t s_nla = side != nullptr ? side->stream : stream;   // stream of the softmax branch
-    // every exit below this point goes through join(): work forked to the side stream is always joined
-    auto join = [&]() -> bool {
-        if (side == nullptr) return true;
-        const bool ok = hipEventRecord(side->join, side->stream) == hipSuccess &&
-                        hipStreamWaitEvent(stream, side->join, 0) == hipSuccess;
-        side = nullptr;
-        side_lock.unlock();
-        if (!ok) set_error("side-stream join failed: %s", hipGetErrorString(hipGetLastError()));
-        return ok;
-    };
+    // The kernels run one after the other on the caller's stream.  (The softmax branch depends on nothing
+    // the preparation of the linear branch computes, but the preparation kernel fills every CU by itself:
+    // beside it on a second stream the softmax branch only waited for free slots, and nothing was gained.)
     {
-        ProfScope ps("scan_compact", s_nla);
+        ProfScope ps("scan_compact", stream);
         st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
                                  uses_chunk_path(pl) ? ws + pl.off_vht : nullptr,
-                                 uses_chunk_path(pl) ? reinterpret_cast<int32_t*>(ws + pl.off_prog) : nullptr, s_nla);
+                                 uses_chunk_path(pl) ? reinterpret_cast<int32_t*>(ws + pl.off_prog) : nullptr, stream);
     }
-    if (st != NATS_OK) { join(); return st; }
+    if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
         void* WF = ws + pl.off_w;
         void* QF = ws + pl.off_qf;
@@ -372,16 +317,15 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         // Eq. 21 needs whole rows of both branches: there the softmax kernel runs last and merges.
         const bool merge_in_scan = pl.combine_mode == 0;
         if (merge_in_scan) {
-            ProfScope ps("flash_softmax", s_nla);
+            ProfScope ps("flash_softmax", stream);
             st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
-                                      s_nla);
-            if (st != NATS_OK) { join(); return st; }
+                                      stream);
+            if (st != NATS_OK) return st;
         }
-        {
+        {   // last before the recurrence, which then finds its first operands in the caches
             ProfScope ps("gdn_chunk_prep", stream);
             st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, WF, QF, KdF, UtF, PF, gamC, stream);
         }
-        if (!join()) return NATS_ERR_HIP;
         if (st != NATS_OK) return st;
         {
             ProfScope ps("gdn_chunk_scan", stream);
