@@ -32,6 +32,13 @@
 #define NATS_MARK_STEP (-1)
 #endif
 
+#ifndef NATS_SCAN_BV128
+#define NATS_SCAN_BV128 32          // d_v values per block for d = 128
+#endif
+#ifndef NATS_SCAN_HELPER_LIMIT
+#define NATS_SCAN_HELPER_LIMIT 256  // prefetch helpers only while compute blocks + helpers stay within the CUs
+#endif
+
 namespace nats {
 
 constexpr int SCAN_THREADS_G = 512;   // 8 wavefronts: 4 carry the state, 4 produce the output
@@ -215,8 +222,8 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
     const bool publisher = progress != nullptr && is_chain && v0 == 0 && tid == 0;   // reports progress
     // Both groups run the same barrier sequence (two per chunk).  Loads are issued PF_DIST chunks
     // ahead of use through PF_DIST + 1 rotating register stages; they are unconditional (the tail re-loads the
-    // last chunk) and the first steps are peeled, so that the compiler's load-wait counts
-    // stay exact and never include the loads issued after the one being waited for.
+    // last chunk), so that the compiler's load-wait counts stay exact and never include the loads issued
+    // after the one being waited for.
 
     if (is_chain) {
         // ---- state: S^T tiles (rows d_k, cols v) as fp32 accumulators; fp16 copy S[v][d_k] in LDS -----
@@ -240,9 +247,14 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         stC.load(WF, KdF, UtF, gamC, gc0 + min(2, n_chunks - 1), v0, w4, lane);
         __syncthreads();   // initial state copy visible
 
+        int c_pub = 0;
         auto step = [&](int c, const ChainStage<D, BV>& cur, ChainStage<D, BV>& nxt) __attribute__((always_inline)) {
             if (c == NATS_MARK_STEP) NATS_MARK(0);
-            if (publisher) __hip_atomic_store(progress + bh * PROG_STRIDE, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // The published chunk number lives in a vector register of its own: a temporary for the store's data
+            // would be a register with a load in flight, and the store would wait for every load before it.
+            asm volatile("" : "+v"(c_pub));
+            if (publisher) __hip_atomic_store(progress + bh * PROG_STRIDE, c_pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c_pub += 1;
             // The loads for chunk c + PF_DIST are issued one at a time between the matrix instructions of
             // this step: issued in a burst they queue in the CU's vector-memory path (about 16 cycles
             // per 1 KiB load, shared with the output group) and stall the wavefront that carries the
@@ -313,17 +325,20 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
             __syncthreads();   // new state copy visible; U copy free again
             if (c == NATS_MARK_STEP) NATS_MARK(4);
         };
-        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST)
-        step(0, stA, stD);
-        if (n_chunks > 1) step(1, stB, stA);
-        if (n_chunks > 2) step(2, stC, stB);
-        if (n_chunks > 3) step(3, stD, stC);
-        for (int c = 4; c < n_chunks; c += 4) {
+        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST).  Four unconditional steps per
+        // trip: every path into the loop header then has the same loads in flight, in the same order (three
+        // stages' worth), and the compiler's wait counts are exact.  A conditional step inside the loop makes it
+        // merge paths with fewer loads in flight and wait for all of them, also for those just issued.
+        int c = 0;
+        for (; c + 4 <= n_chunks; c += 4) {
             step(c, stA, stD);
-            if (c + 1 < n_chunks) step(c + 1, stB, stA);
-            if (c + 2 < n_chunks) step(c + 2, stC, stB);
-            if (c + 3 < n_chunks) step(c + 3, stD, stC);
+            step(c + 1, stB, stA);
+            step(c + 2, stC, stB);
+            step(c + 3, stD, stC);
         }
+        if (c < n_chunks) step(c, stA, stD);
+        if (c + 1 < n_chunks) step(c + 1, stB, stA);
+        if (c + 2 < n_chunks) step(c + 2, stC, stB);
         if (S_final != nullptr) {
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
@@ -351,8 +366,7 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         // wavefront (transposed there so that a lane owns VPL consecutive d_v of one token and every
         // global access is a full row segment).  Between the two barriers of a step stand only the
         // products that read U and the writes into that tile: the dependent chain waits at the second
-        // barrier.  Reading the tile back, the merge and the store of chunk c - 1 are spread between
-        // the matrix instructions of step c's first phase, like the loads for chunk c + PF_DIST.
+        // barrier.  Reading the tile back, the merge and the store of chunk c - 1 come at the start of step c.
         constexpr int OSTR = Lds::OSTR;
         float* Ost = ost_all + w4 * 16 * OSTR;
         using OS_t = OutStage<D, BV>;
@@ -401,8 +415,9 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 ++piece;
                 __builtin_amdgcn_sched_barrier(0);
             };
-            // rows of the previous chunk first: the chain group's reads of the state copy get the LDS
-            // to themselves for a few hundred cycles
+            // rows of the previous chunk first: the chain group's reads of the state copy get the LDS to themselves
+            // for a few hundred cycles.  (Moving them behind the first barrier, where this group has time to
+            // spare, changed nothing: the two groups share the SIMDs.)
             if (c > 0) {
                 store_rows(c - 1, nxt);
                 __builtin_amdgcn_sched_barrier(0);
@@ -439,17 +454,18 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
                 for (int j = 0; j < 4; ++j) Ost[(4 * lq + j) * OSTR + 16 * nt + l16] = la_scale * accO[nt][j];
             __syncthreads();   // U copy free again
         };
-        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST, which held chunk c - 1)
-        step(0, stA, stD);
-        if (n_chunks > 1) step(1, stB, stA);
-        if (n_chunks > 2) step(2, stC, stB);
-        if (n_chunks > 3) step(3, stD, stC);
-        for (int c = 4; c < n_chunks; c += 4) {
+        // step(c, stage holding chunk c, stage to refill with chunk c + PF_DIST, which held chunk c - 1);
+        // the same loop shape as the other group's (same barriers, exact wait counts)
+        int c = 0;
+        for (; c + 4 <= n_chunks; c += 4) {
             step(c, stA, stD);
-            if (c + 1 < n_chunks) step(c + 1, stB, stA);
-            if (c + 2 < n_chunks) step(c + 2, stC, stB);
-            if (c + 3 < n_chunks) step(c + 3, stD, stC);
+            step(c + 1, stB, stA);
+            step(c + 2, stC, stB);
+            step(c + 3, stD, stC);
         }
+        if (c < n_chunks) step(c, stA, stD);
+        if (c + 1 < n_chunks) step(c + 1, stB, stA);
+        if (c + 2 < n_chunks) step(c + 2, stC, stB);
         // rows of the last chunk
         switch ((n_chunks - 1) & 3) {
             case 0: store_rows(n_chunks - 1, stA); break;
@@ -469,7 +485,7 @@ static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* 
     // prefetch helpers only where CUs would otherwise idle (one compute block fills a CU)
     const int n_helper = 8 * ((pl.BH + 7) / 8);
     static const bool helpers_off = getenv("NATS_NO_PREFETCH_HELPERS") != nullptr;   // A/B switch, read once
-    const bool helpers = progress != nullptr && n_compute + n_helper <= 256 && !helpers_off;
+    const bool helpers = progress != nullptr && n_compute + n_helper <= NATS_SCAN_HELPER_LIMIT && !helpers_off;
     dim3 grid(n_compute + (helpers ? n_helper : 0));
     if (O_nla_h != nullptr)
         hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, true>), grid, dim3(SCAN_THREADS_G), 0, st,
@@ -493,7 +509,7 @@ nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void*
     if (pl.d == 64)
         return launch_scan_t<64, 16>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32, O_nla_h, O,
                                      progress, st);
-    return launch_scan_t<128, 32>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
+    return launch_scan_t<128, NATS_SCAN_BV128>(pl, WF, QF, KdF, UtF, PF, gamC, S0, S_final, O_la_h, O_la_f32,
                                                O_nla_h, O, progress, st);
 }
 
