@@ -35,7 +35,13 @@ namespace nats {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int FL_THREADS = 256;
-constexpr int FL_NQ = 2;                 // 16-query MFMA columns per wavefront
+#ifndef NATS_FL_NQ
+#define NATS_FL_NQ 2
+#endif
+#ifndef NATS_FL_OCC
+#define NATS_FL_OCC 2
+#endif
+constexpr int FL_NQ = NATS_FL_NQ;        // 16-query MFMA columns per wavefront
 constexpr int FL_BM = 4 * 16 * FL_NQ;    // queries per block
 constexpr int FL_BN = 64;                // compacted keys per tile
 
@@ -75,7 +81,7 @@ __device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned
 //                compaction, so it can run beside the linear branch's preparation.
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
 template <int D, bool MERGE, bool chunk_routing>
-__global__ __launch_bounds__(FL_THREADS, 2) void flash_softmax_kernel(
+__global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,

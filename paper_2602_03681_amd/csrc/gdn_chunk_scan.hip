@@ -24,6 +24,8 @@
 // length of the dependent chain (L / C steps), not by MFMA throughput.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "mfma_util.h"
 #include "nats_common.h"
 
@@ -34,6 +36,9 @@
 
 #ifndef NATS_SCAN_BV128
 #define NATS_SCAN_BV128 32          // d_v values per block for d = 128
+#endif
+#ifndef NATS_SCAN_HELPER_PARTS
+#define NATS_SCAN_HELPER_PARTS 4    // most prefetch helpers per (batch, head)
 #endif
 #ifndef NATS_SCAN_HELPER_LIMIT
 #define NATS_SCAN_HELPER_LIMIT 256  // prefetch helpers only while compute blocks + helpers stay within the CUs
@@ -179,14 +184,19 @@ __global__ __launch_bounds__(SCAN_THREADS_G) void gdn_chunk_scan_kernel(
         // word of every 64 bytes of the chunks they will need a few steps from now, so that their
         // loads hit in L2.  It follows the published chunk counter and never blocks anyone: every
         // wait is bounded, and the compute blocks never wait for a helper.
-        const int hid = (int)blockIdx.x - n_compute;
+        // Several helpers may serve one (batch, head): helper part p of n_parts takes every n_parts-th of a
+        // wavefront's chunks.  (One CU cannot keep enough misses in flight to fetch a pair's 72 KB per step
+        // from HBM: with one helper, 3 of every 8 chunks arrived in time.)
+        const int n_helper = 8 * ((BH + 7) / 8);
+        const int hid = ((int)blockIdx.x - n_compute) % n_helper, part = ((int)blockIdx.x - n_compute) / n_helper;
+        const int n_parts = ((int)gridDim.x - n_compute) / n_helper;
         const int hbh = (hid >> 3) * 8 + (hid & 7);
         if (hbh >= BH) return;
         constexpr int AHEAD = PF_HELPER_AHEAD;       // chunks of lead over the consumer
         constexpr int SEG = 64 / (int)sizeof(half_t);
         const size_t hgc0 = (size_t)hbh * n_chunks;
         float sink = 0.f;
-        for (int c = PF_HELPER_FIRST + wave; c < n_chunks; c += SCAN_THREADS_G / 64) {
+        for (int c = PF_HELPER_FIRST + wave + part * (SCAN_THREADS_G / 64); c < n_chunks; c += n_parts * (SCAN_THREADS_G / 64)) {
             int spins = 0, done = 0;
             while (true) {
                 done = __hip_atomic_load(progress + hbh * PROG_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -486,7 +496,9 @@ static nats_status launch_scan_t(const FwdPlan& pl, const void* WF, const void* 
     const int n_helper = 8 * ((pl.BH + 7) / 8);
     static const bool helpers_off = getenv("NATS_NO_PREFETCH_HELPERS") != nullptr;   // A/B switch, read once
     const bool helpers = progress != nullptr && n_compute + n_helper <= NATS_SCAN_HELPER_LIMIT && !helpers_off;
-    dim3 grid(n_compute + (helpers ? n_helper : 0));
+    // as many helpers per (batch, head) as idle CUs allow, at most NATS_SCAN_HELPER_PARTS
+    const int n_parts = helpers ? std::min(NATS_SCAN_HELPER_PARTS, (NATS_SCAN_HELPER_LIMIT - n_compute) / n_helper) : 0;
+    dim3 grid(n_compute + n_parts * n_helper);
     if (O_nla_h != nullptr)
         hipLaunchKernelGGL((gdn_chunk_scan_kernel<D, BV, true>), grid, dim3(SCAN_THREADS_G), 0, st,
                            (const half_t*)WF, (const half_t*)QF, (const half_t*)KdF, (const half_t*)UtF,
