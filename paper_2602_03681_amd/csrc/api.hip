@@ -159,20 +159,24 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 // offsets): branch output and lse of the softmax branch, D_i, checkpoints of the state, the scratch rows of
 // the reverse sweep and the partial sums of its blocks.
 struct BwdPlan {
-    size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, total;
+    size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp, total;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
-    const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / 64;
+    const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
     size_t off = align_up(pl.off_ola, 256);   // first byte behind cnt, idx, n_s, Kc, Vc
     bp->off_onla = off;    off = align_up(off + n_tok * pl.d * 4, 256);
     bp->off_lse = off;     off = align_up(off + n_tok * 4, 256);
     bp->off_dvec = off;    off = align_up(off + n_tok * 4, 256);
     bp->off_ckpt = off;    off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
-    bp->off_scratch = off; off = align_up(off + (size_t)pl.BH * ns * 64 * 64 * pl.d * 4, 256);
+    bp->off_scratch = off; off = align_up(off + (size_t)pl.BH * pl.d * 64 * pl.d * 4, 256);   // 64 tokens of every row
     bp->off_dqp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
     bp->off_dkp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
     bp->off_dap = off;     off = align_up(off + ns * n_tok * 4, 256);
     bp->off_dbp = off;     off = align_up(off + ns * n_tok * 4, 256);
+    // partial dK, dV and column sums of the softmax branch, one per query segment and compacted key
+    bp->off_skp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
+    bp->off_svp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
+    bp->off_sgp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * 4, 256);
     bp->total = off;
 }
 
@@ -458,7 +462,9 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     }
     // rows of the softmax tokens in dK, dV (their linear share is zero) and g_nla
     ProfScope ps("softmax_bwd_dkv", stream);
-    return launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla, stream);
+    return launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
+                                  reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
+                                  reinterpret_cast<float*>(ws + bp.off_sgp), stream);
 }
 
 nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,

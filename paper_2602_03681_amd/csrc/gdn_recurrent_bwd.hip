@@ -6,16 +6,18 @@
 //     linear token:  A = dS k_t ;  dbeta_t = r . A ;  dr = b_t A ;  dv_t = dr ;
 //                    dk_t = b_t dS^T r - Sd^T dr ;  dS -= dr k_t^T          (the last two terms: delta rule only)
 //     dalpha_t = <dS, S_{t-1}> = <dS, Sd> / a_t ;  dS <- a_t dS
-// Rows of S (index d_v) never mix: four adjacent lanes own one row (a quarter of its d_k columns each): of dS
-// in registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
+// Rows of S (index d_v) never mix: 16 adjacent lanes own one row (a sixteenth of its d_k columns each; four in
+// the checkpoint kernel): of dS in registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
 // pass: it leaves one checkpoint per chunk of 64 tokens, and a block walks the chunks from the back, first
-// re-running the chunk forwards from its checkpoint and parking the 64 rows Sd in a scratch area (2 MB per
+// re-running the chunk forwards from its checkpoint and parking its rows Sd in a scratch area (0.5 MB per
 // block for d = 128, written and read once, laid out so that a wavefront's accesses are contiguous), then
 // sweeping it backwards.  dq_t, dk_t (vectors over d_k) and dalpha_t, dbeta_t add up over all rows: a block
-// (64 rows) reduces its share through LDS, in a fixed order, and writes one partial per block; a small kernel
-// adds the partials (d / 64 of them) and finishes the outputs.  No floating-point atomics.
+// (16 rows, 4 wavefronts) reduces its share in a fixed order (the 4 rows of a wavefront by recursive halving
+// over lane exchanges, the wavefronts through LDS; one barrier per token) and writes one partial per block; a small
+// kernel adds the partials (d / 16 of them) and finishes the outputs.  No floating-point atomics.
 //
-// VALU- and latency-bound (d / 64 blocks of four wavefronts per (batch, head)): this is the path for
+// VALU- and latency-bound (d / 16 blocks of four wavefronts per (batch, head): the arithmetic of a token is the
+// same however many lanes share a row, so what helps is more CUs): this is the path for
 // checking gradients and for small problems, the counterpart of the fp32 forward path.
 #include "nats_common.h"
 
@@ -26,8 +28,26 @@ constexpr int RB_THREADS = 256;   // 4 adjacent lanes share a row, each owns a q
 constexpr int RB_TT = 16;         // tokens staged per tile
 constexpr int RB_CH = 64;         // tokens between checkpoints
 
+// One step of a sum over the rows of a wavefront by recursive halving.  In the step for lane bit b a lane keeps
+// the half of its N values that its bit selects, hands the other half to its partner and adds what the partner
+// hands over: N values of one row become N / 2 values of two rows.
+template <int N>
+__device__ __forceinline__ void halve_step(float* v, int lane, int bit) {
+    const bool up = ((lane >> bit) & 1) != 0;
+#pragma unroll
+    for (int c = 0; c < N / 2; ++c) {
+        const float keep = up ? v[c + N / 2] : v[c];
+        const float send = up ? v[c] : v[c + N / 2];
+        v[c] = keep + __shfl_xor(send, 1 << bit);
+    }
+}
+
+constexpr int RBW_LPR = 16;                      // lanes per state row in the reverse sweep
+constexpr int RBW_ROWS = BWD_SWEEP_ROWS;         // state rows per block of the reverse sweep
+constexpr int RBW_THREADS = RBW_ROWS * RBW_LPR;  // 256: four wavefronts, four rows each
+
 template <typename T, int D>
-__global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
+__global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ ckpt, float* __restrict__ scratch, float* __restrict__ dq_part,
@@ -35,27 +55,29 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
     float* __restrict__ dV, float* __restrict__ dS0, int L, int BH, float la_scale, int linear_op,
     int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
-    constexpr int DP = D / 4;       // columns of a row per lane
-    constexpr int DPP = DP + 4;     // padded quarter stride: the four quarters land in different banks
-    constexpr int RSTR = D + 1;     // row stride of the reduction tile: rows and columns both hit distinct banks
-    __shared__ __align__(16) float s_k[RB_TT][4 * DPP];
-    __shared__ __align__(16) float s_q[RB_TT][4 * DPP];
-    __shared__ float s_v[RB_TT][RB_ROWS], s_do[RB_TT][RB_ROWS];
+    constexpr int LPR = RBW_LPR, NW = RBW_THREADS / 64;
+    constexpr int DP = D / LPR;     // columns of a row per lane
+    constexpr int KQ = 2 * DP + 4;  // a lane's columns of k, then of q, then padding: the 16 lanes of a row read
+                                    // their 16-byte pieces from different banks
+    constexpr int NF = DP / 4;      // values of a lane that are left after the sum over its wavefront's 4 rows
+    static_assert(DP % 4 == 0, "16-byte pieces and two halving steps");
+    __shared__ __align__(16) float s_kq[RB_TT][LPR * KQ];
+    __shared__ float s_v[RB_TT][RBW_ROWS], s_do[RB_TT][RBW_ROWS];
     __shared__ float s_a[RB_TT], s_b[RB_TT];
     __shared__ uint8_t s_dec[RB_TT];           // 1: the decay acts at this token
     __shared__ uint8_t s_lin[RB_TT];           // 1: linear token (the state is written)
-    __shared__ float s_red[RB_ROWS * RSTR];
-    __shared__ float s_sc[2][RB_THREADS / 64];
+    __shared__ float s_part[2][2][NW][D];      // [token parity][dq, dk][wavefront][column]
+    __shared__ float s_sc[2][2][NW];           // [token parity][dalpha, dbeta][wavefront]
 
     const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
-    const int r = tid >> 2, part = tid & 3, lane = tid & 63, wave = tid >> 6;
-    const int row = slice * RB_ROWS + r;
+    const int r = tid / LPR, part = tid % LPR, lane = tid & 63, wave = tid >> 6;
+    const int row = slice * RBW_ROWS + r;
     const size_t base = (size_t)bh * L;
     const int n_chunks = L / RB_CH;
     const size_t n_tok = (size_t)BH * L;
-    // this block's scratch: [token of the chunk][group of 4 columns inside a quarter][row][quarter][4], so that
-    // the threads of the block, in order, touch consecutive 16 bytes
-    float* my_scr = scratch + ((size_t)bh * gridDim.x + slice) * (size_t)(RB_CH * D * RB_ROWS);
+    // this block's scratch: [token of the chunk][group of 4 columns of a lane][thread][4], so that the threads of
+    // the block, in order, touch consecutive 16 bytes
+    float* my_scr = scratch + ((size_t)bh * gridDim.x + slice) * (size_t)(RB_CH * D * RBW_ROWS);
     float* dq_p = dq_part + (size_t)slice * n_tok * D;
     float* dk_p = dk_part + (size_t)slice * n_tok * D;
     float* da_p = dalpha_part + (size_t)slice * n_tok;
@@ -64,27 +86,26 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
     // stages tokens [t0, t0 + RB_TT): k, v and the gates always, q and do for the backward sweep
     auto stage = [&](int t0, bool with_q) {
         __syncthreads();
-        for (int e = tid * EPL; e < RB_TT * D; e += RB_THREADS * EPL) {
+        for (int e = tid * EPL; e < RB_TT * D; e += RBW_THREADS * EPL) {
             const int i = e / D, c = e % D;
-            const int pq = c / DP, pc = c % DP;   // EPL divides DP: a 16-byte group stays inside one quarter
             float tmp[EPL];
             Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) s_k[i][pq * DPP + pc + j] = tmp[j];
+            for (int j = 0; j < EPL; ++j) s_kq[i][((c + j) / DP) * KQ + (c + j) % DP] = tmp[j];
             if (with_q) {
                 Vec16<T>::load(Q + (base + t0 + i) * D + c, tmp);
 #pragma unroll
-                for (int j = 0; j < EPL; ++j) s_q[i][pq * DPP + pc + j] = tmp[j];
+                for (int j = 0; j < EPL; ++j) s_kq[i][((c + j) / DP) * KQ + DP + (c + j) % DP] = tmp[j];
             }
         }
-        for (int e = tid * EPL; e < RB_TT * RB_ROWS; e += RB_THREADS * EPL) {
-            const int i = e / RB_ROWS, c = e % RB_ROWS;
+        for (int e = tid * EPL; e < RB_TT * RBW_ROWS; e += RBW_THREADS * EPL) {
+            const int i = e / RBW_ROWS, c = e % RBW_ROWS;
             float tmp[EPL];
-            Vec16<T>::load(V + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+            Vec16<T>::load(V + (base + t0 + i) * D + slice * RBW_ROWS + c, tmp);
 #pragma unroll
             for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
             if (with_q) {
-                Vec16<T>::load(dO + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+                Vec16<T>::load(dO + (base + t0 + i) * D + slice * RBW_ROWS + c, tmp);
 #pragma unroll
                 for (int j = 0; j < EPL; ++j) s_do[i][c + j] = tmp[j];
             }
@@ -99,16 +120,9 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
         }
         __syncthreads();
     };
-    auto row_sum = [](float x) { x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); return x; };   // over a row's 4 lanes
-    // column sums of the reduction tile (rows in a fixed order) into dst[c], c = 0..D-1
-    auto reduce_tile = [&](float* dst) {
-        __syncthreads();
-        for (int c = tid; c < D; c += RB_THREADS) {
-            float sum = 0.f;
-            for (int rr = 0; rr < RB_ROWS; ++rr) sum += s_red[rr * RSTR + c];
-            dst[c] = sum;
-        }
-        __syncthreads();
+    auto row_sum = [](float x) {   // over a row's 16 lanes
+        x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); x += __shfl_xor(x, 4); x += __shfl_xor(x, 8);
+        return x;
     };
 
     float dS[DP];
@@ -126,18 +140,20 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
                 const float4 x = *reinterpret_cast<const float4*>(src + c);
                 S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
             }
+#pragma unroll 1
             for (int tt = 0; tt < RB_CH; tt += RB_TT) {
                 stage(tc0 + tt, false);
+#pragma unroll 1
                 for (int i = 0; i < RB_TT; ++i) {
                     const float a = s_a[i], b = s_b[i];
-                    const float* kr = &s_k[i][part * DPP];
-                    float* dst = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;
+                    const float* kr = &s_kq[i][part * KQ];
+                    float* dst = my_scr + (size_t)(tt + i) * (D * RBW_ROWS) + tid * 4;
                     float pred = 0.f;
 #pragma unroll
                     for (int c = 0; c < DP; c += 4) {
                         const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
                         S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
-                        *reinterpret_cast<float4*>(dst + (c / 4) * (RB_THREADS * 4)) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+                        *reinterpret_cast<float4*>(dst + (c / 4) * (RBW_THREADS * 4)) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
                         pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
                     }
                     if (s_lin[i]) {   // uniform across the block
@@ -153,38 +169,55 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
             }
         }
         // ---- backwards through the chunk ------------------------------------------------------------
+        // The parked rows come back one token ahead of use: read at the token that needs them, their latency
+        // (a trip to L2 or further) would be paid 64 times per chunk.
+        float Sn[DP];
+        auto fetch_rows = [&](int tok) {   // this thread's own stores of token tok of the chunk
+            const float* src = my_scr + (size_t)tok * (D * RBW_ROWS) + tid * 4;
+#pragma unroll
+            for (int c = 0; c < DP; c += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RBW_THREADS * 4));
+                Sn[c] = x.x; Sn[c + 1] = x.y; Sn[c + 2] = x.z; Sn[c + 3] = x.w;
+            }
+        };
+        fetch_rows(RB_CH - 1);
+#pragma unroll 1
         for (int tt = RB_CH - RB_TT; tt >= 0; tt -= RB_TT) {
             stage(tc0 + tt, true);
+#pragma unroll 1
             for (int i = RB_TT - 1; i >= 0; --i) {
                 const int t = tc0 + tt + i;
                 const float a = s_a[i], b = s_b[i], go = la_scale * s_do[i][r];
                 const bool lin = s_lin[i] != 0;   // uniform across the block
-                const float* kr = &s_k[i][part * DPP];
-                const float* qr = &s_q[i][part * DPP];
-                const float* src = my_scr + (size_t)(tt + i) * (D * RB_ROWS) + tid * 4;   // this thread's own stores
-                float Sd[DP];
-                float pred = 0.f;
+                const float* kr = &s_kq[i][part * KQ];
+                const float* qr = kr + DP;
+                float Sd[DP], kk[DP], qq[DP];
 #pragma unroll
                 for (int c = 0; c < DP; c += 4) {
-                    const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RB_THREADS * 4));
                     const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
-                    Sd[c] = x.x; Sd[c + 1] = x.y; Sd[c + 2] = x.z; Sd[c + 3] = x.w;
-                    pred += x.x * k4.x + x.y * k4.y + x.z * k4.z + x.w * k4.w;
+                    const float4 q4 = *reinterpret_cast<const float4*>(qr + c);
+                    kk[c] = k4.x; kk[c + 1] = k4.y; kk[c + 2] = k4.z; kk[c + 3] = k4.w;
+                    qq[c] = q4.x; qq[c + 1] = q4.y; qq[c + 2] = q4.z; qq[c + 3] = q4.w;
                 }
+#pragma unroll
+                for (int c = 0; c < DP; ++c) Sd[c] = Sn[c];
+                if (tt + i > 0) fetch_rows(tt + i - 1);
+                float pred = 0.f;
+#pragma unroll
+                for (int c = 0; c < DP; ++c) pred += Sd[c] * kk[c];
                 pred = row_sum(pred);
                 const float rv = lin ? s_v[i][r] - (linear_op == 0 ? pred : 0.f) : 0.f;
                 // dq_t: this row's share la_scale do S_t, S_t = Sd + b r k;   dS += la_scale do q^T;   A = dS k
                 float A = 0.f;
                 const float br = b * rv;
+                float xq[DP], xk[DP];
 #pragma unroll
                 for (int c = 0; c < DP; ++c) {
-                    const float kc = kr[c];
-                    s_red[r * RSTR + part * DP + c] = go * (Sd[c] + br * kc);
-                    dS[c] += go * qr[c];
-                    A += dS[c] * kc;
+                    xq[c] = go * (Sd[c] + br * kk[c]);
+                    dS[c] += go * qq[c];
+                    A += dS[c] * kk[c];
                 }
                 A = row_sum(A);
-                reduce_tile(dq_p + (base + t) * D);
                 float dbeta_p = 0.f, dr = 0.f;
                 if (lin) {
                     dbeta_p = rv * A;
@@ -192,14 +225,13 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
                     const float drd = linear_op == 0 ? dr : 0.f;
 #pragma unroll
                     for (int c = 0; c < DP; ++c) {
-                        s_red[r * RSTR + part * DP + c] = br * dS[c] - drd * Sd[c];
-                        dS[c] -= drd * kr[c];
+                        xk[c] = br * dS[c] - drd * Sd[c];
+                        dS[c] -= drd * kk[c];
                     }
                 } else {
 #pragma unroll
-                    for (int c = 0; c < DP; ++c) s_red[r * RSTR + part * DP + c] = 0.f;
+                    for (int c = 0; c < DP; ++c) xk[c] = 0.f;
                 }
-                reduce_tile(dk_p + (base + t) * D);
                 if (part == 0) dV[(base + t) * D + row] = dr;
                 float dalpha_p = 0.f;
                 if (s_dec[i]) {   // uniform
@@ -207,16 +239,36 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_recurrent_bwd_kernel(
                     for (int c = 0; c < DP; ++c) { dalpha_p += dS[c] * Sd[c]; dS[c] *= a; }
                     dalpha_p = row_sum(dalpha_p) / fmaxf(a, 1e-30f);   // S_{t-1} = Sd / a
                 }
+                // sums over the rows of the block: the 4 rows of a wavefront (lane bits 4, 5) by recursive
+                // halving, which leaves a lane with NF columns: the halves its row bits selected ...
+                halve_step<DP>(xq, lane, 4);     halve_step<DP>(xk, lane, 4);
+                halve_step<DP / 2>(xq, lane, 5); halve_step<DP / 2>(xk, lane, 5);
+                const int col = part * DP + (DP / 2) * ((lane >> 4) & 1) + (DP / 4) * ((lane >> 5) & 1);
+                const int buf = t & 1;
+#pragma unroll
+                for (int j = 0; j < NF; ++j) {
+                    s_part[buf][0][wave][col + j] = xq[j];
+                    s_part[buf][1][wave][col + j] = xk[j];
+                }
                 // the two scalars: one value per row (its lane 0), rows of a wavefront, then the wavefronts in order
                 float xa = part == 0 ? dalpha_p : 0.f, xb = part == 0 ? dbeta_p : 0.f;
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) { xa += __shfl_xor(xa, off); xb += __shfl_xor(xb, off); }
-                if (lane == 0) { s_sc[0][wave] = xa; s_sc[1][wave] = xb; }
+                if (lane == 0) { s_sc[buf][0][wave] = xa; s_sc[buf][1][wave] = xb; }
+                // ... then the wavefronts, in order.  One barrier per token: the next token writes the other half
+                // of the buffers, and the barrier after it separates these reads from the writes that follow.
                 __syncthreads();
-                if (tid == 0) {
+                if (tid < 2 * D) {
+                    const int which = tid / D, c = tid % D;
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) sum += s_part[buf][which][w][c];
+                    (which == 0 ? dq_p : dk_p)[(base + t) * D + c] = sum;
+                }
+                if (tid == RBW_THREADS - 1) {
                     float sa = 0.f, sb = 0.f;
 #pragma unroll
-                    for (int w = 0; w < RB_THREADS / 64; ++w) { sa += s_sc[0][w]; sb += s_sc[1][w]; }
+                    for (int w = 0; w < NW; ++w) { sa += s_sc[buf][0][w]; sb += s_sc[buf][1][w]; }
                     da_p[base + t] = sa;
                     db_p[base + t] = sb;
                 }
@@ -320,7 +372,7 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(
     const float* __restrict__ dq_part, const float* __restrict__ dk_part, const float* __restrict__ dalpha_part,
     const float* __restrict__ dbeta_part, float* __restrict__ dQ, float* __restrict__ dK,
     float* __restrict__ dalpha, float* __restrict__ dbeta, float* __restrict__ g_nla, size_t n_tok) {
-    constexpr int NS = D / RB_ROWS;
+    constexpr int NS = D / RBW_ROWS;
     const size_t n4 = n_tok * D / 4;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256) {
         float4 q = reinterpret_cast<const float4*>(dQ)[e];
@@ -349,19 +401,19 @@ template <typename T>
 static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO, const float* alpha,
                       const float* beta, const uint8_t* mask, const float* ckpt, float* scratch, float* dq_part,
                       float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
-    dim3 grid(pl.d / RB_ROWS, pl.BH);
+    dim3 grid(pl.d / RBW_ROWS, pl.BH);
     if (pl.d == 64)
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RB_THREADS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RBW_THREADS), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
     else
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RB_THREADS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RBW_THREADS), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
 }
 
-// scratch: BH * (d / 64) * 64 * d * 64 floats;  dq_part, dk_part: (d / 64) * BH * L * d floats;
-// dalpha_part, dbeta_part: (d / 64) * BH * L floats;  dV [B,H,L,d] f32 is written for every token
+// scratch: BH * d * d * 64 floats;  dq_part, dk_part: (d / 16) * BH * L * d floats;
+// dalpha_part, dbeta_part: (d / 16) * BH * L floats;  dV [B,H,L,d] f32 is written for every token
 nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                      const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
                                      float* scratch, float* dq_part, float* dk_part, float* dalpha_part,

@@ -106,6 +106,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ints between the chunk-progress counters of two (batch, head) pairs: one 256-byte line each, so
 // that polling one counter never touches the line another block stores to
 constexpr int PROG_STRIDE = 64;
+constexpr int BWD_DKV_SEGMENTS = 8;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
+constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse sweep: d / 16 blocks and partial sums per (batch, head)
 
 struct FwdPlan {
     int B, H, L, d, C, BH;
@@ -171,7 +173,8 @@ nats_status launch_softmax_bwd_dq(const FwdPlan& pl, const void* Q, const void* 
                                   hipStream_t st);
 nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                                    const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* lse,
-                                   const float* Dvec, float* dK, float* dV, float* g_nla, hipStream_t st);
+                                   const float* Dvec, float* dK, float* dV, float* g_nla, float* dk_part, float* dv_part, float* g_part,
+                                   hipStream_t st);
 nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                      const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
                                      float* scratch, float* dq_part, float* dk_part, float* dalpha_part,

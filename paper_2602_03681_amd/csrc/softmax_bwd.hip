@@ -106,8 +106,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc, const T* __restrict__ dO,
     const int32_t* __restrict__ cnt, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_s,
-    const float* __restrict__ lse, const float* __restrict__ Dvec, float* __restrict__ dK,
-    float* __restrict__ dV, float* __restrict__ g_nla, int L, float scale) {
+    const float* __restrict__ lse, const float* __restrict__ Dvec, float* __restrict__ dk_part,
+    float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale) {
     constexpr int DP = D / 4, DPP = DP + 4, EPL = Vec16<T>::N;
     __shared__ __align__(16) float s_q[SB_TILE][4 * DPP];
     __shared__ __align__(16) float s_do[SB_TILE][4 * DPP];
@@ -128,8 +128,14 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
     for (int e = 0; e < DP; ++e) { k[e] *= scale; dk[e] = 0.f; dv[e] = 0.f; }
     float g = 0.f;
 
-    const int i_first = idx[tokb + c0] & ~(SB_TILE - 1);   // tile of the first query that sees the tile's first key
-    for (int i0 = i_first; i0 < L; i0 += SB_TILE) {
+    // The queries that see the tile's first key, in tiles; the blocks of the tile (blockIdx.z) take equal shares
+    // of them: the first key tile of a head is seen by every query, and one block walking all of them was the
+    // whole kernel's run time.
+    const int i_first = idx[tokb + c0] & ~(SB_TILE - 1);
+    const int n_tiles = (L - i_first) / SB_TILE, seg = blockIdx.z, n_seg = gridDim.z;
+    const int i_lo = i_first + (int)((long long)n_tiles * seg / n_seg) * SB_TILE;
+    const int i_hi = i_first + (int)((long long)n_tiles * (seg + 1) / n_seg) * SB_TILE;
+    for (int i0 = i_lo; i0 < i_hi; i0 += SB_TILE) {
         __syncthreads();
         for (int e = tid * EPL; e < SB_TILE * D; e += SB_THREADS * EPL) {
             const int i = e / D, col = e % D;
@@ -173,24 +179,49 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
             }
         }
     }
-    if (valid) {   // back to the token the row was gathered from (its linear-branch gradient is zero)
-        const int pos = idx[tokb + c];
-        const size_t dst = (tokb + pos) * D + part * DP;
+    if (valid) {   // this segment's share, by compacted key; a second kernel adds the shares up in order
+        const size_t row = ((size_t)seg * gridDim.y + bh) * L + c;
 #pragma unroll
         for (int e = 0; e < DP; e += 4) {
-            *reinterpret_cast<float4*>(dK + dst + e) =
-                make_float4(scale * dk[e], scale * dk[e + 1], scale * dk[e + 2], scale * dk[e + 3]);
-            *reinterpret_cast<float4*>(dV + dst + e) = make_float4(dv[e], dv[e + 1], dv[e + 2], dv[e + 3]);
+            *reinterpret_cast<float4*>(dk_part + row * D + part * DP + e) = make_float4(dk[e], dk[e + 1], dk[e + 2], dk[e + 3]);
+            *reinterpret_cast<float4*>(dv_part + row * D + part * DP + e) = make_float4(dv[e], dv[e + 1], dv[e + 2], dv[e + 3]);
         }
-        if (part == 0 && g_nla != nullptr) g_nla[tokb + pos] = g;
+        if (part == 0) g_part[row] = g;
     }
+}
+
+// Adds the segments' shares of a compacted key up, in order, and writes the rows of dK, dV (and g_nla) of the
+// token the key was gathered from (its linear-branch gradient is zero).  One thread per key and 4 columns.
+template <int D>
+__global__ __launch_bounds__(256) void softmax_bwd_dkv_combine_kernel(
+    const float* __restrict__ dk_part, const float* __restrict__ dv_part, const float* __restrict__ g_part,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ n_s, float* __restrict__ dK, float* __restrict__ dV,
+    float* __restrict__ g_nla, int L, int n_seg, float scale) {
+    constexpr int TPK = D / 4;                 // threads per key
+    const int bh = blockIdx.y, c = blockIdx.x * (256 / TPK) + threadIdx.x / TPK, col = (threadIdx.x % TPK) * 4;
+    if (c >= n_s[bh]) return;
+    const size_t tokb = (size_t)bh * L;
+    float4 k = make_float4(0.f, 0.f, 0.f, 0.f), v = k;
+    float g = 0.f;
+    for (int s = 0; s < n_seg; ++s) {
+        const size_t row = ((size_t)s * gridDim.y + bh) * L + c;
+        const float4 a = *reinterpret_cast<const float4*>(dk_part + row * D + col);
+        const float4 b = *reinterpret_cast<const float4*>(dv_part + row * D + col);
+        k.x += a.x; k.y += a.y; k.z += a.z; k.w += a.w;
+        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+        g += g_part[row];
+    }
+    const size_t dst = (tokb + idx[tokb + c]) * D + col;
+    *reinterpret_cast<float4*>(dK + dst) = make_float4(scale * k.x, scale * k.y, scale * k.z, scale * k.w);
+    *reinterpret_cast<float4*>(dV + dst) = v;
+    if (col == 0 && g_nla != nullptr) g_nla[tokb + idx[tokb + c]] = g;
 }
 
 template <typename T>
 static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                       const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* O_nla, const float* lse,
                       float* Dvec, float* dQ, float* dK, float* dV, float* g_nla, bool dkv, hipStream_t st) {
-    dim3 grid(pl.L / SB_ROWS, pl.BH);
+    dim3 grid(pl.L / SB_ROWS, pl.BH, dkv ? BWD_DKV_SEGMENTS : 1);
 #define NATS_SB_LAUNCH(DD)                                                                                          \
     if (!dkv)                                                                                                        \
         hipLaunchKernelGGL((softmax_bwd_dq_kernel<T, DD>), grid, dim3(SB_THREADS), 0, st, (const T*)Q, (const T*)Kc, \
@@ -215,15 +246,30 @@ nats_status launch_softmax_bwd_dq(const FwdPlan& pl, const void* Q, const void* 
     return check_launch("softmax_bwd_dq");
 }
 
-// the rows idx[c] of dK, dV [B,H,L,d] f32 (and of g_nla [B,H,L], optional) are overwritten; other rows are left alone
+// the rows idx[c] of dK, dV [B,H,L,d] f32 (and of g_nla [B,H,L], optional) are overwritten; other rows are left alone.
+// dk_part, dv_part: BWD_DKV_SEGMENTS * BH * L * d floats, g_part: BWD_DKV_SEGMENTS * BH * L floats (scratch)
 nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                                    const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* lse,
-                                   const float* Dvec, float* dK, float* dV, float* g_nla, hipStream_t st) {
+                                   const float* Dvec, float* dK, float* dV, float* g_nla, float* dk_part, float* dv_part,
+                                   float* g_part, hipStream_t st) {
     if (pl.dtype == NATS_BF16)
-        launch_sb<bf16_t>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dK, dV, g_nla, true, st);
+        launch_sb<bf16_t>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dk_part, dv_part,
+                          g_part, true, st);
     else
-        launch_sb<float>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dK, dV, g_nla, true, st);
-    return check_launch("softmax_bwd_dkv");
+        launch_sb<float>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dk_part, dv_part,
+                         g_part, true, st);
+    nats_status rc = check_launch("softmax_bwd_dkv");
+    if (rc != NATS_OK) return rc;
+    if (pl.d == 64) {
+        dim3 grid((pl.L + 15) / 16, pl.BH);   // 256 / (64 / 4) keys per block
+        hipLaunchKernelGGL((softmax_bwd_dkv_combine_kernel<64>), grid, dim3(256), 0, st, dk_part, dv_part, g_part, idx, n_s,
+                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale);
+    } else {
+        dim3 grid((pl.L + 7) / 8, pl.BH);     // 256 / (128 / 4) keys per block
+        hipLaunchKernelGGL((softmax_bwd_dkv_combine_kernel<128>), grid, dim3(256), 0, st, dk_part, dv_part, g_part, idx, n_s,
+                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale);
+    }
+    return check_launch("softmax_bwd_dkv_combine");
 }
 
 }  // namespace nats
