@@ -6,8 +6,8 @@
 //     linear token:  A = dS k_t ;  dbeta_t = r . A ;  dr = b_t A ;  dv_t = dr ;
 //                    dk_t = b_t dS^T r - Sd^T dr ;  dS -= dr k_t^T          (the last two terms: delta rule only)
 //     dalpha_t = <dS, S_{t-1}> = <dS, Sd> / a_t ;  dS <- a_t dS
-// Rows of S (index d_v) never mix: 16 adjacent lanes own one row (a sixteenth of its d_k columns each; four in
-// the checkpoint kernel): of dS in registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
+// Rows of S (index d_v) never mix: 16 adjacent lanes own one row (a sixteenth of its d_k columns each): of dS
+// in registers across the whole sweep, and of Sd for the token at hand.  The states are not kept by the forward
 // pass: it leaves one checkpoint per chunk of 64 tokens, and a block walks the chunks from the back, first
 // re-running the chunk forwards from its checkpoint and parking its rows Sd in a scratch area (0.5 MB per
 // block for d = 128, written and read once, laid out so that a wavefront's accesses are contiguous), then
@@ -23,8 +23,6 @@
 
 namespace nats {
 
-constexpr int RB_ROWS = 64;       // state rows per block
-constexpr int RB_THREADS = 256;   // 4 adjacent lanes share a row, each owns a quarter of its d_k columns
 constexpr int RB_TT = 16;         // tokens staged per tile
 constexpr int RB_CH = 64;         // tokens between checkpoints
 
@@ -283,22 +281,23 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
 }
 
 // The forward recurrence once more, only to leave the checkpoints the reverse sweep starts from: the row of the
-// state before every chunk of 64 tokens, ckpt[bh][chunk][row][d_k].  Same thread layout as the kernel above.
+// state before every chunk of 64 tokens, ckpt[bh][chunk][row][d_k].  Same thread layout as the kernel above
+// (16 rows per block, 16 lanes per row).
 template <typename T, int D>
-__global__ __launch_bounds__(RB_THREADS) void gdn_checkpoint_kernel(
+__global__ __launch_bounds__(RBW_THREADS) void gdn_checkpoint_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ S0, float* __restrict__ ckpt, int L, int linear_op,
     int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
-    constexpr int DP = D / 4, DPP = DP + 4;
+    constexpr int LPR = RBW_LPR, DP = D / LPR, DPP = DP + 4;
     constexpr int TT = 32;
-    __shared__ __align__(16) float s_k[TT][4 * DPP];
-    __shared__ float s_v[TT][RB_ROWS];
+    __shared__ __align__(16) float s_k[TT][LPR * DPP];
+    __shared__ float s_v[TT][RBW_ROWS];
     __shared__ float s_a[TT], s_b[TT];
     __shared__ uint8_t s_lin[TT];
     const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
-    const int r = tid >> 2, part = tid & 3;
-    const int row = slice * RB_ROWS + r;
+    const int r = tid / LPR, part = tid % LPR;
+    const int row = slice * RBW_ROWS + r;
     const size_t base = (size_t)bh * L;
     const int n_chunks = L / RB_CH;
     float S[DP];
@@ -315,17 +314,17 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_checkpoint_kernel(
     }
     for (int t0 = 0; t0 < L; t0 += TT) {
         __syncthreads();
-        for (int e = tid * EPL; e < TT * D; e += RB_THREADS * EPL) {
+        for (int e = tid * EPL; e < TT * D; e += RBW_THREADS * EPL) {
             const int i = e / D, c = e % D;
             float tmp[EPL];
             Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) s_k[i][(c / DP) * DPP + c % DP + j] = tmp[j];
+            for (int j = 0; j < EPL; ++j) s_k[i][((c + j) / DP) * DPP + (c + j) % DP] = tmp[j];
         }
-        for (int e = tid * EPL; e < TT * RB_ROWS; e += RB_THREADS * EPL) {
-            const int i = e / RB_ROWS, c = e % RB_ROWS;
+        for (int e = tid * EPL; e < TT * RBW_ROWS; e += RBW_THREADS * EPL) {
+            const int i = e / RBW_ROWS, c = e % RBW_ROWS;
             float tmp[EPL];
-            Vec16<T>::load(V + (base + t0 + i) * D + slice * RB_ROWS + c, tmp);
+            Vec16<T>::load(V + (base + t0 + i) * D + slice * RBW_ROWS + c, tmp);
 #pragma unroll
             for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
         }
@@ -336,6 +335,7 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_checkpoint_kernel(
             s_b[tid] = soft ? 0.f : beta[base + t0 + tid];
         }
         __syncthreads();
+#pragma unroll 1
         for (int i = 0; i < TT; ++i) {
             if (((t0 + i) & (RB_CH - 1)) == 0) {
                 float* dst = ckpt + (((size_t)bh * n_chunks + (t0 + i) / RB_CH) * D + row) * D + part * DP;
@@ -344,22 +344,23 @@ __global__ __launch_bounds__(RB_THREADS) void gdn_checkpoint_kernel(
             }
             const float a = s_a[i];
             const float* kr = &s_k[i][part * DPP];
+            float kk[DP];
             float pred = 0.f;
 #pragma unroll
             for (int c = 0; c < DP; c += 4) {
                 const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
-                S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
-                pred += S[c] * k4.x + S[c + 1] * k4.y + S[c + 2] * k4.z + S[c + 3] * k4.w;
+                kk[c] = k4.x; kk[c + 1] = k4.y; kk[c + 2] = k4.z; kk[c + 3] = k4.w;
             }
+#pragma unroll
+            for (int c = 0; c < DP; ++c) { S[c] *= a; pred += S[c] * kk[c]; }
             if (s_lin[i]) {   // uniform across the block
                 pred += __shfl_xor(pred, 1);
                 pred += __shfl_xor(pred, 2);
+                pred += __shfl_xor(pred, 4);
+                pred += __shfl_xor(pred, 8);
                 const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
-                for (int c = 0; c < DP; c += 4) {
-                    const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
-                    S[c] += delta * k4.x; S[c + 1] += delta * k4.y; S[c + 2] += delta * k4.z; S[c + 3] += delta * k4.w;
-                }
+                for (int c = 0; c < DP; ++c) S[c] += delta * kk[c];
             }
         }
     }
@@ -430,9 +431,9 @@ nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const voi
 // ckpt [BH][L/64][d][d] f32: the state before every chunk of 64 tokens (S0 may be NULL: zero)
 nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st) {
-    dim3 grid(pl.d / RB_ROWS, pl.BH);
+    dim3 grid(pl.d / RBW_ROWS, pl.BH);
 #define NATS_CK_LAUNCH(TT, DD)                                                                                        \
-    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(RB_THREADS), 0, st, (const TT*)K, (const TT*)V, alpha, \
+    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(RBW_THREADS), 0, st, (const TT*)K, (const TT*)V, alpha, \
                        beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax)
     if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_CK_LAUNCH(bf16_t, 64); else NATS_CK_LAUNCH(bf16_t, 128); }
     else { if (pl.d == 64) NATS_CK_LAUNCH(float, 64); else NATS_CK_LAUNCH(float, 128); }
