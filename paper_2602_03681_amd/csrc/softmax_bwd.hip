@@ -13,8 +13,11 @@
 //   softmax_bwd_dkv: a block owns 64 compacted keys and walks the queries from the first one that can
 //                    see its first key to the end of the sequence
 // Nothing is accumulated across blocks: results are deterministic.
+// For bf16 tensors the second kernel has a form on MFMA (below): its products run on the matrix cores with
+// operands that are exact (the bf16 inputs) or split into two fp16 terms (P and dS), so that it meets the same bar.
 #include <math.h>
 
+#include "mfma_util.h"
 #include "nats_common.h"
 
 namespace nats {
@@ -217,6 +220,177 @@ __global__ __launch_bounds__(256) void softmax_bwd_dkv_combine_kernel(
     if (col == 0 && g_nla != nullptr) g_nla[tokb + idx[tokb + c]] = g;
 }
 
+// ---- dKc, dVc, g on MFMA, bf16 tensors ---------------------------------------------------------------------
+// A block owns 64 compacted keys, wavefront w the 16 keys of tile w, and walks the queries that can see them
+// in tiles of 64 (its share of them: blockIdx.z).  Per query tile, with everything a wavefront needs of P and dS
+// staying in its own registers:
+//   S [q][key] = Q K^T,  dP[q][key] = dO V^T     bf16 MFMA, inputs exact; A = the Q / dO tile (LDS, row-major),
+//                                                 B = the wavefront's K / V rows, held in registers
+//   P = exp(scale S - lse_q) under the column mask,  dS = P (dP - D_q),  g += column sums of dS      (fp32)
+//   dV^T[d][key] += dO^T P,  dK^T[d][key] += Q^T dS   fp16 MFMA; B = P / dS straight from the accumulators: a
+//       result tile gives a lane 4 consecutive queries of one key, and two tiles fill the 8 contraction slots of
+//       a lane; A = the transposed dO / Q tile (LDS, fp16, columns stored in that slot order).  P and dS enter
+//       as hi + lo, two fp16 terms each (two products): their rounding then costs 2^-22, not 2^-11.
+constexpr int SBM_QT = 64;       // queries per tile
+
+__device__ __forceinline__ f32x4 sbm_mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
+    typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+}
+
+// column of query q (0..63) in the transposed tiles: the 8 queries {16 (2 mp) + 4 lq + j, 16 (2 mp + 1) + 4 lq + j},
+// j < 4, are the contraction slots of lane quarter lq in step mp, and sit side by side
+__device__ __forceinline__ int sbm_col(int q) {
+    const int mt = q >> 4, lq = (q >> 2) & 3, j = q & 3;
+    return (mt >> 1) * 32 + lq * 8 + (mt & 1) * 4 + j;
+}
+// element (d, col) of a transposed tile [D][TS]: the 8-column groups are xor-swizzled with d / 8, so that the 2-byte
+// writes of lanes that hold different d of one query spread over the banks
+__device__ __forceinline__ int sbm_at(int d, int col, int TS) {
+    return d * TS + ((((col >> 3) ^ (d >> 3)) & 7) << 3) + (col & 7);
+}
+
+template <int D>
+constexpr int sbm_lds_bytes() { return 2 * SBM_QT * (D + LDS_PAD) * 2 + 2 * D * (SBM_QT + LDS_PAD) * 2 + 3 * SBM_QT * 4; }
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc,
+    const bf16_t* __restrict__ dO, const int32_t* __restrict__ cnt, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ n_s, const float* __restrict__ lse, const float* __restrict__ Dvec,
+    float* __restrict__ dk_part, float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale) {
+    constexpr int RS = D + LDS_PAD, TS = SBM_QT + LDS_PAD;
+    constexpr int KS_D = D / 32, MD = D / 16, NPC = SBM_QT * D / 8 / 256;
+    extern __shared__ __align__(16) unsigned char sbm_smem[];
+    uint16_t* Qs = reinterpret_cast<uint16_t*>(sbm_smem);                    // bf16, row-major [64][RS]
+    uint16_t* dOs = Qs + SBM_QT * RS;
+    half_t* QT = reinterpret_cast<half_t*>(dOs + SBM_QT * RS);                // fp16, transposed [D][TS]
+    half_t* dOT = QT + D * TS;
+    float* s_lse2 = reinterpret_cast<float*>(dOT + D * TS);
+    float* s_D = s_lse2 + SBM_QT;
+    int* s_cnt = reinterpret_cast<int*>(s_D + SBM_QT);
+
+    const int bh = blockIdx.y, c0 = blockIdx.x * 64, tid = threadIdx.x;
+    const int n_keys = n_s[bh];
+    if (c0 >= n_keys) return;                          // uniform: this tile holds no key
+    const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    const int c = c0 + 16 * wave + l16;                // this lane's key
+    const bool valid = c < n_keys;
+    const size_t tokb = (size_t)bh * L;
+    const float LOG2E = 1.44269504088896341f;
+    const float scale2 = scale * LOG2E;
+
+    // the wavefront's rows of Kc and Vc as B operands (row of an invalid key: the tile's first, masked below)
+    u32x4 kf[KS_D], vf[KS_D];
+    {
+        const size_t row = (tokb + (valid ? c : c0)) * D + 8 * lq;
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            kf[ks] = *reinterpret_cast<const u32x4*>(Kc + row + 32 * ks);
+            vf[ks] = *reinterpret_cast<const u32x4*>(Vc + row + 32 * ks);
+        }
+    }
+    f32x4 accK[MD], accV[MD];
+#pragma unroll
+    for (int md = 0; md < MD; ++md) { accK[md] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[md] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    float g = 0.f;
+
+    // the queries that see the tile's first key, in tiles; the blocks of the tile take equal shares of them
+    const int i_first = idx[tokb + c0] & ~(SBM_QT - 1);
+    const int n_tiles = (L - i_first) / SBM_QT, seg = blockIdx.z, n_seg = gridDim.z;
+    const int i_lo = i_first + (int)((long long)n_tiles * seg / n_seg) * SBM_QT;
+    const int i_hi = i_first + (int)((long long)n_tiles * (seg + 1) / n_seg) * SBM_QT;
+#pragma unroll 1
+    for (int i0 = i_lo; i0 < i_hi; i0 += SBM_QT) {
+        __syncthreads();   // the previous tile has been read by everyone
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            const int e = tid + 256 * i, q = e / (D / 8), c8 = e % (D / 8);
+            const size_t src = (tokb + i0 + q) * D + 8 * c8;     // L is a multiple of the tile
+            const u32x4 rq = *reinterpret_cast<const u32x4*>(Q + src);
+            const u32x4 rd = *reinterpret_cast<const u32x4*>(dO + src);
+            *reinterpret_cast<u32x4*>(Qs + q * RS + 8 * c8) = rq;
+            *reinterpret_cast<u32x4*>(dOs + q * RS + 8 * c8) = rd;
+            const half8 hq = bf16x8_to_half8(rq), hd = bf16x8_to_half8(rd);
+            const int col = sbm_col(q);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                QT[sbm_at(8 * c8 + j, col, TS)] = hq[j];
+                dOT[sbm_at(8 * c8 + j, col, TS)] = hd[j];
+            }
+        }
+        if (tid < SBM_QT) {
+            s_lse2[tid] = lse[tokb + i0 + tid] * LOG2E;
+            s_D[tid] = Dvec[tokb + i0 + tid];
+            s_cnt[tid] = cnt[tokb + i0 + tid];
+        }
+        __syncthreads();
+
+        // ---- S and dP for 64 queries x this wavefront's 16 keys -----------------------------------------
+        f32x4 accS[4], accP[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) { accS[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; accP[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const u32x4 fq = *reinterpret_cast<const u32x4*>(Qs + (16 * mt + l16) * RS + 32 * ks + 8 * lq);
+                const u32x4 fd = *reinterpret_cast<const u32x4*>(dOs + (16 * mt + l16) * RS + 32 * ks + 8 * lq);
+                accS[mt] = sbm_mfma_bf16(fq, kf[ks], accS[mt]);   // rows: queries 16 mt + 4 lq + j, col: key l16
+                accP[mt] = sbm_mfma_bf16(fd, vf[ks], accP[mt]);
+            }
+        // ---- P, dS (fp32), split into two fp16 terms; column sums of dS ---------------------------------
+        half8 p_hi[2], p_lo[2], s_hi[2], s_lo[2];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const float4 l4 = *reinterpret_cast<const float4*>(s_lse2 + 16 * mt + 4 * lq);
+            const float4 d4 = *reinterpret_cast<const float4*>(s_D + 16 * mt + 4 * lq);
+            const int4 c4 = *reinterpret_cast<const int4*>(s_cnt + 16 * mt + 4 * lq);
+            const float lq4[4] = {l4.x, l4.y, l4.z, l4.w}, dq4[4] = {d4.x, d4.y, d4.z, d4.w};
+            const int cq4[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p = (valid && c < cq4[j]) ? __builtin_amdgcn_exp2f(scale2 * accS[mt][j] - lq4[j]) : 0.f;
+                const float ds = p * (accP[mt][j] - dq4[j]);
+                g += ds;
+                const half_t ph = (half_t)p, sh = f32_to_half_sat(ds);
+                const int slot = 4 * (mt & 1) + j;
+                p_hi[mt >> 1][slot] = ph;
+                p_lo[mt >> 1][slot] = (half_t)(p - (float)ph);
+                s_hi[mt >> 1][slot] = sh;
+                s_lo[mt >> 1][slot] = (half_t)(ds - (float)sh);
+            }
+        }
+        // ---- dV^T += dO^T P,  dK^T += Q^T dS  (rows d = 16 md + 4 lq + j, col key l16) -------------------
+#pragma unroll
+        for (int md = 0; md < MD; ++md)
+#pragma unroll
+            for (int mp = 0; mp < 2; ++mp) {
+                const half8 ad = lds_read8(dOT + sbm_at(16 * md + l16, 32 * mp + 8 * lq, TS));
+                const half8 aq = lds_read8(QT + sbm_at(16 * md + l16, 32 * mp + 8 * lq, TS));
+                accV[md] = mfma16(ad, p_hi[mp], accV[md]);
+                accV[md] = mfma16(ad, p_lo[mp], accV[md]);
+                accK[md] = mfma16(aq, s_hi[mp], accK[md]);
+                accK[md] = mfma16(aq, s_lo[mp], accK[md]);
+            }
+    }
+    // this segment's share, by compacted key; a second kernel adds the shares up in order
+    g += __shfl_xor(g, 16);
+    g += __shfl_xor(g, 32);
+    if (valid) {
+        const size_t row = ((size_t)seg * gridDim.y + bh) * L + c;
+#pragma unroll
+        for (int md = 0; md < MD; ++md) {
+            *reinterpret_cast<float4*>(dk_part + row * D + 16 * md + 4 * lq) =
+                make_float4(accK[md][0], accK[md][1], accK[md][2], accK[md][3]);
+            *reinterpret_cast<float4*>(dv_part + row * D + 16 * md + 4 * lq) =
+                make_float4(accV[md][0], accV[md][1], accV[md][2], accV[md][3]);
+        }
+        if (lq == 0) g_part[row] = g;
+    }
+}
+
 template <typename T>
 static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                       const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* O_nla, const float* lse,
@@ -252,10 +426,37 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
                                    const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* lse,
                                    const float* Dvec, float* dK, float* dV, float* g_nla, float* dk_part, float* dv_part,
                                    float* g_part, hipStream_t st) {
-    if (pl.dtype == NATS_BF16)
-        launch_sb<bf16_t>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dk_part, dv_part,
-                          g_part, true, st);
-    else
+    if (pl.dtype == NATS_BF16) {   // the MFMA form
+        dim3 grid(pl.L / 64, pl.BH, BWD_DKV_SEGMENTS);
+        // the LDS-size attribute is per function and device: set once per device, not per launch
+        static bool attr_done[2][64] = {};
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        dev = (dev >= 0 && dev < 64) ? dev : 0;
+        if (pl.d == 64) {
+            auto kern = softmax_bwd_dkv_mfma_kernel<64>;
+            if (!attr_done[0][dev]) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        sbm_lds_bytes<64>()) != hipSuccess)
+                    return check_launch("softmax_bwd_dkv (LDS attribute)");
+                attr_done[0][dev] = true;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(256), sbm_lds_bytes<64>(), st, (const bf16_t*)Q, (const bf16_t*)Kc,
+                               (const bf16_t*)Vc, (const bf16_t*)dO, cnt, idx, n_s, lse, Dvec, dk_part, dv_part, g_part,
+                               pl.L, pl.softmax_scale);
+        } else {
+            auto kern = softmax_bwd_dkv_mfma_kernel<128>;
+            if (!attr_done[1][dev]) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        sbm_lds_bytes<128>()) != hipSuccess)
+                    return check_launch("softmax_bwd_dkv (LDS attribute)");
+                attr_done[1][dev] = true;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(256), sbm_lds_bytes<128>(), st, (const bf16_t*)Q, (const bf16_t*)Kc,
+                               (const bf16_t*)Vc, (const bf16_t*)dO, cnt, idx, n_s, lse, Dvec, dk_part, dv_part, g_part,
+                               pl.L, pl.softmax_scale);
+        }
+    } else
         launch_sb<float>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dk_part, dv_part,
                          g_part, true, st);
     nats_status rc = check_launch("softmax_bwd_dkv");
