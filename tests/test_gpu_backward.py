@@ -42,7 +42,9 @@ def check(r, ref, extra=()):
 
 @pytest.mark.parametrize("dtype,B,H,L,d,p", [("f32", 1, 2, 320, 64, 0.15), ("f32", 2, 2, 256, 128, 0.1),
                                              ("bf16", 1, 3, 1088, 64, 0.08), ("bf16", 1, 2, 448, 128, 0.2),
-                                             ("f32", 1, 1, 64, 64, 0.5)])
+                                             ("f32", 1, 1, 64, 64, 0.5),
+                                             # many key tiles, several query tiles per block share (MFMA dK / dV kernel)
+                                             ("bf16", 1, 1, 2048, 128, 0.3), ("bf16", 2, 2, 1024, 64, 0.5)])
 def test_backward_matches_the_oracle(dtype, B, H, L, d, p):
     x = make_fwd_inputs(B, H, L, d, dtype, p, seed=200 + L + d)
     dO = make_grad_output(B, H, L, d, dtype, seed=300 + L)
