@@ -24,7 +24,7 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "alu_f32": (1
 def kernel_work(name, cfg, sum_cnt):
     """Algorithmic work of one launch of each kernel at this workload -> (bound, amount, unit-scale).
 
-    bytes for HBM-bound kernels, FLOP for arithmetic-bound ones (counts documented in the design doc)."""
+    bytes for HBM-bound kernels, FLOP for arithmetic-bound ones."""
     BH, L, d = cfg.B * cfg.H, cfg.L, cfg.d
     n_tok = BH * L
     esz = 2 if cfg.dtype == "bf16" else 4
