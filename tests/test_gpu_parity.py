@@ -329,3 +329,28 @@ def test_one_chunk_and_long_thin_shapes_bf16():
         ref = oracle_fwd(x, want=("S",))
         assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"], (L, d)
         assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (L, d)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_chunk_count_up_to_nine_bf16(d):
+    """1..9 chunks: the recurrence kernel walks its chunks four to a loop trip and up to three in a tail, and
+    prefetches three chunks ahead with a clamped index; every combination of trips and tail is taken here, with
+    a given initial state."""
+    for n_chunks in range(1, 10):
+        L = 64 * n_chunks
+        x = make_fwd_inputs(1, 3, L, d, "bf16", 0.1, seed=500 + 10 * n_chunks + d)
+        S0 = (0.1 * np.random.default_rng(n_chunks).standard_normal((1, 3, d, d))).astype(np.float32)
+        r = run_ex(x, "bf16", want=("final_state",), initial_state=S0)
+        ref = oracle_fwd(x, S0=S0, want=("S",))
+        assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"], (L, d)
+        assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (L, d)
+
+
+def test_pair_counts_that_change_the_number_of_prefetch_helpers_bf16():
+    """B*H = 40 (two helper blocks per pair fit beside the 160 compute blocks), 48 (one), 56 (none)."""
+    for B, H in ((5, 8), (6, 8), (7, 8)):
+        x = make_fwd_inputs(B, H, 1024, 128, "bf16", 0.05, seed=600 + B)
+        r = run_ex(x, "bf16", want=("final_state",))
+        ref = oracle_fwd(x, want=("S",))
+        assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"], (B, H)
+        assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (B, H)
