@@ -23,29 +23,60 @@
 
 namespace nats {
 
-constexpr int RB_TT = 16;         // tokens staged per tile
+constexpr int RB_TT = 16;         // tokens staged per tile (a multiple of 4)
 constexpr int RB_CH = 64;         // tokens between checkpoints
 
 // One step of a sum over the rows of a wavefront by recursive halving.  In the step for lane bit b a lane keeps
 // the half of its N values that its bit selects, hands the other half to its partner and adds what the partner
 // hands over: N values of one row become N / 2 values of two rows.
-template <int N>
-__device__ __forceinline__ void halve_step(float* v, int lane, int bit) {
-    const bool up = ((lane >> bit) & 1) != 0;
+template <int N, int BIT>
+__device__ __forceinline__ void halve_step(float* v, int lane);   // defined below the lane exchanges
+
+constexpr int RBW_ROWS = BWD_SWEEP_ROWS;         // state rows per block of the reverse sweep
+// 16 lanes per state row: a row is then one 16-lane row of the wavefront, inside which sums run on DPP row
+// rotations; sums across the four rows of a wavefront run on gfx950's row swaps.  (Through __shfl_xor every step
+// of these sums was an LDS round trip of its own, about thirty of them in a row per token.)
+constexpr int rbw_lpr(int) { return 16; }
+constexpr int rbw_threads(int d) { return RBW_ROWS * rbw_lpr(d); }   // 256
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {   // x of the lane that the DPP control CTRL names
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+// sum over the 16 lanes of a row, in every lane: row rotations by 8, 4, 2, 1
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_move<0x128>(x);
+    x += dpp_move<0x124>(x);
+    x += dpp_move<0x122>(x);
+    x += dpp_move<0x121>(x);
+    return x;
+}
+// x of lane ^ 16 / lane ^ 32.  v_permlane16_swap exchanges the odd rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second; given the same
+// value twice, one of the two results holds the partner's value, which one depends on the lane's own row / half.
+__device__ __forceinline__ float lane_xor16(float x, int lane) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(((lane >> 4) & 1) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor32(float x, int lane) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float((lane >> 5) ? r[0] : r[1]);
+}
+
+template <int N, int BIT>
+__device__ __forceinline__ void halve_step(float* v, int lane) {
+    static_assert(BIT == 4 || BIT == 5, "rows of a wavefront differ in lane bits 4 and 5");
+    const bool up = ((lane >> BIT) & 1) != 0;
 #pragma unroll
     for (int c = 0; c < N / 2; ++c) {
         const float keep = up ? v[c + N / 2] : v[c];
         const float send = up ? v[c] : v[c + N / 2];
-        v[c] = keep + __shfl_xor(send, 1 << bit);
+        v[c] = keep + (BIT == 4 ? lane_xor16(send, lane) : lane_xor32(send, lane));
     }
 }
 
-constexpr int RBW_LPR = 16;                      // lanes per state row in the reverse sweep
-constexpr int RBW_ROWS = BWD_SWEEP_ROWS;         // state rows per block of the reverse sweep
-constexpr int RBW_THREADS = RBW_ROWS * RBW_LPR;  // 256: four wavefronts, four rows each
-
 template <typename T, int D>
-__global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
+__global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ ckpt, float* __restrict__ scratch, float* __restrict__ dq_part,
@@ -53,12 +84,13 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
     float* __restrict__ dV, float* __restrict__ dS0, int L, int BH, float la_scale, int linear_op,
     int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
-    constexpr int LPR = RBW_LPR, NW = RBW_THREADS / 64;
+    constexpr int LPR = rbw_lpr(D), RBW_THREADS = rbw_threads(D), NW = RBW_THREADS / 64;
+    constexpr int RPW = 64 / LPR;   // rows of a wavefront: 2 or 4
     constexpr int DP = D / LPR;     // columns of a row per lane
     constexpr int KQ = 2 * DP + 4;  // a lane's columns of k, then of q, then padding: the 16 lanes of a row read
                                     // their 16-byte pieces from different banks
-    constexpr int NF = DP / 4;      // values of a lane that are left after the sum over its wavefront's 4 rows
-    static_assert(DP % 4 == 0, "16-byte pieces and two halving steps");
+    constexpr int NF = DP / RPW;    // values of a lane that are left after the sum over its wavefront's rows
+    static_assert(DP % 4 == 0 && RPW == 4, "16-byte pieces; two halving steps");
     __shared__ __align__(16) float s_kq[RB_TT][LPR * KQ];
     __shared__ float s_v[RB_TT][RBW_ROWS], s_do[RB_TT][RBW_ROWS];
     __shared__ float s_a[RB_TT], s_b[RB_TT];
@@ -118,10 +150,8 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
         }
         __syncthreads();
     };
-    auto row_sum = [](float x) {   // over a row's 16 lanes
-        x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); x += __shfl_xor(x, 4); x += __shfl_xor(x, 8);
-        return x;
-    };
+    static_assert(LPR == 16, "a state row is one DPP row");
+    auto row_sum = [](float x) { return row16_sum(x); };   // over a row's lanes
 
     float dS[DP];
 #pragma unroll
@@ -167,23 +197,30 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
             }
         }
         // ---- backwards through the chunk ------------------------------------------------------------
-        // The parked rows come back one token ahead of use: read at the token that needs them, their latency
-        // (a trip to L2 or further) would be paid 64 times per chunk.
-        float Sn[DP];
-        auto fetch_rows = [&](int tok) {   // this thread's own stores of token tok of the chunk
+        // The parked rows come back PFR tokens ahead of use, through a ring of registers (token tok in slot
+        // tok % PFR; the token loop is unrolled PFR times, so the slots are fixed at compile time): read at the
+        // token that needs them, or only one token ahead, their latency (a trip past L2: the scratch of all
+        // blocks is 134 MB) is paid at every token.
+        constexpr int PFR = 4;
+        float Sn[PFR][DP];
+        auto fetch_rows = [&](int tok, float* dst) {   // this thread's own stores of token tok of the chunk
             const float* src = my_scr + (size_t)tok * (D * RBW_ROWS) + tid * 4;
 #pragma unroll
             for (int c = 0; c < DP; c += 4) {
                 const float4 x = *reinterpret_cast<const float4*>(src + (c / 4) * (RBW_THREADS * 4));
-                Sn[c] = x.x; Sn[c + 1] = x.y; Sn[c + 2] = x.z; Sn[c + 3] = x.w;
+                dst[c] = x.x; dst[c + 1] = x.y; dst[c + 2] = x.z; dst[c + 3] = x.w;
             }
         };
-        fetch_rows(RB_CH - 1);
+#pragma unroll
+        for (int u = 0; u < PFR; ++u) fetch_rows(RB_CH - 1 - u, Sn[(RB_CH - 1 - u) % PFR]);
 #pragma unroll 1
         for (int tt = RB_CH - RB_TT; tt >= 0; tt -= RB_TT) {
             stage(tc0 + tt, true);
 #pragma unroll 1
-            for (int i = RB_TT - 1; i >= 0; --i) {
+            for (int i4 = RB_TT - PFR; i4 >= 0; i4 -= PFR)
+#pragma unroll
+            for (int u = PFR - 1; u >= 0; --u) {
+                const int i = i4 + u;
                 const int t = tc0 + tt + i;
                 const float a = s_a[i], b = s_b[i], go = la_scale * s_do[i][r];
                 const bool lin = s_lin[i] != 0;   // uniform across the block
@@ -198,8 +235,8 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
                     qq[c] = q4.x; qq[c + 1] = q4.y; qq[c + 2] = q4.z; qq[c + 3] = q4.w;
                 }
 #pragma unroll
-                for (int c = 0; c < DP; ++c) Sd[c] = Sn[c];
-                if (tt + i > 0) fetch_rows(tt + i - 1);
+                for (int c = 0; c < DP; ++c) Sd[c] = Sn[u][c];   // (tt + i) % PFR == u: tt and i4 are multiples of PFR
+                if (tt + i >= PFR) fetch_rows(tt + i - PFR, Sn[u]);
                 float pred = 0.f;
 #pragma unroll
                 for (int c = 0; c < DP; ++c) pred += Sd[c] * kk[c];
@@ -237,10 +274,11 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
                     for (int c = 0; c < DP; ++c) { dalpha_p += dS[c] * Sd[c]; dS[c] *= a; }
                     dalpha_p = row_sum(dalpha_p) / fmaxf(a, 1e-30f);   // S_{t-1} = Sd / a
                 }
-                // sums over the rows of the block: the 4 rows of a wavefront (lane bits 4, 5) by recursive
-                // halving, which leaves a lane with NF columns: the halves its row bits selected ...
-                halve_step<DP>(xq, lane, 4);     halve_step<DP>(xk, lane, 4);
-                halve_step<DP / 2>(xq, lane, 5); halve_step<DP / 2>(xk, lane, 5);
+                // sums over the rows of the block: the rows of a wavefront by recursive halving, which leaves a
+                // lane with NF columns: the halves its row bits selected ...
+                // rows differ in lane bits 4 and 5
+                halve_step<DP, 4>(xq, lane);     halve_step<DP, 4>(xk, lane);
+                halve_step<DP / 2, 5>(xq, lane); halve_step<DP / 2, 5>(xk, lane);
                 const int col = part * DP + (DP / 2) * ((lane >> 4) & 1) + (DP / 4) * ((lane >> 5) & 1);
                 const int buf = t & 1;
 #pragma unroll
@@ -250,8 +288,8 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
                 }
                 // the two scalars: one value per row (its lane 0), rows of a wavefront, then the wavefronts in order
                 float xa = part == 0 ? dalpha_p : 0.f, xb = part == 0 ? dbeta_p : 0.f;
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) { xa += __shfl_xor(xa, off); xb += __shfl_xor(xb, off); }
+                xa += lane_xor16(xa, lane); xb += lane_xor16(xb, lane);   // only the rows' lanes 0 hold values: lane 0
+                xa += lane_xor32(xa, lane); xb += lane_xor32(xb, lane);   // ends up with the sum over the four rows
                 if (lane == 0) { s_sc[buf][0][wave] = xa; s_sc[buf][1][wave] = xb; }
                 // ... then the wavefronts, in order.  One barrier per token: the next token writes the other half
                 // of the buffers, and the barrier after it separates these reads from the writes that follow.
@@ -284,12 +322,12 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_recurrent_bwd_kernel(
 // state before every chunk of 64 tokens, ckpt[bh][chunk][row][d_k].  Same thread layout as the kernel above
 // (16 rows per block, 16 lanes per row).
 template <typename T, int D>
-__global__ __launch_bounds__(RBW_THREADS) void gdn_checkpoint_kernel(
+__global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ S0, float* __restrict__ ckpt, int L, int linear_op,
     int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
-    constexpr int LPR = RBW_LPR, DP = D / LPR, DPP = DP + 4;
+    constexpr int LPR = rbw_lpr(D), RBW_THREADS = rbw_threads(D), DP = D / LPR, DPP = DP + 4;
     constexpr int TT = 32;
     __shared__ __align__(16) float s_k[TT][LPR * DPP];
     __shared__ float s_v[TT][RBW_ROWS];
@@ -354,10 +392,7 @@ __global__ __launch_bounds__(RBW_THREADS) void gdn_checkpoint_kernel(
 #pragma unroll
             for (int c = 0; c < DP; ++c) { S[c] *= a; pred += S[c] * kk[c]; }
             if (s_lin[i]) {   // uniform across the block
-                pred += __shfl_xor(pred, 1);
-                pred += __shfl_xor(pred, 2);
-                pred += __shfl_xor(pred, 4);
-                pred += __shfl_xor(pred, 8);
+                pred = row16_sum(pred);
                 const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
                 for (int c = 0; c < DP; ++c) S[c] += delta * kk[c];
@@ -404,11 +439,11 @@ static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const voi
                       float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
     dim3 grid(pl.d / RBW_ROWS, pl.BH);
     if (pl.d == 64)
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(RBW_THREADS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(rbw_threads(64)), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
     else
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(RBW_THREADS), 0, st, (const T*)Q, (const T*)K,
+        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(rbw_threads(128)), 0, st, (const T*)Q, (const T*)K,
                            (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
                            dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
 }
@@ -433,7 +468,7 @@ nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void*
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st) {
     dim3 grid(pl.d / RBW_ROWS, pl.BH);
 #define NATS_CK_LAUNCH(TT, DD)                                                                                        \
-    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(RBW_THREADS), 0, st, (const TT*)K, (const TT*)V, alpha, \
+    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(rbw_threads(DD)), 0, st, (const TT*)K, (const TT*)V, alpha, \
                        beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax)
     if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_CK_LAUNCH(bf16_t, 64); else NATS_CK_LAUNCH(bf16_t, 128); }
     else { if (pl.d == 64) NATS_CK_LAUNCH(float, 64); else NATS_CK_LAUNCH(float, 128); }
