@@ -20,13 +20,6 @@ namespace nats {
 
 constexpr int DEC_THREADS = 256;
 
-template <int W>
-__device__ __forceinline__ float group_sum(float x) {
-#pragma unroll
-    for (int off = 1; off < W; off <<= 1) x += __shfl_xor(x, off);
-    return x;
-}
-
 // CHUNK = false: routing per token (mask: the token's type).
 // CHUNK = true : routing per chunk, known only after the chunk (Section 4.1, per-token generation): every
 //   token is written into the state and appended to the cache provisionally (row cache_len +
@@ -94,11 +87,11 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
             float4 s = S4[p];
             s.x *= a; s.y *= a; s.z *= a; s.w *= a;
             if (b != 0.f) {
-                const float pred = group_sum<LPR>(s.x * k4.x + s.y * k4.y + s.z * k4.z + s.w * k4.w);
+                const float pred = lane_group_sum<LPR>(s.x * k4.x + s.y * k4.y + s.z * k4.z + s.w * k4.w);
                 const float delta = b * (s_v[row] - (linear_op == 0 ? pred : 0.f));   // no correction without the delta rule
                 s.x += delta * k4.x; s.y += delta * k4.y; s.z += delta * k4.z; s.w += delta * k4.w;
             }
-            const float oq = group_sum<LPR>(s.x * q4.x + s.y * q4.y + s.z * q4.z + s.w * q4.w);
+            const float oq = lane_group_sum<LPR>(s.x * q4.x + s.y * q4.y + s.z * q4.z + s.w * q4.w);
             if (lr == 0) s_ola[row] = la_scale * oq;
             *reinterpret_cast<float4*>(Sb + (size_t)row * D + lr * 4) = s;
         }
@@ -132,7 +125,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
             float dot = 0.f;
 #pragma unroll
             for (int j = 0; j < EPL; ++j) dot += qf[j] * kf[u][j];
-            dot = group_sum<LPK>(dot);
+            dot = lane_group_sum<LPK>(dot);
             s[u] = (c0 + u * NSG < n_old) ? dot : -INFINITY;
             bm = fmaxf(bm, s[u]);
         }
@@ -154,7 +147,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
         float dot = 0.f;
 #pragma unroll
         for (int j = 0; j < EPL; ++j) dot += qf[j] * s_kn[lk * EPL + j];
-        dot = group_sum<LPK>(dot);
+        dot = lane_group_sum<LPK>(dot);
         const float m_new = fmaxf(m_run, dot);
         const float corr = expf(m_run - m_new);
         const float p = expf(dot - m_new);
@@ -207,7 +200,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     } else if (combine_mode == 2) {   // one normalisation of the (weighted) sum
         const float sum = (w_nla ? w_nla[bh] : 1.f) * o_nla + (w_la ? w_la[bh] : 1.f) * o_la;
         float x = (tid < D) ? sum * sum : 0.f;
-        x = group_sum<64>(x);
+        x = lane_group_sum<64>(x);
         if ((tid & 63) == 0 && tid < 128) s_red[tid >> 6] = x;
         __syncthreads();
         if (tid < D) {
@@ -216,7 +209,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
         }
     } else {
         float x = (tid < D) ? o_la * o_la : 0.f, y = (tid < D) ? o_nla * o_nla : 0.f;
-        x = group_sum<64>(x); y = group_sum<64>(y);
+        x = lane_group_sum<64>(x); y = lane_group_sum<64>(y);
         if ((tid & 63) == 0 && tid < 128) { s_red[(tid >> 6) * 2] = x; s_red[(tid >> 6) * 2 + 1] = y; }
         __syncthreads();
         if (tid < D) {

@@ -68,13 +68,6 @@ __device__ __forceinline__ float quad_sum(float x) {
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <int W>
-__device__ __forceinline__ float lane_group_sum(float x) {   // sum over aligned groups of W lanes
-#pragma unroll
-    for (int off = 1; off < W; off <<= 1) x += __shfl_xor(x, off);
-    return x;
-}
-
 // MERGE = true : the epilogue reads the linear branch's output (fp16), merges and stores O.
 // MERGE = false: the epilogue stores the softmax branch's output as fp16 (O_nla_h); the kernel that
 //                carries the state merges and stores O.  This variant depends on nothing but the

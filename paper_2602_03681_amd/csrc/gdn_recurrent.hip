@@ -34,7 +34,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     const int tid = threadIdx.x, r = tid >> 2, part = tid & 3;
     const int row = blockIdx.x * REC_ROWS + r;  // d_v index of this lane's row
     const size_t base = (size_t)bh * L;
-    auto row_sum = [](float x) { x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); return x; };   // over a row's 4 lanes
+    auto row_sum = [](float x) { return lane_group_sum<4>(x); };   // over a row's 4 lanes
 
     float S[DP];
     if (S0 != nullptr) {

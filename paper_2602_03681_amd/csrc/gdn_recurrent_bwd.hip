@@ -33,35 +33,11 @@ template <int N, int BIT>
 __device__ __forceinline__ void halve_step(float* v, int lane);   // defined below the lane exchanges
 
 constexpr int RBW_ROWS = BWD_SWEEP_ROWS;         // state rows per block of the reverse sweep
-// 16 lanes per state row: a row is then one 16-lane row of the wavefront, inside which sums run on DPP row
-// rotations; sums across the four rows of a wavefront run on gfx950's row swaps.  (Through __shfl_xor every step
-// of these sums was an LDS round trip of its own, about thirty of them in a row per token.)
+// 16 lanes per state row: a row is then one 16-lane row of the wavefront, inside which sums run on DPP moves;
+// sums across the four rows of a wavefront run on gfx950's row swaps.  (Through __shfl_xor every step of these
+// sums was an LDS round trip of its own, about thirty of them in a row per token.)
 constexpr int rbw_lpr(int) { return 16; }
 constexpr int rbw_threads(int d) { return RBW_ROWS * rbw_lpr(d); }   // 256
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float x) {   // x of the lane that the DPP control CTRL names
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
-}
-// sum over the 16 lanes of a row, in every lane: row rotations by 8, 4, 2, 1
-__device__ __forceinline__ float row16_sum(float x) {
-    x += dpp_move<0x128>(x);
-    x += dpp_move<0x124>(x);
-    x += dpp_move<0x122>(x);
-    x += dpp_move<0x121>(x);
-    return x;
-}
-// x of lane ^ 16 / lane ^ 32.  v_permlane16_swap exchanges the odd rows of its first operand with the even rows of
-// its second, v_permlane32_swap the upper half of the first with the lower half of the second; given the same
-// value twice, one of the two results holds the partner's value, which one depends on the lane's own row / half.
-__device__ __forceinline__ float lane_xor16(float x, int lane) {
-    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(((lane >> 4) & 1) ? r[0] : r[1]);
-}
-__device__ __forceinline__ float lane_xor32(float x, int lane) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float((lane >> 5) ? r[0] : r[1]);
-}
 
 template <int N, int BIT>
 __device__ __forceinline__ void halve_step(float* v, int lane) {
@@ -151,7 +127,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
         __syncthreads();
     };
     static_assert(LPR == 16, "a state row is one DPP row");
-    auto row_sum = [](float x) { return row16_sum(x); };   // over a row's lanes
+    auto row_sum = [](float x) { return lane_group_sum<16>(x); };   // over a row's lanes
 
     float dS[DP];
 #pragma unroll
@@ -392,7 +368,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
 #pragma unroll
             for (int c = 0; c < DP; ++c) { S[c] *= a; pred += S[c] * kk[c]; }
             if (s_lin[i]) {   // uniform across the block
-                pred = row16_sum(pred);
+                pred = lane_group_sum<16>(pred);
                 const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
                 for (int c = 0; c < DP; ++c) S[c] += delta * kk[c];

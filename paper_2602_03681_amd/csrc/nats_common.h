@@ -31,6 +31,38 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 
+// ---- sums across lanes without LDS ------------------------------------------------------------------------
+// __shfl_xor compiles to an LDS permute with a wait behind it; a reduction of n steps is n LDS round trips in
+// a row.  Inside a 16-lane row the steps below are DPP moves (a modifier of an ordinary vector instruction);
+// across rows they are gfx950's row swaps.  Blocks are one-dimensional and a multiple of 64 threads wide.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {   // x of the lane that the DPP control CTRL names
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+// x of lane ^ 16 / lane ^ 32.  v_permlane16_swap exchanges the odd rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second; given the same
+// value twice, one of the two results holds the partner's value, which one depends on the lane's own row / half.
+__device__ __forceinline__ float lane_xor16(float x, int lane) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(((lane >> 4) & 1) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor32(float x, int lane) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(((lane >> 5) & 1) ? r[0] : r[1]);
+}
+// sum over aligned groups of W lanes (a power of two), in every lane of the group; fixed order
+template <int W>
+__device__ __forceinline__ float lane_group_sum(float x) {
+    static_assert(W == 1 || W == 2 || W == 4 || W == 8 || W == 16 || W == 32 || W == 64, "group width");
+    if (W >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1, 0, 3, 2]
+    if (W >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2, 3, 0, 1]
+    if (W >= 8) x += dpp_move<0x141>(x);   // row_half_mirror: lane i of 8 <- lane 7 - i (the other quad's sum)
+    if (W >= 16) x += dpp_move<0x140>(x);  // row_mirror: lane i of 16 <- lane 15 - i (the other half's sum)
+    if (W >= 32) x += lane_xor16(x, (int)(threadIdx.x & 63));
+    if (W >= 64) x += lane_xor32(x, (int)(threadIdx.x & 63));
+    return x;
+}
+
 template <typename T>
 __device__ __forceinline__ T from_float(float f);
 template <>

@@ -48,8 +48,7 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dq_kernel(
         const float4 o = *reinterpret_cast<const float4*>(O_nla + row_off + c);
         Di += dout[c] * o.x + dout[c + 1] * o.y + dout[c + 2] * o.z + dout[c + 3] * o.w;
     }
-    Di += __shfl_xor(Di, 1);
-    Di += __shfl_xor(Di, 2);
+    Di = lane_group_sum<4>(Di);
     if (part == 0) Dvec[tokb + t] = Di;
 #pragma unroll
     for (int c = 0; c < DP; ++c) { q[c] *= scale; acc[c] = 0.f; }
@@ -88,8 +87,8 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dq_kernel(
                 s += q[c] * k4.x + q[c + 1] * k4.y + q[c + 2] * k4.z + q[c + 3] * k4.w;
                 dp += dout[c] * v4.x + dout[c + 1] * v4.y + dout[c + 2] * v4.z + dout[c + 3] * v4.w;
             }
-            s += __shfl_xor(s, 1); s += __shfl_xor(s, 2);
-            dp += __shfl_xor(dp, 1); dp += __shfl_xor(dp, 2);
+            s = lane_group_sum<4>(s);
+            dp = lane_group_sum<4>(dp);
             const float p = (j < mine) ? expf(s - lse_t) : 0.f;   // a row that sees nothing has mine <= 0
             const float ds = p * (dp - Di);
 #pragma unroll
@@ -168,8 +167,8 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
                 s += k[e] * q4.x + k[e + 1] * q4.y + k[e + 2] * q4.z + k[e + 3] * q4.w;
                 dp += v[e] * d4.x + v[e + 1] * d4.y + v[e + 2] * d4.z + v[e + 3] * d4.w;
             }
-            s += __shfl_xor(s, 1); s += __shfl_xor(s, 2);
-            dp += __shfl_xor(dp, 1); dp += __shfl_xor(dp, 2);
+            s = lane_group_sum<4>(s);
+            dp = lane_group_sum<4>(dp);
             const float p = (valid && c < s_cnt[i]) ? expf(s - s_lse[i]) : 0.f;
             const float ds = p * (dp - s_D[i]);
             g += ds;
@@ -376,8 +375,8 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
             }
     }
     // this segment's share, by compacted key; a second kernel adds the shares up in order
-    g += __shfl_xor(g, 16);
-    g += __shfl_xor(g, 32);
+    g += lane_xor16(g, lane);
+    g += lane_xor32(g, lane);
     if (valid) {
         const size_t row = ((size_t)seg * gridDim.y + bh) * L + c;
 #pragma unroll

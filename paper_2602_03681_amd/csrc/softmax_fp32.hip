@@ -91,8 +91,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
                     const float4 k4 = *reinterpret_cast<const float4*>(kr + c);
                     dot += q[c] * k4.x + q[c + 1] * k4.y + q[c + 2] * k4.z + q[c + 3] * k4.w;
                 }
-                dot += __shfl_xor(dot, 1);
-                dot += __shfl_xor(dot, 2);
+                dot = lane_group_sum<4>(dot);
                 s[j] = (kb + j < mine) ? dot : -INFINITY;
             }
             float bm = s[0];
@@ -150,8 +149,8 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         float ss_la = 0.f, ss_nla = 0.f;
 #pragma unroll
         for (int c = 0; c < DP; ++c) { ss_la += la[c] * la[c]; ss_nla += acc[c] * acc[c]; }
-        ss_la += __shfl_xor(ss_la, 1); ss_la += __shfl_xor(ss_la, 2);
-        ss_nla += __shfl_xor(ss_nla, 1); ss_nla += __shfl_xor(ss_nla, 2);
+        ss_la = lane_group_sum<4>(ss_la);
+        ss_nla = lane_group_sum<4>(ss_nla);
         const float wn = (w_nla ? w_nla[(size_t)bh * L + t] : 0.5f) / sqrtf(ss_nla / D + eps);
         const float wl = (w_la ? w_la[(size_t)bh * L + t] : 0.5f) / sqrtf(ss_la / D + eps);
 #pragma unroll
@@ -161,7 +160,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         float ss = 0.f;
 #pragma unroll
         for (int c = 0; c < DP; ++c) { out[c] = wn * acc[c] + wl * la[c]; ss += out[c] * out[c]; }
-        ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2);
+        ss = lane_group_sum<4>(ss);
         const float inv = 1.f / sqrtf(ss / D + eps);
 #pragma unroll
         for (int c = 0; c < DP; ++c) out[c] *= inv;
