@@ -181,12 +181,16 @@ __global__ __launch_bounds__(PREP_THREADS, 3) void gdn_chunk_prep_kernel(
         // variant without decay on softmax tokens (routing per token): their alpha counts as 1
         const float a = (freeze_on_softmax && !chunk_mask && mask[tok0 + lane]) ? 1.f : alpha[tok0 + lane];
         float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float up = __shfl_up(g, off);
-            if (lane >= off) g += up;
-        }
-        const float gC = __shfl(g, 63);
+        // inclusive scan over the 64 lanes on DPP moves (no LDS): inside the 16-lane rows by shifts of 1, 2, 4, 8
+        // (a lane without a source adds 0), then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into
+        // the upper half
+        g += dpp_move<0x111>(g);
+        g += dpp_move<0x112>(g);
+        g += dpp_move<0x114>(g);
+        g += dpp_move<0x118>(g);
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x142, 0xA, 0xF, false));   // row_bcast15
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x143, 0xC, 0xF, false));   // row_bcast31
+        const float gC = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g), 63));
         s_g2[lane] = g;
         s_gam[lane] = __builtin_amdgcn_exp2f(g);
         // Routing per token: a softmax token writes nothing (b' = 0).  Routing per chunk: every token
