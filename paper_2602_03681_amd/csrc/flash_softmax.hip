@@ -198,11 +198,8 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
         wave_hi = max(wave_hi, my_cnt[nq]);
         wave_lo = min(wave_lo, my_cnt[nq]);
     }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        wave_hi = max(wave_hi, __shfl_xor(wave_hi, off));
-        wave_lo = min(wave_lo, __shfl_xor(wave_lo, off));
-    }
+    wave_hi = wave_extreme_i32<true>(wave_hi);
+    wave_lo = wave_extreme_i32<false>(wave_lo);
 
     f32x4 accO[FL_NQ][DT];
     float m_run[FL_NQ], l_run[FL_NQ];

@@ -63,6 +63,20 @@ __device__ __forceinline__ float lane_group_sum(float x) {
     return x;
 }
 
+// maximum / minimum of an int over the 64 lanes of a wavefront, in every lane (same steps as lane_group_sum<64>)
+template <bool MAX>
+__device__ __forceinline__ int wave_extreme_i32(int x) {
+    auto pick = [](int a, int b) { return MAX ? max(a, b) : min(a, b); };
+    const int lane = (int)(threadIdx.x & 63);
+    x = pick(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false));
+    x = pick(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false));
+    x = pick(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xF, 0xF, false));
+    x = pick(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xF, 0xF, false));
+    x = pick(x, __float_as_int(lane_xor16(__int_as_float(x), lane)));
+    x = pick(x, __float_as_int(lane_xor32(__int_as_float(x), lane)));
+    return x;
+}
+
 template <typename T>
 __device__ __forceinline__ T from_float(float f);
 template <>
