@@ -36,8 +36,8 @@ constexpr int RBW_ROWS = BWD_SWEEP_ROWS;         // state rows per block of the 
 // 16 lanes per state row: a row is then one 16-lane row of the wavefront, inside which sums run on DPP moves;
 // sums across the four rows of a wavefront run on gfx950's row swaps.  (Through __shfl_xor every step of these
 // sums was an LDS round trip of its own, about thirty of them in a row per token.)
-constexpr int rbw_lpr(int) { return 16; }
-constexpr int rbw_threads(int d) { return RBW_ROWS * rbw_lpr(d); }   // 256
+constexpr int rbw_lpr(int d) { return d / 4; }                       // 4 columns per lane
+constexpr int rbw_threads(int d) { return RBW_ROWS * rbw_lpr(d); }   // 512 for d = 128, 256 for d = 64
 
 template <int N, int BIT>
 __device__ __forceinline__ void halve_step(float* v, int lane) {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
     constexpr int KQ = 2 * DP + 4;  // a lane's columns of k, then of q, then padding: the 16 lanes of a row read
                                     // their 16-byte pieces from different banks
     constexpr int NF = DP / RPW;    // values of a lane that are left after the sum over its wavefront's rows
-    static_assert(DP % 4 == 0 && RPW == 4, "16-byte pieces; two halving steps");
+    static_assert(DP % 4 == 0 && (RPW == 2 || RPW == 4), "16-byte pieces; one or two halving steps");
     __shared__ __align__(16) float s_kq[RB_TT][LPR * KQ];
     __shared__ float s_v[RB_TT][RBW_ROWS], s_do[RB_TT][RBW_ROWS];
     __shared__ float s_a[RB_TT], s_b[RB_TT];
@@ -126,8 +126,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
         }
         __syncthreads();
     };
-    static_assert(LPR == 16, "a state row is one DPP row");
-    auto row_sum = [](float x) { return lane_group_sum<16>(x); };   // over a row's lanes
+    auto row_sum = [](float x) { return lane_group_sum<LPR>(x); };   // over a row's lanes
 
     float dS[DP];
 #pragma unroll
@@ -252,10 +251,15 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                 }
                 // sums over the rows of the block: the rows of a wavefront by recursive halving, which leaves a
                 // lane with NF columns: the halves its row bits selected ...
-                // rows differ in lane bits 4 and 5
-                halve_step<DP, 4>(xq, lane);     halve_step<DP, 4>(xk, lane);
-                halve_step<DP / 2, 5>(xq, lane); halve_step<DP / 2, 5>(xk, lane);
-                const int col = part * DP + (DP / 2) * ((lane >> 4) & 1) + (DP / 4) * ((lane >> 5) & 1);
+                int col = part * DP;
+                if (RPW == 4) {   // rows differ in lane bits 4 and 5
+                    halve_step<DP, 4>(xq, lane);     halve_step<DP, 4>(xk, lane);
+                    halve_step<DP / 2, 5>(xq, lane); halve_step<DP / 2, 5>(xk, lane);
+                    col += (DP / 2) * ((lane >> 4) & 1) + (DP / 4) * ((lane >> 5) & 1);
+                } else {          // in lane bit 5
+                    halve_step<DP, 5>(xq, lane);     halve_step<DP, 5>(xk, lane);
+                    col += (DP / 2) * ((lane >> 5) & 1);
+                }
                 const int buf = t & 1;
 #pragma unroll
                 for (int j = 0; j < NF; ++j) {
@@ -264,8 +268,8 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                 }
                 // the two scalars: one value per row (its lane 0), rows of a wavefront, then the wavefronts in order
                 float xa = part == 0 ? dalpha_p : 0.f, xb = part == 0 ? dbeta_p : 0.f;
-                xa += lane_xor16(xa, lane); xb += lane_xor16(xb, lane);   // only the rows' lanes 0 hold values: lane 0
-                xa += lane_xor32(xa, lane); xb += lane_xor32(xb, lane);   // ends up with the sum over the four rows
+                if (RPW == 4) { xa += lane_xor16(xa, lane); xb += lane_xor16(xb, lane); }   // only the rows' lanes 0 hold
+                xa += lane_xor32(xa, lane); xb += lane_xor32(xb, lane);   // values: lane 0 ends up with the sum over the rows
                 if (lane == 0) { s_sc[buf][0][wave] = xa; s_sc[buf][1][wave] = xb; }
                 // ... then the wavefronts, in order.  One barrier per token: the next token writes the other half
                 // of the buffers, and the barrier after it separates these reads from the writes that follow.
@@ -368,7 +372,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
 #pragma unroll
             for (int c = 0; c < DP; ++c) { S[c] *= a; pred += S[c] * kk[c]; }
             if (s_lin[i]) {   // uniform across the block
-                pred = lane_group_sum<16>(pred);
+                pred = lane_group_sum<LPR>(pred);
                 const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
                 for (int c = 0; c < DP; ++c) S[c] += delta * kk[c];
