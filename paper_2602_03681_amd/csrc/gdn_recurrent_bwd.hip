@@ -211,7 +211,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                 }
 #pragma unroll
                 for (int c = 0; c < DP; ++c) Sd[c] = Sn[u][c];   // (tt + i) % PFR == u: tt and i4 are multiples of PFR
-                if (tt + i >= PFR) fetch_rows(tt + i - PFR, Sn[u]);
+                fetch_rows(max(tt + i - PFR, 0), Sn[u]);   // unconditional (the last four re-read token 0): see below
                 float pred = 0.f;
 #pragma unroll
                 for (int c = 0; c < DP; ++c) pred += Sd[c] * kk[c];
@@ -242,7 +242,12 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
 #pragma unroll
                     for (int c = 0; c < DP; ++c) xk[c] = 0.f;
                 }
-                if (part == 0) dV[(base + t) * D + row] = dr;
+                // Every memory operation of the token body is issued by every wavefront on every path: the loads of
+                // the ring and the stores share one in-order counter, and only with a fixed number of operations
+                // between a load and its use can the compiler wait for that load alone; with a store under a
+                // condition it waits for the newest stores as well, at every token.  So lanes that hold a copy
+                // of a value store it too (same value, same address).
+                dV[(base + t) * D + row] = dr;   // all lanes of the row hold dr
                 float dalpha_p = 0.f;
                 if (s_dec[i]) {   // uniform
 #pragma unroll
@@ -274,14 +279,12 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                 // ... then the wavefronts, in order.  One barrier per token: the next token writes the other half
                 // of the buffers, and the barrier after it separates these reads from the writes that follow.
                 __syncthreads();
-                if (tid < 2 * D) {
-                    const int which = tid / D, c = tid % D;
+                {   // threads beyond 2 D repeat the first ones
+                    const int e = tid % (2 * D), which = e / D, c = e % D;
                     float sum = 0.f;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) sum += s_part[buf][which][w][c];
                     (which == 0 ? dq_p : dk_p)[(base + t) * D + c] = sum;
-                }
-                if (tid == RBW_THREADS - 1) {
                     float sa = 0.f, sb = 0.f;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) { sa += s_sc[buf][0][w]; sb += s_sc[buf][1][w]; }
