@@ -152,7 +152,10 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ints between the chunk-progress counters of two (batch, head) pairs: one 256-byte line each, so
 // that polling one counter never touches the line another block stores to
 constexpr int PROG_STRIDE = 64;
-constexpr int BWD_DKV_SEGMENTS = 8;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
+#ifndef NATS_BWD_DKV_SEGMENTS
+#define NATS_BWD_DKV_SEGMENTS 8
+#endif
+constexpr int BWD_DKV_SEGMENTS = NATS_BWD_DKV_SEGMENTS;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
 constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse sweep: d / 16 blocks and partial sums per (batch, head)
 
 struct FwdPlan {

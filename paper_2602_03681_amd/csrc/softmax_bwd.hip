@@ -109,13 +109,15 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc, const T* __restrict__ dO,
     const int32_t* __restrict__ cnt, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_s,
     const float* __restrict__ lse, const float* __restrict__ Dvec, float* __restrict__ dk_part,
-    float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale) {
+    float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale, int BH, int n_seg) {
     constexpr int DP = D / 4, DPP = DP + 4, EPL = Vec16<T>::N;
     __shared__ __align__(16) float s_q[SB_TILE][4 * DPP];
     __shared__ __align__(16) float s_do[SB_TILE][4 * DPP];
     __shared__ float s_lse[SB_TILE], s_D[SB_TILE];
     __shared__ int s_cnt[SB_TILE];
-    const int bh = blockIdx.y, c0 = blockIdx.x * SB_ROWS, tid = threadIdx.x;
+    // one-dimensional grid, the key tile slowest (see the MFMA kernel below)
+    const int seg = blockIdx.x % n_seg, bh = (blockIdx.x / n_seg) % BH, c0 = (blockIdx.x / n_seg / BH) * SB_ROWS;
+    const int tid = threadIdx.x;
     const int n_keys = n_s[bh];
     if (c0 >= n_keys) return;                          // uniform: this tile holds no key
     const int kr = tid >> 2, part = tid & 3, c = c0 + kr;
@@ -130,11 +132,11 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
     for (int e = 0; e < DP; ++e) { k[e] *= scale; dk[e] = 0.f; dv[e] = 0.f; }
     float g = 0.f;
 
-    // The queries that see the tile's first key, in tiles; the blocks of the tile (blockIdx.z) take equal shares
+    // The queries that see the tile's first key, in tiles; the blocks of the tile take equal shares
     // of them: the first key tile of a head is seen by every query, and one block walking all of them was the
     // whole kernel's run time.
     const int i_first = idx[tokb + c0] & ~(SB_TILE - 1);
-    const int n_tiles = (L - i_first) / SB_TILE, seg = blockIdx.z, n_seg = gridDim.z;
+    const int n_tiles = (L - i_first) / SB_TILE;
     const int i_lo = i_first + (int)((long long)n_tiles * seg / n_seg) * SB_TILE;
     const int i_hi = i_first + (int)((long long)n_tiles * (seg + 1) / n_seg) * SB_TILE;
     for (int i0 = i_lo; i0 < i_hi; i0 += SB_TILE) {
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dkv_kernel(
         }
     }
     if (valid) {   // this segment's share, by compacted key; a second kernel adds the shares up in order
-        const size_t row = ((size_t)seg * gridDim.y + bh) * L + c;
+        const size_t row = ((size_t)seg * BH + bh) * L + c;
 #pragma unroll
         for (int e = 0; e < DP; e += 4) {
             *reinterpret_cast<float4*>(dk_part + row * D + part * DP + e) = make_float4(dk[e], dk[e + 1], dk[e + 2], dk[e + 3]);
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_dkv_combine_kernel(
 
 // ---- dKc, dVc, g on MFMA, bf16 tensors ---------------------------------------------------------------------
 // A block owns 64 compacted keys, wavefront w the 16 keys of tile w, and walks the queries that can see them
-// in tiles of 64 (its share of them: blockIdx.z).  Per query tile, with everything a wavefront needs of P and dS
+// in tiles of 64 (its share of them).  Per query tile, with everything a wavefront needs of P and dS
 // staying in its own registers:
 //   S [q][key] = Q K^T,  dP[q][key] = dO V^T     bf16 MFMA, inputs exact; A = the Q / dO tile (LDS, row-major),
 //                                                 B = the wavefront's K / V rows, held in registers
@@ -258,7 +260,8 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ cnt, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_s, const float* __restrict__ lse, const float* __restrict__ Dvec,
-    float* __restrict__ dk_part, float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale) {
+    float* __restrict__ dk_part, float* __restrict__ dv_part, float* __restrict__ g_part, int L, float scale, int BH,
+    int n_seg) {
     constexpr int RS = D + LDS_PAD, TS = SBM_QT + LDS_PAD;
     constexpr int KS_D = D / 32, MD = D / 16, NPC = SBM_QT * D / 8 / 256;
     extern __shared__ __align__(16) unsigned char sbm_smem[];
@@ -270,7 +273,12 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
     float* s_D = s_lse2 + SBM_QT;
     int* s_cnt = reinterpret_cast<int*>(s_D + SBM_QT);
 
-    const int bh = blockIdx.y, c0 = blockIdx.x * 64, tid = threadIdx.x;
+    // One-dimensional grid, the key tile slowest: the tiles that hold keys (the first ones) are dispatched first,
+    // the heaviest of all (tile 0, seen by every query) at the very front; the empty ones follow and exit at once.
+    // (With the key tile as the fastest dimension the few working blocks sat between thousands of empty ones,
+    // each of which claims a block's LDS and registers before it can exit: 1.2 ms instead of 0.35.)
+    const int seg = blockIdx.x % n_seg, bh = (blockIdx.x / n_seg) % BH, c0 = (blockIdx.x / n_seg / BH) * 64;
+    const int tid = threadIdx.x;
     const int n_keys = n_s[bh];
     if (c0 >= n_keys) return;                          // uniform: this tile holds no key
     const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
 
     // the queries that see the tile's first key, in tiles; the blocks of the tile take equal shares of them
     const int i_first = idx[tokb + c0] & ~(SBM_QT - 1);
-    const int n_tiles = (L - i_first) / SBM_QT, seg = blockIdx.z, n_seg = gridDim.z;
+    const int n_tiles = (L - i_first) / SBM_QT;
     const int i_lo = i_first + (int)((long long)n_tiles * seg / n_seg) * SBM_QT;
     const int i_hi = i_first + (int)((long long)n_tiles * (seg + 1) / n_seg) * SBM_QT;
 #pragma unroll 1
@@ -378,7 +386,7 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
     g += lane_xor16(g, lane);
     g += lane_xor32(g, lane);
     if (valid) {
-        const size_t row = ((size_t)seg * gridDim.y + bh) * L + c;
+        const size_t row = ((size_t)seg * BH + bh) * L + c;
 #pragma unroll
         for (int md = 0; md < MD; ++md) {
             *reinterpret_cast<float4*>(dk_part + row * D + 16 * md + 4 * lq) =
@@ -394,7 +402,8 @@ template <typename T>
 static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                       const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* O_nla, const float* lse,
                       float* Dvec, float* dQ, float* dK, float* dV, float* g_nla, bool dkv, hipStream_t st) {
-    dim3 grid(pl.L / SB_ROWS, pl.BH, dkv ? BWD_DKV_SEGMENTS : 1);
+    dim3 grid(pl.L / SB_ROWS, pl.BH);
+    if (dkv) grid = dim3((unsigned)((size_t)(pl.L / SB_ROWS) * pl.BH * BWD_DKV_SEGMENTS));
 #define NATS_SB_LAUNCH(DD)                                                                                          \
     if (!dkv)                                                                                                        \
         hipLaunchKernelGGL((softmax_bwd_dq_kernel<T, DD>), grid, dim3(SB_THREADS), 0, st, (const T*)Q, (const T*)Kc, \
@@ -402,7 +411,7 @@ static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const vo
     else                                                                                                             \
         hipLaunchKernelGGL((softmax_bwd_dkv_kernel<T, DD>), grid, dim3(SB_THREADS), 0, st, (const T*)Q,              \
                            (const T*)Kc, (const T*)Vc, (const T*)dO, cnt, idx, n_s, lse, Dvec, dK, dV, g_nla, pl.L,  \
-                           pl.softmax_scale)
+                           pl.softmax_scale, pl.BH, BWD_DKV_SEGMENTS)
     if (pl.d == 64) NATS_SB_LAUNCH(64);
     else NATS_SB_LAUNCH(128);
 #undef NATS_SB_LAUNCH
@@ -426,7 +435,7 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
                                    const float* Dvec, float* dK, float* dV, float* g_nla, float* dk_part, float* dv_part,
                                    float* g_part, hipStream_t st) {
     if (pl.dtype == NATS_BF16) {   // the MFMA form
-        dim3 grid(pl.L / 64, pl.BH, BWD_DKV_SEGMENTS);
+        dim3 grid((unsigned)((size_t)(pl.L / 64) * pl.BH * BWD_DKV_SEGMENTS));
         // the LDS-size attribute is per function and device: set once per device, not per launch
         static bool attr_done[2][64] = {};
         int dev = 0;
@@ -442,7 +451,7 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
             }
             hipLaunchKernelGGL(kern, grid, dim3(256), sbm_lds_bytes<64>(), st, (const bf16_t*)Q, (const bf16_t*)Kc,
                                (const bf16_t*)Vc, (const bf16_t*)dO, cnt, idx, n_s, lse, Dvec, dk_part, dv_part, g_part,
-                               pl.L, pl.softmax_scale);
+                               pl.L, pl.softmax_scale, pl.BH, BWD_DKV_SEGMENTS);
         } else {
             auto kern = softmax_bwd_dkv_mfma_kernel<128>;
             if (!attr_done[1][dev]) {
@@ -453,7 +462,7 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
             }
             hipLaunchKernelGGL(kern, grid, dim3(256), sbm_lds_bytes<128>(), st, (const bf16_t*)Q, (const bf16_t*)Kc,
                                (const bf16_t*)Vc, (const bf16_t*)dO, cnt, idx, n_s, lse, Dvec, dk_part, dv_part, g_part,
-                               pl.L, pl.softmax_scale);
+                               pl.L, pl.softmax_scale, pl.BH, BWD_DKV_SEGMENTS);
         }
     } else
         launch_sb<float>(pl, Q, Kc, Vc, dO, cnt, idx, n_s, nullptr, lse, const_cast<float*>(Dvec), nullptr, dk_part, dv_part,
