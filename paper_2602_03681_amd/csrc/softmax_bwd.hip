@@ -34,7 +34,7 @@ __global__ __launch_bounds__(SB_THREADS) void softmax_bwd_dq_kernel(
     constexpr int DP = D / 4, DPP = DP + 4, EPL = Vec16<T>::N;
     __shared__ __align__(16) float s_k[SB_TILE][4 * DPP];
     __shared__ __align__(16) float s_v[SB_TILE][4 * DPP];
-    const int bh = blockIdx.y, q0 = blockIdx.x * SB_ROWS, tid = threadIdx.x;
+    const int bh = blockIdx.y, q0 = (gridDim.x - 1 - blockIdx.x) * SB_ROWS, tid = threadIdx.x;   // long blocks first
     const int r = tid >> 2, part = tid & 3, t = q0 + r;
     const size_t tokb = (size_t)bh * L;
     const size_t row_off = (tokb + t) * D + part * DP;

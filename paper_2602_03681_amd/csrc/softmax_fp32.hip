@@ -35,7 +35,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     __shared__ __align__(16) float s_v[SM_BN][4 * DPP];
 
     const int bh = blockIdx.y;
-    const int q0 = blockIdx.x * SM_BM;
+    const int q0 = (gridDim.x - 1 - blockIdx.x) * SM_BM;   // later queries see more keys: the long blocks go first
     const int tid = threadIdx.x;
     const int r = tid >> 2, part = tid & 3;
     const int t = q0 + r;
