@@ -398,6 +398,125 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
     }
 }
 
+// ---- dQ and D on MFMA, bf16 tensors: the mirror image of the kernel above ----------------------------------------
+// A block owns 64 queries, wavefront w the 16 queries of tile w (their Q and dO rows are its B operands, in
+// registers), and walks the key tiles its last query sees.  Per key tile:
+//   S^T [key][q] = K Q^T,  dP^T[key][q] = V dO^T     bf16 MFMA, A = the K / V tile (LDS, row-major)
+//   P, dS (fp32, as above; a query is one MFMA column, so lse, D and the count are per-lane scalars)
+//   dQ^T[d][q] += K^T dS^T      fp16 MFMA, A = the transposed K tile (LDS, columns in slot order),
+//                               B = dS straight from the accumulators, as two fp16 terms
+template <int D>
+__global__ __launch_bounds__(256, 2) void softmax_bwd_dq_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc,
+    const bf16_t* __restrict__ dO, const int32_t* __restrict__ cnt, const float* __restrict__ O_nla,
+    const float* __restrict__ lse, float* __restrict__ Dvec, float* __restrict__ dQ, int L, float scale) {
+    constexpr int RS = D + LDS_PAD, TS = 64 + LDS_PAD;
+    constexpr int KS_D = D / 32, MD = D / 16, NPC = 64 * D / 8 / 256;
+    __shared__ __align__(16) uint16_t Ks[64 * RS], Vs[64 * RS];   // bf16, row-major
+    __shared__ __align__(16) half_t KT[D * TS];                    // fp16, transposed
+    __shared__ float s_D[64];
+
+    const int bh = blockIdx.y, q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * 64, tid = threadIdx.x;   // long blocks first
+    const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    const size_t tokb = (size_t)bh * L;
+    const float LOG2E = 1.44269504088896341f;
+    const float scale2 = scale * LOG2E;
+
+    // D_i = do_i . o_i: four lanes per query, as in the fp32 kernel
+    {
+        const int r = tid >> 2, part = tid & 3;
+        const size_t off = (tokb + q0 + r) * D + part * (D / 4);
+        float Di = 0.f;
+#pragma unroll
+        for (int c = 0; c < D / 4; c += 8) {
+            float dv[8];
+            Vec16<bf16_t>::load(dO + off + c, dv);
+            const float4 o0 = *reinterpret_cast<const float4*>(O_nla + off + c);
+            const float4 o1 = *reinterpret_cast<const float4*>(O_nla + off + c + 4);
+            Di += dv[0] * o0.x + dv[1] * o0.y + dv[2] * o0.z + dv[3] * o0.w + dv[4] * o1.x + dv[5] * o1.y + dv[6] * o1.z +
+                  dv[7] * o1.w;
+        }
+        Di = lane_group_sum<4>(Di);
+        if (part == 0) { s_D[r] = Di; Dvec[tokb + q0 + r] = Di; }
+    }
+    // this lane's query (an MFMA column): its rows of Q and dO as B operands, its scalars
+    const int qi = q0 + 16 * wave + l16;
+    u32x4 qf[KS_D], dof[KS_D];
+#pragma unroll
+    for (int ks = 0; ks < KS_D; ++ks) {
+        qf[ks] = *reinterpret_cast<const u32x4*>(Q + (tokb + qi) * D + 32 * ks + 8 * lq);
+        dof[ks] = *reinterpret_cast<const u32x4*>(dO + (tokb + qi) * D + 32 * ks + 8 * lq);
+    }
+    const float lse2_q = lse[tokb + qi] * LOG2E;
+    const int cnt_q = cnt[tokb + qi];
+    const int n_hi = cnt[tokb + q0 + 63];   // cnt is non-decreasing: the block's bound
+    __syncthreads();
+    const float D_q = s_D[16 * wave + l16];
+
+    f32x4 accQ[MD];
+#pragma unroll
+    for (int md = 0; md < MD; ++md) accQ[md] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll 1
+    for (int c0 = 0; c0 < n_hi; c0 += 64) {
+        __syncthreads();   // the previous tile has been read by everyone
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            const int e = tid + 256 * i, key = e / (D / 8), c8 = e % (D / 8);
+            u32x4 rk = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
+            if (c0 + key < n_hi) {   // rows past the block's bound are not initialised: they enter as zeros
+                const size_t src = (tokb + c0 + key) * D + 8 * c8;
+                rk = *reinterpret_cast<const u32x4*>(Kc + src);
+                rv = *reinterpret_cast<const u32x4*>(Vc + src);
+            }
+            *reinterpret_cast<u32x4*>(Ks + key * RS + 8 * c8) = rk;
+            *reinterpret_cast<u32x4*>(Vs + key * RS + 8 * c8) = rv;
+            const half8 hk = bf16x8_to_half8(rk);
+            const int col = sbm_col(key);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) KT[sbm_at(8 * c8 + j, col, TS)] = hk[j];
+        }
+        __syncthreads();
+        f32x4 accS[4], accP[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) { accS[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; accP[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const u32x4 fk = *reinterpret_cast<const u32x4*>(Ks + (16 * mt + l16) * RS + 32 * ks + 8 * lq);
+                const u32x4 fv = *reinterpret_cast<const u32x4*>(Vs + (16 * mt + l16) * RS + 32 * ks + 8 * lq);
+                accS[mt] = sbm_mfma_bf16(fk, qf[ks], accS[mt]);   // rows: keys 16 mt + 4 lq + j, col: query l16
+                accP[mt] = sbm_mfma_bf16(fv, dof[ks], accP[mt]);
+            }
+        half8 s_hi[2], s_lo[2];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = c0 + 16 * mt + 4 * lq + j;
+                const float p = (c < cnt_q) ? __builtin_amdgcn_exp2f(scale2 * accS[mt][j] - lse2_q) : 0.f;
+                const float ds = p * (accP[mt][j] - D_q);
+                const half_t sh = f32_to_half_sat(ds);
+                const int slot = 4 * (mt & 1) + j;
+                s_hi[mt >> 1][slot] = sh;
+                s_lo[mt >> 1][slot] = (half_t)(ds - (float)sh);
+            }
+#pragma unroll
+        for (int md = 0; md < MD; ++md)
+#pragma unroll
+            for (int mp = 0; mp < 2; ++mp) {
+                const half8 ak = lds_read8(KT + sbm_at(16 * md + l16, 32 * mp + 8 * lq, TS));
+                accQ[md] = mfma16(ak, s_hi[mp], accQ[md]);   // rows d = 16 md + 4 lq + j, col query l16
+                accQ[md] = mfma16(ak, s_lo[mp], accQ[md]);
+            }
+    }
+#pragma unroll
+    for (int md = 0; md < MD; ++md)
+        *reinterpret_cast<float4*>(dQ + (tokb + qi) * D + 16 * md + 4 * lq) =
+            make_float4(scale * accQ[md][0], scale * accQ[md][1], scale * accQ[md][2], scale * accQ[md][3]);
+}
+
 template <typename T>
 static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                       const int32_t* cnt, const int32_t* idx, const int32_t* n_s, const float* O_nla, const float* lse,
@@ -421,9 +540,15 @@ static void launch_sb(const FwdPlan& pl, const void* Q, const void* Kc, const vo
 nats_status launch_softmax_bwd_dq(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc, const void* dO,
                                   const int32_t* cnt, const float* O_nla, const float* lse, float* Dvec, float* dQ,
                                   hipStream_t st) {
-    if (pl.dtype == NATS_BF16)
-        launch_sb<bf16_t>(pl, Q, Kc, Vc, dO, cnt, nullptr, nullptr, O_nla, lse, Dvec, dQ, nullptr, nullptr, nullptr, false, st);
-    else
+    if (pl.dtype == NATS_BF16) {   // the MFMA form
+        dim3 grid(pl.L / 64, pl.BH);
+        if (pl.d == 64)
+            hipLaunchKernelGGL((softmax_bwd_dq_mfma_kernel<64>), grid, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)Kc,
+                               (const bf16_t*)Vc, (const bf16_t*)dO, cnt, O_nla, lse, Dvec, dQ, pl.L, pl.softmax_scale);
+        else
+            hipLaunchKernelGGL((softmax_bwd_dq_mfma_kernel<128>), grid, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)Kc,
+                               (const bf16_t*)Vc, (const bf16_t*)dO, cnt, O_nla, lse, Dvec, dQ, pl.L, pl.softmax_scale);
+    } else
         launch_sb<float>(pl, Q, Kc, Vc, dO, cnt, nullptr, nullptr, O_nla, lse, Dvec, dQ, nullptr, nullptr, nullptr, false, st);
     return check_launch("softmax_bwd_dq");
 }
