@@ -77,6 +77,27 @@ __device__ __forceinline__ int wave_extreme_i32(int x) {
     return x;
 }
 
+// sum of an int over the 64 lanes of a wavefront, in every lane; inclusive prefix sum over the lanes
+__device__ __forceinline__ int wave_sum_i32(int x) {
+    const int lane = (int)(threadIdx.x & 63);
+    x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);
+    x += __float_as_int(lane_xor16(__int_as_float(x), lane));
+    x += __float_as_int(lane_xor32(__int_as_float(x), lane));
+    return x;
+}
+__device__ __forceinline__ int wave_inclusive_scan_i32(int x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false);   // row_shr 1, 2, 4, 8: a lane without a source adds 0
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);   // lane 15 of rows 0 and 2 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);   // lane 31 into the upper half
+    return x;
+}
+
 template <typename T>
 __device__ __forceinline__ T from_float(float f);
 template <>

@@ -47,8 +47,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
                 before += nonzero_bytes(w.x) + nonzero_bytes(w.y) + nonzero_bytes(w.z) + nonzero_bytes(w.w);
             }
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off);
+        before = wave_sum_i32(before);
         if (lane == 0) s_wave[wave] = before;
         __syncthreads();
         before = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
@@ -61,12 +60,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     if (t0 < L)   // L % 4 == 0: a word is all in or all out; its 4 tokens lie in one chunk
         w = chunk_mask ? (m[t0 >> 6] ? 0x01010101u : 0u) : *reinterpret_cast<const uint32_t*>(m + t0);
     const int mine = nonzero_bytes(w);
-    int incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int up = __shfl_up(incl, off);
-        if (lane >= off) incl += up;
-    }
+    const int incl = wave_inclusive_scan_i32(mine);
     if (lane == 63) s_wave[wave] = incl;
     __syncthreads();
     int wave_base = 0, seg_total = 0;
