@@ -160,7 +160,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
                                     void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
- * Backward pass (Section 4.2), routing per token, plain-sum merge, fp32 arithmetic
+ * Backward pass (Section 4.2), routing per token, plain-sum merge, fp32 results
  * ------------------------------------------------------------------------- */
 typedef struct nats_bwd_extra {
     const float* initial_state; /* in  [B,H,d,d] f32, the state the forward started from (NULL -> 0)         */
@@ -177,7 +177,10 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  * attention backward over the softmax columns of Eq. 12 with the mask gradients of Eq. 15.  k and v of a
  * softmax token get nothing from the linear branch and vice versa (Section 4.2).
  *   Q, K, V, alpha, beta, mask : as in the forward (p->routing must be NATS_ROUTE_TOKEN, p->combine_mode 0;
- *             p->math is not looked at: every product and sum here is fp32)
+ *             p->math is not looked at).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.
+ *             For bf16 tensors the softmax branch's dQ, dK, dV products run on the matrix cores: Q, K, V, dO
+ *             enter exactly (they are bf16), the probabilities and dS enter as the sum of two fp16 terms,
+ *             so the gradients keep fp32-level accuracy; for f32 tensors those products are fp32 too
  *   dO      : in  [B,H,L,d] dtype p->dtype
  *   dQ, dK, dV : out [B,H,L,d] f32 (whatever p->dtype);  dalpha, dbeta : out [B,H,L] f32
  *   extra   : optional, may be NULL
