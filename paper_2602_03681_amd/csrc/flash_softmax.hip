@@ -61,12 +61,6 @@ __device__ __forceinline__ float quad_max(float x) {
     const auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-__device__ __forceinline__ float quad_sum(float x) {
-    const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-    const auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
 
 // MERGE = true : the epilogue reads the linear branch's output (fp16), merges and stores O.
 // MERGE = false: the epilogue stores the softmax branch's output as fp16 (O_nla_h); the kernel that
@@ -202,11 +196,12 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
     wave_lo = wave_extreme_i32<false>(wave_lo);
 
     f32x4 accO[FL_NQ][DT];
-    float m_run[FL_NQ], l_run[FL_NQ];
+    float m_run[FL_NQ];
+    f32x4 accL[FL_NQ];   // running sum of the weights, the same value in every row
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         m_run[nq] = -INFINITY;
-        l_run[nq] = 0.f;
+        accL[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int t = 0; t < DT; ++t) accO[nq][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -272,10 +267,11 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
         if (kt == NATS_MARK_TILE) NATS_MARK(14);
         // ---- online softmax per query column; P^T fragments ------------------------------------------
         // VALU work is what bounds this loop, so it is kept to one fused multiply-add, one exponential,
-        // one add and one conversion per logit: masking only in tiles that are not visible in full to
-        // every query of the wavefront; the running maximum is raised only when the tile's maximum
-        // exceeds it by more than 2^8 (the weights then stay below 2^8, exact enough in fp16 and far
-        // from overflow), so rescaling of the accumulators is rare and skipped by the whole wavefront.
+        // half a maximum and half a conversion per logit: masking only in tiles that are not visible in
+        // full to every query of the wavefront; the sums of the weights are left to the matrix cores (see
+        // below); the running maximum is raised only when the tile's maximum exceeds it by more than 2^8
+        // (the weights then stay below 2^8, exact enough in fp16 and far from overflow), so rescaling of
+        // the accumulators is rare and skipped by the whole wavefront.
         half8 pf[FL_NQ][2];
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
@@ -287,34 +283,39 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
                         if (16 * m + 4 * lq + j >= vis[nq]) accS[nq][m][j] = -INFINITY;
                     }
             }
-            float tmax = -INFINITY;
+            // Logits relative to the running maximum as it stands: the fused multiply-add's result feeds the
+            // tile maximum and, unless the maximum is raised, the exponential as it is.
+            const float m_old = m_run[nq];
+            const float m_sub = m_old > -INFINITY ? m_old : 0.f;   // nothing visible yet: weights exp2(-inf) = 0
 #pragma unroll
             for (int m = 0; m < 4; ++m)
-                tmax = fmaxf(fmaxf(tmax, fmaxf(accS[nq][m][0], accS[nq][m][1])), fmaxf(accS[nq][m][2], accS[nq][m][3]));
-            tmax = quad_max(tmax) * scale2;    // scale2 > 0: the maximum commutes with the scaling
-            const float m_old = m_run[nq];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) accS[nq][m][j] = __builtin_fmaf(accS[nq][m][j], scale2, -m_sub);
+            float tz = -INFINITY;
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                tz = fmaxf(fmaxf(tz, fmaxf(accS[nq][m][0], accS[nq][m][1])), fmaxf(accS[nq][m][2], accS[nq][m][3]));
+            tz = quad_max(tz);
+            const float tmax = tz + m_sub;
             const bool raise = tmax > m_old + 8.f;   // also true for the first visible key (m_old = -inf)
-            const float m_new = raise ? tmax : m_old;
-            const float m_sub = m_new > -INFINITY ? m_new : 0.f;   // nothing visible yet: weights exp2(-inf) = 0
             if (__any(raise)) {
-                const float corr = raise ? __builtin_amdgcn_exp2f(m_old - m_new) : 1.f;   // exp2(-inf) = 0
-                l_run[nq] *= corr;
+                const float corr = raise ? __builtin_amdgcn_exp2f(m_old - tmax) : 1.f;   // exp2(-inf) = 0
+                const float delta = raise ? tz : 0.f;
+                m_run[nq] = raise ? tmax : m_old;
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) accS[nq][m][j] -= delta;
+                accL[nq][0] *= corr; accL[nq][1] *= corr; accL[nq][2] *= corr; accL[nq][3] *= corr;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
                     accO[nq][t][0] *= corr; accO[nq][t][1] *= corr; accO[nq][t][2] *= corr; accO[nq][t][3] *= corr;
                 }
             }
-            m_run[nq] = m_new;
-            float psum = 0.f;
 #pragma unroll
             for (int m = 0; m < 4; ++m)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(accS[nq][m][j], scale2, -m_sub));
-                    accS[nq][m][j] = pv;
-                    psum += pv;
-                }
-            l_run[nq] += quad_sum(psum);
+                for (int j = 0; j < 4; ++j) accS[nq][m][j] = __builtin_amdgcn_exp2f(accS[nq][m][j]);
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {   // contraction step s2: slots 0-3 <- key tile 2 s2, 4-7 <- 2 s2 + 1
                 const f32x4 lo = accS[nq][2 * s2], hi = accS[nq][2 * s2 + 1];   // weights <= 2^8: no clamp needed
@@ -334,6 +335,16 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
             }
+        // The sums of the weights come from the same products: a 16-row tile of ones above V^T puts, in
+        // every accumulator row, the sum over the keys of the fp16 weights that multiply V.
+        {
+            const half8 ones = half8{(half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f,
+                                     (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f};
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int nq = 0; nq < FL_NQ; ++nq) accL[nq] = mfma16(ones, pf[nq][s2], accL[nq]);
+        }
         if (kt == NATS_MARK_TILE) NATS_MARK(16);
     }
     NATS_MARK(2);
@@ -359,7 +370,7 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         const int qbase = q0 + (wave * FL_NQ + nq) * 16;
-        const float l = l_run[nq];
+        const float l = accL[nq][0];
         const float inv_l = l > 0.f ? 1.f / l : 0.f;
         if (lse_out != nullptr && lq == 0 && qbase + l16 < L)
             lse_out[tokbase + qbase + l16] =
