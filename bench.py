@@ -117,7 +117,7 @@ def bench_decode(args):
 
 
 def bench_backward(args):
-    """Backward pass on workload 2's shapes (fp32 arithmetic; the recurrence's reverse sweep dominates): a step
+    """Backward pass on workload 2's shapes (fp32 sums everywhere; for bf16 tensors the softmax branch's products run on the matrix cores; the recurrence's reverse sweep dominates): a step
     is one nats_hybrid_attn_bwd call.  Roofline: plain fp32 vector arithmetic of the reverse sweep."""
     import torch
 
@@ -159,7 +159,7 @@ def bench_backward(args):
     out = {"metric": "hybrid_attn_bwd_tokens_per_s", "value": round(cfg.B * cfg.L / (ms * 1e-3), 1), "unit": "tokens/s",
            "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 arithmetic, fp32 gradients)"},
+           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 gradients; recurrence in fp32, softmax-branch products on MFMA with two-term fp16 weights)"},
            "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,
            "roofline": {"kernel": "gdn_recurrent_bwd", "bound": "alu", "achieved": round(achieved, 3), "peak": 157.3,
                         "unit": "TFLOP/s", "frac": round(achieved / 157.3, 5), "traffic": None,
@@ -185,7 +185,7 @@ def main():
     ap.add_argument("--routing", choices=("token", "chunk"), default="token",
                     help="granularity of the routing mask: per token (default, the headline workload) or per chunk")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
-    ap.add_argument("--backward", action="store_true", help="measure the backward pass (fp32 arithmetic) instead")
+    ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")

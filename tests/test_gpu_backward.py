@@ -1,4 +1,4 @@
-"""GPU parity of the backward pass (Section 4.2; fp32 arithmetic, routing per token, plain-sum merge) against
+"""GPU parity of the backward pass (Section 4.2; fp32-accurate gradients, routing per token, plain-sum merge) against
 the backward oracle, through the C ABI.  Every gradient tensor is held to max|err| / RMS(oracle) <= 1e-4 (the
 outputs are fp32 whatever the input dtype)."""
 import numpy as np
