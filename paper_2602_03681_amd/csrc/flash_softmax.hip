@@ -38,6 +38,9 @@ constexpr int FL_THREADS = 256;
 #ifndef NATS_FL_NQ
 #define NATS_FL_NQ 2
 #endif
+#ifndef NATS_FL_VAHEAD
+#define NATS_FL_VAHEAD 6          // V^T fragment reads in flight ahead of their matrix instructions
+#endif
 #ifndef NATS_FL_OCC
 #define NATS_FL_OCC 2
 #endif
@@ -263,6 +266,13 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accS[nq][m] = mfma16_bf16(fk, qf[nq][ks], accS[nq][m]);
             }
+        // issue order: K fragments several reads ahead of the matrix instructions that take them
+        __builtin_amdgcn_sched_group_barrier(0x100, NATS_FL_VAHEAD, 0);
+#pragma unroll
+        for (int i = 0; i < KS_D * 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
 
         if (kt == NATS_MARK_TILE) NATS_MARK(14);
         // ---- online softmax per query column; P^T fragments ------------------------------------------
@@ -344,6 +354,14 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
             for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
                 for (int nq = 0; nq < FL_NQ; ++nq) accL[nq] = mfma16(ones, pf[nq][s2], accL[nq]);
+        }
+        // Issue order of this block: V^T fragments several reads ahead of the matrix instructions that take
+        // them (the compiler's own order waits for every other read just before its use).
+        __builtin_amdgcn_sched_group_barrier(0x100, NATS_FL_VAHEAD, 0);
+#pragma unroll
+        for (int i = 0; i < DT * 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         if (kt == NATS_MARK_TILE) NATS_MARK(16);
     }
