@@ -369,6 +369,44 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
     __syncthreads();   // tiles are dead: the region becomes the output staging
     NATS_MARK(3);
 
+    if (!MERGE && O_nla_out == nullptr) {
+        // Nothing to merge and no fp32 copy asked for: the normalised rows are staged as fp16, both
+        // 16-query groups of the wavefront at once, so that all LDS writes, then all LDS reads, then all
+        // stores (16 bytes per lane, full rows) are in flight together.
+        constexpr int HS = D + 8;                 // staged row, fp16 elements
+        constexpr int LPR_H = D / 8;              // lanes per row
+        constexpr int RPP_H = 64 / LPR_H;         // rows per pass
+        static_assert(4 * FL_NQ * 16 * HS * 2 <= LDS_BYTES, "fp16 output staging must fit the tile region");
+        half_t* Oh = reinterpret_cast<half_t*>(smem) + wave * (FL_NQ * 16 * HS);
+#pragma unroll
+        for (int nq = 0; nq < FL_NQ; ++nq) {
+            const int q = q0 + (wave * FL_NQ + nq) * 16 + l16;
+            const float l = accL[nq][0];
+            const float inv_l = l > 0.f ? 1.f / l : 0.f;
+            if (lse_out != nullptr && lq == 0 && q < L)
+                lse_out[tokbase + q] = l > 0.f ? (m_run[nq] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f : -INFINITY;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+                *reinterpret_cast<half4*>(Oh + (nq * 16 + l16) * HS + 16 * t + 4 * lq) =
+                    to_half4(f32x4{accO[nq][t][0] * inv_l, accO[nq][t][1] * inv_l, accO[nq][t][2] * inv_l,
+                                   accO[nq][t][3] * inv_l});
+        }
+        __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
+        NATS_MARK(21);
+        u32x4 rows[FL_NQ * 16 / RPP_H];
+#pragma unroll
+        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass)
+            rows[pass] = *reinterpret_cast<const u32x4*>(Oh + (pass * RPP_H + lane / LPR_H) * HS + 8 * (lane % LPR_H));
+#pragma unroll
+        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
+            const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
+            if (q < L) *reinterpret_cast<u32x4*>(O_nla_h + (tokbase + q) * D + 8 * (lane % LPR_H)) = rows[pass];
+        }
+        NATS_MARK(22);
+        NATS_MARK(4);
+        return;
+    }
+
     // ---- epilogue: normalise; transpose each 16-query x D result through LDS so that every global
     //      access below is a full row segment; merge with the linear branch; store ------------------
     constexpr int LPR = D / 4;            // lanes per output row (float4 each)
