@@ -417,9 +417,10 @@ def decode_step_chunk_routed(st, q, k, v, alpha, beta, softmax_scale=None, la_sc
         o_nla = (e / e.sum()) @ st["v_cache"][:n]
     else:
         o_nla = np.zeros_like(o_la)
-    if mode == 0:
-        return o_la + o_nla, overflow
-    return w_nla * rms_norm_rows(o_nla[None], eps)[0] + w_la * rms_norm_rows(o_la[None], eps)[0], overflow
+    # the merge of the forward, on this one row (mode 0: sum; 1: Eq. 21; 2: one normalisation of the weighted sum)
+    o = combine(o_la[None], o_nla[None], mode, None if w_nla is None else np.array([w_nla]),
+                None if w_la is None else np.array([w_la]), eps)[0]
+    return o, overflow
 
 
 def decode_commit_chunk(st, m, decay_on_softmax=True):

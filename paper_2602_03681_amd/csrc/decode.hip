@@ -61,8 +61,11 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     // variant without decay on softmax tokens: alpha counts as 1 there (routing per chunk: the commit decides)
     const float a = (!CHUNK && is_softmax && freeze_on_softmax) ? 1.f : alpha[bh];
     const float b = (!CHUNK && is_softmax) ? 0.f : beta[bh];  // ... and into the state
-    const int n_old = cache_len[bh] + pos;                    // rows present, provisional ones included
-    const bool append = is_softmax && n_old < cap;
+    // Rows present, provisional ones included.  Never beyond the cache: once an open chunk has filled it, or when
+    // the caller's cache_len exceeds cap, the rows that exist are [0, cap) and later tokens are not stored.
+    const int n_want = cache_len[bh] + pos;
+    const int n_old = min(max(n_want, 0), cap);
+    const bool append = is_softmax && n_want >= 0 && n_want < cap;
     __syncthreads();
 
     // ---- phase A: state update and o_la = la_scale * S q --------------------------------

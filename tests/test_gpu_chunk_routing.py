@@ -126,28 +126,116 @@ def test_generation_with_commits_continues_the_forward(dtype, d):
 
 
 def test_generation_cache_overflow_is_flagged():
+    """A cache of 70 rows and 128 tokens of softmax chunks: token 70 is the first without a row.  Every output,
+    also those after the cache is full (they cover the 70 rows that exist), follows the oracle; the rows behind
+    the cache of the last (batch, head) pair are never touched (canary rows stay as they were)."""
+    from oracle import nats_oracle as npo
     B, H, d = 1, 2, 64
     cap = 70
     x = inputs(B, H, 128, d, "f32", 1.0, seed=70, kind="all_softmax")
     full = to_dev(x, "f32")
+    # the caches are views of larger buffers whose tails hold a canary value
+    kbuf = torch.full((B * H * cap + 64, d), 777.0, device="cuda")
+    vbuf = torch.full((B * H * cap + 64, d), 777.0, device="cuda")
+    kbuf[:B * H * cap] = 0
+    vbuf[:B * H * cap] = 0
     st = {"state": torch.zeros((B, H, d, d), device="cuda"), "state_start": torch.zeros((B, H, d, d), device="cuda"),
           "chunk_decay": torch.ones((B, H), device="cuda"), "chunk_pos": torch.zeros((B, H), dtype=torch.int32, device="cuda"),
-          "k_cache": torch.zeros((B, H, cap, d), device="cuda"), "v_cache": torch.zeros((B, H, cap, d), device="cuda"),
+          "k_cache": kbuf[:B * H * cap].view(B, H, cap, d), "v_cache": vbuf[:B * H * cap].view(B, H, cap, d),
           "cache_len": torch.zeros((B, H), dtype=torch.int32, device="cuda")}
+    ref = [[npo.decode_chunk_state(np.zeros((d, d)), np.zeros((cap, d)), np.zeros((cap, d)), 0) for _ in range(H)]
+           for _ in range(B)]
     err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
     flagged_at = None
     for t in range(128):
-        nats.hybrid_attn_decode_chunk(st, *(full[k][:, :, t].contiguous() for k in ("Q", "K", "V", "alpha", "beta")),
-                                      err_flags=err)
+        o = nats.hybrid_attn_decode_chunk(st, *(full[k][:, :, t].contiguous() for k in ("Q", "K", "V", "alpha", "beta")),
+                                          err_flags=err)
+        o = host(o)
+        for b in range(B):
+            for h in range(H):
+                o_ref, ovf = npo.decode_step_chunk_routed(ref[b][h], x["Q"][b, h, t], x["K"][b, h, t], x["V"][b, h, t],
+                                                          x["alpha"][b, h, t], x["beta"][b, h, t])
+                assert int(err[b, h]) == int(ovf), (t, b, h)
+                e = np.abs(o[b, h] - o_ref).max() / max(np.sqrt(np.mean(o_ref ** 2)), 1e-3)
+                assert e <= TOL["f32"], (t, b, h, e)
         if int(err.sum()) and flagged_at is None:
             flagged_at = t
         if (t + 1) % C == 0:
             cerr = torch.zeros_like(err)
             nats.hybrid_attn_decode_commit(st, full["mask"][:, :, t // C].contiguous(), err_flags=cerr)
+            for b in range(B):
+                for h in range(H):
+                    npo.decode_commit_chunk(ref[b][h], int(x["mask"][b, h, t // C]))
             if t + 1 == 128:
                 assert int(cerr.sum()) == B * H          # 128 rows do not fit into 70
     assert flagged_at == cap                             # token index 70 is the first one without a row
     np.testing.assert_array_equal(host(st["cache_len"]), cap)
+    assert bool((kbuf[B * H * cap:] == 777.0).all()) and bool((vbuf[B * H * cap:] == 777.0).all())
+
+
+def test_plain_decode_with_cache_len_beyond_cap_reads_only_the_cache():
+    """nats_hybrid_attn_decode given a cache_len larger than cap (as n_s of a prefill whose softmax tokens did not
+    all fit): the rows that exist are [0, cap), the output covers those, a softmax token is flagged."""
+    B, H, d, cap = 1, 2, 64, 6
+    rng = np.random.default_rng(9)
+    f = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32)).cuda()
+    state = f(B, H, d, d) * 0.1
+    kc, vc = f(B, H, cap, d), f(B, H, cap, d)
+    clen = torch.tensor([[cap + 5, cap + 1]], dtype=torch.int32, device="cuda")
+    q, k, v = f(B, H, d), f(B, H, d), f(B, H, d)
+    alpha = torch.full((B, H), 0.9, device="cuda"); beta = torch.full((B, H), 0.5, device="cuda")
+    mask = torch.tensor([[0, 1]], dtype=torch.uint8, device="cuda")
+    err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    S_ref = host(state).astype(np.float64)
+    kc_ref, vc_ref = host(kc).copy(), host(vc).copy()
+    o = nats.hybrid_attn_decode(state, kc, vc, clen, q, k, v, alpha, beta, mask, err_flags=err)
+    o_ref, ovf = c_oracle.decode(S_ref, kc_ref, vc_ref, np.full((B, H), cap, dtype=np.int32), host(q), host(k), host(v),
+                                 host(alpha), host(beta), host(mask))
+    assert rel_err(host(o), o_ref) <= TOL["f32"]
+    np.testing.assert_array_equal(host(err), [[0, 1]])
+    np.testing.assert_array_equal(host(kc), kc_ref)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_generation_with_the_single_normalisation_merge(dtype, d):
+    """nats_hybrid_attn_decode_chunk with combine_mode 2 (Section 5, ablation (iii)) and given weights: two chunks
+    generated from an empty state, every row against the oracle's chunk-routed generation step."""
+    from oracle import nats_oracle as npo
+    from gpu_util import bf16_half_ulp
+    B, H, n_new = 2, 2, 2 * C
+    cap = n_new
+    x = inputs(B, H, n_new, d, dtype, 0.5, seed=90 + d)
+    w = np.random.default_rng(91).random((2, B, H, n_new)).astype(np.float32)
+    full = to_dev(x, dtype)
+    wd = torch.from_numpy(w).cuda()
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    st = {"state": torch.zeros((B, H, d, d), device="cuda"), "state_start": torch.zeros((B, H, d, d), device="cuda"),
+          "chunk_decay": torch.ones((B, H), device="cuda"), "chunk_pos": torch.zeros((B, H), dtype=torch.int32, device="cuda"),
+          "k_cache": torch.zeros((B, H, cap, d), dtype=tdt, device="cuda"),
+          "v_cache": torch.zeros((B, H, cap, d), dtype=tdt, device="cuda"),
+          "cache_len": torch.zeros((B, H), dtype=torch.int32, device="cuda")}
+    ref = [[npo.decode_chunk_state(np.zeros((d, d)), np.zeros((cap, d)), np.zeros((cap, d)), 0) for _ in range(H)]
+           for _ in range(B)]
+    worst = 0.0
+    for t in range(n_new):
+        o = nats.hybrid_attn_decode_chunk(st, *(full[k][:, :, t].contiguous() for k in ("Q", "K", "V", "alpha", "beta")),
+                                          combine_mode=2, w_nla=wd[0, :, :, t].contiguous(), w_la=wd[1, :, :, t].contiguous())
+        o = host(o).astype(np.float64)
+        for b in range(B):
+            for h in range(H):
+                o_ref, _ = npo.decode_step_chunk_routed(ref[b][h], x["Q"][b, h, t], x["K"][b, h, t], x["V"][b, h, t],
+                                                        x["alpha"][b, h, t], x["beta"][b, h, t], mode=2,
+                                                        w_nla=float(w[0, b, h, t]), w_la=float(w[1, b, h, t]))
+                diff = np.abs(o[b, h] - o_ref)
+                if dtype == "bf16":
+                    diff = np.maximum(diff - bf16_half_ulp(o_ref), 0.0)
+                worst = max(worst, float(diff.max() / np.sqrt(np.mean(o_ref ** 2))))
+        if (t + 1) % C == 0:
+            nats.hybrid_attn_decode_commit(st, full["mask"][:, :, t // C].contiguous())
+            for b in range(B):
+                for h in range(H):
+                    npo.decode_commit_chunk(ref[b][h], int(x["mask"][b, h, t // C]))
+    assert worst <= TOL[dtype], worst
 
 
 # ---- the score layer on the device (Eq. 8-9) ------------------------------------------------------------

@@ -119,13 +119,17 @@ def test_c_oracle_matches_numpy_oracle_chunk_routed(mode):
             assert np.array_equal(b["idx"][bb, h, :n], a["idx"][bb][h])
 
 
-def test_generation_with_reroll_continues_the_chunk_routed_forward():
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_generation_with_reroll_continues_the_chunk_routed_forward(mode):
     """Prefill by the (pinned) chunk-routed forward, then token-by-token generation with provisional
-    updates and a commit per chunk must reproduce the rows of the forward over the longer sequence."""
+    updates and a commit per chunk must reproduce the rows of the forward over the longer sequence,
+    under every merge (sum, Eq. 21, the single-normalisation ablation)."""
     L0, n_new, d, C = 32, 24, 8, 8
     L = L0 + n_new
     x, mc = _inputs(L, d, 21, C, p=0.5)
-    full = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, la_scale=0.8)
+    w = np.random.default_rng(22).random((2, L))
+    full = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, la_scale=0.8, mode=mode,
+                                       w_nla=w[0], w_la=w[1])
     pre = no.hybrid_head_chunk_routed(x["Q"][:L0], x["K"][:L0], x["V"][:L0], x["alpha"][:L0], x["beta"][:L0],
                                       mc[:L0 // C], C, la_scale=0.8)
     cap = L
@@ -135,9 +139,12 @@ def test_generation_with_reroll_continues_the_chunk_routed_forward():
     st = no.decode_chunk_state(pre["S"], kc, vc, pre["n_s"])
     for t in range(L0, L):
         o, ovf = no.decode_step_chunk_routed(st, x["Q"][t], x["K"][t], x["V"][t], x["alpha"][t], x["beta"][t],
-                                             la_scale=0.8)
+                                             la_scale=0.8, mode=mode, w_nla=w[0, t], w_la=w[1, t])
         assert not ovf
         np.testing.assert_allclose(o, full["O"][t], rtol=0, atol=1e-12)
+        if mode == 2:   # the ablation's definition, written out: one RMS norm of the weighted sum
+            y = w[0, t] * full["O_nla"][t] + w[1, t] * full["O_la"][t]
+            np.testing.assert_allclose(o, y / np.sqrt(np.mean(y * y) + 1e-6), rtol=0, atol=1e-12)
         if (t + 1) % C == 0:
             no.decode_commit_chunk(st, mc[t // C])
     np.testing.assert_allclose(st["S"], full["S"], rtol=0, atol=1e-12)
