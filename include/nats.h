@@ -159,6 +159,20 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
                                     const nats_fwd_extra* extra, void* workspace, size_t workspace_bytes,
                                     void* hip_stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): nats_hybrid_attn_fwd with the workspace taken from a buffer of NATS_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's device code, one copy per GPU, held from the moment the library is loaded until the
+ * process ends.  The call allocates nothing and frees nothing (no hipMalloc, no allocating library routine); its
+ * first call on a device looks up the buffer's address (no stream operation).  Problems whose
+ * nats_hybrid_attn_fwd_workspace_bytes() exceeds NATS_NOALLOC_SCRATCH_BYTES return NATS_ERR_WORKSPACE and
+ * launch nothing.  Every call on a GPU shares that GPU's buffer: calls that overlap in time on one GPU (two
+ * streams, two threads) race; calls ordered on one stream do not.  The buffer keeps the last call's contents;
+ * no kernel needs it cleared.  Arguments and result as nats_hybrid_attn_fwd. */
+#define NATS_NOALLOC_SCRATCH_BYTES (32u << 20)
+nats_status nats_hybrid_attn_fwd_noalloc(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                         const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                         void* hip_stream);
+
 /* ------------------------------------------------------------------------- *
  * Backward pass (Section 4.2), routing per token, plain-sum merge, fp32 results
  * ------------------------------------------------------------------------- */

@@ -68,7 +68,7 @@ EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
            "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks",
-           "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd")
+           "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd", "nats_hybrid_attn_fwd_noalloc")
 
 
 def library_path() -> str:
@@ -90,6 +90,8 @@ def load_library():
     lib.nats_hybrid_attn_fwd_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams)]
     lib.nats_hybrid_attn_fwd.restype = ctypes.c_int
     lib.nats_hybrid_attn_fwd.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.nats_hybrid_attn_fwd_noalloc.restype = ctypes.c_int
+    lib.nats_hybrid_attn_fwd_noalloc.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 7 + [vp]
     lib.nats_hybrid_attn_fwd_ex.restype = ctypes.c_int
     lib.nats_hybrid_attn_fwd_ex.argtypes = ([ctypes.POINTER(FwdParams)] + [vp] * 7
                                             + [ctypes.POINTER(FwdExtra), vp, ctypes.c_size_t, vp])
@@ -251,6 +253,30 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
     _check(lib.nats_hybrid_attn_fwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
                                     _ptr(mask), _ptr(O), _ptr(workspace), workspace.numel(), _stream_ptr()))
     return O
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20   # NATS_NOALLOC_SCRATCH_BYTES of nats.h
+
+
+def hybrid_attn_fwd_noalloc(Q, K, V, alpha, beta, mask, out, C: int = 64, *, softmax_scale: float = 0.0,
+                            la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
+                            math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN,
+                            linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False) -> torch.Tensor:
+    """nats_hybrid_attn_fwd_noalloc: the forward on the library's built-in scratch buffer; the caller passes the
+    output tensor, nothing is allocated here or in the library."""
+    lib = load_library()
+    B, H, L, d = Q.shape
+    dt = Q.dtype
+    for name, t in (("Q", Q), ("K", K), ("V", V), ("out", out)):
+        _require(t, name, (B, H, L, d), dt)
+    _require(alpha, "alpha", (B, H, L), torch.float32)
+    _require(beta, "beta", (B, H, L), torch.float32)
+    _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
+                             routing, linear_op, freeze_on_softmax)
+    _check(lib.nats_hybrid_attn_fwd_noalloc(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta),
+                                            _ptr(mask), _ptr(out), _stream_ptr()))
+    return out
 
 
 def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,

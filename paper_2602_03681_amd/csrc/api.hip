@@ -196,6 +196,33 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
 
 using namespace nats;
 
+// Scratch memory of nats_hybrid_attn_fwd_noalloc: one array per GPU, part of the loaded code object, so that the
+// call needs no allocation.  Host code never passes the array's name to a kernel (on the host it is only a
+// stand-in for the symbol): the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[NATS_NOALLOC_SCRATCH_BYTES];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[64] = {};
+
+static nats_status noalloc_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        set_error("nats_hybrid_attn_fwd_noalloc: no current device (or device index beyond 63)");
+        return NATS_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            set_error("nats_hybrid_attn_fwd_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+            return NATS_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return NATS_OK;
+}
+
 extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
@@ -471,6 +498,25 @@ nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const 
                                  const float* alpha, const float* beta, const uint8_t* mask, void* O,
                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
     return nats_hybrid_attn_fwd_ex(p, Q, K, V, alpha, beta, mask, O, nullptr, workspace, workspace_bytes,
+                                   hip_stream);
+}
+
+nats_status nats_hybrid_attn_fwd_noalloc(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                         const float* alpha, const float* beta, const uint8_t* mask, void* O,
+                                         void* hip_stream) {
+    FwdPlan pl;
+    nats_status st = validate_fwd_params(p, &pl);
+    if (st != NATS_OK) return st;
+    if (pl.total > (size_t)NATS_NOALLOC_SCRATCH_BYTES) {
+        set_error("nats_hybrid_attn_fwd_noalloc: this problem needs %zu bytes of scratch memory, the built-in buffer "
+                  "holds %zu; use nats_hybrid_attn_fwd with a workspace", pl.total, (size_t)NATS_NOALLOC_SCRATCH_BYTES);
+        return NATS_ERR_WORKSPACE;
+    }
+    void* ws = nullptr;
+    st = noalloc_scratch(&ws);
+    if (st != NATS_OK) return st;
+    // nothing in the workspace has to start at zero: every kernel writes what it later reads
+    return nats_hybrid_attn_fwd_ex(p, Q, K, V, alpha, beta, mask, O, nullptr, ws, (size_t)NATS_NOALLOC_SCRATCH_BYTES,
                                    hip_stream);
 }
 

@@ -203,3 +203,14 @@ def test_binding_refuses_cpu_tensors():
     m = torch.zeros((1, 1, 64), dtype=torch.uint8)
     with pytest.raises(ValueError):
         nb.hybrid_attn_fwd(x, x, x, a, a, m)
+
+
+def test_noalloc_forward_rejects_large_problems_on_the_host(lib):
+    """The entry point without allocation checks the size against its built-in buffer before anything touches a
+    device: too large a problem is an error, and so are bad parameters."""
+    big = good_params(B=2, H=16, L=8192, d=128, dtype_code=nb.NATS_BF16)
+    assert nb.fwd_workspace_bytes(big) > nb.NOALLOC_SCRATCH_BYTES
+    assert lib.nats_hybrid_attn_fwd_noalloc(ctypes.byref(big), *([FAKE] * 7), None) == -5     # NATS_ERR_WORKSPACE
+    assert b"scratch" in lib.nats_last_error()
+    assert lib.nats_hybrid_attn_fwd_noalloc(ctypes.byref(good_params(L=100)), *([FAKE] * 7), None) == E_SHAPE
+    assert lib.nats_hybrid_attn_fwd_noalloc(None, *([FAKE] * 7), None) == E_NULL
