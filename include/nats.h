@@ -104,6 +104,11 @@ typedef struct nats_fwd_params {
                               without linear-attention decay (Section 5, Ablation Study (ii)): softmax
                               tokens, or softmax chunks as a whole, leave the carried state unchanged  */
     int32_t weight_act;    /* nats_weight_act, used where the weights come from W_out                     */
+    int32_t gdn_segments;  /* bf16 path: segments the sequence of every (batch, head) is cut into, which then
+                              run side by side (the recurrence over chunks is affine in the state, so the
+                              segments' start states are composed afterwards); 0 chooses automatically
+                              (about 256 / (B*H), at least 4 chunks per segment).  The result does not depend
+                              on it beyond rounding                                                          */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */

@@ -35,7 +35,8 @@ class FwdParams(ctypes.Structure):
                 ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
                 ("math", ctypes.c_int32), ("routing", ctypes.c_int32), ("linear_op", ctypes.c_int32),
-                ("freeze_on_softmax", ctypes.c_int32), ("weight_act", ctypes.c_int32)]
+                ("freeze_on_softmax", ctypes.c_int32), ("weight_act", ctypes.c_int32),
+                ("gdn_segments", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -155,9 +156,9 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
                     math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN, linear_op=NATS_LINEAR_GDN,
-                    freeze_on_softmax=0, weight_act=0) -> FwdParams:
+                    freeze_on_softmax=0, weight_act=0, gdn_segments=0) -> FwdParams:
     return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing,
-                     linear_op, int(freeze_on_softmax), weight_act)
+                     linear_op, int(freeze_on_softmax), weight_act, gdn_segments)
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -173,7 +174,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                        freeze_on_softmax: bool = False, w_nla=None, w_la=None,
                        W_out=None, weight_act: int = NATS_WEIGHTS_SOFTMAX, initial_state=None, Q_nla=None, K_nla=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
-                       workspace=None) -> Dict[str, torch.Tensor]:
+                       workspace=None, gdn_segments: int = 0) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
     (any of final_state, Kc, Vc, n_s, idx, cnt, O_la, O_nla, lse); the result dict always holds "O"."""
     lib = load_library()
@@ -190,7 +191,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
     _require(Q_nla, "Q_nla", (B, H, L, d), dt)
     _require(K_nla, "K_nla", (B, H, L, d), dt)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing, linear_op, freeze_on_softmax, weight_act)
+                             routing, linear_op, freeze_on_softmax, weight_act, gdn_segments)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))

@@ -117,6 +117,11 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         return NATS_ERR_SHAPE;
     }
     pl->weight_act = p->weight_act;
+    if (p->gdn_segments < 0 || p->gdn_segments > 64) {
+        set_error("gdn_segments must be between 0 (automatic) and 64 (got %d)", p->gdn_segments);
+        return NATS_ERR_SHAPE;
+    }
+    pl->gdn_segments = p->gdn_segments;
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
     pl->dtype = p->dtype;
     pl->math = p->math;
@@ -134,22 +139,22 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
     pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
-    pl->off_w = pl->off_qf = pl->off_kd = pl->off_ut = pl->off_p = pl->off_gam = pl->off_vht = pl->off_olah = pl->off_prog = 0;
+    pl->off_tf = pl->off_p = pl->off_gamv = pl->off_kdv = pl->off_gam = pl->off_seg = pl->off_vht = pl->off_olah = 0;
     pl->off_snap = 0;
     pl->off_wout = off; off = align_up(off + 2 * n_tok * 4, 256);   // weights of Eq. 21 when computed by Eq. 22
     if (!uses_chunk_path(*pl) && pl->routing == NATS_ROUTE_CHUNK) {   // chunk-start state of the fp32 recurrence
         pl->off_snap = off; off = align_up(off + (size_t)pl->BH * pl->d * pl->d * 4, 256);
     }
-    if (uses_chunk_path(*pl)) {   // fp16 per-chunk operands of the chunkwise linear branch
-        pl->off_w = off;   off = align_up(off + n_tok * pl->d * 2, 256);
-        pl->off_qf = off;  off = align_up(off + n_tok * pl->d * 2, 256);
-        pl->off_kd = off;  off = align_up(off + n_tok * pl->d * 2, 256);
-        pl->off_ut = off;  off = align_up(off + n_tok * pl->d * 2, 256);
-        pl->off_p = off;   off = align_up(off + n_tok * pl->C * 2, 256);
-        pl->off_gam = off; off = align_up(off + n_tok * 4, 256);
-        pl->off_vht = off; off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
-        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);  // fp16 hand-off between the branches
-        pl->off_prog = off; off = align_up(off + (size_t)pl->BH * PROG_STRIDE * 4, 256);  // chunk progress per (b,h), one line each
+    if (uses_chunk_path(*pl)) {   // per-chunk operands of the chunkwise linear branch
+        pl->off_tf = off;   off = align_up(off + n_tok * pl->C * 2, 256);    // T'' fp16
+        pl->off_p = off;    off = align_up(off + n_tok * pl->C * 2, 256);    // P fp16
+        pl->off_gamv = off; off = align_up(off + n_tok * 4, 256);
+        pl->off_kdv = off;  off = align_up(off + n_tok * 4, 256);
+        pl->off_gam = off;  off = align_up(off + (n_tok / pl->C) * 4, 256);
+        // start state, zero-run end state and transposed transition of every segment
+        pl->off_seg = off;  off = align_up(off + 3 * (size_t)pl->BH * gdn_segments(*pl) * pl->d * pl->d * 4, 256);
+        pl->off_vht = off;  off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
+        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 hand-off between the branches
     }
     pl->total = off;
     return NATS_OK;
@@ -227,7 +232,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 107; }
+int nats_abi_version(void) { return 108; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -348,17 +353,16 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     {
         ProfScope ps("scan_compact", stream);
         st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
-                                 uses_chunk_path(pl) ? ws + pl.off_vht : nullptr,
-                                 uses_chunk_path(pl) ? reinterpret_cast<int32_t*>(ws + pl.off_prog) : nullptr, stream);
+                                 uses_chunk_path(pl) ? ws + pl.off_vht : nullptr, stream);
     }
     if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
-        void* WF = ws + pl.off_w;
-        void* QF = ws + pl.off_qf;
-        void* KdF = ws + pl.off_kd;
-        void* UtF = ws + pl.off_ut;
+        void* TF = ws + pl.off_tf;
         void* PF = ws + pl.off_p;
+        float* gamv = reinterpret_cast<float*>(ws + pl.off_gamv);
+        float* kdv = reinterpret_cast<float*>(ws + pl.off_kdv);
         float* gamC = reinterpret_cast<float*>(ws + pl.off_gam);
+        float* seg_ws = reinterpret_cast<float*>(ws + pl.off_seg);
         void* VhT = ws + pl.off_vht;
         void* Oh = ws + pl.off_olah;   // fp16 hand-off between the two branches
         // Plain-sum merge (Section 4.1): the softmax branch runs first and hands its output over in
@@ -371,17 +375,13 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
                                       stream);
             if (st != NATS_OK) return st;
         }
-        {   // last before the recurrence, which then finds its first operands in the caches
-            ProfScope ps("gdn_chunk_prep", stream);
-            st = launch_gdn_chunk_prep(pl, Q, K, V, alpha, beta, mask, WF, QF, KdF, UtF, PF, gamC, stream);
+        {
+            ProfScope ps("gdn_chunk_inv", stream);
+            st = launch_gdn_chunk_inv(pl, Q, K, alpha, beta, mask, TF, PF, gamv, kdv, gamC, stream);
         }
         if (st != NATS_OK) return st;
-        {
-            ProfScope ps("gdn_chunk_scan", stream);
-            st = launch_gdn_chunk_scan(pl, WF, QF, KdF, UtF, PF, gamC, ex.initial_state, ex.final_state,
-                                       merge_in_scan ? nullptr : Oh, ex.O_la, merge_in_scan ? Oh : nullptr, O,
-                                       reinterpret_cast<int32_t*>(ws + pl.off_prog), stream);
-        }
+        st = launch_gdn_seg_scan(pl, Q, K, V, TF, PF, gamv, kdv, gamC, ex.initial_state, ex.final_state, seg_ws,
+                                 merge_in_scan ? nullptr : Oh, ex.O_la, merge_in_scan ? Oh : nullptr, O, stream);
         if (st != NATS_OK) return st;
         if (!merge_in_scan) {
             ProfScope ps("flash_softmax", stream);
@@ -458,7 +458,7 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     ProfChain prof_chain;   // the kernels below follow each other on one stream
     {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
         ProfScope ps("scan_compact", stream);
-        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, nullptr, nullptr, stream);
+        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, nullptr, stream);
         if (st != NATS_OK) return st;
     }
     {

@@ -1,0 +1,338 @@
+// Chunkwise Gated DeltaNet, step 1 of 2: the part of a chunk that depends neither on the running
+// state nor on the values (Section 3, Eq. 6-7 applied to the update rule of Eq. 19, with Eq. 14 /
+// Eq. 20 folded in as  b'_t = beta_t (1 - m_t)  and decay at every token).
+//
+// For one chunk of C = 64 tokens, with g_r = sum_{i<=r} log alpha_i (inside the chunk), gam_r = exp(g_r):
+//   D[r,i]  = exp(g_r - g_i)                       (i <= r)
+//   A       = strict_lower( diag(b') (K K^T . D) )
+//   T       = (I + A)^{-1}                         (unit lower triangular; fp32, blocks of 16)
+//   T''     = T diag(b')                           (stored, fp16)
+//   P       = (Q K^T) . D  (i <= r, zero above the diagonal)   (stored, fp16)
+//   gam_r,  kd_r = gam_C / gam_r,  gam_C           (stored, fp32)
+// The state-carrying kernel then needs only the raw K, Q, V beside these:
+//   U  = T'' (V - diag(gam) K S0^T)
+//   O  = diag(gam) Q S0^T + P U
+//   S1 = gam_C S0 + U^T diag(kd) K.
+// (The products T diag(b' gam) K and T diag(b') V of the usual chunkwise form are never stored: they are
+// as large as K and V themselves, and writing and re-reading them cost more than the whole recurrence.)
+//
+// Output format, fp16, "fragment-major": both matrices are written in the order in which a wavefront of
+// the state-carrying kernel loads them as MFMA operands (row of the lane, 8 contraction slots), so that
+// each of its loads is one contiguous 1 KiB.  With lane = 16 lq + l16 and token tile tw = 0..3:
+//   TF [chunk][tw][ks < 2][lane][8] = T''[r = 16 tw + l16][i = 32 ks + 8 lq + j]
+//   PF [chunk][tw][ks < 2][lane][8] = P  [r = 16 tw + l16][i = 32 ks + 8 lq + j]
+//   gamv[chunk][64], kdv[chunk][64], gamC[chunk]   (fp32)
+//
+// One block per chunk and (batch, head) (a one-dimensional grid, chunk-major), 4 wavefronts.  K K^T and
+// Q K^T run on MFMA with fp16 operands (bf16 inputs convert exactly) and fp32 accumulation.  The
+// triangular inverse is blocked 16x16: substitution inside the four diagonal blocks (one per wavefront),
+// fp32 MFMA for the blocks below them.
+#include <math.h>
+
+#include "mfma_util.h"
+#include "nats_common.h"
+
+namespace nats {
+
+constexpr int INV_THREADS = 256;
+constexpr int CH = 64;                 // chunk size
+constexpr int AT = 20;                 // fp32 row stride of a 16x16 tile of A or T in LDS (rows stay 16-byte aligned)
+constexpr int AT_TILE = 16 * AT + 16;  // floats per tile; the 16 extra shift the next tile by 16 banks
+constexpr int N_TRI = 10;              // 16x16 tiles on and below the diagonal of a 64x64 matrix
+
+// A and T are lower triangular: only the tiles (a, b), b <= a, exist, row by row
+__device__ __forceinline__ int tri_tile(int a, int b) { return ((a * (a + 1)) / 2 + b) * AT_TILE; }
+
+// LDS plan (bytes): the K tile (fp16 [64][d+8]) is dead once A and P are complete, and T takes its place.
+template <int D>
+struct InvLds {
+    static constexpr int RS = D + LDS_PAD;
+    static constexpr int tri_bytes = N_TRI * AT_TILE * 4;
+    static constexpr int k_bytes = CH * RS * 2;
+    static constexpr int r1_bytes = k_bytes > tri_bytes ? k_bytes : tri_bytes;
+    static constexpr int o_as = r1_bytes;
+    static constexpr int o_gate = o_as + tri_bytes;
+    static constexpr int bytes = o_gate + 4 * CH * 4;
+};
+
+// offset (in halves) of element (r, i) of a 64 x 64 operand in the fragment-major layout above; i a multiple of 4
+__device__ __forceinline__ int frag_off(int r, int i) {
+    return ((((r >> 4) * 2 + (i >> 5)) * 64) + 16 * ((i >> 3) & 3) + (r & 15)) * 8 + (i & 7);
+}
+
+template <int D>
+__global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ alpha,
+    const float* __restrict__ beta, const uint8_t* __restrict__ mask, int L, int chunk_mask,
+    half_t* __restrict__ TF, half_t* __restrict__ PF, float* __restrict__ gamv, float* __restrict__ kdv,
+    float* __restrict__ gamC, int BH, int linear_op, int freeze_on_softmax) {
+    using Lds = InvLds<D>;
+    constexpr int RS = Lds::RS;
+    constexpr int NPC = CH * D / 8 / INV_THREADS;   // 16-byte pieces of a [64][D] tile per thread
+    constexpr int KS_D = D / 32;
+    __shared__ __align__(16) unsigned char smem[Lds::bytes];
+    half_t* Ks = reinterpret_cast<half_t*>(smem);              // [64][RS]
+    float* Ts = reinterpret_cast<float*>(smem);                // lower tiles   (after Ks)
+    float* As = reinterpret_cast<float*>(smem + Lds::o_as);    // lower tiles
+    float* s_g2 = reinterpret_cast<float*>(smem + Lds::o_gate);  // cumulative log2-decay
+    float* s_gam = s_g2 + CH;
+    float* s_bp = s_gam + CH;
+    float* s_gdec = s_bp + CH;
+
+    const int tid = threadIdx.x;
+    const int n_chunks = L / CH;
+    // One-dimensional grid, chunk-major: all (batch, head) pairs of a chunk side by side (padded to a
+    // multiple of 8, so that a pair's blocks land on the XCD whose L2 the recurrence blocks of that pair use).
+    const int bh8 = (BH + 7) & ~7;
+    const int bh = blockIdx.x % bh8;
+    if (bh >= BH) return;
+    const int chunk = blockIdx.x / bh8;
+    const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
+    const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // ---- K tile: coalesced 16-byte loads (a [64][D] tile is contiguous in global memory) ----
+    // ---- Q: MFMA fragments straight from global memory.  Wavefront w multiplies query tile a0 = 3 - w
+    //      (wavefront 3 also tile 3); lane (l16, lq) holds, per step ks, the 8 elements
+    //      d_k = (D/4) lq + 8 ks + j of token 16 a + l16 (any contraction order does, as long as both
+    //      operands use it).
+    u32x4 rk[NPC], q0[KS_D], q1[KS_D];
+    {
+        const u32x4* Kg = reinterpret_cast<const u32x4*>(K + tok0 * D);
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) rk[i] = Kg[tid + INV_THREADS * i];
+        const int qa0 = 3 - wave, qa1 = (wave == 3) ? 3 : qa0;
+        const bf16_t* Qc = Q + (tok0 + l16) * D + (D / 4) * lq;
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            q0[ks] = *reinterpret_cast<const u32x4*>(Qc + (size_t)(16 * qa0) * D + 8 * ks);
+            q1[ks] = *reinterpret_cast<const u32x4*>(Qc + (size_t)(16 * qa1) * D + 8 * ks);
+        }
+    }
+    // ---- gates: cumulative log-decay and write strengths -------------------------------
+    if (wave == 0) {
+        // variant without decay on softmax tokens (routing per token): their alpha counts as 1
+        const float a = (freeze_on_softmax && !chunk_mask && mask[tok0 + lane]) ? 1.f : alpha[tok0 + lane];
+        float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2
+        // inclusive scan over the 64 lanes on DPP moves (no LDS): inside the 16-lane rows by shifts of 1, 2, 4, 8
+        // (a lane without a source adds 0), then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into
+        // the upper half
+        g += dpp_move<0x111>(g);
+        g += dpp_move<0x112>(g);
+        g += dpp_move<0x114>(g);
+        g += dpp_move<0x118>(g);
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x142, 0xA, 0xF, false));   // row_bcast15
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x143, 0xC, 0xF, false));   // row_bcast31
+        const float gC = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g), 63));
+        const float gam = __builtin_amdgcn_exp2f(g);
+        s_g2[lane] = g;
+        s_gam[lane] = gam;
+        // Routing per token: a softmax token writes nothing (b' = 0).  Routing per chunk: every token
+        // writes inside its chunk (the intra-chunk part is computed for every chunk), and a softmax
+        // chunk hands nothing on: its kd is zero, so the state only takes the chunk's decay.
+        const bool soft_chunk = chunk_mask && mask[gc] != 0;
+        const float kd = soft_chunk ? 0.f : __builtin_amdgcn_exp2f(gC - g);
+        s_gdec[lane] = kd;
+        s_bp[lane] = (!chunk_mask && mask[tok0 + lane]) ? 0.f : beta[tok0 + lane];
+        gamv[gc * CH + lane] = gam;
+        kdv[gc * CH + lane] = kd;
+        // the decay the recurrence applies to the state it carries over this chunk (1 for a softmax chunk in
+        // the variant without decay there: inside the chunk the decays still act on the provisional state)
+        if (lane == 63) gamC[gc] = (freeze_on_softmax && soft_chunk) ? 1.f : gam;
+    }
+#pragma unroll
+    for (int i = 0; i < NPC; ++i) {
+        const int e = tid + INV_THREADS * i;
+        const int row = e / (D / 8), c8 = e % (D / 8);
+        *reinterpret_cast<half8*>(Ks + row * RS + c8 * 8) = bf16x8_to_half8(rk[i]);
+    }
+    // the query fragments in fp16 (wavefronts 0..2 use one tile for all their products)
+    half8 hq0[KS_D], hq1[KS_D];
+#pragma unroll
+    for (int ks = 0; ks < KS_D; ++ks) hq0[ks] = bf16x8_to_half8(q0[ks]);
+    if (wave == 3) {
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) hq1[ks] = bf16x8_to_half8(q1[ks]);
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) hq1[ks] = hq0[ks];
+    }
+    __syncthreads();
+
+    // ---- K K^T -> A (LDS, fp32) and (Q K^T . D) -> P (global), lower 16x16 tiles ----------
+    const int a0 = 3 - wave, a1 = (wave == 3) ? 3 : a0;
+    {
+        // 16x16 tile products (a, b), b <= a: wavefront w takes (a0, 0), (a1, 1) [wavefront 3: (3, 3)] and, for
+        // w < 2, (a0, 2); the third slot of wavefronts 2 and 3 repeats their first product and is not stored.
+        // The three run as one straight-line sequence with separate accumulators, so that the LDS reads and
+        // MFMA chains of one fill the latencies of the others.
+        constexpr int NJ = 3;
+        const int ja[NJ] = {a0, a1, a0};
+        const int jb[NJ] = {0, (wave == 3) ? 3 : 1, (wave < 2) ? 2 : 0};
+        half_t* Pc = PF + gc * (CH * CH);
+        f32x4 accK[NJ], accP[NJ];
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            accK[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+            accP[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            const int ko = (D / 4) * lq + 8 * ks;
+            const half8 fa0 = lds_read8(Ks + (16 * a0 + l16) * RS + ko);
+            const half8 fa1 = lds_read8(Ks + (16 * a1 + l16) * RS + ko);
+            const half8 fb0 = lds_read8(Ks + (16 * jb[0] + l16) * RS + ko);
+            const half8 fb1 = lds_read8(Ks + (16 * jb[1] + l16) * RS + ko);
+            const half8 fb2 = lds_read8(Ks + (16 * jb[2] + l16) * RS + ko);
+            accK[0] = mfma16(fa0, fb0, accK[0]);   // rows: tokens of block a, cols: tokens of block b
+            accP[0] = mfma16(fb0, hq0[ks], accP[0]);   // rows: key tokens i of block b, cols: query tokens r of block a
+            accK[1] = mfma16(fa1, fb1, accK[1]);
+            accP[1] = mfma16(fb1, hq1[ks], accP[1]);
+            accK[2] = mfma16(fa0, fb2, accK[2]);
+            accP[2] = mfma16(fb2, hq0[ks], accP[2]);
+        }
+        // every gate value first, then the stores: LDS reads are not moved across LDS writes
+        float gi[NJ], gr[NJ];
+        float4 gr4[NJ], bp4[NJ], gi4[NJ];
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            gi[jj] = s_g2[16 * jb[jj] + l16];
+            gr[jj] = s_g2[16 * ja[jj] + l16];
+            gr4[jj] = *reinterpret_cast<const float4*>(s_g2 + 16 * ja[jj] + 4 * lq);
+            bp4[jj] = *reinterpret_cast<const float4*>(s_bp + 16 * ja[jj] + 4 * lq);
+            gi4[jj] = *reinterpret_cast<const float4*>(s_g2 + 16 * jb[jj] + 4 * lq);
+        }
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            if (jj == 2 && wave >= 2) continue;   // uniform per wavefront
+            const int a = ja[jj], b = jb[jj];
+            {   // A[r][i], r = 16a + 4 lq + j, i = 16b + l16
+                float* At = As + tri_tile(a, b) + (4 * lq) * AT + l16;
+                const float g4[4] = {gr4[jj].x, gr4[jj].y, gr4[jj].z, gr4[jj].w};
+                const float b4[4] = {bp4[jj].x, bp4[jj].y, bp4[jj].z, bp4[jj].w};
+                const int i = 16 * b + l16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 16 * a + 4 * lq + j;
+                    // gated linear attention (no delta rule): A = 0, so T = (I + A)^-1 = I below
+                    At[j * AT] = (i < r && linear_op == 0)
+                                     ? b4[j] * accK[jj][j] * __builtin_amdgcn_exp2f(g4[j] - gi[jj]) : 0.f;
+                }
+            }
+            {   // P[r][i], r = 16a + l16, i = 16b + 4 lq + j
+                const int r = 16 * a + l16;
+                const float g4[4] = {gi4[jj].x, gi4[jj].y, gi4[jj].z, gi4[jj].w};
+                f32x4 pv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = 16 * b + 4 * lq + j;
+                    pv[j] = (i <= r) ? accP[jj][j] * __builtin_amdgcn_exp2f(gr[jj] - g4[j]) : 0.f;
+                }
+                *reinterpret_cast<half4*>(Pc + frag_off(r, 16 * b + 4 * lq)) = to_half4(pv);
+            }
+        }
+        // the 6 tiles of P above the diagonal are zeros: (0,1) (0,2) (0,3) (1,2) (1,3) (2,3)
+        for (int z = wave; z < 6; z += 4) {
+            const int a = (0x211000 >> (4 * z)) & 15, b = (0x332321 >> (4 * z)) & 15;
+            half4 zero = {0, 0, 0, 0};
+            *reinterpret_cast<half4*>(Pc + frag_off(16 * a + l16, 16 * b + 4 * lq)) = zero;
+        }
+    }
+    __syncthreads();   // A complete; the K tile is dead from here on: its region becomes T
+
+    // ---- T = (I + A)^{-1}, unit lower triangular, by 16x16 blocks in fp32 ------------------------
+    // (a) diagonal blocks: wavefront b inverts I + A_bb by forward substitution; lane j < 16 owns
+    //     column j, row r needs rows < r of the same column
+    if (lane < 16) {
+        const float* At = As + tri_tile(wave, wave);
+        float* Tt = Ts + tri_tile(wave, wave);
+        float col[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) col[r] = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float acc = 0.f;
+#pragma unroll
+            for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {   // A[r][i] is 0 for i >= r, col[i] is 0 there too
+                const float4 a4 = *reinterpret_cast<const float4*>(At + r * AT + 4 * i4);
+                acc += a4.x * col[4 * i4] + a4.y * col[4 * i4 + 1] + a4.z * col[4 * i4 + 2] +
+                       a4.w * col[4 * i4 + 3];
+            }
+            col[r] = ((r == lane) ? 1.f : 0.f) - acc;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Tt[r * AT + lane] = col[r];
+    }
+    __syncthreads();
+    // (b) blocks below the diagonal: T_ab = -T_aa sum_{b <= k < a} A_ak T_kb.  Wavefront b owns block
+    //     column b and walks down it; products are 16x16x16 in fp32 MFMA (four 16x16x4 steps).  Step j of a
+    //     product contracts over the indices 4 lq + j (lq: the lane's quarter): then the left operand is one
+    //     16-byte read per lane, and a result tile, which a lane holds as rows 4 lq + j, is the right operand
+    //     of the next product as it sits in registers.
+    {
+        const int b = wave;
+        for (int a = b + 1; a < 4; ++a) {
+            f32x4 X = {0.f, 0.f, 0.f, 0.f};
+            for (int k = b; k < a; ++k) {
+                const float4 af = *reinterpret_cast<const float4*>(As + tri_tile(a, k) + l16 * AT + 4 * lq);
+                const float* Tkb = Ts + tri_tile(k, b) + (4 * lq) * AT + l16;
+                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, Tkb[0], X, 0, 0, 0);
+                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, Tkb[AT], X, 0, 0, 0);
+                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, Tkb[2 * AT], X, 0, 0, 0);
+                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, Tkb[3 * AT], X, 0, 0, 0);
+            }
+            const float4 tf = *reinterpret_cast<const float4*>(Ts + tri_tile(a, a) + l16 * AT + 4 * lq);
+            f32x4 Y = {0.f, 0.f, 0.f, 0.f};
+            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.x, X[0], Y, 0, 0, 0);
+            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.y, X[1], Y, 0, 0, 0);
+            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.z, X[2], Y, 0, 0, 0);
+            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.w, X[3], Y, 0, 0, 0);
+            float* Tab = Ts + tri_tile(a, b) + (4 * lq) * AT + l16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Tab[j * AT] = -Y[j];
+            __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
+        }
+    }
+    __syncthreads();   // T complete
+    // (c) T'' = T diag(b'), fp16, straight to global memory in fragment order: thread e writes the 4-element
+    //     piece e of the chunk's 8 KiB, so a wavefront's store is one contiguous run.
+    {
+        half_t* Tc = TF + gc * (CH * CH);
+        constexpr int QPT = CH * CH / 4 / INV_THREADS;   // pieces of 4 per thread
+#pragma unroll
+        for (int k = 0; k < QPT; ++k) {
+            const int e = tid + INV_THREADS * k;         // piece index: ((tw * 2 + ks) * 64 + lane') * 2 + half
+            const int ln = (e >> 1) & 63, ks = (e >> 7) & 1, tw = e >> 8;
+            const int r = 16 * tw + (ln & 15), i = 32 * ks + 8 * (ln >> 4) + 4 * (e & 1);
+            const int a = r >> 4, b = i >> 4;
+            const float4 bp = *reinterpret_cast<const float4*>(s_bp + i);
+            float4 t = {0.f, 0.f, 0.f, 0.f};
+            if (b <= a) t = *reinterpret_cast<const float4*>(Ts + tri_tile(a, b) + (r & 15) * AT + (i & 15));
+            f32x4 t4;
+            t4[0] = (i <= r) ? t.x * bp.x : 0.f;
+            t4[1] = (i + 1 <= r) ? t.y * bp.y : 0.f;
+            t4[2] = (i + 2 <= r) ? t.z * bp.z : 0.f;
+            t4[3] = (i + 3 <= r) ? t.w * bp.w : 0.f;
+            *reinterpret_cast<half4*>(Tc + 4 * e) = to_half4(t4);
+        }
+    }
+}
+
+// per chunk: TF, PF (64 * 64 fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above
+nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K, const float* alpha,
+                                 const float* beta, const uint8_t* mask, void* TF, void* PF, float* gamv,
+                                 float* kdv, float* gamC, hipStream_t st) {
+    dim3 grid((unsigned)((pl.L / CH) * ((pl.BH + 7) & ~7)));
+    if (pl.d == 64)
+        hipLaunchKernelGGL(gdn_chunk_inv_kernel<64>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
+                           (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
+                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
+    else
+        hipLaunchKernelGGL(gdn_chunk_inv_kernel<128>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
+                           (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
+                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
+    return check_launch("gdn_chunk_inv");
+}
+
+}  // namespace nats

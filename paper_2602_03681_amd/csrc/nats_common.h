@@ -170,9 +170,6 @@ struct ProfScope {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Resolved forward problem handed to the kernel launchers.
-// ints between the chunk-progress counters of two (batch, head) pairs: one 256-byte line each, so
-// that polling one counter never touches the line another block stores to
-constexpr int PROG_STRIDE = 64;
 #ifndef NATS_BWD_DKV_SEGMENTS
 #define NATS_BWD_DKV_SEGMENTS 8
 #endif
@@ -188,27 +185,28 @@ struct FwdPlan {
     int routing;   // nats_routing
     int linear_op, freeze_on_softmax;   // variants of the linear branch, see nats_fwd_params
     int weight_act;                     // nats_weight_act
+    int gdn_segments;                   // requested number of sequence segments of the chunkwise linear branch (0: automatic)
     // workspace carve-up (byte offsets)
     size_t off_cnt, off_idx, off_ns, off_kc, off_vc, off_ola, total;
     // chunkwise (MFMA) linear branch: per-chunk operands
-    size_t off_w, off_qf, off_kd, off_ut, off_p, off_gam, off_vht, off_olah, off_prog, off_snap, off_wout;
+    size_t off_tf, off_p, off_gamv, off_kdv, off_gam, off_seg, off_vht, off_olah, off_snap, off_wout;
 };
 
 // kernel launchers (one per .hip file); every pointer is a device pointer
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
                                 int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
-                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, int32_t* progress,
-                                hipStream_t st);
+                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, hipStream_t st);
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask,
                                  const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st);
-nats_status launch_gdn_chunk_prep(const FwdPlan& pl, const void* Q, const void* K, const void* V,
-                                  const float* alpha, const float* beta, const uint8_t* mask, void* WF,
-                                  void* QF, void* KdF, void* UtF, void* PF, float* gamC, hipStream_t st);
-nats_status launch_gdn_chunk_scan(const FwdPlan& pl, const void* WF, const void* QF, const void* KdF,
-                                  const void* UtF, const void* PF, const float* gamC, const float* S0,
-                                  float* S_final, void* O_la_h, float* O_la_f32, const void* O_nla_h, void* O,
-                                  int32_t* progress, hipStream_t st);
+nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K, const float* alpha,
+                                 const float* beta, const uint8_t* mask, void* TF, void* PF, float* gamv,
+                                 float* kdv, float* gamC, hipStream_t st);
+int gdn_segments(const FwdPlan& pl);   // segments per (batch, head) the chunkwise linear branch will use
+nats_status launch_gdn_seg_scan(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* TF,
+                                const void* PF, const float* gamv, const float* kdv, const float* gamC,
+                                const float* S0, float* S_final, float* seg_ws, void* O_la_h, float* O_la_f32,
+                                const void* O_nla_h, void* O, hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
                                 const void* K, const void* V,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     const uint8_t* __restrict__ mask, const T* __restrict__ K, const T* __restrict__ V, int L, int d,
     int32_t* __restrict__ cnt, int32_t* __restrict__ idx, int32_t* __restrict__ n_s, T* __restrict__ Kc,
     T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user,
-    half_t* __restrict__ VhT, int32_t* __restrict__ progress, int chunk_mask) {
+    half_t* __restrict__ VhT, int chunk_mask) {
     __shared__ int s_wave[SCAN_THREADS / 64];
     __shared__ int s_pos[SCAN_SEG];
     const int bh = blockIdx.y;
@@ -84,8 +84,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
         *reinterpret_cast<int4*>(cnt + (size_t)bh * L + t0) = make_int4(c[0], c[1], c[2], c[3]);
     }
     if (seg0 + SCAN_SEG >= L && tid == 0) n_s[bh] = before + seg_total;
-    // chunk counter the recurrence kernel publishes for its prefetch helpers: starts at zero
-    if (progress != nullptr && blockIdx.x == 0 && tid == 0) progress[bh * PROG_STRIDE] = 0;
     __syncthreads();
 
     // ---- 3. gather the K / V rows of this segment's softmax tokens ------------------------
@@ -128,18 +126,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
 
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
                                 int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
-                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, int32_t* progress,
-                                hipStream_t st) {
+                                void* Kc_user, void* Vc_user, int cap_user, void* VhT, hipStream_t st) {
     dim3 grid((pl.L + SCAN_SEG - 1) / SCAN_SEG, pl.BH);
     if (pl.dtype == NATS_BF16) {
         hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
-                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT, progress,
+                           (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT,
                            pl.routing == NATS_ROUTE_CHUNK);
     } else {
         hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
-                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT, progress,
+                           (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT,
                            pl.routing == NATS_ROUTE_CHUNK);
     }
     return check_launch("scan_compact");

@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 107   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2
+    assert lib.nats_abi_version() == 108   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc
 
 
 def good_params(**over):

@@ -425,3 +425,34 @@ def test_decay_near_zero_bf16():
     assert rel_err(host(r["O"]), ref["O"], "bf16") <= TOL["bf16"]
     assert rel_err(host(r["O_la"]), ref["O_la"]) <= TOL["bf16"]
     assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------------------------------------
+# the segmented recurrence of the bf16 path
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_segment_count_bf16(d):
+    """The chunk recurrence cut into 1..8 segments (start states composed from the segments' affine maps): 22
+    chunks, so that the last segment is ragged (and 7 segments collapse to 6), with an initial state; alpha near 1
+    in half of the cases so that the carried state matters across many segments."""
+    L = 64 * 22
+    for slow_decay in (False, True):
+        x = make_fwd_inputs(1, 3, L, d, "bf16", 0.1, seed=800 + d)
+        if slow_decay:
+            x["alpha"] = (1.0 - 0.002 * (1.0 - x["alpha"])).astype(np.float32)
+        S0 = (0.3 * np.random.default_rng(801).standard_normal((1, 3, d, d))).astype(np.float32)
+        ref = oracle_fwd(x, S0=S0, want=("S", "O_la"))
+        for n_seg in (1, 2, 3, 4, 5, 7, 8):
+            r = run_ex(x, "bf16", want=("final_state", "O_la"), initial_state=S0, gdn_segments=n_seg)
+            e = {"O": rel_err(host(r["O"]), ref["O"], "bf16"), "O_la": rel_err(host(r["O_la"]), ref["O_la"]),
+                 "S": rel_err(host(r["final_state"]), ref["S"])}
+            assert max(e.values()) <= TOL["bf16"], (d, slow_decay, n_seg, e)
+
+
+def test_segment_count_does_not_change_the_result_beyond_rounding_bf16():
+    x = make_fwd_inputs(2, 2, 2048, 128, "bf16", 0.05, seed=810)
+    base = run_ex(x, "bf16", want=("O_la",), gdn_segments=1)
+    for n_seg in (2, 8):
+        r = run_ex(x, "bf16", want=("O_la",), gdn_segments=n_seg)
+        a, b = host(r["O_la"]), host(base["O_la"])
+        assert np.abs(a - b).max() <= 2e-3 * np.sqrt(np.mean(b * b)), n_seg
