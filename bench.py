@@ -184,6 +184,8 @@ def main():
                     help="also time an MFMA-issue probe and a 256 MiB copy and report them as measured_peaks")
     ap.add_argument("--routing", choices=("token", "chunk"), default="token",
                     help="granularity of the routing mask: per token (default, the headline workload) or per chunk")
+    ap.add_argument("--gdn-segments", type=int, default=0,
+                    help="segments per (batch, head) of the linear branch's recurrence (0: the library's choice)")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
     ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
     args = ap.parse_args()
@@ -222,12 +224,14 @@ def main():
         sum_cnt = int((before + np.arange(cfg.L) % cfg.C + 1).sum())                # + own chunk, causally
     else:
         sum_cnt = int(np.cumsum(x["mask"] != 0, axis=-1, dtype=np.int64).sum())
-    params = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, routing=routing)
+    params = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, routing=routing,
+                                gdn_segments=args.gdn_segments)
     ws = torch.empty(nb.fwd_workspace_bytes(params), dtype=torch.uint8, device=dev)
     O = torch.empty_like(Q)
 
     def step():
-        nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, routing=routing, out=O, workspace=ws)
+        nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, routing=routing, out=O, workspace=ws,
+                             gdn_segments=args.gdn_segments)
 
     for _ in range(args.warmup):
         step()

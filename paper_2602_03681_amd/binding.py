@@ -235,7 +235,7 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
                     la_scale: float = 0.0, combine_mode: int = 0, rms_eps: float = 0.0,
                     math: int = NATS_MATH_AUTO, routing: int = NATS_ROUTE_TOKEN, linear_op: int = NATS_LINEAR_GDN,
                     freeze_on_softmax: bool = False, out=None,
-                    workspace=None) -> torch.Tensor:
+                    workspace=None, gdn_segments: int = 0) -> torch.Tensor:
     """nats_hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C) -> O."""
     lib = load_library()
     B, H, L, d = Q.shape
@@ -246,7 +246,7 @@ def hybrid_attn_fwd(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale: f
     _require(beta, "beta", (B, H, L), torch.float32)
     _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing, linear_op, freeze_on_softmax)
+                             routing, linear_op, freeze_on_softmax, 0, gdn_segments)
     if workspace is None:
         workspace = torch.empty(max(fwd_workspace_bytes(params), 16), dtype=torch.uint8, device=Q.device)
     O = torch.empty_like(Q) if out is None else out

@@ -17,11 +17,15 @@
 // as large as K and V themselves, and writing and re-reading them cost more than the whole recurrence.)
 //
 // Output format, fp16, "fragment-major": both matrices are written in the order in which a wavefront of
-// the state-carrying kernel loads them as MFMA operands (row of the lane, 8 contraction slots), so that
-// each of its loads is one contiguous 1 KiB.  With lane = 16 lq + l16 and token tile tw = 0..3:
-//   TF [chunk][tw][ks < 2][lane][8] = T''[r = 16 tw + l16][i = 32 ks + 8 lq + j]
-//   PF [chunk][tw][ks < 2][lane][8] = P  [r = 16 tw + l16][i = 32 ks + 8 lq + j]
+// the state-carrying kernel reads them as MFMA operands (row of the lane, 8 contraction slots), so that
+// a fragment is one contiguous 1 KiB.  With lane = 16 lq + l16 and token tile tw = 0..3:
+//   TF [chunk][tw][ks < 2][lane][s < 8] = T''[r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
+//   PF [chunk][tw][ks < 2][lane][s < 8] = P  [r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
 //   gamv[chunk][64], kdv[chunk][64], gamC[chunk]   (fp32)
+// The contraction slots of a lane stand for tokens 4 lq .. 4 lq + 3 of two neighbouring 16-token tiles:
+// that is how a lane holds two accumulator tiles of a product over tokens, so the other operand of such a
+// product (R, U of the state-carrying kernel) goes from the accumulators into the next matrix instruction
+// without leaving the registers.
 //
 // One block per chunk and (batch, head) (a one-dimensional grid, chunk-major), 4 wavefronts.  K K^T and
 // Q K^T run on MFMA with fp16 operands (bf16 inputs convert exactly) and fp32 accumulation.  The
@@ -57,7 +61,7 @@ struct InvLds {
 
 // offset (in halves) of element (r, i) of a 64 x 64 operand in the fragment-major layout above; i a multiple of 4
 __device__ __forceinline__ int frag_off(int r, int i) {
-    return ((((r >> 4) * 2 + (i >> 5)) * 64) + 16 * ((i >> 3) & 3) + (r & 15)) * 8 + (i & 7);
+    return ((((r >> 4) * 2 + (i >> 5)) * 64) + 16 * ((i >> 2) & 3) + (r & 15)) * 8 + 4 * ((i >> 4) & 1) + (i & 3);
 }
 
 template <int D>
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
         for (int k = 0; k < QPT; ++k) {
             const int e = tid + INV_THREADS * k;         // piece index: ((tw * 2 + ks) * 64 + lane') * 2 + half
             const int ln = (e >> 1) & 63, ks = (e >> 7) & 1, tw = e >> 8;
-            const int r = 16 * tw + (ln & 15), i = 32 * ks + 8 * (ln >> 4) + 4 * (e & 1);
+            const int r = 16 * tw + (ln & 15), i = 32 * ks + 16 * (e & 1) + 4 * (ln >> 4);
             const int a = r >> 4, b = i >> 4;
             const float4 bp = *reinterpret_cast<const float4*>(s_bp + i);
             float4 t = {0.f, 0.f, 0.f, 0.f};

@@ -16,17 +16,22 @@
 // A (batch, head) with L / 64 chunks then costs about 2 L / (64 n_seg) dependent steps instead of L / 64, for
 // 2 (n_seg - 2) / n_seg more state products.
 //
-// One block = one (batch, head, segment), 8 wavefronts, all d_v rows: wavefront (tw, vh) owns token tile tw
-// (16 tokens) and half vh of the d_v columns in the products over d_k and over tokens, and a quarter of d_k
-// by half of d_v of the state.  The state lives transposed, S^T [d_k x d_v], as fp32 MFMA accumulators and
-// never leaves registers in fp32; an fp16 copy S[v][d_k] in LDS is the operand of the products that read it.
-// Every operand that comes from memory (K, Q, V rows, T'', P) is loaded as the MFMA fragment of the
-// wavefront that uses it, straight from global memory, one chunk ahead; LDS carries the exchanged copies
-// S, R, U and the transposed K.  Transpositions run on the matrix cores: a product with a 0/1 selector
-// matrix hands a row-major fragment back in the accumulator layout, exactly (K^T for the state update, V
-// added onto - gam K S0^T).  The output is computed transposed (S0 Q^T, U^T P^T): an accumulator then holds
-// four consecutive d_v of one token, which is the layout O is stored in.
-// Per chunk: three block barriers (R ready, U ready, S ready).
+// One block = one (batch, head, segment), 8 wavefronts in two groups.
+//   The four STATE wavefronts each own a quarter of the d_v rows and everything that is indexed by d_v: their
+// slice of the state (S^T tiles in fp32 MFMA accumulators), of R, U and of the output.  The rows of S never mix,
+// so the whole dependent chain  S0 -> K S0^T -> R -> U = T'' R -> S1  of a slice runs inside one wavefront, and
+// every link stays in registers: a lane holds two 16-row accumulator tiles of a product as rows 4 lq .. 4 lq + 3
+// of each, and the contraction slots of the next product's operand are defined as exactly those 8 rows (the
+// operands that come from memory are laid out to match: K, Q rows by the block's other group, T'' and P by the
+// inversion kernel).  No barrier and no LDS round trip stands inside the chain.
+//   The four STAGING wavefronts prepare what all d_v slices share, one chunk ahead, in a double-buffered LDS
+// set: the K and Q tiles (contiguous loads, converted to fp16 once, columns permuted into the slot order above),
+// K^T scaled by kd (transposed on the matrix cores: a product with a 0/1 selector hands a row-major fragment
+// back in the accumulator layout, exactly), T'', P and the gates.  They also merge and store the output rows,
+// which the state wavefronts leave in an LDS tile (computed transposed, S0 Q^T and U^T P^T, so that a lane
+// holds four consecutive d_v of a token): whole rows of 2 d bytes go out.
+//   Two block barriers per chunk: one before the output tile is overwritten, one when the next operand set is
+// complete.
 #include <algorithm>
 
 #include "mfma_util.h"
@@ -35,18 +40,27 @@
 namespace nats {
 
 constexpr int SEG_THREADS = 512;
-constexpr int SC = 64;   // chunk size
+constexpr int SEG_GROUP = 256;   // threads of a group (state / staging)
+constexpr int SC = 64;           // chunk size
 
 template <int D>
 struct SegLds {
-    static constexpr int SS = D + LDS_PAD;     // halves per row of the state copy   S [d_v][SS]
-    static constexpr int TS = SC + LDS_PAD;    // halves per row of a token-contraction copy: R, U [d_v][TS], Kd^T [d_k][TS]
-    static constexpr int o_S = 0;
-    static constexpr int o_R = o_S + D * SS;
-    static constexpr int o_U = o_R + D * TS;
-    static constexpr int o_K = o_U + D * TS;
-    static constexpr int n_half = o_K + D * TS;
+    static constexpr int SS = D + LDS_PAD;     // halves per row of the K, Q tiles [64][SS] and of the output tile
+    static constexpr int TS = SC + LDS_PAD;    // halves per row of Kd^T [d_k][TS]
+    // one operand set (halves)
+    static constexpr int o_Kt = 0;
+    static constexpr int o_Qt = o_Kt + SC * SS;
+    static constexpr int o_T = o_Qt + SC * SS;         // T'' in fragment order, 64 x 64
+    static constexpr int o_P = o_T + SC * SC;          // P in fragment order, times la_scale
+    static constexpr int o_G = o_P + SC * SC;          // fp32: gam[64], gam_C at [64], kd[64] from [68]
+    static constexpr int G_KD = 68;
+    static constexpr int SET = o_G + 2 * 132;          // 132 floats
+    static constexpr int o_Kd = 2 * SET;               // Kd^T [d_k][TS]: written and read inside one step
+    static constexpr int o_Out = o_Kd + D * TS;        // output tile [64][SS], fp16
+    static constexpr int n_half = o_Out + SC * SS;
     static constexpr int bytes = n_half * 2;
+    static_assert(bytes <= 160 * 1024, "one block per CU");
+    static_assert(SET % 8 == 0, "sets stay 16-byte aligned");
 };
 
 // Block roles (uniform per block)
@@ -85,27 +99,452 @@ __device__ __forceinline__ half8 cvt_bf16x8(u32x4 u) {
     return h;
 }
 
-template <int D>
-__global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs<D> a) {
+// two accumulator tiles (rows 4 lq + j of each) -> the 8 contraction slots of one operand fragment
+__device__ __forceinline__ half8 pack_tiles(f32x4 lo, f32x4 hi) {
+    half8 h;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        h[j] = (half_t)lo[j];
+        h[4 + j] = (half_t)hi[j];
+    }
+    return h;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// STATE wavefronts.  ROLE and F32OUT are compile-time: the chunk loop is straight-line code.
+// Index conventions of a lane (l16 = lane % 16, lq = lane / 16):
+//   accumulator tile      : rows 4 lq + j (j < 4), column l16
+//   operand fragment      : row / column l16, contraction slots s < 8 of step ks:
+//                           index 32 ks + 16 (s / 4) + 4 lq + s % 4   (d_k, or token)
+// ------------------------------------------------------------------------------------------------------------
+template <int D, int ROLE, bool F32OUT>
+__device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
     using Lds = SegLds<D>;
     constexpr int SS = Lds::SS, TS = Lds::TS;
     constexpr int KS_D = D / 32;      // contraction steps over d_k
-    constexpr int NVT = D / 32;       // 16-wide d_v tiles of one wavefront (half of d_v)
-    constexpr int KS_V = D / 64;      // 32-wide steps over this wavefront's d_v half, for the V fragments
-    constexpr int MS = D / 64;        // 16-row d_k tiles of S^T owned by one wavefront
-    extern __shared__ __align__(16) unsigned char seg_smem[];
-    half_t* Ss = reinterpret_cast<half_t*>(seg_smem) + Lds::o_S;
-    half_t* Rs = reinterpret_cast<half_t*>(seg_smem) + Lds::o_R;
-    half_t* Us = reinterpret_cast<half_t*>(seg_smem) + Lds::o_U;
-    half_t* Kds = reinterpret_cast<half_t*>(seg_smem) + Lds::o_K;
+    constexpr int NDT = D / 16;       // 16-row d_k tiles of S^T
+    constexpr int NVT = D / 64;       // 16-wide d_v tiles of one wavefront (a quarter of d_v)
+    constexpr bool HAS_OUT = ROLE == ROLE_OUT, HAS_V = ROLE != ROLE_ACC_E;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tw = wave & 3, vh = wave >> 2;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..3
     const int l16 = lane & 15, lq = lane >> 4;
-    const int vbase = vh * (D / 2);
+    const int vbase = wave * (D / 4);
     const int n_chunks = a.L / SC;
+    const int c_begin = seg * a.seg_len, c_end = min(c_begin + a.seg_len, n_chunks);
+    const size_t seg_slot = (size_t)bh * a.n_seg + seg;
+    const float* init = nullptr;           // state the segment starts from (nullptr: zero, or the unit rows)
+    float* dest = nullptr;                 // where its end state goes
+    if (ROLE == ROLE_OUT) {
+        init = seg == 0 ? (a.S0 ? a.S0 + (size_t)bh * D * D : nullptr) : a.S_start + seg_slot * D * D;
+        if (seg == a.n_seg - 1) dest = a.S_final ? a.S_final + (size_t)bh * D * D : nullptr;
+        else if (seg == 0) dest = a.S_start + (seg_slot + 1) * D * D;   // the later start states come from the fix-up
+    } else if (ROLE == ROLE_ACC_S) {
+        dest = a.Nbuf + seg_slot * D * D;
+    } else {
+        dest = a.MTbuf + seg_slot * D * D;
+    }
 
+    // ---- state: S^T tiles (rows d_k, cols v) as fp32 accumulators, and its fp16 operand form ----
+    f32x4 accS[NDT][NVT];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) {
+            const int dk = 16 * dt + 4 * lq, v = vbase + 16 * vt + l16;
+            if (ROLE == ROLE_ACC_E) {   // unit rows: "v" counts the rows e of the identity
+                accS[dt][vt] = f32x4{v == dk ? 1.f : 0.f, v == dk + 1 ? 1.f : 0.f, v == dk + 2 ? 1.f : 0.f,
+                                     v == dk + 3 ? 1.f : 0.f};
+            } else if (init != nullptr) {
+                const float4 x = *reinterpret_cast<const float4*>(init + (size_t)v * D + dk);
+                accS[dt][vt] = f32x4{x.x, x.y, x.z, x.w};
+            } else {
+                accS[dt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    half8 sfrag[NVT][KS_D];   // S[v = l16][d_k slots]: B operand of K S0^T, A operand of S0 Q^T
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) sfrag[vt][ks] = pack_tiles(accS[2 * ks][vt], accS[2 * ks + 1][vt]);
+
+    // 0/1 selector fragments: B operand whose column n picks slot n (lo) or 16 + n (hi) of a row-major fragment
+    // (there the slots of a lane are the 8 consecutive indices 8 lq + j)
+    half8 isel[2];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) isel[hf][j] = (8 * lq + j == 16 * hf + l16) ? (half_t)1.f : (half_t)0.f;
+
+    // V rows of the four token tiles, the 32 columns that hold this wavefront's slice: row-major fragments
+    // straight from global memory, one chunk ahead
+    const int vb32 = vbase & ~31, vhf = (vbase & 31) >> 4;   // d = 64: two wavefronts share a 32-column group
+    u32x4 vraw[4];
+    const size_t tokb = (size_t)bh * a.L;
+    const uint32_t v_off = (uint32_t)(l16 * D + vb32 + 8 * lq);
+    auto load_v = [&](int c) __attribute__((always_inline)) {
+        if (!HAS_V) return;
+        const bf16_t* Vc = a.V + (tokb + (size_t)c * SC) * D;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) vraw[tt] = *reinterpret_cast<const u32x4*>(Vc + v_off + (uint32_t)(16 * tt * D));
+    };
+    const float gated_off = a.gated ? 0.f : 1.f;   // without the delta rule the state does not enter R
+    half_t* OutT = lds + Lds::o_Out;
+    half_t* Kd = lds + Lds::o_Kd;
+    // Kd^T[d_k][token slots] = kd_tok K[tok][d_k] is made here too, from the K tile: a product with a 0/1 selector
+    // hands 16 d_k columns of a token tile's K fragment back as an accumulator tile (rows tok 4 lq + j, col d_k),
+    // exactly; those are 4 consecutive slots of a Kd^T row.  The (contraction step, column half) pairs are dealt
+    // to the four wavefronts: d = 128: step = wavefront, both halves; d = 64: step = wavefront % 2, half = wavefront / 2.
+    constexpr int NTR = KS_D / 2;                   // pairs per wavefront and token tile
+    const int tr_ks = KS_D == 4 ? wave : (wave & 1);
+    half8 iselp[NTR];                               // selector for a fragment in slot order: column n <- d_k 16 hf + n
+    int tr_hf[NTR];
+#pragma unroll
+    for (int i = 0; i < NTR; ++i) {
+        tr_hf[i] = KS_D == 4 ? i : (wave >> 1);
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+            iselp[i][s8] = (lq == (l16 >> 2) && s8 == 4 * tr_hf[i] + (l16 & 3)) ? (half_t)1.f : (half_t)0.f;
+    }
+
+    load_v(c_begin);
+    __syncthreads();   // the first operand set is complete
+
+    for (int c = c_begin; c < c_end; ++c) {
+        const int cn = min(c + 1, c_end - 1);   // the tail re-loads the last chunk: loads stay unconditional
+        const half_t* set = lds + ((c - c_begin) & 1) * Lds::SET;
+        const half_t* Kt = set + Lds::o_Kt;
+        const half_t* Qt = set + Lds::o_Qt;
+        const half8* Tt = reinterpret_cast<const half8*>(set + Lds::o_T);
+        const half8* Pt = reinterpret_cast<const half8*>(set + Lds::o_P);
+        const float* Gt = reinterpret_cast<const float*>(set + Lds::o_G);
+
+        half8 vf[4];
+        if (HAS_V) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) vf[tt] = cvt_bf16x8(vraw[tt]);
+        }
+        load_v(cn);
+
+        // ---- K S0^T -> R, and S0 Q^T, two token tiles (one contraction step of the next product) at a time ----
+        f32x4 accO[NVT][4];
+        half8 rfrag[2][NVT];      // R[token slots][v = l16]: B operand of T'' R
+#pragma unroll
+        for (int kp = 0; kp < 2; ++kp) {
+            f32x4 accR[2][NVT];
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                const int tt = 2 * kp + t2;
+                half8 kf[KS_D], qf[KS_D];
+#pragma unroll
+                for (int ks = 0; ks < KS_D; ++ks) kf[ks] = lds_read8(Kt + (16 * tt + l16) * SS + 32 * ks + 8 * lq);
+                if (HAS_OUT) {
+#pragma unroll
+                    for (int ks = 0; ks < KS_D; ++ks) qf[ks] = lds_read8(Qt + (16 * tt + l16) * SS + 32 * ks + 8 * lq);
+                }
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) {
+                    accR[t2][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (HAS_OUT) accO[vt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int ks = 0; ks < KS_D; ++ks)
+#pragma unroll
+                    for (int vt = 0; vt < NVT; ++vt) {
+                        accR[t2][vt] = mfma16(kf[ks], sfrag[vt][ks], accR[t2][vt]);                 // rows tok, col v
+                        if (HAS_OUT) accO[vt][tt] = mfma16(sfrag[vt][ks], qf[ks], accO[vt][tt]);   // rows v, col tok
+                    }
+                {   // this wavefront's share of Kd^T for token tile tt
+                    const half8 kt = lds_read8(Kt + (16 * tt + l16) * SS + 32 * tr_ks + 8 * lq);
+                    const float4 k4 = *reinterpret_cast<const float4*>(Gt + Lds::G_KD + 16 * tt + 4 * lq);
+                    const float kk[4] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+                    for (int i = 0; i < NTR; ++i) {
+                        f32x4 t = mfma16(kt, iselp[i], f32x4{0.f, 0.f, 0.f, 0.f});   // col d_k = 32 tr_ks + 16 hf + l16
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) t[j] *= kk[j];
+                        *reinterpret_cast<half4*>(Kd + (32 * tr_ks + 16 * tr_hf[i] + l16) * TS + 32 * kp + 8 * lq + 4 * t2) =
+                            to_half4_hw(t);
+                    }
+                }
+                // R = V - gam (K S0^T): the gate per row, then V added by the selector product (exactly)
+                const float4 g4 = *reinterpret_cast<const float4*>(Gt + 16 * tt + 4 * lq);
+                const float gg[4] = {g4.x * gated_off, g4.y * gated_off, g4.z * gated_off, g4.w * gated_off};
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) accR[t2][vt][j] *= -gg[j];
+                    if (HAS_V) accR[t2][vt] = mfma16(vf[tt], isel[vhf + vt], accR[t2][vt]);
+                }
+            }
+#pragma unroll
+            for (int vt = 0; vt < NVT; ++vt) rfrag[kp][vt] = pack_tiles(accR[0][vt], accR[1][vt]);
+        }
+
+        // ---- U = T'' R (T'' lower triangular: token tiles 0, 1 need the first contraction step only) ----
+        half8 ufrag[2][NVT];      // U[token slots][v = l16]: B operand of Kd^T U, A operand of U^T P^T
+#pragma unroll
+        for (int kp = 0; kp < 2; ++kp) {
+            f32x4 accU[2][NVT];
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                const int tt = 2 * kp + t2;
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) accU[t2][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks <= kp; ++ks) {
+                    const half8 tf = Tt[(tt * 2 + ks) * 64 + lane];
+#pragma unroll
+                    for (int vt = 0; vt < NVT; ++vt) accU[t2][vt] = mfma16(tf, rfrag[ks][vt], accU[t2][vt]);   // rows r, col v
+                }
+            }
+#pragma unroll
+            for (int vt = 0; vt < NVT; ++vt) ufrag[kp][vt] = pack_tiles(accU[0][vt], accU[1][vt]);
+        }
+
+        // ---- output rows: gam (S0 Q^T) + U^T P^T, into the LDS tile (la_scale rides on the gate and on P) ----
+        if (HAS_OUT) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const float go = Gt[16 * tt + l16] * a.la_scale;
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) accO[vt][tt][j] *= go;
+#pragma unroll
+                for (int ks = 0; ks <= tt / 2; ++ks) {
+                    const half8 pf = Pt[(tt * 2 + ks) * 64 + lane];
+#pragma unroll
+                    for (int vt = 0; vt < NVT; ++vt) accO[vt][tt] = mfma16(ufrag[ks][vt], pf, accO[vt][tt]);   // rows v, col r
+                }
+            }
+        }
+        __syncthreads();   // the staging group has taken the previous chunk's rows out of the output tile; Kd^T complete
+        if (HAS_OUT) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) {
+                    // this lane: token 16 tt + l16, d_v vbase + 16 vt + 4 lq + j
+                    *reinterpret_cast<half4*>(OutT + (16 * tt + l16) * SS + vbase + 16 * vt + 4 * lq) = to_half4_hw(accO[vt][tt]);
+                    if (F32OUT)
+                        *reinterpret_cast<float4*>(a.O_la_f32 + (tokb + (size_t)c * SC + 16 * tt + l16) * D + vbase + 16 * vt + 4 * lq) =
+                            make_float4(accO[vt][tt][0], accO[vt][tt][1], accO[vt][tt][2], accO[vt][tt][3]);
+                }
+        }
+
+        // ---- S1^T = gam_C S0^T + Kd^T U, and its operand form for the next chunk ----
+        const float gC = Gt[64];
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            half8 af[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) af[ks] = lds_read8(Kd + (16 * dt + l16) * TS + 32 * ks + 8 * lq);
+#pragma unroll
+            for (int vt = 0; vt < NVT; ++vt) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) accS[dt][vt][j] *= gC;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) accS[dt][vt] = mfma16(af[ks], ufrag[ks][vt], accS[dt][vt]);   // rows d_k, col v
+            }
+        }
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks) sfrag[vt][ks] = pack_tiles(accS[2 * ks][vt], accS[2 * ks + 1][vt]);
+        __syncthreads();   // the next operand set and this chunk's output tile are complete
+    }
+
+    // ---- end state ----
+    if (dest != nullptr) {
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int vt = 0; vt < NVT; ++vt) {
+                const int dk = 16 * dt + 4 * lq, v = vbase + 16 * vt + l16;
+                if (ROLE == ROLE_ACC_E) {
+                    // M[i = unit row][j = d_k] as the fp16 pair the fix-up multiplies with (a plane of leading
+                    // halves, then a plane of remainders), each plane in the order its wavefronts load it:
+                    // [j / 16][i / 32][lane = 16 ((i % 32) / 8) + j % 16][i % 8]
+                    half_t* mh = reinterpret_cast<half_t*>(dest);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float x = accS[dt][vt][j];
+                        const half_t hi = f32_to_half_sat(x);
+                        const int jj = dk + j;
+                        const size_t o = ((size_t)((jj >> 4) * KS_D + (v >> 5)) * 64 + 16 * ((v & 31) >> 3) + (jj & 15)) * 8 +
+                                         (v & 7);
+                        mh[o] = hi;
+                        mh[(size_t)D * D + o] = (half_t)(x - (float)hi);
+                    }
+                } else {
+                    *reinterpret_cast<float4*>(dest + (size_t)v * D + dk) =
+                        make_float4(accS[dt][vt][0], accS[dt][vt][1], accS[dt][vt][2], accS[dt][vt][3]);
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// STAGING wavefronts: the operand set of the next chunk, and the previous chunk's output rows.
+//   MERGE: add the softmax branch's fp16 rows and store O (bf16); otherwise store the linear branch's rows as fp16
+// ------------------------------------------------------------------------------------------------------------
+// what a staging thread carries from memory to the next operand set
+template <int D, bool HAS_OUT>
+struct StageRegs {
+    static constexpr int NPC = SC * D / 8 / SEG_GROUP;     // 16-byte pieces of a [64][D] tile per thread
+    static constexpr int NTP = SC * SC / 8 / SEG_GROUP;    // ... of a 64 x 64 fp16 matrix
+    u32x4 kp[NPC], qp[NPC];        // pieces of the K and Q tiles (contiguous)
+    half8 tp[NTP], pp[NTP];        // pieces of T'' and P (already in fragment order)
+    float g0, g1;                  // thread t < 64: gam and kd of token t; thread 64: gam_C
+    static constexpr int N_LOADS = NPC * (HAS_OUT ? 2 : 1) + NTP * (HAS_OUT ? 2 : 1) + 2;
+    // load number i of chunk c (one at a time, so that a step can spread them between its other work: issued
+    // in a burst they queue in the CU's vector-memory path and the wavefront stalls until all are accepted)
+    __device__ __forceinline__ void load_piece(int i, const SegArgs<D>& a, size_t cb, size_t ch, int pt) {
+        if (i < NPC) { kp[i] = reinterpret_cast<const u32x4*>(a.K + cb)[pt + SEG_GROUP * i]; return; }
+        i -= NPC;
+        if (HAS_OUT) {
+            if (i < NPC) { qp[i] = reinterpret_cast<const u32x4*>(a.Q + cb)[pt + SEG_GROUP * i]; return; }
+            i -= NPC;
+        }
+        if (i < NTP) { tp[i] = reinterpret_cast<const half8*>(a.TF + ch * (size_t)(SC * SC))[pt + SEG_GROUP * i]; return; }
+        i -= NTP;
+        if (HAS_OUT) {
+            if (i < NTP) { pp[i] = reinterpret_cast<const half8*>(a.PF + ch * (size_t)(SC * SC))[pt + SEG_GROUP * i]; return; }
+            i -= NTP;
+        }
+        if (i == 0) g0 = pt < SC ? a.gamv[ch * SC + pt] : a.gamC[ch];
+        else g1 = a.kdv[ch * SC + (pt & (SC - 1))];
+    }
+};
+
+// ------------------------------------------------------------------------------------------------------------
+// STAGING wavefronts: the operand set of the next chunk, and the current chunk's output rows.
+//   MERGE: add the softmax branch's fp16 rows and store O (bf16); otherwise store the linear branch's rows as fp16
+// ------------------------------------------------------------------------------------------------------------
+template <int D, int ROLE, bool MERGE>
+__device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
+    using Lds = SegLds<D>;
+    constexpr int SS = Lds::SS;
+    constexpr bool HAS_OUT = ROLE == ROLE_OUT;
+    using Regs = StageRegs<D, HAS_OUT>;
+    constexpr int NPC = Regs::NPC, NTP = Regs::NTP;
+    const int pt = threadIdx.x - SEG_GROUP;
+    const int n_chunks = a.L / SC;
+    const int c_begin = seg * a.seg_len, c_end = min(c_begin + a.seg_len, n_chunks);
+    const size_t tokb = (size_t)bh * a.L;
+    const size_t chb = (size_t)bh * n_chunks;
+    const half_t lah = (half_t)a.la_scale;
+    const half8 la8 = {lah, lah, lah, lah, lah, lah, lah, lah};
+    half_t* OutT = lds + Lds::o_Out;
+
+    // The operand set is written in N_WRITE pieces and the loads of the following chunk go out between them:
+    // issued in one burst, the loads queue in the CU's vector-memory path (a KiB takes it 16 cycles) and the
+    // wavefront stands still until all are accepted, although nothing it does next depends on them.
+    constexpr int N_WRITE = NPC + 1;
+    auto write_piece = [&](int i, const Regs& r, half_t* set) __attribute__((always_inline)) {
+        if (i < NPC) {
+            // K, Q tiles: fp16, the 32 columns of a contraction step permuted into slot order: column 8 q + j of
+            // the step goes to position 16 (q % 2) + 8 (j / 4) + 4 (q / 2) + j % 4, i.e. a piece is stored as two halves
+            const int e = pt + SEG_GROUP * i, row = e / (D / 8), c8 = e % (D / 8);
+            const int pos = 32 * (c8 >> 2) + 16 * (c8 & 1) + 4 * ((c8 >> 1) & 1);
+            const half8 hk = cvt_bf16x8(r.kp[i]);
+            *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos) = half4{hk[0], hk[1], hk[2], hk[3]};
+            *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos + 8) = half4{hk[4], hk[5], hk[6], hk[7]};
+            if (HAS_OUT) {
+                const half8 hq = cvt_bf16x8(r.qp[i]);
+                *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos) = half4{hq[0], hq[1], hq[2], hq[3]};
+                *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos + 8) = half4{hq[4], hq[5], hq[6], hq[7]};
+            }
+            return;
+        }
+#pragma unroll
+        for (int k = 0; k < NTP; ++k) {
+            reinterpret_cast<half8*>(set + Lds::o_T)[pt + SEG_GROUP * k] = r.tp[k];
+            if (HAS_OUT) reinterpret_cast<half8*>(set + Lds::o_P)[pt + SEG_GROUP * k] = r.pp[k] * la8;
+        }
+        float* G = reinterpret_cast<float*>(set + Lds::o_G);
+        if (pt <= SC) G[pt] = r.g0;
+        if (pt < SC) G[Lds::G_KD + pt] = r.g1;
+    };
+    auto write_set = [&](const Regs& r, half_t* set) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < N_WRITE; ++i) write_piece(i, r, set);
+    };
+    u32x4 onla[NPC];               // the softmax branch's rows of the chunk whose output is merged next
+    auto load_onla = [&](int c) __attribute__((always_inline)) {
+        if (!MERGE) return;
+        const u32x4* Og = reinterpret_cast<const u32x4*>(a.O_nla_h + (tokb + (size_t)c * SC) * D);
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) onla[i] = Og[pt + SEG_GROUP * i];
+    };
+    // rows of chunk c out of the output tile: merge and store, 16 bytes per lane, whole rows contiguous
+    auto store_rows = [&](int c) __attribute__((always_inline)) {
+        if (!HAS_OUT) return;
+        const size_t ob = (tokb + (size_t)c * SC) * D;
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            const int e = pt + SEG_GROUP * i, row = e / (D / 8), c8 = e % (D / 8);
+            const half8 o = lds_read8(OutT + row * SS + 8 * c8);
+            if (MERGE) {   // plain-sum merge (Section 4.1)
+                const half8 h = __builtin_bit_cast(half8, onla[i]);
+                u32x4 w;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    w[k] = pack_bf16x2((float)o[2 * k] + (float)h[2 * k], (float)o[2 * k + 1] + (float)h[2 * k + 1]);
+                reinterpret_cast<u32x4*>(a.O + ob)[e] = w;
+            } else {       // the linear branch's rows as fp16 for the softmax kernel's merge epilogue
+                reinterpret_cast<half8*>(a.O_la_h + ob)[e] = o;
+            }
+        }
+    };
+    auto load_all = [&](Regs& r, int c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < Regs::N_LOADS; ++i) r.load_piece(i, a, (tokb + (size_t)c * SC) * D, chb + c, pt);
+    };
+
+    // One step: the registers `cur` hold chunk c + 1; it goes into the LDS set the state group reads next, while
+    // chunk c + 2 is asked for into `nxt`.
+    auto step = [&](int c, const Regs& cur, Regs& nxt) __attribute__((always_inline)) {
+        half_t* set = lds + (((c - c_begin) & 1) ^ 1) * Lds::SET;
+        const int c2 = min(c + 2, c_end - 1);
+        constexpr int PER = (Regs::N_LOADS + N_WRITE - 1) / N_WRITE;   // loads per written piece
+        int li = 0;
+#pragma unroll
+        for (int i = 0; i < N_WRITE; ++i) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < PER; ++k, ++li)
+                if (li < Regs::N_LOADS) nxt.load_piece(li, a, (tokb + (size_t)c2 * SC) * D, chb + c2, pt);
+            __builtin_amdgcn_sched_barrier(0);
+            write_piece(i, cur, set);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_onla(c);
+        __syncthreads();   // (the state group overwrites the output tile after this)
+        __syncthreads();   // the output tile of chunk c is complete
+        store_rows(c);
+    };
+
+    Regs ra, rb;
+    load_all(ra, c_begin);
+    load_all(rb, min(c_begin + 1, c_end - 1));
+    write_set(ra, lds);
+    __syncthreads();   // the first operand set is complete
+    // two steps per trip: the two register sets swap roles without a copy
+    int c = c_begin;
+    for (; c + 2 <= c_end; c += 2) {
+        step(c, rb, ra);
+        step(c + 1, ra, rb);
+    }
+    if (c < c_end) step(c, rb, ra);
+}
+
+template <int D, bool MERGE, bool F32OUT>
+__global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs<D> a) {
+    extern __shared__ __align__(16) unsigned char seg_smem[];
+    half_t* lds = reinterpret_cast<half_t*>(seg_smem);
+    fp16_saturate_on();   // conversions to fp16 clamp to the fp16 range (see to_half4_hw)
     // ---- block -> (batch*head, role, segment).  Blocks with ids congruent modulo 8 share an XCD and its L2:
     //      the blocks of one (batch, head) are given such ids (the two blocks of a middle segment read the
     //      same K and T'').
@@ -115,271 +554,20 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     const int bh = (slot / per_bh) * 8 + xcd;
     if (bh >= a.BH) return;
     const int sub = slot % per_bh;
+    const bool staging = threadIdx.x >= SEG_GROUP;   // uniform per wavefront
     int role, seg;
-    if (a.pass == 1) {
-        role = sub == 0 ? ROLE_OUT : (((sub - 1) & 1) ? ROLE_ACC_E : ROLE_ACC_S);
-        seg = sub == 0 ? 0 : 1 + ((sub - 1) >> 1);
-    } else {
-        role = ROLE_OUT;
-        seg = 1 + sub;
-    }
-    const bool has_out = role == ROLE_OUT, has_v = role != ROLE_ACC_E;
-    const int c_begin = seg * a.seg_len, c_end = min(c_begin + a.seg_len, n_chunks);
-    const size_t seg_slot = (size_t)bh * a.n_seg + seg;
-    const float* init = nullptr;           // state the segment starts from (nullptr: zero, or the unit rows)
-    float* dest = nullptr;                 // where its end state goes
+    if (a.pass == 2) { role = ROLE_OUT; seg = 1 + sub; }
+    else if (sub == 0) { role = ROLE_OUT; seg = 0; }
+    else { role = ((sub - 1) & 1) ? ROLE_ACC_E : ROLE_ACC_S; seg = 1 + ((sub - 1) >> 1); }
     if (role == ROLE_OUT) {
-        init = seg == 0 ? (a.S0 ? a.S0 + (size_t)bh * D * D : nullptr) : a.S_start + seg_slot * D * D;
-        if (seg == a.n_seg - 1) dest = a.S_final ? a.S_final + (size_t)bh * D * D : nullptr;
-        else if (seg == 0) dest = a.S_start + (seg_slot + 1) * D * D;   // the later start states come from the fix-up
+        if (staging) seg_staging_waves<D, ROLE_OUT, MERGE>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_OUT, F32OUT>(a, bh, seg, lds);
     } else if (role == ROLE_ACC_S) {
-        dest = a.Nbuf + seg_slot * D * D;
+        if (staging) seg_staging_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
     } else {
-        dest = a.MTbuf + seg_slot * D * D;
-    }
-
-    // ---- state: S^T tiles (rows d_k, cols v) as fp32 accumulators; fp16 copy S[v][d_k] in LDS -----
-    const int dq = tw;   // this wavefront's quarter of d_k in the state update
-    f32x4 accS[MS][NVT];
-#pragma unroll
-    for (int m = 0; m < MS; ++m)
-#pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) {
-            const int dk = (D / 4) * dq + 16 * m + 4 * lq, v = vbase + 16 * vt + l16;
-            if (init != nullptr) {
-                const float4 x = *reinterpret_cast<const float4*>(init + (size_t)v * D + dk);
-                accS[m][vt] = f32x4{x.x, x.y, x.z, x.w};
-            } else if (role == ROLE_ACC_E) {   // unit rows: "v" counts the rows e of the identity
-                accS[m][vt] = f32x4{v == dk ? 1.f : 0.f, v == dk + 1 ? 1.f : 0.f, v == dk + 2 ? 1.f : 0.f,
-                                    v == dk + 3 ? 1.f : 0.f};
-            } else {
-                accS[m][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            *reinterpret_cast<half4*>(Ss + v * SS + dk) = to_half4(accS[m][vt]);
-        }
-
-    // 0/1 selector fragments: B operand whose column n picks contraction slot n (lo) or 16 + n (hi) of a 32-slot step
-    half8 isel[2];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) isel[hf][j] = (8 * lq + j == 16 * hf + l16) ? (half_t)1.f : (half_t)0.f;
-
-    // ---- operands of one chunk, as this wavefront's MFMA fragments (raw bf16 words for K, Q, V) ----
-    // contraction slot (lq, j) of step ks stands for d_k (or token, or d_v) index 32 ks + 8 lq + j
-    u32x4 kraw[KS_D], qraw[KS_D], vraw[KS_V];
-    half8 tfr[2], pfr[2];
-    uint2 onla[NVT];
-    float4 gam4, kd4;      // gates of rows 4 lq + j of token tile tw
-    float gam_t, gC;       // gate of token 16 tw + l16; decay of the whole chunk
-    const size_t tokb = (size_t)bh * a.L;
-    const size_t chb = (size_t)bh * n_chunks;
-    auto load_kqv = [&](int c) __attribute__((always_inline)) {
-        const size_t row = (tokb + (size_t)c * SC + 16 * tw + l16) * D;
-        const bf16_t* Kr = a.K + row + 8 * lq;
-#pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) kraw[ks] = *reinterpret_cast<const u32x4*>(Kr + 32 * ks);
-        if (has_out) {
-            const bf16_t* Qr = a.Q + row + 8 * lq;
-#pragma unroll
-            for (int ks = 0; ks < KS_D; ++ks) qraw[ks] = *reinterpret_cast<const u32x4*>(Qr + 32 * ks);
-        }
-        if (has_v) {
-            const bf16_t* Vr = a.V + row + vbase + 8 * lq;
-#pragma unroll
-            for (int ks = 0; ks < KS_V; ++ks) vraw[ks] = *reinterpret_cast<const u32x4*>(Vr + 32 * ks);
-        }
-        const size_t gv = (chb + c) * SC + 16 * tw;
-        gam4 = *reinterpret_cast<const float4*>(a.gamv + gv + 4 * lq);
-        kd4 = *reinterpret_cast<const float4*>(a.kdv + gv + 4 * lq);
-        gam_t = a.gamv[gv + l16];
-        gC = a.gamC[chb + c];
-    };
-    auto load_t = [&](int c) __attribute__((always_inline)) {
-        const half8* Tc = reinterpret_cast<const half8*>(a.TF + (chb + c) * (size_t)(SC * SC)) + (tw * 2) * 64 + lane;
-        tfr[0] = Tc[0];
-        if (tw >= 2) tfr[1] = Tc[64];
-    };
-    auto load_p = [&](int c) __attribute__((always_inline)) {
-        if (!has_out) return;
-        const half8* Pc = reinterpret_cast<const half8*>(a.PF + (chb + c) * (size_t)(SC * SC)) + (tw * 2) * 64 + lane;
-        pfr[0] = Pc[0];
-        if (tw >= 2) pfr[1] = Pc[64];
-        if (a.O_nla_h != nullptr) {
-            const half_t* Or = a.O_nla_h + (tokb + (size_t)c * SC + 16 * tw + l16) * D + vbase + 4 * lq;
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) onla[vt] = *reinterpret_cast<const uint2*>(Or + 16 * vt);
-        }
-    };
-    // One word of every 128 bytes of a later chunk's K, Q, V (and of the softmax branch's rows), so that the
-    // fragment loads one step ahead find them in L2; the value is not used.
-    // (The word of one step is folded into a sink one step later, so that nothing waits for it where it is issued.)
-    uint32_t sink = 0, touched = 0;
-    auto touch = [&](int c) __attribute__((always_inline)) {
-        sink ^= touched;
-        if (c >= c_end) return;
-        constexpr int LINES = SC * D * 2 / 128;          // 128-byte lines of one [64][D] bf16 tile
-        const size_t off = (tokb + (size_t)c * SC) * D;
-        const int t = tid;
-        if (t < LINES) touched = *reinterpret_cast<const uint32_t*>(a.K + off + (size_t)t * 64);
-        else if (t < 2 * LINES && has_v)
-            touched = *reinterpret_cast<const uint32_t*>(a.V + off + (size_t)(t - LINES) * 64);
-        else if (t < 3 * LINES && has_out)
-            touched = *reinterpret_cast<const uint32_t*>(a.Q + off + (size_t)(t - 2 * LINES) * 64);
-        else if (t < 4 * LINES && has_out && a.O_nla_h != nullptr)
-            touched = *reinterpret_cast<const uint32_t*>(a.O_nla_h + off + (size_t)(t - 3 * LINES) * 64);
-    };
-
-    load_kqv(c_begin);
-    load_t(c_begin);
-    load_p(c_begin);
-    touch(c_begin + 1);
-    __syncthreads();   // initial state copy visible
-
-    for (int c = c_begin; c < c_end; ++c) {
-        const int cn = min(c + 1, c_end - 1);   // the tail re-loads the last chunk: loads stay unconditional
-        touch(c + 2);
-        // ================= phase a: R = V - gam K S0^T,  O^T = S0 Q^T,  Kd^T ==================
-        half8 kf[KS_D], qf[KS_D];
-#pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) kf[ks] = cvt_bf16x8(kraw[ks]);
-        if (has_out) {
-#pragma unroll
-            for (int ks = 0; ks < KS_D; ++ks) qf[ks] = cvt_bf16x8(qraw[ks]);
-        }
-        f32x4 accR[NVT], accO[NVT];
-#pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) {
-            half8 fs[KS_D];
-#pragma unroll
-            for (int ks = 0; ks < KS_D; ++ks) fs[ks] = lds_read8(Ss + (vbase + 16 * vt + l16) * SS + 32 * ks + 8 * lq);
-            accR[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (!a.gated) {
-#pragma unroll
-                for (int ks = 0; ks < KS_D; ++ks) accR[vt] = mfma16(kf[ks], fs[ks], accR[vt]);   // rows tok, col v
-            }
-            if (has_out) {
-                accO[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS_D; ++ks) accO[vt] = mfma16(fs[ks], qf[ks], accO[vt]);   // rows v, col tok
-            }
-        }
-        {
-            const float g4[4] = {gam4.x, gam4.y, gam4.z, gam4.w};
-            half8 vf[KS_V];
-            if (has_v) {
-#pragma unroll
-                for (int ks = 0; ks < KS_V; ++ks) vf[ks] = cvt_bf16x8(vraw[ks]);
-            }
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) {
-                f32x4 r;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) r[j] = -g4[j] * accR[vt][j];
-                if (has_v) r = mfma16(vf[vt >> 1], isel[vt & 1], r);    // + V[tok][v], exactly
-                *reinterpret_cast<half4*>(Rs + (vbase + 16 * vt + l16) * TS + 16 * tw + 4 * lq) = to_half4(r);
-            }
-        }
-        {   // Kd^T[d_k][tok] = kd_tok K[tok][d_k]: this wavefront's share of the d_k steps of token tile tw
-            const float k4[4] = {kd4.x, kd4.y, kd4.z, kd4.w};
-#pragma unroll
-            for (int kk = 0; kk < KS_D / 2; ++kk) {
-                const int ks = vh * (KS_D / 2) + kk;
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    f32x4 t = mfma16(kf[ks], isel[hf], f32x4{0.f, 0.f, 0.f, 0.f});   // rows tok, col d_k = 32 ks + 16 hf + l16
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[j] *= k4[j];
-                    *reinterpret_cast<half4*>(Kds + (32 * ks + 16 * hf + l16) * TS + 16 * tw + 4 * lq) = to_half4(t);
-                }
-            }
-        }
-        const float gC_cur = gC, gam_t_cur = gam_t;
-        load_kqv(cn);      // next chunk's rows and gates: their registers are free from here on
-        __syncthreads();   // R and Kd^T complete; every wavefront has read the old state copy
-
-        // ================= phase b: U = T'' R ==================
-        {
-            f32x4 accU[NVT];
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) {
-                accU[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                const half_t* Rr = Rs + (vbase + 16 * vt + l16) * TS + 8 * lq;
-                accU[vt] = mfma16(tfr[0], lds_read8(Rr), accU[vt]);
-                if (tw >= 2) accU[vt] = mfma16(tfr[1], lds_read8(Rr + 32), accU[vt]);   // T'' is lower triangular
-                *reinterpret_cast<half4*>(Us + (vbase + 16 * vt + l16) * TS + 16 * tw + 4 * lq) = to_half4(accU[vt]);
-            }
-        }
-        load_t(cn);
-        __syncthreads();   // U complete
-
-        // ================= phase c: S1^T = gam_C S0^T + Kd^T U,  O^T += U^T P^T ==================
-        {
-            half8 fu[NVT][2];
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt)
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) fu[vt][ks] = lds_read8(Us + (vbase + 16 * vt + l16) * TS + 32 * ks + 8 * lq);
-#pragma unroll
-            for (int m = 0; m < MS; ++m) {
-                const int dk0 = (D / 4) * dq + 16 * m;
-                half8 fa[2];
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) fa[ks] = lds_read8(Kds + (dk0 + l16) * TS + 32 * ks + 8 * lq);
-#pragma unroll
-                for (int vt = 0; vt < NVT; ++vt) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) accS[m][vt][j] *= gC_cur;
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) accS[m][vt] = mfma16(fa[ks], fu[vt][ks], accS[m][vt]);
-                    *reinterpret_cast<half4*>(Ss + (vbase + 16 * vt + l16) * SS + dk0 + 4 * lq) = to_half4(accS[m][vt]);
-                }
-            }
-            if (has_out) {
-                const size_t orow = (tokb + (size_t)c * SC + 16 * tw + l16) * D + vbase + 4 * lq;
-#pragma unroll
-                for (int vt = 0; vt < NVT; ++vt) {
-                    f32x4 o;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) o[j] = gam_t_cur * accO[vt][j];
-                    o = mfma16(fu[vt][0], pfr[0], o);                       // rows v, col r = 16 tw + l16
-                    if (tw >= 2) o = mfma16(fu[vt][1], pfr[1], o);          // P is lower triangular
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) o[j] *= a.la_scale;
-                    if (a.O_la_f32 != nullptr)
-                        *reinterpret_cast<float4*>(a.O_la_f32 + orow + 16 * vt) = make_float4(o[0], o[1], o[2], o[3]);
-                    if (a.O_nla_h != nullptr) {   // plain-sum merge (Section 4.1): add the softmax branch's row piece, store bf16
-                        const half4 h = __builtin_bit_cast(half4, onla[vt]);
-                        *reinterpret_cast<uint2*>(a.O + orow + 16 * vt) =
-                            make_uint2(pack_bf16x2(o[0] + (float)h[0], o[1] + (float)h[1]),
-                                       pack_bf16x2(o[2] + (float)h[2], o[3] + (float)h[3]));
-                    } else {                      // the linear branch's rows as fp16 for the softmax kernel's merge epilogue
-                        *reinterpret_cast<half4*>(a.O_la_h + orow + 16 * vt) = to_half4(o);
-                    }
-                }
-            }
-        }
-        load_p(cn);
-        __syncthreads();   // new state copy visible; R, U and Kd^T free again
-    }
-    sink ^= touched;
-    asm volatile("" ::"v"(sink));   // keeps the touching loads alive
-
-    // ---- end state ----
-    if (dest != nullptr) {
-#pragma unroll
-        for (int m = 0; m < MS; ++m)
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) {
-                const int dk = (D / 4) * dq + 16 * m + 4 * lq, v = vbase + 16 * vt + l16;
-                if (role == ROLE_ACC_E) {   // transposed: MT[j = d_k][i = unit row]
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) dest[(size_t)(dk + j) * D + v] = accS[m][vt][j];
-                } else {
-                    *reinterpret_cast<float4*>(dest + (size_t)v * D + dk) =
-                        make_float4(accS[m][vt][0], accS[m][vt][1], accS[m][vt][2], accS[m][vt][3]);
-                }
-            }
+        if (staging) seg_staging_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
     }
 }
 
@@ -387,81 +575,135 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
 // One block = 16 state rows of one (batch, head), 4 wavefronts, each owning d / 64 column tiles of 16.  The
 // product runs on fp16 MFMA with both operands split into two fp16 terms (hi + lo, three products): the error
 // is about 2^-21 relative, so the carried state keeps fp32-level accuracy.
-constexpr int FIX_THREADS = 256;
-
-__device__ __forceinline__ void split8(const float* x, half8& hi, half8& lo) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        hi[j] = f32_to_half_sat(x[j]);
-        lo[j] = (half_t)(x[j] - (float)hi[j]);
-    }
-}
+constexpr int FIX_THREADS = 512;   // four multiplying wavefronts and four that only pull the operands into L2
 
 template <int D>
 __global__ __launch_bounds__(FIX_THREADS) void gdn_seg_fix_kernel(float* __restrict__ S_start,
                                                                  const float* __restrict__ Nbuf,
                                                                  const float* __restrict__ MTbuf, int BH, int n_seg) {
     constexpr int KS_D = D / 32, NT = D / 64;   // contraction steps; column tiles per wavefront
-    constexpr int RS = D + 4;                   // fp32 row stride of the state rows in LDS
-    __shared__ __align__(16) float Srow[16 * RS];
+    constexpr int RS = D + 8;                   // fp16 row stride of the carried rows in LDS
+    // the 16 carried rows as an fp16 pair (leading half, remainder): the A operand of the next step as it is
+    __shared__ __align__(16) half_t Shi[16 * RS], Slo[16 * RS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int bh = blockIdx.x / (D / 16), v0 = (blockIdx.x % (D / 16)) * 16;
+    // The D/16 blocks of one (batch, head) read the same M and N: consecutive block indices go to different
+    // XCDs, so the blocks are renumbered to put them behind one L2 (grid = 8 x ceil(blocks / 8)).
+    const int vid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int bh = vid / (D / 16), v0 = (vid % (D / 16)) * 16;
     if (bh >= BH) return;
     const size_t base = (size_t)bh * n_seg;
-    for (int e = tid; e < 16 * D / 4; e += FIX_THREADS) {
-        const int r = e / (D / 4), c4 = (e % (D / 4)) * 4;
-        *reinterpret_cast<float4*>(Srow + r * RS + c4) =
-            *reinterpret_cast<const float4*>(S_start + ((base + 1) * D + v0 + r) * D + c4);
-    }
-    __syncthreads();
-    for (int s = 1; s + 1 < n_seg; ++s) {
-        const float* MT = MTbuf + (base + s) * D * D;
-        const float* Nn = Nbuf + (base + s) * D * D;
-        // A operand: rows v0 + l16, slots i = 32 ks + 8 lq + j
-        half8 ahi[KS_D], alo[KS_D];
+    const int last = n_seg - 2;   // steps s = 1 .. last
+    if (last < 1) return;
+    if (wave >= 4) {
+        // The operands of every step were written by blocks behind other L2s, so a first read comes from memory
+        // and a step that waits for it costs a full memory latency.  These wavefronts read, once and all at the
+        // start, the block's share of every later step's M (a (D/16)-th: the blocks of this (batch, head) sit
+        // behind the same L2) and its own rows of N, so that the multiplying wavefronts find them in L2.
+        constexpr int SHARE = D * D * 4 / (D / 16);   // bytes of M (and of N) per block and step
+        constexpr int PIECES = SHARE / 16 / 256;      // 16-byte pieces per thread
+        const int t = tid - 256, part = vid % (D / 16);
+        unsigned seen = 0;
+        for (int sg = 2; sg <= last; ++sg) {
+            const uint4* m = reinterpret_cast<const uint4*>(MTbuf + (base + sg) * D * D) + (size_t)part * (SHARE / 16);
+            const uint4* n = reinterpret_cast<const uint4*>(Nbuf + (base + sg) * D * D) + (size_t)part * (SHARE / 16);
 #pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) {
-            float x[8];
-            const float4 x0 = *reinterpret_cast<const float4*>(Srow + l16 * RS + 32 * ks + 8 * lq);
-            const float4 x1 = *reinterpret_cast<const float4*>(Srow + l16 * RS + 32 * ks + 8 * lq + 4);
-            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-            split8(x, ahi[ks], alo[ks]);
+            for (int i = 0; i < PIECES; ++i) {
+                const uint4 a = m[t + 256 * i], b = n[t + 256 * i];
+                seen |= a.x | b.x;
+            }
         }
-        f32x4 acc[NT];
+        if (seen == 0xffffffffu && n_seg < 0) S_start[0] = 0.f;   // never true: keeps the reads alive
+        for (int sg = 1; sg <= last; ++sg) {
+            __syncthreads();
+            __syncthreads();
+        }
+        __syncthreads();
+        return;
+    }
+    // What a step takes from memory (its M and N) does not depend on the carried rows: it is fetched one step
+    // ahead, so that the dependent chain along the segments holds no memory latency.  Two register sets take
+    // turns (two steps per loop trip): with one set the compiler would copy the fresh values into the registers
+    // the loop carries, and wait for them, inside the same step.
+    struct Fetch {
+        half8 mh[NT][KS_D], ml[NT][KS_D];   // A operand: row j0 + l16 of M^T, slots i = 32 ks + 8 lq + s
+        float4 n[NT];                       // N[v0 + l16][j0 + 4 lq ..]
+    };
+    auto load_step = [&](Fetch& f, int sg) __attribute__((always_inline)) {
+        const half_t* MT = reinterpret_cast<const half_t*>(MTbuf + (base + sg) * D * D);
+        const float* Nn = Nbuf + (base + sg) * D * D;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int j0 = 16 * (wave * NT + nt);
+            const int jt = wave * NT + nt;
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks) {
+                const half_t* mp = MT + ((size_t)(jt * KS_D + ks) * 64 + lane) * 8;
+                f.mh[nt][ks] = *reinterpret_cast<const half8*>(mp);
+                f.ml[nt][ks] = *reinterpret_cast<const half8*>(mp + D * D);
+            }
+            f.n[nt] = *reinterpret_cast<const float4*>(Nn + (size_t)(v0 + l16) * D + 16 * jt + 4 * lq);
+        }
+    };
+    auto step = [&](int sg, const Fetch& cur, Fetch& nxt) __attribute__((always_inline)) {
+        load_step(nxt, min(sg + 1, last));
+        __builtin_amdgcn_sched_barrier(0);   // the fetch leads the step
+        // B operand: the carried rows, col v0 + l16, slots i = 32 ks + 8 lq + s
+        half8 bhi[KS_D], blo[KS_D];
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            bhi[ks] = *reinterpret_cast<const half8*>(Shi + l16 * RS + 32 * ks + 8 * lq);
+            blo[ks] = *reinterpret_cast<const half8*>(Slo + l16 * RS + 32 * ks + 8 * lq);
+        }
+        f32x4 acc[NT];   // transposed product: rows j0 + 4 lq + jj, col v0 + l16
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
             acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS_D; ++ks) {   // B operand: col j0 + l16, slots i: row j of MT is contiguous in i
-                float x[8];
-                const float* mp = MT + (size_t)(j0 + l16) * D + 32 * ks + 8 * lq;
-                const float4 x0 = *reinterpret_cast<const float4*>(mp);
-                const float4 x1 = *reinterpret_cast<const float4*>(mp + 4);
-                x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-                half8 bhi, blo;
-                split8(x, bhi, blo);
-                acc[nt] = mfma16(alo[ks], bhi, acc[nt]);
-                acc[nt] = mfma16(ahi[ks], blo, acc[nt]);
-                acc[nt] = mfma16(ahi[ks], bhi, acc[nt]);
+            for (int ks = 0; ks < KS_D; ++ks) {
+                acc[nt] = mfma16(cur.mh[nt][ks], blo[ks], acc[nt]);
+                acc[nt] = mfma16(cur.ml[nt][ks], bhi[ks], acc[nt]);
+                acc[nt] = mfma16(cur.mh[nt][ks], bhi[ks], acc[nt]);
             }
         }
         __syncthreads();   // every wavefront has read the old rows
-        float* out = S_start + (base + s + 1) * D * D;
+        float* out = S_start + (base + sg + 1) * D * D;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int j = 16 * (wave * NT + nt) + l16;
+            const int j = 16 * (wave * NT + nt) + 4 * lq;
+            const float y[4] = {acc[nt][0] + cur.n[nt].x, acc[nt][1] + cur.n[nt].y, acc[nt][2] + cur.n[nt].z,
+                                acc[nt][3] + cur.n[nt].w};
+            half4 hi, lo;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {   // rows v0 + 4 lq + jj, col j
-                const int r = 4 * lq + jj;
-                const float y = acc[nt][jj] + Nn[(size_t)(v0 + r) * D + j];
-                Srow[r * RS + j] = y;
-                out[(size_t)(v0 + r) * D + j] = y;
+            for (int jj = 0; jj < 4; ++jj) {
+                hi[jj] = f32_to_half_sat(y[jj]);
+                lo[jj] = (half_t)(y[jj] - (float)hi[jj]);
             }
+            *reinterpret_cast<half4*>(Shi + l16 * RS + j) = hi;
+            *reinterpret_cast<half4*>(Slo + l16 * RS + j) = lo;
+            *reinterpret_cast<float4*>(out + (size_t)(v0 + l16) * D + j) = make_float4(y[0], y[1], y[2], y[3]);
         }
         __syncthreads();
+    };
+    Fetch fa, fb;
+    load_step(fa, 1);
+    for (int e = tid; e < 16 * D / 4; e += 256) {
+        const int r = e / (D / 4), c4 = (e % (D / 4)) * 4;
+        const float4 x4 = *reinterpret_cast<const float4*>(S_start + ((base + 1) * D + v0 + r) * D + c4);
+        const float x[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half_t hi = f32_to_half_sat(x[j]);
+            Shi[r * RS + c4 + j] = hi;
+            Slo[r * RS + c4 + j] = (half_t)(x[j] - (float)hi);
+        }
     }
+    __syncthreads();
+    int sg = 1;
+    for (; sg + 1 <= last; sg += 2) {
+        step(sg, fa, fb);
+        step(sg + 1, fb, fa);
+    }
+    if (sg <= last) step(sg, fa, fb);
 }
 
 // number of segments a (batch, head) is cut into: enough blocks to fill the chip, at least 4 chunks each
@@ -472,13 +714,13 @@ int gdn_segments(const FwdPlan& pl) {
     return std::max(1, std::min(n, 64));
 }
 
-template <int D>
-static nats_status launch_seg_t(const FwdPlan& pl, SegArgs<D> a, hipStream_t st) {
+template <int D, bool MERGE, bool F32OUT>
+static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st) {
     static bool attr_done[64] = {};
     int dev = 0;
     (void)hipGetDevice(&dev);
     dev = (dev >= 0 && dev < 64) ? dev : 0;
-    auto kern = gdn_seg_scan_kernel<D>;
+    auto kern = gdn_seg_scan_kernel<D, MERGE, F32OUT>;
     if (!attr_done[dev]) {   // the LDS-size attribute is per function and device
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 SegLds<D>::bytes) != hipSuccess)
@@ -492,7 +734,7 @@ static nats_status launch_seg_t(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     const int bh8 = 8 * ((pl.BH + 7) / 8);
     const int n_mid = a.n_seg > 2 ? a.n_seg - 2 : 0;
     {
-        ProfScope ps("gdn_seg_scan", st);
+        ProfScope ps("gdn_seg_pass1", st);
         a.pass = 1;
         hipLaunchKernelGGL(kern, dim3(bh8 * (1 + 2 * n_mid)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
     }
@@ -500,17 +742,24 @@ static nats_status launch_seg_t(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     if (s != NATS_OK || a.n_seg == 1) return s;
     if (n_mid > 0) {
         ProfScope ps("gdn_seg_fix", st);
-        hipLaunchKernelGGL(gdn_seg_fix_kernel<D>, dim3(pl.BH * (D / 16)), dim3(FIX_THREADS), 0, st, a.S_start, a.Nbuf,
+        hipLaunchKernelGGL(gdn_seg_fix_kernel<D>, dim3(8 * ((pl.BH * (D / 16) + 7) / 8)), dim3(FIX_THREADS), 0, st, a.S_start, a.Nbuf,
                            a.MTbuf, pl.BH, a.n_seg);
         s = check_launch("gdn_seg_fix");
         if (s != NATS_OK) return s;
     }
     {
-        ProfScope ps("gdn_seg_scan", st);
+        ProfScope ps("gdn_seg_pass2", st);
         a.pass = 2;
         hipLaunchKernelGGL(kern, dim3(bh8 * (a.n_seg - 1)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
     }
     return check_launch("gdn_seg_scan (pass 2)");
+}
+
+template <int D>
+static nats_status launch_seg_t(const FwdPlan& pl, const SegArgs<D>& a, hipStream_t st) {
+    const bool merge = a.O_nla_h != nullptr, f32 = a.O_la_f32 != nullptr;
+    if (merge) return f32 ? launch_seg_k<D, true, true>(pl, a, st) : launch_seg_k<D, true, false>(pl, a, st);
+    return f32 ? launch_seg_k<D, false, true>(pl, a, st) : launch_seg_k<D, false, false>(pl, a, st);
 }
 
 // O_nla_h == nullptr: writes O_la_h (fp16) for the softmax kernel to merge.  Otherwise merges (plain sum)

@@ -54,6 +54,20 @@ __device__ __forceinline__ half4 to_half4(f32x4 v) {
     return h;
 }
 
+// Conversions to fp16 without the explicit clamp, for kernels that have switched the hardware's fp16 overflow
+// mode on (fp16_saturate_on): a result beyond the fp16 range then becomes +-65504 instead of infinity, at no
+// instruction cost (the clamp costs one vector instruction per element, a fifth of the vector work of the
+// recurrence kernel).
+__device__ __forceinline__ void fp16_saturate_on() {
+    // MODE register (hardware register 1), bit 23, one bit wide: FP16_OVFL
+    __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);
+}
+__device__ __forceinline__ half4 to_half4_hw(f32x4 v) {
+    half4 h;
+    h[0] = (half_t)v[0]; h[1] = (half_t)v[1]; h[2] = (half_t)v[2]; h[3] = (half_t)v[3];
+    return h;
+}
+
 constexpr int LDS_PAD = 8;  // fp16 elements added to every LDS row: 16-byte reads of 16 rows hit distinct banks
 
 }  // namespace nats

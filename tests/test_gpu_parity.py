@@ -456,3 +456,13 @@ def test_segment_count_does_not_change_the_result_beyond_rounding_bf16():
         r = run_ex(x, "bf16", want=("O_la",), gdn_segments=n_seg)
         a, b = host(r["O_la"]), host(base["O_la"])
         assert np.abs(a - b).max() <= 2e-3 * np.sqrt(np.mean(b * b)), n_seg
+
+
+def test_values_beyond_the_fp16_range_saturate_bf16():
+    """|V| around 2^20: the linear branch's fp16 intermediates leave the stated range.  They saturate (the result
+    is then inaccurate, as nats.h says) but nothing turns into inf or NaN."""
+    x = make_fwd_inputs(1, 2, 512, 128, "bf16", 0.1, seed=730)
+    x["V"] = (x["V"] * 2.0 ** 20).astype(np.float32)
+    r = run_ex(x, "bf16", want=("final_state", "O_la"))
+    assert np.isfinite(host(r["O"])).all() and np.isfinite(host(r["O_la"])).all()
+    assert np.isfinite(host(r["final_state"])).all()
