@@ -18,14 +18,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # MI355X published peaks
-PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "alu_f32": (157.3, "TFLOP/s")}
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu_f32": (157.3, "TFLOP/s")}
+
+# the launches that together are the linear branch's segmented scan (recurrence, output and merge)
+SEG_SCAN = ("gdn_seg_pass1", "gdn_seg_fix", "gdn_seg_pass2")
 
 
 def kernel_work(name, cfg, sum_cnt):
-    """Algorithmic work of one launch of each kernel at this workload -> (bound, amount, unit-scale).
+    """Algorithmic work of one forward call that falls to each kernel -> (bound, amount).
 
-    bytes for HBM-bound kernels, FLOP for arithmetic-bound ones."""
-    BH, L, d = cfg.B * cfg.H, cfg.L, cfg.d
+    bytes for HBM-bound kernels, FLOP for the kernels whose work is dense products (priced against the
+    bf16/fp16 matrix-core peak whatever the time they take is really spent on).  Only what the method needs is
+    counted: work a kernel repeats to run segments of the recurrence side by side is not."""
+    BH, L, d, C = cfg.B * cfg.H, cfg.L, cfg.d, cfg.C
     n_tok = BH * L
     esz = 2 if cfg.dtype == "bf16" else 4
     if name == "scan_compact":      # mask in, cnt + idx out, gathered K/V rows in and out
@@ -35,32 +40,45 @@ def kernel_work(name, cfg, sum_cnt):
         return "alu_f32", n_tok * d * (7 * d)
     if name == "softmax_fp32":      # QK^T and PV: 4 d FLOP per visible (query, key) pair (fp32 VALU)
         return "alu_f32", 4 * d * sum_cnt
-    if name == "gdn_chunk_prep":
-        # HBM-bound in practice (its 4 products are 66 kFLOP per token against 1.9 kB moved per token).
-        # Algorithmic bytes: K, Q, V, alpha, beta, mask in; W, U~ (fp16) and P (C fp16 per token) out.
-        # The re-laid-out copies of Q and K it also writes are this design's choice and are not counted.
-        return "hbm", n_tok * (3 * d * esz + 9 + 2 * d * 2 + cfg.C * 2)
-    if name == "gdn_chunk_scan":
-        # Its products (W S^T, Q S^T, U^T K: 3 x 2 d^2, and P U: 2 C d FLOP per token) would take a fifth of the
-        # time its operands take to stream at the HBM peak, so HBM is the roofline that bounds it: per token
-        # W, U~, Kd, Qg (fp16) and P (C fp16) in, the softmax branch's output (fp16) in, O out.
-        return "hbm", n_tok * (4 * d * 2 + cfg.C * 2 + d * 2 + d * esz) + (n_tok // cfg.C) * 4
+    if name == "gdn_chunk_inv":     # K K^T and Q K^T (2 x 2 C d per token) and the triangular solve (C^2 / 3)
+        return "mfma", n_tok * (4 * C * d + C * C / 3.0)
+    if name == "gdn_seg_scan":      # K S0^T, Q S0^T, U^T K (3 x 2 d^2) and T (.), P U and the W-type product (3 x 2 C d)
+        return "mfma", n_tok * (6 * d * d + 6 * C * d)
     if name == "flash_softmax":
-        return "mfma_bf16", 4 * d * sum_cnt
+        return "mfma", 4 * d * sum_cnt
+    return None
+
+
+def profile_cell(fname, kernel, column):
+    """Cell (as text) of the row `kernel` under the header `column` in a committed rocprofv3 summary table."""
+    try:
+        header = None
+        for line in open(os.path.join(ROOT, "profiles", fname)):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) < 3:
+                continue
+            if header is None and column in cells:
+                header = cells
+            elif header is not None and cells[1] == kernel:
+                return cells[header.index(column)]
+    except (OSError, ValueError):
+        pass
     return None
 
 
 def measured_traffic_bytes(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", "fwd_cfg2_headline_bf16_hbm_traffic.md")
+    """HBM bytes per forward call of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
+    c = profile_cell("fwd_cfg2_headline_bf16_hbm_traffic.md", kernel, "total MB")
+    return float(c) * 1e6 if c else None
+
+
+def measured_mfma_busy(kernel):
+    """Share of the busy CU cycles in which a matrix instruction was executing, from the committed counter summary."""
+    c = profile_cell("fwd_cfg2_headline_bf16_mfma_lds_counters.md", kernel, "MFMA utilisation")
     try:
-        for line in open(path):
-            cells = [c.strip() for c in line.split("|")]
-            if len(cells) >= 5 and cells[1] == kernel:
-                return float(cells[4]) * 1e6
-    except OSError:
-        pass
-    return None
+        return float(c.split("%")[0]) / 100.0
+    except (AttributeError, ValueError):
+        return None
 
 
 def bench_decode(args):
@@ -295,38 +313,40 @@ def main():
     tokens = cfg.B * cfg.L
     value = tokens / (ms_per_step * 1e-3)
 
-    roofline = None
-    if kernels:
-        dom = max(kernels, key=lambda k: kernels[k]["total_ms"])
-        work = kernel_work(dom, cfg, sum_cnt)
-        if work is not None:
-            bound, amount = work
-            # the work of one step is spread evenly over that step's launches of the kernel
-            amount = amount * args.steps / max(kernels[dom]["launches"], 1)
-            peak, unit = PEAK[bound]
-            achieved = amount / (kernels[dom]["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
-            roofline = {"kernel": dom, "bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
-                        "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                        "frac": round(achieved / peak, 5), "traffic": measured_traffic_bytes(dom),
-                        "avg_kernel_ms": round(kernels[dom]["avg_ms"], 4)}
-
-    # every kernel of the step against its own bound
-    kernel_rooflines = {}
+    # per step: time and algorithmic work of each kernel; the two passes and the fix-up of the segmented scan count
+    # as one kernel (its average duration is the sum of the three launches' averages)
+    per_step = {}
     for name, k in kernels.items():
+        key = "gdn_seg_scan" if name in SEG_SCAN else name
+        per_step[key] = per_step.get(key, 0.0) + k["total_ms"] / args.steps
+    n_tok = cfg.B * cfg.H * cfg.L
+    compulsory = 4 * n_tok * cfg.d * 2 + 8 * n_tok + n_tok      # Q, K, V in, O out; alpha, beta; mask
+    kernel_rooflines = {}
+    for name, ms in per_step.items():
         work = kernel_work(name, cfg, sum_cnt)
         if work is None:
             continue
         bound, amount = work
-        amount = amount * args.steps / max(k["launches"], 1)
         peak, unit = PEAK[bound]
-        ach = amount / (k["avg_ms"] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
-        kernel_rooflines[name] = {"bound": {"hbm": "hbm", "mfma_bf16": "mfma", "alu_f32": "alu"}[bound],
-                                  "achieved": round(ach, 2), "unit": unit, "frac": round(ach / peak, 4)}
+        ach = amount / (ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        kernel_rooflines[name] = {"bound": {"hbm": "hbm", "mfma": "mfma", "alu_f32": "alu"}[bound],
+                                  "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                                  "work": amount, "ms_per_step": round(ms, 4),
+                                  "traffic": measured_traffic_bytes(name), "mfma_busy": measured_mfma_busy(name)}
+    roofline = None
+    if per_step:
+        dom = max(per_step, key=per_step.get)
+        if dom in kernel_rooflines:
+            r = kernel_rooflines[dom]
+            roofline = {"kernel": dom, "bound": r["bound"], "achieved": r["achieved"], "peak": r["peak"],
+                        "unit": r["unit"], "frac": r["frac"], "traffic": r["traffic"],
+                        "avg_kernel_ms": r["ms_per_step"], "mfma_busy": r["mfma_busy"],
+                        "launches": [n for n in SEG_SCAN if n in kernels] if dom == "gdn_seg_scan" else [dom]}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import c_oracle
-        heads = 8       # first 8 heads of batch 0, all L tokens: each (b,h) is an independent unit
+        heads = 16      # all heads of batch 0, all L tokens: each (b,h) is an independent unit and takes one thread
         xs = {k: np.ascontiguousarray(v[:1, :heads]) for k, v in x.items()}
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 20:
@@ -336,7 +356,7 @@ def main():
             reps += 1
         head_tok_per_s = reps * heads * cfg.L / t_cpu
         cpu_baseline = {"value": round(head_tok_per_s / cfg.H, 1), "unit": "tokens/s",
-                        "cores": c_oracle.threads(), "kind": "oracle",
+                        "cores": min(c_oracle.threads(), heads), "kind": "oracle",
                         "sample": f"{heads} of {cfg.B * cfg.H} (batch, head) pairs, all {cfg.L} tokens, "
                                   f"{reps} repetitions; rate scaled by 1/H to whole tokens"}
 
@@ -357,6 +377,9 @@ def main():
         out["graph_replay_ms_per_step"] = round(graph_ms, 4)
     flop_total = 4.0 * cfg.d * sum_cnt + (10.0 * cfg.C * cfg.d + 6.0 * cfg.d ** 2 + cfg.C ** 2 / 3.0) * cfg.B * cfg.H * cfg.L
     out["algorithmic_TFLOPs"] = round(flop_total / (ms_per_step * 1e-3) / 1e12, 2)
+    out["mfma_frac_whole_forward"] = round(flop_total / (ms_per_step * 1e-3) / 1e12 / PEAK["mfma"][0], 4)
+    tr = [measured_traffic_bytes(k) for k in per_step]
+    out["hbm_bytes"] = {"compulsory": compulsory, "measured": sum(tr) if tr and all(t is not None for t in tr) else None}
     print(json.dumps(out))
 
 

@@ -15,9 +15,7 @@
  *     stream reaches the end of what the call enqueued, and the call returns
  *     immediately.  Every kernel of a call runs on the given stream (legal
  *     under stream capture).  Two calls that overlap in time need different
- *     workspaces.  One switch in the environment, read once, for comparisons:
- *     NATS_NO_PREFETCH_HELPERS=1 runs the recurrence kernel without the extra
- *     blocks that touch its operands ahead of use.
+ *     workspaces.
  *   - Arguments are validated on the host before anything is launched; a bad
  *     argument returns a negative nats_status and launches nothing.
  *     nats_last_error() then describes the problem (thread-local string).
@@ -151,6 +149,12 @@ size_t nats_hybrid_attn_fwd_workspace_bytes(const nats_fwd_params* p);
  *   O       : out [B,H,L,d] dtype p->dtype
  *   workspace, workspace_bytes : device scratch of at least *_workspace_bytes(p); contents
  *             are undefined afterwards; two calls in flight must not share it.
+ * Value range of the bf16 path: its products take fp16 operands (fp32 sums, fp32 carried state), so
+ * V, the carried state, the rows V - S k that the delta rule writes and both branches' output rows are
+ * rounded to fp16 on their way into a product.  Magnitudes up to 65504 are represented; anything
+ * beyond saturates at +-65504 (the hardware's fp16 clamp is on, no infinity or NaN arises) and no
+ * status reports it.  alpha is clamped below at 1e-30 per token.  The fp32 path (NATS_F32 tensors,
+ * or math = NATS_MATH_F32) has neither limit.
  * Returns NATS_OK once everything is enqueued. */
 nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
                                  const float* alpha, const float* beta, const uint8_t* mask, void* O,
@@ -303,27 +307,6 @@ nats_status nats_hybrid_attn_decode_chunk(const nats_dec_params* p, const nats_d
  * chunk), as described above.  err_flags [B,H] or NULL: 1 where rows of a softmax chunk had not fitted. */
 nats_status nats_hybrid_attn_decode_commit(const nats_dec_params* p, const nats_dec_chunk_state* s,
                                            const uint8_t* mask_c, int32_t* err_flags, void* hip_stream);
-
-/* ------------------------------------------------------------------------- *
- * Optional per-kernel timing (for benchmarks; off by default)
- * ------------------------------------------------------------------------- */
-/* Creates max_records hipEvent pairs and turns recording on: until nats_profile_end, every kernel
- * the forward / decode calls launch is bracketed by an event pair on the call's stream (records
- * beyond max_records are dropped).  This is the one place the library creates HIP objects. */
-nats_status nats_profile_begin(int max_records);
-
-/* Turns recording off, waits for the recorded events, and aggregates per kernel name:
- * names[i*32 .. i*32+31] (NUL-terminated), total_ms[i], launches[i] for up to max_kernels kernels.
- * All three arrays are HOST memory owned by the caller.  Destroys the events.
- * Returns the number of distinct kernels written, or a negative nats_status. */
-int nats_profile_end(char* names, float* total_ms, int32_t* launches, int max_kernels);
-
-/* Measurement helper, no part of the method: launches a kernel in which every wavefront of a
- * chip-filling grid issues iters x 8 independent 16x16x32 fp16 MFMA (the instruction the bf16 path
- * is built on) and nothing else.  out: DEVICE buffer of at least 2048 floats (scratch, overwritten).
- * Returns the floating-point operations that launch performs (the caller times it on the stream),
- * or a negative value on error (see nats_last_error). */
-double nats_probe_mfma(int iters, float* out, size_t out_floats, void* hip_stream);
 
 /* Host-side message for the last non-OK status returned on this thread ("" if none). */
 const char* nats_last_error(void);

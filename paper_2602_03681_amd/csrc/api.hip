@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "nats_common.h"
+#include "nats_measure.h"
 
 namespace nats {
 
@@ -62,6 +63,8 @@ ProfScope::ProfScope(const char* name, hipStream_t st) : slot(-1), stream(st) {
 }
 ProfScope::~ProfScope() {
     if (slot < 0) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (slot >= (int)g_prof.size()) return;   // recording was ended in between
     (void)hipEventRecord(g_prof[slot].stop, stream);
     if (g_chain_prev != -2) { g_chain_prev = slot; g_chain_stream = stream; }
 }
@@ -239,9 +242,14 @@ nats_status nats_profile_begin(int max_records) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (!g_prof.empty()) { set_error("profiling is already on"); return NATS_ERR_UNSUPPORTED; }
     g_prof.resize(max_records);
+    for (auto& r : g_prof) { r.start = nullptr; r.stop = nullptr; }
     for (auto& r : g_prof) {
         if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
             set_error("hipEventCreate failed");
+            for (auto& q : g_prof) {   // give back what was created
+                if (q.start) (void)hipEventDestroy(q.start);
+                if (q.stop) (void)hipEventDestroy(q.stop);
+            }
             g_prof.clear();
             return NATS_ERR_HIP;
         }

@@ -23,28 +23,14 @@
 #include "mfma_util.h"
 #include "nats_common.h"
 
-#ifndef NATS_MARK
-#define NATS_MARK(i) do {} while (0)   // phase timestamps, only in debug harness builds
-#endif
-#ifndef NATS_MARK_TILE
-#define NATS_MARK_TILE 3               // the key tile whose inner phases the debug harness times
-#endif
-
 namespace nats {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int FL_THREADS = 256;
-#ifndef NATS_FL_NQ
-#define NATS_FL_NQ 2
-#endif
-#ifndef NATS_FL_VAHEAD
-#define NATS_FL_VAHEAD 6          // V^T fragment reads in flight ahead of their matrix instructions
-#endif
-#ifndef NATS_FL_OCC
-#define NATS_FL_OCC 2
-#endif
-constexpr int FL_NQ = NATS_FL_NQ;        // 16-query MFMA columns per wavefront
+constexpr int FL_NQ = 2;                 // 16-query MFMA columns per wavefront
+constexpr int FL_VAHEAD = 6;             // V^T fragment reads in flight ahead of their matrix instructions
+constexpr int FL_OCC = 2;                // blocks per CU the kernel is built for
 constexpr int FL_BM = 4 * 16 * FL_NQ;    // queries per block
 constexpr int FL_BN = 64;                // compacted keys per tile
 
@@ -71,7 +57,7 @@ __device__ __forceinline__ float quad_max(float x) {
 //                compaction, so it can run beside the linear branch's preparation.
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
 template <int D, bool MERGE, bool chunk_routing>
-__global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
+__global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
@@ -113,7 +99,6 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
     const size_t tokbase = (size_t)bh * L;
     const float scale2 = scale * 1.44269504088896341f;   // logits in base-2 units
 
-    NATS_MARK(0);
     // ---- prologue: the block's Q rows, coalesced, through LDS into B-operand fragments ------------
     constexpr int NQP = FL_BM * D / 8 / FL_THREADS;   // 16-byte pieces per thread of the Q tile
     constexpr int NKP = FL_BN * D / 8 / FL_THREADS;   // ... of a K tile and of a V^T tile
@@ -209,13 +194,10 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
         for (int t = 0; t < DT; ++t) accO[nq][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    NATS_MARK(1);
     for (int kt = 0; kt < n_all; ++kt) {
         const bool own = kt >= n_tiles;      // one of the block's own chunks (uniform)
         const int dc = kt - n_tiles;
-        if (kt == NATS_MARK_TILE) NATS_MARK(10);
         __syncthreads();   // the previous tile (or the Q tile) is no longer read
-        if (kt == NATS_MARK_TILE) NATS_MARK(11);
 #pragma unroll
         for (int i = 0; i < NKP; ++i) {   // registers -> LDS: K rows [key][d], V^T rows [d_v][key]
             const int e = tid + FL_THREADS * i;
@@ -229,9 +211,7 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
                 for (int j = 0; j < 8; ++j) Vs[(c8 * 8 + j) * TS + vht_col(key)] = hv[j];
             }
         }
-        if (kt == NATS_MARK_TILE) NATS_MARK(12);
         __syncthreads();
-        if (kt == NATS_MARK_TILE) NATS_MARK(13);
         load_any(kt + 1 < n_all ? kt + 1 : kt);   // next tile in flight during this tile's products
         // keys of this tile visible to each of this lane's queries (may be <= 0 or >= 64)
         int vis[FL_NQ];
@@ -267,14 +247,13 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
                 for (int nq = 0; nq < FL_NQ; ++nq) accS[nq][m] = mfma16_bf16(fk, qf[nq][ks], accS[nq][m]);
             }
         // issue order: K fragments several reads ahead of the matrix instructions that take them
-        __builtin_amdgcn_sched_group_barrier(0x100, NATS_FL_VAHEAD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, FL_VAHEAD, 0);
 #pragma unroll
         for (int i = 0; i < KS_D * 4; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
 
-        if (kt == NATS_MARK_TILE) NATS_MARK(14);
         // ---- online softmax per query column; P^T fragments ------------------------------------------
         // VALU work is what bounds this loop, so it is kept to one fused multiply-add, one exponential,
         // half a maximum and half a conversion per logit: masking only in tiles that are not visible in
@@ -334,7 +313,6 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
             }
         }
 
-        if (kt == NATS_MARK_TILE) NATS_MARK(15);
         // ---- O^T += V^T P^T -----------------------------------------------------------------------
 #pragma unroll
         for (int t = 0; t < DT; ++t)
@@ -357,17 +335,14 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
         }
         // Issue order of this block: V^T fragments several reads ahead of the matrix instructions that take
         // them (the compiler's own order waits for every other read just before its use).
-        __builtin_amdgcn_sched_group_barrier(0x100, NATS_FL_VAHEAD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, FL_VAHEAD, 0);
 #pragma unroll
         for (int i = 0; i < DT * 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        if (kt == NATS_MARK_TILE) NATS_MARK(16);
     }
-    NATS_MARK(2);
     __syncthreads();   // tiles are dead: the region becomes the output staging
-    NATS_MARK(3);
 
     if (!MERGE && O_nla_out == nullptr) {
         // Nothing to merge and no fp32 copy asked for: the normalised rows are staged as fp16, both
@@ -392,7 +367,6 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
                                    accO[nq][t][3] * inv_l});
         }
         __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
-        NATS_MARK(21);
         u32x4 rows[FL_NQ * 16 / RPP_H];
 #pragma unroll
         for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass)
@@ -402,8 +376,6 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
             const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
             if (q < L) *reinterpret_cast<u32x4*>(O_nla_h + (tokbase + q) * D + 8 * (lane % LPR_H)) = rows[pass];
         }
-        NATS_MARK(22);
-        NATS_MARK(4);
         return;
     }
 
@@ -475,7 +447,6 @@ __global__ __launch_bounds__(FL_THREADS, NATS_FL_OCC) void flash_softmax_kernel(
         }
         __builtin_amdgcn_wave_barrier();
     }
-    NATS_MARK(4);
 }
 
 template <int D, bool MERGE>

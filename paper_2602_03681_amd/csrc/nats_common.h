@@ -169,13 +169,10 @@ struct ProfScope {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Resolved forward problem handed to the kernel launchers.
-#ifndef NATS_BWD_DKV_SEGMENTS
-#define NATS_BWD_DKV_SEGMENTS 8
-#endif
-constexpr int BWD_DKV_SEGMENTS = NATS_BWD_DKV_SEGMENTS;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
+constexpr int BWD_DKV_SEGMENTS = 8;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
 constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse sweep: d / 16 blocks and partial sums per (batch, head)
 
+// Resolved forward problem handed to the kernel launchers.
 struct FwdPlan {
     int B, H, L, d, C, BH;
     int dtype;

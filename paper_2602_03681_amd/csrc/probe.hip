@@ -3,6 +3,7 @@
 // kernel rates against this measured ceiling beside the published peak.
 #include "mfma_util.h"
 #include "nats_common.h"
+#include "nats_measure.h"
 
 namespace nats {
 

@@ -9,7 +9,7 @@ import pytest
 from paper_2602_03681_amd import binding as nb
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "nats.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 
 OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_UNSUP = 0, -1, -2, -3, -4, -5, -6
 FAKE = 0x10000  # an aligned non-NULL "device pointer"; validation fails before it is ever used
@@ -24,7 +24,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(nats_[a-z0-9_]+)\s*\(", text)))
 
