@@ -26,8 +26,9 @@
 // inversion kernel).  No barrier and no LDS round trip stands inside the chain.
 //   The four STAGING wavefronts prepare what all d_v slices share, one chunk ahead, in a double-buffered LDS
 // set: the K and Q tiles (contiguous loads, converted to fp16 once, columns permuted into the slot order above),
-// K^T scaled by kd (transposed on the matrix cores: a product with a 0/1 selector hands a row-major fragment
-// back in the accumulator layout, exactly), T'', P and the gates.  They also merge and store the output rows,
+// T'', P and the gates.  (K^T scaled by kd, the operand of the state update, is made by the state wavefronts
+// from the K tile, a (contraction step, column half) share each: a product with a 0/1 selector hands a row-major
+// fragment back in the accumulator layout, exactly.)  They also merge and store the output rows,
 // which the state wavefronts leave in an LDS tile (computed transposed, S0 Q^T and U^T P^T, so that a lane
 // holds four consecutive d_v of a token): whole rows of 2 d bytes go out.
 //   Two block barriers per chunk: one before the output tile is overwritten, one when the next operand set is
