@@ -431,3 +431,66 @@ def decode_commit_chunk(st, m, decay_on_softmax=True):
         st["cache_len"] = min(st["cache_len"] + st["pos"], st["k_cache"].shape[0])
         st["S"] = (st["decay"] if decay_on_softmax else 1.0) * st["S_start"]
     st["pos"] = 0
+
+
+# --------------------------------------------------------------------------- #
+# head grouping (Section 4.3; appendix "Experimental details": 2 or 3 softmax heads per Gated DeltaNet head)
+# --------------------------------------------------------------------------- #
+def hybrid_fwd_grouped(Q, K, V, alpha, beta, mask, G, C=None, softmax_scale=None, la_scale=1.0, mode=0,
+                       w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
+                       Q_nla=None, K_nla=None):
+    """G softmax heads share the routing mask (and so the set of softmax tokens) of one linear head.
+
+    The linear family uses fewer, wider heads than the softmax family, so every linear head h is matched by the
+    G softmax heads h G .. h G + G - 1, which "share the same set of attention types and the corresponding masks";
+    each linear head has its own mask.  Shapes: Q, K [B,H,L,d] (linear head: its queries and keys), alpha, beta,
+    mask [B,H,L] (mask [B,H,L/C] with routing per chunk, C given); V [B,H G,L,d]: the value columns of linear head
+    h are the G blocks V[:, h G + g] side by side, i.e. its state is S in R^{(G d) x d}, and softmax head h G + g
+    attends with the g-th block as its values; Q_nla, K_nla [B,H G,L,d] are the softmax heads' queries and keys
+    (None: every softmax head of a group uses the linear head's).  Output head h G + g merges the g-th block of
+    the linear head's output columns with softmax head h G + g (sum, or Eq. 21 with the normalisations over the d
+    columns of the block and weights w [B,H G,L]).
+    Returns the dict of hybrid_fwd with H G heads (S [B,H G,d,d]: row blocks of the wide states); cnt, n_s, idx
+    per linear head."""
+    Q, K, V = (np.asarray(a, dtype=np.float64) for a in (Q, K, V))
+    B, H, L, d = Q.shape
+    assert V.shape[:3] == (B, H * G, L)
+    dv = V.shape[-1]
+    out = {"O": np.zeros((B, H * G, L, dv)), "O_la": np.zeros((B, H * G, L, dv)), "O_nla": np.zeros((B, H * G, L, dv)),
+           "lse": np.zeros((B, H * G, L)), "S": np.zeros((B, H * G, dv, d)),
+           "cnt": np.zeros((B, H, L), dtype=np.int32), "n_s": np.zeros((B, H), dtype=np.int32),
+           "idx": [[None] * H for _ in range(B)]}
+    for b in range(B):
+        for h in range(H):
+            hs = slice(h * G, (h + 1) * G)
+            v_wide = np.concatenate(list(V[b, hs]), axis=-1)                       # [L, G d]
+            s0_wide = None if S0 is None else np.concatenate(list(np.asarray(S0, dtype=np.float64)[b, hs]), axis=0)
+            if C is None:
+                tok_mask = np.asarray(mask[b, h])
+                o_la, S = gdn_recurrent(Q[b, h], K[b, h], v_wide, alpha[b, h], beta[b, h], tok_mask, S0=s0_wide,
+                                        la_scale=la_scale, decay_on_softmax=decay_on_softmax, linear_op=linear_op)
+            else:
+                r = hybrid_head_chunk_routed(Q[b, h], K[b, h], v_wide, alpha[b, h], beta[b, h], mask[b, h], C,
+                                             softmax_scale, la_scale, 0, S0=s0_wide, linear_op=linear_op,
+                                             decay_on_softmax=decay_on_softmax)
+                o_la, S = r["O_la"], r["S"]
+                tok_mask = np.repeat(np.asarray(mask[b, h]).reshape(-1) != 0, C)
+            cnt, idx, n_s = compaction(tok_mask)
+            out["cnt"][b, h], out["n_s"][b, h] = cnt, n_s
+            out["idx"][b][h] = idx
+            for g in range(G):
+                hg = h * G + g
+                qn = Q[b, h] if Q_nla is None else np.asarray(Q_nla[b, hg], dtype=np.float64)
+                kn = K[b, h] if K_nla is None else np.asarray(K_nla[b, hg], dtype=np.float64)
+                scale = (1.0 / np.sqrt(d)) if softmax_scale is None else softmax_scale
+                if C is None:
+                    o_nla, lse = softmax_branch(qn, kn, V[b, hg], tok_mask, scale)
+                else:   # the softmax side of the chunk-routed head (its linear side is not used)
+                    r = hybrid_head_chunk_routed(qn, kn, V[b, hg], alpha[b, h], beta[b, h], mask[b, h], C, scale)
+                    o_nla, lse = r["O_nla"], r["lse"]
+                o_la_g = o_la[:, g * dv:(g + 1) * dv]
+                out["O"][b, hg] = combine(o_la_g, o_nla, mode, None if w_nla is None else w_nla[b, hg],
+                                          None if w_la is None else w_la[b, hg], eps)
+                out["O_la"][b, hg], out["O_nla"][b, hg], out["lse"][b, hg] = o_la_g, o_nla, lse
+                out["S"][b, hg] = S[g * dv:(g + 1) * dv]
+    return out

@@ -1,0 +1,90 @@
+"""Pins of the oracle's head grouping (Section 4.3: several softmax heads share the mask of one linear head).
+
+The grouped operator is written with the linear head's wide state (G d value columns).  It must equal
+(i) G independent single-head operators on repeated q, k, alpha, beta, mask (rows of the state never mix);
+(ii) for the softmax heads, library attention over H G heads with the group's boolean mask repeated;
+(iii) for the wide linear head, the product of the transition matrices of Eq. 19 written out here."""
+import numpy as np
+import pytest
+import torch
+
+from nats_inputs import make_chunk_mask, make_fwd_inputs
+from oracle import nats_oracle as npo
+
+
+def grouped_inputs(B, H, G, L, d, p, seed, own_qk=True):
+    x = make_fwd_inputs(B, H, L, d, "f32", p, seed=seed)
+    rng = np.random.default_rng(seed + 77)
+    x["V"] = rng.standard_normal((B, H * G, L, d)).astype(np.float32)
+    if own_qk:
+        x["Q_nla"] = rng.standard_normal((B, H * G, L, d)).astype(np.float32)
+        x["K_nla"] = rng.standard_normal((B, H * G, L, d)).astype(np.float32)
+    return x
+
+
+def rep(a, G):
+    return np.repeat(a, G, axis=1)
+
+
+@pytest.mark.parametrize("G", [1, 2, 3])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_grouped_equals_independent_heads_with_repeated_mask(G, mode):
+    B, H, L, d = 1, 2, 48, 8
+    x = grouped_inputs(B, H, G, L, d, 0.2, seed=5 + G)
+    rng = np.random.default_rng(3)
+    w1, w2 = rng.random((B, H * G, L)), rng.random((B, H * G, L))
+    S0 = rng.standard_normal((B, H * G, d, d)) * 0.1
+    got = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], G, mode=mode,
+                                 w_nla=w1, w_la=w2, S0=S0, Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    ref = npo.hybrid_fwd(rep(x["Q"], G), rep(x["K"], G), x["V"], rep(x["alpha"], G), rep(x["beta"], G),
+                         rep(x["mask"], G), mode=mode, w_nla=w1, w_la=w2, S0=S0, Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    for key in ("O", "O_la", "O_nla", "S"):
+        np.testing.assert_allclose(got[key], ref[key], rtol=1e-11, atol=1e-12, err_msg=key)
+    np.testing.assert_array_equal(got["cnt"], ref["cnt"][:, ::G])
+    np.testing.assert_array_equal(got["n_s"], ref["n_s"][:, ::G])
+
+
+@pytest.mark.parametrize("G", [2, 3])
+def test_grouped_chunk_routing_equals_independent_heads(G):
+    B, H, L, d, C = 1, 2, 64, 8, 16
+    x = grouped_inputs(B, H, G, L, d, 0.2, seed=11 + G)
+    mc = make_chunk_mask(B, H, L // C, 0.4, 9)
+    mc[:, :, 0] = 1
+    got = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, G, C=C, Q_nla=x["Q_nla"],
+                                 K_nla=x["K_nla"])
+    ref = npo.hybrid_fwd_chunk_routed(rep(x["Q"], G), rep(x["K"], G), x["V"], rep(x["alpha"], G), rep(x["beta"], G),
+                                      rep(mc, G), C, Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    for key in ("O", "O_la", "O_nla", "S", "lse"):
+        np.testing.assert_allclose(got[key], ref[key], rtol=1e-11, atol=1e-12, err_msg=key)
+
+
+def test_softmax_heads_of_a_group_against_library_attention():
+    B, H, G, L, d = 2, 2, 3, 40, 16
+    x = grouped_inputs(B, H, G, L, d, 0.25, seed=21)
+    x["mask"][:, :, 0] = 1
+    got = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], G, softmax_scale=0.3,
+                                 Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    q, k, v = (torch.from_numpy(x[n].astype(np.float64)) for n in ("Q_nla", "K_nla", "V"))
+    col = torch.from_numpy(x["mask"] != 0).repeat_interleave(G, dim=1)            # [B, H G, L]: one mask per group
+    allowed = col[:, :, None, :] & torch.tril(torch.ones(L, L, dtype=torch.bool))   # column j is a softmax token, j <= i
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=allowed, scale=0.3).numpy()
+    np.testing.assert_allclose(got["O_nla"], ref, rtol=1e-10, atol=1e-12)
+
+
+def test_wide_linear_head_against_transition_matrices():
+    """S_t = S_{t-1} alpha_t (I - b_t k_t k_t^T) + b_t v_t k_t^T with b_t = beta_t (1 - m_t) and v_t the G d wide
+    value row (Eq. 19, Eq. 14, Eq. 20), multiplied out for a group of three."""
+    B, H, G, L, d = 1, 1, 3, 24, 6
+    x = grouped_inputs(B, H, G, L, d, 0.3, seed=33, own_qk=False)
+    got = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], G)
+    q, k = x["Q"][0, 0].astype(np.float64), x["K"][0, 0].astype(np.float64)
+    v = np.concatenate([x["V"][0, g].astype(np.float64) for g in range(G)], axis=-1)
+    S = np.zeros((G * d, d))
+    o = np.zeros((L, G * d))
+    for t in range(L):
+        b = float(x["beta"][0, 0, t]) * (1.0 - float(x["mask"][0, 0, t] != 0))
+        S = S @ (float(x["alpha"][0, 0, t]) * (np.eye(d) - b * np.outer(k[t], k[t]))) + b * np.outer(v[t], k[t])
+        o[t] = S @ q[t]
+    for g in range(G):
+        np.testing.assert_allclose(got["O_la"][0, g], o[:, g * d:(g + 1) * d], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(got["S"][0, g], S[g * d:(g + 1) * d], rtol=1e-10, atol=1e-12)
