@@ -107,6 +107,22 @@ typedef struct nats_fwd_params {
                               segments' start states are composed afterwards); 0 chooses automatically
                               (about 256 / (B*H), at least 4 chunks per segment).  The result does not depend
                               on it beyond rounding                                                          */
+    int32_t group;         /* head grouping (Section 4.3; the appendix's model sizes use 2 and 3): G = group
+                              softmax heads share the mask of one linear head, 0 counts as 1, at most 8.
+                              H stays the number of linear heads: Q, K, alpha, beta, mask, cnt, idx, n_s are
+                              [B,H,...].  Everything else has B, H*G heads, output head h*G + g belonging to
+                              linear head h: V (the linear head's value columns are the G blocks V[:, h*G + g]
+                              side by side, i.e. its state is (G d) x d, and softmax head h*G + g attends with
+                              block g), O, Q_nla, K_nla (absent: the softmax heads of a group use the linear
+                              head's Q, K), w_nla, w_la, W_out [H*G,2,d] (applied to the linear head's query),
+                              initial_state, final_state [B,H*G,d,d] (row blocks of the wide states), Kc, Vc,
+                              O_la, O_nla, lse.  Output head h*G + g is the merge of block g of the linear
+                              head's output with softmax head h*G + g (Eq. 21: norms over the d columns of the
+                              block).  The result equals that of group = 1 on H*G heads with Q, K, alpha, beta
+                              and the mask repeated G times; the integers and the per-chunk work of the linear
+                              branch that does not depend on V are done once per linear head.  A generation
+                              step (nats_hybrid_attn_decode) is a call on H*G heads with the linear head's
+                              q, k, alpha, beta, mask repeated.  Not available in the backward pass          */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */

@@ -36,7 +36,7 @@ class FwdParams(ctypes.Structure):
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
                 ("math", ctypes.c_int32), ("routing", ctypes.c_int32), ("linear_op", ctypes.c_int32),
                 ("freeze_on_softmax", ctypes.c_int32), ("weight_act", ctypes.c_int32),
-                ("gdn_segments", ctypes.c_int32)]
+                ("gdn_segments", ctypes.c_int32), ("group", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -156,9 +156,9 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
                     math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN, linear_op=NATS_LINEAR_GDN,
-                    freeze_on_softmax=0, weight_act=0, gdn_segments=0) -> FwdParams:
+                    freeze_on_softmax=0, weight_act=0, gdn_segments=0, group=1) -> FwdParams:
     return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing,
-                     linear_op, int(freeze_on_softmax), weight_act, gdn_segments)
+                     linear_op, int(freeze_on_softmax), weight_act, gdn_segments, group)
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -174,32 +174,36 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                        freeze_on_softmax: bool = False, w_nla=None, w_la=None,
                        W_out=None, weight_act: int = NATS_WEIGHTS_SOFTMAX, initial_state=None, Q_nla=None, K_nla=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
-                       workspace=None, gdn_segments: int = 0) -> Dict[str, torch.Tensor]:
+                       workspace=None, gdn_segments: int = 0, group: int = 1) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
-    (any of final_state, Kc, Vc, n_s, idx, cnt, O_la, O_nla, lse); the result dict always holds "O"."""
+    (any of final_state, Kc, Vc, n_s, idx, cnt, O_la, O_nla, lse); the result dict always holds "O".
+    group = G > 1 (head grouping): Q, K, alpha, beta, mask have H heads, everything else H * G."""
     lib = load_library()
     B, H, L, d = Q.shape
+    HG = H * group
     dt = Q.dtype
-    for name, t in (("Q", Q), ("K", K), ("V", V)):
+    for name, t in (("Q", Q), ("K", K)):
         _require(t, name, (B, H, L, d), dt)
+    _require(V, "V", (B, HG, L, d), dt)
     _require(alpha, "alpha", (B, H, L), torch.float32)
     _require(beta, "beta", (B, H, L), torch.float32)
     _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
-    _require(w_nla, "w_nla", (B, H, L), torch.float32)
-    _require(w_la, "w_la", (B, H, L), torch.float32)
-    _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
-    _require(Q_nla, "Q_nla", (B, H, L, d), dt)
-    _require(K_nla, "K_nla", (B, H, L, d), dt)
+    _require(w_nla, "w_nla", (B, HG, L), torch.float32)
+    _require(w_la, "w_la", (B, HG, L), torch.float32)
+    _require(initial_state, "initial_state", (B, HG, d, d), torch.float32)
+    _require(Q_nla, "Q_nla", (B, HG, L, d), dt)
+    _require(K_nla, "K_nla", (B, HG, L, d), dt)
+    _require(W_out, "W_out", (HG, 2, d), torch.float32)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing, linear_op, freeze_on_softmax, weight_act, gdn_segments)
+                             routing, linear_op, freeze_on_softmax, weight_act, gdn_segments, group)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     dev = Q.device
-    O = torch.empty_like(Q) if out is None else out
-    _require(O, "out", (B, H, L, d), dt)
+    O = torch.empty_like(V) if out is None else out
+    _require(O, "out", (B, HG, L, d), dt)
     want = set(want)
     unknown = want - set(_EX_OUTPUTS)
     if unknown:
@@ -208,16 +212,16 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
         raise ValueError("Kc and Vc come together")
     cap = L if cap is None else cap
     res: Dict[str, torch.Tensor] = {"O": O}
-    if "final_state" in want: res["final_state"] = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    if "final_state" in want: res["final_state"] = torch.empty((B, HG, d, d), dtype=torch.float32, device=dev)
     if "Kc" in want:
-        res["Kc"] = torch.zeros((B, H, cap, d), dtype=dt, device=dev)
-        res["Vc"] = torch.zeros((B, H, cap, d), dtype=dt, device=dev)
+        res["Kc"] = torch.zeros((B, HG, cap, d), dtype=dt, device=dev)
+        res["Vc"] = torch.zeros((B, HG, cap, d), dtype=dt, device=dev)
     if "n_s" in want: res["n_s"] = torch.empty((B, H), dtype=torch.int32, device=dev)
     if "idx" in want: res["idx"] = torch.full((B, H, L), -1, dtype=torch.int32, device=dev)
     if "cnt" in want: res["cnt"] = torch.empty((B, H, L), dtype=torch.int32, device=dev)
-    if "O_la" in want: res["O_la"] = torch.empty((B, H, L, d), dtype=torch.float32, device=dev)
-    if "O_nla" in want: res["O_nla"] = torch.empty((B, H, L, d), dtype=torch.float32, device=dev)
-    if "lse" in want: res["lse"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    if "O_la" in want: res["O_la"] = torch.empty((B, HG, L, d), dtype=torch.float32, device=dev)
+    if "O_nla" in want: res["O_nla"] = torch.empty((B, HG, L, d), dtype=torch.float32, device=dev)
+    if "lse" in want: res["lse"] = torch.empty((B, HG, L), dtype=torch.float32, device=dev)
     g = lambda k: res[k].data_ptr() if k in res else None
     extra = FwdExtra(w_nla.data_ptr() if w_nla is not None else None,
                      w_la.data_ptr() if w_la is not None else None,

@@ -125,7 +125,15 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         return NATS_ERR_SHAPE;
     }
     pl->gdn_segments = p->gdn_segments;
+    if (p->group < 0 || p->group > 8) { set_error("group must be between 1 and 8 (0 counts as 1; got %d)", p->group); return NATS_ERR_SHAPE; }
+    pl->G = p->group > 0 ? p->group : 1;
+    if ((long long)p->B * p->H * pl->G > 65535 || (long long)p->B * p->H * pl->G * p->L > (1ll << 31) - 1) {
+        set_error("B*H*group must not exceed 65535 and B*H*group*L must fit in 31 bits");
+        return NATS_ERR_SHAPE;
+    }
+    pl->qk_per_out_head = 0;   // set by the call: whether the softmax heads have queries and keys of their own
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
+    pl->BHG = pl->BH * pl->G;
     pl->dtype = p->dtype;
     pl->math = p->math;
     pl->softmax_scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
@@ -134,19 +142,20 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     pl->combine_mode = p->combine_mode;
 
     const size_t esz = p->dtype == NATS_BF16 ? 2 : 4;
-    const size_t n_tok = (size_t)pl->BH * pl->L;
+    const size_t n_tok = (size_t)pl->BH * pl->L;     // per linear head: the integers and the per-chunk operands
+    const size_t n_out = (size_t)pl->BHG * pl->L;    // per output head: rows of the cache, of the outputs, weights
     size_t off = 0;
     pl->off_cnt = off; off = align_up(off + n_tok * 4, 256);
     pl->off_idx = off; off = align_up(off + n_tok * 4, 256);
     pl->off_ns = off;  off = align_up(off + (size_t)pl->BH * 4, 256);
-    pl->off_kc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
-    pl->off_vc = off;  off = align_up(off + n_tok * pl->d * esz, 256);
-    pl->off_ola = off; off = align_up(off + n_tok * pl->d * 4, 256);
+    pl->off_kc = off;  off = align_up(off + n_out * pl->d * esz, 256);
+    pl->off_vc = off;  off = align_up(off + n_out * pl->d * esz, 256);
+    pl->off_ola = off; off = align_up(off + n_out * pl->d * 4, 256);
     pl->off_tf = pl->off_p = pl->off_gamv = pl->off_kdv = pl->off_gam = pl->off_seg = pl->off_vht = pl->off_olah = 0;
     pl->off_snap = 0;
-    pl->off_wout = off; off = align_up(off + 2 * n_tok * 4, 256);   // weights of Eq. 21 when computed by Eq. 22
+    pl->off_wout = off; off = align_up(off + 2 * n_out * 4, 256);   // weights of Eq. 21 when computed by Eq. 22
     if (!uses_chunk_path(*pl) && pl->routing == NATS_ROUTE_CHUNK) {   // chunk-start state of the fp32 recurrence
-        pl->off_snap = off; off = align_up(off + (size_t)pl->BH * pl->d * pl->d * 4, 256);
+        pl->off_snap = off; off = align_up(off + (size_t)pl->BHG * pl->d * pl->d * 4, 256);
     }
     if (uses_chunk_path(*pl)) {   // per-chunk operands of the chunkwise linear branch
         pl->off_tf = off;   off = align_up(off + n_tok * pl->C * 2, 256);    // T'' fp16
@@ -155,9 +164,9 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         pl->off_kdv = off;  off = align_up(off + n_tok * 4, 256);
         pl->off_gam = off;  off = align_up(off + (n_tok / pl->C) * 4, 256);
         // start state, zero-run end state and transposed transition of every segment
-        pl->off_seg = off;  off = align_up(off + 3 * (size_t)pl->BH * gdn_segments(*pl) * pl->d * pl->d * 4, 256);
-        pl->off_vht = off;  off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
-        pl->off_olah = off; off = align_up(off + n_tok * pl->d * 2, 256);   // fp16 hand-off between the branches
+        pl->off_seg = off;  off = align_up(off + 3 * (size_t)pl->BHG * gdn_segments(*pl) * pl->d * pl->d * 4, 256);
+        pl->off_vht = off;  off = align_up(off + n_out * pl->d * 2, 256);   // fp16 V^T tiles of the softmax branch
+        pl->off_olah = off; off = align_up(off + n_out * pl->d * 2, 256);   // fp16 hand-off between the branches
     }
     pl->total = off;
     return NATS_OK;
@@ -196,6 +205,7 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
                   pl->routing, pl->combine_mode);
         return NATS_ERR_UNSUPPORTED;
     }
+    if (pl->G != 1) { set_error("the backward pass has no head grouping (group %d given)", pl->G); return NATS_ERR_UNSUPPORTED; }
     plan_bwd(*pl, bp);
     return NATS_OK;
 }
@@ -235,7 +245,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 108; }
+int nats_abi_version(void) { return 109; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -330,6 +340,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     // queries and keys of the softmax branch (the linear branch always takes Q, K)
     const void* Qs = ex.Q_nla != nullptr ? ex.Q_nla : Q;
     const void* Ks = ex.K_nla != nullptr ? ex.K_nla : K;
+    pl.qk_per_out_head = ex.Q_nla != nullptr;   // [B,H*group,L,d]; otherwise the softmax heads of a group share Q, K
 
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
@@ -349,11 +360,11 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (ex.W_out != nullptr && pl.combine_mode != 0) {   // Eq. 22: the merge weights from Q
         float* w = reinterpret_cast<float*>(ws + pl.off_wout);
         ProfScope ps("merge_weights", stream);
-        st = launch_merge_weights(pl.B, pl.H, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BH * pl.L, pl.weight_act,
-                                  stream);
+        st = launch_merge_weights(pl.B, pl.H * pl.G, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BHG * pl.L,
+                                  pl.weight_act, pl.G, stream);
         if (st != NATS_OK) return st;
         ex.w_nla = w;
-        ex.w_la = w + (size_t)pl.BH * pl.L;
+        ex.w_la = w + (size_t)pl.BHG * pl.L;
     }
     // The kernels run one after the other on the caller's stream.  (The softmax branch depends on nothing
     // the preparation of the linear branch computes, but the preparation kernel fills every CU by itself:
@@ -573,7 +584,9 @@ nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const fl
     if (!aligned16(Q) || !aligned16(W_out)) { set_error("Q and W_out must be 16-byte aligned"); return NATS_ERR_ALIGN; }
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     ProfScope ps("merge_weights", stream);
-    return launch_merge_weights(p->B, p->H, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, p->weight_act, stream);
+    const int G = p->group > 0 ? p->group : 1;
+    if (G > 8) { set_error("group must be between 1 and 8 (got %d)", p->group); return NATS_ERR_SHAPE; }
+    return launch_merge_weights(p->B, p->H * G, p->L, p->d, p->dtype, Q, W_out, w_nla, w_la, p->weight_act, G, stream);
 }
 
 nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, int32_t H, int32_t dtype,

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
-    float eps, int BH) {
+    float eps, int BH, int G, int qk_per_out_head) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -96,7 +96,9 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const int tile = n_tiles_g - 1 - (chunk_routing ? blockIdx.x % n_tiles_g : blockIdx.x / bh8);
     if (bh >= BH) return;
     const int q0 = tile * FL_BM;
-    const size_t tokbase = (size_t)bh * L;
+    const size_t tokbase = (size_t)bh * L;                 // bh counts output heads (BH of them)
+    const size_t tokbase_lin = (size_t)(bh / G) * L;       // the linear head whose mask the group shares: cnt
+    const size_t tokbase_qk = qk_per_out_head ? tokbase : tokbase_lin;   // queries and raw keys of the softmax branch
     const float scale2 = scale * 1.44269504088896341f;   // logits in base-2 units
 
     // ---- prologue: the block's Q rows, coalesced, through LDS into B-operand fragments ------------
@@ -111,9 +113,9 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     // earlier chunks, i.e. cnt at the last token before the query's chunk (the chunk's own tokens come
     // from K and V after the compacted tiles, see below).
     auto visible_rows = [&](int t) __attribute__((always_inline)) -> int {
-        if (!chunk_routing) return cnt[tokbase + t];
+        if (!chunk_routing) return cnt[tokbase_lin + t];
         const int cs = t & ~(FL_BN - 1);
-        return cs > 0 ? cnt[tokbase + cs - 1] : 0;
+        return cs > 0 ? cnt[tokbase_lin + cs - 1] : 0;
     };
     int my_cnt[FL_NQ];
 #pragma unroll
@@ -134,9 +136,9 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     };
     // routing per chunk: the dc-th chunk of this block's queries, rows of K and V as they are (V row-major)
     auto load_own_chunk = [&](int dc) __attribute__((always_inline)) {
-        const size_t t0 = tokbase + min(q0 + dc * FL_BN, L - FL_BN);
-        const u32x4* Kt = reinterpret_cast<const u32x4*>(K + t0 * D);
-        const u32x4* Vt = reinterpret_cast<const u32x4*>(V + t0 * D);
+        const size_t t0 = min(q0 + dc * FL_BN, L - FL_BN);
+        const u32x4* Kt = reinterpret_cast<const u32x4*>(K + (tokbase_qk + t0) * D);
+        const u32x4* Vt = reinterpret_cast<const u32x4*>(V + (tokbase + t0) * D);
 #pragma unroll
         for (int i = 0; i < NKP; ++i) {
             kreg[i] = Kt[tid + FL_THREADS * i];
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
         for (int i = 0; i < NQP; ++i) {
             const int e = tid + FL_THREADS * i;
             const int row = e / (D / 8), c8 = e % (D / 8);
-            qreg[i] = *reinterpret_cast<const u32x4*>(Q + (tokbase + min(q0 + row, L - 1)) * D + c8 * 8);
+            qreg[i] = *reinterpret_cast<const u32x4*>(Q + (tokbase_qk + min(q0 + row, L - 1)) * D + c8 * 8);
         }
         if (!chunk_routing) load_tile(0);
 #pragma unroll
@@ -454,17 +456,17 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
                       const void* V, const int32_t* cnt,
                       const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
-    dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BH + 7) & ~7)));
+    dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BHG + 7) & ~7)));
     if (pl.routing == NATS_ROUTE_CHUNK)
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BH);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head);
     else
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BH);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head);
 }
 
 // O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
-    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax) {
+    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax, int G) {
     constexpr int DP = D / 4;       // columns of a row per lane
     constexpr int DPP = DP + 4;     // padded quarter stride: the four quarters land in different banks
     __shared__ __align__(16) float s_k[REC_TT][4 * DPP];
@@ -33,7 +33,9 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     const int bh = blockIdx.y;
     const int tid = threadIdx.x, r = tid >> 2, part = tid & 3;
     const int row = blockIdx.x * REC_ROWS + r;  // d_v index of this lane's row
-    const size_t base = (size_t)bh * L;
+    // bh counts output heads: the G heads of a group are row blocks of one wide state, fed by their own value
+    // columns and by the queries, keys, gates and mask of linear head bh / G (Section 4.3)
+    const size_t base = (size_t)bh * L, lin = (size_t)(bh / G) * L;
     auto row_sum = [](float x) { return lane_group_sum<4>(x); };   // over a row's 4 lanes
 
     float S[DP];
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     // chunk the row goes back to its value at the chunk's start, kept in snap, times the chunk's decay.
     const bool chunk_mask = snap != nullptr;
     float* my_snap = chunk_mask ? snap + ((size_t)bh * D + row) * D + part * DP : nullptr;
-    const uint8_t* mask_c = mask + (size_t)bh * (L / 64);
+    const uint8_t* mask_c = mask + (size_t)(bh / G) * (L / 64);
     float chunk_decay = 1.f;
 
     constexpr int EPL = Vec16<T>::N;
@@ -65,10 +67,10 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
             const int i = e / D, c = e % D;
             const int pq = c / DP, pc = c % DP;   // EPL divides DP: a 16-byte group stays inside one quarter
             float tmp[EPL];
-            Vec16<T>::load(K + (base + t0 + i) * D + c, tmp);
+            Vec16<T>::load(K + (lin + t0 + i) * D + c, tmp);
 #pragma unroll
             for (int j = 0; j < EPL; ++j) s_k[i][pq * DPP + pc + j] = tmp[j];
-            Vec16<T>::load(Q + (base + t0 + i) * D + c, tmp);
+            Vec16<T>::load(Q + (lin + t0 + i) * D + c, tmp);
 #pragma unroll
             for (int j = 0; j < EPL; ++j) s_q[i][pq * DPP + pc + j] = tmp[j];
         }
@@ -81,9 +83,9 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
         }
         if (tid < REC_TT) {
             // variant without decay on softmax tokens (routing per token): their alpha counts as 1
-            s_a[tid] = (freeze_on_softmax && !chunk_mask && mask[base + t0 + tid]) ? 1.f : alpha[base + t0 + tid];
+            s_a[tid] = (freeze_on_softmax && !chunk_mask && mask[lin + t0 + tid]) ? 1.f : alpha[lin + t0 + tid];
             // routing per token: softmax tokens never write
-            s_b[tid] = (!chunk_mask && mask[base + t0 + tid]) ? 0.f : beta[base + t0 + tid];
+            s_b[tid] = (!chunk_mask && mask[lin + t0 + tid]) ? 0.f : beta[lin + t0 + tid];
         }
         __syncthreads();
 
@@ -151,15 +153,15 @@ template <typename T>
 static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const void* V, const float* alpha,
                        const float* beta, const uint8_t* mask, const float* S0, float* S_final,
                        float* O_la, float* snap, hipStream_t st) {
-    dim3 grid(pl.d / REC_ROWS, pl.BH);
+    dim3 grid(pl.d / REC_ROWS, pl.BHG);
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,

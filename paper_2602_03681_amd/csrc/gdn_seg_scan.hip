@@ -81,7 +81,9 @@ struct SegArgs {
     float* O_la_f32;          // optional fp32 copy of the linear-branch output
     const half_t* O_nla_h;    // fp16 softmax-branch output to add (plain-sum merge) or nullptr
     bf16_t* O;                // merged output (with O_nla_h)
-    int L, BH, n_seg, seg_len, pass, gated;
+    int L, BH, n_seg, seg_len, pass, gated;   // BH counts output heads
+    int G;                    // output heads per linear head (head grouping): K, Q, T'', P and the gates are the
+                              // linear head's (index bh / G), V, the state and the outputs the output head's
     float la_scale;
 };
 
@@ -433,8 +435,9 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
     const int pt = threadIdx.x - SEG_GROUP;
     const int n_chunks = a.L / SC;
     const int c_begin = seg * a.seg_len, c_end = min(c_begin + a.seg_len, n_chunks);
-    const size_t tokb = (size_t)bh * a.L;
-    const size_t chb = (size_t)bh * n_chunks;
+    const size_t tokb = (size_t)bh * a.L;                  // output rows (and the softmax branch's)
+    const size_t tokl = (size_t)(bh / a.G) * a.L;          // K, Q rows: the linear head's
+    const size_t chb = (size_t)(bh / a.G) * n_chunks;      // its per-chunk operands
     const half_t lah = (half_t)a.la_scale;
     const half8 la8 = {lah, lah, lah, lah, lah, lah, lah, lah};
     half_t* OutT = lds + Lds::o_Out;
@@ -501,7 +504,7 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
     };
     auto load_all = [&](Regs& r, int c) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < Regs::N_LOADS; ++i) r.load_piece(i, a, (tokb + (size_t)c * SC) * D, chb + c, pt);
+        for (int i = 0; i < Regs::N_LOADS; ++i) r.load_piece(i, a, (tokl + (size_t)c * SC) * D, chb + c, pt);
     };
 
     // One step: the registers `cur` hold chunk c + 1; it goes into the LDS set the state group reads next, while
@@ -516,7 +519,7 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < PER; ++k, ++li)
-                if (li < Regs::N_LOADS) nxt.load_piece(li, a, (tokb + (size_t)c2 * SC) * D, chb + c2, pt);
+                if (li < Regs::N_LOADS) nxt.load_piece(li, a, (tokl + (size_t)c2 * SC) * D, chb + c2, pt);
             __builtin_amdgcn_sched_barrier(0);
             write_piece(i, cur, set);
         }
@@ -552,8 +555,10 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     const int n_mid = a.n_seg > 2 ? a.n_seg - 2 : 0;
     const int per_bh = a.pass == 1 ? 1 + 2 * n_mid : a.n_seg - 1;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int bh = (slot / per_bh) * 8 + xcd;
-    if (bh >= a.BH) return;
+    // (with head grouping the G output heads of a linear head, which read the same K, Q, T'', P, share it too)
+    const int hq = slot / per_bh, grp = (hq / a.G) * 8 + xcd;
+    if (grp >= a.BH / a.G) return;
+    const int bh = grp * a.G + hq % a.G;
     const int sub = slot % per_bh;
     const bool staging = threadIdx.x >= SEG_GROUP;   // uniform per wavefront
     int role, seg;
@@ -710,7 +715,7 @@ __global__ __launch_bounds__(FIX_THREADS) void gdn_seg_fix_kernel(float* __restr
 // number of segments a (batch, head) is cut into: enough blocks to fill the chip, at least 4 chunks each
 int gdn_segments(const FwdPlan& pl) {
     const int n_chunks = pl.L / SC;
-    int n = pl.gdn_segments > 0 ? pl.gdn_segments : std::max(1, 256 / pl.BH);
+    int n = pl.gdn_segments > 0 ? pl.gdn_segments : std::max(1, 256 / pl.BHG);
     n = std::min(n, std::max(1, n_chunks / 4));
     return std::max(1, std::min(n, 64));
 }
@@ -732,7 +737,7 @@ static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     a.n_seg = gdn_segments(pl);
     a.seg_len = (n_chunks + a.n_seg - 1) / a.n_seg;
     a.n_seg = (n_chunks + a.seg_len - 1) / a.seg_len;   // no empty segment
-    const int bh8 = 8 * ((pl.BH + 7) / 8);
+    const int bh8 = 8 * ((pl.BH + 7) / 8) * pl.G;   // linear heads padded to the XCD count, times the group size
     const int n_mid = a.n_seg > 2 ? a.n_seg - 2 : 0;
     {
         ProfScope ps("gdn_seg_pass1", st);
@@ -743,8 +748,8 @@ static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     if (s != NATS_OK || a.n_seg == 1) return s;
     if (n_mid > 0) {
         ProfScope ps("gdn_seg_fix", st);
-        hipLaunchKernelGGL(gdn_seg_fix_kernel<D>, dim3(8 * ((pl.BH * (D / 16) + 7) / 8)), dim3(FIX_THREADS), 0, st, a.S_start, a.Nbuf,
-                           a.MTbuf, pl.BH, a.n_seg);
+        hipLaunchKernelGGL(gdn_seg_fix_kernel<D>, dim3(8 * ((pl.BHG * (D / 16) + 7) / 8)), dim3(FIX_THREADS), 0, st, a.S_start, a.Nbuf,
+                           a.MTbuf, pl.BHG, a.n_seg);
         s = check_launch("gdn_seg_fix");
         if (s != NATS_OK) return s;
     }
@@ -769,18 +774,18 @@ nats_status launch_gdn_seg_scan(const FwdPlan& pl, const void* Q, const void* K,
                                 const void* PF, const float* gamv, const float* kdv, const float* gamC,
                                 const float* S0, float* S_final, float* seg_ws, void* O_la_h, float* O_la_f32,
                                 const void* O_nla_h, void* O, hipStream_t st) {
-    const size_t per = (size_t)pl.BH * gdn_segments(pl) * pl.d * pl.d;
+    const size_t per = (size_t)pl.BHG * gdn_segments(pl) * pl.d * pl.d;
     if (pl.d == 64) {
         SegArgs<64> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const half_t*)TF, (const half_t*)PF,
                       gamv, kdv, gamC, S0, S_final, seg_ws, seg_ws + per, seg_ws + 2 * per, (half_t*)O_la_h,
-                      O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BH, 0, 0, 0,
-                      pl.linear_op == NATS_LINEAR_GATED, pl.la_scale};
+                      O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BHG, 0, 0, 0,
+                      pl.linear_op == NATS_LINEAR_GATED, pl.G, pl.la_scale};
         return launch_seg_t<64>(pl, a, st);
     }
     SegArgs<128> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const half_t*)TF, (const half_t*)PF,
                    gamv, kdv, gamC, S0, S_final, seg_ws, seg_ws + per, seg_ws + 2 * per, (half_t*)O_la_h,
-                   O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BH, 0, 0, 0,
-                   pl.linear_op == NATS_LINEAR_GATED, pl.la_scale};
+                   O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BHG, 0, 0, 0,
+                   pl.linear_op == NATS_LINEAR_GATED, pl.G, pl.la_scale};
     return launch_seg_t<128>(pl, a, st);
 }
 

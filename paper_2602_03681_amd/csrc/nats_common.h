@@ -175,6 +175,10 @@ constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse swee
 // Resolved forward problem handed to the kernel launchers.
 struct FwdPlan {
     int B, H, L, d, C, BH;
+    // head grouping (Section 4.3): G output heads (own V, own softmax branch, own state rows) per linear head (own
+    // Q, K, alpha, beta, mask).  BHG = BH * G output heads; qk_per_out_head: the softmax branch's queries and keys
+    // are given per output head (otherwise it uses the linear head's)
+    int G, BHG, qk_per_out_head;
     int dtype;
     int math;
     float softmax_scale, la_scale, rms_eps;
@@ -227,7 +231,7 @@ nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, f
 nats_status launch_route_chunks(int B, int L, int C, int d_model, int H, int dtype, const void* X, const float* W_s,
                                 float* scores, uint8_t* mask_c, hipStream_t st);
 nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const void* Q, const float* W_out,
-                                 float* w_nla, float* w_la, int act, hipStream_t st);
+                                 float* w_nla, float* w_la, int act, int G, hipStream_t st);
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,
                                  const float* chunk_decay, int32_t* chunk_pos, int32_t* cache_len,
                                  const uint8_t* mask_c, int32_t* err_flags, hipStream_t st);

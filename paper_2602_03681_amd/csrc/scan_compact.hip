@@ -25,10 +25,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     const uint8_t* __restrict__ mask, const T* __restrict__ K, const T* __restrict__ V, int L, int d,
     int32_t* __restrict__ cnt, int32_t* __restrict__ idx, int32_t* __restrict__ n_s, T* __restrict__ Kc,
     T* __restrict__ Vc, T* __restrict__ Kc_user, T* __restrict__ Vc_user, int cap_user,
-    half_t* __restrict__ VhT, int chunk_mask) {
+    half_t* __restrict__ VhT, int chunk_mask, int G, int k_per_out_head) {
     __shared__ int s_wave[SCAN_THREADS / 64];
     __shared__ int s_pos[SCAN_SEG];
-    const int bh = blockIdx.y;
+    // Head grouping (Section 4.3): G output heads share the mask of linear head bh.  Every output head gathers
+    // its own value rows (and its own key rows, if the softmax heads have keys of their own); the integers are
+    // the group's and are stored by its first head.
+    const int bo = blockIdx.y;           // output head
+    const int bh = bo / G;               // linear head: mask, cnt, idx, n_s
+    const bool first = bo % G == 0;
+    const int bk = k_per_out_head ? bo : bh;
     const int seg0 = blockIdx.x * SCAN_SEG;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // chunk_mask: one mask byte per chunk of 64 tokens (routing per chunk: every token of a softmax
@@ -76,14 +82,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
         for (int j = 0; j < 4; ++j) {
             if ((w >> (8 * j)) & 0xffu) {
                 s_pos[local] = t0 + j;
-                idx[(size_t)bh * L + before + local] = t0 + j;
+                if (first) idx[(size_t)bh * L + before + local] = t0 + j;
                 ++local;
             }
             c[j] = before + local;
         }
-        *reinterpret_cast<int4*>(cnt + (size_t)bh * L + t0) = make_int4(c[0], c[1], c[2], c[3]);
+        if (first) *reinterpret_cast<int4*>(cnt + (size_t)bh * L + t0) = make_int4(c[0], c[1], c[2], c[3]);
     }
-    if (seg0 + SCAN_SEG >= L && tid == 0) n_s[bh] = before + seg_total;
+    if (seg0 + SCAN_SEG >= L && tid == 0 && first) n_s[bh] = before + seg_total;
     __syncthreads();
 
     // ---- 3. gather the K / V rows of this segment's softmax tokens ------------------------
@@ -94,20 +100,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     for (int r = tid / lpr; r < seg_total; r += rows_per_pass) {
         const int t = s_pos[r];
         const int c = before + r;
-        const size_t src = ((size_t)bh * L + t) * d + part * EPL;
-        const uint4 kv = *reinterpret_cast<const uint4*>(K + src);
-        const uint4 vv = *reinterpret_cast<const uint4*>(V + src);
-        const size_t dst = ((size_t)bh * L + c) * d + part * EPL;
+        const uint4 kv = *reinterpret_cast<const uint4*>(K + ((size_t)bk * L + t) * d + part * EPL);
+        const uint4 vv = *reinterpret_cast<const uint4*>(V + ((size_t)bo * L + t) * d + part * EPL);
+        const size_t dst = ((size_t)bo * L + c) * d + part * EPL;
         *reinterpret_cast<uint4*>(Kc + dst) = kv;
         *reinterpret_cast<uint4*>(Vc + dst) = vv;
         if (Kc_user != nullptr && c < cap_user) {
-            const size_t du = ((size_t)bh * cap_user + c) * d + part * EPL;
+            const size_t du = ((size_t)bo * cap_user + c) * d + part * EPL;
             *reinterpret_cast<uint4*>(Kc_user + du) = kv;
             *reinterpret_cast<uint4*>(Vc_user + du) = vv;
         }
         if (VhT != nullptr) {   // fp16 copy, transposed inside tiles of 64 compacted rows: [tile][d][64]
             const T* ve = reinterpret_cast<const T*>(&vv);
-            half_t* tile = VhT + ((size_t)bh * L + (size_t)(c >> 6) * 64) * d;
+            half_t* tile = VhT + ((size_t)bo * L + (size_t)(c >> 6) * 64) * d;
 #pragma unroll
             for (int j = 0; j < EPL; ++j) tile[(size_t)(part * EPL + j) * 64 + vht_col(c)] = elem_to_half(ve[j]);
         }
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
     if (VhT != nullptr && seg0 + SCAN_SEG >= L) {
         const int n_total = before + seg_total;
         const int pad = ((n_total + 63) & ~63) - n_total;
-        half_t* tile = VhT + ((size_t)bh * L + (size_t)(n_total >> 6) * 64) * d;
+        half_t* tile = VhT + ((size_t)bo * L + (size_t)(n_total >> 6) * 64) * d;
         for (int e = tid; e < pad * d; e += SCAN_THREADS) {
             const int dv = e / pad, cc = (n_total & 63) + e % pad;
             tile[(size_t)dv * 64 + vht_col(cc)] = (half_t)0.f;
@@ -127,17 +132,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,
                                 int32_t* cnt, int32_t* idx, int32_t* n_s, void* Kc, void* Vc,
                                 void* Kc_user, void* Vc_user, int cap_user, void* VhT, hipStream_t st) {
-    dim3 grid((pl.L + SCAN_SEG - 1) / SCAN_SEG, pl.BH);
+    dim3 grid((pl.L + SCAN_SEG - 1) / SCAN_SEG, pl.BHG);
     if (pl.dtype == NATS_BF16) {
         hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
                            (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT,
-                           pl.routing == NATS_ROUTE_CHUNK);
+                           pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head);
     } else {
         hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, mask,
                            (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
                            (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT,
-                           pl.routing == NATS_ROUTE_CHUNK);
+                           pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head);
     }
     return check_launch("scan_compact");
 }

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc,
     const T* __restrict__ K, const T* __restrict__ V, int chunk_routing, const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, T* __restrict__ O, float* __restrict__ O_nla_out,
-    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps) {
+    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps, int G, int qk_per_out_head) {
     constexpr int DP = D / 4;       // elements of a row per lane
     constexpr int DPP = DP + 4;     // padded quarter stride (floats): quarters land in different banks
     constexpr int EPL = Vec16<T>::N;
@@ -39,11 +39,15 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     const int tid = threadIdx.x;
     const int r = tid >> 2, part = tid & 3;
     const int t = q0 + r;
-    const size_t row_off = ((size_t)bh * L + t) * D + part * DP;
+    // bh counts output heads; the G heads of a group share the counts of linear head bh / G, and take their
+    // queries (and the raw keys of their own chunk) from it unless the softmax heads have their own
+    const size_t tokb = (size_t)bh * L, tokb_lin = (size_t)(bh / G) * L;
+    const size_t tokb_qk = qk_per_out_head ? tokb : tokb_lin;
+    const size_t row_off = (tokb + t) * D + part * DP;
 
     float q[DP], acc[DP];
 #pragma unroll
-    for (int c = 0; c < DP; c += EPL) Vec16<T>::load(Q + row_off + c, q + c);
+    for (int c = 0; c < DP; c += EPL) Vec16<T>::load(Q + (tokb_qk + t) * D + part * DP + c, q + c);
 #pragma unroll
     for (int c = 0; c < DP; ++c) { q[c] *= scale; acc[c] = 0.f; }
     float m_run = -INFINITY, l_run = 0.f;
@@ -51,21 +55,19 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     // Routing per token: the first cnt[t] compacted rows are visible.  Routing per chunk: a block is
     // exactly one chunk (64 queries); its queries see the compacted rows of earlier chunks, cnt at the
     // last token before the chunk, and then, causally, the chunk's own rows of K and V.
-    const size_t tokb = (size_t)bh * L;
-    const int my_cnt = chunk_routing ? (q0 > 0 ? cnt[tokb + q0 - 1] : 0) : cnt[tokb + t];
-    const int n_hi = chunk_routing ? my_cnt : cnt[tokb + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
+    const int my_cnt = chunk_routing ? (q0 > 0 ? cnt[tokb_lin + q0 - 1] : 0) : cnt[tokb_lin + t];
+    const int n_hi = chunk_routing ? my_cnt : cnt[tokb_lin + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
 
     // One tile of SM_BN rows of (Ks, Vs) starting at row0, the first n_rows of which exist; this
     // query sees the first `mine` of them.
-    auto tile = [&](const T* Ks, const T* Vs, int row0, int n_rows, int mine) {
+    auto tile = [&](const T* Ks, size_t kbase, const T* Vs, int row0, int n_rows, int mine) {
         __syncthreads();
         for (int e = tid * EPL; e < SM_BN * D; e += SM_THREADS * EPL) {
             const int i = e / D, c = e % D;
             float tk[EPL], tv[EPL];
             if (i < n_rows) {
-                const size_t src = (tokb + row0 + i) * D + c;
-                Vec16<T>::load(Ks + src, tk);
-                Vec16<T>::load(Vs + src, tv);
+                Vec16<T>::load(Ks + (kbase + row0 + i) * D + c, tk);
+                Vec16<T>::load(Vs + (tokb + row0 + i) * D + c, tv);
             } else {
 #pragma unroll
                 for (int j = 0; j < EPL; ++j) { tk[j] = 0.f; tv[j] = 0.f; }
@@ -118,9 +120,9 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
             }
         }
     };
-    for (int c0 = 0; c0 < n_hi; c0 += SM_BN) tile(Kc, Vc, c0, min(SM_BN, n_hi - c0), my_cnt - c0);
+    for (int c0 = 0; c0 < n_hi; c0 += SM_BN) tile(Kc, tokb, Vc, c0, min(SM_BN, n_hi - c0), my_cnt - c0);
     if (chunk_routing)   // the block's own chunk, rows q0 .. q0 + 63 of K and V: query row r sees rows <= r
-        for (int d0 = 0; d0 < SM_BM; d0 += SM_BN) tile(K, V, q0 + d0, SM_BN, r + 1 - d0);
+        for (int d0 = 0; d0 < SM_BM; d0 += SM_BN) tile(K, tokb_qk, V, q0 + d0, SM_BN, r + 1 - d0);
 
     // ---- epilogue: normalise, optional branch outputs, merge, store -----------------------
     const float inv_l = (l_run > 0.f) ? 1.f / l_run : 0.f;
@@ -174,17 +176,17 @@ static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const vo
                       const void* V, const int32_t* cnt,
                       const float* O_la, const float* w_nla, const float* w_la, void* O, float* O_nla_out,
                       float* lse_out, hipStream_t st) {
-    dim3 grid(pl.L / SM_BM, pl.BH);
+    dim3 grid(pl.L / SM_BM, pl.BHG);
     if (pl.d == 64)
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 64>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
                            (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
-                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head);
     else
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 128>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
                            (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
-                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps);
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head);
 }
 
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,

@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 108   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc
+    assert lib.nats_abi_version() == 109   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group
 
 
 def good_params(**over):
@@ -214,3 +214,13 @@ def test_noalloc_forward_rejects_large_problems_on_the_host(lib):
     assert b"scratch" in lib.nats_last_error()
     assert lib.nats_hybrid_attn_fwd_noalloc(ctypes.byref(good_params(L=100)), *([FAKE] * 7), None) == E_SHAPE
     assert lib.nats_hybrid_attn_fwd_noalloc(None, *([FAKE] * 7), None) == E_NULL
+
+
+def test_head_grouping_is_validated_on_the_host(lib):
+    assert nb.fwd_workspace_bytes(good_params(group=9)) == 0
+    assert nb.fwd_workspace_bytes(good_params(group=-1)) == 0
+    one, three = nb.fwd_workspace_bytes(good_params(group=0)), nb.fwd_workspace_bytes(good_params(group=3))
+    assert one == nb.fwd_workspace_bytes(good_params(group=1))
+    assert one < three < 3 * one     # rows per output head grow with the group, the integers do not
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=2))) == 0
+    assert b"group" in lib.nats_last_error()
