@@ -81,9 +81,10 @@ def measured_mfma_busy(kernel):
         return None
 
 
-def bench_decode(args):
+def measure_decode(steps, warmup, split=True):
     """Decode workload (B=64, H=16, d=128, bf16, cache length U{64..2048}): HBM-bound streaming of the
-    fp32 state (read + write) and the live cache rows, one launch per token."""
+    fp32 state (read + write) and the live cache rows, one call per token.  split: the step runs on a caller
+    workspace as many blocks of equal size (two launches) instead of one block per (batch, head)."""
     import numpy as np
     import torch
 
@@ -92,8 +93,8 @@ def bench_decode(args):
     from nats_inputs import CONFIGS, make_decode_inputs
 
     cfg = CONFIGS["cfg4_decode_bf16"]
-    steps = max(args.steps, 1)
-    x = make_decode_inputs(cfg, steps=steps + args.warmup)
+    steps = max(steps, 1)
+    x = make_decode_inputs(cfg, steps=steps + warmup)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     g = {}
@@ -102,19 +103,23 @@ def bench_decode(args):
             t = torch.from_numpy(v).to(dev)
             g[k] = t.to(torch.bfloat16) if k in ("q", "k", "v", "k_cache", "v_cache") else t
     o = torch.empty((cfg.B, cfg.H, cfg.d), dtype=torch.bfloat16, device=dev)
+    ws = None
+    if split:
+        ws = torch.empty(nb.decode_workspace_bytes(cfg.B, cfg.H, cfg.d, g["k_cache"].shape[2], nb.NATS_BF16),
+                         dtype=torch.uint8, device=dev)
 
     def step(i):
         nats.hybrid_attn_decode(g["state"], g["k_cache"], g["v_cache"], g["cache_len"], g["q"][i], g["k"][i],
-                                g["v"][i], g["alpha"][i], g["beta"][i], g["mask"][i], out=o)
+                                g["v"][i], g["alpha"][i], g["beta"][i], g["mask"][i], out=o, workspace=ws)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     len0 = g["cache_len"].sum().item()
     nb.profile_begin(4 * steps)
     t0 = time.perf_counter()
     for i in range(steps):
-        step(args.warmup + i)
+        step(warmup + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern = nb.profile_end()
@@ -122,15 +127,22 @@ def bench_decode(args):
     ms = (t1 - t0) * 1e3 / steps
     bh, d = cfg.B * cfg.H, cfg.d
     bytes_per_step = bh * 8 * d * d + 0.5 * (len0 + len1) * 4 * d      # state r+w (fp32) + live K,V rows (bf16)
-    achieved = bytes_per_step / (kern["decode"]["avg_ms"] * 1e-3) / 1e9
-    out = {"metric": "hybrid_attn_decode_tokens_per_s", "value": round(cfg.B / (ms * 1e-3), 1), "unit": "tokens/s",
-           "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": "cfg4_decode_bf16: B=64 H=16 d=128, cache length U{64..2048}, one token per step"},
-           "roofline": {"kernel": "decode", "bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0,
-                        "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
-                        "avg_kernel_ms": round(kern["decode"]["avg_ms"], 4)},
-           "cpu_baseline": None}
+    kernel_ms = sum(k["total_ms"] for k in kern.values()) / steps        # all launches of a step
+    achieved = bytes_per_step / (kernel_ms * 1e-3) / 1e9
+    return {"metric": "hybrid_attn_decode_tokens_per_s", "value": round(cfg.B / (ms * 1e-3), 1), "unit": "tokens/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "cfg4_decode_bf16: B=64 H=16 d=128, cache length U{64..2048}, one token per step"
+                                   + (", step as equal blocks on a caller workspace" if split else "")},
+            "kernels_ms": {k: round(v["total_ms"] / steps, 4) for k, v in kern.items()},
+            "roofline": {"kernel": "+".join(kern) if kern else "decode", "bound": "hbm", "achieved": round(achieved, 1),
+                         "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
+                         "algorithmic_bytes": int(bytes_per_step), "avg_kernel_ms": round(kernel_ms, 4)},
+            "cpu_baseline": None}
+
+
+def bench_decode(args):
+    out = measure_decode(args.steps, args.warmup, split=not args.decode_one_block)
     print(json.dumps(out))
 
 
@@ -205,6 +217,10 @@ def main():
     ap.add_argument("--gdn-segments", type=int, default=0,
                     help="segments per (batch, head) of the linear branch's recurrence (0: the library's choice)")
     ap.add_argument("--decode", action="store_true", help="measure the decode workload instead of the forward")
+    ap.add_argument("--decode-one-block", action="store_true",
+                    help="with --decode: one block per (batch, head), no workspace (the step's other form)")
+    ap.add_argument("--no-decode-line", action="store_true",
+                    help="leave the short decode measurement out of the forward's JSON line")
     ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -371,6 +387,12 @@ def main():
            "kernels_ms": {k: round(v["total_ms"] / args.steps, 4) for k, v in kernels.items()},
            "kernel_launches_per_step": {k: v["launches"] // args.steps for k, v in kernels.items()},
            "roofline": roofline, "kernel_rooflines": kernel_rooflines, "cpu_baseline": cpu_baseline}
+    if not args.no_decode_line:
+        # the decode workload beside the headline figure (30 steps after 5): tokens/s and its HBM roofline
+        del Q, K, V, O, ws
+        torch.cuda.empty_cache()
+        dec = measure_decode(30, 5)
+        out["decode"] = {k: dec[k] for k in ("metric", "value", "unit", "ms_per_step", "config", "kernels_ms", "roofline")}
     if measured_peaks is not None:
         out["measured_peaks"] = measured_peaks
     if graph_ms is not None:

@@ -248,7 +248,16 @@ typedef struct nats_dec_params {
     int32_t freeze_on_softmax; /* as in nats_fwd_params (routing per chunk: applied by the commit) */
     const void* q_nla;         /* [B,H,d] dtype or NULL: the softmax branch's own query and key of this token  */
     const void* k_nla;         /* (see nats_fwd_extra.Q_nla); both or neither; k_nla is what the cache receives */
+    void* workspace;           /* NULL, or device scratch of nats_hybrid_attn_decode_workspace_bytes(p) bytes for    */
+    size_t workspace_bytes;    /* nats_hybrid_attn_decode: the step then runs as many blocks of equal size (state
+                                  rows and cache rows of a (b,h) spread over blocks, partial results merged by a
+                                  second kernel) instead of one block per (b,h); same result up to the order of
+                                  the softmax sums.  Worth it when cache lengths differ across the batch.
+                                  Contents undefined afterwards; calls in flight must not share it             */
 } nats_dec_params;
+
+/* Bytes of the optional workspace of nats_hybrid_attn_decode (0 if the params are invalid).  Host-only. */
+size_t nats_hybrid_attn_decode_workspace_bytes(const nats_dec_params* p);
 
 /* For every (b,h):  S <- alpha S;  linear token: S <- S + beta (v - S k) k^T;  softmax token:
  * (k,v) appended to the cache first (it sees itself, Eq. 12 i >= j);  then
@@ -261,7 +270,7 @@ typedef struct nats_dec_params {
  *   o         : out [B,H,d]
  *   err_flags : out [B,H] i32 or NULL; set to 1 where a softmax token found its cache full
  *               (the token is then not stored and o covers the existing rows), else 0.
- * Needs no workspace. */
+ * Needs no workspace (p->workspace = NULL); with one it balances uneven cache lengths, see nats_dec_params. */
 nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void* k_cache, void* v_cache,
                                     int32_t* cache_len, const void* q, const void* k, const void* v,
                                     const float* alpha, const float* beta, const uint8_t* mask,

@@ -62,14 +62,16 @@ class DecParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("la_scale", ctypes.c_float),
                 ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("linear_op", ctypes.c_int32),
-                ("freeze_on_softmax", ctypes.c_int32), ("q_nla", ctypes.c_void_p), ("k_nla", ctypes.c_void_p)]
+                ("freeze_on_softmax", ctypes.c_int32), ("q_nla", ctypes.c_void_p), ("k_nla", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats_hybrid_attn_fwd_ex",
            "nats_hybrid_attn_decode", "nats_last_error", "nats_abi_version", "nats_profile_begin",
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
            "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks",
-           "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd", "nats_hybrid_attn_fwd_noalloc")
+           "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd", "nats_hybrid_attn_fwd_noalloc",
+           "nats_hybrid_attn_decode_workspace_bytes")
 
 
 def library_path() -> str:
@@ -106,6 +108,8 @@ def load_library():
     lib.nats_merge_weights.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 5
     lib.nats_route_chunks.restype = ctypes.c_int
     lib.nats_route_chunks.argtypes = [ctypes.c_int32] * 6 + [vp] * 5
+    lib.nats_hybrid_attn_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.nats_hybrid_attn_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecParams)]
     lib.nats_hybrid_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.nats_hybrid_attn_bwd_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams)]
     lib.nats_hybrid_attn_bwd.restype = ctypes.c_int
@@ -326,8 +330,10 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
 def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta, mask, *,
                        softmax_scale: float = 0.0, la_scale: float = 0.0, combine_mode: int = 0,
                        rms_eps: float = 0.0, linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False,
-                       q_nla=None, k_nla=None, w_nla=None, w_la=None, out=None, err_flags=None) -> torch.Tensor:
-    """nats_hybrid_attn_decode: one token per (b,h); state, caches and cache_len are updated in place."""
+                       q_nla=None, k_nla=None, w_nla=None, w_la=None, out=None, err_flags=None,
+                       workspace=None) -> torch.Tensor:
+    """nats_hybrid_attn_decode: one token per (b,h); state, caches and cache_len are updated in place.
+    workspace: uint8 device tensor of decode_workspace_bytes(...) bytes -> the step runs as many equal blocks."""
     lib = load_library()
     B, H, cap, d = k_cache.shape
     dt = k_cache.dtype
@@ -347,12 +353,20 @@ def hybrid_attn_decode(state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
     _require(k_nla, "k_nla", (B, H, d), dt)
     params = DecParams(B, H, d, cap, _dtype_code(k_cache), softmax_scale, la_scale, combine_mode, rms_eps, linear_op,
                        int(freeze_on_softmax), q_nla.data_ptr() if q_nla is not None else None,
-                       k_nla.data_ptr() if k_nla is not None else None)
+                       k_nla.data_ptr() if k_nla is not None else None,
+                       workspace.data_ptr() if workspace is not None else None,
+                       workspace.numel() if workspace is not None else 0)
     _check(lib.nats_hybrid_attn_decode(ctypes.byref(params), _ptr(state), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(cache_len), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta),
                                        _ptr(mask), _ptr(w_nla), _ptr(w_la), _ptr(o), _ptr(err_flags),
                                        _stream_ptr()))
     return o
+
+
+def decode_workspace_bytes(B, H, d, cap, dtype_code) -> int:
+    """nats_hybrid_attn_decode_workspace_bytes for a cache of `cap` rows per (b,h)."""
+    params = DecParams(B, H, d, cap, dtype_code, 0.0, 0.0, 0, 0.0, 0, 0, None, None, None, 0)
+    return int(load_library().nats_hybrid_attn_decode_workspace_bytes(ctypes.byref(params)))
 
 
 def route_chunks(X, W_s, C: int = 64, want_scores: bool = True):

@@ -559,9 +559,26 @@ nats_status nats_hybrid_attn_decode(const nats_dec_params* p, float* state, void
     const float la_scale = p->la_scale > 0.f ? p->la_scale : 1.0f;
     const float eps = p->rms_eps > 0.f ? p->rms_eps : 1e-6f;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (p->workspace != nullptr) {
+        const size_t need = decode_split_workspace_bytes(*p);
+        if (p->cap > 32768) { set_error("the decode step on a workspace covers caches of at most 32768 rows (cap %d)", p->cap); return NATS_ERR_UNSUPPORTED; }
+        if (p->workspace_bytes < need) {
+            set_error("decode workspace of %zu bytes given, %zu needed", p->workspace_bytes, need);
+            return NATS_ERR_WORKSPACE;
+        }
+        if (!aligned16(p->workspace)) { set_error("the decode workspace is not 16-byte aligned"); return NATS_ERR_ALIGN; }
+        ProfChain prof_chain;
+        return launch_decode_split(*p, scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
+                                   mask, w_nla, w_la, o, err_flags, static_cast<float*>(p->workspace), stream);
+    }
     ProfScope ps("decode", stream);
     return launch_decode(*p, scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, v, alpha, beta,
                          mask, w_nla, w_la, o, err_flags, stream);
+}
+
+size_t nats_hybrid_attn_decode_workspace_bytes(const nats_dec_params* p) {
+    if (validate_dec_params(p) != NATS_OK) return 0;
+    return decode_split_workspace_bytes(*p);
 }
 
 nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const float* W_out, float* w_nla,

@@ -225,6 +225,240 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The same step (routing per token) as many small blocks of equal size, for batches whose caches differ in
+// length: with one block per (batch, head) the longest caches set the time of the step while most CUs idle.
+//   decode_split_kernel   grid (D / DSP_SROWS + n_split, B*H): the first D / DSP_SROWS blocks of a (batch, head)
+//                         each update DSP_SROWS rows of the state (rows are independent) and leave their part
+//                         of o_la in the workspace; block D / DSP_SROWS + s runs the online softmax over cache
+//                         rows [s DSP_ROWS, (s + 1) DSP_ROWS) (exits at once if the cache ends before them) and
+//                         leaves (acc[D], max, sum) in the workspace;
+//   decode_combine_kernel one block per (batch, head): merges the partial softmax results and the new token
+//                         (from registers), merges the branches, appends the token, stores o.
+// Workspace per (batch, head): n_split x (D + 4) floats of partial results, then D floats of o_la.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int DSP_ROWS = 256;    // cache rows per block
+constexpr int DSP_SROWS = 32;    // state rows per block
+
+template <typename T, int D>
+__global__ __launch_bounds__(DEC_THREADS) void decode_split_kernel(
+    float* __restrict__ state, const T* __restrict__ k_cache, const T* __restrict__ v_cache,
+    const int32_t* __restrict__ cache_len, const T* __restrict__ q, const T* __restrict__ k,
+    const T* __restrict__ v, const float* __restrict__ alpha, const float* __restrict__ beta,
+    const uint8_t* __restrict__ mask, float* __restrict__ ws, int cap, int n_split, float scale, float la_scale,
+    int linear_op, int freeze_on_softmax, const T* __restrict__ q_nla) {
+    constexpr int NSP = D / DSP_SROWS;            // state blocks per (batch, head)
+    constexpr int LPR = D / 4;                    // lanes per state row
+    constexpr int ROWS_PER_PASS = DEC_THREADS / LPR;
+    constexpr int PASSES = DSP_SROWS / ROWS_PER_PASS;
+    constexpr int EPL = Vec16<T>::N;
+    constexpr int LPK = D / EPL;
+    constexpr int NSG = DEC_THREADS / LPK;
+    constexpr int UNROLL = 4;
+    const int bh = blockIdx.y, tid = threadIdx.x;
+    float* wsb = ws + (size_t)bh * ((size_t)n_split * (D + 4) + D);
+
+    if (blockIdx.x < NSP) {   // ---- state rows [part * DSP_SROWS, + DSP_SROWS) ----
+        const int lr = tid % LPR, r0 = tid / LPR, row0 = blockIdx.x * DSP_SROWS;
+        float* Sb = state + (size_t)bh * D * D;
+        float4 S4[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+            S4[p] = *reinterpret_cast<const float4*>(Sb + (size_t)(row0 + p * ROWS_PER_PASS + r0) * D + lr * 4);
+        const bool is_softmax = mask[bh] != 0;
+        const float a = (is_softmax && freeze_on_softmax) ? 1.f : alpha[bh];
+        const float b = is_softmax ? 0.f : beta[bh];
+        float kk[4], qq[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            kk[j] = to_float(k[(size_t)bh * D + lr * 4 + j]);
+            qq[j] = to_float(q[(size_t)bh * D + lr * 4 + j]);
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = row0 + p * ROWS_PER_PASS + r0;
+            float4 s = S4[p];
+            s.x *= a; s.y *= a; s.z *= a; s.w *= a;
+            if (b != 0.f) {
+                const float pred = lane_group_sum<LPR>(s.x * kk[0] + s.y * kk[1] + s.z * kk[2] + s.w * kk[3]);
+                const float delta = b * (to_float(v[(size_t)bh * D + row]) - (linear_op == 0 ? pred : 0.f));
+                s.x += delta * kk[0]; s.y += delta * kk[1]; s.z += delta * kk[2]; s.w += delta * kk[3];
+            }
+            const float oq = lane_group_sum<LPR>(s.x * qq[0] + s.y * qq[1] + s.z * qq[2] + s.w * qq[3]);
+            if (lr == 0) wsb[(size_t)n_split * (D + 4) + row] = la_scale * oq;
+            *reinterpret_cast<float4*>(Sb + (size_t)row * D + lr * 4) = s;
+        }
+        return;
+    }
+
+    // ---- cache rows [split * DSP_ROWS, ...) of the rows present ----
+    const int split = blockIdx.x - NSP;
+    const int n_old = min(max(cache_len[bh], 0), cap);
+    const int c_lo = split * DSP_ROWS, c_hi = min(c_lo + DSP_ROWS, n_old);
+    if (c_lo >= c_hi) return;   // uniform: the combine kernel knows which parts exist from the same length
+    __shared__ float s_m[NSG], s_l[NSG];
+    __shared__ float s_acc[NSG][D];
+    const int lk = tid % LPK, sg = tid / LPK;
+    float qf[EPL], acc[EPL];
+    {
+        const T* qs = (q_nla != nullptr ? q_nla : q) + (size_t)bh * D + lk * EPL;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) { qf[j] = to_float(qs[j]) * scale; acc[j] = 0.f; }
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    const T* Kb = k_cache + (size_t)bh * cap * D + lk * EPL;
+    const T* Vb = v_cache + (size_t)bh * cap * D + lk * EPL;
+    for (int c0 = c_lo + sg; c0 < c_hi; c0 += NSG * UNROLL) {
+        float kf[UNROLL][EPL], vf[UNROLL][EPL], sc[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int c = c0 + u * NSG;
+            if (c < c_hi) {
+                Vec16<T>::load(Kb + (size_t)c * D, kf[u]);
+                Vec16<T>::load(Vb + (size_t)c * D, vf[u]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) { kf[u][j] = 0.f; vf[u][j] = 0.f; }
+            }
+        }
+        float bm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) dot += qf[j] * kf[u][j];
+            dot = lane_group_sum<LPK>(dot);
+            sc[u] = (c0 + u * NSG < c_hi) ? dot : -INFINITY;
+            bm = fmaxf(bm, sc[u]);
+        }
+        const float m_new = fmaxf(m_run, bm);   // finite: row c0 exists
+        const float corr = expf(m_run - m_new);
+        l_run *= corr;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[j] *= corr;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const float pw = expf(sc[u] - m_new);
+            l_run += pw;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) acc[j] += pw * vf[u][j];
+        }
+        m_run = m_new;
+    }
+    if (lk == 0) { s_m[sg] = m_run; s_l[sg] = l_run; }
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) s_acc[sg][lk * EPL + j] = acc[j];
+    __syncthreads();
+    if (tid < D) {   // the block's key groups into one partial result, relative to the block's maximum
+        float M = -INFINITY;
+#pragma unroll
+        for (int g = 0; g < NSG; ++g) M = fmaxf(M, s_m[g]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int g = 0; g < NSG; ++g) {
+            const float wgt = expf(s_m[g] - M);   // groups that saw no row have m = -inf -> 0
+            num += wgt * s_acc[g][tid];
+            den += wgt * s_l[g];
+        }
+        float* part = wsb + (size_t)split * (D + 4);
+        part[tid] = num;
+        if (tid == 0) { part[D] = M; part[D + 1] = den; }
+    }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(128) void decode_combine_kernel(
+    const float* __restrict__ ws, T* __restrict__ k_cache, T* __restrict__ v_cache, int32_t* __restrict__ cache_len,
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, const uint8_t* __restrict__ mask,
+    const float* __restrict__ w_nla, const float* __restrict__ w_la, T* __restrict__ o,
+    int32_t* __restrict__ err_flags, int cap, int n_split, float scale, int combine_mode, float eps,
+    const T* __restrict__ q_nla, const T* __restrict__ k_nla) {
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const float* wsb = ws + (size_t)bh * ((size_t)n_split * (D + 4) + D);
+    __shared__ float s_red[4];
+    const bool is_softmax = mask[bh] != 0;
+    const int n_want = cache_len[bh];
+    const int n_old = min(max(n_want, 0), cap);
+    const bool append = is_softmax && n_want >= 0 && n_want < cap;
+    const int n_parts = (n_old + DSP_ROWS - 1) / DSP_ROWS;
+    const bool live = tid < D;
+    const T* qs = q_nla != nullptr ? q_nla : q;
+    const T* ks = k_nla != nullptr ? k_nla : k;
+    // logit of the new token (it attends to itself, Eq. 12 i >= j)
+    float dot = 0.f;
+    if (append) {
+        float x = live ? to_float(qs[(size_t)bh * D + tid]) * scale * to_float(ks[(size_t)bh * D + tid]) : 0.f;
+        x = lane_group_sum<64>(x);
+        if ((tid & 63) == 0) s_red[tid >> 6] = x;
+        __syncthreads();
+        dot = s_red[0] + (D > 64 ? s_red[1] : 0.f);
+        __syncthreads();
+    }
+    // maxima and sums of the parts: loaded side by side (one per thread), then shared
+    __shared__ float s_pm[128], s_pl[128];
+    if (tid < n_parts) {
+        s_pm[tid] = wsb[(size_t)tid * (D + 4) + D];
+        s_pl[tid] = wsb[(size_t)tid * (D + 4) + D + 1];
+    }
+    __syncthreads();
+    float M = append ? dot : -INFINITY;
+    for (int sp = 0; sp < n_parts; ++sp) M = fmaxf(M, s_pm[sp]);
+    float o_nla = 0.f, o_la = 0.f;
+    if (live) {
+        o_la = wsb[(size_t)n_split * (D + 4) + tid];
+        if (M > -INFINITY) {
+            float num = 0.f, den = 0.f;
+#pragma unroll 4
+            for (int sp = 0; sp < n_parts; ++sp) {   // the loads do not depend on each other
+                const float wgt = expf(s_pm[sp] - M);
+                num += wgt * wsb[(size_t)sp * (D + 4) + tid];
+                den += wgt * s_pl[sp];
+            }
+            if (append) {
+                const float pw = expf(dot - M);
+                num += pw * to_float(v[(size_t)bh * D + tid]);
+                den += pw;
+            }
+            o_nla = num / den;
+        }
+    }
+    // ---- append the new token, bookkeeping ----
+    if (append && live) {
+        k_cache[((size_t)bh * cap + n_old) * D + tid] = ks[(size_t)bh * D + tid];
+        v_cache[((size_t)bh * cap + n_old) * D + tid] = v[(size_t)bh * D + tid];
+    }
+    if (tid == 0) {
+        if (append) cache_len[bh] = n_old + 1;
+        if (err_flags != nullptr) err_flags[bh] = (is_softmax && !append) ? 1 : 0;
+    }
+    // ---- merge of the branches ----
+    if (combine_mode == 0) {
+        if (live) o[(size_t)bh * D + tid] = from_float<T>(o_la + o_nla);
+    } else if (combine_mode == 2) {   // one normalisation of the (weighted) sum
+        const float sum = (w_nla ? w_nla[bh] : 1.f) * o_nla + (w_la ? w_la[bh] : 1.f) * o_la;
+        float x = live ? sum * sum : 0.f;
+        x = lane_group_sum<64>(x);
+        if ((tid & 63) == 0) s_red[tid >> 6] = x;
+        __syncthreads();
+        if (live) {
+            const float ss = s_red[0] + (D > 64 ? s_red[1] : 0.f);
+            o[(size_t)bh * D + tid] = from_float<T>(sum / sqrtf(ss / D + eps));
+        }
+    } else {
+        float x = live ? o_la * o_la : 0.f, y = live ? o_nla * o_nla : 0.f;
+        x = lane_group_sum<64>(x); y = lane_group_sum<64>(y);
+        if ((tid & 63) == 0) { s_red[(tid >> 6) * 2] = x; s_red[(tid >> 6) * 2 + 1] = y; }
+        __syncthreads();
+        if (live) {
+            const float ss_la = s_red[0] + (D > 64 ? s_red[2] : 0.f);
+            const float ss_nla = s_red[1] + (D > 64 ? s_red[3] : 0.f);
+            const float wn = (w_nla ? w_nla[bh] : 0.5f) / sqrtf(ss_nla / D + eps);
+            const float wl = (w_la ? w_la[bh] : 0.5f) / sqrtf(ss_la / D + eps);
+            o[(size_t)bh * D + tid] = from_float<T>(wn * o_nla + wl * o_la);
+        }
+    }
+}
+
 // After a chunk has been seen and its type decided (mask_c[b,h] != 0: softmax chunk): a softmax chunk keeps
 // its provisional cache rows and gives the state back as (chunk decay) x (chunk-start state); a linear
 // chunk keeps the state and drops the rows.  chunk_pos returns to 0.  err_flags (optional) is set where
@@ -288,6 +522,44 @@ nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float l
         launch_dec<float, false>(p, softmax_scale, la_scale, eps, state, nullptr, nullptr, nullptr, k_cache, v_cache,
                                  cache_len, q, k, v, alpha, beta, mask, w_nla, w_la, o, err_flags, st);
     return check_launch("decode");
+}
+
+size_t decode_split_workspace_bytes(const nats_dec_params& p) {
+    const size_t n_split = ((size_t)p.cap + DSP_ROWS - 1) / DSP_ROWS;
+    return (size_t)p.B * p.H * (n_split * (p.d + 4) + p.d) * sizeof(float);
+}
+
+template <typename T, int D>
+static void launch_dec_split(const nats_dec_params& p, float scale, float la_scale, float eps, float* state,
+                             void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,
+                             const void* v, const float* alpha, const float* beta, const uint8_t* mask,
+                             const float* w_nla, const float* w_la, void* o, int32_t* err_flags, float* ws,
+                             hipStream_t st) {
+    const int n_split = (p.cap + DSP_ROWS - 1) / DSP_ROWS;
+    {
+        ProfScope ps("decode_split", st);
+        hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(D / DSP_SROWS + n_split, p.B * p.H), dim3(DEC_THREADS), 0, st,
+                           state, (const T*)k_cache, (const T*)v_cache, cache_len, (const T*)q, (const T*)k, (const T*)v,
+                           alpha, beta, mask, ws, p.cap, n_split, scale, la_scale, p.linear_op, p.freeze_on_softmax,
+                           (const T*)p.q_nla);
+    }
+    ProfScope ps("decode_combine", st);
+    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(p.B * p.H), dim3(128), 0, st, ws, (T*)k_cache, (T*)v_cache,
+                       cache_len, (const T*)q, (const T*)k, (const T*)v, mask, w_nla, w_la, (T*)o, err_flags, p.cap,
+                       n_split, scale, p.combine_mode, eps, (const T*)p.q_nla, (const T*)p.k_nla);
+}
+
+nats_status launch_decode_split(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
+                                float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
+                                const void* k, const void* v, const float* alpha, const float* beta,
+                                const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
+                                int32_t* err_flags, float* ws, hipStream_t st) {
+#define NATS_DEC_SPLIT(T, D) launch_dec_split<T, D>(p, softmax_scale, la_scale, eps, state, k_cache, v_cache, cache_len, q, k, \
+                                                    v, alpha, beta, mask, w_nla, w_la, o, err_flags, ws, st)
+    if (p.dtype == NATS_BF16) { if (p.d == 64) NATS_DEC_SPLIT(bf16_t, 64); else NATS_DEC_SPLIT(bf16_t, 128); }
+    else { if (p.d == 64) NATS_DEC_SPLIT(float, 64); else NATS_DEC_SPLIT(float, 128); }
+#undef NATS_DEC_SPLIT
+    return check_launch("decode (split)");
 }
 
 nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,

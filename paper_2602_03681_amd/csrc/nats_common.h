@@ -223,6 +223,12 @@ nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float l
                           const void* k, const void* v, const float* alpha, const float* beta,
                           const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
                           int32_t* err_flags, hipStream_t st);
+size_t decode_split_workspace_bytes(const nats_dec_params& p);
+nats_status launch_decode_split(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
+                                float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
+                                const void* k, const void* v, const float* alpha, const float* beta,
+                                const uint8_t* mask, const float* w_nla, const float* w_la, void* o,
+                                int32_t* err_flags, float* ws, hipStream_t st);
 nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
                                 float* state, float* state_start, float* chunk_decay, int32_t* chunk_pos,
                                 void* k_cache, void* v_cache, int32_t* cache_len, const void* q, const void* k,

@@ -38,7 +38,7 @@ def test_every_declared_function_is_exported(lib):
 
 def test_abi_version(lib):
     assert lib.nats_abi_version() == 109   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
-    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group
+    # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group, decode workspace
 
 
 def good_params(**over):
@@ -224,3 +224,14 @@ def test_head_grouping_is_validated_on_the_host(lib):
     assert one < three < 3 * one     # rows per output head grow with the group, the integers do not
     assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=2))) == 0
     assert b"group" in lib.nats_last_error()
+
+
+def test_decode_workspace_is_validated_on_the_host(lib):
+    n = nb.decode_workspace_bytes(2, 3, 128, 1000, nb.NATS_BF16)
+    assert n == 2 * 3 * (4 * (128 + 4) + 128) * 4          # 4 blocks of 256 rows: (acc, max, sum) each, then o_la
+    assert nb.decode_workspace_bytes(2, 3, 100, 1000, nb.NATS_BF16) == 0
+    p = nb.DecParams(2, 3, 128, 1000, nb.NATS_BF16, 0.0, 0.0, 0, 0.0, 0, 0, None, None, FAKE, n - 1)
+    args = [FAKE] * 15
+    assert lib.nats_hybrid_attn_decode(ctypes.byref(p), *args[:13], None, None) == -5      # NATS_ERR_WORKSPACE
+    p = nb.DecParams(2, 3, 128, 40000, nb.NATS_BF16, 0.0, 0.0, 0, 0.0, 0, 0, None, None, FAKE, 1 << 40)
+    assert lib.nats_hybrid_attn_decode(ctypes.byref(p), *args[:13], None, None) == -6      # cap beyond the form's limit

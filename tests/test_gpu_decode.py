@@ -12,10 +12,21 @@ from gpu_util import TOL, host, oracle_fwd, rel_err, stored, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def run_decode_chain(cfg, steps, n_check_b, dtype, **kw):
-    """GPU runs all B sequences for `steps` steps; the oracle follows the first n_check_b of them."""
+def split_workspace(B, H, d, cap, dtype):
+    """Scratch for the decode step as many equal blocks (nats_dec_params.workspace), poisoned."""
+    from paper_2602_03681_amd import binding as nb
+    n = nb.decode_workspace_bytes(B, H, d, cap, nb.NATS_BF16 if dtype == "bf16" else nb.NATS_F32)
+    assert n > 0
+    return torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda")
+
+
+def run_decode_chain(cfg, steps, n_check_b, dtype, split=False, **kw):
+    """GPU runs all B sequences for `steps` steps; the oracle follows the first n_check_b of them.
+    split: the step runs on the caller's workspace as many equal blocks."""
     x = make_decode_inputs(cfg, steps=steps)
     g = to_dev(x, dtype)
+    if split:
+        kw = dict(kw, workspace=split_workspace(cfg.B, cfg.H, cfg.d, g["k_cache"].shape[2], dtype))
     state = g["state"].clone()
     kc, vc, clen = g["k_cache"].clone(), g["v_cache"].clone(), g["cache_len"].clone()
     err = torch.zeros((cfg.B, cfg.H), dtype=torch.int32, device="cuda")
@@ -24,7 +35,7 @@ def run_decode_chain(cfg, steps, n_check_b, dtype, **kw):
     kc_ref = x["k_cache"][:nb_].copy(); vc_ref = x["v_cache"][:nb_].copy()   # the oracle updates these in place
     clen_ref = x["cache_len"][:nb_].copy()
     worst = 0.0
-    okw = {k: v for k, v in kw.items()}
+    okw = {k: v for k, v in kw.items() if k != "workspace"}
     for s in range(steps):
         o = nats.hybrid_attn_decode(state, kc, vc, clen, g["q"][s], g["k"][s], g["v"][s], g["alpha"][s],
                                     g["beta"][s], g["mask"][s], err_flags=err, **kw)
@@ -56,12 +67,30 @@ def test_cfg4_decode_256_steps():
     print("cfg4 worst step err (adjusted for bf16 storage)", worst)
 
 
+def test_cfg4_decode_256_steps_as_equal_blocks():
+    """The same with the caller's workspace: state rows and cache rows of a (b,h) spread over blocks of equal size
+    (the configuration bench.py times)."""
+    cfg = CONFIGS["cfg4_decode_bf16"]
+    worst = run_decode_chain(cfg, cfg.steps, n_check_b=cfg.B, dtype="bf16", split=True)
+    print("cfg4, split: worst step err (adjusted for bf16 storage)", worst)
+
+
+@pytest.mark.parametrize("split", [False, True])
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64)])
-def test_decode_small_variants(dtype, d):
+def test_decode_small_variants(dtype, d, split):
     cfg = DecodeConfig("small", 3, 2, d, dtype, 0.3, seed=31 + d, len_lo=1, len_hi=70, steps=24)
-    run_decode_chain(cfg, 24, n_check_b=3, dtype=dtype)
-    run_decode_chain(cfg, 8, n_check_b=3, dtype=dtype, combine_mode=1, softmax_scale=float(np.sqrt(d)),
+    run_decode_chain(cfg, 24, n_check_b=3, dtype=dtype, split=split)
+    run_decode_chain(cfg, 8, n_check_b=3, dtype=dtype, split=split, combine_mode=1, softmax_scale=float(np.sqrt(d)),
                      la_scale=0.7, rms_eps=1e-5)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_decode_as_equal_blocks_across_block_boundaries(dtype, d):
+    """Cache lengths that start below and cross 256 and 512 rows (the rows of one block) while the chain runs;
+    every merge mode."""
+    cfg = DecodeConfig("edges", 4, 2, d, dtype, 0.6, seed=77 + d, len_lo=240, len_hi=520, steps=40)
+    for mode in (0, 1, 2):
+        run_decode_chain(cfg, 40, n_check_b=4, dtype=dtype, split=True, combine_mode=mode)
 
 
 def test_decode_empty_cache_and_overflow():
@@ -78,10 +107,19 @@ def test_decode_empty_cache_and_overflow():
     err = torch.zeros((B, H), dtype=torch.int32, device="cuda")
     S_ref = host(state).astype(np.float64); kc_ref, vc_ref = host(kc).copy(), host(vc).copy()
     clen_ref = host(clen).copy()
+    state2, kc2, vc2, clen2, err2 = state.clone(), kc.clone(), vc.clone(), clen.clone(), err.clone()
     o = nats.hybrid_attn_decode(state, kc, vc, clen, q, k, v, alpha, beta, mask, err_flags=err)
     o_ref, ovf = c_oracle.decode(S_ref, kc_ref, vc_ref, clen_ref, host(q), host(k), host(v), host(alpha),
                                  host(beta), host(mask))
     assert rel_err(host(o), o_ref) <= TOL["f32"]
+    # the same step as equal blocks
+    o2 = nats.hybrid_attn_decode(state2, kc2, vc2, clen2, q, k, v, alpha, beta, mask, err_flags=err2,
+                                 workspace=split_workspace(B, H, d, cap, "f32"))
+    assert rel_err(host(o2), o_ref) <= TOL["f32"]
+    np.testing.assert_array_equal(host(err2), [[0, 1]])
+    np.testing.assert_array_equal(host(clen2), [[0, cap]])
+    np.testing.assert_array_equal(host(kc2), kc_ref)
+    assert rel_err(host(state2), S_ref) <= TOL["f32"]
     np.testing.assert_array_equal(host(err), [[0, 1]])
     np.testing.assert_array_equal(ovf, [[0, 1]])
     np.testing.assert_array_equal(host(clen), [[0, cap]])
