@@ -12,6 +12,12 @@ Given dO = dLoss/dO for the plain-sum merge O = O_la + O_nla (Section 4.1), per 
   * softmax branch  -- the usual attention backward over the softmax columns j <= i, and the column sums
     of Eq. 15:  dM_ij = P_ij (dP_ij - do_i . o_i),  g_j = sum_i dM_ij,  which Eq. 16 adds up per chunk into
     the gradient of the softmax score.
+  * score gradient of the linear operation (Eq. 17, "sum of dS . S" over a chunk): the linear mask multiplies what a
+    token (a chunk) adds to the carried state (Eq. 14), so its gradient is the sum over the state's entries of
+    (gradient of the loss with respect to the state after the write) x (what was written); a token or chunk that is
+    inactive for an operation gets no score gradient for it (Section 4.2, last paragraph).
+  * routing per chunk (hybrid_head_chunk_routed_bwd): the adjoint of nats_oracle.hybrid_head_chunk_routed, in
+    which both operations compute every chunk's inner part and the masks act between chunks.
 
 Parity pins: tests/test_oracle_bwd_pins.py checks every output against automatic differentiation of an
 independently written forward (plain PyTorch fp64 on the CPU), the column sums against the derivative with
@@ -49,6 +55,7 @@ def gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0=None, la_scale=1.0, lin
         S_new.append(S)
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
     dalpha, dbeta = np.zeros(L), np.zeros(L)
+    g_la = np.zeros(L)                              # Eq. 17 per token: sum(dS . written) for linear tokens
     dS = np.zeros((d_v, d_k))                       # dLoss/dS after token t, from the tokens behind it
     for t in range(L - 1, -1, -1):
         linear = (mask[t] == 0)
@@ -57,6 +64,7 @@ def gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0=None, la_scale=1.0, lin
         dS = dS + la_scale * np.outer(do[t], q[t])
         if linear:                                  # S_t = Sd + beta r k^T,  r = v - Sd k (delta rule) or v
             r = resid[t]
+            g_la[t] = np.sum(dS * (S_new[t] - S_dec[t]))   # dS is the gradient w.r.t. the state after the write
             dSk = dS @ k[t]                         # [d_v]
             dbeta[t] = r @ dSk
             dr = beta[t] * dSk
@@ -68,7 +76,15 @@ def gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0=None, la_scale=1.0, lin
         if linear or decay_on_softmax:              # Sd = alpha S_{t-1}
             dalpha[t] = np.sum(dS * S_prev[t])
             dS = alpha[t] * dS
-    return {"dq": dq, "dk": dk, "dv": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS}
+    return {"dq": dq, "dk": dk, "dv": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS, "g_la": g_la}
+
+
+def score_gradients(g_nla, g_la, C):
+    """Eq. 16 and Eq. 17 at the granularity of chunks of C tokens: the per-token sums added up per chunk
+    (last axis L -> L / C).  Returns (dscore_nla, dscore_la)."""
+    g_nla, g_la = np.asarray(g_nla, dtype=np.float64), np.asarray(g_la, dtype=np.float64)
+    shp = g_nla.shape[:-1] + (g_nla.shape[-1] // C, C)
+    return g_nla.reshape(shp).sum(-1), g_la.reshape(shp).sum(-1)
 
 
 def softmax_branch_bwd(q, k, v, mask, scale, do):
@@ -104,7 +120,7 @@ def hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=None, la_scale
     la = gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, la_scale, linear_op, decay_on_softmax)
     nla = softmax_branch_bwd(q, k, v, mask, scale, do)
     return {"dQ": la["dq"] + nla["dq"], "dK": la["dk"] + nla["dk"], "dV": la["dv"] + nla["dv"],
-            "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_nla": nla["g"]}
+            "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_nla": nla["g"], "g_la": la["g_la"]}
 
 
 def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
@@ -113,12 +129,128 @@ def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0,
     B, H, L, d = np.asarray(Q).shape
     out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
            "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
-           "g_nla": np.zeros((B, H, L))}
+           "g_nla": np.zeros((B, H, L)), "g_la": np.zeros((B, H, L))}
     for b in range(B):
         for h in range(H):
             r = hybrid_head_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask[b, h], dO[b, h],
                                 softmax_scale, la_scale, None if S0 is None else S0[b, h], linear_op,
                                 decay_on_softmax)
+            for key in out:
+                out[key][b, h] = r[key]
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# routing per chunk (Section 4.1 as stated; Section 4.2 for the score gradients)
+# --------------------------------------------------------------------------- #
+def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_scale=None, la_scale=1.0, S0=None,
+                                 linear_op=0, decay_on_softmax=True):
+    """Adjoint of nats_oracle.hybrid_head_chunk_routed (plain-sum merge).
+
+    Forward being differentiated, per chunk c with carried state S_c: inside the chunk Eq. 19 runs on every token
+    from S_c (the provisional states feed the chunk's own outputs); a linear chunk hands on its last provisional
+    state, a softmax chunk hands on decay_c S_c (its writes are dropped).  Query i attends to all tokens of earlier
+    softmax chunks and to the tokens j <= i of its own chunk.
+    Score gradients (one per chunk): dscore_nla[c] = sum over the columns j of softmax chunk c and the queries i of
+    later chunks of dM_ij (Eq. 15-16; the inner part of a chunk is computed whatever its type, no mask stands on
+    it); dscore_la[c] = sum(dS_{c+1} . (S_{c+1} - decay_c S_c)) for a linear chunk (Eq. 17); zero where the chunk is
+    inactive for the operation.
+    Returns dict(dQ, dK, dV [L,d], dalpha, dbeta [L], dS0, dscore_nla, dscore_la [L/C])."""
+    q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
+    alpha = np.asarray(alpha, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    mask_c = np.asarray(mask_c).reshape(-1) != 0
+    L, d_k = k.shape
+    d_v = v.shape[1]
+    n_c = L // C
+    scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    dalpha, dbeta = np.zeros(L), np.zeros(L)
+    ds_nla, ds_la = np.zeros(n_c), np.zeros(n_c)
+
+    # ---- softmax branch ----
+    earlier = []
+    for c in range(n_c):
+        for i in range(c * C, (c + 1) * C):
+            own = list(range(c * C, i + 1))
+            J = np.asarray(earlier + own, dtype=np.int64)
+            s = scale * (k[J] @ q[i])
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            o = p @ v[J]
+            dm = p * (v[J] @ do[i] - do[i] @ o)           # Eq. 15 (also dLoss/ds_ij)
+            for jj, j in enumerate(J[:len(earlier)]):      # only these columns stand behind the mask
+                ds_nla[j // C] += dm[jj]
+            dv[J] += np.outer(p, do[i])
+            dq[i] += scale * (dm @ k[J])
+            dk[J] += scale * np.outer(dm, q[i])
+        if mask_c[c]:
+            earlier += list(range(c * C, (c + 1) * C))
+
+    # ---- linear branch: forward with everything the reverse sweep needs ----
+    S = np.zeros((d_v, d_k)) if S0 is None else np.array(S0, dtype=np.float64)
+    S_start, S_prev, S_dec, S_new, resid, decay = [], [None] * L, [None] * L, [None] * L, [None] * L, []
+    for c in range(n_c):
+        S_start.append(S)
+        dcy = 1.0
+        for t in range(c * C, (c + 1) * C):
+            S_prev[t] = S
+            S = alpha[t] * S
+            dcy *= alpha[t]
+            S_dec[t] = S
+            r = v[t] - (S @ k[t] if linear_op == 0 else 0.0)
+            S = S + beta[t] * np.outer(r, k[t])
+            resid[t], S_new[t] = r, S
+        decay.append(dcy)
+        if mask_c[c]:
+            S = (dcy if decay_on_softmax else 1.0) * S_start[c]
+    dS_next = np.zeros((d_v, d_k))                     # gradient w.r.t. the state carried into the next chunk
+    for c in range(n_c - 1, -1, -1):
+        last = (c + 1) * C - 1
+        if mask_c[c]:
+            dS = np.zeros((d_v, d_k))                  # the provisional states end with the chunk
+        else:
+            dS = dS_next
+            ds_la[c] = np.sum(dS_next * (S_new[last] - decay[c] * S_start[c]))
+        for t in range(last, c * C - 1, -1):
+            dq[t] += la_scale * (S_new[t].T @ do[t])
+            dS = dS + la_scale * np.outer(do[t], q[t])
+            r = resid[t]
+            dSk = dS @ k[t]
+            dbeta[t] += r @ dSk
+            dr = beta[t] * dSk
+            dk[t] += beta[t] * (dS.T @ r)
+            dv[t] += dr
+            if linear_op == 0:
+                dk[t] -= S_dec[t].T @ dr
+                dS = dS - np.outer(dr, k[t])
+            dalpha[t] += np.sum(dS * S_prev[t])
+            dS = alpha[t] * dS
+        if mask_c[c]:                                  # carried state of a softmax chunk: decay_c S_c
+            if decay_on_softmax:
+                dd = np.sum(dS_next * S_start[c])      # d/d decay_c, decay_c = prod alpha_t
+                for t in range(c * C, (c + 1) * C):
+                    dalpha[t] += dd * decay[c] / alpha[t]
+                dS = dS + decay[c] * dS_next
+            else:
+                dS = dS + dS_next
+        dS_next = dS
+    return {"dQ": dq, "dK": dk, "dV": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS_next,
+            "dscore_nla": ds_nla, "dscore_la": ds_la}
+
+
+def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
+                            decay_on_softmax=True):
+    """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; returns a dict of stacked fp64 arrays."""
+    B, H, L, d = np.asarray(Q).shape
+    out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
+           "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
+           "dscore_nla": np.zeros((B, H, L // C)), "dscore_la": np.zeros((B, H, L // C))}
+    for b in range(B):
+        for h in range(H):
+            r = hybrid_head_chunk_routed_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask_c[b, h], C,
+                                             dO[b, h], softmax_scale, la_scale, None if S0 is None else S0[b, h],
+                                             linear_op, decay_on_softmax)
             for key in out:
                 out[key][b, h] = r[key]
     return out

@@ -133,3 +133,121 @@ def test_batched_wrapper_stacks_heads():
     one = nbw.hybrid_head_bwd(Q[1, 0], K[1, 0], V[1, 0], alpha[1, 0], beta[1, 0], mask[1, 0], dO[1, 0])
     for key in ("dQ", "dK", "dV", "dalpha", "dbeta", "g_nla"):
         np.testing.assert_array_equal(r[key][1, 0], one[key])
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 17 and the backward under routing per chunk
+# --------------------------------------------------------------------------- #
+def test_linear_score_gradient_is_the_derivative_of_a_multiplier_on_the_write():
+    """Eq. 14 / Eq. 17: put a multiplier mu_t on what token t adds to the state, S_t = S' + mu_t beta_t r_t k_t^T;
+    dLoss/dmu_t at mu = 1 is the oracle's g_la[t] (sum of dS . written), zero for softmax tokens, and the chunk
+    sums of Eq. 16-17 are the derivatives with respect to one multiplier per chunk."""
+    q, k, v, alpha, beta, mask, do, S0 = inputs(L=24, d=5, seed=11, p=0.3)
+    L = 24
+    for linear_op in (0, 1):
+        mu = torch.ones(L, dtype=torch.float64, requires_grad=True)
+        tq, tk, tv, ta, tb = (torch.tensor(a, dtype=torch.float64) for a in (q, k, v, alpha, beta))
+        S = torch.tensor(S0)
+        o = []
+        for t in range(L):
+            S = ta[t] * S
+            if mask[t] == 0:
+                r = tv[t] - (S @ tk[t] if linear_op == 0 else 0.0)
+                S = S + mu[t] * tb[t] * torch.outer(r, tk[t])
+            o.append(1.3 * (S @ tq[t]))
+        (torch.stack(o) * torch.tensor(do)).sum().backward()
+        r = nbw.gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, 1.3, linear_op, True)
+        np.testing.assert_allclose(r["g_la"], mu.grad.numpy(), rtol=1e-9, atol=1e-12)
+        assert np.all(r["g_la"][mask != 0] == 0)
+        np.testing.assert_allclose(r["g_la"], beta * r["dbeta"], rtol=1e-9, atol=1e-12)   # the same number, seen from beta
+        C = 8
+        _, ds_la = nbw.score_gradients(np.zeros(L), r["g_la"], C)
+        np.testing.assert_allclose(ds_la, mu.grad.numpy().reshape(L // C, C).sum(1), rtol=1e-12)
+
+
+def torch_forward_chunk_routed(q, k, v, alpha, beta, mask_c, C, S0, scale, la_scale, linear_op, decay_on_softmax,
+                               M=None, mu=None):
+    """Routing per chunk written with torch ops, independently of the oracle: both operations compute the inner
+    part of every chunk; between chunks the column mask of Eq. 12 (softmax) and Eq. 14 (linear) act.  M [L,L]:
+    optional multiplier on exp(A) for the columns of earlier chunks; mu [L/C]: optional multiplier on what a linear
+    chunk adds to the carried state."""
+    L = q.shape[0]
+    S = S0
+    o_la = []
+    for c in range(L // C):
+        S_c, dec = S, 1.0
+        for t in range(c * C, (c + 1) * C):
+            S = alpha[t] * S
+            dec = dec * alpha[t]
+            r = v[t] - (S @ k[t] if linear_op == 0 else 0.0)
+            S = S + beta[t] * torch.outer(r, k[t])
+            o_la.append(la_scale * (S @ q[t]))
+        if mask_c[c]:
+            S = (dec if decay_on_softmax else 1.0) * S_c
+        elif mu is not None:
+            S = dec * S_c + mu[c] * (S - dec * S_c)
+    o_la = torch.stack(o_la)
+    A = scale * (q @ k.T)
+    ci = torch.arange(L) // C
+    soft_col = torch.from_numpy(np.repeat(np.asarray(mask_c) != 0, C))
+    earlier = (ci[None, :] < ci[:, None]) & soft_col[None, :]
+    own = (ci[None, :] == ci[:, None]) & torch.tril(torch.ones(L, L, dtype=torch.bool))
+    E = torch.where(earlier | own, torch.exp(A - A.detach().max()), torch.zeros_like(A))
+    if M is not None:
+        E = torch.where(earlier, E * M, E)
+    P = E / E.sum(1, keepdim=True)
+    return o_la + P @ v, S
+
+
+@pytest.mark.parametrize("linear_op,decay_on_softmax", [(0, True), (1, True), (0, False)])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_chunk_routed_backward_against_autograd(seed, linear_op, decay_on_softmax):
+    L, d, C = 24, 5, 4
+    q, k, v, alpha, beta, _, do, S0 = inputs(L=L, d=d, seed=20 + seed)
+    mask_c = (np.random.default_rng(30 + seed).random(L // C) < 0.4).astype(np.uint8)
+    mask_c[0] = 1
+    scale, la_scale = 0.6, 1.2
+    t = {n: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+         for n, a in dict(q=q, k=k, v=v, alpha=alpha, beta=beta, S0=S0).items()}
+    M = torch.ones(L, L, dtype=torch.float64, requires_grad=True)
+    mu = torch.ones(L // C, dtype=torch.float64, requires_grad=True)
+    O, S_end = torch_forward_chunk_routed(t["q"], t["k"], t["v"], t["alpha"], t["beta"], mask_c, C, t["S0"], scale,
+                                          la_scale, linear_op, decay_on_softmax, M=M, mu=mu)
+    (O * torch.tensor(do)).sum().backward()
+    r = nbw.hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_scale=scale, la_scale=la_scale,
+                                         S0=S0, linear_op=linear_op, decay_on_softmax=decay_on_softmax)
+    for name, key in (("q", "dQ"), ("k", "dK"), ("v", "dV"), ("alpha", "dalpha"), ("beta", "dbeta"), ("S0", "dS0")):
+        np.testing.assert_allclose(r[key], t[name].grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=key)
+    # Eq. 15-16: column sums of the mask gradient, per chunk; Eq. 17: derivative of the chunk's multiplier
+    np.testing.assert_allclose(r["dscore_nla"], M.grad.numpy().sum(0).reshape(L // C, C).sum(1), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(r["dscore_la"], mu.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert np.all(r["dscore_nla"][mask_c == 0] == 0) and np.all(r["dscore_la"][mask_c != 0] == 0)
+    # the forward differentiated here is the forward oracle's
+    ref = npo.hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=scale, la_scale=la_scale, S0=S0,
+                                       linear_op=linear_op, decay_on_softmax=decay_on_softmax)
+    np.testing.assert_allclose(O.detach().numpy(), ref["O"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(S_end.detach().numpy(), ref["S"], rtol=1e-10, atol=1e-12)
+
+
+def test_chunk_routed_backward_single_entries_against_finite_differences():
+    L, d, C = 16, 4, 4
+    q, k, v, alpha, beta, _, do, S0 = inputs(L=L, d=d, seed=41)
+    mask_c = np.array([1, 0, 1, 0], dtype=np.uint8)
+    r = nbw.hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, S0=S0)
+
+    def loss(**over):
+        a = dict(q=q, k=k, v=v, alpha=alpha, beta=beta)
+        a.update(over)
+        return float(np.sum(npo.hybrid_head_chunk_routed(a["q"], a["k"], a["v"], a["alpha"], a["beta"], mask_c, C,
+                                                         S0=S0)["O"] * do))
+
+    h = 1e-6
+    for name, key, pos in (("q", "dQ", (9, 2)), ("k", "dK", (2, 1)), ("k", "dK", (6, 0)), ("v", "dV", (10, 3)),
+                           ("alpha", "dalpha", (1,)), ("alpha", "dalpha", (9,)), ("beta", "dbeta", (5,)),
+                           ("beta", "dbeta", (8,))):
+        base = dict(q=q, k=k, v=v, alpha=alpha, beta=beta)[name]
+        up, dn = base.copy(), base.copy()
+        up[pos] += h
+        dn[pos] -= h
+        fd = (loss(**{name: up}) - loss(**{name: dn})) / (2 * h)
+        assert abs(fd - r[key][pos]) <= 1e-6 * max(1.0, abs(fd)), (name, pos, fd, r[key][pos])
