@@ -207,6 +207,17 @@ typedef struct nats_bwd_extra {
     float* g_nla;               /* out [B,H,L] f32: g_j = sum_i dM_ij of Eq. 15 for softmax tokens j, 0 for
                                    linear tokens; Eq. 16 (the gradient of a chunk's softmax score) is the sum
                                    of g over the chunk's tokens                                              */
+    float* g_la;                /* out [B,H,L] f32: the linear operation's counterpart (Eq. 17, "sum of dS . S"):
+                                   for a linear token, the sum over the state's entries of (gradient of the loss
+                                   with respect to the state after the token's write) x (what the token wrote),
+                                   i.e. the derivative with respect to a multiplier on the write of Eq. 14;
+                                   0 for softmax tokens.  With routing per chunk: not available (NULL)          */
+    float* dscore_nla;          /* out [B,H,L/C] f32: Eq. 16, gradient of a chunk's softmax score                */
+    float* dscore_la;           /* out [B,H,L/C] f32: Eq. 17, gradient of a chunk's linear score.  Routing per
+                                   token: the sums of g_nla and g_la over the chunk's tokens.  Routing per chunk:
+                                   the mask gradients between chunks (the inner part of a chunk is computed by
+                                   both operations whatever its type, no mask stands on it); a chunk gets no
+                                   gradient for the operation it is inactive for (Section 4.2)                   */
 } nats_bwd_extra;
 
 size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);

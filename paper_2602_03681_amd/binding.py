@@ -49,7 +49,8 @@ class FwdExtra(ctypes.Structure):
 
 
 class BwdExtra(ctypes.Structure):
-    _fields_ = [("initial_state", ctypes.c_void_p), ("d_initial_state", ctypes.c_void_p), ("g_nla", ctypes.c_void_p)]
+    _fields_ = [("initial_state", ctypes.c_void_p), ("d_initial_state", ctypes.c_void_p), ("g_nla", ctypes.c_void_p),
+                ("g_la", ctypes.c_void_p), ("dscore_nla", ctypes.c_void_p), ("dscore_la", ctypes.c_void_p)]
 
 
 class DecChunkState(ctypes.Structure):
@@ -290,9 +291,10 @@ def hybrid_attn_fwd_noalloc(Q, K, V, alpha, beta, mask, out, C: int = 64, *, sof
 
 def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
                     linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False, initial_state=None,
-                    want=(), workspace=None) -> Dict[str, torch.Tensor]:
-    """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla (routing per token) given dO.  Returns dQ, dK, dV
-    [B,H,L,d] f32, dalpha, dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla [B,H,L]."""
+                    want=(), workspace=None, routing: int = NATS_ROUTE_TOKEN) -> Dict[str, torch.Tensor]:
+    """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla given dO.  Returns dQ, dK, dV [B,H,L,d] f32, dalpha,
+    dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla, g_la [B,H,L] (routing per token),
+    dscore_nla, dscore_la [B,H,L/C] (Eq. 16, Eq. 17)."""
     lib = load_library()
     B, H, L, d = Q.shape
     dt = Q.dtype
@@ -300,13 +302,13 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
         _require(t, name, (B, H, L, d), dt)
     _require(alpha, "alpha", (B, H, L), torch.float32)
     _require(beta, "beta", (B, H, L), torch.float32)
-    _require(mask, "mask", (B, H, L), torch.uint8)
+    _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
     _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
-    unknown = set(want) - {"d_initial_state", "g_nla"}
+    unknown = set(want) - {"d_initial_state", "g_nla", "g_la", "dscore_nla", "dscore_la"}
     if unknown:
         raise ValueError(f"unknown outputs {sorted(unknown)}")
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, NATS_MATH_AUTO,
-                             NATS_ROUTE_TOKEN, linear_op, freeze_on_softmax)
+                             routing, linear_op, freeze_on_softmax)
     need = int(lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(params)))
     if need == 0:   # let the library say what is wrong with the parameters
         _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), *([None] * 12), None, None, 0, None))
@@ -317,9 +319,13 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
     res["dalpha"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
     res["dbeta"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
     if "d_initial_state" in want: res["d_initial_state"] = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
-    if "g_nla" in want: res["g_nla"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    for key in ("g_nla", "g_la"):
+        if key in want: res[key] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    for key in ("dscore_nla", "dscore_la"):
+        if key in want: res[key] = torch.empty((B, H, L // C), dtype=torch.float32, device=dev)
     g = lambda k: res[k].data_ptr() if k in res else None
-    extra = BwdExtra(initial_state.data_ptr() if initial_state is not None else None, g("d_initial_state"), g("g_nla"))
+    extra = BwdExtra(initial_state.data_ptr() if initial_state is not None else None, g("d_initial_state"), g("g_nla"),
+                     g("g_la"), g("dscore_nla"), g("dscore_la"))
     _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta), _ptr(mask),
                                     _ptr(dO), _ptr(res["dQ"]), _ptr(res["dK"]), _ptr(res["dV"]), _ptr(res["dalpha"]),
                                     _ptr(res["dbeta"]), ctypes.byref(extra), _ptr(workspace), workspace.numel(),

@@ -176,7 +176,8 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 // offsets): branch output and lse of the softmax branch, D_i, checkpoints of the state, the scratch rows of
 // the reverse sweep and the partial sums of its blocks.
 struct BwdPlan {
-    size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp, total;
+    size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp,
+        off_gnla, total;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -194,6 +195,7 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_skp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
     bp->off_svp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
     bp->off_sgp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * 4, 256);
+    bp->off_gnla = off;    off = align_up(off + n_tok * 4, 256);   // column sums of Eq. 15 when only their chunk sums are asked for
     bp->total = off;
 }
 
@@ -448,7 +450,7 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     memset(&ex, 0, sizeof(ex));
     if (extra) ex = *extra;
     const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
-                          ex.d_initial_state, ex.g_nla};
+                          ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la};
     for (const void* ptr : ptrs)
         if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
     const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
@@ -474,6 +476,7 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     float* dkp = reinterpret_cast<float*>(ws + bp.off_dkp);
     float* dap = reinterpret_cast<float*>(ws + bp.off_dap);
     float* dbp = reinterpret_cast<float*>(ws + bp.off_dbp);
+    if (ex.dscore_nla != nullptr && ex.g_nla == nullptr) ex.g_nla = reinterpret_cast<float*>(ws + bp.off_gnla);
     ProfChain prof_chain;   // the kernels below follow each other on one stream
     {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
         ProfScope ps("scan_compact", stream);
@@ -506,11 +509,18 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         st = launch_bwd_combine(pl, dqp, dkp, dap, dbp, dQ, dK, dalpha, dbeta, ex.g_nla, stream);
         if (st != NATS_OK) return st;
     }
-    // rows of the softmax tokens in dK, dV (their linear share is zero) and g_nla
-    ProfScope ps("softmax_bwd_dkv", stream);
-    return launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
-                                  reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
-                                  reinterpret_cast<float*>(ws + bp.off_sgp), stream);
+    {   // rows of the softmax tokens in dK, dV (their linear share is zero) and g_nla
+        ProfScope ps("softmax_bwd_dkv", stream);
+        st = launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
+                                    reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
+                                    reinterpret_cast<float*>(ws + bp.off_sgp), stream);
+        if (st != NATS_OK) return st;
+    }
+    if (ex.g_la != nullptr || ex.dscore_nla != nullptr || ex.dscore_la != nullptr) {   // Eq. 16, Eq. 17
+        ProfScope ps("score_gradients", stream);
+        st = launch_score_gradients(pl, beta, mask, dbeta, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, stream);
+    }
+    return st;
 }
 
 nats_status nats_hybrid_attn_fwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,

@@ -473,4 +473,33 @@ nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const fl
     return check_launch("bwd_combine");
 }
 
+// Score gradients with routing per token (Section 4.2).  Eq. 17 for one token: the sum over the state's entries
+// of (gradient w.r.t. the state after the token's write) x (what the token wrote) = beta_t (r_t . dS_t k_t), which is
+// beta_t times the gradient of beta_t that the reverse sweep has already reduced; zero for softmax tokens.  Eq. 16
+// and Eq. 17 per chunk of 64 tokens: the sums over the chunk.  One wavefront per (chunk, batch*head).
+__global__ __launch_bounds__(64) void score_gradients_kernel(const float* __restrict__ beta, const uint8_t* __restrict__ mask,
+                                                            const float* __restrict__ dbeta, const float* __restrict__ g_nla,
+                                                            float* __restrict__ g_la, float* __restrict__ dscore_nla,
+                                                            float* __restrict__ dscore_la, int L) {
+    const size_t t = (size_t)blockIdx.y * L + (size_t)blockIdx.x * 64 + threadIdx.x;
+    const float gl = mask[t] ? 0.f : beta[t] * dbeta[t];
+    if (g_la != nullptr) g_la[t] = gl;
+    const size_t c = (size_t)blockIdx.y * (L / 64) + blockIdx.x;
+    if (dscore_la != nullptr) {
+        const float s = lane_group_sum<64>(gl);
+        if (threadIdx.x == 0) dscore_la[c] = s;
+    }
+    if (dscore_nla != nullptr) {
+        const float s = lane_group_sum<64>(g_nla[t]);
+        if (threadIdx.x == 0) dscore_nla[c] = s;
+    }
+}
+
+nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,
+                                   const float* g_nla, float* g_la, float* dscore_nla, float* dscore_la, hipStream_t st) {
+    hipLaunchKernelGGL(score_gradients_kernel, dim3(pl.L / 64, pl.BH), dim3(64), 0, st, beta, mask, dbeta, g_nla, g_la,
+                       dscore_nla, dscore_la, pl.L);
+    return check_launch("score_gradients");
+}
+
 }  // namespace nats

@@ -256,6 +256,8 @@ nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const voi
                                      float* dbeta_part, float* dV, float* dS0, hipStream_t st);
 nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st);
+nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,
+                                   const float* g_nla, float* g_la, float* dscore_nla, float* dscore_la, hipStream_t st);
 nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,
                                const float* dbeta_part, float* dQ, float* dK, float* dalpha, float* dbeta,
                                float* g_nla, hipStream_t st);

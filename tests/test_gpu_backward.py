@@ -59,6 +59,24 @@ def test_backward_matches_the_oracle(dtype, B, H, L, d, p):
     assert np.all(host(r["g_nla"])[~soft] == 0)
 
 
+@pytest.mark.parametrize("dtype,B,H,L,d,p", [("f32", 1, 2, 320, 64, 0.15), ("bf16", 1, 2, 448, 128, 0.2)])
+@pytest.mark.parametrize("ask", ["all", "chunk sums only"])
+def test_score_gradients_per_token_and_per_chunk(dtype, B, H, L, d, p, ask):
+    """Eq. 16 and Eq. 17: the column sums of the softmax mask gradient, the linear operation's sum of dS . (written),
+    and their sums per chunk of 64 tokens (asked for alone, the per-token sums live in the workspace)."""
+    x = make_fwd_inputs(B, H, L, d, dtype, p, seed=700 + L)
+    dO = make_grad_output(B, H, L, d, dtype, seed=701)
+    want = ("g_nla", "g_la", "dscore_nla", "dscore_la") if ask == "all" else ("dscore_nla", "dscore_la")
+    r = run_bwd(x, dO, dtype, want=want)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO)
+    ref["dscore_nla"], ref["dscore_la"] = nbw.score_gradients(ref["g_nla"], ref["g_la"], 64)
+    for key in want:
+        e = rel_err(host(r[key]), ref[key])
+        assert e <= TOL_BWD, (key, e)
+    if ask == "all":
+        assert np.all(host(r["g_la"])[x["mask"] != 0] == 0)
+
+
 @pytest.mark.parametrize("linear_op,freeze", [(nb.NATS_LINEAR_GATED, False), (nb.NATS_LINEAR_GDN, True),
                                               (nb.NATS_LINEAR_GATED, True)])
 def test_backward_variants_and_scales(linear_op, freeze):
