@@ -199,7 +199,7 @@ nats_status nats_hybrid_attn_fwd_noalloc(const nats_fwd_params* p, const void* Q
                                          void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
- * Backward pass (Section 4.2), routing per token, plain-sum merge, fp32 results
+ * Backward pass (Section 4.2), plain-sum merge, fp32 results
  * ------------------------------------------------------------------------- */
 typedef struct nats_bwd_extra {
     const float* initial_state; /* in  [B,H,d,d] f32, the state the forward started from (NULL -> 0)         */
@@ -226,8 +226,10 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  * the adjoint of the recurrence of Eq. 19 / 14 / 20 (or of the gated operation) for the linear branch, and the
  * attention backward over the softmax columns of Eq. 12 with the mask gradients of Eq. 15.  k and v of a
  * softmax token get nothing from the linear branch and vice versa (Section 4.2).
- *   Q, K, V, alpha, beta, mask : as in the forward (p->routing must be NATS_ROUTE_TOKEN, p->combine_mode 0;
- *             p->math is not looked at).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.
+ *   Q, K, V, alpha, beta, mask : as in the forward (either routing; p->combine_mode must be 0, p->group 1;
+ *             p->math is not looked at).  With routing per chunk the function differentiated is the one the
+ *             forward computes there: both operations compute every chunk's inner part, the masks act between
+ *             chunks, a softmax chunk hands on (its decay) x (the state at its start).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.
  *             For bf16 tensors the softmax branch's dQ, dK, dV products run on the matrix cores: Q, K, V, dO
  *             enter exactly (they are bf16), the probabilities and dS enter as the sum of two fp16 terms,
  *             so the gradients keep fp32-level accuracy; for f32 tensors those products are fp32 too

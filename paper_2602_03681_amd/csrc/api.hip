@@ -177,7 +177,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 // the reverse sweep and the partial sums of its blocks.
 struct BwdPlan {
     size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp,
-        off_gnla, total;
+        off_gnla, off_vis, off_dslap, total;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -196,15 +196,16 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_svp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
     bp->off_sgp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * 4, 256);
     bp->off_gnla = off;    off = align_up(off + n_tok * 4, 256);   // column sums of Eq. 15 when only their chunk sums are asked for
+    bp->off_vis = off;     off = align_up(off + n_tok * 4, 256);   // routing per chunk: compacted rows visible to a query
+    bp->off_dslap = off;   off = align_up(off + ns * (n_tok / 64) * 4, 256);   // ... and the sweep's partials of Eq. 17
     bp->total = off;
 }
 
 static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, BwdPlan* bp) {
     nats_status st = validate_fwd_params(p, pl);
     if (st != NATS_OK) return st;
-    if (pl->routing != NATS_ROUTE_TOKEN || pl->combine_mode != 0) {
-        set_error("the backward pass covers routing per token with the plain-sum merge (routing %d, combine_mode %d given)",
-                  pl->routing, pl->combine_mode);
+    if (pl->combine_mode != 0) {
+        set_error("the backward pass covers the plain-sum merge (combine_mode %d given)", pl->combine_mode);
         return NATS_ERR_UNSUPPORTED;
     }
     if (pl->G != 1) { set_error("the backward pass has no head grouping (group %d given)", pl->G); return NATS_ERR_UNSUPPORTED; }
@@ -476,7 +477,13 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     float* dkp = reinterpret_cast<float*>(ws + bp.off_dkp);
     float* dap = reinterpret_cast<float*>(ws + bp.off_dap);
     float* dbp = reinterpret_cast<float*>(ws + bp.off_dbp);
+    const bool chunk = pl.routing == NATS_ROUTE_CHUNK;
+    if (chunk && ex.g_la != nullptr) {
+        set_error("g_la (the linear score gradient per token) exists with routing per token only; ask for dscore_la");
+        return NATS_ERR_UNSUPPORTED;
+    }
     if (ex.dscore_nla != nullptr && ex.g_nla == nullptr) ex.g_nla = reinterpret_cast<float*>(ws + bp.off_gnla);
+    float* dslap = (chunk && ex.dscore_la != nullptr) ? reinterpret_cast<float*>(ws + bp.off_dslap) : nullptr;
     ProfChain prof_chain;   // the kernels below follow each other on one stream
     {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
         ProfScope ps("scan_compact", stream);
@@ -488,9 +495,17 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;
     }
-    {   // dQ = the softmax branch's share (written); also D_i
+    const int32_t* vis = cnt;   // compacted rows visible to a query
+    if (chunk) {
+        ProfScope ps("visible_rows", stream);
+        int32_t* v = reinterpret_cast<int32_t*>(ws + bp.off_vis);
+        st = launch_visible_rows(pl, cnt, v, stream);
+        if (st != NATS_OK) return st;
+        vis = v;
+    }
+    {   // dQ = the softmax branch's share over the compacted rows (written); also D_i
         ProfScope ps("softmax_bwd_dq", stream);
-        st = launch_softmax_bwd_dq(pl, Q, Kc, Vc, dO, cnt, O_nla, lse, Dvec, dQ, stream);
+        st = launch_softmax_bwd_dq(pl, Q, Kc, Vc, dO, vis, O_nla, lse, Dvec, dQ, stream);
         if (st != NATS_OK) return st;
     }
     {   // the linear branch forwards once more, leaving a checkpoint of the state per chunk
@@ -501,7 +516,7 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     {
         ProfScope ps("gdn_recurrent_bwd", stream);
         st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
-                                      ex.d_initial_state, stream);
+                                      ex.d_initial_state, dslap, stream);
         if (st != NATS_OK) return st;
     }
     {   // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
@@ -509,16 +524,22 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         st = launch_bwd_combine(pl, dqp, dkp, dap, dbp, dQ, dK, dalpha, dbeta, ex.g_nla, stream);
         if (st != NATS_OK) return st;
     }
-    {   // rows of the softmax tokens in dK, dV (their linear share is zero) and g_nla
+    if (chunk) {   // every chunk's inner part of the softmax branch: added to dQ, dK, dV
+        ProfScope ps("softmax_bwd_own_chunk", stream);
+        st = launch_softmax_bwd_own_chunk(pl, Q, K, V, dO, lse, Dvec, dQ, dK, dV, stream);
+        if (st != NATS_OK) return st;
+    }
+    {   // rows of the softmax tokens in dK, dV (routing per token: their linear share is zero; per chunk: added) and g_nla
         ProfScope ps("softmax_bwd_dkv", stream);
-        st = launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, cnt, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
+        st = launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, vis, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
                                     reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
                                     reinterpret_cast<float*>(ws + bp.off_sgp), stream);
         if (st != NATS_OK) return st;
     }
     if (ex.g_la != nullptr || ex.dscore_nla != nullptr || ex.dscore_la != nullptr) {   // Eq. 16, Eq. 17
         ProfScope ps("score_gradients", stream);
-        st = launch_score_gradients(pl, beta, mask, dbeta, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, stream);
+        st = chunk ? launch_score_gradients_chunk(pl, ex.g_nla, dslap, ex.dscore_nla, ex.dscore_la, stream)
+                   : launch_score_gradients(pl, beta, mask, dbeta, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, stream);
     }
     return st;
 }

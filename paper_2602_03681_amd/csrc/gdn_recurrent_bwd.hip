@@ -51,14 +51,22 @@ __device__ __forceinline__ void halve_step(float* v, int lane) {
     }
 }
 
-template <typename T, int D>
+// CHUNK: routing per chunk (mask holds one byte per chunk of 64 tokens).  Inside a chunk every token is written
+// (both operations compute every chunk's inner part) from the carried state at the chunk's start, which is what
+// the checkpoint holds; a linear chunk hands its last state on, a softmax chunk hands on decay x (state at its
+// start).  In reverse: a linear chunk's sweep starts from the gradient of the state carried out of it; a softmax
+// chunk's sweep starts from zero (its provisional states end with the chunk), and when it reaches the chunk's start
+// the gradient of the carried state joins it, times the chunk's decay, whose own gradient <dS_next, S_start> goes
+// to the alphas of the chunk's tokens.  ds_la_part [d/16][BH][L/64] (optional): Eq. 17 for a linear chunk, this
+// block's rows' share of <dS_next, S_end - decay S_start>.
+template <typename T, int D, bool CHUNK>
 __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ ckpt, float* __restrict__ scratch, float* __restrict__ dq_part,
     float* __restrict__ dk_part, float* __restrict__ dalpha_part, float* __restrict__ dbeta_part,
-    float* __restrict__ dV, float* __restrict__ dS0, int L, int BH, float la_scale, int linear_op,
-    int freeze_on_softmax) {
+    float* __restrict__ dV, float* __restrict__ dS0, float* __restrict__ ds_la_part, int L, int BH, float la_scale,
+    int linear_op, int freeze_on_softmax) {
     constexpr int EPL = Vec16<T>::N;
     constexpr int LPR = rbw_lpr(D), RBW_THREADS = rbw_threads(D), NW = RBW_THREADS / 64;
     constexpr int RPW = 64 / LPR;   // rows of a wavefront: 2 or 4
@@ -74,6 +82,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
     __shared__ uint8_t s_lin[RB_TT];           // 1: linear token (the state is written)
     __shared__ float s_part[2][2][NW][D];      // [token parity][dq, dk][wavefront][column]
     __shared__ float s_sc[2][2][NW];           // [token parity][dalpha, dbeta][wavefront]
+    __shared__ float s_blk[NW];                // a sum over the block's rows, once per chunk (routing per chunk)
 
     const int bh = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
     const int r = tid / LPR, part = tid % LPR, lane = tid & 63, wave = tid >> 6;
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
             }
         }
         if (tid < RB_TT) {
-            const bool soft = mask[base + t0 + tid] != 0;
+            const bool soft = CHUNK ? false : mask[base + t0 + tid] != 0;   // CHUNK: every token of a chunk is written
             const bool dec = !(soft && freeze_on_softmax);
             s_dec[tid] = dec ? 1 : 0;
             s_lin[tid] = soft ? 0 : 1;
@@ -127,6 +136,21 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
         __syncthreads();
     };
     auto row_sum = [](float x) { return lane_group_sum<LPR>(x); };   // over a row's lanes
+    // sum over the block's rows of a value every lane of a row holds: rows of a wavefront by lane exchanges, the
+    // wavefronts in order through LDS (two barriers; called by every thread)
+    auto block_sum = [&](float x) -> float {
+        float y = part == 0 ? x : 0.f;
+        if (RPW == 4) y += lane_xor16(y, lane);
+        y += lane_xor32(y, lane);
+        __syncthreads();
+        if (lane == 0) s_blk[wave] = y;
+        __syncthreads();
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) tot += s_blk[w];
+        return tot;
+    };
+    const uint8_t* mask_c = mask + (size_t)bh * (L / RB_CH);   // CHUNK only
 
     float dS[DP];
 #pragma unroll
@@ -135,20 +159,28 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
     for (int chunk = n_chunks - 1; chunk >= 0; --chunk) {
         const int tc0 = chunk * RB_CH;
         // ---- forwards through the chunk from its checkpoint: park Sd of every token ----------------
+        const bool soft_chunk = CHUNK && mask_c[chunk] != 0;   // uniform
+        float dS_next[DP];          // CHUNK, softmax chunk: gradient of the state carried out of the chunk
+        float carry_dd = 0.f;       // ... and this block's share of <dS_next, S_start> x decay (to the alphas)
+        float carry_scale = 1.f;    // decay of the chunk (1 in the variant without decay on softmax chunks)
         {
-            float S[DP];
+            float S[DP], S_start[DP];
+            float decay = 1.f;
             const float* src = ckpt + (((size_t)bh * n_chunks + chunk) * D + row) * D + part * DP;
 #pragma unroll
             for (int c = 0; c < DP; c += 4) {
                 const float4 x = *reinterpret_cast<const float4*>(src + c);
                 S[c] = x.x; S[c + 1] = x.y; S[c + 2] = x.z; S[c + 3] = x.w;
             }
+#pragma unroll
+            for (int c = 0; c < DP; ++c) S_start[c] = S[c];
 #pragma unroll 1
             for (int tt = 0; tt < RB_CH; tt += RB_TT) {
                 stage(tc0 + tt, false);
 #pragma unroll 1
                 for (int i = 0; i < RB_TT; ++i) {
                     const float a = s_a[i], b = s_b[i];
+                    decay *= a;
                     const float* kr = &s_kq[i][part * KQ];
                     float* dst = my_scr + (size_t)(tt + i) * (D * RBW_ROWS) + tid * 4;
                     float pred = 0.f;
@@ -169,6 +201,23 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                         }
                     }
                 }
+            }
+            if (CHUNK) {
+                if (soft_chunk) {
+                    float dd = 0.f;
+#pragma unroll
+                    for (int c = 0; c < DP; ++c) { dS_next[c] = dS[c]; dd += dS[c] * S_start[c]; dS[c] = 0.f; }
+                    carry_scale = freeze_on_softmax ? 1.f : decay;
+                    carry_dd = freeze_on_softmax ? 0.f : block_sum(row_sum(dd)) * decay;
+                } else if (ds_la_part != nullptr) {   // Eq. 17: <dS_next, what the chunk added to the carried state>
+                    float x = 0.f;
+#pragma unroll
+                    for (int c = 0; c < DP; ++c) x += dS[c] * (S[c] - decay * S_start[c]);
+                    x = block_sum(row_sum(x));
+                    if (tid == 0) ds_la_part[((size_t)slice * BH + bh) * n_chunks + chunk] = x;
+                }
+                if (soft_chunk && ds_la_part != nullptr && tid == 0)
+                    ds_la_part[((size_t)slice * BH + bh) * n_chunks + chunk] = 0.f;
             }
         }
         // ---- backwards through the chunk ------------------------------------------------------------
@@ -288,10 +337,15 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
                     float sa = 0.f, sb = 0.f;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) { sa += s_sc[buf][0][w]; sb += s_sc[buf][1][w]; }
-                    da_p[base + t] = sa;
+                    // (softmax chunk: the decay handed on with the carried state is a product of the chunk's alphas)
+                    da_p[base + t] = (CHUNK && soft_chunk) ? sa + carry_dd / fmaxf(a, 1e-30f) : sa;
                     db_p[base + t] = sb;
                 }
             }
+        }
+        if (CHUNK && soft_chunk) {   // the gradient of the state carried over the chunk joins at the chunk's start
+#pragma unroll
+            for (int c = 0; c < DP; ++c) dS[c] += carry_scale * dS_next[c];
         }
     }
     if (dS0 != nullptr) {
@@ -304,7 +358,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_recurrent_bwd_kernel(
 // The forward recurrence once more, only to leave the checkpoints the reverse sweep starts from: the row of the
 // state before every chunk of 64 tokens, ckpt[bh][chunk][row][d_k].  Same thread layout as the kernel above
 // (16 rows per block, 16 lanes per row).
-template <typename T, int D>
+template <typename T, int D, bool CHUNK>
 __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ alpha, const float* __restrict__ beta,
     const uint8_t* __restrict__ mask, const float* __restrict__ S0, float* __restrict__ ckpt, int L, int linear_op,
@@ -333,6 +387,9 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
 #pragma unroll
         for (int c = 0; c < DP; ++c) S[c] = 0.f;
     }
+    // routing per chunk: the carried state; a softmax chunk hands on decay x (its start state), see the sweep kernel
+    float S_start[DP], decay = 1.f;
+    const uint8_t* mask_c = mask + (size_t)bh * (L / RB_CH);
     for (int t0 = 0; t0 < L; t0 += TT) {
         __syncthreads();
         for (int e = tid * EPL; e < TT * D; e += RBW_THREADS * EPL) {
@@ -350,7 +407,7 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
             for (int j = 0; j < EPL; ++j) s_v[i][c + j] = tmp[j];
         }
         if (tid < TT) {
-            const bool soft = mask[base + t0 + tid] != 0;
+            const bool soft = CHUNK ? false : mask[base + t0 + tid] != 0;
             s_lin[tid] = soft ? 0 : 1;
             s_a[tid] = (soft && freeze_on_softmax) ? 1.f : alpha[base + t0 + tid];
             s_b[tid] = soft ? 0.f : beta[base + t0 + tid];
@@ -362,8 +419,14 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
                 float* dst = ckpt + (((size_t)bh * n_chunks + (t0 + i) / RB_CH) * D + row) * D + part * DP;
 #pragma unroll
                 for (int c = 0; c < DP; c += 4) *reinterpret_cast<float4*>(dst + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
+                if (CHUNK) {
+                    decay = 1.f;
+#pragma unroll
+                    for (int c = 0; c < DP; ++c) S_start[c] = S[c];
+                }
             }
             const float a = s_a[i];
+            decay *= a;
             const float* kr = &s_k[i][part * DPP];
             float kk[DP];
             float pred = 0.f;
@@ -379,6 +442,11 @@ __global__ __launch_bounds__(rbw_threads(D)) void gdn_checkpoint_kernel(
                 const float delta = s_b[i] * (s_v[i][r] - (linear_op == 0 ? pred : 0.f));
 #pragma unroll
                 for (int c = 0; c < DP; ++c) S[c] += delta * kk[c];
+            }
+            if (CHUNK && ((t0 + i) & (RB_CH - 1)) == RB_CH - 1 && mask_c[(t0 + i) / RB_CH]) {   // end of a softmax chunk
+                const float f = freeze_on_softmax ? 1.f : decay;
+#pragma unroll
+                for (int c = 0; c < DP; ++c) S[c] = f * S_start[c];
             }
         }
     }
@@ -419,16 +487,17 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(
 template <typename T>
 static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO, const float* alpha,
                       const float* beta, const uint8_t* mask, const float* ckpt, float* scratch, float* dq_part,
-                      float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
+                      float* dk_part, float* dalpha_part, float* dbeta_part, float* dV, float* dS0, float* ds_la_part,
+                      hipStream_t st) {
     dim3 grid(pl.d / RBW_ROWS, pl.BH);
-    if (pl.d == 64)
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 64>), grid, dim3(rbw_threads(64)), 0, st, (const T*)Q, (const T*)K,
-                           (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
-                           dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
-    else
-        hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, 128>), grid, dim3(rbw_threads(128)), 0, st, (const T*)Q, (const T*)K,
-                           (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part,
-                           dbeta_part, dV, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax);
+#define NATS_RB_LAUNCH(DD, CH)                                                                                                   \
+    hipLaunchKernelGGL((gdn_recurrent_bwd_kernel<T, DD, CH>), grid, dim3(rbw_threads(DD)), 0, st, (const T*)Q, (const T*)K,      \
+                       (const T*)V, (const T*)dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,  \
+                       dV, dS0, ds_la_part, pl.L, pl.BH, pl.la_scale, pl.linear_op, pl.freeze_on_softmax)
+    const bool chunk = pl.routing == NATS_ROUTE_CHUNK;
+    if (pl.d == 64) { if (chunk) NATS_RB_LAUNCH(64, true); else NATS_RB_LAUNCH(64, false); }
+    else { if (chunk) NATS_RB_LAUNCH(128, true); else NATS_RB_LAUNCH(128, false); }
+#undef NATS_RB_LAUNCH
 }
 
 // scratch: BH * d * d * 64 floats;  dq_part, dk_part: (d / 16) * BH * L * d floats;
@@ -436,13 +505,13 @@ static void launch_rb(const FwdPlan& pl, const void* Q, const void* K, const voi
 nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                      const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
                                      float* scratch, float* dq_part, float* dk_part, float* dalpha_part,
-                                     float* dbeta_part, float* dV, float* dS0, hipStream_t st) {
+                                     float* dbeta_part, float* dV, float* dS0, float* ds_la_part, hipStream_t st) {
     if (pl.dtype == NATS_BF16)
         launch_rb<bf16_t>(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,
-                          dV, dS0, st);
+                          dV, dS0, ds_la_part, st);
     else
         launch_rb<float>(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dq_part, dk_part, dalpha_part, dbeta_part,
-                         dV, dS0, st);
+                         dV, dS0, ds_la_part, st);
     return check_launch("gdn_recurrent_bwd");
 }
 
@@ -451,8 +520,14 @@ nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void*
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st) {
     dim3 grid(pl.d / RBW_ROWS, pl.BH);
 #define NATS_CK_LAUNCH(TT, DD)                                                                                        \
-    hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD>), grid, dim3(rbw_threads(DD)), 0, st, (const TT*)K, (const TT*)V, alpha, \
-                       beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax)
+    do {                                                                                                              \
+        if (pl.routing == NATS_ROUTE_CHUNK)                                                                           \
+            hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD, true>), grid, dim3(rbw_threads(DD)), 0, st, (const TT*)K, \
+                               (const TT*)V, alpha, beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax);   \
+        else                                                                                                          \
+            hipLaunchKernelGGL((gdn_checkpoint_kernel<TT, DD, false>), grid, dim3(rbw_threads(DD)), 0, st, (const TT*)K, \
+                               (const TT*)V, alpha, beta, mask, S0, ckpt, pl.L, pl.linear_op, pl.freeze_on_softmax);   \
+    } while (0)
     if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_CK_LAUNCH(bf16_t, 64); else NATS_CK_LAUNCH(bf16_t, 128); }
     else { if (pl.d == 64) NATS_CK_LAUNCH(float, 64); else NATS_CK_LAUNCH(float, 128); }
 #undef NATS_CK_LAUNCH
@@ -500,6 +575,33 @@ nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const u
     hipLaunchKernelGGL(score_gradients_kernel, dim3(pl.L / 64, pl.BH), dim3(64), 0, st, beta, mask, dbeta, g_nla, g_la,
                        dscore_nla, dscore_la, pl.L);
     return check_launch("score_gradients");
+}
+
+// Score gradients with routing per chunk: Eq. 16 = the column sums of the mask gradient over the chunk's tokens
+// (only columns of earlier softmax chunks stand behind the mask, and only they are in g_nla); Eq. 17 = the sum of
+// the reverse sweep's d / 16 partials of <dS_next, what the chunk added> (zero for softmax chunks).
+__global__ __launch_bounds__(64) void score_gradients_chunk_kernel(const float* __restrict__ g_nla,
+                                                                  const float* __restrict__ ds_la_part,
+                                                                  float* __restrict__ dscore_nla,
+                                                                  float* __restrict__ dscore_la, int L, int n_part,
+                                                                  size_t n_chunks_all) {
+    const size_t c = (size_t)blockIdx.y * (L / 64) + blockIdx.x;
+    if (dscore_nla != nullptr) {
+        const float s = lane_group_sum<64>(g_nla[(size_t)blockIdx.y * L + (size_t)blockIdx.x * 64 + threadIdx.x]);
+        if (threadIdx.x == 0) dscore_nla[c] = s;
+    }
+    if (dscore_la != nullptr && threadIdx.x == 0) {
+        float s = 0.f;
+        for (int p = 0; p < n_part; ++p) s += ds_la_part[(size_t)p * n_chunks_all + c];
+        dscore_la[c] = s;
+    }
+}
+
+nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
+                                         float* dscore_la, hipStream_t st) {
+    hipLaunchKernelGGL(score_gradients_chunk_kernel, dim3(pl.L / 64, pl.BH), dim3(64), 0, st, g_nla, ds_la_part, dscore_nla,
+                       dscore_la, pl.L, pl.d / RBW_ROWS, (size_t)pl.BH * (pl.L / 64));
+    return check_launch("score_gradients (routing per chunk)");
 }
 
 }  // namespace nats

@@ -253,9 +253,15 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
 nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                      const float* alpha, const float* beta, const uint8_t* mask, const float* ckpt,
                                      float* scratch, float* dq_part, float* dk_part, float* dalpha_part,
-                                     float* dbeta_part, float* dV, float* dS0, hipStream_t st);
+                                     float* dbeta_part, float* dV, float* dS0, float* ds_la_part, hipStream_t st);
 nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st);
+nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st);
+nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
+                                         const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
+                                         hipStream_t st);
+nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
+                                         float* dscore_la, hipStream_t st);
 nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,
                                    const float* g_nla, float* g_la, float* dscore_nla, float* dscore_la, hipStream_t st);
 nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,

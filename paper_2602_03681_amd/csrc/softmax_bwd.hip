@@ -200,7 +200,7 @@ template <int D>
 __global__ __launch_bounds__(256) void softmax_bwd_dkv_combine_kernel(
     const float* __restrict__ dk_part, const float* __restrict__ dv_part, const float* __restrict__ g_part,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_s, float* __restrict__ dK, float* __restrict__ dV,
-    float* __restrict__ g_nla, int L, int n_seg, float scale) {
+    float* __restrict__ g_nla, int L, int n_seg, float scale, int accumulate) {
     constexpr int TPK = D / 4;                 // threads per key
     const int bh = blockIdx.y, c = blockIdx.x * (256 / TPK) + threadIdx.x / TPK, col = (threadIdx.x % TPK) * 4;
     if (c >= n_s[bh]) return;
@@ -216,8 +216,14 @@ __global__ __launch_bounds__(256) void softmax_bwd_dkv_combine_kernel(
         g += g_part[row];
     }
     const size_t dst = (tokb + idx[tokb + c]) * D + col;
-    *reinterpret_cast<float4*>(dK + dst) = make_float4(scale * k.x, scale * k.y, scale * k.z, scale * k.w);
-    *reinterpret_cast<float4*>(dV + dst) = v;
+    if (accumulate) {   // routing per chunk: the token's rows already hold its shares from inside its chunk
+        const float4 k0 = *reinterpret_cast<const float4*>(dK + dst), v0 = *reinterpret_cast<const float4*>(dV + dst);
+        *reinterpret_cast<float4*>(dK + dst) = make_float4(k0.x + scale * k.x, k0.y + scale * k.y, k0.z + scale * k.z, k0.w + scale * k.w);
+        *reinterpret_cast<float4*>(dV + dst) = make_float4(v0.x + v.x, v0.y + v.y, v0.z + v.z, v0.w + v.w);
+    } else {
+        *reinterpret_cast<float4*>(dK + dst) = make_float4(scale * k.x, scale * k.y, scale * k.z, scale * k.w);
+        *reinterpret_cast<float4*>(dV + dst) = v;
+    }
     if (col == 0 && g_nla != nullptr) g_nla[tokb + idx[tokb + c]] = g;
 }
 
@@ -597,13 +603,156 @@ nats_status launch_softmax_bwd_dkv(const FwdPlan& pl, const void* Q, const void*
     if (pl.d == 64) {
         dim3 grid((pl.L + 15) / 16, pl.BH);   // 256 / (64 / 4) keys per block
         hipLaunchKernelGGL((softmax_bwd_dkv_combine_kernel<64>), grid, dim3(256), 0, st, dk_part, dv_part, g_part, idx, n_s,
-                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale);
+                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale, pl.routing == NATS_ROUTE_CHUNK);
     } else {
         dim3 grid((pl.L + 7) / 8, pl.BH);     // 256 / (128 / 4) keys per block
         hipLaunchKernelGGL((softmax_bwd_dkv_combine_kernel<128>), grid, dim3(256), 0, st, dk_part, dv_part, g_part, idx, n_s,
-                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale);
+                           dK, dV, g_nla, pl.L, BWD_DKV_SEGMENTS, pl.softmax_scale, pl.routing == NATS_ROUTE_CHUNK);
     }
     return check_launch("softmax_bwd_dkv_combine");
+}
+
+// ---- routing per chunk -------------------------------------------------------------------------------------
+// Compacted rows a query sees: with routing per token the first cnt[t]; with routing per chunk those of earlier
+// chunks, cnt at the last token before the query's chunk.  Written out once so that the kernels above, which take
+// "rows visible to query t" as an array, serve both routings unchanged.
+__global__ __launch_bounds__(256) void visible_rows_kernel(const int32_t* __restrict__ cnt, int32_t* __restrict__ vis, int L,
+                                                          size_t n_tok) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_tok) return;
+    const size_t cs = t - (t % L) % 64;          // first token of the query's chunk
+    vis[t] = (cs % L) > 0 ? cnt[cs - 1] : 0;
+}
+
+// The inner part of every chunk (routing per chunk): query i of a chunk also attends to the chunk's own tokens
+// j <= i, whatever the chunk's type; no mask stands on these columns, so they add to dQ, dK, dV but not to the score
+// gradient.  One block per (chunk, batch*head), the 64 x 64 causal block in fp32:
+//   p_ij = exp(scale q_i.k_j - lse_i),  ds_ij = p_ij (do_i.v_j - D_i)        (lse_i, D_i: of the whole row)
+//   dQ_i += scale sum_j ds_ij k_j;   dK_j += scale sum_i ds_ij q_i;   dV_j += sum_i p_ij do_i
+// Rows of Q, K, V, dO pass through LDS 64 columns at a time.  Thread (i = tid / 4, quarter = tid % 4) owns 16
+// entries of a 64 x 64 result.  Accumulates into dQ, dK, dV (no other kernel runs beside it).
+constexpr int OC_TS = 65;
+constexpr int OC_LDS_BYTES = 4 * 64 * OC_TS * 4;
+template <typename T, int D>
+__global__ __launch_bounds__(256) void softmax_bwd_own_chunk_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
+    const float* __restrict__ lse, const float* __restrict__ Dvec, float* __restrict__ dQ, float* __restrict__ dK,
+    float* __restrict__ dV, int L, float scale) {
+    constexpr int TS = OC_TS;   // row stride (floats) of the 64 x 64 tiles
+    extern __shared__ __align__(16) unsigned char oc_smem[];
+    float* s_x = reinterpret_cast<float*>(oc_smem);
+    float* s_y = s_x + 64 * TS;
+    float* s_p = s_y + 64 * TS;
+    float* s_ds = s_p + 64 * TS;
+    const int bh = blockIdx.y, c0 = blockIdx.x * 64, tid = threadIdx.x;
+    const size_t rowb = (size_t)bh * L + c0;
+    const int i = tid >> 2, qt = tid & 3;
+    // loads columns [dc, dc + 64) of 64 rows of a tensor into a tile
+    auto load_tile = [&](const T* src, float* dst, int dc) {
+        for (int e = tid; e < 64 * 64; e += 256) {
+            const int r = e >> 6, c = e & 63;
+            dst[r * TS + c] = to_float(src[(rowb + r) * D + dc + c]);
+        }
+    };
+    float acc_s[16], acc_dp[16];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) { acc_s[m] = 0.f; acc_dp[m] = 0.f; }
+    for (int dc = 0; dc < D; dc += 64) {
+        __syncthreads();
+        load_tile(Q, s_x, dc);
+        load_tile(K, s_y, dc);
+        __syncthreads();
+        for (int c = 0; c < 64; ++c) {
+            const float x = s_x[i * TS + c];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) acc_s[m] += x * s_y[(qt + 4 * m) * TS + c];
+        }
+        __syncthreads();
+        load_tile(dO, s_x, dc);
+        load_tile(V, s_y, dc);
+        __syncthreads();
+        for (int c = 0; c < 64; ++c) {
+            const float x = s_x[i * TS + c];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) acc_dp[m] += x * s_y[(qt + 4 * m) * TS + c];
+        }
+    }
+    {
+        const float l = lse[rowb + i], Di = Dvec[rowb + i];
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int j = qt + 4 * m;
+            const float p = j <= i ? expf(scale * acc_s[m] - l) : 0.f;
+            s_p[i * TS + j] = p;
+            s_ds[i * TS + j] = p * (acc_dp[m] - Di);
+        }
+    }
+    for (int dc = 0; dc < D; dc += 64) {
+        float out[16];
+        // dQ_i[c] += scale sum_j ds_ij K_j[c]
+        __syncthreads();
+        load_tile(K, s_y, dc);
+        load_tile(Q, s_x, dc);
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) out[m] = 0.f;
+        for (int j = 0; j < 64; ++j) {
+            const float w = s_ds[i * TS + j];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) out[m] += w * s_y[j * TS + qt + 4 * m];
+        }
+#pragma unroll
+        for (int m = 0; m < 16; ++m) dQ[(rowb + i) * D + dc + qt + 4 * m] += scale * out[m];
+        // dK_j[c] += scale sum_i ds_ij Q_i[c]      (this thread's row index now counts keys)
+#pragma unroll
+        for (int m = 0; m < 16; ++m) out[m] = 0.f;
+        for (int q = 0; q < 64; ++q) {
+            const float w = s_ds[q * TS + i];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) out[m] += w * s_x[q * TS + qt + 4 * m];
+        }
+#pragma unroll
+        for (int m = 0; m < 16; ++m) dK[(rowb + i) * D + dc + qt + 4 * m] += scale * out[m];
+        // dV_j[c] += sum_i p_ij dO_i[c]
+        __syncthreads();
+        load_tile(dO, s_x, dc);
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) out[m] = 0.f;
+        for (int q = 0; q < 64; ++q) {
+            const float w = s_p[q * TS + i];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) out[m] += w * s_x[q * TS + qt + 4 * m];
+        }
+#pragma unroll
+        for (int m = 0; m < 16; ++m) dV[(rowb + i) * D + dc + qt + 4 * m] += out[m];
+    }
+}
+
+nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st) {
+    const size_t n_tok = (size_t)pl.BH * pl.L;
+    hipLaunchKernelGGL(visible_rows_kernel, dim3((unsigned)((n_tok + 255) / 256)), dim3(256), 0, st, cnt, vis, pl.L, n_tok);
+    return check_launch("visible_rows");
+}
+
+nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
+                                         const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
+                                         hipStream_t st) {
+    dim3 grid(pl.L / 64, pl.BH);
+    // more than 64 KB of LDS: the limit is raised per kernel (cheap, so done at every launch)
+#define NATS_OC_LAUNCH(TT, DD)                                                                                       \
+    do {                                                                                                             \
+        auto kern = softmax_bwd_own_chunk_kernel<TT, DD>;                                                            \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                OC_LDS_BYTES) != hipSuccess)                                                         \
+            return check_launch("softmax_bwd_own_chunk (LDS attribute)");                                            \
+        hipLaunchKernelGGL(kern, grid, dim3(256), OC_LDS_BYTES, st, (const TT*)Q, (const TT*)K, (const TT*)V,        \
+                           (const TT*)dO, lse, Dvec, dQ, dK, dV, pl.L, pl.softmax_scale);                           \
+    } while (0)
+    if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_OC_LAUNCH(bf16_t, 64); else NATS_OC_LAUNCH(bf16_t, 128); }
+    else { if (pl.d == 64) NATS_OC_LAUNCH(float, 64); else NATS_OC_LAUNCH(float, 128); }
+#undef NATS_OC_LAUNCH
+    return check_launch("softmax_bwd_own_chunk");
 }
 
 }  // namespace nats

@@ -167,14 +167,18 @@ def test_backward_validation(lib):
     p = good_params()
     need = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(p))
     assert need > nb.fwd_workspace_bytes(p) // 2
-    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK))) == 0
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK))) == need
     assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(combine_mode=1))) == 0
 
     def call(prm, ptrs=None, ws=FAKE, ws_bytes=1 << 40):
         ptrs = [FAKE + 16 * i for i in range(12)] if ptrs is None else ptrs
         return lib.nats_hybrid_attn_bwd(ctypes.byref(prm), *ptrs, None, ws, ws_bytes, None)
 
-    assert call(good_params(routing=nb.NATS_ROUTE_CHUNK)) == E_UNSUP
+    # the per-token linear score gradient does not exist with routing per chunk (rejected before any launch)
+    ex = nb.BwdExtra(None, None, None, FAKE, None, None)
+    ptrs0 = [FAKE + 16 * i for i in range(12)]
+    assert lib.nats_hybrid_attn_bwd(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK)), *ptrs0, ctypes.byref(ex), FAKE,
+                                    1 << 40, None) == E_UNSUP
     assert call(good_params(combine_mode=1)) == E_UNSUP
     assert call(good_params(L=100)) == E_SHAPE
     ptrs = [FAKE + 16 * i for i in range(12)]

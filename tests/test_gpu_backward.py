@@ -7,7 +7,7 @@ import torch
 
 import paper_2602_03681_amd as nats
 from paper_2602_03681_amd import binding as nb
-from nats_inputs import make_fwd_inputs, make_grad_output
+from nats_inputs import make_chunk_mask, make_fwd_inputs, make_grad_output
 from oracle import nats_oracle_bwd as nbw
 
 from gpu_util import host, rel_err, to_dev
@@ -115,3 +115,49 @@ def test_backward_is_deterministic_and_reuses_a_poisoned_workspace():
     r2 = run_bwd(x, dO, "bf16")
     for k in ("dQ", "dK", "dV", "dalpha", "dbeta", "g_nla", "d_initial_state"):
         assert torch.equal(r1[k], r2[k]), k
+
+
+# ---- routing per chunk (Section 4.1 as stated): both operations compute every chunk's inner part, the masks act
+#      between chunks; score gradients per chunk (Eq. 16, Eq. 17) ---------------------------------------------------
+CHUNK_KEYS = (("d_initial_state", "dS0"), ("dscore_nla", "dscore_nla"), ("dscore_la", "dscore_la"))
+
+
+@pytest.mark.parametrize("dtype,B,H,L,d,p", [("f32", 1, 2, 256, 64, 0.4), ("f32", 1, 1, 192, 128, 0.3),
+                                             ("bf16", 2, 2, 512, 64, 0.3), ("bf16", 1, 2, 448, 128, 0.25),
+                                             ("bf16", 1, 1, 1024, 128, 0.5)])
+def test_backward_with_routing_per_chunk(dtype, B, H, L, d, p):
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.1, seed=800 + L + d)
+    x["mask"] = make_chunk_mask(B, H, L // 64, p, 801 + L, "bernoulli")
+    dO = make_grad_output(B, H, L, d, dtype, seed=802 + L)
+    S0 = (0.05 * np.random.default_rng(L + 1).standard_normal((B, H, d, d))).astype(np.float32)
+    r = run_bwd(x, dO, dtype, S0=S0, routing=nb.NATS_ROUTE_CHUNK, want=("d_initial_state", "dscore_nla", "dscore_la"))
+    ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO, S0=S0)
+    errs = check(r, ref, extra=CHUNK_KEYS)
+    print(dtype, L, d, errs)
+    # Section 4.2: no score gradient for the operation a chunk is inactive for
+    soft = x["mask"] != 0
+    assert np.all(host(r["dscore_la"])[soft] == 0) and np.all(host(r["dscore_nla"])[~soft] == 0)
+
+
+@pytest.mark.parametrize("linear_op,freeze", [(nb.NATS_LINEAR_GATED, False), (nb.NATS_LINEAR_GDN, True)])
+def test_backward_with_routing_per_chunk_variants(linear_op, freeze):
+    B, H, L, d = 1, 2, 256, 64
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=810 + linear_op)
+    x["mask"] = make_chunk_mask(B, H, L // 64, 0.5, 811, "bernoulli")
+    dO = make_grad_output(B, H, L, d, "f32", seed=812)
+    r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, softmax_scale=0.3, la_scale=1.7, linear_op=linear_op,
+                freeze_on_softmax=freeze, want=("d_initial_state", "dscore_nla", "dscore_la"))
+    ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO, softmax_scale=0.3,
+                                      la_scale=1.7, linear_op=linear_op, decay_on_softmax=not freeze)
+    check(r, ref, extra=CHUNK_KEYS)
+
+
+@pytest.mark.parametrize("kind", ["all_softmax", "all_linear"])
+def test_backward_with_routing_per_chunk_degenerate_masks(kind):
+    B, H, L, d = 1, 2, 192, 64
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=820)
+    x["mask"] = np.full((B, H, L // 64), 1 if kind == "all_softmax" else 0, dtype=np.uint8)
+    dO = make_grad_output(B, H, L, d, "f32", seed=821)
+    r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, want=("dscore_nla", "dscore_la"))
+    ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO)
+    check(r, ref, extra=CHUNK_KEYS[1:])
