@@ -232,6 +232,15 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
         // ---- K S0^T -> R, and S0 Q^T, two token tiles (one contraction step of the next product) at a time ----
         f32x4 accO[NVT][4];
         half8 rfrag[2][NVT];      // R[token slots][v = l16]: B operand of T'' R
+        // Without outputs there are registers to spare: the K fragments of the next token tile are read while the
+        // current tile's products run (the write of Kd^T below keeps the compiler from moving those reads up by
+        // itself: it cannot tell the two LDS regions apart).
+        half8 kf_next[KS_D], kt_next;
+        if (!HAS_OUT) {
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks) kf_next[ks] = lds_read8(Kt + l16 * SS + 32 * ks + 8 * lq);
+            kt_next = lds_read8(Kt + l16 * SS + 32 * tr_ks + 8 * lq);
+        }
 #pragma unroll
         for (int kp = 0; kp < 2; ++kp) {
             f32x4 accR[2][NVT];
@@ -239,8 +248,22 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
             for (int t2 = 0; t2 < 2; ++t2) {
                 const int tt = 2 * kp + t2;
                 half8 kf[KS_D], qf[KS_D];
+                half8 kt;
+                if (!HAS_OUT) {
 #pragma unroll
-                for (int ks = 0; ks < KS_D; ++ks) kf[ks] = lds_read8(Kt + (16 * tt + l16) * SS + 32 * ks + 8 * lq);
+                    for (int ks = 0; ks < KS_D; ++ks) kf[ks] = kf_next[ks];
+                    kt = kt_next;
+                    if (tt < 3) {
+#pragma unroll
+                        for (int ks = 0; ks < KS_D; ++ks)
+                            kf_next[ks] = lds_read8(Kt + (16 * (tt + 1) + l16) * SS + 32 * ks + 8 * lq);
+                        kt_next = lds_read8(Kt + (16 * (tt + 1) + l16) * SS + 32 * tr_ks + 8 * lq);
+                    }
+                } else {
+#pragma unroll
+                    for (int ks = 0; ks < KS_D; ++ks) kf[ks] = lds_read8(Kt + (16 * tt + l16) * SS + 32 * ks + 8 * lq);
+                    kt = lds_read8(Kt + (16 * tt + l16) * SS + 32 * tr_ks + 8 * lq);
+                }
                 if (HAS_OUT) {
 #pragma unroll
                     for (int ks = 0; ks < KS_D; ++ks) qf[ks] = lds_read8(Qt + (16 * tt + l16) * SS + 32 * ks + 8 * lq);
@@ -258,7 +281,6 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
                         if (HAS_OUT) accO[vt][tt] = mfma16(sfrag[vt][ks], qf[ks], accO[vt][tt]);   // rows v, col tok
                     }
                 {   // this wavefront's share of Kd^T for token tile tt
-                    const half8 kt = lds_read8(Kt + (16 * tt + l16) * SS + 32 * tr_ks + 8 * lq);
                     const float4 k4 = *reinterpret_cast<const float4*>(Gt + Lds::G_KD + 16 * tt + 4 * lq);
                     const float kk[4] = {k4.x, k4.y, k4.z, k4.w};
 #pragma unroll
