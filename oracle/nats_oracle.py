@@ -165,6 +165,23 @@ def eq22_weights(Q, W_out, act=0):
     return w[..., 0], w[..., 1]
 
 
+def weights_from_x(X, W_x, act=0):
+    """Section 5, ablation (v): the weights of Eq. 21 computed from the layer's input features instead of the
+    queries.  X [B,L,d_model]; W_x [H,2,d_model] (row 0: softmax attention, row 1: the linear operation).
+    Returns (w_nla, w_la) [B,H,L], with the activations of eq22_weights."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W_x, dtype=np.float64)
+    logits = np.einsum("bld,hkd->bhlk", X, W)
+    if act == 1:
+        w = 1.0 / (1.0 + np.exp(-logits))
+    elif act == 2:
+        w = logits
+    else:
+        e = np.exp(logits - logits.max(axis=-1, keepdims=True))
+        w = e / e.sum(axis=-1, keepdims=True)
+    return w[..., 0], w[..., 1]
+
+
 # --------------------------------------------------------------------------- #
 # whole operator for one (batch, head), and over [B,H,...]
 # --------------------------------------------------------------------------- #
@@ -297,7 +314,7 @@ def gdn_chunkwise(q, k, v, alpha, beta, mask, C, S0=None, la_scale=1.0):
 # --------------------------------------------------------------------------- #
 def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
                              w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
-                             q_nla=None, k_nla=None):
+                             q_nla=None, k_nla=None, inner=0):
     """One (batch, head) with one routing decision per chunk of C tokens (mask_c[c] = 1: softmax chunk).
 
     Section 4.1: a chunk's type is known only once the whole chunk has been seen, so both
@@ -313,6 +330,11 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
     cnt / idx / n_s describe the compaction of the tokens of softmax chunks.
     linear_op, decay_on_softmax: the variants of gdn_recurrent (without decay on softmax chunks the state
     after such a chunk is the chunk-start state itself).
+    inner: which operation computes the inner part of a chunk (Section 5, ablation (i)): 0 both (the method);
+    1 softmax attention only ("SAttn Out": the linear branch's output reads the carried state of the chunk's
+    start, decayed up to the query, and nothing of the chunk's own tokens); 2 the linear operation only ("GDN
+    Out": a query attends to the tokens of earlier softmax chunks and to nothing of its own chunk; a query with
+    nothing visible gets o_nla = 0, lse = -inf).  The carried state and the cache are the same in all three.
     """
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
     qn = q if q_nla is None else np.asarray(q_nla, dtype=np.float64)   # the softmax branch's own queries and keys
@@ -336,8 +358,11 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
             decay *= alpha[t]
             pred = S @ k[t] if linear_op == 0 else 0.0
             S = S + beta[t] * np.outer(v[t] - pred, k[t])            # Eq. 19, every token of the chunk
-            o_la[t] = la_scale * (S @ q[t])
-            J = np.asarray(earlier + list(range(c * C, t + 1)), dtype=np.int64)
+            o_la[t] = la_scale * ((S if inner != 1 else decay * S_start) @ q[t])
+            own = list(range(c * C, t + 1)) if inner != 2 else []
+            J = np.asarray(earlier + own, dtype=np.int64)
+            if J.size == 0:
+                continue
             s = scale * (kn[J] @ qn[t])
             smax = s.max()
             e = np.exp(s - smax)
@@ -354,7 +379,7 @@ def hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale=None
 
 def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None, la_scale=1.0, mode=0,
                             w_nla=None, w_la=None, eps=1e-6, S0=None, linear_op=0, decay_on_softmax=True,
-                            Q_nla=None, K_nla=None):
+                            Q_nla=None, K_nla=None, inner=0):
     """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; same result layout as hybrid_fwd."""
     B, H, L, _ = np.asarray(Q).shape
     d_v = np.asarray(V).shape[-1]
@@ -370,7 +395,8 @@ def hybrid_fwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, softmax_scale=None,
                                          None if w_nla is None else w_nla[b, h],
                                          None if w_la is None else w_la[b, h], eps,
                                          None if S0 is None else S0[b, h], linear_op, decay_on_softmax,
-                                         None if Q_nla is None else Q_nla[b, h], None if K_nla is None else K_nla[b, h])
+                                         None if Q_nla is None else Q_nla[b, h], None if K_nla is None else K_nla[b, h],
+                                         inner)
             for key in ("O", "O_la", "O_nla", "lse", "S", "cnt", "n_s"):
                 out[key][b, h] = r[key]
             out["idx"][b][h] = r["idx"]

@@ -166,3 +166,68 @@ def test_chunk_routed_separate_softmax_queries_and_keys():
     r = no2.hybrid_head_chunk_routed(q, k, v, a, b, mc, 64, q_nla=qn, k_nla=kn)
     np.testing.assert_allclose(r["O_la"], no2.hybrid_head_chunk_routed(q, k, v, a, b, mc, 64)["O_la"], rtol=1e-12)
     np.testing.assert_allclose(r["O_nla"], no2.hybrid_head_chunk_routed(qn, kn, v, a, b, mc, 64)["O_nla"], rtol=1e-12)
+
+
+# ---- Section 5, ablation (i): the inner part of a chunk by one operation only -----------------------------------
+def _abl_inputs(L=48, d=6, C=8, seed=3):
+    from nats_inputs import make_fwd_inputs
+    x = make_fwd_inputs(1, 1, L, d, "f32", 0.2, seed=seed)
+    mc = (np.random.default_rng(seed + 1).random(L // C) < 0.4).astype(np.uint8)
+    return {k: v[0, 0].astype(np.float64) for k, v in x.items() if k != "mask"}, mc, C
+
+
+def test_inner_part_by_the_linear_operation_only():
+    """"GDN Out": the softmax branch is library attention under the mask "column in an earlier softmax chunk"
+    (rows that see nothing give zero); the linear branch and the carried state are those of the method."""
+    import torch
+    x, mc, C = _abl_inputs()
+    L = x["Q"].shape[0]
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, softmax_scale=0.8, inner=2)
+    ref = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, softmax_scale=0.8)
+    np.testing.assert_array_equal(r["O_la"], ref["O_la"])
+    np.testing.assert_array_equal(r["S"], ref["S"])
+    ci = np.arange(L) // C
+    allowed = (ci[None, :] < ci[:, None]) & np.repeat(mc != 0, C)[None, :]
+    q, k, v = (torch.tensor(x[n][None, None].astype(np.float64)) for n in ("Q", "K", "V"))
+    seen = allowed.any(1)
+    safe = allowed | ~seen[:, None]          # rows that see nothing: attend to everything, then zeroed
+    o = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=torch.tensor(safe)[None, None], scale=0.8)[0, 0].numpy()
+    o[~seen] = 0.0
+    np.testing.assert_allclose(r["O_nla"], o, rtol=1e-10, atol=1e-12)
+    assert np.all(np.isneginf(r["lse"][~seen])) and np.all(np.isfinite(r["lse"][seen]))
+    np.testing.assert_allclose(r["O"], r["O_la"] + r["O_nla"], rtol=0, atol=0)
+
+
+def test_inner_part_by_softmax_attention_only():
+    """"SAttn Out": the linear branch's output is that of a run in which the chunk's own tokens write nothing,
+    started from the method's carried state at the chunk's start; the softmax branch and the carried state are
+    those of the method."""
+    x, mc, C = _abl_inputs(seed=5)
+    L = x["Q"].shape[0]
+    S0 = 0.1 * np.random.default_rng(9).standard_normal((6, 6))
+    r = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, la_scale=1.3, S0=S0, inner=1)
+    ref = no.hybrid_head_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], mc, C, la_scale=1.3, S0=S0)
+    np.testing.assert_array_equal(r["O_nla"], ref["O_nla"])
+    np.testing.assert_array_equal(r["S"], ref["S"])
+    S = S0
+    for c in range(L // C):
+        sl = slice(c * C, (c + 1) * C)
+        o, _ = no.gdn_recurrent(x["Q"][sl], x["K"][sl], x["V"][sl], x["alpha"][sl], np.zeros(C), np.zeros(C), S0=S,
+                                 la_scale=1.3)
+        np.testing.assert_allclose(r["O_la"][sl], o, rtol=1e-12, atol=1e-14)
+        # the state the method carries into the next chunk
+        _, S_lin = no.gdn_recurrent(x["Q"][sl], x["K"][sl], x["V"][sl], x["alpha"][sl], x["beta"][sl], np.zeros(C), S0=S)
+        S = S_lin if mc[c] == 0 else np.prod(x["alpha"][sl]) * S
+
+
+def test_weights_from_the_input_features():
+    """Ablation (v): the same activations as Eq. 22 on W_x x_t, against library linear / softmax / sigmoid."""
+    import torch
+    rng = np.random.default_rng(4)
+    X, W = rng.standard_normal((2, 10, 12)), rng.standard_normal((3, 2, 12))
+    logits = torch.nn.functional.linear(torch.tensor(X), torch.tensor(W).reshape(6, 12)).reshape(2, 10, 3, 2).permute(0, 2, 1, 3)
+    for act, f in ((0, lambda z: torch.softmax(z, -1)), (1, torch.sigmoid), (2, lambda z: z)):
+        wn, wl = no.weights_from_x(X, W, act)
+        w = f(logits).numpy()
+        np.testing.assert_allclose(wn, w[..., 0], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(wl, w[..., 1], rtol=1e-12, atol=1e-14)
