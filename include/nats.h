@@ -123,6 +123,13 @@ typedef struct nats_fwd_params {
                               branch that does not depend on V are done once per linear head.  A generation
                               step (nats_hybrid_attn_decode) is a call on H*G heads with the linear head's
                               q, k, alpha, beta, mask repeated.  Not available in the backward pass          */
+    int32_t inner_chunk;   /* routing per chunk only (else 0): which operation computes the inner part of a chunk.
+                              0: both (the method, Section 4.1).  The ablation (i) of Section 5:
+                              1: softmax attention only: the linear branch's output reads the state carried into
+                                 the chunk, decayed up to the query, and nothing the chunk's own tokens wrote;
+                              2: the linear operation only: a query attends to earlier softmax chunks only (a
+                                 query that then sees nothing gets O_nla = 0, lse = -inf).
+                              The carried state and the cache are the same in all three.  Forward only          */
 } nats_fwd_params;
 
 /* Optional inputs / outputs of nats_hybrid_attn_fwd_ex; any pointer may be NULL. */
@@ -306,6 +313,13 @@ nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, 
  *   Q [B,H,L,d] dtype p->dtype (L = 1 for a generation step; only B, H, L, d, dtype, weight_act of p are used),
  *   W_out [H,2,d] f32  ->  w_nla, w_la [B,H,L] f32,  [w_nla, w_la] = softmax([W_out[h,0] . q, W_out[h,1] . q]).
  * The paper maps "the attention q values" to the weights; the Q given here is used as it is. */
+/* The ablation (v) of Section 5, "Weights From X": the merge weights from the layer's input features instead of
+ * the queries.  X [B,L,d_model] dtype (d_model a multiple of 8, at most 65536), W_x [H,2,d_model] f32 (row 0:
+ * softmax attention, row 1: the linear operation; H at most 32)  ->  w_nla, w_la [B,H,L] f32 =
+ * weight_act([W_x[h,0] . x_t, W_x[h,1] . x_t]), to be passed to the forward as its w_nla, w_la. */
+nats_status nats_merge_weights_from_x(int32_t B, int32_t L, int32_t d_model, int32_t H, int32_t dtype, const void* X,
+                                      const float* W_x, int32_t weight_act, float* w_nla, float* w_la, void* hip_stream);
+
 nats_status nats_merge_weights(const nats_fwd_params* p, const void* Q, const float* W_out, float* w_nla,
                                float* w_la, void* hip_stream);
 

@@ -36,7 +36,7 @@ class FwdParams(ctypes.Structure):
                 ("la_scale", ctypes.c_float), ("combine_mode", ctypes.c_int32), ("rms_eps", ctypes.c_float),
                 ("math", ctypes.c_int32), ("routing", ctypes.c_int32), ("linear_op", ctypes.c_int32),
                 ("freeze_on_softmax", ctypes.c_int32), ("weight_act", ctypes.c_int32),
-                ("gdn_segments", ctypes.c_int32), ("group", ctypes.c_int32)]
+                ("gdn_segments", ctypes.c_int32), ("group", ctypes.c_int32), ("inner_chunk", ctypes.c_int32)]
 
 
 class FwdExtra(ctypes.Structure):
@@ -72,7 +72,7 @@ EXPORTS = ("nats_hybrid_attn_fwd_workspace_bytes", "nats_hybrid_attn_fwd", "nats
            "nats_profile_end", "nats_probe_mfma", "nats_hybrid_attn_decode_chunk",
            "nats_hybrid_attn_decode_commit", "nats_merge_weights", "nats_route_chunks",
            "nats_hybrid_attn_bwd_workspace_bytes", "nats_hybrid_attn_bwd", "nats_hybrid_attn_fwd_noalloc",
-           "nats_hybrid_attn_decode_workspace_bytes")
+           "nats_hybrid_attn_decode_workspace_bytes", "nats_merge_weights_from_x")
 
 
 def library_path() -> str:
@@ -109,6 +109,8 @@ def load_library():
     lib.nats_merge_weights.argtypes = [ctypes.POINTER(FwdParams)] + [vp] * 5
     lib.nats_route_chunks.restype = ctypes.c_int
     lib.nats_route_chunks.argtypes = [ctypes.c_int32] * 6 + [vp] * 5
+    lib.nats_merge_weights_from_x.restype = ctypes.c_int
+    lib.nats_merge_weights_from_x.argtypes = [ctypes.c_int32] * 5 + [vp, vp, ctypes.c_int32, vp, vp, vp]
     lib.nats_hybrid_attn_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.nats_hybrid_attn_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecParams)]
     lib.nats_hybrid_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -161,9 +163,9 @@ def _stream_ptr() -> ctypes.c_void_p:
 
 def make_fwd_params(B, H, L, d, C, dtype_code, softmax_scale=0.0, la_scale=0.0, combine_mode=0, rms_eps=0.0,
                     math=NATS_MATH_AUTO, routing=NATS_ROUTE_TOKEN, linear_op=NATS_LINEAR_GDN,
-                    freeze_on_softmax=0, weight_act=0, gdn_segments=0, group=1) -> FwdParams:
+                    freeze_on_softmax=0, weight_act=0, gdn_segments=0, group=1, inner_chunk=0) -> FwdParams:
     return FwdParams(B, H, L, d, C, dtype_code, softmax_scale, la_scale, combine_mode, rms_eps, math, routing,
-                     linear_op, int(freeze_on_softmax), weight_act, gdn_segments, group)
+                     linear_op, int(freeze_on_softmax), weight_act, gdn_segments, group, inner_chunk)
 
 
 def fwd_workspace_bytes(params: FwdParams) -> int:
@@ -179,7 +181,8 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
                        freeze_on_softmax: bool = False, w_nla=None, w_la=None,
                        W_out=None, weight_act: int = NATS_WEIGHTS_SOFTMAX, initial_state=None, Q_nla=None, K_nla=None,
                        want: Sequence[str] = (), cap: Optional[int] = None, out=None,
-                       workspace=None, gdn_segments: int = 0, group: int = 1) -> Dict[str, torch.Tensor]:
+                       workspace=None, gdn_segments: int = 0, group: int = 1,
+                       inner_chunk: int = 0) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_fwd_ex.  `want` lists optional outputs to allocate and return
     (any of final_state, Kc, Vc, n_s, idx, cnt, O_la, O_nla, lse); the result dict always holds "O".
     group = G > 1 (head grouping): Q, K, alpha, beta, mask have H heads, everything else H * G."""
@@ -200,7 +203,7 @@ def hybrid_attn_fwd_ex(Q, K, V, alpha, beta, mask, C: int = 64, *, softmax_scale
     _require(K_nla, "K_nla", (B, HG, L, d), dt)
     _require(W_out, "W_out", (HG, 2, d), torch.float32)
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
-                             routing, linear_op, freeze_on_softmax, weight_act, gdn_segments, group)
+                             routing, linear_op, freeze_on_softmax, weight_act, gdn_segments, group, inner_chunk)
     need = lib.nats_hybrid_attn_fwd_workspace_bytes(ctypes.byref(params))
     if need == 0:
         _check(lib.nats_hybrid_attn_fwd_ex(ctypes.byref(params), *([None] * 7), None, None, 0, None))
@@ -388,6 +391,20 @@ def route_chunks(X, W_s, C: int = 64, want_scores: bool = True):
     _check(lib.nats_route_chunks(B, L, C, dm, H, _dtype_code(X), _ptr(X), _ptr(W_s), _ptr(scores), _ptr(mask_c),
                                  _stream_ptr()))
     return mask_c, scores
+
+
+def merge_weights_from_x(X, W_x, weight_act: int = NATS_WEIGHTS_SOFTMAX):
+    """nats_merge_weights_from_x: X [B,L,d_model], W_x [H,2,d_model] f32 -> (w_nla, w_la) [B,H,L] f32."""
+    lib = load_library()
+    B, L, dm = X.shape
+    H = W_x.shape[0]
+    _require(X, "X", (B, L, dm), X.dtype)
+    _require(W_x, "W_x", (H, 2, dm), torch.float32)
+    w_nla = torch.empty((B, H, L), dtype=torch.float32, device=X.device)
+    w_la = torch.empty_like(w_nla)
+    _check(lib.nats_merge_weights_from_x(B, L, dm, H, _dtype_code(X), _ptr(X), _ptr(W_x), weight_act, _ptr(w_nla),
+                                         _ptr(w_la), _stream_ptr()))
+    return w_nla, w_la
 
 
 def merge_weights(Q, W_out, weight_act: int = NATS_WEIGHTS_SOFTMAX):

@@ -131,6 +131,11 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         set_error("B*H*group must not exceed 65535 and B*H*group*L must fit in 31 bits");
         return NATS_ERR_SHAPE;
     }
+    if (p->inner_chunk < 0 || p->inner_chunk > 2 || (p->inner_chunk != 0 && p->routing != NATS_ROUTE_CHUNK)) {
+        set_error("inner_chunk must be 0, or 1 / 2 with routing per chunk (got %d)", p->inner_chunk);
+        return NATS_ERR_SHAPE;
+    }
+    pl->inner_chunk = p->inner_chunk;
     pl->qk_per_out_head = 0;   // set by the call: whether the softmax heads have queries and keys of their own
     pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
     pl->BHG = pl->BH * pl->G;
@@ -209,6 +214,7 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
         return NATS_ERR_UNSUPPORTED;
     }
     if (pl->G != 1) { set_error("the backward pass has no head grouping (group %d given)", pl->G); return NATS_ERR_UNSUPPORTED; }
+    if (pl->inner_chunk != 0) { set_error("the backward pass covers inner_chunk 0 only (got %d)", pl->inner_chunk); return NATS_ERR_UNSUPPORTED; }
     plan_bwd(*pl, bp);
     return NATS_OK;
 }
@@ -655,7 +661,32 @@ nats_status nats_route_chunks(int32_t B, int32_t L, int32_t C, int32_t d_model, 
     if (!aligned16(X) || !aligned16(W_s)) { set_error("X and W_s must be 16-byte aligned"); return NATS_ERR_ALIGN; }
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     ProfScope ps("route_chunks", stream);
-    return launch_route_chunks(B, L, C, d_model, H, dtype, X, W_s, scores, mask_c, stream);
+    return launch_route_chunks(B, L, C, d_model, H, dtype, X, W_s, scores, mask_c, nullptr, nullptr, 0, stream);
+}
+
+nats_status nats_merge_weights_from_x(int32_t B, int32_t L, int32_t d_model, int32_t H, int32_t dtype, const void* X,
+                                      const float* W_x, int32_t weight_act, float* w_nla, float* w_la, void* hip_stream) {
+    if (dtype != NATS_F32 && dtype != NATS_BF16) { set_error("dtype %d is neither NATS_F32 nor NATS_BF16", dtype); return NATS_ERR_DTYPE; }
+    if (B <= 0 || L <= 0 || H <= 0 || d_model <= 0) {
+        set_error("B, L, H, d_model must be positive (got %d, %d, %d, %d)", B, L, H, d_model);
+        return NATS_ERR_SHAPE;
+    }
+    if (H > 32) { set_error("H must not exceed 32 (got %d)", H); return NATS_ERR_SHAPE; }
+    if (d_model % 8 != 0 || d_model > 65536) {
+        set_error("d_model must be a multiple of 8 and at most 65536 (got %d)", d_model);
+        return NATS_ERR_SHAPE;
+    }
+    if ((long long)B * L > (1ll << 31) - 1) { set_error("B * L must fit in 31 bits"); return NATS_ERR_SHAPE; }
+    if (weight_act < NATS_WEIGHTS_SOFTMAX || weight_act > NATS_WEIGHTS_LINEAR) {
+        set_error("weight_act must be a nats_weight_act (got %d)", weight_act);
+        return NATS_ERR_SHAPE;
+    }
+    if (!X || !W_x || !w_nla || !w_la) { set_error("X, W_x, w_nla and w_la must be non-NULL"); return NATS_ERR_NULL; }
+    if (!aligned16(X) || !aligned16(W_x)) { set_error("X and W_x must be 16-byte aligned"); return NATS_ERR_ALIGN; }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps("merge_weights_from_x", stream);
+    // the score layer's kernel with chunks of one token: the same mean (of one row) and linear map
+    return launch_route_chunks(B, L, 1, d_model, H, dtype, X, W_x, nullptr, nullptr, w_nla, w_la, weight_act, stream);
 }
 
 static nats_status validate_dec_params(const nats_dec_params* p) {

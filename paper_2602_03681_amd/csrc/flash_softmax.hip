@@ -63,7 +63,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
-    float eps, int BH, int G, int qk_per_out_head) {
+    float eps, int BH, int G, int qk_per_out_head, int own_chunk) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -163,7 +163,8 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const int n_tiles = (n_hi + FL_BN - 1) / FL_BN;
     // The tiles of this block in order: n_tiles compacted ones, then (routing per chunk) the chunks the
     // block's own queries lie in.  Tile i + 1 is loaded while tile i is used.
-    const int n_own = chunk_routing ? (min(q0 + FL_BM, L) - q0) / FL_BN : 0;
+    // (own_chunk = 0: the variant in which only the linear operation computes the inner part of a chunk)
+    const int n_own = (chunk_routing && own_chunk) ? (min(q0 + FL_BM, L) - q0) / FL_BN : 0;
     const int n_all = n_tiles + n_own;
     auto load_any = [&](int i) __attribute__((always_inline)) {
         if (i < n_tiles) load_tile(i); else load_own_chunk(i - n_tiles);
@@ -461,12 +462,12 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
     else
         hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
 }
 
 // O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ alpha,
     const float* __restrict__ beta, const uint8_t* __restrict__ mask, int L, int chunk_mask,
     half_t* __restrict__ TF, half_t* __restrict__ PF, float* __restrict__ gamv, float* __restrict__ kdv,
-    float* __restrict__ gamC, int BH, int linear_op, int freeze_on_softmax) {
+    float* __restrict__ gamC, int BH, int linear_op, int freeze_on_softmax, int no_inner_output) {
     using Lds = InvLds<D>;
     constexpr int RS = Lds::RS;
     constexpr int NPC = CH * D / 8 / INV_THREADS;   // 16-byte pieces of a [64][D] tile per thread
@@ -231,7 +231,8 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int i = 16 * b + 4 * lq + j;
-                    pv[j] = (i <= r) ? accP[jj][j] * __builtin_amdgcn_exp2f(gr[jj] - g4[j]) : 0.f;
+                    // no_inner_output: the variant in which the linear branch's output reads the carried state only
+                    pv[j] = (i <= r && !no_inner_output) ? accP[jj][j] * __builtin_amdgcn_exp2f(gr[jj] - g4[j]) : 0.f;
                 }
                 *reinterpret_cast<half4*>(Pc + frag_off(r, 16 * b + 4 * lq)) = to_half4(pv);
             }
@@ -331,11 +332,11 @@ nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K
     if (pl.d == 64)
         hipLaunchKernelGGL(gdn_chunk_inv_kernel<64>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
-                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
+                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax, pl.inner_chunk == 1);
     else
         hipLaunchKernelGGL(gdn_chunk_inv_kernel<128>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
-                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax);
+                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax, pl.inner_chunk == 1);
     return check_launch("gdn_chunk_inv");
 }
 

@@ -22,7 +22,8 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
-    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax, int G) {
+    float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax, int G,
+    int no_inner_output) {
     constexpr int DP = D / 4;       // columns of a row per lane
     constexpr int DPP = DP + 4;     // padded quarter stride: the four quarters land in different banks
     __shared__ __align__(16) float s_k[REC_TT][4 * DPP];
@@ -58,6 +59,11 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     float* my_snap = chunk_mask ? snap + ((size_t)bh * D + row) * D + part * DP : nullptr;
     const uint8_t* mask_c = mask + (size_t)(bh / G) * (L / 64);
     float chunk_decay = 1.f;
+    // no_inner_output (routing per chunk only): the output reads the state carried into the chunk, decayed up to
+    // the query, and nothing the chunk's own tokens wrote; that state lives in Sc beside the provisional one
+    float Sc[DP];
+#pragma unroll
+    for (int c = 0; c < DP; ++c) Sc[c] = S[c];
 
     constexpr int EPL = Vec16<T>::N;
     for (int t0 = 0; t0 < L; t0 += REC_TT) {
@@ -99,6 +105,10 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
                 for (int c = 0; c < DP; c += 4)
                     *reinterpret_cast<float4*>(my_snap + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
                 chunk_decay = 1.f;
+                if (no_inner_output) {
+#pragma unroll
+                    for (int c = 0; c < DP; ++c) Sc[c] = S[c];
+                }
             }
             chunk_decay *= a;
             if (b != 0.f) {  // uniform across the block
@@ -126,6 +136,15 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
                     const float4 q4 = *reinterpret_cast<const float4*>(qr + c);
                     S[c] *= a; S[c + 1] *= a; S[c + 2] *= a; S[c + 3] *= a;
                     o += S[c] * q4.x + S[c + 1] * q4.y + S[c + 2] * q4.z + S[c + 3] * q4.w;
+                }
+            }
+            if (no_inner_output) {   // uniform
+                o = 0.f;
+#pragma unroll
+                for (int c = 0; c < DP; c += 4) {
+                    const float4 q4 = *reinterpret_cast<const float4*>(qr + c);
+                    Sc[c] *= a; Sc[c + 1] *= a; Sc[c + 2] *= a; Sc[c + 3] *= a;
+                    o += Sc[c] * q4.x + Sc[c + 1] * q4.y + Sc[c + 2] * q4.z + Sc[c + 3] * q4.w;
                 }
             }
             o = row_sum(o);
@@ -157,11 +176,11 @@ static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const vo
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax, pl.G);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax, pl.G);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,

@@ -179,6 +179,7 @@ struct FwdPlan {
     // Q, K, alpha, beta, mask).  BHG = BH * G output heads; qk_per_out_head: the softmax branch's queries and keys
     // are given per output head (otherwise it uses the linear head's)
     int G, BHG, qk_per_out_head;
+    int inner_chunk;   // routing per chunk: 0 both operations compute a chunk's inner part, 1 softmax attention only, 2 the linear operation only
     int dtype;
     int math;
     float softmax_scale, la_scale, rms_eps;
@@ -235,7 +236,7 @@ nats_status launch_decode_chunk(const nats_dec_params& p, float softmax_scale, f
                                 const void* v, const float* alpha, const float* beta, const float* w_nla,
                                 const float* w_la, void* o, int32_t* err_flags, hipStream_t st);
 nats_status launch_route_chunks(int B, int L, int C, int d_model, int H, int dtype, const void* X, const float* W_s,
-                                float* scores, uint8_t* mask_c, hipStream_t st);
+                                float* scores, uint8_t* mask_c, float* w_nla, float* w_la, int act, hipStream_t st);
 nats_status launch_merge_weights(int B, int H, int L, int d, int dtype, const void* Q, const float* W_out,
                                  float* w_nla, float* w_la, int act, int G, hipStream_t st);
 nats_status launch_decode_commit(const nats_dec_params& p, float* state, const float* state_start,

@@ -32,7 +32,8 @@ constexpr int RC_OPW = RC_MAX_OUT / RC_WAVES;   // outputs per wavefront
 template <typename T>
 __global__ __launch_bounds__(RC_THREADS) void route_chunks_kernel(
     const T* __restrict__ X, const float* __restrict__ W_s, float* __restrict__ scores,
-    uint8_t* __restrict__ mask_c, int L, int C, int d_model, int H) {
+    uint8_t* __restrict__ mask_c, int L, int C, int d_model, int H, float* __restrict__ w_nla,
+    float* __restrict__ w_la, int act) {
     constexpr int EPL = Vec16<T>::N;
     constexpr int SLICE = RC_COLS * EPL;           // columns per pass
     __shared__ float s_sum[RC_GROUPS][SLICE];
@@ -105,20 +106,33 @@ __global__ __launch_bounds__(RC_THREADS) void route_chunks_kernel(
             float* dst = scores + (((size_t)b * n_chunks + c) * H + tid) * 2;
             dst[0] = s0; dst[1] = s1;
         }
-        mask_c[((size_t)b * H + tid) * n_chunks + c] = s0 >= s1 ? 1 : 0;
+        if (mask_c != nullptr) mask_c[((size_t)b * H + tid) * n_chunks + c] = s0 >= s1 ? 1 : 0;
+        if (w_nla != nullptr) {   // the same linear map as a source of merge weights (Section 5, ablation (v))
+            float a0 = s0, a1 = s1;
+            if (act == 0) {          // the softmax over the pair, as in Eq. 22
+                const float m = fmaxf(s0, s1);
+                const float e0 = expf(s0 - m), e1 = expf(s1 - m);
+                a0 = e0 / (e0 + e1); a1 = e1 / (e0 + e1);
+            } else if (act == 1) {   // a sigmoid of each
+                a0 = 1.f / (1.f + expf(-s0)); a1 = 1.f / (1.f + expf(-s1));
+            }
+            w_nla[((size_t)b * H + tid) * n_chunks + c] = a0;
+            w_la[((size_t)b * H + tid) * n_chunks + c] = a1;
+        }
     }
 }
 
 // X [B,L,d_model] (dtype), W_s [H,2,d_model] f32 -> scores [B,L/C,H,2] f32 (optional), mask_c [B,H,L/C] u8
+// w_nla, w_la [B,H,L/C] f32 (optional): the scores passed through the activation `act` of the merge weights
 nats_status launch_route_chunks(int B, int L, int C, int d_model, int H, int dtype, const void* X, const float* W_s,
-                                float* scores, uint8_t* mask_c, hipStream_t st) {
+                                float* scores, uint8_t* mask_c, float* w_nla, float* w_la, int act, hipStream_t st) {
     dim3 grid((unsigned)(B * (L / C)));
     if (dtype == NATS_BF16)
         hipLaunchKernelGGL(route_chunks_kernel<bf16_t>, grid, dim3(RC_THREADS), 0, st, (const bf16_t*)X, W_s, scores,
-                           mask_c, L, C, d_model, H);
+                           mask_c, L, C, d_model, H, w_nla, w_la, act);
     else
         hipLaunchKernelGGL(route_chunks_kernel<float>, grid, dim3(RC_THREADS), 0, st, (const float*)X, W_s, scores,
-                           mask_c, L, C, d_model, H);
+                           mask_c, L, C, d_model, H, w_nla, w_la, act);
     return check_launch("route_chunks");
 }
 

@@ -27,7 +27,8 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kc, const T* __restrict__ Vc,
     const T* __restrict__ K, const T* __restrict__ V, int chunk_routing, const int32_t* __restrict__ cnt, const float* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, T* __restrict__ O, float* __restrict__ O_nla_out,
-    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps, int G, int qk_per_out_head) {
+    float* __restrict__ lse_out, int L, float scale, int combine_mode, float eps, int G, int qk_per_out_head,
+    int own_chunk) {
     constexpr int DP = D / 4;       // elements of a row per lane
     constexpr int DPP = DP + 4;     // padded quarter stride (floats): quarters land in different banks
     constexpr int EPL = Vec16<T>::N;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         }
     };
     for (int c0 = 0; c0 < n_hi; c0 += SM_BN) tile(Kc, tokb, Vc, c0, min(SM_BN, n_hi - c0), my_cnt - c0);
-    if (chunk_routing)   // the block's own chunk, rows q0 .. q0 + 63 of K and V: query row r sees rows <= r
+    if (chunk_routing && own_chunk)   // the block's own chunk, rows q0 .. q0 + 63 of K and V: query row r sees rows <= r
         for (int d0 = 0; d0 < SM_BM; d0 += SM_BN) tile(K, tokb_qk, V, q0 + d0, SM_BN, r + 1 - d0);
 
     // ---- epilogue: normalise, optional branch outputs, merge, store -----------------------
@@ -181,12 +182,12 @@ static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const vo
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 64>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
                            (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
-                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head);
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
     else
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 128>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
                            (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
-                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head);
+                           pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
 }
 
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,

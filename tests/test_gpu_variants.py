@@ -220,3 +220,45 @@ def test_single_normalisation_merge(dtype, d, math):
         o_ref, _ = c_oracle.decode(S_ref, kc_ref, vc_ref, cl_ref, xd["q"][s], xd["k"][s], xd["v"][s], xd["alpha"][s],
                                    xd["beta"][s], xd["mask"][s], mode=2, w_nla=wd[0, s], w_la=wd[1, s])
         assert rel_err(host(o), o_ref, stored(dtype)) <= TOL[dtype], s
+
+
+# ---- Section 5, ablation (i): the inner part of a chunk by one operation only; (v): weights from the features ----
+@pytest.mark.parametrize("inner", [1, 2])
+@pytest.mark.parametrize("dtype,d,L,math", [("f32", 64, 256, 0), ("bf16", 128, 512, 0), ("bf16", 64, 320, 0),
+                                            ("bf16", 64, 256, 1)])
+def test_inner_part_of_a_chunk_by_one_operation(dtype, d, L, math, inner):
+    B, H = 1, 2
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=900 + d + L)
+    x["mask"] = make_chunk_mask(B, H, L // 64, 0.4, 901 + inner, "bernoulli")
+    S0 = (0.1 * np.random.default_rng(902).standard_normal((B, H, d, d))).astype(np.float32)
+    g = to_dev(x, dtype)
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 64, want=ALL_OUT,
+                                routing=nb.NATS_ROUTE_CHUNK, inner_chunk=inner, math=math,
+                                initial_state=torch.from_numpy(S0).cuda())
+    torch.cuda.synchronize()
+    ref = npo.hybrid_fwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, S0=S0, inner=inner)
+    for key, rk, st in (("O", "O", stored(dtype)), ("O_la", "O_la", None), ("O_nla", "O_nla", None), ("final_state", "S", None)):
+        e = rel_err(host(r[key]), ref[rk], st)
+        assert e <= TOL[dtype], (key, e)
+    lse, lse_ref = host(r["lse"]), ref["lse"]
+    fin = np.isfinite(lse_ref)
+    np.testing.assert_array_equal(np.isfinite(lse), fin)     # inner = 2: queries before the first softmax chunk see nothing
+    assert np.max(np.abs(lse[fin] - lse_ref[fin]), initial=0.0) <= (1e-4 if dtype == "f32" else 2e-2)
+    np.testing.assert_array_equal(host(r["cnt"]), ref["cnt"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("act", [nb.NATS_WEIGHTS_SOFTMAX, nb.NATS_WEIGHTS_SIGMOID, nb.NATS_WEIGHTS_LINEAR])
+def test_merge_weights_from_the_input_features(dtype, act):
+    from nats_inputs import round_to_bf16
+    B, L, dm, H = 2, 192, 1032, 6
+    rng = np.random.default_rng(910 + act)
+    X = rng.standard_normal((B, L, dm)).astype(np.float32)
+    if dtype == "bf16":
+        X = round_to_bf16(X)
+    W = (rng.standard_normal((H, 2, dm)) / np.sqrt(dm)).astype(np.float32)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    wn, wl = nb.merge_weights_from_x(torch.from_numpy(X).to(tdt).cuda(), torch.from_numpy(W).cuda(), act)
+    torch.cuda.synchronize()
+    rn, rl = npo.weights_from_x(X, W, act)
+    assert np.max(np.abs(host(wn) - rn)) <= 1e-5 and np.max(np.abs(host(wl) - rl)) <= 1e-5
