@@ -393,27 +393,22 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         float* seg_ws = reinterpret_cast<float*>(ws + pl.off_seg);
         void* VhT = ws + pl.off_vht;
         void* Oh = ws + pl.off_olah;   // fp16 hand-off between the two branches
-        // Plain-sum merge (Section 4.1): the softmax branch runs first and hands its output over in
-        // fp16; the kernel that carries the state adds it where the linear output is in registers.
-        // Eq. 21 needs whole rows of both branches: there the softmax kernel runs last and merges.
-        const bool merge_in_scan = pl.combine_mode == 0;
-        if (merge_in_scan) {
-            ProfScope ps("flash_softmax", stream);
-            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, Oh, ex.O_nla, ex.lse,
-                                      stream);
-            if (st != NATS_OK) return st;
-        }
+        // The linear branch first, leaving its rows as fp16; the softmax kernel runs last and merges where its own
+        // rows are in registers (the plain sum of Section 4.1 as well as Eq. 21, which needs whole rows of both
+        // branches).  With the merge inside the scan instead, its second pass, which runs at the rate its bytes
+        // stream at, read the softmax branch's rows on top of its operands and took longer than the softmax
+        // kernel saved.
         {
             ProfScope ps("gdn_chunk_inv", stream);
             st = launch_gdn_chunk_inv(pl, Q, K, alpha, beta, mask, TF, PF, gamv, kdv, gamC, stream);
         }
         if (st != NATS_OK) return st;
-        st = launch_gdn_seg_scan(pl, Q, K, V, TF, PF, gamv, kdv, gamC, ex.initial_state, ex.final_state, seg_ws,
-                                 merge_in_scan ? nullptr : Oh, ex.O_la, merge_in_scan ? Oh : nullptr, O, stream);
+        st = launch_gdn_seg_scan(pl, Q, K, V, TF, PF, gamv, kdv, gamC, ex.initial_state, ex.final_state, seg_ws, Oh,
+                                 ex.O_la, stream);
         if (st != NATS_OK) return st;
-        if (!merge_in_scan) {
+        {
             ProfScope ps("flash_softmax", stream);
-            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, Oh, ex.w_nla, ex.w_la, O, nullptr, ex.O_nla, ex.lse, stream);
+            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, Oh, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
         }
     } else {
         {

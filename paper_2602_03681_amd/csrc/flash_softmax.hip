@@ -51,17 +51,15 @@ __device__ __forceinline__ float quad_max(float x) {
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-// MERGE = true : the epilogue reads the linear branch's output (fp16), merges and stores O.
-// MERGE = false: the epilogue stores the softmax branch's output as fp16 (O_nla_h); the kernel that
-//                carries the state merges and stores O.  This variant depends on nothing but the
-//                compaction, so it can run beside the linear branch's preparation.
+// The epilogue reads the linear branch's output (fp16), merges (Section 4.1 sum, Eq. 21 or its ablation) and
+// stores O.
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
-template <int D, bool MERGE, bool chunk_routing>
+template <int D, bool chunk_routing>
 __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
-    const float* __restrict__ w_la, bf16_t* __restrict__ O, half_t* __restrict__ O_nla_h,
+    const float* __restrict__ w_la, bf16_t* __restrict__ O,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
     float eps, int BH, int G, int qk_per_out_head, int own_chunk) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
@@ -347,15 +345,21 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     }
     __syncthreads();   // tiles are dead: the region becomes the output staging
 
-    if (!MERGE && O_nla_out == nullptr) {
-        // Nothing to merge and no fp32 copy asked for: the normalised rows are staged as fp16, both
-        // 16-query groups of the wavefront at once, so that all LDS writes, then all LDS reads, then all
-        // stores (16 bytes per lane, full rows) are in flight together.
+    if (combine_mode == 0 && O_nla_out == nullptr) {
+        // The plain sum (no row statistics needed) and no fp32 copy asked for: the
+        // normalised rows are staged as fp16, both 16-query groups of the wavefront at once, so that all LDS
+        // writes, then all LDS reads, then all stores (16 bytes per lane, full rows) are in flight together.
         constexpr int HS = D + 8;                 // staged row, fp16 elements
         constexpr int LPR_H = D / 8;              // lanes per row
         constexpr int RPP_H = 64 / LPR_H;         // rows per pass
         static_assert(4 * FL_NQ * 16 * HS * 2 <= LDS_BYTES, "fp16 output staging must fit the tile region");
         half_t* Oh = reinterpret_cast<half_t*>(smem) + wave * (FL_NQ * 16 * HS);
+        u32x4 la_rows[FL_NQ * 16 / RPP_H];   // the linear branch's rows (fp16), asked for up front
+#pragma unroll
+        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
+            const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
+            la_rows[pass] = *reinterpret_cast<const u32x4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 8 * (lane % LPR_H));
+        }
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
             const int q = q0 + (wave * FL_NQ + nq) * 16 + l16;
@@ -377,7 +381,14 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
 #pragma unroll
         for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
             const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
-            if (q < L) *reinterpret_cast<u32x4*>(O_nla_h + (tokbase + q) * D + 8 * (lane % LPR_H)) = rows[pass];
+            if (q >= L) continue;
+            // O = O_la + O_nla (Section 4.1), rounded to bf16 once
+            const half8 a = __builtin_bit_cast(half8, rows[pass]), b = __builtin_bit_cast(half8, la_rows[pass]);
+            u32x4 w;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                w[j] = pack_bf16x2((float)a[2 * j] + (float)b[2 * j], (float)a[2 * j + 1] + (float)b[2 * j + 1]);
+            *reinterpret_cast<u32x4*>(O + (tokbase + q) * D + 8 * (lane % LPR_H)) = w;
         }
         return;
     }
@@ -388,16 +399,14 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     constexpr int RPP = 64 / LPR;         // rows per pass of a wavefront
     float* Ow = Ot + wave * 16 * OS;
     half4 lah_all[FL_NQ][16 / RPP];       // the linear branch's rows, all loads issued up front
-    if (MERGE) {
 #pragma unroll
-        for (int nq = 0; nq < FL_NQ; ++nq)
+    for (int nq = 0; nq < FL_NQ; ++nq)
 #pragma unroll
-            for (int pass = 0; pass < 16 / RPP; ++pass) {
-                const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
-                lah_all[nq][pass] =
-                    *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
-            }
-    }
+        for (int pass = 0; pass < 16 / RPP; ++pass) {
+            const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
+            lah_all[nq][pass] =
+                *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
+        }
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
         const int qbase = q0 + (wave * FL_NQ + nq) * 16;
@@ -420,12 +429,13 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
             const float4 x = *reinterpret_cast<const float4*>(Ow + row * OS + 4 * c4);
             const size_t off = (tokbase + (live ? q : 0)) * D + 4 * c4;
             if (O_nla_out != nullptr && live) *reinterpret_cast<float4*>(O_nla_out + off) = x;
-            if (!MERGE) {
-                if (live) *reinterpret_cast<half4*>(O_nla_h + off) = to_half4(f32x4{x.x, x.y, x.z, x.w});
-                continue;
-            }
             const half4 lah = lah_all[nq][pass];
             const float la0 = (float)lah[0], la1 = (float)lah[1], la2 = (float)lah[2], la3 = (float)lah[3];
+            float4 xs = x;
+            if (combine_mode == 0) {   // the plain sum takes this branch's rows as fp16, as the path above does: same bits
+                const half4 xh = to_half4(f32x4{x.x, x.y, x.z, x.w});
+                xs = make_float4((float)xh[0], (float)xh[1], (float)xh[2], (float)xh[3]);
+            }
             float wn = 1.f, wl = 1.f;
             if (combine_mode == 1) {          // Eq. 21: each branch normalised, then weighted
                 const float ss_nla = lane_group_sum<LPR>(x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w);
@@ -436,7 +446,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                 wn = w_nla ? w_nla[tokbase + (live ? q : 0)] : 1.f;
                 wl = w_la ? w_la[tokbase + (live ? q : 0)] : 1.f;
             }
-            float o0 = wn * x.x + wl * la0, o1 = wn * x.y + wl * la1, o2 = wn * x.z + wl * la2, o3 = wn * x.w + wl * la3;
+            float o0 = wn * xs.x + wl * la0, o1 = wn * xs.y + wl * la1, o2 = wn * xs.z + wl * la2, o3 = wn * xs.w + wl * la3;
             if (combine_mode == 2) {
                 const float inv = 1.f / sqrtf(lane_group_sum<LPR>(o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3) / D + eps);
                 o0 *= inv; o1 *= inv; o2 *= inv; o3 *= inv;
@@ -452,36 +462,30 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     }
 }
 
-template <int D, bool MERGE>
+template <int D>
 static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT, const void* K,
                       const void* V, const int32_t* cnt,
-                      const void* O_la, const float* w_nla, const float* w_la, void* O, void* O_nla_h,
+                      const void* O_la, const float* w_nla, const float* w_la, void* O,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
     dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BHG + 7) & ~7)));
     if (pl.routing == NATS_ROUTE_CHUNK)
-        hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
-                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
+                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
     else
-        hipLaunchKernelGGL((flash_softmax_kernel<D, MERGE, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
-                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, (half_t*)O_nla_h, O_nla_out, lse_out, pl.L,
+                           (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
 }
 
-// O_nla_h == nullptr: merge variant (reads O_la fp16, writes O).  Otherwise: writes O_nla_h only.
+// reads O_la (fp16, the linear branch's rows), merges, writes O
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const void* K, const void* V, const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
-                                 hipStream_t st) {
-    if (O_nla_h == nullptr) {
-        if (pl.d == 64) launch_fl<64, true>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
-        else launch_fl<128, true>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, nullptr, O_nla_out, lse_out, st);
-    } else {
-        if (pl.d == 64) launch_fl<64, false>(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
-        else launch_fl<128, false>(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla_h, O_nla_out, lse_out, st);
-    }
+                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st) {
+    if (pl.d == 64) launch_fl<64>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+    else launch_fl<128>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
     return check_launch("flash_softmax");
 }
 

@@ -28,9 +28,10 @@
 // set: the K and Q tiles (contiguous loads, converted to fp16 once, columns permuted into the slot order above),
 // T'', P and the gates.  (K^T scaled by kd, the operand of the state update, is made by the state wavefronts
 // from the K tile, a (contraction step, column half) share each: a product with a 0/1 selector hands a row-major
-// fragment back in the accumulator layout, exactly.)  They also merge and store the output rows,
-// which the state wavefronts leave in an LDS tile (computed transposed, S0 Q^T and U^T P^T, so that a lane
-// holds four consecutive d_v of a token): whole rows of 2 d bytes go out.
+// fragment back in the accumulator layout, exactly.)  They also store the output rows (fp16; the
+// softmax kernel, which runs afterwards, merges the two branches), which the state wavefronts leave in an LDS
+// tile (computed transposed, S0 Q^T and U^T P^T, so that a lane holds four consecutive d_v of a token): whole
+// rows of 2 d bytes go out.
 //   Two block barriers per chunk: one before the output tile is overwritten, one when the next operand set is
 // complete.
 #include <algorithm>
@@ -77,10 +78,8 @@ struct SegArgs {
     float* S_start;           // [BH][n_seg][D][D] start state of every segment (slot 0 unused)
     float* Nbuf;              // [BH][n_seg][D][D] end state of a middle segment run from zero
     float* MTbuf;             // [BH][n_seg][D][D] transposed transition of a middle segment: MT[j][i] = M[i][j]
-    half_t* O_la_h;           // fp16 linear-branch output (for the merge in the softmax kernel) or nullptr
+    half_t* O_la_h;           // fp16 linear-branch output, for the merge in the softmax kernel
     float* O_la_f32;          // optional fp32 copy of the linear-branch output
-    const half_t* O_nla_h;    // fp16 softmax-branch output to add (plain-sum merge) or nullptr
-    bf16_t* O;                // merged output (with O_nla_h)
     int L, BH, n_seg, seg_len, pass, gated;   // BH counts output heads
     int G;                    // output heads per linear head (head grouping): K, Q, T'', P and the gates are the
                               // linear head's (index bh / G), V, the state and the outputs the output head's
@@ -412,7 +411,6 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
 
 // ------------------------------------------------------------------------------------------------------------
 // STAGING wavefronts: the operand set of the next chunk, and the previous chunk's output rows.
-//   MERGE: add the softmax branch's fp16 rows and store O (bf16); otherwise store the linear branch's rows as fp16
 // ------------------------------------------------------------------------------------------------------------
 // what a staging thread carries from memory to the next operand set
 template <int D, bool HAS_OUT>
@@ -444,10 +442,9 @@ struct StageRegs {
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// STAGING wavefronts: the operand set of the next chunk, and the current chunk's output rows.
-//   MERGE: add the softmax branch's fp16 rows and store O (bf16); otherwise store the linear branch's rows as fp16
+// STAGING wavefronts: the operand set of the next chunk, and the current chunk's output rows (fp16).
 // ------------------------------------------------------------------------------------------------------------
-template <int D, int ROLE, bool MERGE>
+template <int D, int ROLE>
 __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
     using Lds = SegLds<D>;
     constexpr int SS = Lds::SS;
@@ -497,31 +494,15 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
 #pragma unroll
         for (int i = 0; i < N_WRITE; ++i) write_piece(i, r, set);
     };
-    u32x4 onla[NPC];               // the softmax branch's rows of the chunk whose output is merged next
-    auto load_onla = [&](int c) __attribute__((always_inline)) {
-        if (!MERGE) return;
-        const u32x4* Og = reinterpret_cast<const u32x4*>(a.O_nla_h + (tokb + (size_t)c * SC) * D);
-#pragma unroll
-        for (int i = 0; i < NPC; ++i) onla[i] = Og[pt + SEG_GROUP * i];
-    };
-    // rows of chunk c out of the output tile: merge and store, 16 bytes per lane, whole rows contiguous
+    // rows of chunk c out of the output tile, as fp16 for the softmax kernel's merge epilogue: 16 bytes per lane,
+    // whole rows contiguous
     auto store_rows = [&](int c) __attribute__((always_inline)) {
         if (!HAS_OUT) return;
         const size_t ob = (tokb + (size_t)c * SC) * D;
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             const int e = pt + SEG_GROUP * i, row = e / (D / 8), c8 = e % (D / 8);
-            const half8 o = lds_read8(OutT + row * SS + 8 * c8);
-            if (MERGE) {   // plain-sum merge (Section 4.1)
-                const half8 h = __builtin_bit_cast(half8, onla[i]);
-                u32x4 w;
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    w[k] = pack_bf16x2((float)o[2 * k] + (float)h[2 * k], (float)o[2 * k + 1] + (float)h[2 * k + 1]);
-                reinterpret_cast<u32x4*>(a.O + ob)[e] = w;
-            } else {       // the linear branch's rows as fp16 for the softmax kernel's merge epilogue
-                reinterpret_cast<half8*>(a.O_la_h + ob)[e] = o;
-            }
+            reinterpret_cast<half8*>(a.O_la_h + ob)[e] = lds_read8(OutT + row * SS + 8 * c8);
         }
     };
     auto load_all = [&](Regs& r, int c) __attribute__((always_inline)) {
@@ -546,7 +527,6 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
             write_piece(i, cur, set);
         }
         __builtin_amdgcn_sched_barrier(0);
-        load_onla(c);
         __syncthreads();   // (the state group overwrites the output tile after this)
         __syncthreads();   // the output tile of chunk c is complete
         store_rows(c);
@@ -566,7 +546,7 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
     if (c < c_end) step(c, rb, ra);
 }
 
-template <int D, bool MERGE, bool F32OUT>
+template <int D, bool F32OUT>
 __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs<D> a) {
     extern __shared__ __align__(16) unsigned char seg_smem[];
     half_t* lds = reinterpret_cast<half_t*>(seg_smem);
@@ -588,13 +568,13 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     else if (sub == 0) { role = ROLE_OUT; seg = 0; }
     else { role = ((sub - 1) & 1) ? ROLE_ACC_E : ROLE_ACC_S; seg = 1 + ((sub - 1) >> 1); }
     if (role == ROLE_OUT) {
-        if (staging) seg_staging_waves<D, ROLE_OUT, MERGE>(a, bh, seg, lds);
+        if (staging) seg_staging_waves<D, ROLE_OUT>(a, bh, seg, lds);
         else seg_state_waves<D, ROLE_OUT, F32OUT>(a, bh, seg, lds);
     } else if (role == ROLE_ACC_S) {
-        if (staging) seg_staging_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
+        if (staging) seg_staging_waves<D, ROLE_ACC_S>(a, bh, seg, lds);
         else seg_state_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
     } else {
-        if (staging) seg_staging_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
+        if (staging) seg_staging_waves<D, ROLE_ACC_E>(a, bh, seg, lds);
         else seg_state_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
     }
 }
@@ -742,13 +722,13 @@ int gdn_segments(const FwdPlan& pl) {
     return std::max(1, std::min(n, 64));
 }
 
-template <int D, bool MERGE, bool F32OUT>
+template <int D, bool F32OUT>
 static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st) {
     static bool attr_done[64] = {};
     int dev = 0;
     (void)hipGetDevice(&dev);
     dev = (dev >= 0 && dev < 64) ? dev : 0;
-    auto kern = gdn_seg_scan_kernel<D, MERGE, F32OUT>;
+    auto kern = gdn_seg_scan_kernel<D, F32OUT>;
     if (!attr_done[dev]) {   // the LDS-size attribute is per function and device
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 SegLds<D>::bytes) != hipSuccess)
@@ -785,28 +765,26 @@ static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
 
 template <int D>
 static nats_status launch_seg_t(const FwdPlan& pl, const SegArgs<D>& a, hipStream_t st) {
-    const bool merge = a.O_nla_h != nullptr, f32 = a.O_la_f32 != nullptr;
-    if (merge) return f32 ? launch_seg_k<D, true, true>(pl, a, st) : launch_seg_k<D, true, false>(pl, a, st);
-    return f32 ? launch_seg_k<D, false, true>(pl, a, st) : launch_seg_k<D, false, false>(pl, a, st);
+    return a.O_la_f32 != nullptr ? launch_seg_k<D, true>(pl, a, st) : launch_seg_k<D, false>(pl, a, st);
 }
 
-// O_nla_h == nullptr: writes O_la_h (fp16) for the softmax kernel to merge.  Otherwise merges (plain sum)
-// with O_nla_h and writes O.  seg_ws: 3 * BH * n_seg * d * d floats (start states, N, M^T).
+// Writes O_la_h (fp16) for the softmax kernel to merge, and O_la_f32 if given.
+// seg_ws: 3 * BH * n_seg * d * d floats (start states, N, M^T).
 nats_status launch_gdn_seg_scan(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* TF,
                                 const void* PF, const float* gamv, const float* kdv, const float* gamC,
                                 const float* S0, float* S_final, float* seg_ws, void* O_la_h, float* O_la_f32,
-                                const void* O_nla_h, void* O, hipStream_t st) {
+                                hipStream_t st) {
     const size_t per = (size_t)pl.BHG * gdn_segments(pl) * pl.d * pl.d;
     if (pl.d == 64) {
         SegArgs<64> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const half_t*)TF, (const half_t*)PF,
                       gamv, kdv, gamC, S0, S_final, seg_ws, seg_ws + per, seg_ws + 2 * per, (half_t*)O_la_h,
-                      O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BHG, 0, 0, 0,
+                      O_la_f32, pl.L, pl.BHG, 0, 0, 0,
                       pl.linear_op == NATS_LINEAR_GATED, pl.G, pl.la_scale};
         return launch_seg_t<64>(pl, a, st);
     }
     SegArgs<128> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const half_t*)TF, (const half_t*)PF,
                    gamv, kdv, gamC, S0, S_final, seg_ws, seg_ws + per, seg_ws + 2 * per, (half_t*)O_la_h,
-                   O_la_f32, (const half_t*)O_nla_h, (bf16_t*)O, pl.L, pl.BHG, 0, 0, 0,
+                   O_la_f32, pl.L, pl.BHG, 0, 0, 0,
                    pl.linear_op == NATS_LINEAR_GATED, pl.G, pl.la_scale};
     return launch_seg_t<128>(pl, a, st);
 }

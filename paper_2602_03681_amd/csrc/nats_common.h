@@ -208,7 +208,7 @@ int gdn_segments(const FwdPlan& pl);   // segments per (batch, head) the chunkwi
 nats_status launch_gdn_seg_scan(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* TF,
                                 const void* PF, const float* gamv, const float* kdv, const float* gamC,
                                 const float* S0, float* S_final, float* seg_ws, void* O_la_h, float* O_la_f32,
-                                const void* O_nla_h, void* O, hipStream_t st);
+                                hipStream_t st);
 nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc, const void* Vc,
                                 const void* K, const void* V,
                                 const int32_t* cnt, const float* O_la, const float* w_nla,
@@ -217,8 +217,7 @@ nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const void* K, const void* V,
                                  const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, void* O_nla_h, float* O_nla_out, float* lse_out,
-                                 hipStream_t st);
+                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st);
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
                           float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
                           const void* k, const void* v, const float* alpha, const float* beta,
