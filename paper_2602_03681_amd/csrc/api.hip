@@ -378,10 +378,9 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     // The kernels run one after the other on the caller's stream.  (The softmax branch depends on nothing
     // the preparation of the linear branch computes, but the preparation kernel fills every CU by itself:
     // beside it on a second stream the softmax branch only waited for free slots, and nothing was gained.)
-    {
+    if (!uses_chunk_path(pl)) {
         ProfScope ps("scan_compact", stream);
-        st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap,
-                                 uses_chunk_path(pl) ? ws + pl.off_vht : nullptr, stream);
+        st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, ex.Kc, ex.Vc, ex.cap, nullptr, stream);
     }
     if (st != NATS_OK) return st;
     if (uses_chunk_path(pl)) {
@@ -400,7 +399,9 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         // kernel saved.
         {
             ProfScope ps("gdn_chunk_inv", stream);
-            st = launch_gdn_chunk_inv(pl, Q, K, alpha, beta, mask, TF, PF, gamv, kdv, gamC, stream);
+            // (this launch also carries the blocks of the mask scan and compaction)
+            st = launch_gdn_chunk_inv(pl, Q, K, alpha, beta, mask, TF, PF, gamv, kdv, gamC, Ks, V, cnt, idx, n_s, Kc, Vc,
+                                      ex.Kc, ex.Vc, ex.cap, VhT, stream);
         }
         if (st != NATS_OK) return st;
         st = launch_gdn_seg_scan(pl, Q, K, V, TF, PF, gamv, kdv, gamC, ex.initial_state, ex.final_state, seg_ws, Oh,

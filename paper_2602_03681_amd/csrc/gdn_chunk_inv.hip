@@ -35,6 +35,7 @@
 
 #include "mfma_util.h"
 #include "nats_common.h"
+#include "scan_compact_block.h"
 
 namespace nats {
 
@@ -64,12 +65,31 @@ __device__ __forceinline__ int frag_off(int r, int i) {
     return ((((r >> 4) * 2 + (i >> 5)) * 64) + 16 * ((i >> 2) & 3) + (r & 15)) * 8 + 4 * ((i >> 4) & 1) + (i & 3);
 }
 
+struct InvArgs {
+    const bf16_t *Q, *K;
+    const float *alpha, *beta;
+    const uint8_t* mask;
+    int L, chunk_mask;
+    half_t *TF, *PF;
+    float *gamv, *kdv, *gamC;
+    int BH, linear_op, freeze_on_softmax, no_inner_output;
+};
+
+// one block of the inversion: block_id counts (chunk, batch*head padded to a multiple of 8)
 template <int D>
-__global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ alpha,
-    const float* __restrict__ beta, const uint8_t* __restrict__ mask, int L, int chunk_mask,
-    half_t* __restrict__ TF, half_t* __restrict__ PF, float* __restrict__ gamv, float* __restrict__ kdv,
-    float* __restrict__ gamC, int BH, int linear_op, int freeze_on_softmax, int no_inner_output) {
+__device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int block_id) {
+    const bf16_t* __restrict__ Q = a.Q;
+    const bf16_t* __restrict__ K = a.K;
+    const float* __restrict__ alpha = a.alpha;
+    const float* __restrict__ beta = a.beta;
+    const uint8_t* __restrict__ mask = a.mask;
+    const int L = a.L, chunk_mask = a.chunk_mask, BH = a.BH, linear_op = a.linear_op;
+    const int freeze_on_softmax = a.freeze_on_softmax, no_inner_output = a.no_inner_output;
+    half_t* __restrict__ TF = a.TF;
+    half_t* __restrict__ PF = a.PF;
+    float* __restrict__ gamv = a.gamv;
+    float* __restrict__ kdv = a.kdv;
+    float* __restrict__ gamC = a.gamC;
     using Lds = InvLds<D>;
     constexpr int RS = Lds::RS;
     constexpr int NPC = CH * D / 8 / INV_THREADS;   // 16-byte pieces of a [64][D] tile per thread
@@ -88,9 +108,9 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
     // One-dimensional grid, chunk-major: all (batch, head) pairs of a chunk side by side (padded to a
     // multiple of 8, so that a pair's blocks land on the XCD whose L2 the recurrence blocks of that pair use).
     const int bh8 = (BH + 7) & ~7;
-    const int bh = blockIdx.x % bh8;
+    const int bh = block_id % bh8;
     if (bh >= BH) return;
-    const int chunk = blockIdx.x / bh8;
+    const int chunk = block_id / bh8;
     const size_t gc = (size_t)bh * n_chunks + chunk;  // global chunk id
     const size_t tok0 = (size_t)bh * L + (size_t)chunk * CH;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -324,19 +344,37 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(
     }
 }
 
-// per chunk: TF, PF (64 * 64 fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above
+// The grid: first the blocks of the mask scan and compaction (the softmax branch's inputs, which nothing of the linear
+// branch needs: a few hundred blocks, each a chain of memory latencies, that would otherwise stand alone on the
+// stream for as long as a fifth of this kernel), then one block per chunk and (batch, head).
+template <int D>
+__global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(const InvArgs a, const ScanArgs<bf16_t> sc,
+                                                                       const int scan_segs, const int scan_blocks) {
+    static_assert(INV_THREADS == SCAN_THREADS, "the two kinds of block share one launch");
+    if ((int)blockIdx.x < scan_blocks) {
+        scan_compact_block<bf16_t>(sc, blockIdx.x % scan_segs, blockIdx.x / scan_segs);
+        return;
+    }
+    gdn_chunk_inv_block<D>(a, blockIdx.x - scan_blocks);
+}
+
+// per chunk: TF, PF (64 * 64 fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above.
+// The same launch carries the mask scan and compaction (arguments as launch_scan_compact).
 nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K, const float* alpha,
                                  const float* beta, const uint8_t* mask, void* TF, void* PF, float* gamv,
-                                 float* kdv, float* gamC, hipStream_t st) {
-    dim3 grid((unsigned)((pl.L / CH) * ((pl.BH + 7) & ~7)));
-    if (pl.d == 64)
-        hipLaunchKernelGGL(gdn_chunk_inv_kernel<64>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
-                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax, pl.inner_chunk == 1);
-    else
-        hipLaunchKernelGGL(gdn_chunk_inv_kernel<128>, grid, dim3(INV_THREADS), 0, st, (const bf16_t*)Q,
-                           (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK, (half_t*)TF,
-                           (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax, pl.inner_chunk == 1);
+                                 float* kdv, float* gamC, const void* K_sm, const void* V, int32_t* cnt, int32_t* idx,
+                                 int32_t* n_s, void* Kc, void* Vc, void* Kc_user, void* Vc_user, int cap_user, void* VhT,
+                                 hipStream_t st) {
+    const InvArgs a{(const bf16_t*)Q, (const bf16_t*)K, alpha, beta, mask, pl.L, pl.routing == NATS_ROUTE_CHUNK,
+                    (half_t*)TF, (half_t*)PF, gamv, kdv, gamC, pl.BH, pl.linear_op, pl.freeze_on_softmax,
+                    pl.inner_chunk == 1};
+    const ScanArgs<bf16_t> sc{mask, (const bf16_t*)K_sm, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
+                              (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT,
+                              pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head};
+    const int scan_segs = (pl.L + SCAN_SEG - 1) / SCAN_SEG, scan_blocks = scan_segs * pl.BHG;
+    dim3 grid((unsigned)(scan_blocks + (pl.L / CH) * ((pl.BH + 7) & ~7)));
+    if (pl.d == 64) hipLaunchKernelGGL(gdn_chunk_inv_kernel<64>, grid, dim3(INV_THREADS), 0, st, a, sc, scan_segs, scan_blocks);
+    else hipLaunchKernelGGL(gdn_chunk_inv_kernel<128>, grid, dim3(INV_THREADS), 0, st, a, sc, scan_segs, scan_blocks);
     return check_launch("gdn_chunk_inv");
 }
 

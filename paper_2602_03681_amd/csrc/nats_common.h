@@ -203,7 +203,9 @@ nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K
                                  const float* S0, float* S_final, float* O_la, float* snap, hipStream_t st);
 nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K, const float* alpha,
                                  const float* beta, const uint8_t* mask, void* TF, void* PF, float* gamv,
-                                 float* kdv, float* gamC, hipStream_t st);
+                                 float* kdv, float* gamC, const void* K_sm, const void* V, int32_t* cnt, int32_t* idx,
+                                 int32_t* n_s, void* Kc, void* Vc, void* Kc_user, void* Vc_user, int cap_user, void* VhT,
+                                 hipStream_t st);
 int gdn_segments(const FwdPlan& pl);   // segments per (batch, head) the chunkwise linear branch will use
 nats_status launch_gdn_seg_scan(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* TF,
                                 const void* PF, const float* gamv, const float* kdv, const float* gamC,
