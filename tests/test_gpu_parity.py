@@ -355,9 +355,10 @@ def test_one_chunk_and_long_thin_shapes_bf16():
 
 @pytest.mark.parametrize("d", [64, 128])
 def test_every_chunk_count_up_to_nine_bf16(d):
-    """1..9 chunks: the recurrence kernel walks its chunks four to a loop trip and up to three in a tail, and
-    prefetches three chunks ahead with a clamped index; every combination of trips and tail is taken here, with
-    a given initial state."""
+    """1..9 chunks: the scan's staging wavefronts walk a segment's chunks two to a loop trip with an odd one behind,
+    one chunk ahead of the state wavefronts and with a clamped index at the end; with the automatic segment count
+    these lengths give segments of one to nine chunks (1 .. 7 chunks: one segment; 8, 9: two), with a given
+    initial state."""
     for n_chunks in range(1, 10):
         L = 64 * n_chunks
         x = make_fwd_inputs(1, 3, L, d, "bf16", 0.1, seed=500 + 10 * n_chunks + d)
@@ -368,8 +369,9 @@ def test_every_chunk_count_up_to_nine_bf16(d):
         assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (L, d)
 
 
-def test_pair_counts_that_change_the_number_of_prefetch_helpers_bf16():
-    """B*H = 40 (two helper blocks per pair fit beside the 160 compute blocks), 48 (one), 56 (none)."""
+def test_pair_counts_that_change_the_automatic_segment_count_bf16():
+    """B*H = 40, 48, 56 at 16 chunks: the automatic choice (about 256 / (B*H) segments) gives 6, 5 and 4 segments;
+    the padded block grids (pairs in groups of 8, one XCD each) hold unused slots for none of them / all of them."""
     for B, H in ((5, 8), (6, 8), (7, 8)):
         x = make_fwd_inputs(B, H, 1024, 128, "bf16", 0.05, seed=600 + B)
         r = run_ex(x, "bf16", want=("final_state",))
