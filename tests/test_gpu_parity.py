@@ -369,9 +369,9 @@ def test_every_chunk_count_up_to_nine_bf16(d):
         assert rel_err(host(r["final_state"]), ref["S"]) <= TOL["bf16"], (L, d)
 
 
-def test_pair_counts_that_change_the_automatic_segment_count_bf16():
-    """B*H = 40, 48, 56 at 16 chunks: the automatic choice (about 256 / (B*H) segments) gives 6, 5 and 4 segments;
-    the padded block grids (pairs in groups of 8, one XCD each) hold unused slots for none of them / all of them."""
+def test_pair_counts_between_powers_of_two_bf16():
+    """B*H = 40, 48, 56 at 16 chunks: pair counts between the powers of two, four segments each (the automatic
+    count, about 256 / (B*H), is capped at a quarter of the chunks): 200 to 280 blocks in the first pass."""
     for B, H in ((5, 8), (6, 8), (7, 8)):
         x = make_fwd_inputs(B, H, 1024, 128, "bf16", 0.05, seed=600 + B)
         r = run_ex(x, "bf16", want=("final_state",))
