@@ -182,7 +182,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 // the reverse sweep and the partial sums of its blocks.
 struct BwdPlan {
     size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp,
-        off_gnla, off_vis, off_dslap, total;
+        off_gnla, off_vis, off_dslap, off_ops, off_ug, off_uh, off_dck, total;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -203,6 +203,11 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_gnla = off;    off = align_up(off + n_tok * 4, 256);   // column sums of Eq. 15 when only their chunk sums are asked for
     bp->off_vis = off;     off = align_up(off + n_tok * 4, 256);   // routing per chunk: compacted rows visible to a query
     bp->off_dslap = off;   off = align_up(off + ns * (n_tok / 64) * 4, 256);   // ... and the sweep's partials of Eq. 17
+    // chunkwise backward of the linear branch: operands of every chunk, U and the residuals, state gradients per chunk
+    bp->off_ops = off;     off = align_up(off + chunk_ops_floats(pl) * 4, 256);
+    bp->off_ug = off;      off = align_up(off + n_tok * pl.d * 4, 256);
+    bp->off_uh = off;      off = align_up(off + n_tok * pl.d * 4, 256);
+    bp->off_dck = off;     off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
     bp->total = off;
 }
 
@@ -510,7 +515,19 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         st = launch_softmax_bwd_dq(pl, Q, Kc, Vc, dO, vis, O_nla, lse, Dvec, dQ, stream);
         if (st != NATS_OK) return st;
     }
-    {   // the linear branch forwards once more, leaving a checkpoint of the state per chunk
+    float* ops = reinterpret_cast<float*>(ws + bp.off_ops);
+    float* Ug = reinterpret_cast<float*>(ws + bp.off_ug);
+    float* Uh = reinterpret_cast<float*>(ws + bp.off_uh);
+    if (!chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
+        {
+            ProfScope ps("gdn_bwd_prep", stream);
+            st = launch_gdn_bwd_prep(pl, Q, K, alpha, beta, mask, ops, stream);
+            if (st != NATS_OK) return st;
+        }
+        ProfScope ps("gdn_chunk_states", stream);
+        st = launch_gdn_chunk_states(pl, K, V, ops, ex.initial_state, ckpt, Ug, Uh, stream);
+        if (st != NATS_OK) return st;
+    } else {   // ... token by token
         ProfScope ps("gdn_checkpoints", stream);
         st = launch_gdn_checkpoints(pl, K, V, alpha, beta, mask, ex.initial_state, ckpt, stream);
         if (st != NATS_OK) return st;

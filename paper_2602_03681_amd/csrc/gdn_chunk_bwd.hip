@@ -1,0 +1,496 @@
+// Backward of the linear branch by chunks of 64 tokens, on fp32 matrix instructions (Section 4.2; the recurrence is
+// Eq. 19 with the decay of Eq. 20, written for linear tokens only, Eq. 14).
+//
+// One chunk, with the state S0 [d_v][d_k] at its start, b' = beta (0 for a softmax token), gamma_r the product of the
+// chunk's alphas up to token r, Gamma_ri = gamma_r / gamma_i, kd_i = gamma_C / gamma_i:
+//     At = strict lower (Gamma . K K^T),  P = lower (Gamma . Q K^T),  T = (I + diag(b') At)^-1
+//     R = V - diag(gamma) K S0^T,   U = T diag(b') R,   Uh = R - At U  (= v_t - Sd k_t, the residual of Eq. 19),
+//     O = la (diag(gamma) Q S0^T + P U),   S1 = gamma_C S0 + U^T diag(kd) K.
+// Given dO' = la dO and dS1 (from the chunks behind):
+//     dU = P^T dO' + diag(kd) K dS1^T,   dRt = T^T dU,   dR = diag(b') dRt = dV,   dbeta_r = Uh_r . dRt_r
+//     dS0 = gamma_C dS1 + dO'^T diag(gamma) Q - dR^T diag(gamma) K
+//     dP = lower (dO' U^T),   dAt = - strict lower (dR U^T)
+//     dQ = diag(gamma) dO' S0 + (dP . Gamma) K
+//     dK = (dP . Gamma)^T Q + ((dAt . Gamma) + (dAt . Gamma)^T) K + diag(kd) U dS1 - diag(gamma) dR S0
+//     d ln gamma_r = sum_i (dAt_ri At_ri + dP_ri P_ri) - sum_r' (dAt_r'r At_r'r + dP_r'r P_r'r)
+//                    + gamma_r (Q_r . (dO' S0)_r - K_r . (dR S0)_r) - E_r,      E_i = kd_i K_i . (U dS1)_i
+//     d ln gamma_C += sum_i E_i + gamma_C <dS1, S0>;     dalpha_t = (sum over r >= t of d ln gamma_r) / alpha_t.
+// (The gated operation without the delta rule has At = 0, T = I, R = V: the terms that come from K S0^T drop.)
+//
+// Four kinds of kernel: the operands of every chunk (parallel over chunks), the states at the chunk starts (forwards
+// along the sequence), the state gradients (backwards along it), and the gradients of every chunk from those
+// (parallel over chunks).  Columns of V (rows of the state) never mix along the sequence, so the two sequential
+// kernels split every (batch, head) into slices of 16 value columns, one block each.
+//
+// Matrix instruction used throughout: v_mfma_f32_16x16x4_f32, out[m][n] += sum_kk A[m][kk] B[kk][n]; lane (l16, lq)
+// gives A[m = l16][kk = lq], B[kk = lq][n = l16] and holds out[m = 4 lq + j][n = l16], j = 0..3.  A product over 16
+// contraction indices takes four instructions; instruction j contracts over the indices 4 lq + j, so that a lane's A
+// operands are four consecutive elements of a row (one 16-byte LDS read when the buffer is contiguous along the
+// contraction index) and a result tile can be the B operand of the next product as it sits in registers.
+#include "nats_common.h"
+#include "mfma_util.h"
+
+namespace nats {
+
+constexpr int CB_C = 64;          // chunk
+constexpr int CB_MS = CB_C + 4;   // row stride (floats) of a 64 x 64 operand in LDS
+constexpr int CB_NV = 16;         // value columns per block of the sequential kernels
+
+struct ChunkOps {   // per chunk: Tm, At, Pm [64][64] f32 row-major;  per token: g2 (log2 of gamma), gam, kd, bp;  per chunk: gamC
+    float *Tm, *At, *Pm, *g2, *gam, *kd, *bp, *gamC;
+};
+
+__device__ __forceinline__ f32x4 mac16(const float4 a, const float4 b, f32x4 c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, c, 0, 0, 0);
+    return c;
+}
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+// four elements of one column, rows r0 .. r0 + 3 (row stride rs)
+__device__ __forceinline__ float4 ld4col(const float* p, int rs) { return make_float4(p[0], p[rs], p[2 * rs], p[3 * rs]); }
+
+// ---- operands of a chunk ---------------------------------------------------------------------------------------------
+// One block per (chunk, batch*head).  Products in fp32 from the inputs as given (bf16 converts exactly); the inverse
+// by forward substitution, one lane per column.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__ Q, const T* __restrict__ K,
+                                                           const float* __restrict__ alpha, const float* __restrict__ beta,
+                                                           const uint8_t* __restrict__ mask, const ChunkOps o, const int L,
+                                                           const int BH, const int freeze_on_softmax, const int linear_op) {
+    constexpr int KS = D + 4, E = Vec16<T>::N, NP = CB_C * D / E / 256;
+    extern __shared__ __align__(16) float cb_smem[];
+    float* Ks = cb_smem;
+    float* Qs = cb_smem + CB_C * KS;
+    float* As = Qs;                         // after the products: diag(b') At, [64][CB_MS]
+    float* s_g = cb_smem + 2 * CB_C * KS;   // log2 gamma
+    float* s_bp = s_g + CB_C;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int n_chunks = L / CB_C;
+    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
+    const size_t gc = (size_t)bh * n_chunks + chunk, tok0 = (size_t)bh * L + (size_t)chunk * CB_C;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int e = tid + 256 * i, row = e / (D / E), c = (e % (D / E)) * E;
+        float tmp[E];
+        Vec16<T>::load(K + (tok0 + row) * D + c, tmp);
+#pragma unroll
+        for (int j = 0; j < E; j += 4) *reinterpret_cast<float4*>(Ks + row * KS + c + j) = make_float4(tmp[j], tmp[j + 1], tmp[j + 2], tmp[j + 3]);
+        Vec16<T>::load(Q + (tok0 + row) * D + c, tmp);
+#pragma unroll
+        for (int j = 0; j < E; j += 4) *reinterpret_cast<float4*>(Qs + row * KS + c + j) = make_float4(tmp[j], tmp[j + 1], tmp[j + 2], tmp[j + 3]);
+    }
+    if (w == 0) {
+        const bool soft = mask[tok0 + lane] != 0;
+        const float a = (freeze_on_softmax && soft) ? 1.f : alpha[tok0 + lane];
+        float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2; inclusive scan over the 64 lanes
+        g += dpp_move<0x111>(g);
+        g += dpp_move<0x112>(g);
+        g += dpp_move<0x114>(g);
+        g += dpp_move<0x118>(g);
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x142, 0xA, 0xF, false));
+        g += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(g), 0x143, 0xC, 0xF, false));
+        const float gC = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g), 63));
+        const float gam = __builtin_amdgcn_exp2f(g);
+        const float bp = soft ? 0.f : beta[tok0 + lane];
+        s_g[lane] = g;
+        s_bp[lane] = bp;
+        o.g2[tok0 + lane] = g;
+        o.gam[tok0 + lane] = gam;
+        o.kd[tok0 + lane] = __builtin_amdgcn_exp2f(gC - g);
+        o.bp[tok0 + lane] = bp;
+        if (lane == 63) o.gamC[gc] = gam;
+    }
+    __syncthreads();
+    // the 10 lower tiles (a, b), b <= a, of K K^T and Q K^T: tile t of the list to wavefront t % 4
+    float* Ato = o.At + gc * (CB_C * CB_C);
+    float* Pmo = o.Pm + gc * (CB_C * CB_C);
+    float* Tmo = o.Tm + gc * (CB_C * CB_C);
+    f32x4 keepA[3];
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        const int t = w + 4 * s;   // uniform
+        keepA[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (t < 10) {
+            const int a = (0x3333222110 >> (4 * t)) & 15, b = (0x3210210100 >> (4 * t)) & 15;
+            f32x4 accK = {0.f, 0.f, 0.f, 0.f}, accQ = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+            for (int kt = 0; kt < D / 16; ++kt) {
+                const float4 bk = ld4(Ks + (16 * b + l16) * KS + 16 * kt + 4 * lq);
+                accK = mac16(ld4(Ks + (16 * a + l16) * KS + 16 * kt + 4 * lq), bk, accK);
+                accQ = mac16(ld4(Qs + (16 * a + l16) * KS + 16 * kt + 4 * lq), bk, accQ);
+            }
+            const int i = 16 * b + l16;
+            const float gi = s_g[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 16 * a + 4 * lq + j;
+                const float G = __builtin_amdgcn_exp2f(s_g[r] - gi);
+                const float at = (i < r && linear_op == 0) ? G * accK[j] : 0.f;
+                Ato[r * CB_C + i] = at;
+                Pmo[r * CB_C + i] = (i <= r) ? G * accQ[j] : 0.f;
+                keepA[s][j] = s_bp[r] * at;
+            }
+        }
+    }
+    // the 6 tiles above the diagonal are zeros (T's come out of the substitution below)
+    for (int z = w; z < 6; z += 4) {
+        const int a = (0x211000 >> (4 * z)) & 15, b = (0x332321 >> (4 * z)) & 15;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int off = (16 * a + 4 * lq + j) * CB_C + 16 * b + l16;
+            Ato[off] = 0.f;
+            Pmo[off] = 0.f;
+        }
+    }
+    __syncthreads();   // the Q tile is dead: its region takes diag(b') At
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        const int t = w + 4 * s;
+        if (t < 10) {
+            const int a = (0x3333222110 >> (4 * t)) & 15, b = (0x3210210100 >> (4 * t)) & 15;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) As[(16 * a + 4 * lq + j) * CB_MS + 16 * b + l16] = keepA[s][j];
+        }
+    }
+    __syncthreads();
+    // T = (I + A)^-1: lane j of wavefront 0 solves column j, T[r][j] = [r == j] - sum over i < r of A[r][i] T[i][j]
+    // (entries above the diagonal come out as exact zeros).  Wavefront a handles rows 16 a ..: it needs the rows
+    // before, so the wavefronts would only wait for each other; wavefront 0 does all of it.
+    if (w == 0) {
+        float col[CB_C];
+#pragma unroll
+        for (int r = 0; r < CB_C; ++r) {
+            float acc = 0.f;
+#pragma unroll
+            for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {
+                const float4 a4 = ld4(As + r * CB_MS + 4 * i4);
+                acc += a4.x * col[4 * i4];
+                if (4 * i4 + 1 < r) acc += a4.y * col[4 * i4 + 1];
+                if (4 * i4 + 2 < r) acc += a4.z * col[4 * i4 + 2];
+                if (4 * i4 + 3 < r) acc += a4.w * col[4 * i4 + 3];
+            }
+            col[r] = ((r == lane) ? 1.f : 0.f) - acc;
+        }
+#pragma unroll
+        for (int r = 0; r < CB_C; ++r) Tmo[r * CB_C + lane] = col[r];
+    }
+}
+
+// ---- the states along the sequence -------------------------------------------------------------------------------------
+// DIR 0: forwards, the state S^T [d_k][16] of the block's 16 value columns; leaves S0 of every chunk (ck), U and Uh.
+// DIR 1: backwards, the gradient of that state; leaves dS1 of every chunk (ck), dV, the block's share of dbeta and the
+// gradient of the initial state.  Wavefront w owns the chunk's tokens 16 w .. 16 w + 15 in everything that is one
+// row per token, and D / 64 of the state's 16 x 16 tiles.
+template <typename T>
+struct SeqArgs {
+    const T *K, *Q, *X;            // X: V (DIR 0) or dO (DIR 1), [BH][L][D]
+    ChunkOps o;
+    const uint8_t* mask;
+    const float* S_init;           // DIR 0: [BH][D][D] or NULL
+    float* ck;                     // [BH][L/64][D][D]
+    float *Ug, *Uh;                // [BH][L][D]: DIR 0 writes both, DIR 1 reads Uh
+    float *dV, *dbeta_part, *dS0;  // DIR 1
+    int L, BH;
+    float la_scale;
+    int delta;                     // 1: delta rule; 0: gated linear attention
+};
+
+template <typename T, int D, int DIR>
+__global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) {
+    constexpr int KS = D + 4, E = Vec16<T>::N, NP = CB_C * D / E / 256, KT = D / 64, MS = CB_MS;
+    extern __shared__ __align__(16) float cb_smem[];
+    float* Ks = cb_smem;
+    float* M1 = Ks + CB_C * KS;            // T
+    float* M2 = M1 + CB_C * MS;            // At (DIR 0), P (DIR 1)
+    float* St = M2 + CB_C * MS;            // state, [16 v][KS]
+    float* B0 = St + CB_NV * KS;           // [16 v][MS] each: operands with the tokens as contraction index
+    float* B1 = B0 + CB_NV * MS;
+    float* B2 = B1 + CB_NV * MS;
+    float* B3 = B2 + CB_NV * MS;
+    float* Qs = B3 + CB_NV * MS;           // DIR 1 only
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int bh = blockIdx.x % a.BH, slice = blockIdx.x / a.BH, v0 = CB_NV * slice;
+    const int L = a.L, n_chunks = L / CB_C;
+    const size_t n_tok = (size_t)a.BH * L;
+    const float delta = a.delta ? 1.f : 0.f;
+
+    // what the next chunk needs, fetched a chunk ahead into registers
+    float kreg[NP][E], qreg[DIR ? NP : 1][E];
+    float4 m1reg[4], m2reg[4], g4n, kd4n, bp4n;
+    float xvn[4], uhn[4] = {0.f, 0.f, 0.f, 0.f}, gCn;
+    uint32_t linn = 0;
+    // ... and of the chunk at hand
+    float4 g4, kd4, bp4;
+    float xv[4], uh[4], gC;
+    uint32_t lin = 0;
+
+    auto fetch = [&](int c) {
+        const size_t gc = (size_t)bh * n_chunks + c, tok0 = (size_t)bh * L + (size_t)c * CB_C;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int e = tid + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
+            Vec16<T>::load(a.K + (tok0 + row) * D + cc, kreg[i]);
+            if (DIR) Vec16<T>::load(a.Q + (tok0 + row) * D + cc, qreg[i]);
+        }
+        const float* m1 = a.o.Tm + gc * (CB_C * CB_C);
+        const float* m2 = (DIR ? a.o.Pm : a.o.At) + gc * (CB_C * CB_C);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m1reg[i] = ld4(m1 + 4 * (tid + 256 * i));
+            m2reg[i] = ld4(m2 + 4 * (tid + 256 * i));
+        }
+        const size_t t4 = tok0 + 16 * w + 4 * lq;
+        g4n = ld4(a.o.gam + t4);
+        kd4n = ld4(a.o.kd + t4);
+        bp4n = ld4(a.o.bp + t4);
+        gCn = a.o.gamC[gc];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            xvn[j] = to_float(a.X[(t4 + j) * D + v0 + l16]);
+            if (DIR) uhn[j] = a.Uh[(t4 + j) * D + v0 + l16];
+        }
+        if (DIR) linn = *reinterpret_cast<const uint32_t*>(a.mask + t4);
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int e = tid + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
+#pragma unroll
+            for (int j = 0; j < E; j += 4) {
+                *reinterpret_cast<float4*>(Ks + row * KS + cc + j) = make_float4(kreg[i][j], kreg[i][j + 1], kreg[i][j + 2], kreg[i][j + 3]);
+                if (DIR) *reinterpret_cast<float4*>(Qs + row * KS + cc + j) = make_float4(qreg[i][j], qreg[i][j + 1], qreg[i][j + 2], qreg[i][j + 3]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i, row = e / 16, c4 = (e % 16) * 4;
+            *reinterpret_cast<float4*>(M1 + row * MS + c4) = m1reg[i];
+            *reinterpret_cast<float4*>(M2 + row * MS + c4) = m2reg[i];
+        }
+        g4 = g4n; kd4 = kd4n; bp4 = bp4n; gC = gCn; lin = linn;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { xv[j] = xvn[j]; uh[j] = uhn[j]; }
+        if (DIR) {   // dO' and diag(gamma) dO' with the tokens as contraction index
+            const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
+            float4 x, y;
+            x.x = a.la_scale * xv[0]; x.y = a.la_scale * xv[1]; x.z = a.la_scale * xv[2]; x.w = a.la_scale * xv[3];
+            y.x = gg[0] * x.x; y.y = gg[1] * x.y; y.z = gg[2] * x.z; y.w = gg[3] * x.w;
+            *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = x;
+            *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = y;
+        }
+    };
+
+    // the state: tiles kt = KT w + t, element [k = 16 kt + 4 lq + j][v = l16]
+    f32x4 Sacc[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        const int kt = KT * w + t;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (DIR == 0 && a.S_init != nullptr) s = ld4(a.S_init + ((size_t)bh * D + v0 + l16) * D + 16 * kt + 4 * lq);
+        Sacc[t] = f32x4{s.x, s.y, s.z, s.w};
+        *reinterpret_cast<float4*>(St + l16 * KS + 16 * kt + 4 * lq) = s;
+    }
+    fetch(DIR ? n_chunks - 1 : 0);
+    commit();
+    __syncthreads();
+
+    for (int ci = 0; ci < n_chunks; ++ci) {
+        const int c = DIR ? n_chunks - 1 - ci : ci;
+        const size_t gc = (size_t)bh * n_chunks + c;
+        const size_t t4 = (size_t)bh * L + (size_t)c * CB_C + 16 * w + 4 * lq;   // the lane's first token
+        const float gg[4] = {g4.x, g4.y, g4.z, g4.w}, kk[4] = {kd4.x, kd4.y, kd4.z, kd4.w}, bb[4] = {bp4.x, bp4.y, bp4.z, bp4.w};
+        if (ci + 1 < n_chunks) fetch(DIR ? c - 1 : c + 1);
+        // ---- 1: the state seen by the wavefront's tokens: K_w S^T --------------------------------------------
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int kt = 0; kt < D / 16; ++kt)
+            acc = mac16(ld4(Ks + (16 * w + l16) * KS + 16 * kt + 4 * lq), ld4(St + l16 * KS + 16 * kt + 4 * lq), acc);
+        float R[4];
+        if (DIR == 0) {
+            float4 br;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) R[j] = xv[j] - delta * gg[j] * acc[j];
+            br.x = bb[0] * R[0]; br.y = bb[1] * R[1]; br.z = bb[2] * R[2]; br.w = bb[3] * R[3];
+            *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = br;
+        } else {
+            // dU = P^T dO' + diag(kd) K dS1^T: rows of P behind the wavefront's tokens
+            f32x4 accP = {0.f, 0.f, 0.f, 0.f};
+            for (int ta = w; ta < 4; ++ta)
+                accP = mac16(ld4col(M2 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B0 + l16 * MS + 16 * ta + 4 * lq), accP);
+            float4 du;
+            du.x = kk[0] * acc[0] + accP[0]; du.y = kk[1] * acc[1] + accP[1];
+            du.z = kk[2] * acc[2] + accP[2]; du.w = kk[3] * acc[3] + accP[3];
+            *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = du;
+        }
+        __syncthreads();
+        // ---- 2: through the inverse ------------------------------------------------------------------------
+        if (DIR == 0) {
+            f32x4 U = {0.f, 0.f, 0.f, 0.f};
+            for (int tb = 0; tb <= w; ++tb)
+                U = mac16(ld4(M1 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B0 + l16 * MS + 16 * tb + 4 * lq), U);
+            *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = make_float4(U[0], U[1], U[2], U[3]);
+            *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = make_float4(kk[0] * U[0], kk[1] * U[1], kk[2] * U[2], kk[3] * U[3]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a.Ug[(t4 + j) * D + v0 + l16] = U[j];
+        } else {
+            f32x4 Rt = {0.f, 0.f, 0.f, 0.f};
+            for (int ta = w; ta < 4; ++ta)
+                Rt = mac16(ld4col(M1 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B2 + l16 * MS + 16 * ta + 4 * lq), Rt);
+            float4 ng;
+            float dr[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                dr[j] = bb[j] * Rt[j];
+                a.dV[(t4 + j) * D + v0 + l16] = dr[j];
+                const float s = lane_group_sum<16>(uh[j] * Rt[j]);
+                if (l16 == 0) a.dbeta_part[(size_t)slice * n_tok + t4 + j] = ((lin >> (8 * j)) & 0xff) ? 0.f : s;
+            }
+            ng.x = -delta * gg[0] * dr[0]; ng.y = -delta * gg[1] * dr[1]; ng.z = -delta * gg[2] * dr[2]; ng.w = -delta * gg[3] * dr[3];
+            *reinterpret_cast<float4*>(B3 + l16 * MS + 16 * w + 4 * lq) = ng;
+        }
+        __syncthreads();
+        // ---- 3: the chunk's contribution to the state ------------------------------------------------------------
+        if (DIR == 0) {
+            f32x4 AU = {0.f, 0.f, 0.f, 0.f};
+            for (int tb = 0; tb <= w; ++tb)
+                AU = mac16(ld4(M2 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), AU);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a.Uh[(t4 + j) * D + v0 + l16] = R[j] - AU[j];
+        }
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            const int kt = KT * w + t;
+            *reinterpret_cast<float4*>(a.ck + (gc * D + v0 + l16) * D + 16 * kt + 4 * lq) =
+                make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+            f32x4 s = Sacc[t];
+            s[0] *= gC; s[1] *= gC; s[2] *= gC; s[3] *= gC;
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                if (DIR == 0) {
+                    s = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B2 + l16 * MS + 16 * tb + 4 * lq), s);
+                } else {
+                    s = mac16(ld4col(Qs + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), s);
+                    s = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B3 + l16 * MS + 16 * tb + 4 * lq), s);
+                }
+            }
+            Sacc[t] = s;
+        }
+        __syncthreads();   // every read of the chunk's operands and of the old state is done
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+            *reinterpret_cast<float4*>(St + l16 * KS + 16 * (KT * w + t) + 4 * lq) = make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+        if (ci + 1 < n_chunks) commit();
+        __syncthreads();
+    }
+    if (DIR == 1 && a.dS0 != nullptr) {
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+            *reinterpret_cast<float4*>(a.dS0 + ((size_t)bh * D + v0 + l16) * D + 16 * (KT * w + t) + 4 * lq) =
+                make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+    }
+}
+
+template <int D, int DIR>
+constexpr size_t seq_lds_bytes() {
+    return sizeof(float) * ((size_t)CB_C * (D + 4) * (DIR ? 2 : 1) + 2 * CB_C * CB_MS + CB_NV * (D + 4) + 4 * CB_NV * CB_MS);
+}
+template <int D>
+constexpr size_t prep_lds_bytes() { return sizeof(float) * (2 * (size_t)CB_C * (D + 4) + 2 * CB_C); }
+
+static ChunkOps chunk_ops(const FwdPlan& pl, float* base) {
+    const size_t n_tok = (size_t)pl.BH * pl.L, n_ch = n_tok / CB_C;
+    ChunkOps o;
+    o.Tm = base;
+    o.At = o.Tm + n_ch * CB_C * CB_C;
+    o.Pm = o.At + n_ch * CB_C * CB_C;
+    o.g2 = o.Pm + n_ch * CB_C * CB_C;
+    o.gam = o.g2 + n_tok;
+    o.kd = o.gam + n_tok;
+    o.bp = o.kd + n_tok;
+    o.gamC = o.bp + n_tok;
+    return o;
+}
+size_t chunk_ops_floats(const FwdPlan& pl) {
+    const size_t n_tok = (size_t)pl.BH * pl.L, n_ch = n_tok / CB_C;
+    return 3 * n_ch * CB_C * CB_C + 4 * n_tok + align_up(n_ch, 64);
+}
+
+template <typename T, int D>
+static bool launch_prep_t(const FwdPlan& pl, const void* Q, const void* K, const float* alpha, const float* beta,
+                          const uint8_t* mask, const ChunkOps& o, hipStream_t st) {
+    auto kern = gdn_bwd_prep_kernel<T, D>;
+    constexpr size_t lds = prep_lds_bytes<D>();
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+        hipSuccess) return false;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (pl.L / CB_C))), dim3(256), lds, st, (const T*)Q,
+                       (const T*)K, alpha, beta, mask, o, pl.L, pl.BH, pl.freeze_on_softmax, pl.linear_op);
+    return true;
+}
+
+// ops: chunk_ops_floats(pl) floats.  Routing per token.
+nats_status launch_gdn_bwd_prep(const FwdPlan& pl, const void* Q, const void* K, const float* alpha, const float* beta,
+                                const uint8_t* mask, float* ops, hipStream_t st) {
+    const ChunkOps o = chunk_ops(pl, ops);
+    bool ok;
+    if (pl.dtype == NATS_BF16) ok = pl.d == 64 ? launch_prep_t<bf16_t, 64>(pl, Q, K, alpha, beta, mask, o, st)
+                                               : launch_prep_t<bf16_t, 128>(pl, Q, K, alpha, beta, mask, o, st);
+    else ok = pl.d == 64 ? launch_prep_t<float, 64>(pl, Q, K, alpha, beta, mask, o, st)
+                         : launch_prep_t<float, 128>(pl, Q, K, alpha, beta, mask, o, st);
+    if (!ok) { set_error("gdn_bwd_prep: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
+    return check_launch("gdn_bwd_prep");
+}
+
+template <typename T, int D, int DIR>
+static bool launch_seq_t(const FwdPlan& pl, const SeqArgs<T>& a, hipStream_t st) {
+    auto kern = gdn_chunk_seq_kernel<T, D, DIR>;
+    constexpr size_t lds = seq_lds_bytes<D, DIR>();
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+        hipSuccess) return false;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (D / CB_NV))), dim3(256), lds, st, a);
+    return true;
+}
+template <typename T, int DIR>
+static bool launch_seq_d(const FwdPlan& pl, const SeqArgs<T>& a, hipStream_t st) {
+    return pl.d == 64 ? launch_seq_t<T, 64, DIR>(pl, a, st) : launch_seq_t<T, 128, DIR>(pl, a, st);
+}
+
+// The states at the chunk starts, ck [BH][L/64][d][d], with U and Uh [BH][L][d] of every chunk.
+nats_status launch_gdn_chunk_states(const FwdPlan& pl, const void* K, const void* V, float* ops, const float* S_init,
+                                    float* ck, float* Ug, float* Uh, hipStream_t st) {
+    bool ok;
+    if (pl.dtype == NATS_BF16) {
+        const SeqArgs<bf16_t> a{(const bf16_t*)K, nullptr, (const bf16_t*)V, chunk_ops(pl, ops), nullptr, S_init, ck, Ug, Uh,
+                                nullptr, nullptr, nullptr, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
+        ok = launch_seq_d<bf16_t, 0>(pl, a, st);
+    } else {
+        const SeqArgs<float> a{(const float*)K, nullptr, (const float*)V, chunk_ops(pl, ops), nullptr, S_init, ck, Ug, Uh,
+                               nullptr, nullptr, nullptr, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
+        ok = launch_seq_d<float, 0>(pl, a, st);
+    }
+    if (!ok) { set_error("gdn_chunk_states: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
+    return check_launch("gdn_chunk_states");
+}
+
+// The state gradients behind every chunk, dck [BH][L/64][d][d]; dV (every row), dbeta_part [d/16][BH][L], dS0 (or NULL).
+nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO,
+                                         const uint8_t* mask, float* ops, float* dck, float* Uh, float* dV,
+                                         float* dbeta_part, float* dS0, hipStream_t st) {
+    bool ok;
+    if (pl.dtype == NATS_BF16) {
+        const SeqArgs<bf16_t> a{(const bf16_t*)K, (const bf16_t*)Q, (const bf16_t*)dO, chunk_ops(pl, ops), mask, nullptr, dck,
+                                nullptr, Uh, dV, dbeta_part, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
+        ok = launch_seq_d<bf16_t, 1>(pl, a, st);
+    } else {
+        const SeqArgs<float> a{(const float*)K, (const float*)Q, (const float*)dO, chunk_ops(pl, ops), mask, nullptr, dck,
+                               nullptr, Uh, dV, dbeta_part, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
+        ok = launch_seq_d<float, 1>(pl, a, st);
+    }
+    if (!ok) { set_error("gdn_chunk_state_grads: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
+    return check_launch("gdn_chunk_state_grads");
+}
+
+}  // namespace nats

@@ -258,6 +258,15 @@ nats_status launch_gdn_recurrent_bwd(const FwdPlan& pl, const void* Q, const voi
                                      float* dbeta_part, float* dV, float* dS0, float* ds_la_part, hipStream_t st);
 nats_status launch_gdn_checkpoints(const FwdPlan& pl, const void* K, const void* V, const float* alpha, const float* beta,
                                    const uint8_t* mask, const float* S0, float* ckpt, hipStream_t st);
+// chunkwise backward of the linear branch (fp32 matrix instructions), routing per token
+size_t chunk_ops_floats(const FwdPlan& pl);
+nats_status launch_gdn_bwd_prep(const FwdPlan& pl, const void* Q, const void* K, const float* alpha, const float* beta,
+                                const uint8_t* mask, float* ops, hipStream_t st);
+nats_status launch_gdn_chunk_states(const FwdPlan& pl, const void* K, const void* V, float* ops, const float* S_init,
+                                    float* ck, float* Ug, float* Uh, hipStream_t st);
+nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO,
+                                         const uint8_t* mask, float* ops, float* dck, float* Uh, float* dV,
+                                         float* dbeta_part, float* dS0, hipStream_t st);
 nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st);
 nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                          const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
