@@ -294,10 +294,12 @@ def hybrid_attn_fwd_noalloc(Q, K, V, alpha, beta, mask, out, C: int = 64, *, sof
 
 def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
                     linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False, initial_state=None,
-                    want=(), workspace=None, routing: int = NATS_ROUTE_TOKEN) -> Dict[str, torch.Tensor]:
+                    want=(), workspace=None, routing: int = NATS_ROUTE_TOKEN,
+                    math: int = NATS_MATH_AUTO) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla given dO.  Returns dQ, dK, dV [B,H,L,d] f32, dalpha,
     dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla, g_la [B,H,L] (routing per token),
-    dscore_nla, dscore_la [B,H,L/C] (Eq. 16, Eq. 17)."""
+    dscore_nla, dscore_la [B,H,L/C] (Eq. 16, Eq. 17).  math = NATS_MATH_FP32: the linear branch's adjoint token by
+    token instead of by chunks."""
     lib = load_library()
     B, H, L, d = Q.shape
     dt = Q.dtype
@@ -310,7 +312,7 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
     unknown = set(want) - {"d_initial_state", "g_nla", "g_la", "dscore_nla", "dscore_la"}
     if unknown:
         raise ValueError(f"unknown outputs {sorted(unknown)}")
-    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, NATS_MATH_AUTO,
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, math,
                              routing, linear_op, freeze_on_softmax)
     need = int(lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(params)))
     if need == 0:   # let the library say what is wrong with the parameters

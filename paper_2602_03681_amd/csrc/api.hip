@@ -518,6 +518,8 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     float* ops = reinterpret_cast<float*>(ws + bp.off_ops);
     float* Ug = reinterpret_cast<float*>(ws + bp.off_ug);
     float* Uh = reinterpret_cast<float*>(ws + bp.off_uh);
+    float* dck = reinterpret_cast<float*>(ws + bp.off_dck);
+    const bool by_chunks = !chunk && pl.math != NATS_MATH_FP32;   // the linear branch's backward by chunks of 64 tokens
     if (!chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
         {
             ProfScope ps("gdn_bwd_prep", stream);
@@ -532,13 +534,25 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         st = launch_gdn_checkpoints(pl, K, V, alpha, beta, mask, ex.initial_state, ckpt, stream);
         if (st != NATS_OK) return st;
     }
-    {
-        ProfScope ps("gdn_recurrent_bwd", stream);
-        st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
-                                      ex.d_initial_state, dslap, stream);
+    if (by_chunks) {
+        {   // backwards along the sequence: the state gradient behind every chunk, dV, the partials of dbeta
+            ProfScope ps("gdn_chunk_state_grads", stream);
+            st = launch_gdn_chunk_state_grads(pl, Q, K, dO, mask, ops, dck, Uh, dV, dbp, ex.d_initial_state, stream);
+            if (st != NATS_OK) return st;
+        }
+        // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
+        ProfScope ps("gdn_chunk_grads", stream);
+        st = launch_gdn_chunk_grads(pl, Q, K, dO, alpha, mask, ops, ckpt, dck, Ug, dV, dbp, dQ, dK, dalpha, dbeta, ex.g_nla,
+                                    stream);
         if (st != NATS_OK) return st;
-    }
-    {   // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
+    } else {
+        {
+            ProfScope ps("gdn_recurrent_bwd", stream);
+            st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
+                                          ex.d_initial_state, dslap, stream);
+            if (st != NATS_OK) return st;
+        }
+        // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
         ProfScope ps("bwd_combine", stream);
         st = launch_bwd_combine(pl, dqp, dkp, dap, dbp, dQ, dK, dalpha, dbeta, ex.g_nla, stream);
         if (st != NATS_OK) return st;

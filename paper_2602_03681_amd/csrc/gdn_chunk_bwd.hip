@@ -394,6 +394,285 @@ __global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
     }
 }
 
+// ---- the gradients of a chunk -------------------------------------------------------------------------------------------
+// One block per (chunk, batch*head), d / 16 wavefronts; wavefront w owns the columns 16 w .. 16 w + 15 of dQ and dK
+// (all 64 rows: four accumulator tiles each) and of the three products with the states that feed them.  Three LDS
+// regions are filled in turn:   A: S0, then U with dS1 (64 rows at a time), then K with Q;   B: dO', then dP . Gamma;
+// C: dR, then the symmetric (dAt . Gamma) + (dAt . Gamma)^T.  Sums over rows, columns or wavefronts go through small
+// per-tile or per-wavefront arrays that one wavefront adds up in a fixed order (no atomics).
+template <typename T>
+struct GradArgs {
+    const T *Q, *K, *dO;
+    ChunkOps o;
+    const float *alpha;
+    const uint8_t* mask;
+    const float *ck, *dck, *Ug, *dR, *dbeta_part;
+    float *dQ, *dK, *dalpha, *dbeta, *g_nla;
+    int L, BH;
+    float la_scale;
+    int delta, freeze_on_softmax;
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T> a) {
+    constexpr int NW = D / 16, NT = 64 * NW, KS = D + 4, MS = CB_MS, E = Vec16<T>::N;
+    constexpr int HALF = CB_C * KS;            // floats of a [64][KS] tile
+    constexpr int NS0 = D * D / 4 / NT;        // 16-byte pieces of a state per thread
+    constexpr int NSH = 64 * D / 4 / NT;       // ... of 64 rows of it (or of a [64][D] fp32 tile)
+    extern __shared__ __align__(16) float cb_smem[];
+    float* RA = cb_smem;
+    float* RAhi = RA + HALF;
+    float* RB = RA + 2 * HALF;
+    float* RC = RB + HALF;
+    float* s_g2 = RC + HALF;
+    float* s_gam = s_g2 + CB_C;
+    float* s_kd = s_gam + CB_C;
+    float* rs = s_kd + CB_C;                   // [4 column tiles][64 rows]: row sums of dAt . At + dP . P per tile
+    float* cs = rs + 4 * CB_C;                 // [4 row tiles][64 columns]: column sums
+    float* gk = cs + 4 * CB_C;                 // [NW][64]: the state terms of d ln gamma, per wavefront's columns
+    float* ge = gk + NW * CB_C;                // [NW][64]: E_r likewise
+    float* s_dot = ge + NW * CB_C;             // [NW]: <dS1, S0>
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int n_chunks = a.L / CB_C;
+    const int bh = blockIdx.x % a.BH, chunk = blockIdx.x / a.BH;
+    const size_t gc = (size_t)bh * n_chunks + chunk, tok0 = (size_t)bh * a.L + (size_t)chunk * CB_C;
+    const float delta = a.delta ? 1.f : 0.f;
+
+    auto load_rows_f32 = [&](float* dst, const float* src) {   // [64][D] fp32, rows contiguous
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) {
+            const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+            *reinterpret_cast<float4*>(dst + row * KS + c4) = ld4(src + (size_t)row * D + c4);
+        }
+    };
+    auto load_rows_T = [&](float* dst, const T* src, float scale) {
+        constexpr int NPT = 64 * D / E / NT;
+#pragma unroll
+        for (int i = 0; i < NPT; ++i) {
+            const int e = tid + NT * i, row = e / (D / E), c = (e % (D / E)) * E;
+            float tmp[E];
+            Vec16<T>::load(src + (size_t)row * D + c, tmp);
+#pragma unroll
+            for (int j = 0; j < E; j += 4)
+                *reinterpret_cast<float4*>(dst + row * KS + c + j) = make_float4(scale * tmp[j], scale * tmp[j + 1], scale * tmp[j + 2], scale * tmp[j + 3]);
+        }
+    };
+
+    // ---- stage 1: S0, dO', dR ------------------------------------------------------------------------------
+    float4 s0reg[NS0];
+    {
+        const float* S0g = a.ck + gc * ((size_t)D * D);
+#pragma unroll
+        for (int i = 0; i < NS0; ++i) {
+            const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+            s0reg[i] = ld4(S0g + (size_t)row * D + c4);
+            *reinterpret_cast<float4*>(RA + row * KS + c4) = s0reg[i];
+        }
+    }
+    load_rows_T(RB, a.dO + tok0 * D, a.la_scale);
+    load_rows_f32(RC, a.dR + tok0 * D);
+    if (tid < CB_C) {
+        s_g2[tid] = a.o.g2[tok0 + tid];
+        s_gam[tid] = a.o.gam[tok0 + tid];
+        s_kd[tid] = a.o.kd[tok0 + tid];
+    }
+    for (int e = tid; e < 8 * CB_C; e += NT) rs[e] = 0.f;   // rs and cs
+    __syncthreads();
+    f32x4 Gdq[4], Gdk[4], Gu[4];
+#pragma unroll
+    for (int ta = 0; ta < 4; ++ta) {
+        Gdq[ta] = f32x4{0.f, 0.f, 0.f, 0.f};
+        Gdk[ta] = f32x4{0.f, 0.f, 0.f, 0.f};
+        Gu[ta] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll 2
+    for (int kv = 0; kv < D / 16; ++kv) {
+        const float4 bs = ld4col(RA + (16 * kv + 4 * lq) * KS + 16 * w + l16, KS);
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) {
+            Gdq[ta] = mac16(ld4(RB + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gdq[ta]);
+            Gdk[ta] = mac16(ld4(RC + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gdk[ta]);
+        }
+    }
+    __syncthreads();
+    // ---- stage 2: U and the first 64 rows of dS1; dP and dAt ---------------------------------------------------
+    float dot = 0.f;
+    const float* dS1g = a.dck + gc * ((size_t)D * D);
+    load_rows_f32(RA, a.Ug + tok0 * D);
+#pragma unroll
+    for (int i = 0; i < NSH; ++i) {
+        const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+        const float4 x = ld4(dS1g + (size_t)row * D + c4);
+        *reinterpret_cast<float4*>(RAhi + row * KS + c4) = x;
+        dot += x.x * s0reg[i].x + x.y * s0reg[i].y + x.z * s0reg[i].z + x.w * s0reg[i].w;
+    }
+    __syncthreads();
+#pragma unroll 2
+    for (int kv = 0; kv < 4; ++kv) {
+        const float4 bs = ld4col(RAhi + (16 * kv + 4 * lq) * KS + 16 * w + l16, KS);
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) Gu[ta] = mac16(ld4(RA + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gu[ta]);
+    }
+    constexpr int NTL = (10 + NW - 1) / NW;   // lower tiles per wavefront
+    f32x4 DPv[NTL], DAv[NTL];
+#pragma unroll
+    for (int s = 0; s < NTL; ++s) {
+        const int t = w + NW * s;   // uniform
+        if (t < 10) {
+            const int ta = (0x3333222110 >> (4 * t)) & 15, tb = (0x3210210100 >> (4 * t)) & 15;
+            f32x4 accP = {0.f, 0.f, 0.f, 0.f}, accA = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+            for (int kv = 0; kv < D / 16; ++kv) {
+                const float4 bu = ld4(RA + (16 * tb + l16) * KS + 16 * kv + 4 * lq);
+                accP = mac16(ld4(RB + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bu, accP);
+                accA = mac16(ld4(RC + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bu, accA);
+            }
+            const int i = 16 * tb + l16;
+            const float gi = s_g2[i];
+            const float* Atg = a.o.At + gc * (CB_C * CB_C);
+            const float* Pmg = a.o.Pm + gc * (CB_C * CB_C);
+            float csum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 16 * ta + 4 * lq + j;
+                const float G = __builtin_amdgcn_exp2f(s_g2[r] - gi);
+                const float dp = (i <= r) ? accP[j] : 0.f, da = (i < r) ? -delta * accA[j] : 0.f;   // no At without the delta rule
+                const float e = da * Atg[r * CB_C + i] + dp * Pmg[r * CB_C + i];
+                const float rsum = lane_group_sum<16>(e);
+                if (l16 == 0) rs[tb * CB_C + r] = rsum;
+                csum += e;
+                DPv[s][j] = dp * G;
+                DAv[s][j] = da * G;
+            }
+            csum += lane_xor16(csum, lane);
+            csum += lane_xor32(csum, lane);
+            if (lq == 0) cs[ta * CB_C + i] = csum;
+        }
+    }
+    __syncthreads();
+    // ---- stage 3: the two 64 x 64 operands take the places of dO' and dR; the rest of dS1 ------------------------
+#pragma unroll
+    for (int s = 0; s < NTL; ++s) {
+        const int t = w + NW * s;
+        if (t < 10) {
+            const int ta = (0x3333222110 >> (4 * t)) & 15, tb = (0x3210210100 >> (4 * t)) & 15;
+            const int i = 16 * tb + l16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 16 * ta + 4 * lq + j;
+                RB[r * MS + i] = DPv[s][j];
+                if (i < r) {
+                    RC[r * MS + i] = DAv[s][j];
+                    RC[i * MS + r] = DAv[s][j];
+                } else if (i == r) {
+                    RC[r * MS + i] = 0.f;
+                }
+            }
+        }
+    }
+    if (D > 64) {
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) {
+            const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+            const float4 x = ld4(dS1g + (size_t)(64 + row) * D + c4);
+            *reinterpret_cast<float4*>(RAhi + row * KS + c4) = x;
+            const float4 y = s0reg[(NS0 > NSH ? NSH : 0) + i];
+            dot += x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int kv = 4; kv < D / 16; ++kv) {
+            const float4 bs = ld4col(RAhi + (16 * (kv - 4) + 4 * lq) * KS + 16 * w + l16, KS);
+#pragma unroll
+            for (int ta = 0; ta < 4; ++ta) Gu[ta] = mac16(ld4(RA + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gu[ta]);
+        }
+    }
+    __syncthreads();
+    // ---- stage 4: K and Q ----------------------------------------------------------------------------------------
+    load_rows_T(RA, a.K + tok0 * D, 1.f);
+    load_rows_T(RAhi, a.Q + tok0 * D, 1.f);
+    {   // <dS1, S0>: the wavefront's sum
+        float x = lane_group_sum<64>(dot);
+        if (lane == 0) s_dot[w] = x;
+    }
+    __syncthreads();
+    f32x4 dQa[4], dKa[4];
+#pragma unroll
+    for (int ta = 0; ta < 4; ++ta) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 16 * ta + 4 * lq + j;
+            const float gam = s_gam[r], kd = s_kd[r];
+            const float qv = RAhi[r * KS + 16 * w + l16], kv = RA[r * KS + 16 * w + l16];
+            const float eu = kd * kv * Gu[ta][j];
+            const float x = gam * (qv * Gdq[ta][j] - delta * kv * Gdk[ta][j]) - eu;
+            const float xs = lane_group_sum<16>(x), es = lane_group_sum<16>(eu);
+            if (l16 == 0) { gk[w * CB_C + r] = xs; ge[w * CB_C + r] = es; }
+            dQa[ta][j] = gam * Gdq[ta][j];
+            dKa[ta][j] = kd * Gu[ta][j] - delta * gam * Gdk[ta][j];
+        }
+    }
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+        const float4 kc = ld4col(RA + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);     // K rows of tile tb, own columns
+        const float4 qc = ld4col(RAhi + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);   // Q likewise
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) {
+            if (tb <= ta) dQa[ta] = mac16(ld4(RB + (16 * ta + l16) * MS + 16 * tb + 4 * lq), kc, dQa[ta]);
+            dKa[ta] = mac16(ld4(RC + (16 * ta + l16) * MS + 16 * tb + 4 * lq), kc, dKa[ta]);
+            // (dP . Gamma)^T Q: rows tb of dP (as contraction index) against the columns of tile ta
+            if (tb >= ta) dKa[ta] = mac16(ld4col(RB + (16 * tb + 4 * lq) * MS + 16 * ta + l16, MS), qc, dKa[ta]);
+        }
+    }
+#pragma unroll
+    for (int ta = 0; ta < 4; ++ta) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t off = (tok0 + 16 * ta + 4 * lq + j) * D + 16 * w + l16;
+            a.dQ[off] += dQa[ta][j];   // the softmax branch's share is there already
+            a.dK[off] = dKa[ta][j];
+        }
+    }
+    __syncthreads();
+    // ---- the gates: d ln gamma of every token, its sum from the back, dalpha; dbeta ----------------------------
+    if (w == 0) {
+        const int r = 63 - lane;   // reversed, so that the inclusive scan below sums from the chunk's end
+        float dl = 0.f, et = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dl += rs[q * CB_C + r];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dl -= cs[q * CB_C + r];
+#pragma unroll
+        for (int q = 0; q < NW; ++q) { dl += gk[q * CB_C + r]; et += ge[q * CB_C + r]; }
+        et = lane_group_sum<64>(et);
+        float dt = 0.f;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) dt += s_dot[q];
+        if (r == 63) dl += et + a.o.gamC[gc] * dt;
+        dl += dpp_move<0x111>(dl);
+        dl += dpp_move<0x112>(dl);
+        dl += dpp_move<0x114>(dl);
+        dl += dpp_move<0x118>(dl);
+        dl += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dl), 0x142, 0xA, 0xF, false));
+        dl += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dl), 0x143, 0xC, 0xF, false));
+        const size_t t = tok0 + r;
+        const bool frozen = a.freeze_on_softmax && a.mask[t] != 0;   // its alpha counted as 1
+        a.dalpha[t] = frozen ? 0.f : dl / fmaxf(a.alpha[t], 1e-30f);
+        float db = 0.f;
+        const size_t n_tok = (size_t)a.BH * a.L;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) db += a.dbeta_part[(size_t)q * n_tok + t];
+        a.dbeta[t] = db;
+        if (a.g_nla != nullptr) a.g_nla[t] = 0.f;
+    }
+}
+
+template <int D>
+constexpr size_t grads_lds_bytes() {
+    return sizeof(float) * (4 * (size_t)CB_C * (D + 4) + 3 * CB_C + 8 * CB_C + 2 * (D / 16) * CB_C + 64);
+}
+
 template <int D, int DIR>
 constexpr size_t seq_lds_bytes() {
     return sizeof(float) * ((size_t)CB_C * (D + 4) * (DIR ? 2 : 1) + 2 * CB_C * CB_MS + CB_NV * (D + 4) + 4 * CB_NV * CB_MS);
@@ -491,6 +770,38 @@ nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const
     }
     if (!ok) { set_error("gdn_chunk_state_grads: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
     return check_launch("gdn_chunk_state_grads");
+}
+
+template <typename T, int D>
+static bool launch_grads_t(const FwdPlan& pl, const GradArgs<T>& a, hipStream_t st) {
+    auto kern = gdn_chunk_grads_kernel<T, D>;
+    constexpr size_t lds = grads_lds_bytes<D>();
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+        hipSuccess) return false;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (pl.L / CB_C))), dim3(D * 4), lds, st, a);
+    return true;
+}
+
+// dQ += the linear branch's share; dK, dalpha, dbeta = it; g_nla (optional) cleared.  ck, dck: the states and state
+// gradients per chunk; Ug, dR (= the linear branch's dV) [BH][L][d]; dbeta_part [d/16][BH][L].
+nats_status launch_gdn_chunk_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO, const float* alpha,
+                                   const uint8_t* mask, float* ops, const float* ck, const float* dck, const float* Ug,
+                                   const float* dR, const float* dbeta_part, float* dQ, float* dK, float* dalpha,
+                                   float* dbeta, float* g_nla, hipStream_t st) {
+    bool ok;
+    if (pl.dtype == NATS_BF16) {
+        const GradArgs<bf16_t> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)dO, chunk_ops(pl, ops), alpha, mask, ck, dck,
+                                 Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, pl.L, pl.BH, pl.la_scale,
+                                 pl.linear_op == 0, pl.freeze_on_softmax};
+        ok = pl.d == 64 ? launch_grads_t<bf16_t, 64>(pl, a, st) : launch_grads_t<bf16_t, 128>(pl, a, st);
+    } else {
+        const GradArgs<float> a{(const float*)Q, (const float*)K, (const float*)dO, chunk_ops(pl, ops), alpha, mask, ck, dck,
+                                Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, pl.L, pl.BH, pl.la_scale,
+                                pl.linear_op == 0, pl.freeze_on_softmax};
+        ok = pl.d == 64 ? launch_grads_t<float, 64>(pl, a, st) : launch_grads_t<float, 128>(pl, a, st);
+    }
+    if (!ok) { set_error("gdn_chunk_grads: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
+    return check_launch("gdn_chunk_grads");
 }
 
 }  // namespace nats

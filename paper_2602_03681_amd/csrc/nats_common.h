@@ -267,6 +267,10 @@ nats_status launch_gdn_chunk_states(const FwdPlan& pl, const void* K, const void
 nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO,
                                          const uint8_t* mask, float* ops, float* dck, float* Uh, float* dV,
                                          float* dbeta_part, float* dS0, hipStream_t st);
+nats_status launch_gdn_chunk_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO, const float* alpha,
+                                   const uint8_t* mask, float* ops, const float* ck, const float* dck, const float* Ug,
+                                   const float* dR, const float* dbeta_part, float* dQ, float* dK, float* dalpha,
+                                   float* dbeta, float* g_nla, hipStream_t st);
 nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st);
 nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                          const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
