@@ -1,6 +1,8 @@
 """GPU parity of the backward pass (Section 4.2; fp32-accurate gradients, routing per token, plain-sum merge) against
 the backward oracle, through the C ABI.  Every gradient tensor is held to max|err| / RMS(oracle) <= 1e-4 (the
-outputs are fp32 whatever the input dtype)."""
+outputs are fp32 whatever the input dtype).  With routing per token the linear branch's adjoint runs by chunks of 64
+tokens on fp32 matrix instructions (the default) or token by token (math = NATS_MATH_FP32): both are held to the
+same bar."""
 import numpy as np
 import pytest
 import torch
@@ -45,11 +47,12 @@ def check(r, ref, extra=()):
                                              ("f32", 1, 1, 64, 64, 0.5),
                                              # many key tiles, several query tiles per block share (MFMA dK / dV kernel)
                                              ("bf16", 1, 1, 2048, 128, 0.3), ("bf16", 2, 2, 1024, 64, 0.5)])
-def test_backward_matches_the_oracle(dtype, B, H, L, d, p):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_matches_the_oracle(dtype, B, H, L, d, p, math):
     x = make_fwd_inputs(B, H, L, d, dtype, p, seed=200 + L + d)
     dO = make_grad_output(B, H, L, d, dtype, seed=300 + L)
     S0 = (0.05 * np.random.default_rng(L).standard_normal((B, H, d, d))).astype(np.float32)
-    r = run_bwd(x, dO, dtype, S0=S0)
+    r = run_bwd(x, dO, dtype, S0=S0, math=math)
     ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, S0=S0)
     errs = check(r, ref, extra=(("d_initial_state", "dS0"), ("g_nla", "g_nla")))
     print(dtype, L, d, errs)
@@ -79,11 +82,12 @@ def test_score_gradients_per_token_and_per_chunk(dtype, B, H, L, d, p, ask):
 
 @pytest.mark.parametrize("linear_op,freeze", [(nb.NATS_LINEAR_GATED, False), (nb.NATS_LINEAR_GDN, True),
                                               (nb.NATS_LINEAR_GATED, True)])
-def test_backward_variants_and_scales(linear_op, freeze):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_variants_and_scales(linear_op, freeze, math):
     B, H, L, d = 1, 2, 256, 64
     x = make_fwd_inputs(B, H, L, d, "f32", 0.2, seed=410 + linear_op)
     dO = make_grad_output(B, H, L, d, "f32", seed=411)
-    r = run_bwd(x, dO, "f32", softmax_scale=0.3, la_scale=1.7, linear_op=linear_op, freeze_on_softmax=freeze)
+    r = run_bwd(x, dO, "f32", softmax_scale=0.3, la_scale=1.7, linear_op=linear_op, freeze_on_softmax=freeze, math=math)
     ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, softmax_scale=0.3, la_scale=1.7,
                          linear_op=linear_op, decay_on_softmax=not freeze)
     check(r, ref, extra=(("d_initial_state", "dS0"), ("g_nla", "g_nla")))
@@ -92,16 +96,36 @@ def test_backward_variants_and_scales(linear_op, freeze):
 
 
 @pytest.mark.parametrize("kind", ["all_softmax", "all_linear"])
-def test_backward_degenerate_masks(kind):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_degenerate_masks(kind, math):
     B, H, L, d = 1, 2, 192, 64
     x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=420)
     x["mask"][:] = 1 if kind == "all_softmax" else 0
     dO = make_grad_output(B, H, L, d, "f32", seed=421)
-    r = run_bwd(x, dO, "f32")
+    r = run_bwd(x, dO, "f32", math=math)
     ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO)
     check(r, ref, extra=(("g_nla", "g_nla"),) if kind == "all_softmax" else ())
     if kind == "all_linear":
         assert np.all(host(r["g_nla"]) == 0)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_backward_by_chunks_with_gates_at_their_ends(dtype, d):
+    """Write strengths of exactly 0 and 1 on linear tokens, strong and no decay inside one chunk: the chunkwise form
+    divides by no gate but alpha itself (dalpha comes through ln gamma)."""
+    B, H, L = 1, 2, 256
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.2, seed=440)
+    rng = np.random.default_rng(441)
+    x["beta"][..., ::7] = 0.0
+    x["beta"][..., 3::7] = 1.0
+    x["alpha"][..., ::5] = 1.0
+    x["alpha"][..., 2::11] = rng.uniform(0.01, 0.2, x["alpha"][..., 2::11].shape).astype(np.float32)
+    dO = make_grad_output(B, H, L, d, dtype, seed=442)
+    r = run_bwd(x, dO, dtype)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO)
+    check(r, ref, extra=(("d_initial_state", "dS0"), ("g_nla", "g_nla")))
+    lin0 = (x["mask"] == 0) & (x["beta"] == 0)
+    assert lin0.any() and np.any(host(r["dbeta"])[lin0] != 0)   # a linear token with beta = 0 still has a gradient for it
 
 
 def test_backward_is_deterministic_and_reuses_a_poisoned_workspace():
