@@ -147,8 +147,11 @@ def bench_decode(args):
 
 
 def bench_backward(args):
-    """Backward pass on workload 2's shapes (fp32 sums everywhere; for bf16 tensors the softmax branch's products run on the matrix cores; the recurrence's reverse sweep dominates): a step
-    is one nats_hybrid_attn_bwd call.  Roofline: plain fp32 vector arithmetic of the reverse sweep."""
+    """Backward pass on workload 2's shapes (bf16 tensors, fp32 gradients): a step is one nats_hybrid_attn_bwd call.
+    The linear branch's adjoint runs by chunks on fp32 matrix instructions (operands per chunk, states forwards,
+    state gradients backwards, then every chunk's gradients); the softmax branch's products run on fp16 / bf16 matrix
+    instructions with two-term fp16 weights.  Roofline: fp32 matrix peak for the chunk kernels, counted per chunk of
+    64 tokens with triangular products at 10 of 16 tiles."""
     import torch
 
     import paper_2602_03681_amd as nats
@@ -163,15 +166,16 @@ def bench_backward(args):
     Q, K, V = (g[k].to(torch.bfloat16) for k in ("Q", "K", "V"))
     dO = torch.from_numpy(make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 1)).to(dev).to(torch.bfloat16)
     import ctypes
-    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16)
+    math = nb.NATS_MATH_FP32 if args.backward_by_tokens else nb.NATS_MATH_AUTO
+    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, math=math)
     ws = torch.empty(int(nb.load_library().nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(prm))), dtype=torch.uint8,
                      device=dev)
 
     def step():
-        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws)
+        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math)
 
-    steps = max(1, min(args.steps, 5))
-    for _ in range(max(1, min(args.warmup, 2))):
+    steps = max(1, min(args.steps, 20))
+    for _ in range(max(1, min(args.warmup, 3))):
         step()
     torch.cuda.synchronize()
     nb.profile_begin(16 * steps)
@@ -182,18 +186,33 @@ def bench_backward(args):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     kern = nb.profile_end()
     n_tok = cfg.B * cfg.H * cfg.L
+    n_chunks, d = n_tok // 64, cfg.d
+    tri = 10.0 / 16.0   # tiles of a 64 x 64 triangular operand that are multiplied
+    sq, st = 2.0 * 64 * d * d, 2.0 * 64 * 64 * d   # a [64 x d] . [d x d] product, a [64 x 64] . [64 x d] one
+    flops = {   # per chunk
+        "gdn_bwd_prep": 2 * tri * st,                       # K K^T, Q K^T
+        "gdn_chunk_states": 2 * sq + 2 * tri * st,          # K S^T, the state update; T and At products
+        "gdn_chunk_state_grads": 3 * sq + 2 * tri * st,     # K dS^T, two state updates; P^T and T^T products
+        "gdn_chunk_grads": 3 * sq + 4 * tri * st + st,      # dO' S0, dR S0, U dS1; dP, dAt, (dP.G) K, (dP.G)^T Q; symmetric . K
+        # token by token: about 25 d_k flops per state row and token (re-run of the chunk, then the adjoint)
+        "gdn_recurrent_bwd": 25.0 * 64 * d * d,
+    }
     dom = max(kern, key=lambda k: kern[k]["total_ms"])
-    # reverse sweep: about 25 d_k flops per state row and token (re-run of the chunk, then the adjoint)
-    flops = 25.0 * n_tok * cfg.d * cfg.d
-    achieved = flops / (kern["gdn_recurrent_bwd"]["avg_ms"] * 1e-3) / 1e12
+    roofs = {}
+    for k, f in flops.items():
+        if k in kern:
+            ach = f * n_chunks / (kern[k]["avg_ms"] * 1e-3) / 1e12
+            roofs[k] = {"bound": "alu" if k == "gdn_recurrent_bwd" else "mfma", "achieved": round(ach, 3), "peak": 157.3,
+                        "unit": "TFLOP/s", "frac": round(ach / 157.3, 5), "avg_kernel_ms": round(kern[k]["avg_ms"], 4)}
+    lead = max(roofs, key=lambda k: roofs[k]["avg_kernel_ms"])
     out = {"metric": "hybrid_attn_bwd_tokens_per_s", "value": round(cfg.B * cfg.L / (ms * 1e-3), 1), "unit": "tokens/s",
            "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 gradients; recurrence in fp32, softmax-branch products on MFMA with two-term fp16 weights)"},
+           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 gradients; linear branch "
+                                  + ("token by token in fp32" if args.backward_by_tokens else "by chunks on fp32 MFMA")
+                                  + ", softmax-branch products on MFMA with two-term fp16 weights)"},
            "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,
-           "roofline": {"kernel": "gdn_recurrent_bwd", "bound": "alu", "achieved": round(achieved, 3), "peak": 157.3,
-                        "unit": "TFLOP/s", "frac": round(achieved / 157.3, 5), "traffic": None,
-                        "avg_kernel_ms": round(kern["gdn_recurrent_bwd"]["avg_ms"], 4)},
+           "roofline": dict(kernel=lead, traffic=None, **roofs[lead]), "kernel_rooflines": roofs,
            "cpu_baseline": None}
     print(json.dumps(out))
 
@@ -222,6 +241,8 @@ def main():
     ap.add_argument("--no-decode-line", action="store_true",
                     help="leave the short decode measurement out of the forward's JSON line")
     ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
+    ap.add_argument("--backward-by-tokens", action="store_true",
+                    help="with --backward: the linear branch's adjoint token by token (math = NATS_MATH_FP32)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")

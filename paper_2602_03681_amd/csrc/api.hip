@@ -182,7 +182,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 // the reverse sweep and the partial sums of its blocks.
 struct BwdPlan {
     size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp,
-        off_gnla, off_vis, off_dslap, off_ops, off_ug, off_uh, off_dck, total;
+        off_gnla, off_vis, off_dslap, off_ops, off_ug, off_uh, off_dck, off_vht, total;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -208,6 +208,7 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_ug = off;      off = align_up(off + n_tok * pl.d * 4, 256);
     bp->off_uh = off;      off = align_up(off + n_tok * pl.d * 4, 256);
     bp->off_dck = off;     off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
+    bp->off_vht = off;     off = align_up(off + n_tok * pl.d * 2, 256);   // fp16 V^T tiles of the compacted values (bf16 tensors)
     bp->total = off;
 }
 
@@ -492,12 +493,18 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     if (ex.dscore_nla != nullptr && ex.g_nla == nullptr) ex.g_nla = reinterpret_cast<float*>(ws + bp.off_gnla);
     float* dslap = (chunk && ex.dscore_la != nullptr) ? reinterpret_cast<float*>(ws + bp.off_dslap) : nullptr;
     ProfChain prof_chain;   // the kernels below follow each other on one stream
+    const bool mfma_stats = pl.dtype == NATS_BF16;   // the softmax branch's forward on the matrix cores
+    void* VhT = mfma_stats ? ws + bp.off_vht : nullptr;
     {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
         ProfScope ps("scan_compact", stream);
-        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, nullptr, stream);
+        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, VhT, stream);
         if (st != NATS_OK) return st;
     }
-    {
+    if (mfma_stats) {
+        ProfScope ps("flash_softmax", stream);
+        st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
+        if (st != NATS_OK) return st;
+    } else {
         ProfScope ps("softmax_fp32", stream);
         st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;

@@ -54,8 +54,10 @@ __device__ __forceinline__ float quad_max(float x) {
 // The epilogue reads the linear branch's output (fp16), merges (Section 4.1 sum, Eq. 21 or its ablation) and
 // stores O.
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
-template <int D, bool chunk_routing>
-__global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
+// STATS: what the backward pass needs from this branch's forward, to fp32 accuracy: the weights enter the second
+// product (and their sum) as the sum of two fp16 terms, and only O_nla_out (fp32) and lse_out are written; no merge.
+template <int D, bool chunk_routing, bool STATS>
+__global__ __launch_bounds__(FL_THREADS, STATS ? 1 : FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
         // below); the running maximum is raised only when the tile's maximum exceeds it by more than 2^8
         // (the weights then stay below 2^8, exact enough in fp16 and far from overflow), so rescaling of
         // the accumulators is rare and skipped by the whole wavefront.
-        half8 pf[FL_NQ][2];
+        half8 pf[FL_NQ][2], pr[FL_NQ][2];   // pr (STATS): what rounding to fp16 left of the weights
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
             if (!full_tile) {
@@ -311,6 +313,13 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                 const f32x4 lo = accS[nq][2 * s2], hi = accS[nq][2 * s2 + 1];   // weights <= 2^8: no clamp needed
                 pf[nq][s2] = half8{(half_t)lo[0], (half_t)lo[1], (half_t)lo[2], (half_t)lo[3],
                                    (half_t)hi[0], (half_t)hi[1], (half_t)hi[2], (half_t)hi[3]};
+                if (STATS) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        pr[nq][s2][j] = (half_t)(lo[j] - (float)pf[nq][s2][j]);
+                        pr[nq][s2][4 + j] = (half_t)(hi[j] - (float)pf[nq][s2][4 + j]);
+                    }
+                }
             }
         }
 
@@ -322,7 +331,10 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                 // the tile's columns were stored in contraction-slot order by the compaction kernel
                 const half8 fv = lds_read8(Vs + (16 * t + l16) * TS + 32 * s2 + 8 * lq);
 #pragma unroll
-                for (int nq = 0; nq < FL_NQ; ++nq) accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
+                for (int nq = 0; nq < FL_NQ; ++nq) {
+                    accO[nq][t] = mfma16(fv, pf[nq][s2], accO[nq][t]);
+                    if (STATS) accO[nq][t] = mfma16(fv, pr[nq][s2], accO[nq][t]);
+                }
             }
         // The sums of the weights come from the same products: a 16-row tile of ones above V^T puts, in
         // every accumulator row, the sum over the keys of the fp16 weights that multiply V.
@@ -332,20 +344,25 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-                for (int nq = 0; nq < FL_NQ; ++nq) accL[nq] = mfma16(ones, pf[nq][s2], accL[nq]);
+                for (int nq = 0; nq < FL_NQ; ++nq) {
+                    accL[nq] = mfma16(ones, pf[nq][s2], accL[nq]);
+                    if (STATS) accL[nq] = mfma16(ones, pr[nq][s2], accL[nq]);
+                }
         }
         // Issue order of this block: V^T fragments several reads ahead of the matrix instructions that take
         // them (the compiler's own order waits for every other read just before its use).
-        __builtin_amdgcn_sched_group_barrier(0x100, FL_VAHEAD, 0);
+        if (!STATS) {
+            __builtin_amdgcn_sched_group_barrier(0x100, FL_VAHEAD, 0);
 #pragma unroll
-        for (int i = 0; i < DT * 2; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int i = 0; i < DT * 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, FL_NQ, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
     }
     __syncthreads();   // tiles are dead: the region becomes the output staging
 
-    if (combine_mode == 0 && O_nla_out == nullptr) {
+    if (!STATS && combine_mode == 0 && O_nla_out == nullptr) {
         // The plain sum (no row statistics needed) and no fp32 copy asked for: the
         // normalised rows are staged as fp16, both 16-query groups of the wavefront at once, so that all LDS
         // writes, then all LDS reads, then all stores (16 bytes per lane, full rows) are in flight together.
@@ -404,8 +421,10 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
 #pragma unroll
         for (int pass = 0; pass < 16 / RPP; ++pass) {
             const int q = q0 + (wave * FL_NQ + nq) * 16 + pass * RPP + lane / LPR;
-            lah_all[nq][pass] =
-                *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
+            lah_all[nq][pass] = half4{0, 0, 0, 0};
+            if (!STATS)
+                lah_all[nq][pass] =
+                    *reinterpret_cast<const half4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 4 * (lane % LPR));
         }
 #pragma unroll
     for (int nq = 0; nq < FL_NQ; ++nq) {
@@ -429,6 +448,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
             const float4 x = *reinterpret_cast<const float4*>(Ow + row * OS + 4 * c4);
             const size_t off = (tokbase + (live ? q : 0)) * D + 4 * c4;
             if (O_nla_out != nullptr && live) *reinterpret_cast<float4*>(O_nla_out + off) = x;
+            if (STATS) continue;
             const half4 lah = lah_all[nq][pass];
             const float la0 = (float)lah[0], la1 = (float)lah[1], la2 = (float)lah[2], la3 = (float)lah[3];
             float4 xs = x;
@@ -468,19 +488,33 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
                       const void* O_la, const float* w_nla, const float* w_la, void* O,
                       float* O_nla_out, float* lse_out, hipStream_t st) {
     dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BHG + 7) & ~7)));
+    if (O == nullptr) {   // the backward pass's call: branch output and log-sum-exp only
+        if (pl.routing == NATS_ROUTE_CHUNK)
+            hipLaunchKernelGGL((flash_softmax_kernel<D, true, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                               (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
+                               nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
+                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+        else
+            hipLaunchKernelGGL((flash_softmax_kernel<D, false, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                               (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
+                               nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
+                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+        return;
+    }
     if (pl.routing == NATS_ROUTE_CHUNK)
-        hipLaunchKernelGGL((flash_softmax_kernel<D, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, true, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
     else
-        hipLaunchKernelGGL((flash_softmax_kernel<D, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, false, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
 }
 
-// reads O_la (fp16, the linear branch's rows), merges, writes O
+// reads O_la (fp16, the linear branch's rows), merges, writes O.  O = NULL: no merge, O_nla_out and lse_out (both
+// required then) to fp32 accuracy
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const void* K, const void* V, const int32_t* cnt, const void* O_la, const float* w_nla,
                                  const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st) {
