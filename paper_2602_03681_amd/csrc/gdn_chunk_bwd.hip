@@ -48,6 +48,18 @@ __device__ __forceinline__ f32x4 mac16(const float4 a, const float4 b, f32x4 c) 
     return c;
 }
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+// a 16-byte word of T as it came from memory -> floats (8 for bf16, 4 for fp32)
+__device__ __forceinline__ void unpack16(const u32x4 w, float (&out)[8], bf16_t) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        out[2 * q] = __uint_as_float(w[q] << 16);
+        out[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void unpack16(const u32x4 w, float (&out)[4], float) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) out[q] = __uint_as_float(w[q]);
+}
 // four elements of one column, rows r0 .. r0 + 3 (row stride rs)
 __device__ __forceinline__ float4 ld4col(const float* p, int rs) { return make_float4(p[0], p[rs], p[2 * rs], p[3 * rs]); }
 
@@ -198,8 +210,12 @@ struct SeqArgs {
     int delta;                     // 1: delta rule; 0: gated linear attention
 };
 
+// Eight wavefronts: four compute (as above), four only move the next chunk's operands from global memory to LDS.
+// A burst of loads of this size keeps a wavefront at the issue of its memory instructions for about as long as a
+// whole phase of the chunk's products takes, and there is one block per CU with nothing else to fill the time:
+// so the wavefronts that multiply issue no global loads at all.
 template <typename T, int D, int DIR>
-__global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) {
+__global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) {
     constexpr int KS = D + 4, E = Vec16<T>::N, NP = CB_C * D / E / 256, KT = D / 64, MS = CB_MS;
     extern __shared__ __align__(16) float cb_smem[];
     float* Ks = cb_smem;
@@ -210,81 +226,104 @@ __global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
     float* B1 = B0 + CB_NV * MS;
     float* B2 = B1 + CB_NV * MS;
     float* B3 = B2 + CB_NV * MS;
-    float* Qs = B3 + CB_NV * MS;           // DIR 1 only
-    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float* Xt = B3 + CB_NV * MS;           // [16 v][MS]: V (DIR 0) or Uh (DIR 1) of the block's columns, tokens along a row
+    float* Gt = Xt + CB_NV * MS;           // gam, kd, bp [64] each, then gamC, then (DIR 1) the chunk's 64 mask bytes
+    float* Qs = Gt + 4 * CB_C;             // DIR 1 only
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave >= 4;
+    const int w = wave & 3, lt = tid & 255;
     const int l16 = lane & 15, lq = lane >> 4;
     const int bh = blockIdx.x % a.BH, slice = blockIdx.x / a.BH, v0 = CB_NV * slice;
     const int L = a.L, n_chunks = L / CB_C;
     const size_t n_tok = (size_t)a.BH * L;
     const float delta = a.delta ? 1.f : 0.f;
 
-    // what the next chunk needs, fetched a chunk ahead into registers
-    float kreg[NP][E], qreg[DIR ? NP : 1][E];
-    float4 m1reg[4], m2reg[4], g4n, kd4n, bp4n;
-    float xvn[4], uhn[4] = {0.f, 0.f, 0.f, 0.f}, gCn;
+    // loader wavefronts: the next chunk's operands as they come from memory
+    u32x4 kreg[NP], qreg[DIR ? NP : 1];
+    float4 m1reg[4], m2reg[4], gate4 = make_float4(0.f, 0.f, 0.f, 0.f), g4n = gate4;
+    T xvn[4];
+    float uhn[4] = {0.f, 0.f, 0.f, 0.f}, gCn = 0.f;
     uint32_t linn = 0;
-    // ... and of the chunk at hand
-    float4 g4, kd4, bp4;
-    float xv[4], uh[4], gC;
-    uint32_t lin = 0;
-
     auto fetch = [&](int c) {
         const size_t gc = (size_t)bh * n_chunks + c, tok0 = (size_t)bh * L + (size_t)c * CB_C;
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int e = tid + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
-            Vec16<T>::load(a.K + (tok0 + row) * D + cc, kreg[i]);
-            if (DIR) Vec16<T>::load(a.Q + (tok0 + row) * D + cc, qreg[i]);
+        for (int i = 0; i < NP; ++i) {   // a chunk's rows are contiguous
+            kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[lt + 256 * i];
+            if (DIR) qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[lt + 256 * i];
         }
         const float* m1 = a.o.Tm + gc * (CB_C * CB_C);
         const float* m2 = (DIR ? a.o.Pm : a.o.At) + gc * (CB_C * CB_C);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            m1reg[i] = ld4(m1 + 4 * (tid + 256 * i));
-            m2reg[i] = ld4(m2 + 4 * (tid + 256 * i));
+            m1reg[i] = ld4(m1 + 4 * (lt + 256 * i));
+            m2reg[i] = ld4(m2 + 4 * (lt + 256 * i));
         }
+        if (lt < 48) gate4 = ld4((lt < 16 ? a.o.gam : lt < 32 ? a.o.kd : a.o.bp) + tok0 + 4 * (lt & 15));
+        if (lt == 48) gCn = a.o.gamC[gc];
+        if (DIR && lt >= 64 && lt < 80) linn = *reinterpret_cast<const uint32_t*>(a.mask + tok0 + 4 * (lt - 64));
         const size_t t4 = tok0 + 16 * w + 4 * lq;
-        g4n = ld4(a.o.gam + t4);
-        kd4n = ld4(a.o.kd + t4);
-        bp4n = ld4(a.o.bp + t4);
-        gCn = a.o.gamC[gc];
+        if (DIR) g4n = ld4(a.o.gam + t4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            xvn[j] = to_float(a.X[(t4 + j) * D + v0 + l16]);
+            xvn[j] = a.X[(t4 + j) * D + v0 + l16];
             if (DIR) uhn[j] = a.Uh[(t4 + j) * D + v0 + l16];
         }
-        if (DIR) linn = *reinterpret_cast<const uint32_t*>(a.mask + t4);
     };
     auto commit = [&]() {
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int e = tid + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
+            const int e = lt + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
+            float kf[E], qf[E];
+            unpack16(kreg[i], kf, T{});
+            if (DIR) unpack16(qreg[i], qf, T{});
 #pragma unroll
             for (int j = 0; j < E; j += 4) {
-                *reinterpret_cast<float4*>(Ks + row * KS + cc + j) = make_float4(kreg[i][j], kreg[i][j + 1], kreg[i][j + 2], kreg[i][j + 3]);
-                if (DIR) *reinterpret_cast<float4*>(Qs + row * KS + cc + j) = make_float4(qreg[i][j], qreg[i][j + 1], qreg[i][j + 2], qreg[i][j + 3]);
+                *reinterpret_cast<float4*>(Ks + row * KS + cc + j) = make_float4(kf[j], kf[j + 1], kf[j + 2], kf[j + 3]);
+                if (DIR) *reinterpret_cast<float4*>(Qs + row * KS + cc + j) = make_float4(qf[j], qf[j + 1], qf[j + 2], qf[j + 3]);
             }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int e = tid + 256 * i, row = e / 16, c4 = (e % 16) * 4;
+            const int e = lt + 256 * i, row = e / 16, c4 = (e % 16) * 4;
             *reinterpret_cast<float4*>(M1 + row * MS + c4) = m1reg[i];
             *reinterpret_cast<float4*>(M2 + row * MS + c4) = m2reg[i];
         }
-        g4 = g4n; kd4 = kd4n; bp4 = bp4n; gC = gCn; lin = linn;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { xv[j] = xvn[j]; uh[j] = uhn[j]; }
-        if (DIR) {   // dO' and diag(gamma) dO' with the tokens as contraction index
-            const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
+        if (lt < 48) *reinterpret_cast<float4*>(Gt + 4 * lt) = gate4;
+        if (lt == 48) Gt[3 * CB_C] = gCn;
+        if (DIR && lt >= 64 && lt < 80) reinterpret_cast<uint32_t*>(Gt + 3 * CB_C + 4)[lt - 64] = linn;
+        if (DIR == 0) {
+            *reinterpret_cast<float4*>(Xt + l16 * MS + 16 * w + 4 * lq) =
+                make_float4(to_float(xvn[0]), to_float(xvn[1]), to_float(xvn[2]), to_float(xvn[3]));
+        } else {   // Uh; dO' and diag(gamma) dO' with the tokens as contraction index
+            *reinterpret_cast<float4*>(Xt + l16 * MS + 16 * w + 4 * lq) = make_float4(uhn[0], uhn[1], uhn[2], uhn[3]);
             float4 x, y;
-            x.x = a.la_scale * xv[0]; x.y = a.la_scale * xv[1]; x.z = a.la_scale * xv[2]; x.w = a.la_scale * xv[3];
-            y.x = gg[0] * x.x; y.y = gg[1] * x.y; y.z = gg[2] * x.z; y.w = gg[3] * x.w;
+            x.x = a.la_scale * to_float(xvn[0]); x.y = a.la_scale * to_float(xvn[1]);
+            x.z = a.la_scale * to_float(xvn[2]); x.w = a.la_scale * to_float(xvn[3]);
+            y.x = g4n.x * x.x; y.y = g4n.y * x.y; y.z = g4n.z * x.z; y.w = g4n.w * x.w;
             *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = x;
             *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = y;
         }
     };
 
     // the state: tiles kt = KT w + t, element [k = 16 kt + 4 lq + j][v = l16]
+    // The two kinds of wavefront run loops of their own with the same number of barriers (a barrier counts
+    // arrivals, wherever in the code they come from): what one kind keeps in registers across a chunk then takes
+    // no registers from the other.
+    if (loader) {
+        fetch(DIR ? n_chunks - 1 : 0);
+        commit();
+        __syncthreads();
+        for (int ci = 0; ci < n_chunks; ++ci) {
+            const int c = DIR ? n_chunks - 1 - ci : ci;
+            if (ci + 1 < n_chunks) fetch(DIR ? c - 1 : c + 1);
+            __syncthreads();
+            __syncthreads();
+            __syncthreads();   // every read of the chunk's operands is done
+            if (ci + 1 < n_chunks) commit();
+            __syncthreads();
+        }
+        return;
+    }
     f32x4 Sacc[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
@@ -294,96 +333,110 @@ __global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
         Sacc[t] = f32x4{s.x, s.y, s.z, s.w};
         *reinterpret_cast<float4*>(St + l16 * KS + 16 * kt + 4 * lq) = s;
     }
-    fetch(DIR ? n_chunks - 1 : 0);
-    commit();
     __syncthreads();
 
     for (int ci = 0; ci < n_chunks; ++ci) {
         const int c = DIR ? n_chunks - 1 - ci : ci;
         const size_t gc = (size_t)bh * n_chunks + c;
         const size_t t4 = (size_t)bh * L + (size_t)c * CB_C + 16 * w + 4 * lq;   // the lane's first token
-        const float gg[4] = {g4.x, g4.y, g4.z, g4.w}, kk[4] = {kd4.x, kd4.y, kd4.z, kd4.w}, bb[4] = {bp4.x, bp4.y, bp4.z, bp4.w};
-        if (ci + 1 < n_chunks) fetch(DIR ? c - 1 : c + 1);
-        // ---- 1: the state seen by the wavefront's tokens: K_w S^T --------------------------------------------
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float gg[4], kk[4], bb[4], xv[4], R[4], gC = 0.f;
+        uint32_t lin = 0;
+        {
+            const float4 g4 = ld4(Gt + 16 * w + 4 * lq), kd4 = ld4(Gt + CB_C + 16 * w + 4 * lq);
+            const float4 bp4 = ld4(Gt + 2 * CB_C + 16 * w + 4 * lq), x4 = ld4(Xt + l16 * MS + 16 * w + 4 * lq);
+            gg[0] = g4.x; gg[1] = g4.y; gg[2] = g4.z; gg[3] = g4.w;
+            kk[0] = kd4.x; kk[1] = kd4.y; kk[2] = kd4.z; kk[3] = kd4.w;
+            bb[0] = bp4.x; bb[1] = bp4.y; bb[2] = bp4.z; bb[3] = bp4.w;
+            xv[0] = x4.x; xv[1] = x4.y; xv[2] = x4.z; xv[3] = x4.w;
+            gC = Gt[3 * CB_C];
+            if (DIR) lin = reinterpret_cast<const uint32_t*>(Gt + 3 * CB_C + 4)[4 * w + lq];
+            // ---- 1: the state seen by the wavefront's tokens: K_w S^T ----------------------------------------
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
-        for (int kt = 0; kt < D / 16; ++kt)
-            acc = mac16(ld4(Ks + (16 * w + l16) * KS + 16 * kt + 4 * lq), ld4(St + l16 * KS + 16 * kt + 4 * lq), acc);
-        float R[4];
-        if (DIR == 0) {
-            float4 br;
+            for (int kt = 0; kt < D / 16; ++kt)
+                acc = mac16(ld4(Ks + (16 * w + l16) * KS + 16 * kt + 4 * lq), ld4(St + l16 * KS + 16 * kt + 4 * lq), acc);
+            if (DIR == 0) {
+                float4 br;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) R[j] = xv[j] - delta * gg[j] * acc[j];
-            br.x = bb[0] * R[0]; br.y = bb[1] * R[1]; br.z = bb[2] * R[2]; br.w = bb[3] * R[3];
-            *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = br;
-        } else {
-            // dU = P^T dO' + diag(kd) K dS1^T: rows of P behind the wavefront's tokens
-            f32x4 accP = {0.f, 0.f, 0.f, 0.f};
-            for (int ta = w; ta < 4; ++ta)
-                accP = mac16(ld4col(M2 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B0 + l16 * MS + 16 * ta + 4 * lq), accP);
-            float4 du;
-            du.x = kk[0] * acc[0] + accP[0]; du.y = kk[1] * acc[1] + accP[1];
-            du.z = kk[2] * acc[2] + accP[2]; du.w = kk[3] * acc[3] + accP[3];
-            *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = du;
+                for (int j = 0; j < 4; ++j) R[j] = xv[j] - delta * gg[j] * acc[j];
+                br.x = bb[0] * R[0]; br.y = bb[1] * R[1]; br.z = bb[2] * R[2]; br.w = bb[3] * R[3];
+                *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = br;
+            } else {
+                // dU = P^T dO' + diag(kd) K dS1^T: rows of P behind the wavefront's tokens
+                f32x4 accP = {0.f, 0.f, 0.f, 0.f};
+                for (int ta = w; ta < 4; ++ta)
+                    accP = mac16(ld4col(M2 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B0 + l16 * MS + 16 * ta + 4 * lq), accP);
+                float4 du;
+                du.x = kk[0] * acc[0] + accP[0]; du.y = kk[1] * acc[1] + accP[1];
+                du.z = kk[2] * acc[2] + accP[2]; du.w = kk[3] * acc[3] + accP[3];
+                *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = du;
+            }
         }
         __syncthreads();
         // ---- 2: through the inverse ------------------------------------------------------------------------
-        if (DIR == 0) {
-            f32x4 U = {0.f, 0.f, 0.f, 0.f};
-            for (int tb = 0; tb <= w; ++tb)
-                U = mac16(ld4(M1 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B0 + l16 * MS + 16 * tb + 4 * lq), U);
-            *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = make_float4(U[0], U[1], U[2], U[3]);
-            *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = make_float4(kk[0] * U[0], kk[1] * U[1], kk[2] * U[2], kk[3] * U[3]);
+        {
+            if (DIR == 0) {
+                f32x4 U = {0.f, 0.f, 0.f, 0.f};
+                for (int tb = 0; tb <= w; ++tb)
+                    U = mac16(ld4(M1 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B0 + l16 * MS + 16 * tb + 4 * lq), U);
+                *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = make_float4(U[0], U[1], U[2], U[3]);
+                *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = make_float4(kk[0] * U[0], kk[1] * U[1], kk[2] * U[2], kk[3] * U[3]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a.Ug[(t4 + j) * D + v0 + l16] = U[j];
-        } else {
-            f32x4 Rt = {0.f, 0.f, 0.f, 0.f};
-            for (int ta = w; ta < 4; ++ta)
-                Rt = mac16(ld4col(M1 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B2 + l16 * MS + 16 * ta + 4 * lq), Rt);
-            float4 ng;
-            float dr[4];
+                for (int j = 0; j < 4; ++j) a.Ug[(t4 + j) * D + v0 + l16] = U[j];
+            } else {
+                f32x4 Rt = {0.f, 0.f, 0.f, 0.f};
+                for (int ta = w; ta < 4; ++ta)
+                    Rt = mac16(ld4col(M1 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B2 + l16 * MS + 16 * ta + 4 * lq), Rt);
+                float4 ng;
+                float dr[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                dr[j] = bb[j] * Rt[j];
-                a.dV[(t4 + j) * D + v0 + l16] = dr[j];
-                const float s = lane_group_sum<16>(uh[j] * Rt[j]);
-                if (l16 == 0) a.dbeta_part[(size_t)slice * n_tok + t4 + j] = ((lin >> (8 * j)) & 0xff) ? 0.f : s;
+                for (int j = 0; j < 4; ++j) {
+                    dr[j] = bb[j] * Rt[j];
+                    a.dV[(t4 + j) * D + v0 + l16] = dr[j];
+                    const float sdb = lane_group_sum<16>(xv[j] * Rt[j]);   // xv: Uh
+                    if (l16 == 0) a.dbeta_part[(size_t)slice * n_tok + t4 + j] = ((lin >> (8 * j)) & 0xff) ? 0.f : sdb;
+                }
+                ng.x = -delta * gg[0] * dr[0]; ng.y = -delta * gg[1] * dr[1]; ng.z = -delta * gg[2] * dr[2]; ng.w = -delta * gg[3] * dr[3];
+                *reinterpret_cast<float4*>(B3 + l16 * MS + 16 * w + 4 * lq) = ng;
             }
-            ng.x = -delta * gg[0] * dr[0]; ng.y = -delta * gg[1] * dr[1]; ng.z = -delta * gg[2] * dr[2]; ng.w = -delta * gg[3] * dr[3];
-            *reinterpret_cast<float4*>(B3 + l16 * MS + 16 * w + 4 * lq) = ng;
         }
         __syncthreads();
         // ---- 3: the chunk's contribution to the state ------------------------------------------------------------
-        if (DIR == 0) {
-            f32x4 AU = {0.f, 0.f, 0.f, 0.f};
-            for (int tb = 0; tb <= w; ++tb)
-                AU = mac16(ld4(M2 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), AU);
+        {
+            if (DIR == 0) {
+                f32x4 AU = {0.f, 0.f, 0.f, 0.f};
+                for (int tb = 0; tb <= w; ++tb)
+                    AU = mac16(ld4(M2 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), AU);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a.Uh[(t4 + j) * D + v0 + l16] = R[j] - AU[j];
-        }
+                for (int j = 0; j < 4; ++j) a.Uh[(t4 + j) * D + v0 + l16] = R[j] - AU[j];
+            }
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const int kt = KT * w + t;
-            *reinterpret_cast<float4*>(a.ck + (gc * D + v0 + l16) * D + 16 * kt + 4 * lq) =
-                make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
-            f32x4 s = Sacc[t];
-            s[0] *= gC; s[1] *= gC; s[2] *= gC; s[3] *= gC;
+            for (int t = 0; t < KT; ++t) {
+                const int kt = KT * w + t;
+                *reinterpret_cast<float4*>(a.ck + (gc * D + v0 + l16) * D + 16 * kt + 4 * lq) =
+                    make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+                Sacc[t][0] *= gC; Sacc[t][1] *= gC; Sacc[t][2] *= gC; Sacc[t][3] *= gC;
+            }
+#pragma unroll 2
+            for (int tb = 0; tb < 4; ++tb) {   // token tiles outside: their operands serve all of the wavefront's state tiles
+                const float4 b2 = ld4((DIR ? B1 : B2) + l16 * MS + 16 * tb + 4 * lq);
+                const float4 b3 = DIR ? ld4(B3 + l16 * MS + 16 * tb + 4 * lq) : b2;
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) {
-                if (DIR == 0) {
-                    s = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B2 + l16 * MS + 16 * tb + 4 * lq), s);
-                } else {
-                    s = mac16(ld4col(Qs + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), s);
-                    s = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), ld4(B3 + l16 * MS + 16 * tb + 4 * lq), s);
+                for (int t = 0; t < KT; ++t) {
+                    const int kt = KT * w + t;
+                    if (DIR == 0) {
+                        Sacc[t] = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
+                    } else {
+                        Sacc[t] = mac16(ld4col(Qs + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
+                        Sacc[t] = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b3, Sacc[t]);
+                    }
                 }
             }
-            Sacc[t] = s;
         }
         __syncthreads();   // every read of the chunk's operands and of the old state is done
 #pragma unroll
         for (int t = 0; t < KT; ++t)
             *reinterpret_cast<float4*>(St + l16 * KS + 16 * (KT * w + t) + 4 * lq) = make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
-        if (ci + 1 < n_chunks) commit();
         __syncthreads();
     }
     if (DIR == 1 && a.dS0 != nullptr) {
@@ -393,6 +446,14 @@ __global__ __launch_bounds__(256) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
                 make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
     }
 }
+
+template <int D, int DIR>
+constexpr size_t seq_lds_bytes() {
+    return sizeof(float) * ((size_t)CB_C * (D + 4) * (DIR ? 2 : 1) + 2 * CB_C * CB_MS + CB_NV * (D + 4) + 5 * CB_NV * CB_MS +
+                            4 * CB_C + 32);
+}
+template <int D>
+constexpr size_t prep_lds_bytes() { return sizeof(float) * (2 * (size_t)CB_C * (D + 4) + 2 * CB_C); }
 
 // ---- the gradients of a chunk -------------------------------------------------------------------------------------------
 // One block per (chunk, batch*head), d / 16 wavefronts; wavefront w owns the columns 16 w .. 16 w + 15 of dQ and dK
@@ -439,44 +500,61 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     const size_t gc = (size_t)bh * n_chunks + chunk, tok0 = (size_t)bh * a.L + (size_t)chunk * CB_C;
     const float delta = a.delta ? 1.f : 0.f;
 
-    auto load_rows_f32 = [&](float* dst, const float* src) {   // [64][D] fp32, rows contiguous
+    // Every global load of the block is issued here, in the order of use: the later stages' operands wait in
+    // registers (one block per CU: nothing else would hide their latency).
+    constexpr int NPT = 64 * D / E / NT;       // 16-byte words of a [64][D] tile of T per thread
+    auto put_rows_f32 = [&](float* dst, const float4 (&r)[NSH]) {   // [64][D] fp32 -> LDS rows of KS
 #pragma unroll
         for (int i = 0; i < NSH; ++i) {
             const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
-            *reinterpret_cast<float4*>(dst + row * KS + c4) = ld4(src + (size_t)row * D + c4);
+            *reinterpret_cast<float4*>(dst + row * KS + c4) = r[i];
         }
     };
-    auto load_rows_T = [&](float* dst, const T* src, float scale) {
-        constexpr int NPT = 64 * D / E / NT;
+    auto put_rows_T = [&](float* dst, const u32x4 (&r)[NPT], float scale) {
 #pragma unroll
         for (int i = 0; i < NPT; ++i) {
             const int e = tid + NT * i, row = e / (D / E), c = (e % (D / E)) * E;
             float tmp[E];
-            Vec16<T>::load(src + (size_t)row * D + c, tmp);
+            unpack16(r[i], tmp, T{});
 #pragma unroll
             for (int j = 0; j < E; j += 4)
                 *reinterpret_cast<float4*>(dst + row * KS + c + j) = make_float4(scale * tmp[j], scale * tmp[j + 1], scale * tmp[j + 2], scale * tmp[j + 3]);
         }
     };
-
-    // ---- stage 1: S0, dO', dR ------------------------------------------------------------------------------
-    float4 s0reg[NS0];
+    float4 s0reg[NS0], dRreg[NSH], Ureg[NSH], dS1a[NSH], dS1b[NSH];
+    u32x4 dOreg[NPT], Kreg[NPT], Qreg[NPT];
+    const float* dS1g = a.dck + gc * ((size_t)D * D);
+    float gate_in = 0.f;   // threads 0..191: one of g2, gam, kd of the chunk's tokens
+    if (tid < 3 * CB_C) gate_in = (tid < CB_C ? a.o.g2 : tid < 2 * CB_C ? a.o.gam : a.o.kd)[tok0 + (tid & 63)];
     {
         const float* S0g = a.ck + gc * ((size_t)D * D);
 #pragma unroll
-        for (int i = 0; i < NS0; ++i) {
-            const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
-            s0reg[i] = ld4(S0g + (size_t)row * D + c4);
-            *reinterpret_cast<float4*>(RA + row * KS + c4) = s0reg[i];
+        for (int i = 0; i < NS0; ++i) s0reg[i] = ld4(S0g + 4 * (size_t)(tid + NT * i));   // rows of D floats: contiguous
+#pragma unroll
+        for (int i = 0; i < NPT; ++i) dOreg[i] = reinterpret_cast<const u32x4*>(a.dO + tok0 * D)[tid + NT * i];
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) dRreg[i] = ld4(a.dR + tok0 * D + 4 * (size_t)(tid + NT * i));
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) Ureg[i] = ld4(a.Ug + tok0 * D + 4 * (size_t)(tid + NT * i));
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) dS1a[i] = ld4(dS1g + 4 * (size_t)(tid + NT * i));
+#pragma unroll
+        for (int i = 0; i < NSH; ++i) dS1b[i] = (D > 64) ? ld4(dS1g + (size_t)64 * D + 4 * (size_t)(tid + NT * i)) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < NPT; ++i) {
+            Kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[tid + NT * i];
+            Qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[tid + NT * i];
         }
     }
-    load_rows_T(RB, a.dO + tok0 * D, a.la_scale);
-    load_rows_f32(RC, a.dR + tok0 * D);
-    if (tid < CB_C) {
-        s_g2[tid] = a.o.g2[tok0 + tid];
-        s_gam[tid] = a.o.gam[tok0 + tid];
-        s_kd[tid] = a.o.kd[tok0 + tid];
+    // ---- stage 1: S0, dO', dR ------------------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < NS0; ++i) {
+        const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+        *reinterpret_cast<float4*>(RA + row * KS + c4) = s0reg[i];
     }
+    put_rows_T(RB, dOreg, a.la_scale);
+    put_rows_f32(RC, dRreg);
+    if (tid < 3 * CB_C) s_g2[tid] = gate_in;   // s_g2, s_gam, s_kd lie one behind the other
     for (int e = tid; e < 8 * CB_C; e += NT) rs[e] = 0.f;   // rs and cs
     __syncthreads();
     f32x4 Gdq[4], Gdk[4], Gu[4];
@@ -498,15 +576,11 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     __syncthreads();
     // ---- stage 2: U and the first 64 rows of dS1; dP and dAt ---------------------------------------------------
     float dot = 0.f;
-    const float* dS1g = a.dck + gc * ((size_t)D * D);
-    load_rows_f32(RA, a.Ug + tok0 * D);
+    put_rows_f32(RA, Ureg);
+    put_rows_f32(RAhi, dS1a);
 #pragma unroll
-    for (int i = 0; i < NSH; ++i) {
-        const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
-        const float4 x = ld4(dS1g + (size_t)row * D + c4);
-        *reinterpret_cast<float4*>(RAhi + row * KS + c4) = x;
-        dot += x.x * s0reg[i].x + x.y * s0reg[i].y + x.z * s0reg[i].z + x.w * s0reg[i].w;
-    }
+    for (int i = 0; i < NSH; ++i)
+        dot += dS1a[i].x * s0reg[i].x + dS1a[i].y * s0reg[i].y + dS1a[i].z * s0reg[i].z + dS1a[i].w * s0reg[i].w;
     __syncthreads();
 #pragma unroll 2
     for (int kv = 0; kv < 4; ++kv) {
@@ -572,12 +646,10 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         }
     }
     if (D > 64) {
+        put_rows_f32(RAhi, dS1b);
 #pragma unroll
         for (int i = 0; i < NSH; ++i) {
-            const int e = tid + NT * i, row = e / (D / 4), c4 = (e % (D / 4)) * 4;
-            const float4 x = ld4(dS1g + (size_t)(64 + row) * D + c4);
-            *reinterpret_cast<float4*>(RAhi + row * KS + c4) = x;
-            const float4 y = s0reg[(NS0 > NSH ? NSH : 0) + i];
+            const float4 x = dS1b[i], y = s0reg[(NS0 > NSH ? NSH : 0) + i];
             dot += x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
         }
         __syncthreads();
@@ -590,8 +662,8 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     }
     __syncthreads();
     // ---- stage 4: K and Q ----------------------------------------------------------------------------------------
-    load_rows_T(RA, a.K + tok0 * D, 1.f);
-    load_rows_T(RAhi, a.Q + tok0 * D, 1.f);
+    put_rows_T(RA, Kreg, 1.f);
+    put_rows_T(RAhi, Qreg, 1.f);
     {   // <dS1, S0>: the wavefront's sum
         float x = lane_group_sum<64>(dot);
         if (lane == 0) s_dot[w] = x;
@@ -673,12 +745,6 @@ constexpr size_t grads_lds_bytes() {
     return sizeof(float) * (4 * (size_t)CB_C * (D + 4) + 3 * CB_C + 8 * CB_C + 2 * (D / 16) * CB_C + 64);
 }
 
-template <int D, int DIR>
-constexpr size_t seq_lds_bytes() {
-    return sizeof(float) * ((size_t)CB_C * (D + 4) * (DIR ? 2 : 1) + 2 * CB_C * CB_MS + CB_NV * (D + 4) + 4 * CB_NV * CB_MS);
-}
-template <int D>
-constexpr size_t prep_lds_bytes() { return sizeof(float) * (2 * (size_t)CB_C * (D + 4) + 2 * CB_C); }
 
 static ChunkOps chunk_ops(const FwdPlan& pl, float* base) {
     const size_t n_tok = (size_t)pl.BH * pl.L, n_ch = n_tok / CB_C;
@@ -729,7 +795,7 @@ static bool launch_seq_t(const FwdPlan& pl, const SeqArgs<T>& a, hipStream_t st)
     constexpr size_t lds = seq_lds_bytes<D, DIR>();
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
         hipSuccess) return false;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (D / CB_NV))), dim3(256), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (D / CB_NV))), dim3(512), lds, st, a);
     return true;
 }
 template <typename T, int DIR>
