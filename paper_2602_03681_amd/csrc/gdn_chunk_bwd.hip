@@ -491,7 +491,7 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     float* rs = s_kd + CB_C;                   // [4 column tiles][64 rows]: row sums of dAt . At + dP . P per tile
     float* cs = rs + 4 * CB_C;                 // [4 row tiles][64 columns]: column sums
     float* gk = cs + 4 * CB_C;                 // [NW][64]: the state terms of d ln gamma, per wavefront's columns
-    float* ge = gk + NW * CB_C;                // [NW][64]: E_r likewise
+    float* ge = gk + NW * CB_C;                // [NW]: the sum of E_r over the chunk, likewise
     float* s_dot = ge + NW * CB_C;             // [NW]: <dS1, S0>
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lq = lane >> 4;
@@ -524,6 +524,8 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     float4 s0reg[NS0], dRreg[NSH], Ureg[NSH], dS1a[NSH], dS1b[NSH];
     u32x4 dOreg[NPT], Kreg[NPT], Qreg[NPT];
     const float* dS1g = a.dck + gc * ((size_t)D * D);
+    constexpr int NTL = (10 + NW - 1) / NW;   // lower 16 x 16 tiles of a 64 x 64 operand per wavefront
+    float atv[NTL][4], pmv[NTL][4];           // At and P where this lane will hold dAt and dP
     float gate_in = 0.f;   // threads 0..191: one of g2, gam, kd of the chunk's tokens
     if (tid < 3 * CB_C) gate_in = (tid < CB_C ? a.o.g2 : tid < 2 * CB_C ? a.o.gam : a.o.kd)[tok0 + (tid & 63)];
     {
@@ -544,6 +546,17 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         for (int i = 0; i < NPT; ++i) {
             Kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[tid + NT * i];
             Qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[tid + NT * i];
+        }
+#pragma unroll
+        for (int s = 0; s < NTL; ++s) {
+            const int t = w + NW * s < 10 ? w + NW * s : 0;
+            const int ta = (0x3333222110 >> (4 * t)) & 15, tb = (0x3210210100 >> (4 * t)) & 15;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const size_t off = gc * (CB_C * CB_C) + (16 * ta + 4 * lq + j) * CB_C + 16 * tb + l16;
+                atv[s][j] = a.o.At[off];
+                pmv[s][j] = a.o.Pm[off];
+            }
         }
     }
     // ---- stage 1: S0, dO', dR ------------------------------------------------------------------------------
@@ -588,7 +601,6 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta) Gu[ta] = mac16(ld4(RA + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gu[ta]);
     }
-    constexpr int NTL = (10 + NW - 1) / NW;   // lower tiles per wavefront
     f32x4 DPv[NTL], DAv[NTL];
 #pragma unroll
     for (int s = 0; s < NTL; ++s) {
@@ -604,15 +616,13 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
             }
             const int i = 16 * tb + l16;
             const float gi = s_g2[i];
-            const float* Atg = a.o.At + gc * (CB_C * CB_C);
-            const float* Pmg = a.o.Pm + gc * (CB_C * CB_C);
             float csum = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = 16 * ta + 4 * lq + j;
                 const float G = __builtin_amdgcn_exp2f(s_g2[r] - gi);
                 const float dp = (i <= r) ? accP[j] : 0.f, da = (i < r) ? -delta * accA[j] : 0.f;   // no At without the delta rule
-                const float e = da * Atg[r * CB_C + i] + dp * Pmg[r * CB_C + i];
+                const float e = da * atv[s][j] + dp * pmv[s][j];
                 const float rsum = lane_group_sum<16>(e);
                 if (l16 == 0) rs[tb * CB_C + r] = rsum;
                 csum += e;
@@ -670,25 +680,34 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     }
     __syncthreads();
     f32x4 dQa[4], dKa[4];
+    float4 kcs[4], qcs[4];   // K and Q: rows 4 lq + j of every token tile, the wavefront's own columns
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+        kcs[tb] = ld4col(RA + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);
+        qcs[tb] = ld4col(RAhi + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);
+    }
+    float esum = 0.f;   // E_r is needed only as its sum over the chunk
 #pragma unroll
     for (int ta = 0; ta < 4; ++ta) {
+        const float kq[4] = {kcs[ta].x, kcs[ta].y, kcs[ta].z, kcs[ta].w}, qq[4] = {qcs[ta].x, qcs[ta].y, qcs[ta].z, qcs[ta].w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = 16 * ta + 4 * lq + j;
             const float gam = s_gam[r], kd = s_kd[r];
-            const float qv = RAhi[r * KS + 16 * w + l16], kv = RA[r * KS + 16 * w + l16];
-            const float eu = kd * kv * Gu[ta][j];
-            const float x = gam * (qv * Gdq[ta][j] - delta * kv * Gdk[ta][j]) - eu;
-            const float xs = lane_group_sum<16>(x), es = lane_group_sum<16>(eu);
-            if (l16 == 0) { gk[w * CB_C + r] = xs; ge[w * CB_C + r] = es; }
+            const float eu = kd * kq[j] * Gu[ta][j];
+            const float x = gam * (qq[j] * Gdq[ta][j] - delta * kq[j] * Gdk[ta][j]) - eu;
+            const float xs = lane_group_sum<16>(x);
+            esum += eu;
+            if (l16 == 0) gk[w * CB_C + r] = xs;
             dQa[ta][j] = gam * Gdq[ta][j];
             dKa[ta][j] = kd * Gu[ta][j] - delta * gam * Gdk[ta][j];
         }
     }
+    esum = lane_group_sum<64>(esum);
+    if (lane == 0) ge[w] = esum;
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
-        const float4 kc = ld4col(RA + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);     // K rows of tile tb, own columns
-        const float4 qc = ld4col(RAhi + (16 * tb + 4 * lq) * KS + 16 * w + l16, KS);   // Q likewise
+        const float4 kc = kcs[tb], qc = qcs[tb];
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta) {
             if (tb <= ta) dQa[ta] = mac16(ld4(RB + (16 * ta + l16) * MS + 16 * tb + 4 * lq), kc, dQa[ta]);
@@ -716,8 +735,7 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
 #pragma unroll
         for (int q = 0; q < 4; ++q) dl -= cs[q * CB_C + r];
 #pragma unroll
-        for (int q = 0; q < NW; ++q) { dl += gk[q * CB_C + r]; et += ge[q * CB_C + r]; }
-        et = lane_group_sum<64>(et);
+        for (int q = 0; q < NW; ++q) { dl += gk[q * CB_C + r]; et += ge[q]; }
         float dt = 0.f;
 #pragma unroll
         for (int q = 0; q < NW; ++q) dt += s_dot[q];
