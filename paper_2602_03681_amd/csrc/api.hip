@@ -191,10 +191,13 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_lse = off;     off = align_up(off + n_tok * 4, 256);
     bp->off_dvec = off;    off = align_up(off + n_tok * 4, 256);
     bp->off_ckpt = off;    off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
-    bp->off_scratch = off; off = align_up(off + (size_t)pl.BH * pl.d * 64 * pl.d * 4, 256);   // 64 tokens of every row
-    bp->off_dqp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
-    bp->off_dkp = off;     off = align_up(off + ns * n_tok * pl.d * 4, 256);
-    bp->off_dap = off;     off = align_up(off + ns * n_tok * 4, 256);
+    // the token-by-token adjoint of the linear branch (routing per chunk, or math = NATS_MATH_FP32): the parked rows
+    // of a chunk and the d/16 partial sums per (batch, head); by chunks only the partials of dbeta are used
+    const size_t tk = (pl.routing == NATS_ROUTE_CHUNK || pl.math == NATS_MATH_FP32) ? 1 : 0;
+    bp->off_scratch = off; off = align_up(off + tk * pl.BH * pl.d * 64 * pl.d * 4, 256);   // 64 tokens of every row
+    bp->off_dqp = off;     off = align_up(off + tk * ns * n_tok * pl.d * 4, 256);
+    bp->off_dkp = off;     off = align_up(off + tk * ns * n_tok * pl.d * 4, 256);
+    bp->off_dap = off;     off = align_up(off + tk * ns * n_tok * 4, 256);
     bp->off_dbp = off;     off = align_up(off + ns * n_tok * 4, 256);
     // partial dK, dV and column sums of the softmax branch, one per query segment and compacted key
     bp->off_skp = off;     off = align_up(off + (size_t)BWD_DKV_SEGMENTS * n_tok * pl.d * 4, 256);
@@ -204,10 +207,11 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_vis = off;     off = align_up(off + n_tok * 4, 256);   // routing per chunk: compacted rows visible to a query
     bp->off_dslap = off;   off = align_up(off + ns * (n_tok / 64) * 4, 256);   // ... and the sweep's partials of Eq. 17
     // chunkwise backward of the linear branch: operands of every chunk, U and the residuals, state gradients per chunk
-    bp->off_ops = off;     off = align_up(off + chunk_ops_floats(pl) * 4, 256);
-    bp->off_ug = off;      off = align_up(off + n_tok * pl.d * 4, 256);
-    bp->off_uh = off;      off = align_up(off + n_tok * pl.d * 4, 256);
-    bp->off_dck = off;     off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
+    const size_t ch = pl.routing == NATS_ROUTE_CHUNK ? 0 : 1;
+    bp->off_ops = off;     off = align_up(off + ch * chunk_ops_floats(pl) * 4, 256);
+    bp->off_ug = off;      off = align_up(off + ch * n_tok * pl.d * 4, 256);
+    bp->off_uh = off;      off = align_up(off + ch * n_tok * pl.d * 4, 256);
+    bp->off_dck = off;     off = align_up(off + ch * (1 - tk) * pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
     bp->off_vht = off;     off = align_up(off + n_tok * pl.d * 2, 256);   // fp16 V^T tiles of the compacted values (bf16 tensors)
     bp->total = off;
 }
