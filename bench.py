@@ -167,12 +167,18 @@ def bench_backward(args):
     dO = torch.from_numpy(make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 1)).to(dev).to(torch.bfloat16)
     import ctypes
     math = nb.NATS_MATH_FP32 if args.backward_by_tokens else nb.NATS_MATH_AUTO
-    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, math=math)
+    routing = nb.NATS_ROUTE_CHUNK if args.routing == "chunk" else nb.NATS_ROUTE_TOKEN
+    if routing == nb.NATS_ROUTE_CHUNK:   # same shapes and softmax share, one routing decision per chunk of 64 tokens
+        from nats_inputs import make_chunk_mask
+        mask_c = make_chunk_mask(cfg.B, cfg.H, cfg.L // cfg.C, cfg.p_softmax, cfg.seed + 1)
+        mask_c[:, :, 0] = 1
+        g["mask"] = torch.from_numpy(mask_c).to(dev)
+    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, math=math, routing=routing)
     ws = torch.empty(int(nb.load_library().nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(prm))), dtype=torch.uint8,
                      device=dev)
 
     def step():
-        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math)
+        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math, routing=routing)
 
     steps = max(1, min(args.steps, 20))
     for _ in range(max(1, min(args.warmup, 3))):
@@ -208,7 +214,8 @@ def bench_backward(args):
     out = {"metric": "hybrid_attn_bwd_tokens_per_s", "value": round(cfg.B * cfg.L / (ms * 1e-3), 1), "unit": "tokens/s",
            "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "backward of cfg2_headline_bf16 (bf16 tensors, fp32 gradients; linear branch "
+           "config": {"workload": "backward of cfg2_headline_bf16" + (", routing per chunk" if args.routing == "chunk" else "")
+                                  + " (bf16 tensors, fp32 gradients; linear branch "
                                   + ("token by token in fp32" if args.backward_by_tokens else "by chunks on fp32 MFMA")
                                   + ", softmax-branch products on MFMA with two-term fp16 weights)"},
            "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,

@@ -237,11 +237,11 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  *             With routing per chunk the function differentiated is the one the
  *             forward computes there: both operations compute every chunk's inner part, the masks act between
  *             chunks, a softmax chunk hands on (its decay) x (the state at its start).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.
- *             p->math: with routing per token and NATS_MATH_AUTO the linear branch's adjoint runs by chunks of 64
+ *             p->math: with NATS_MATH_AUTO the linear branch's adjoint runs by chunks of 64
  *             tokens on fp32 matrix instructions (the chunk form of Eq. 19 / 20 and its derivative; the states
  *             at the chunk starts, then the state gradients behind every chunk, then all chunks in parallel);
  *             dalpha then comes through the logarithms of the decays and needs alpha > 0 (an alpha of exactly 0
- *             gets dalpha = 0).  NATS_MATH_FP32, and routing per chunk, take the adjoint token by token.
+ *             gets dalpha = 0).  NATS_MATH_FP32 takes the adjoint token by token (the workspace is larger).
  *             For bf16 tensors the softmax branch's dQ, dK, dV products run on the matrix cores: Q, K, V, dO
  *             enter exactly (they are bf16), the probabilities and dS enter as the sum of two fp16 terms,
  *             so the gradients keep fp32-level accuracy; for f32 tensors those products are fp32 too

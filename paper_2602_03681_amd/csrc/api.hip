@@ -191,9 +191,9 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_lse = off;     off = align_up(off + n_tok * 4, 256);
     bp->off_dvec = off;    off = align_up(off + n_tok * 4, 256);
     bp->off_ckpt = off;    off = align_up(off + (size_t)pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
-    // the token-by-token adjoint of the linear branch (routing per chunk, or math = NATS_MATH_FP32): the parked rows
-    // of a chunk and the d/16 partial sums per (batch, head); by chunks only the partials of dbeta are used
-    const size_t tk = (pl.routing == NATS_ROUTE_CHUNK || pl.math == NATS_MATH_FP32) ? 1 : 0;
+    // the token-by-token adjoint of the linear branch (math = NATS_MATH_FP32): the parked rows of a chunk and the
+    // d/16 partial sums per (batch, head); by chunks only the partials of dbeta are used
+    const size_t tk = pl.math == NATS_MATH_FP32 ? 1 : 0;
     bp->off_scratch = off; off = align_up(off + tk * pl.BH * pl.d * 64 * pl.d * 4, 256);   // 64 tokens of every row
     bp->off_dqp = off;     off = align_up(off + tk * ns * n_tok * pl.d * 4, 256);
     bp->off_dkp = off;     off = align_up(off + tk * ns * n_tok * pl.d * 4, 256);
@@ -207,7 +207,7 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_vis = off;     off = align_up(off + n_tok * 4, 256);   // routing per chunk: compacted rows visible to a query
     bp->off_dslap = off;   off = align_up(off + ns * (n_tok / 64) * 4, 256);   // ... and the sweep's partials of Eq. 17
     // chunkwise backward of the linear branch: operands of every chunk, U and the residuals, state gradients per chunk
-    const size_t ch = pl.routing == NATS_ROUTE_CHUNK ? 0 : 1;
+    const size_t ch = (pl.routing == NATS_ROUTE_CHUNK && tk) ? 0 : 1;   // (token by token with routing per chunk: own checkpoint kernel)
     bp->off_ops = off;     off = align_up(off + ch * chunk_ops_floats(pl) * 4, 256);
     bp->off_ug = off;      off = align_up(off + ch * n_tok * pl.d * 4, 256);
     bp->off_uh = off;      off = align_up(off + ch * n_tok * pl.d * 4, 256);
@@ -495,7 +495,9 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         return NATS_ERR_UNSUPPORTED;
     }
     if (ex.dscore_nla != nullptr && ex.g_nla == nullptr) ex.g_nla = reinterpret_cast<float*>(ws + bp.off_gnla);
-    float* dslap = (chunk && ex.dscore_la != nullptr) ? reinterpret_cast<float*>(ws + bp.off_dslap) : nullptr;
+    // routing per chunk, token by token: the sweep's partials of Eq. 17 (by chunks the gradient kernel writes dscore_la)
+    float* dslap = (chunk && ex.dscore_la != nullptr && pl.math == NATS_MATH_FP32)
+                       ? reinterpret_cast<float*>(ws + bp.off_dslap) : nullptr;
     ProfChain prof_chain;   // the kernels below follow each other on one stream
     const bool mfma_stats = pl.dtype == NATS_BF16;   // the softmax branch's forward on the matrix cores
     void* VhT = mfma_stats ? ws + bp.off_vht : nullptr;
@@ -530,8 +532,8 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     float* Ug = reinterpret_cast<float*>(ws + bp.off_ug);
     float* Uh = reinterpret_cast<float*>(ws + bp.off_uh);
     float* dck = reinterpret_cast<float*>(ws + bp.off_dck);
-    const bool by_chunks = !chunk && pl.math != NATS_MATH_FP32;   // the linear branch's backward by chunks of 64 tokens
-    if (!chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
+    const bool by_chunks = pl.math != NATS_MATH_FP32;   // the linear branch's backward by chunks of 64 tokens
+    if (by_chunks || !chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
         {
             ProfScope ps("gdn_bwd_prep", stream);
             st = launch_gdn_bwd_prep(pl, Q, K, alpha, beta, mask, ops, stream);
@@ -554,7 +556,7 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
         ProfScope ps("gdn_chunk_grads", stream);
         st = launch_gdn_chunk_grads(pl, Q, K, dO, alpha, mask, ops, ckpt, dck, Ug, dV, dbp, dQ, dK, dalpha, dbeta, ex.g_nla,
-                                    stream);
+                                    chunk ? ex.dscore_la : nullptr, stream);
         if (st != NATS_OK) return st;
     } else {
         {

@@ -70,7 +70,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__ Q, const T* __restrict__ K,
                                                            const float* __restrict__ alpha, const float* __restrict__ beta,
                                                            const uint8_t* __restrict__ mask, const ChunkOps o, const int L,
-                                                           const int BH, const int freeze_on_softmax, const int linear_op) {
+                                                           const int BH, const int freeze_on_softmax, const int linear_op,
+                                                           const int chunk_mask) {
     constexpr int KS = D + 4, E = Vec16<T>::N, NP = CB_C * D / E / 256;
     extern __shared__ __align__(16) float cb_smem[];
     float* Ks = cb_smem;
@@ -95,7 +96,12 @@ __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__
         for (int j = 0; j < E; j += 4) *reinterpret_cast<float4*>(Qs + row * KS + c + j) = make_float4(tmp[j], tmp[j + 1], tmp[j + 2], tmp[j + 3]);
     }
     if (w == 0) {
-        const bool soft = mask[tok0 + lane] != 0;
+        // Routing per token: a softmax token writes nothing (b' = 0) and, in the variant without decay there, its
+        // alpha counts as 1.  Routing per chunk (mask: one byte per chunk): every token writes inside its chunk, and
+        // a softmax chunk hands on only (its decay) x (the state at its start): kd = 0, and the carried decay is 1
+        // in the variant without decay (inside the chunk the decays still act on the provisional state).
+        const bool soft = !chunk_mask && mask[tok0 + lane] != 0;
+        const bool soft_chunk = chunk_mask && mask[gc] != 0;
         const float a = (freeze_on_softmax && soft) ? 1.f : alpha[tok0 + lane];
         float g = __builtin_amdgcn_logf(fmaxf(a, 1e-30f));   // log2; inclusive scan over the 64 lanes
         g += dpp_move<0x111>(g);
@@ -111,9 +117,9 @@ __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__
         s_bp[lane] = bp;
         o.g2[tok0 + lane] = g;
         o.gam[tok0 + lane] = gam;
-        o.kd[tok0 + lane] = __builtin_amdgcn_exp2f(gC - g);
+        o.kd[tok0 + lane] = soft_chunk ? 0.f : __builtin_amdgcn_exp2f(gC - g);
         o.bp[tok0 + lane] = bp;
-        if (lane == 63) o.gamC[gc] = gam;
+        if (lane == 63) o.gamC[gc] = (freeze_on_softmax && soft_chunk) ? 1.f : gam;
     }
     __syncthreads();
     // the 10 lower tiles (a, b), b <= a, of K K^T and Q K^T: tile t of the list to wavefront t % 4
@@ -260,7 +266,8 @@ __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
         }
         if (lt < 48) gate4 = ld4((lt < 16 ? a.o.gam : lt < 32 ? a.o.kd : a.o.bp) + tok0 + 4 * (lt & 15));
         if (lt == 48) gCn = a.o.gamC[gc];
-        if (DIR && lt >= 64 && lt < 80) linn = *reinterpret_cast<const uint32_t*>(a.mask + tok0 + 4 * (lt - 64));
+        if (DIR && a.mask != nullptr && lt >= 64 && lt < 80)   // NULL: routing per chunk, every token of a chunk writes
+            linn = *reinterpret_cast<const uint32_t*>(a.mask + tok0 + 4 * (lt - 64));
         const size_t t4 = tok0 + 16 * w + 4 * lq;
         if (DIR) g4n = ld4(a.o.gam + t4);
 #pragma unroll
@@ -469,9 +476,10 @@ struct GradArgs {
     const uint8_t* mask;
     const float *ck, *dck, *Ug, *dR, *dbeta_part;
     float *dQ, *dK, *dalpha, *dbeta, *g_nla;
+    float* dscore_la;   // optional, routing per chunk: Eq. 17 per chunk
     int L, BH;
     float la_scale;
-    int delta, freeze_on_softmax;
+    int delta, freeze_on_softmax, chunk_mask;
 };
 
 template <typename T, int D>
@@ -739,7 +747,12 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         float dt = 0.f;
 #pragma unroll
         for (int q = 0; q < NW; ++q) dt += s_dot[q];
-        if (r == 63) dl += et + a.o.gamC[gc] * dt;
+        // the decay carried over the chunk: not a function of the alphas for a softmax chunk in the variant without decay
+        const bool carry_fixed = a.chunk_mask && a.freeze_on_softmax && a.mask[gc] != 0;
+        if (r == 63) dl += et + (carry_fixed ? 0.f : a.o.gamC[gc] * dt);
+        // Eq. 17 for a chunk: <dS1, what the chunk added to the carried state> = sum_i kd_i K_i . (U dS1)_i (kd = 0 for
+        // a softmax chunk)
+        if (lane == 0 && a.dscore_la != nullptr) a.dscore_la[gc] = et;
         dl += dpp_move<0x111>(dl);
         dl += dpp_move<0x112>(dl);
         dl += dpp_move<0x114>(dl);
@@ -747,7 +760,7 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         dl += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dl), 0x142, 0xA, 0xF, false));
         dl += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(dl), 0x143, 0xC, 0xF, false));
         const size_t t = tok0 + r;
-        const bool frozen = a.freeze_on_softmax && a.mask[t] != 0;   // its alpha counted as 1
+        const bool frozen = a.freeze_on_softmax && !a.chunk_mask && a.mask[t] != 0;   // its alpha counted as 1
         a.dalpha[t] = frozen ? 0.f : dl / fmaxf(a.alpha[t], 1e-30f);
         float db = 0.f;
         const size_t n_tok = (size_t)a.BH * a.L;
@@ -790,11 +803,12 @@ static bool launch_prep_t(const FwdPlan& pl, const void* Q, const void* K, const
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
         hipSuccess) return false;
     hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (pl.L / CB_C))), dim3(256), lds, st, (const T*)Q,
-                       (const T*)K, alpha, beta, mask, o, pl.L, pl.BH, pl.freeze_on_softmax, pl.linear_op);
+                       (const T*)K, alpha, beta, mask, o, pl.L, pl.BH, pl.freeze_on_softmax, pl.linear_op,
+                       pl.routing == NATS_ROUTE_CHUNK);
     return true;
 }
 
-// ops: chunk_ops_floats(pl) floats.  Routing per token.
+// ops: chunk_ops_floats(pl) floats.  Either routing.
 nats_status launch_gdn_bwd_prep(const FwdPlan& pl, const void* Q, const void* K, const float* alpha, const float* beta,
                                 const uint8_t* mask, float* ops, hipStream_t st) {
     const ChunkOps o = chunk_ops(pl, ops);
@@ -842,13 +856,14 @@ nats_status launch_gdn_chunk_states(const FwdPlan& pl, const void* K, const void
 nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO,
                                          const uint8_t* mask, float* ops, float* dck, float* Uh, float* dV,
                                          float* dbeta_part, float* dS0, hipStream_t st) {
+    const uint8_t* tok_mask = pl.routing == NATS_ROUTE_CHUNK ? nullptr : mask;
     bool ok;
     if (pl.dtype == NATS_BF16) {
-        const SeqArgs<bf16_t> a{(const bf16_t*)K, (const bf16_t*)Q, (const bf16_t*)dO, chunk_ops(pl, ops), mask, nullptr, dck,
+        const SeqArgs<bf16_t> a{(const bf16_t*)K, (const bf16_t*)Q, (const bf16_t*)dO, chunk_ops(pl, ops), tok_mask, nullptr, dck,
                                 nullptr, Uh, dV, dbeta_part, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
         ok = launch_seq_d<bf16_t, 1>(pl, a, st);
     } else {
-        const SeqArgs<float> a{(const float*)K, (const float*)Q, (const float*)dO, chunk_ops(pl, ops), mask, nullptr, dck,
+        const SeqArgs<float> a{(const float*)K, (const float*)Q, (const float*)dO, chunk_ops(pl, ops), tok_mask, nullptr, dck,
                                nullptr, Uh, dV, dbeta_part, dS0, pl.L, pl.BH, pl.la_scale, pl.linear_op == 0};
         ok = launch_seq_d<float, 1>(pl, a, st);
     }
@@ -871,17 +886,17 @@ static bool launch_grads_t(const FwdPlan& pl, const GradArgs<T>& a, hipStream_t 
 nats_status launch_gdn_chunk_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO, const float* alpha,
                                    const uint8_t* mask, float* ops, const float* ck, const float* dck, const float* Ug,
                                    const float* dR, const float* dbeta_part, float* dQ, float* dK, float* dalpha,
-                                   float* dbeta, float* g_nla, hipStream_t st) {
+                                   float* dbeta, float* g_nla, float* dscore_la, hipStream_t st) {
     bool ok;
     if (pl.dtype == NATS_BF16) {
         const GradArgs<bf16_t> a{(const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)dO, chunk_ops(pl, ops), alpha, mask, ck, dck,
-                                 Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, pl.L, pl.BH, pl.la_scale,
-                                 pl.linear_op == 0, pl.freeze_on_softmax};
+                                 Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, dscore_la, pl.L, pl.BH, pl.la_scale,
+                                 pl.linear_op == 0, pl.freeze_on_softmax, pl.routing == NATS_ROUTE_CHUNK};
         ok = pl.d == 64 ? launch_grads_t<bf16_t, 64>(pl, a, st) : launch_grads_t<bf16_t, 128>(pl, a, st);
     } else {
         const GradArgs<float> a{(const float*)Q, (const float*)K, (const float*)dO, chunk_ops(pl, ops), alpha, mask, ck, dck,
-                                Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, pl.L, pl.BH, pl.la_scale,
-                                pl.linear_op == 0, pl.freeze_on_softmax};
+                                Ug, dR, dbeta_part, dQ, dK, dalpha, dbeta, g_nla, dscore_la, pl.L, pl.BH, pl.la_scale,
+                                pl.linear_op == 0, pl.freeze_on_softmax, pl.routing == NATS_ROUTE_CHUNK};
         ok = pl.d == 64 ? launch_grads_t<float, 64>(pl, a, st) : launch_grads_t<float, 128>(pl, a, st);
     }
     if (!ok) { set_error("gdn_chunk_grads: the kernel's LDS size was refused"); return NATS_ERR_HIP; }

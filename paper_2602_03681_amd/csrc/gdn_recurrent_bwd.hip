@@ -590,7 +590,7 @@ __global__ __launch_bounds__(64) void score_gradients_chunk_kernel(const float* 
         const float s = lane_group_sum<64>(g_nla[(size_t)blockIdx.y * L + (size_t)blockIdx.x * 64 + threadIdx.x]);
         if (threadIdx.x == 0) dscore_nla[c] = s;
     }
-    if (dscore_la != nullptr && threadIdx.x == 0) {
+    if (dscore_la != nullptr && ds_la_part != nullptr && threadIdx.x == 0) {
         float s = 0.f;
         for (int p = 0; p < n_part; ++p) s += ds_la_part[(size_t)p * n_chunks_all + c];
         dscore_la[c] = s;

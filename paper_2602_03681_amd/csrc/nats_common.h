@@ -270,13 +270,13 @@ nats_status launch_gdn_chunk_state_grads(const FwdPlan& pl, const void* Q, const
 nats_status launch_gdn_chunk_grads(const FwdPlan& pl, const void* Q, const void* K, const void* dO, const float* alpha,
                                    const uint8_t* mask, float* ops, const float* ck, const float* dck, const float* Ug,
                                    const float* dR, const float* dbeta_part, float* dQ, float* dK, float* dalpha,
-                                   float* dbeta, float* g_nla, hipStream_t st);
+                                   float* dbeta, float* g_nla, float* dscore_la, hipStream_t st);
 nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st);
 nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                          const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
                                          hipStream_t st);
 nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
-                                         float* dscore_la, hipStream_t st);
+                                         float* dscore_la, hipStream_t st);   // ds_la_part NULL: dscore_la is left as it is
 nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,
                                    const float* g_nla, float* g_la, float* dscore_nla, float* dscore_la, hipStream_t st);
 nats_status launch_bwd_combine(const FwdPlan& pl, const float* dq_part, const float* dk_part, const float* dalpha_part,

@@ -1,8 +1,8 @@
 """GPU parity of the backward pass (Section 4.2; fp32-accurate gradients, routing per token, plain-sum merge) against
 the backward oracle, through the C ABI.  Every gradient tensor is held to max|err| / RMS(oracle) <= 1e-4 (the
-outputs are fp32 whatever the input dtype).  With routing per token the linear branch's adjoint runs by chunks of 64
-tokens on fp32 matrix instructions (the default) or token by token (math = NATS_MATH_FP32): both are held to the
-same bar."""
+outputs are fp32 whatever the input dtype).  The linear branch's adjoint runs by chunks of 64
+tokens on fp32 matrix instructions (the default) or token by token (math = NATS_MATH_FP32), with either routing: both
+are held to the same bar."""
 import numpy as np
 import pytest
 import torch
@@ -149,12 +149,14 @@ CHUNK_KEYS = (("d_initial_state", "dS0"), ("dscore_nla", "dscore_nla"), ("dscore
 @pytest.mark.parametrize("dtype,B,H,L,d,p", [("f32", 1, 2, 256, 64, 0.4), ("f32", 1, 1, 192, 128, 0.3),
                                              ("bf16", 2, 2, 512, 64, 0.3), ("bf16", 1, 2, 448, 128, 0.25),
                                              ("bf16", 1, 1, 1024, 128, 0.5)])
-def test_backward_with_routing_per_chunk(dtype, B, H, L, d, p):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_with_routing_per_chunk(dtype, B, H, L, d, p, math):
     x = make_fwd_inputs(B, H, L, d, dtype, 0.1, seed=800 + L + d)
     x["mask"] = make_chunk_mask(B, H, L // 64, p, 801 + L, "bernoulli")
     dO = make_grad_output(B, H, L, d, dtype, seed=802 + L)
     S0 = (0.05 * np.random.default_rng(L + 1).standard_normal((B, H, d, d))).astype(np.float32)
-    r = run_bwd(x, dO, dtype, S0=S0, routing=nb.NATS_ROUTE_CHUNK, want=("d_initial_state", "dscore_nla", "dscore_la"))
+    r = run_bwd(x, dO, dtype, S0=S0, routing=nb.NATS_ROUTE_CHUNK, want=("d_initial_state", "dscore_nla", "dscore_la"),
+                math=math)
     ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO, S0=S0)
     errs = check(r, ref, extra=CHUNK_KEYS)
     print(dtype, L, d, errs)
@@ -164,24 +166,26 @@ def test_backward_with_routing_per_chunk(dtype, B, H, L, d, p):
 
 
 @pytest.mark.parametrize("linear_op,freeze", [(nb.NATS_LINEAR_GATED, False), (nb.NATS_LINEAR_GDN, True)])
-def test_backward_with_routing_per_chunk_variants(linear_op, freeze):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_with_routing_per_chunk_variants(linear_op, freeze, math):
     B, H, L, d = 1, 2, 256, 64
     x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=810 + linear_op)
     x["mask"] = make_chunk_mask(B, H, L // 64, 0.5, 811, "bernoulli")
     dO = make_grad_output(B, H, L, d, "f32", seed=812)
     r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, softmax_scale=0.3, la_scale=1.7, linear_op=linear_op,
-                freeze_on_softmax=freeze, want=("d_initial_state", "dscore_nla", "dscore_la"))
+                freeze_on_softmax=freeze, want=("d_initial_state", "dscore_nla", "dscore_la"), math=math)
     ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO, softmax_scale=0.3,
                                       la_scale=1.7, linear_op=linear_op, decay_on_softmax=not freeze)
     check(r, ref, extra=CHUNK_KEYS)
 
 
 @pytest.mark.parametrize("kind", ["all_softmax", "all_linear"])
-def test_backward_with_routing_per_chunk_degenerate_masks(kind):
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_with_routing_per_chunk_degenerate_masks(kind, math):
     B, H, L, d = 1, 2, 192, 64
     x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=820)
     x["mask"] = np.full((B, H, L // 64), 1 if kind == "all_softmax" else 0, dtype=np.uint8)
     dO = make_grad_output(B, H, L, d, "f32", seed=821)
-    r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, want=("dscore_nla", "dscore_la"))
+    r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, want=("dscore_nla", "dscore_la"), math=math)
     ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO)
     check(r, ref, extra=CHUNK_KEYS[1:])
