@@ -147,6 +147,10 @@ def bench_decode(args):
 
 
 def bench_backward(args):
+    print(json.dumps(measure_backward(args.steps, args.warmup, args.routing, args.backward_by_tokens)))
+
+
+def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False):
     """Backward pass on workload 2's shapes (bf16 tensors, fp32 gradients): a step is one nats_hybrid_attn_bwd call.
     The linear branch's adjoint runs by chunks on fp32 matrix instructions (operands per chunk, states forwards,
     state gradients backwards, then every chunk's gradients); the softmax branch's products run on fp16 / bf16 matrix
@@ -166,8 +170,8 @@ def bench_backward(args):
     Q, K, V = (g[k].to(torch.bfloat16) for k in ("Q", "K", "V"))
     dO = torch.from_numpy(make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 1)).to(dev).to(torch.bfloat16)
     import ctypes
-    math = nb.NATS_MATH_FP32 if args.backward_by_tokens else nb.NATS_MATH_AUTO
-    routing = nb.NATS_ROUTE_CHUNK if args.routing == "chunk" else nb.NATS_ROUTE_TOKEN
+    math = nb.NATS_MATH_FP32 if by_tokens else nb.NATS_MATH_AUTO
+    routing = nb.NATS_ROUTE_CHUNK if routing_name == "chunk" else nb.NATS_ROUTE_TOKEN
     if routing == nb.NATS_ROUTE_CHUNK:   # same shapes and softmax share, one routing decision per chunk of 64 tokens
         from nats_inputs import make_chunk_mask
         mask_c = make_chunk_mask(cfg.B, cfg.H, cfg.L // cfg.C, cfg.p_softmax, cfg.seed + 1)
@@ -180,8 +184,8 @@ def bench_backward(args):
     def step():
         return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math, routing=routing)
 
-    steps = max(1, min(args.steps, 20))
-    for _ in range(max(1, min(args.warmup, 3))):
+    steps = max(1, min(steps_in, 20))
+    for _ in range(max(1, min(warmup_in, 3))):
         step()
     torch.cuda.synchronize()
     nb.profile_begin(16 * steps)
@@ -212,16 +216,16 @@ def bench_backward(args):
                         "unit": "TFLOP/s", "frac": round(ach / 157.3, 5), "avg_kernel_ms": round(kern[k]["avg_ms"], 4)}
     lead = max(roofs, key=lambda k: roofs[k]["avg_kernel_ms"])
     out = {"metric": "hybrid_attn_bwd_tokens_per_s", "value": round(cfg.B * cfg.L / (ms * 1e-3), 1), "unit": "tokens/s",
-           "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+           "n_gpus": 1, "steps": steps, "warmup": warmup_in, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "backward of cfg2_headline_bf16" + (", routing per chunk" if args.routing == "chunk" else "")
+           "config": {"workload": "backward of cfg2_headline_bf16" + (", routing per chunk" if routing_name == "chunk" else "")
                                   + " (bf16 tensors, fp32 gradients; linear branch "
-                                  + ("token by token in fp32" if args.backward_by_tokens else "by chunks on fp32 MFMA")
+                                  + ("token by token in fp32" if by_tokens else "by chunks on fp32 MFMA")
                                   + ", softmax-branch products on MFMA with two-term fp16 weights)"},
            "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,
            "roofline": dict(kernel=lead, traffic=None, **roofs[lead]), "kernel_rooflines": roofs,
            "cpu_baseline": None}
-    print(json.dumps(out))
+    return out
 
 
 def main():
@@ -247,6 +251,8 @@ def main():
                     help="with --decode: one block per (batch, head), no workspace (the step's other form)")
     ap.add_argument("--no-decode-line", action="store_true",
                     help="leave the short decode measurement out of the forward's JSON line")
+    ap.add_argument("--no-backward-line", action="store_true",
+                    help="leave the short backward measurement out of the forward's JSON line")
     ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
     ap.add_argument("--backward-by-tokens", action="store_true",
                     help="with --backward: the linear branch's adjoint token by token (math = NATS_MATH_FP32)")
@@ -421,6 +427,11 @@ def main():
         torch.cuda.empty_cache()
         dec = measure_decode(30, 5)
         out["decode"] = {k: dec[k] for k in ("metric", "value", "unit", "ms_per_step", "config", "kernels_ms", "roofline")}
+    if not args.no_backward_line:
+        # ... and the backward pass on the headline shapes (10 calls after 2)
+        torch.cuda.empty_cache()
+        bw = measure_backward(10, 2, args.routing)
+        out["backward"] = {k: bw[k] for k in ("metric", "value", "unit", "ms_per_step", "config", "kernels_ms", "roofline")}
     if measured_peaks is not None:
         out["measured_peaks"] = measured_peaks
     if graph_ms is not None:
