@@ -128,6 +128,25 @@ def test_backward_by_chunks_with_gates_at_their_ends(dtype, d):
     assert lin0.any() and np.any(host(r["dbeta"])[lin0] != 0)   # a linear token with beta = 0 still has a gradient for it
 
 
+def test_backward_at_the_headline_size_on_sampled_heads():
+    """The shapes and launch configuration bench.py --backward times (B=2, H=16, L=8192, d=128, bf16): the oracle
+    recomputes the first and the last (batch, head) in full; 128 chunks of state and state gradient in a row."""
+    from nats_inputs import CONFIGS, make_config_inputs
+    cfg = CONFIGS["cfg2_headline_bf16"]
+    x = make_config_inputs(cfg)
+    dO = make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 1)
+    r = run_bwd(x, dO, "bf16", want=("d_initial_state", "g_nla", "g_la"))
+    for b, h in ((0, 0), (cfg.B - 1, cfg.H - 1)):
+        ref = nbw.hybrid_head_bwd(x["Q"][b, h], x["K"][b, h], x["V"][b, h], x["alpha"][b, h], x["beta"][b, h],
+                                  x["mask"][b, h], dO[b, h])
+        errs = {}
+        for got, want in KEYS + (("d_initial_state", "dS0"), ("g_nla", "g_nla"), ("g_la", "g_la")):
+            errs[got] = rel_err(host(r[got][b, h]), ref[want])
+        print((b, h), errs)
+        for k, e in errs.items():
+            assert e <= TOL_BWD, f"{(b, h)} {k}: {e:.3e} (all: {errs})"
+
+
 def test_backward_is_deterministic_and_reuses_a_poisoned_workspace():
     B, H, L, d = 1, 2, 256, 128
     x = make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=430)
