@@ -22,11 +22,9 @@
 // (parallel over chunks).  Columns of V (rows of the state) never mix along the sequence, so the two sequential
 // kernels split every (batch, head) into slices of 16 value columns, one block each.
 //
-// Matrix instruction used throughout: v_mfma_f32_16x16x4_f32, out[m][n] += sum_kk A[m][kk] B[kk][n]; lane (l16, lq)
-// gives A[m = l16][kk = lq], B[kk = lq][n = l16] and holds out[m = 4 lq + j][n = l16], j = 0..3.  A product over 16
-// contraction indices takes four instructions; instruction j contracts over the indices 4 lq + j, so that a lane's A
-// operands are four consecutive elements of a row (one 16-byte LDS read when the buffer is contiguous along the
-// contraction index) and a result tile can be the B operand of the next product as it sits in registers.
+// Matrix instruction used throughout: v_mfma_f32_16x16x4_f32 through mac16 (sixteen contraction indices in four
+// instructions, a lane's A operands four consecutive elements of a row: one 16-byte LDS read when the buffer is
+// contiguous along the contraction index).
 #include "nats_common.h"
 #include "mfma_util.h"
 
@@ -40,14 +38,6 @@ struct ChunkOps {   // per chunk: Tm, At, Pm [64][64] f32 row-major;  per token:
     float *Tm, *At, *Pm, *g2, *gam, *kd, *bp, *gamC;
 };
 
-__device__ __forceinline__ f32x4 mac16(const float4 a, const float4 b, f32x4 c) {
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, c, 0, 0, 0);
-    return c;
-}
-__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 // a 16-byte word of T as it came from memory -> floats (8 for bf16, 4 for fp32)
 __device__ __forceinline__ void unpack16(const u32x4 w, float (&out)[8], bf16_t) {
 #pragma unroll
@@ -60,8 +50,6 @@ __device__ __forceinline__ void unpack16(const u32x4 w, float (&out)[4], float) 
 #pragma unroll
     for (int q = 0; q < 4; ++q) out[q] = __uint_as_float(w[q]);
 }
-// four elements of one column, rows r0 .. r0 + 3 (row stride rs)
-__device__ __forceinline__ float4 ld4col(const float* p, int rs) { return make_float4(p[0], p[rs], p[2 * rs], p[3 * rs]); }
 
 // ---- operands of a chunk ---------------------------------------------------------------------------------------------
 // One block per (chunk, batch*head).  Products in fp32 from the inputs as given (bf16 converts exactly); the inverse

@@ -68,6 +68,31 @@ __device__ __forceinline__ half4 to_half4_hw(f32x4 v) {
     return h;
 }
 
+// ---- fp32 matrix instruction v_mfma_f32_16x16x4_f32: out[m][n] += sum_kk A[m][kk] B[kk][n]; lane (l16, lq) gives
+// A[m = l16][kk = lq], B[kk = lq][n = l16] and holds out[m = 4 lq + j][n = l16], j = 0..3.  mac16 contracts over 16
+// indices in four instructions, instruction j over the indices 4 lq + j: a lane's A operands are then four
+// consecutive elements of a row, and a result tile can be the B operand of a next product as it sits in registers.
+__device__ __forceinline__ f32x4 mac16(const float4 a, const float4 b, f32x4 c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, c, 0, 0, 0);
+    return c;
+}
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+// four elements of one column, rows r0 .. r0 + 3 (row stride rs)
+__device__ __forceinline__ float4 ld4col(const float* p, int rs) { return make_float4(p[0], p[rs], p[2 * rs], p[3 * rs]); }
+// the same two reads from a buffer of bf16 (raw 16 bits; p 8-byte aligned for ldb4)
+__device__ __forceinline__ float4 ldb4(const uint16_t* p) {
+    const uint2 w = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                       __uint_as_float(w.y & 0xffff0000u));
+}
+__device__ __forceinline__ float4 ldbcol(const uint16_t* p, int rs) {
+    return make_float4(__uint_as_float((uint32_t)p[0] << 16), __uint_as_float((uint32_t)p[rs] << 16),
+                       __uint_as_float((uint32_t)p[2 * rs] << 16), __uint_as_float((uint32_t)p[3 * rs] << 16));
+}
+
 constexpr int LDS_PAD = 8;  // fp16 elements added to every LDS row: 16-byte reads of 16 rows hit distinct banks
 
 }  // namespace nats

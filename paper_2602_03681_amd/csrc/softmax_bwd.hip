@@ -729,6 +729,100 @@ __global__ __launch_bounds__(256) void softmax_bwd_own_chunk_kernel(
     }
 }
 
+// The same on fp32 matrix instructions, for bf16 tensors: the four 64 x D tiles stay in LDS as they are (bf16,
+// widened when read), S = Q K^T and dP = dO V^T by 16 x 16 tiles below the diagonal (wavefront w: query tile w), then
+// p and scale x ds through LDS as fp32, and dQ_w = ds_w K, dK_w = ds^T Q, dV_w = p^T dO (wavefront w: key tile w).
+constexpr int OCM_PS = 68;   // row stride (floats) of the p and ds tiles
+template <int D>
+__global__ __launch_bounds__(256) void softmax_bwd_own_chunk_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
+    const float* __restrict__ lse, const float* __restrict__ Dvec, float* __restrict__ dQ, float* __restrict__ dK,
+    float* __restrict__ dV, int L, float scale) {
+    constexpr int RS = D + 8, PS = OCM_PS, NP = 64 * D / 8 / 256;
+    extern __shared__ __align__(16) unsigned char oc_smem[];
+    uint16_t* Qs = reinterpret_cast<uint16_t*>(oc_smem);
+    uint16_t* Ks = Qs + 64 * RS;
+    uint16_t* Vs = Ks + 64 * RS;
+    uint16_t* Os = Vs + 64 * RS;
+    float* s_p = reinterpret_cast<float*>(Os + 64 * RS);
+    float* s_ds = s_p + 64 * PS;
+    const int bh = blockIdx.y, c0 = blockIdx.x * 64, tid = threadIdx.x;
+    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), l16 = lane & 15, lq = lane >> 4;
+    const size_t rowb = (size_t)bh * L + c0;
+    {
+        u32x4 r[4][NP];
+        const bf16_t* src[4] = {Q, K, V, dO};
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int i = 0; i < NP; ++i) r[a][i] = reinterpret_cast<const u32x4*>(src[a] + rowb * D)[tid + 256 * i];
+        uint16_t* dst[4] = {Qs, Ks, Vs, Os};
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int e = tid + 256 * i;
+                *reinterpret_cast<u32x4*>(dst[a] + (e / (D / 8)) * RS + (e % (D / 8)) * 8) = r[a][i];
+            }
+    }
+    float lq4[4], dq4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        lq4[j] = lse[rowb + 16 * w + 4 * lq + j] * 1.44269504088896341f;
+        dq4[j] = Dvec[rowb + 16 * w + 4 * lq + j];
+    }
+    const float scale2 = scale * 1.44269504088896341f;
+    __syncthreads();
+    for (int tb = 0; tb <= w; ++tb) {
+        f32x4 accS = {0.f, 0.f, 0.f, 0.f}, accD = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int kt = 0; kt < D / 16; ++kt) {
+            accS = mac16(ldb4(Qs + (16 * w + l16) * RS + 16 * kt + 4 * lq), ldb4(Ks + (16 * tb + l16) * RS + 16 * kt + 4 * lq), accS);
+            accD = mac16(ldb4(Os + (16 * w + l16) * RS + 16 * kt + 4 * lq), ldb4(Vs + (16 * tb + l16) * RS + 16 * kt + 4 * lq), accD);
+        }
+        const int key = 16 * tb + l16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = 16 * w + 4 * lq + j;
+            const float p = key <= q ? __builtin_amdgcn_exp2f(scale2 * accS[j] - lq4[j]) : 0.f;   // base-2 units
+            s_p[q * PS + key] = p;
+            s_ds[q * PS + key] = scale * p * (accD[j] - dq4[j]);
+        }
+    }
+    __syncthreads();
+    // The old values of dQ, dK, dV that the results are added to: asked for up front, all at once (a read inside
+    // the loop below would cost a trip to memory per column tile).
+    constexpr int NKT = D / 16;
+    float oq[NKT][4], ok[NKT][4], ov[NKT][4];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t off = (rowb + 16 * w + 4 * lq + j) * D + 16 * kt + l16;
+            oq[kt][j] = dQ[off];
+            ok[kt][j] = dK[off];
+            ov[kt][j] = dV[off];
+        }
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+        f32x4 aq = {oq[kt][0], oq[kt][1], oq[kt][2], oq[kt][3]}, ak = {ok[kt][0], ok[kt][1], ok[kt][2], ok[kt][3]};
+        f32x4 av = {ov[kt][0], ov[kt][1], ov[kt][2], ov[kt][3]};
+        for (int tb = 0; tb <= w; ++tb)     // dQ of query tile w: keys of the tiles up to it
+            aq = mac16(ld4(s_ds + (16 * w + l16) * PS + 16 * tb + 4 * lq), ldbcol(Ks + (16 * tb + 4 * lq) * RS + 16 * kt + l16, RS), aq);
+        for (int ta = w; ta < 4; ++ta) {    // dK, dV of key tile w: queries of the tiles from it on
+            ak = mac16(ld4col(s_ds + (16 * ta + 4 * lq) * PS + 16 * w + l16, PS), ldbcol(Qs + (16 * ta + 4 * lq) * RS + 16 * kt + l16, RS), ak);
+            av = mac16(ld4col(s_p + (16 * ta + 4 * lq) * PS + 16 * w + l16, PS), ldbcol(Os + (16 * ta + 4 * lq) * RS + 16 * kt + l16, RS), av);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t off = (rowb + 16 * w + 4 * lq + j) * D + 16 * kt + l16;
+            dQ[off] = aq[j];
+            dK[off] = ak[j];
+            dV[off] = av[j];
+        }
+    }
+}
+
 nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* vis, hipStream_t st) {
     const size_t n_tok = (size_t)pl.BH * pl.L;
     hipLaunchKernelGGL(visible_rows_kernel, dim3((unsigned)((n_tok + 255) / 256)), dim3(256), 0, st, cnt, vis, pl.L, n_tok);
@@ -749,9 +843,20 @@ nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const
         hipLaunchKernelGGL(kern, grid, dim3(256), OC_LDS_BYTES, st, (const TT*)Q, (const TT*)K, (const TT*)V,        \
                            (const TT*)dO, lse, Dvec, dQ, dK, dV, pl.L, pl.softmax_scale);                           \
     } while (0)
-    if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_OC_LAUNCH(bf16_t, 64); else NATS_OC_LAUNCH(bf16_t, 128); }
+#define NATS_OCM_LAUNCH(DD)                                                                                          \
+    do {                                                                                                             \
+        auto kern = softmax_bwd_own_chunk_mfma_kernel<DD>;                                                           \
+        constexpr int lds = 4 * 64 * (DD + 8) * 2 + 2 * 64 * OCM_PS * 4;                                             \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                lds) != hipSuccess)                                                                  \
+            return check_launch("softmax_bwd_own_chunk (LDS attribute)");                                            \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V,     \
+                           (const bf16_t*)dO, lse, Dvec, dQ, dK, dV, pl.L, pl.softmax_scale);                       \
+    } while (0)
+    if (pl.dtype == NATS_BF16) { if (pl.d == 64) NATS_OCM_LAUNCH(64); else NATS_OCM_LAUNCH(128); }
     else { if (pl.d == 64) NATS_OC_LAUNCH(float, 64); else NATS_OC_LAUNCH(float, 128); }
 #undef NATS_OC_LAUNCH
+#undef NATS_OCM_LAUNCH
     return check_launch("softmax_bwd_own_chunk");
 }
 
