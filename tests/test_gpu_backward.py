@@ -147,6 +147,26 @@ def test_backward_at_the_headline_size_on_sampled_heads():
             assert e <= TOL_BWD, f"{(b, h)} {k}: {e:.3e} (all: {errs})"
 
 
+@pytest.mark.parametrize("routing", [nb.NATS_ROUTE_TOKEN, nb.NATS_ROUTE_CHUNK], ids=["per_token", "per_chunk"])
+def test_backward_long_sequence_both_forms_agree(routing):
+    """L = 32768 (512 chunks in a row), beyond what the oracle recomputes in seconds: the two forms of the linear
+    branch's adjoint, which share no kernel of that branch (fp32 vector arithmetic token by token; fp32 matrix
+    instructions by chunks), must give the same gradients; each is held to the oracle at the shorter lengths above."""
+    B, H, L, d = 1, 3, 32768, 128
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.05, seed=450)
+    if routing == nb.NATS_ROUTE_CHUNK:
+        x["mask"] = make_chunk_mask(B, H, L // 64, 0.05, 451, "bernoulli")
+    dO = make_grad_output(B, H, L, d, "bf16", seed=452)
+    want = ("d_initial_state",)
+    a = run_bwd(x, dO, "bf16", want=want, routing=routing, math=nb.NATS_MATH_AUTO)
+    b = run_bwd(x, dO, "bf16", want=want, routing=routing, math=nb.NATS_MATH_FP32)
+    for k in ("dQ", "dK", "dV", "dalpha", "dbeta", "d_initial_state"):
+        ya, yb = host(a[k]), host(b[k])
+        assert np.all(np.isfinite(ya)) and np.all(np.isfinite(yb)), k
+        e = rel_err(ya, yb)
+        assert e <= TOL_BWD, f"{k}: {e:.3e}"
+
+
 def test_backward_is_deterministic_and_reuses_a_poisoned_workspace():
     B, H, L, d = 1, 2, 256, 128
     x = make_fwd_inputs(B, H, L, d, "bf16", 0.1, seed=430)
