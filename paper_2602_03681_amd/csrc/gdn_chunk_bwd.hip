@@ -53,7 +53,7 @@ __device__ __forceinline__ void unpack16(const u32x4 w, float (&out)[4], float) 
 
 // ---- operands of a chunk ---------------------------------------------------------------------------------------------
 // One block per (chunk, batch*head).  Products in fp32 from the inputs as given (bf16 converts exactly); the inverse
-// by forward substitution, one lane per column.
+// by 16 x 16 blocks: forward substitution on the diagonal, matrix instructions below it.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__ Q, const T* __restrict__ K,
                                                            const float* __restrict__ alpha, const float* __restrict__ beta,
@@ -162,17 +162,19 @@ __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__
         }
     }
     __syncthreads();
-    // T = (I + A)^-1: lane j of wavefront 0 solves column j, T[r][j] = [r == j] - sum over i < r of A[r][i] T[i][j]
-    // (entries above the diagonal come out as exact zeros).  Wavefront a handles rows 16 a ..: it needs the rows
-    // before, so the wavefronts would only wait for each other; wavefront 0 does all of it.
-    if (w == 0) {
-        float col[CB_C];
+    // T = (I + A)^-1, unit lower triangular, by 16 x 16 blocks (K's region, dead since the products, holds T).
+    // (a) Diagonal blocks: wavefront b inverts I + A_bb by forward substitution, lane j < 16 owns column j:
+    //     T[r][j] = [r == j] - sum over i < r of A[r][i] T[i][j]  (entries above the diagonal come out as exact zeros).
+    float* Ts = Ks;   // [64][CB_MS]
+    if (lane < 16) {
+        const float* Ab = As + (16 * w) * CB_MS + 16 * w;
+        float col[16];
 #pragma unroll
-        for (int r = 0; r < CB_C; ++r) {
+        for (int r = 0; r < 16; ++r) {
             float acc = 0.f;
 #pragma unroll
             for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {
-                const float4 a4 = ld4(As + r * CB_MS + 4 * i4);
+                const float4 a4 = ld4(Ab + r * CB_MS + 4 * i4);
                 acc += a4.x * col[4 * i4];
                 if (4 * i4 + 1 < r) acc += a4.y * col[4 * i4 + 1];
                 if (4 * i4 + 2 < r) acc += a4.z * col[4 * i4 + 2];
@@ -181,7 +183,30 @@ __global__ __launch_bounds__(256) void gdn_bwd_prep_kernel(const T* __restrict__
             col[r] = ((r == lane) ? 1.f : 0.f) - acc;
         }
 #pragma unroll
-        for (int r = 0; r < CB_C; ++r) Tmo[r * CB_C + lane] = col[r];
+        for (int r = 0; r < 16; ++r) Ts[(16 * w + r) * CB_MS + 16 * w + lane] = col[r];
+    }
+    __syncthreads();
+    // (b) Blocks below the diagonal: T_ab = - T_aa sum over b <= k < a of A_ak T_kb.  Wavefront b owns block column b
+    //     and walks down it; the sum's result tile is the right operand of the product with T_aa as it sits in
+    //     registers.
+    for (int ta = w + 1; ta < 4; ++ta) {
+        f32x4 X = {0.f, 0.f, 0.f, 0.f};
+        for (int k = w; k < ta; ++k)
+            X = mac16(ld4(As + (16 * ta + l16) * CB_MS + 16 * k + 4 * lq), ld4col(Ts + (16 * k + 4 * lq) * CB_MS + 16 * w + l16, CB_MS), X);
+        const f32x4 Y = mac16(ld4(Ts + (16 * ta + l16) * CB_MS + 16 * ta + 4 * lq), make_float4(X[0], X[1], X[2], X[3]),
+                              f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Ts[(16 * ta + 4 * lq + j) * CB_MS + 16 * w + l16] = -Y[j];
+        __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
+    }
+    __syncthreads();
+    // (c) out, 16 bytes per thread and step; the tiles above the diagonal were never written: zeros
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = tid + 256 * i, r = e / 16, c4 = (e % 16) * 4;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((c4 >> 4) <= (r >> 4)) t = ld4(Ts + r * CB_MS + c4);
+        *reinterpret_cast<float4*>(Tmo + r * CB_C + c4) = t;
     }
 }
 
