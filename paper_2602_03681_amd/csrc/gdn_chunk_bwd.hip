@@ -25,6 +25,8 @@
 // Matrix instruction used throughout: v_mfma_f32_16x16x4_f32 through mac16 (sixteen contraction indices in four
 // instructions, a lane's A operands four consecutive elements of a row: one 16-byte LDS read when the buffer is
 // contiguous along the contraction index).
+#include <type_traits>
+
 #include "nats_common.h"
 #include "mfma_util.h"
 
@@ -232,22 +234,61 @@ struct SeqArgs {
 // Eight wavefronts: four compute (as above), four only move the next chunk's operands from global memory to LDS.
 // A burst of loads of this size keeps a wavefront at the issue of its memory instructions for about as long as a
 // whole phase of the chunk's products takes, and there is one block per CU with nothing else to fill the time:
-// so the wavefronts that multiply issue no global loads at all.
+// so the wavefronts that multiply issue no global loads at all.  What is staged has two places in LDS where that
+// fits (K, Q and the per-token vectors; At forwards), so the next chunk is written while this one is multiplied;
+// T and (backwards) P have one place and are replaced once their last reader of the chunk is past, behind the
+// second barrier.
+// With fp32 tensors the backward direction has room for one place only: there the staged operands are replaced
+// between the third barrier and a fourth.
+template <typename T, int D, int DIR>
+struct SeqLds {
+    static constexpr bool two = !(DIR == 1 && sizeof(T) == 4);   // two places for K, Q and the small operands
+    static constexpr int NB = two ? 2 : 1;
+    static constexpr int MS = CB_MS;
+    // K and Q in LDS: fp32 forwards (the moving wavefronts widen bf16 once: widening at every read costs the
+    // multiplying wavefronts more than the second place saves); backwards, where two places for K and Q in fp32 do
+    // not fit, in the tensors' own type (bf16 is widened when read)
+    static constexpr bool wide = DIR == 0 || sizeof(T) == 4;
+    static constexpr int KE_BYTES = wide ? 4 : 2;
+    static constexpr int KS = D + (wide ? 4 : 8);                // row stride of K, Q (elements)
+    static constexpr int KQ_BYTES = CB_C * KS * KE_BYTES * (DIR ? 2 : 1);   // K, then (DIR 1) Q
+    static constexpr int M_BYTES = CB_C * MS * 4;
+    static constexpr int NB2 = DIR ? 1 : NB;                     // places of M2: At (DIR 0) as K; P (DIR 1) one
+    static constexpr int B_BYTES = CB_NV * MS * 4;               // a [16 v][MS] operand with tokens as contraction index
+    // small operands of a chunk: Xt, Gt (256 floats), and (DIR 1) dO' and diag(gamma) dO'
+    static constexpr int SM_BYTES = B_BYTES + 256 * 4 + (DIR ? 2 * B_BYTES : 0);
+    static constexpr int o_kq = 0;
+    static constexpr int o_m1 = o_kq + NB * KQ_BYTES;
+    static constexpr int o_m2 = o_m1 + M_BYTES;
+    static constexpr int o_sm = o_m2 + NB2 * M_BYTES;
+    static constexpr int o_st = o_sm + NB * SM_BYTES;
+    static constexpr int o_b = o_st + CB_NV * (D + 4) * 4;       // DIR 0: B0, B1, B2;  DIR 1: B2, B3
+    static constexpr int bytes = o_b + (DIR ? 2 : 3) * B_BYTES;
+};
+
+__device__ __forceinline__ float4 ldk4(const float* p) { return ld4(p); }
+__device__ __forceinline__ float4 ldk4(const uint16_t* p) { return ldb4(p); }
+__device__ __forceinline__ float4 ldkcol(const float* p, int rs) { return ld4col(p, rs); }
+__device__ __forceinline__ float4 ldkcol(const uint16_t* p, int rs) { return ldbcol(p, rs); }
+
 template <typename T, int D, int DIR>
 __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) {
-    constexpr int KS = D + 4, E = Vec16<T>::N, NP = CB_C * D / E / 256, KT = D / 64, MS = CB_MS;
+    using LY = SeqLds<T, D, DIR>;
+    using KE = typename std::conditional<LY::wide, float, uint16_t>::type;   // K, Q in LDS
+    constexpr int KS = LY::KS, SS = D + 4, NP = CB_C * D * (int)sizeof(T) / 16 / 256, KT = D / 64, MS = CB_MS, NB = LY::NB;
+    constexpr int EPW = 16 / (int)sizeof(T);   // elements of a 16-byte word
     extern __shared__ __align__(16) float cb_smem[];
-    float* Ks = cb_smem;
-    float* M1 = Ks + CB_C * KS;            // T
-    float* M2 = M1 + CB_C * MS;            // At (DIR 0), P (DIR 1)
-    float* St = M2 + CB_C * MS;            // state, [16 v][KS]
-    float* B0 = St + CB_NV * KS;           // [16 v][MS] each: operands with the tokens as contraction index
-    float* B1 = B0 + CB_NV * MS;
-    float* B2 = B1 + CB_NV * MS;
-    float* B3 = B2 + CB_NV * MS;
-    float* Xt = B3 + CB_NV * MS;           // [16 v][MS]: V (DIR 0) or Uh (DIR 1) of the block's columns, tokens along a row
-    float* Gt = Xt + CB_NV * MS;           // gam, kd, bp [64] each, then gamC, then (DIR 1) the chunk's 64 mask bytes
-    float* Qs = Gt + 4 * CB_C;             // DIR 1 only
+    unsigned char* lds = reinterpret_cast<unsigned char*>(cb_smem);
+    auto Ksb = [&](int i) { return reinterpret_cast<KE*>(lds + LY::o_kq + i * LY::KQ_BYTES); };
+    auto Qsb = [&](int i) { return Ksb(i) + CB_C * KS; };                               // DIR 1
+    float* M1 = reinterpret_cast<float*>(lds + LY::o_m1);                                 // T
+    auto M2b = [&](int i) { return reinterpret_cast<float*>(lds + LY::o_m2 + (DIR ? 0 : i) * LY::M_BYTES); };   // At / P
+    auto Xtb = [&](int i) { return reinterpret_cast<float*>(lds + LY::o_sm + i * LY::SM_BYTES); };   // V or Uh, [16 v][MS]
+    auto Gtb = [&](int i) { return Xtb(i) + CB_NV * MS; };       // gam, kd, bp [64] each, gamC, then (DIR 1) 64 mask bytes
+    auto B0b = [&](int i) { return Gtb(i) + 256; };              // DIR 1: dO' with the tokens as contraction index
+    auto B1b = [&](int i) { return B0b(i) + CB_NV * MS; };       // DIR 1: diag(gamma) dO'
+    float* St = reinterpret_cast<float*>(lds + LY::o_st);       // state, [16 v][SS]
+    float* Bx = reinterpret_cast<float*>(lds + LY::o_b);        // exchange between the wavefronts, [16 v][MS] each
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool loader = wave >= 4;
     const int w = wave & 3, lt = tid & 255;
@@ -257,93 +298,114 @@ __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
     const size_t n_tok = (size_t)a.BH * L;
     const float delta = a.delta ? 1.f : 0.f;
 
-    // loader wavefronts: the next chunk's operands as they come from memory
-    u32x4 kreg[NP], qreg[DIR ? NP : 1];
-    float4 m1reg[4], m2reg[4], gate4 = make_float4(0.f, 0.f, 0.f, 0.f), g4n = gate4;
-    T xvn[4];
-    float uhn[4] = {0.f, 0.f, 0.f, 0.f}, gCn = 0.f;
-    uint32_t linn = 0;
-    auto fetch = [&](int c) {
-        const size_t gc = (size_t)bh * n_chunks + c, tok0 = (size_t)bh * L + (size_t)c * CB_C;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {   // a chunk's rows are contiguous
-            kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[lt + 256 * i];
-            if (DIR) qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[lt + 256 * i];
-        }
-        const float* m1 = a.o.Tm + gc * (CB_C * CB_C);
-        const float* m2 = (DIR ? a.o.Pm : a.o.At) + gc * (CB_C * CB_C);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            m1reg[i] = ld4(m1 + 4 * (lt + 256 * i));
-            m2reg[i] = ld4(m2 + 4 * (lt + 256 * i));
-        }
-        if (lt < 48) gate4 = ld4((lt < 16 ? a.o.gam : lt < 32 ? a.o.kd : a.o.bp) + tok0 + 4 * (lt & 15));
-        if (lt == 48) gCn = a.o.gamC[gc];
-        if (DIR && a.mask != nullptr && lt >= 64 && lt < 80)   // NULL: routing per chunk, every token of a chunk writes
-            linn = *reinterpret_cast<const uint32_t*>(a.mask + tok0 + 4 * (lt - 64));
-        const size_t t4 = tok0 + 16 * w + 4 * lq;
-        if (DIR) g4n = ld4(a.o.gam + t4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            xvn[j] = a.X[(t4 + j) * D + v0 + l16];
-            if (DIR) uhn[j] = a.Uh[(t4 + j) * D + v0 + l16];
-        }
-    };
-    auto commit = [&]() {
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int e = lt + 256 * i, row = e / (D / E), cc = (e % (D / E)) * E;
-            float kf[E], qf[E];
-            unpack16(kreg[i], kf, T{});
-            if (DIR) unpack16(qreg[i], qf, T{});
-#pragma unroll
-            for (int j = 0; j < E; j += 4) {
-                *reinterpret_cast<float4*>(Ks + row * KS + cc + j) = make_float4(kf[j], kf[j + 1], kf[j + 2], kf[j + 3]);
-                if (DIR) *reinterpret_cast<float4*>(Qs + row * KS + cc + j) = make_float4(qf[j], qf[j + 1], qf[j + 2], qf[j + 3]);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = lt + 256 * i, row = e / 16, c4 = (e % 16) * 4;
-            *reinterpret_cast<float4*>(M1 + row * MS + c4) = m1reg[i];
-            *reinterpret_cast<float4*>(M2 + row * MS + c4) = m2reg[i];
-        }
-        if (lt < 48) *reinterpret_cast<float4*>(Gt + 4 * lt) = gate4;
-        if (lt == 48) Gt[3 * CB_C] = gCn;
-        if (DIR && lt >= 64 && lt < 80) reinterpret_cast<uint32_t*>(Gt + 3 * CB_C + 4)[lt - 64] = linn;
-        if (DIR == 0) {
-            *reinterpret_cast<float4*>(Xt + l16 * MS + 16 * w + 4 * lq) =
-                make_float4(to_float(xvn[0]), to_float(xvn[1]), to_float(xvn[2]), to_float(xvn[3]));
-        } else {   // Uh; dO' and diag(gamma) dO' with the tokens as contraction index
-            *reinterpret_cast<float4*>(Xt + l16 * MS + 16 * w + 4 * lq) = make_float4(uhn[0], uhn[1], uhn[2], uhn[3]);
-            float4 x, y;
-            x.x = a.la_scale * to_float(xvn[0]); x.y = a.la_scale * to_float(xvn[1]);
-            x.z = a.la_scale * to_float(xvn[2]); x.w = a.la_scale * to_float(xvn[3]);
-            y.x = g4n.x * x.x; y.y = g4n.y * x.y; y.z = g4n.z * x.z; y.w = g4n.w * x.w;
-            *reinterpret_cast<float4*>(B0 + l16 * MS + 16 * w + 4 * lq) = x;
-            *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = y;
-        }
-    };
-
-    // the state: tiles kt = KT w + t, element [k = 16 kt + 4 lq + j][v = l16]
     // The two kinds of wavefront run loops of their own with the same number of barriers (a barrier counts
     // arrivals, wherever in the code they come from): what one kind keeps in registers across a chunk then takes
     // no registers from the other.
     if (loader) {
-        fetch(DIR ? n_chunks - 1 : 0);
-        commit();
+        u32x4 kreg[NP], qreg[DIR ? NP : 1];
+        float4 m1reg[4], m2reg[4], gate4 = make_float4(0.f, 0.f, 0.f, 0.f), g4n = gate4;
+        T xvn[4];
+        float uhn[4] = {0.f, 0.f, 0.f, 0.f}, gCn = 0.f;
+        uint32_t linn = 0;
+        auto fetch = [&](int c) {   // as it comes from memory: a conversion here would wait for the load
+            const size_t gc = (size_t)bh * n_chunks + c, tok0 = (size_t)bh * L + (size_t)c * CB_C;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {   // a chunk's rows are contiguous
+                kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[lt + 256 * i];
+                if (DIR) qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[lt + 256 * i];
+            }
+            if (lt < 48) gate4 = ld4((lt < 16 ? a.o.gam : lt < 32 ? a.o.kd : a.o.bp) + tok0 + 4 * (lt & 15));
+            if (lt == 48) gCn = a.o.gamC[gc];
+            if (DIR && a.mask != nullptr && lt >= 64 && lt < 80)   // NULL: routing per chunk, every token of a chunk writes
+                linn = *reinterpret_cast<const uint32_t*>(a.mask + tok0 + 4 * (lt - 64));
+            const size_t t4 = tok0 + 16 * w + 4 * lq;
+            if (DIR) g4n = ld4(a.o.gam + t4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xvn[j] = a.X[(t4 + j) * D + v0 + l16];
+                if (DIR) uhn[j] = a.Uh[(t4 + j) * D + v0 + l16];
+            }
+            const float* m1 = a.o.Tm + gc * (CB_C * CB_C);
+            const float* m2 = (DIR ? a.o.Pm : a.o.At) + gc * (CB_C * CB_C);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                m2reg[i] = ld4(m2 + 4 * (lt + 256 * i));
+                m1reg[i] = ld4(m1 + 4 * (lt + 256 * i));
+            }
+        };
+        auto put_kq_small = [&](int nb) {
+            KE* Ks = Ksb(nb);
+            KE* Qs = Qsb(nb);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int e = lt + 256 * i, row = e / (D / EPW), cc = (e % (D / EPW)) * EPW;
+                if (sizeof(KE) == sizeof(T)) {   // as they are
+                    *reinterpret_cast<u32x4*>(Ks + row * KS + cc) = kreg[i];
+                    if (DIR) *reinterpret_cast<u32x4*>(Qs + row * KS + cc) = qreg[i];
+                } else {                          // bf16 widened here (forwards only: no Q)
+                    float kf[EPW];
+                    unpack16(kreg[i], kf, T{});
+#pragma unroll
+                    for (int j = 0; j < EPW; j += 4)
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(Ks) + row * KS + cc + j) = make_float4(kf[j], kf[j + 1], kf[j + 2], kf[j + 3]);
+                }
+            }
+            float* Gt = Gtb(nb);
+            if (lt < 48) *reinterpret_cast<float4*>(Gt + 4 * lt) = gate4;
+            if (lt == 48) Gt[3 * CB_C] = gCn;
+            if (DIR && lt >= 64 && lt < 80) reinterpret_cast<uint32_t*>(Gt + 3 * CB_C + 4)[lt - 64] = linn;
+            if (DIR == 0) {
+                *reinterpret_cast<float4*>(Xtb(nb) + l16 * MS + 16 * w + 4 * lq) =
+                    make_float4(to_float(xvn[0]), to_float(xvn[1]), to_float(xvn[2]), to_float(xvn[3]));
+            } else {   // Uh; dO' and diag(gamma) dO' with the tokens as contraction index
+                *reinterpret_cast<float4*>(Xtb(nb) + l16 * MS + 16 * w + 4 * lq) = make_float4(uhn[0], uhn[1], uhn[2], uhn[3]);
+                float4 x, y;
+                x.x = a.la_scale * to_float(xvn[0]); x.y = a.la_scale * to_float(xvn[1]);
+                x.z = a.la_scale * to_float(xvn[2]); x.w = a.la_scale * to_float(xvn[3]);
+                y.x = g4n.x * x.x; y.y = g4n.y * x.y; y.z = g4n.z * x.z; y.w = g4n.w * x.w;
+                *reinterpret_cast<float4*>(B0b(nb) + l16 * MS + 16 * w + 4 * lq) = x;
+                *reinterpret_cast<float4*>(B1b(nb) + l16 * MS + 16 * w + 4 * lq) = y;
+            }
+        };
+        auto put_m = [&](float* M, const float4 (&r)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = lt + 256 * i, row = e / 16, c4 = (e % 16) * 4;
+                *reinterpret_cast<float4*>(M + row * MS + c4) = r[i];
+            }
+        };
+        // Chunk ci + 1 is written to LDS behind the second barrier of chunk ci (by then its loads, issued a chunk
+        // earlier, have long arrived, and the readers of T and P are past), and the loads of chunk ci + 2 are issued
+        // right after: the first two barriers of a chunk never wait for these wavefronts.
+        auto chunk_at = [&](int ci) { return DIR ? n_chunks - 1 - ci : ci; };
+        fetch(chunk_at(0));
+        put_kq_small(0);
+        put_m(M2b(0), m2reg);
+        put_m(M1, m1reg);
+        if (n_chunks > 1) fetch(chunk_at(1));
         __syncthreads();
         for (int ci = 0; ci < n_chunks; ++ci) {
-            const int c = DIR ? n_chunks - 1 - ci : ci;
-            if (ci + 1 < n_chunks) fetch(DIR ? c - 1 : c + 1);
+            const int nb = (ci + 1) % NB;
+            const bool more = ci + 1 < n_chunks;
             __syncthreads();
             __syncthreads();
-            __syncthreads();   // every read of the chunk's operands is done
-            if (ci + 1 < n_chunks) commit();
+            if (more) {
+                if (LY::two) put_kq_small(nb);
+                put_m(M2b(nb), m2reg);
+                put_m(M1, m1reg);
+            }
+            if (LY::two && ci + 2 < n_chunks) fetch(chunk_at(ci + 2));
             __syncthreads();
+            if (!LY::two) {   // one place for K, Q and the per-token vectors: replaced between the third barrier and a fourth
+                if (more) put_kq_small(0);
+                if (ci + 2 < n_chunks) fetch(chunk_at(ci + 2));
+                __syncthreads();
+            }
         }
         return;
     }
+
+    // the state: tiles kt = KT w + t, element [k = 16 kt + 4 lq + j][v = l16]
     f32x4 Sacc[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
@@ -351,30 +413,40 @@ __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
         if (DIR == 0 && a.S_init != nullptr) s = ld4(a.S_init + ((size_t)bh * D + v0 + l16) * D + 16 * kt + 4 * lq);
         Sacc[t] = f32x4{s.x, s.y, s.z, s.w};
-        *reinterpret_cast<float4*>(St + l16 * KS + 16 * kt + 4 * lq) = s;
+        *reinterpret_cast<float4*>(St + l16 * SS + 16 * kt + 4 * lq) = s;
     }
     __syncthreads();
 
     for (int ci = 0; ci < n_chunks; ++ci) {
-        const int c = DIR ? n_chunks - 1 - ci : ci;
+        const int c = DIR ? n_chunks - 1 - ci : ci, cb = ci % NB;
         const size_t gc = (size_t)bh * n_chunks + c;
         const size_t t4 = (size_t)bh * L + (size_t)c * CB_C + 16 * w + 4 * lq;   // the lane's first token
-        float gg[4], kk[4], bb[4], xv[4], R[4], gC = 0.f;
-        uint32_t lin = 0;
+        const KE* Ks = Ksb(cb);
+        const KE* Qs = Qsb(cb);
+        const float* M2 = M2b(cb);
+        const float* Gt = Gtb(cb);
+        // exchange buffers: DIR 0: B0 = b' R, B1 = U, B2 = kd U;  DIR 1: B0, B1 staged (dO', gamma dO'), B2 = dU, B3 = -gamma dR
+        float* B0 = DIR ? B0b(cb) : Bx;
+        float* B1 = DIR ? B1b(cb) : Bx + CB_NV * MS;
+        float* B2 = DIR ? Bx : Bx + 2 * CB_NV * MS;
+        float* B3 = Bx + CB_NV * MS;   // DIR 1
+        float gg[4], kk[4], bb[4], xv[4], R[4];
         {
             const float4 g4 = ld4(Gt + 16 * w + 4 * lq), kd4 = ld4(Gt + CB_C + 16 * w + 4 * lq);
-            const float4 bp4 = ld4(Gt + 2 * CB_C + 16 * w + 4 * lq), x4 = ld4(Xt + l16 * MS + 16 * w + 4 * lq);
+            const float4 bp4 = ld4(Gt + 2 * CB_C + 16 * w + 4 * lq), x4 = ld4(Xtb(cb) + l16 * MS + 16 * w + 4 * lq);
             gg[0] = g4.x; gg[1] = g4.y; gg[2] = g4.z; gg[3] = g4.w;
             kk[0] = kd4.x; kk[1] = kd4.y; kk[2] = kd4.z; kk[3] = kd4.w;
             bb[0] = bp4.x; bb[1] = bp4.y; bb[2] = bp4.z; bb[3] = bp4.w;
             xv[0] = x4.x; xv[1] = x4.y; xv[2] = x4.z; xv[3] = x4.w;
-            gC = Gt[3 * CB_C];
-            if (DIR) lin = reinterpret_cast<const uint32_t*>(Gt + 3 * CB_C + 4)[4 * w + lq];
-            // ---- 1: the state seen by the wavefront's tokens: K_w S^T ----------------------------------------
+        }
+        const float gC = Gt[3 * CB_C];
+        const uint32_t lin = DIR ? reinterpret_cast<const uint32_t*>(Gt + 3 * CB_C + 4)[4 * w + lq] : 0u;
+        // ---- 1: the state seen by the wavefront's tokens: K_w S^T --------------------------------------------
+        {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
             for (int kt = 0; kt < D / 16; ++kt)
-                acc = mac16(ld4(Ks + (16 * w + l16) * KS + 16 * kt + 4 * lq), ld4(St + l16 * KS + 16 * kt + 4 * lq), acc);
+                acc = mac16(ldk4(Ks + (16 * w + l16) * KS + 16 * kt + 4 * lq), ld4(St + l16 * SS + 16 * kt + 4 * lq), acc);
             if (DIR == 0) {
                 float4 br;
 #pragma unroll
@@ -394,70 +466,67 @@ __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
         }
         __syncthreads();
         // ---- 2: through the inverse ------------------------------------------------------------------------
-        {
-            if (DIR == 0) {
-                f32x4 U = {0.f, 0.f, 0.f, 0.f};
-                for (int tb = 0; tb <= w; ++tb)
-                    U = mac16(ld4(M1 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B0 + l16 * MS + 16 * tb + 4 * lq), U);
-                *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = make_float4(U[0], U[1], U[2], U[3]);
-                *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = make_float4(kk[0] * U[0], kk[1] * U[1], kk[2] * U[2], kk[3] * U[3]);
+        if (DIR == 0) {
+            f32x4 U = {0.f, 0.f, 0.f, 0.f};
+            for (int tb = 0; tb <= w; ++tb)
+                U = mac16(ld4(M1 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B0 + l16 * MS + 16 * tb + 4 * lq), U);
+            *reinterpret_cast<float4*>(B1 + l16 * MS + 16 * w + 4 * lq) = make_float4(U[0], U[1], U[2], U[3]);
+            *reinterpret_cast<float4*>(B2 + l16 * MS + 16 * w + 4 * lq) = make_float4(kk[0] * U[0], kk[1] * U[1], kk[2] * U[2], kk[3] * U[3]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) a.Ug[(t4 + j) * D + v0 + l16] = U[j];
-            } else {
-                f32x4 Rt = {0.f, 0.f, 0.f, 0.f};
-                for (int ta = w; ta < 4; ++ta)
-                    Rt = mac16(ld4col(M1 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B2 + l16 * MS + 16 * ta + 4 * lq), Rt);
-                float4 ng;
-                float dr[4];
+            for (int j = 0; j < 4; ++j) a.Ug[(t4 + j) * D + v0 + l16] = U[j];
+        } else {
+            f32x4 Rt = {0.f, 0.f, 0.f, 0.f};
+            for (int ta = w; ta < 4; ++ta)
+                Rt = mac16(ld4col(M1 + (16 * ta + 4 * lq) * MS + 16 * w + l16, MS), ld4(B2 + l16 * MS + 16 * ta + 4 * lq), Rt);
+            float4 ng;
+            float dr[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    dr[j] = bb[j] * Rt[j];
-                    a.dV[(t4 + j) * D + v0 + l16] = dr[j];
-                    const float sdb = lane_group_sum<16>(xv[j] * Rt[j]);   // xv: Uh
-                    if (l16 == 0) a.dbeta_part[(size_t)slice * n_tok + t4 + j] = ((lin >> (8 * j)) & 0xff) ? 0.f : sdb;
-                }
-                ng.x = -delta * gg[0] * dr[0]; ng.y = -delta * gg[1] * dr[1]; ng.z = -delta * gg[2] * dr[2]; ng.w = -delta * gg[3] * dr[3];
-                *reinterpret_cast<float4*>(B3 + l16 * MS + 16 * w + 4 * lq) = ng;
+            for (int j = 0; j < 4; ++j) {
+                dr[j] = bb[j] * Rt[j];
+                a.dV[(t4 + j) * D + v0 + l16] = dr[j];
+                const float sdb = lane_group_sum<16>(xv[j] * Rt[j]);   // xv: Uh
+                if (l16 == 0) a.dbeta_part[(size_t)slice * n_tok + t4 + j] = ((lin >> (8 * j)) & 0xff) ? 0.f : sdb;
             }
+            ng.x = -delta * gg[0] * dr[0]; ng.y = -delta * gg[1] * dr[1]; ng.z = -delta * gg[2] * dr[2]; ng.w = -delta * gg[3] * dr[3];
+            *reinterpret_cast<float4*>(B3 + l16 * MS + 16 * w + 4 * lq) = ng;
         }
         __syncthreads();
         // ---- 3: the chunk's contribution to the state ------------------------------------------------------------
-        {
-            if (DIR == 0) {
-                f32x4 AU = {0.f, 0.f, 0.f, 0.f};
-                for (int tb = 0; tb <= w; ++tb)
-                    AU = mac16(ld4(M2 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), AU);
+        if (DIR == 0) {
+            f32x4 AU = {0.f, 0.f, 0.f, 0.f};
+            for (int tb = 0; tb <= w; ++tb)
+                AU = mac16(ld4(M2 + (16 * w + l16) * MS + 16 * tb + 4 * lq), ld4(B1 + l16 * MS + 16 * tb + 4 * lq), AU);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) a.Uh[(t4 + j) * D + v0 + l16] = R[j] - AU[j];
-            }
+            for (int j = 0; j < 4; ++j) a.Uh[(t4 + j) * D + v0 + l16] = R[j] - AU[j];
+        }
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            const int kt = KT * w + t;
+            *reinterpret_cast<float4*>(a.ck + (gc * D + v0 + l16) * D + 16 * kt + 4 * lq) =
+                make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+            Sacc[t][0] *= gC; Sacc[t][1] *= gC; Sacc[t][2] *= gC; Sacc[t][3] *= gC;
+        }
+#pragma unroll 2
+        for (int tb = 0; tb < 4; ++tb) {   // token tiles outside: their operands serve all of the wavefront's state tiles
+            const float4 b2 = ld4((DIR ? B1 : B2) + l16 * MS + 16 * tb + 4 * lq);
+            const float4 b3 = DIR ? ld4(B3 + l16 * MS + 16 * tb + 4 * lq) : b2;
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
                 const int kt = KT * w + t;
-                *reinterpret_cast<float4*>(a.ck + (gc * D + v0 + l16) * D + 16 * kt + 4 * lq) =
-                    make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
-                Sacc[t][0] *= gC; Sacc[t][1] *= gC; Sacc[t][2] *= gC; Sacc[t][3] *= gC;
-            }
-#pragma unroll 2
-            for (int tb = 0; tb < 4; ++tb) {   // token tiles outside: their operands serve all of the wavefront's state tiles
-                const float4 b2 = ld4((DIR ? B1 : B2) + l16 * MS + 16 * tb + 4 * lq);
-                const float4 b3 = DIR ? ld4(B3 + l16 * MS + 16 * tb + 4 * lq) : b2;
-#pragma unroll
-                for (int t = 0; t < KT; ++t) {
-                    const int kt = KT * w + t;
-                    if (DIR == 0) {
-                        Sacc[t] = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
-                    } else {
-                        Sacc[t] = mac16(ld4col(Qs + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
-                        Sacc[t] = mac16(ld4col(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b3, Sacc[t]);
-                    }
+                if (DIR == 0) {
+                    Sacc[t] = mac16(ldkcol(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
+                } else {
+                    Sacc[t] = mac16(ldkcol(Qs + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b2, Sacc[t]);
+                    Sacc[t] = mac16(ldkcol(Ks + (16 * tb + 4 * lq) * KS + 16 * kt + l16, KS), b3, Sacc[t]);
                 }
             }
         }
-        __syncthreads();   // every read of the chunk's operands and of the old state is done
+        // the state for the next chunk's first phase (nothing reads it in between)
 #pragma unroll
         for (int t = 0; t < KT; ++t)
-            *reinterpret_cast<float4*>(St + l16 * KS + 16 * (KT * w + t) + 4 * lq) = make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
-        __syncthreads();
+            *reinterpret_cast<float4*>(St + l16 * SS + 16 * (KT * w + t) + 4 * lq) = make_float4(Sacc[t][0], Sacc[t][1], Sacc[t][2], Sacc[t][3]);
+        __syncthreads();   // every read of the chunk's operands is done, the new state is in place
+        if (!LY::two) __syncthreads();   // one place for the staged operands: they are replaced in between
     }
     if (DIR == 1 && a.dS0 != nullptr) {
 #pragma unroll
@@ -467,11 +536,8 @@ __global__ __launch_bounds__(512) void gdn_chunk_seq_kernel(const SeqArgs<T> a) 
     }
 }
 
-template <int D, int DIR>
-constexpr size_t seq_lds_bytes() {
-    return sizeof(float) * ((size_t)CB_C * (D + 4) * (DIR ? 2 : 1) + 2 * CB_C * CB_MS + CB_NV * (D + 4) + 5 * CB_NV * CB_MS +
-                            4 * CB_C + 32);
-}
+template <typename T, int D, int DIR>
+constexpr size_t seq_lds_bytes() { return SeqLds<T, D, DIR>::bytes; }
 template <int D>
 constexpr size_t prep_lds_bytes() { return sizeof(float) * (2 * (size_t)CB_C * (D + 4) + 2 * CB_C); }
 
@@ -837,7 +903,7 @@ nats_status launch_gdn_bwd_prep(const FwdPlan& pl, const void* Q, const void* K,
 template <typename T, int D, int DIR>
 static bool launch_seq_t(const FwdPlan& pl, const SeqArgs<T>& a, hipStream_t st) {
     auto kern = gdn_chunk_seq_kernel<T, D, DIR>;
-    constexpr size_t lds = seq_lds_bytes<D, DIR>();
+    constexpr size_t lds = seq_lds_bytes<T, D, DIR>();
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
         hipSuccess) return false;
     hipLaunchKernelGGL(kern, dim3((unsigned)(pl.BH * (D / CB_NV))), dim3(512), lds, st, a);
