@@ -587,8 +587,10 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     const size_t gc = (size_t)bh * n_chunks + chunk, tok0 = (size_t)bh * a.L + (size_t)chunk * CB_C;
     const float delta = a.delta ? 1.f : 0.f;
 
-    // Every global load of the block is issued here, in the order of use: the later stages' operands wait in
-    // registers (one block per CU: nothing else would hide their latency).
+    // The block's global loads: what stage 1 needs goes out first; the later stages' operands are asked for from
+    // inside stage 1's product loop, a few loads per step (the issue of a load costs a wavefront 100 cycles and more
+    // while the CU's miss queue is full; between matrix instructions the SIMD's other wavefront fills that time),
+    // and wait in registers (one block per CU: nothing else would hide their latency).
     constexpr int NPT = 64 * D / E / NT;       // 16-byte words of a [64][D] tile of T per thread
     auto put_rows_f32 = [&](float* dst, const float4 (&r)[NSH]) {   // [64][D] fp32 -> LDS rows of KS
 #pragma unroll
@@ -623,29 +625,37 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         for (int i = 0; i < NPT; ++i) dOreg[i] = reinterpret_cast<const u32x4*>(a.dO + tok0 * D)[tid + NT * i];
 #pragma unroll
         for (int i = 0; i < NSH; ++i) dRreg[i] = ld4(a.dR + tok0 * D + 4 * (size_t)(tid + NT * i));
+    }
+    auto issue_later = [&](int step) {   // step: a compile-time constant where it is called
+        if (step == 0) {
 #pragma unroll
-        for (int i = 0; i < NSH; ++i) Ureg[i] = ld4(a.Ug + tok0 * D + 4 * (size_t)(tid + NT * i));
+            for (int i = 0; i < NSH; ++i) Ureg[i] = ld4(a.Ug + tok0 * D + 4 * (size_t)(tid + NT * i));
+        } else if (step == 1) {
 #pragma unroll
-        for (int i = 0; i < NSH; ++i) dS1a[i] = ld4(dS1g + 4 * (size_t)(tid + NT * i));
+            for (int i = 0; i < NSH; ++i) dS1a[i] = ld4(dS1g + 4 * (size_t)(tid + NT * i));
+        } else if (step == 2) {
 #pragma unroll
-        for (int i = 0; i < NSH; ++i) dS1b[i] = (D > 64) ? ld4(dS1g + (size_t)64 * D + 4 * (size_t)(tid + NT * i)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = 0; i < NSH; ++i) dS1b[i] = (D > 64) ? ld4(dS1g + (size_t)64 * D + 4 * (size_t)(tid + NT * i)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        } else if (step == 3) {
 #pragma unroll
-        for (int i = 0; i < NPT; ++i) {
-            Kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[tid + NT * i];
-            Qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[tid + NT * i];
-        }
+            for (int i = 0; i < NPT; ++i) {
+                Kreg[i] = reinterpret_cast<const u32x4*>(a.K + tok0 * D)[tid + NT * i];
+                Qreg[i] = reinterpret_cast<const u32x4*>(a.Q + tok0 * D)[tid + NT * i];
+            }
+        } else if (step == 4) {
 #pragma unroll
-        for (int s = 0; s < NTL; ++s) {
-            const int t = w + NW * s < 10 ? w + NW * s : 0;
-            const int ta = (0x3333222110 >> (4 * t)) & 15, tb = (0x3210210100 >> (4 * t)) & 15;
+            for (int s = 0; s < NTL; ++s) {
+                const int t = w + NW * s < 10 ? w + NW * s : 0;
+                const int ta = (0x3333222110 >> (4 * t)) & 15, tb = (0x3210210100 >> (4 * t)) & 15;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const size_t off = gc * (CB_C * CB_C) + (16 * ta + 4 * lq + j) * CB_C + 16 * tb + l16;
-                atv[s][j] = a.o.At[off];
-                pmv[s][j] = a.o.Pm[off];
+                for (int j = 0; j < 4; ++j) {
+                    const size_t off = gc * (CB_C * CB_C) + (16 * ta + 4 * lq + j) * CB_C + 16 * tb + l16;
+                    atv[s][j] = a.o.At[off];
+                    pmv[s][j] = a.o.Pm[off];
+                }
             }
         }
-    }
+    };
     // ---- stage 1: S0, dO', dR ------------------------------------------------------------------------------
 #pragma unroll
     for (int i = 0; i < NS0; ++i) {
@@ -664,8 +674,9 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
         Gdk[ta] = f32x4{0.f, 0.f, 0.f, 0.f};
         Gu[ta] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-#pragma unroll 2
+#pragma unroll
     for (int kv = 0; kv < D / 16; ++kv) {
+        issue_later(kv);
         const float4 bs = ld4col(RA + (16 * kv + 4 * lq) * KS + 16 * w + l16, KS);
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta) {
@@ -673,6 +684,8 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
             Gdk[ta] = mac16(ld4(RC + (16 * ta + l16) * KS + 16 * kv + 4 * lq), bs, Gdk[ta]);
         }
     }
+#pragma unroll
+    for (int step = D / 16; step < 5; ++step) issue_later(step);
     __syncthreads();
     // ---- stage 2: U and the first 64 rows of dS1; dP and dAt ---------------------------------------------------
     float dot = 0.f;
@@ -792,6 +805,12 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
     }
     esum = lane_group_sum<64>(esum);
     if (lane == 0) ge[w] = esum;
+    // the softmax branch's share of dQ, which the result is added to: asked for before the products below
+    float oldq[4][4];
+#pragma unroll
+    for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) oldq[ta][j] = a.dQ[(tok0 + 16 * ta + 4 * lq + j) * D + 16 * w + l16];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
         const float4 kc = kcs[tb], qc = qcs[tb];
@@ -808,7 +827,7 @@ __global__ __launch_bounds__(D * 4) void gdn_chunk_grads_kernel(const GradArgs<T
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const size_t off = (tok0 + 16 * ta + 4 * lq + j) * D + 16 * w + l16;
-            a.dQ[off] += dQa[ta][j];   // the softmax branch's share is there already
+            a.dQ[off] = oldq[ta][j] + dQa[ta][j];
             a.dK[off] = dKa[ta][j];
         }
     }
