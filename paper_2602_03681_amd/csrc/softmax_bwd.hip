@@ -317,6 +317,8 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dkv_mfma_kernel(
 #pragma unroll 1
     for (int i0 = i_lo; i0 < i_hi; i0 += SBM_QT) {
         __syncthreads();   // the previous tile has been read by everyone
+        // (fetching the next tile into registers during the products, as the dQ kernel does, costs this kernel more
+        // in registers, which it has none to spare of, than the exposed load costs: 0.26 against 0.22 ms)
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             const int e = tid + 256 * i, q = e / (D / 8), c8 = e % (D / 8);
@@ -463,26 +465,37 @@ __global__ __launch_bounds__(256, 2) void softmax_bwd_dq_mfma_kernel(
 #pragma unroll
     for (int md = 0; md < MD; ++md) accQ[md] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // A key tile is fetched into registers while the tile before it is multiplied.
+    u32x4 rk[NPC], rv[NPC];
+    auto fetch_tile = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            const int e = tid + 256 * i, key = e / (D / 8), c8 = e % (D / 8);
+            rk[i] = u32x4{0u, 0u, 0u, 0u};
+            rv[i] = u32x4{0u, 0u, 0u, 0u};
+            if (c0 + key < n_hi) {   // rows past the block's bound are not initialised: they enter as zeros
+                const size_t src = (tokb + c0 + key) * D + 8 * c8;
+                rk[i] = *reinterpret_cast<const u32x4*>(Kc + src);
+                rv[i] = *reinterpret_cast<const u32x4*>(Vc + src);
+            }
+        }
+    };
+    if (n_hi > 0) fetch_tile(0);
 #pragma unroll 1
     for (int c0 = 0; c0 < n_hi; c0 += 64) {
         __syncthreads();   // the previous tile has been read by everyone
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             const int e = tid + 256 * i, key = e / (D / 8), c8 = e % (D / 8);
-            u32x4 rk = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
-            if (c0 + key < n_hi) {   // rows past the block's bound are not initialised: they enter as zeros
-                const size_t src = (tokb + c0 + key) * D + 8 * c8;
-                rk = *reinterpret_cast<const u32x4*>(Kc + src);
-                rv = *reinterpret_cast<const u32x4*>(Vc + src);
-            }
-            *reinterpret_cast<u32x4*>(Ks + key * RS + 8 * c8) = rk;
-            *reinterpret_cast<u32x4*>(Vs + key * RS + 8 * c8) = rv;
-            const half8 hk = bf16x8_to_half8(rk);
+            *reinterpret_cast<u32x4*>(Ks + key * RS + 8 * c8) = rk[i];
+            *reinterpret_cast<u32x4*>(Vs + key * RS + 8 * c8) = rv[i];
+            const half8 hk = bf16x8_to_half8(rk[i]);
             const int col = sbm_col(key);
 #pragma unroll
             for (int j = 0; j < 8; ++j) KT[sbm_at(8 * c8 + j, col, TS)] = hk[j];
         }
         __syncthreads();
+        if (c0 + 64 < n_hi) fetch_tile(c0 + 64);
         f32x4 accS[4], accP[4];
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) { accS[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; accP[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
