@@ -57,7 +57,7 @@ __device__ __forceinline__ float quad_max(float x) {
 // STATS: what the backward pass needs from this branch's forward, to fp32 accuracy: the weights enter the second
 // product (and their sum) as the sum of two fp16 terms, and only O_nla_out (fp32) and lse_out are written; no merge.
 template <int D, bool chunk_routing, bool STATS>
-__global__ __launch_bounds__(FL_THREADS, STATS ? 1 : FL_OCC) void flash_softmax_kernel(
+__global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
