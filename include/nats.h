@@ -86,7 +86,11 @@ typedef struct nats_fwd_params {
     int32_t B, H;          /* batch, heads (each (b,h) has its own mask: Section 4.3)          */
     int32_t L;             /* tokens; must be a positive multiple of C                          */
     int32_t d;             /* head dim, d_k = d_v = d, 64 or 128                                */
-    int32_t C;             /* chunk size of the chunkwise linear branch (Eq. 6-7); 64           */
+    int32_t C;             /* chunk size, 64 or 128.  Routing per token: the result does not depend on it (the
+                              chunkwise form of Eq. 6-7 is exact; the kernels use their own chunk of 64).
+                              Routing per chunk: tokens per routing decision (mask [B,H,L/C]); C = 128 (the chunk-size
+                              ablation of Section 5) runs the forward on the token-by-token kernels, whatever the
+                              dtype; the backward covers C = 64                                    */
     int32_t dtype;         /* nats_dtype of Q, K, V, O                                          */
     float softmax_scale;   /* logits = scale * q.k ; <= 0 selects 1/sqrt(d)                     */
     float la_scale;        /* o_la = la_scale * S q (Eq. 5 has none); <= 0 selects 1            */

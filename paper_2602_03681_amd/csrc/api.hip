@@ -70,7 +70,11 @@ ProfScope::~ProfScope() {
 }
 
 // bf16 tensors take the chunkwise MFMA kernels unless fp32 arithmetic is asked for
-static bool uses_chunk_path(const FwdPlan& pl) { return pl.dtype == NATS_BF16 && pl.math == NATS_MATH_AUTO; }
+// (routing chunks of 128 tokens run on the token-by-token kernels: the matrix-core path hands a chunk's provisional
+// state on inside its own chunk of 64 only)
+static bool uses_chunk_path(const FwdPlan& pl) {
+    return pl.dtype == NATS_BF16 && pl.math == NATS_MATH_AUTO && !(pl.routing == NATS_ROUTE_CHUNK && pl.RC != 64);
+}
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -91,7 +95,9 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         set_error("B*H*L must fit in 31 bits");
         return NATS_ERR_SHAPE;
     }
-    if (p->C != 64) { set_error("chunk size C=%d has no kernel in this build (64 only)", p->C); return NATS_ERR_UNSUPPORTED; }
+    // C: with routing per token the result does not depend on it (the chunkwise form is exact for any chunk, and the
+    // kernels use their own of 64); with routing per chunk it is the number of tokens per routing decision
+    if (p->C != 64 && p->C != 128) { set_error("chunk size C=%d has no kernel in this build (64 or 128)", p->C); return NATS_ERR_UNSUPPORTED; }
     if (p->combine_mode < 0 || p->combine_mode > 2) {
         set_error("combine_mode must be 0, 1 or 2 (got %d)", p->combine_mode);
         return NATS_ERR_SHAPE;
@@ -137,7 +143,7 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
     }
     pl->inner_chunk = p->inner_chunk;
     pl->qk_per_out_head = 0;   // set by the call: whether the softmax heads have queries and keys of their own
-    pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = p->C; pl->BH = p->B * p->H;
+    pl->B = p->B; pl->H = p->H; pl->L = p->L; pl->d = p->d; pl->C = 64; pl->RC = p->C; pl->BH = p->B * p->H;
     pl->BHG = pl->BH * pl->G;
     pl->dtype = p->dtype;
     pl->math = p->math;
@@ -225,6 +231,10 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
     }
     if (pl->G != 1) { set_error("the backward pass has no head grouping (group %d given)", pl->G); return NATS_ERR_UNSUPPORTED; }
     if (pl->inner_chunk != 0) { set_error("the backward pass covers inner_chunk 0 only (got %d)", pl->inner_chunk); return NATS_ERR_UNSUPPORTED; }
+    if (pl->routing == NATS_ROUTE_CHUNK && pl->RC != 64) {
+        set_error("the backward pass with routing per chunk covers chunks of 64 tokens (C=%d given)", pl->RC);
+        return NATS_ERR_UNSUPPORTED;
+    }
     plan_bwd(*pl, bp);
     return NATS_OK;
 }

@@ -370,7 +370,7 @@ nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K
                     pl.inner_chunk == 1};
     const ScanArgs<bf16_t> sc{mask, (const bf16_t*)K_sm, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
                               (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT,
-                              pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head};
+                              pl.routing == NATS_ROUTE_CHUNK ? 6 : 0, pl.G, pl.qk_per_out_head};   // (this path: routing chunks of 64)
     const int scan_segs = (pl.L + SCAN_SEG - 1) / SCAN_SEG, scan_blocks = scan_segs * pl.BHG;
     dim3 grid((unsigned)(scan_blocks + (pl.L / CH) * ((pl.BH + 7) & ~7)));
     if (pl.d == 64) hipLaunchKernelGGL(gdn_chunk_inv_kernel<64>, grid, dim3(INV_THREADS), 0, st, a, sc, scan_segs, scan_blocks);

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
     const float* __restrict__ alpha, const float* __restrict__ beta, const uint8_t* __restrict__ mask,
     const float* __restrict__ S0, float* __restrict__ S_final, float* __restrict__ O_la,
     float* __restrict__ snap, int L, float la_scale, int linear_op, int freeze_on_softmax, int G,
-    int no_inner_output) {
+    int no_inner_output, int RC) {
     constexpr int DP = D / 4;       // columns of a row per lane
     constexpr int DPP = DP + 4;     // padded quarter stride: the four quarters land in different banks
     __shared__ __align__(16) float s_k[REC_TT][4 * DPP];
@@ -52,12 +52,12 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
         for (int c = 0; c < DP; ++c) S[c] = 0.f;
     }
 
-    // Routing per chunk (snap != nullptr; mask holds one byte per chunk of 64 tokens): every token
+    // Routing per chunk (snap != nullptr; mask holds one byte per chunk of RC tokens, 64 or 128): every token
     // of a chunk is written (the intra-chunk part is computed for every chunk); at the end of a softmax
     // chunk the row goes back to its value at the chunk's start, kept in snap, times the chunk's decay.
     const bool chunk_mask = snap != nullptr;
     float* my_snap = chunk_mask ? snap + ((size_t)bh * D + row) * D + part * DP : nullptr;
-    const uint8_t* mask_c = mask + (size_t)(bh / G) * (L / 64);
+    const uint8_t* mask_c = mask + (size_t)(bh / G) * (L / RC);
     float chunk_decay = 1.f;
     // no_inner_output (routing per chunk only): the output reads the state carried into the chunk, decayed up to
     // the query, and nothing the chunk's own tokens wrote; that state lives in Sc beside the provisional one
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
             const float* kr = &s_k[i][part * DPP];
             const float* qr = &s_q[i][part * DPP];
             float o = 0.f;
-            if (chunk_mask && ((t0 + i) & 63) == 0) {   // chunk start (uniform)
+            if (chunk_mask && ((t0 + i) & (RC - 1)) == 0) {   // chunk start (uniform)
 #pragma unroll
                 for (int c = 0; c < DP; c += 4)
                     *reinterpret_cast<float4*>(my_snap + c) = make_float4(S[c], S[c + 1], S[c + 2], S[c + 3]);
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(REC_THREADS) void gdn_recurrent_kernel(
             }
             o = row_sum(o);
             if (part == 0) O_la[(base + t0 + i) * D + row] = la_scale * o;
-            if (chunk_mask && ((t0 + i) & 63) == 63 && mask_c[(t0 + i) >> 6]) {   // end of a softmax chunk
+            if (chunk_mask && ((t0 + i) & (RC - 1)) == RC - 1 && mask_c[(t0 + i) / RC]) {   // end of a softmax chunk
                 if (freeze_on_softmax) chunk_decay = 1.f;   // variant: a softmax chunk leaves the state as it found it
 #pragma unroll
                 for (int c = 0; c < DP; c += 4) {
@@ -176,11 +176,11 @@ static void launch_rec(const FwdPlan& pl, const void* Q, const void* K, const vo
     if (pl.d == 64)
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 64>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1, pl.RC);
     else
         hipLaunchKernelGGL((gdn_recurrent_kernel<T, 128>), grid, dim3(REC_THREADS), 0, st, (const T*)Q,
                            (const T*)K, (const T*)V, alpha, beta, mask, S0, S_final, O_la, snap, pl.L, pl.la_scale,
-                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1);
+                           pl.linear_op, pl.freeze_on_softmax, pl.G, pl.inner_chunk == 1, pl.RC);
 }
 
 nats_status launch_gdn_recurrent(const FwdPlan& pl, const void* Q, const void* K, const void* V,

@@ -174,7 +174,8 @@ constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse swee
 
 // Resolved forward problem handed to the kernel launchers.
 struct FwdPlan {
-    int B, H, L, d, C, BH;
+    int B, H, L, d, C, BH;   // C: the kernels' own chunk (64)
+    int RC;                  // tokens per routing decision with routing per chunk (64 or 128; p->C)
     // head grouping (Section 4.3): G output heads (own V, own softmax branch, own state rows) per linear head (own
     // Q, K, alpha, beta, mask).  BHG = BH * G output heads; qk_per_out_head: the softmax branch's queries and keys
     // are given per output head (otherwise it uses the linear head's)

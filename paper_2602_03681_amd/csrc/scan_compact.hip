@@ -24,12 +24,12 @@ nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const vo
     if (pl.dtype == NATS_BF16) {
         const ScanArgs<bf16_t> a{mask, (const bf16_t*)K, (const bf16_t*)V, pl.L, pl.d, cnt, idx, n_s, (bf16_t*)Kc,
                                  (bf16_t*)Vc, (bf16_t*)Kc_user, (bf16_t*)Vc_user, cap_user, (half_t*)VhT,
-                                 pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head};
+                                 pl.routing == NATS_ROUTE_CHUNK ? (pl.RC == 128 ? 7 : 6) : 0, pl.G, pl.qk_per_out_head};
         hipLaunchKernelGGL(scan_compact_kernel<bf16_t>, grid, dim3(SCAN_THREADS), 0, st, a);
     } else {
         const ScanArgs<float> a{mask, (const float*)K, (const float*)V, pl.L, pl.d, cnt, idx, n_s, (float*)Kc,
                                 (float*)Vc, (float*)Kc_user, (float*)Vc_user, cap_user, (half_t*)VhT,
-                                pl.routing == NATS_ROUTE_CHUNK, pl.G, pl.qk_per_out_head};
+                                pl.routing == NATS_ROUTE_CHUNK ? (pl.RC == 128 ? 7 : 6) : 0, pl.G, pl.qk_per_out_head};
         hipLaunchKernelGGL(scan_compact_kernel<float>, grid, dim3(SCAN_THREADS), 0, st, a);
     }
     return check_launch("scan_compact");

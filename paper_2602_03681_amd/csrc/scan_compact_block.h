@@ -25,7 +25,8 @@ struct ScanArgs {
     T *Kc, *Vc, *Kc_user, *Vc_user;
     int cap_user;
     half_t* VhT;
-    int chunk_mask, G, k_per_out_head;
+    int chunk_mask;   // 0: one mask byte per token; otherwise log2 of the routing chunk (6 or 7): one byte per chunk
+    int G, k_per_out_head;
 };
 
 // One block: SCAN_SEG tokens (segment number seg_no) of output head bo.  SCAN_THREADS threads.
@@ -53,15 +54,15 @@ __device__ __forceinline__ void scan_compact_block(const ScanArgs<T>& a, const i
     const int bk = k_per_out_head ? bo : bh;
     const int seg0 = seg_no * SCAN_SEG;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // chunk_mask: one mask byte per chunk of 64 tokens (routing per chunk: every token of a softmax
+    // chunk_mask: one mask byte per chunk of 2^chunk_mask tokens (routing per chunk: every token of a softmax
     // chunk is a softmax token); otherwise one byte per token
-    const uint8_t* m = mask + (size_t)bh * (chunk_mask ? L / 64 : L);
+    const uint8_t* m = mask + (size_t)bh * (chunk_mask ? L >> chunk_mask : L);
 
     // ---- 1. softmax tokens in front of this segment -----------------------------------
     int before = 0;
     {
         if (chunk_mask) {   // a few hundred bytes at most, at no particular alignment
-            for (int i = tid; i < seg0 / 64; i += SCAN_THREADS) before += m[i] ? 64 : 0;
+            for (int i = tid; i < (seg0 >> chunk_mask); i += SCAN_THREADS) before += m[i] ? (1 << chunk_mask) : 0;
         } else {
             const uint4* m16 = reinterpret_cast<const uint4*>(m);  // seg0 is a multiple of 1024
             for (int i = tid; i < seg0 / 16; i += SCAN_THREADS) {
@@ -80,7 +81,7 @@ __device__ __forceinline__ void scan_compact_block(const ScanArgs<T>& a, const i
     const int t0 = seg0 + tid * 4;
     uint32_t w = 0;
     if (t0 < L)   // L % 4 == 0: a word is all in or all out; its 4 tokens lie in one chunk
-        w = chunk_mask ? (m[t0 >> 6] ? 0x01010101u : 0u) : *reinterpret_cast<const uint32_t*>(m + t0);
+        w = chunk_mask ? (m[t0 >> chunk_mask] ? 0x01010101u : 0u) : *reinterpret_cast<const uint32_t*>(m + t0);
     const int mine = nonzero_bytes(w);
     const int incl = wave_inclusive_scan_i32(mine);
     if (lane == 63) s_wave[wave] = incl;

@@ -53,10 +53,12 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
     for (int c = 0; c < DP; ++c) { q[c] *= scale; acc[c] = 0.f; }
     float m_run = -INFINITY, l_run = 0.f;
 
-    // Routing per token: the first cnt[t] compacted rows are visible.  Routing per chunk: a block is
-    // exactly one chunk (64 queries); its queries see the compacted rows of earlier chunks, cnt at the
-    // last token before the chunk, and then, causally, the chunk's own rows of K and V.
-    const int my_cnt = chunk_routing ? (q0 > 0 ? cnt[tokb_lin + q0 - 1] : 0) : cnt[tokb_lin + t];
+    // Routing per token: the first cnt[t] compacted rows are visible.  Routing per chunk (chunk_routing = tokens
+    // per routing chunk, 64 or 128): a block's 64 queries lie in one chunk, which starts at cs; they see the
+    // compacted rows of earlier chunks, cnt at the last token before the chunk, and then, causally, the chunk's own
+    // rows of K and V.
+    const int cs = chunk_routing ? (q0 & ~(chunk_routing - 1)) : 0;
+    const int my_cnt = chunk_routing ? (cs > 0 ? cnt[tokb_lin + cs - 1] : 0) : cnt[tokb_lin + t];
     const int n_hi = chunk_routing ? my_cnt : cnt[tokb_lin + q0 + SM_BM - 1];  // cnt is non-decreasing: the tile's bound
 
     // One tile of SM_BN rows of (Ks, Vs) starting at row0, the first n_rows of which exist; this
@@ -122,8 +124,8 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_fp32_kernel(
         }
     };
     for (int c0 = 0; c0 < n_hi; c0 += SM_BN) tile(Kc, tokb, Vc, c0, min(SM_BN, n_hi - c0), my_cnt - c0);
-    if (chunk_routing && own_chunk)   // the block's own chunk, rows q0 .. q0 + 63 of K and V: query row r sees rows <= r
-        for (int d0 = 0; d0 < SM_BM; d0 += SM_BN) tile(K, tokb_qk, V, q0 + d0, SM_BN, r + 1 - d0);
+    if (chunk_routing && own_chunk)   // the chunk's own rows cs .. q0 + 63 of K and V: query t sees rows <= t
+        for (int row0 = cs; row0 < q0 + SM_BM; row0 += SM_BN) tile(K, tokb_qk, V, row0, SM_BN, t + 1 - row0);
 
     // ---- epilogue: normalise, optional branch outputs, merge, store -----------------------
     const float inv_l = (l_run > 0.f) ? 1.f / l_run : 0.f;
@@ -180,12 +182,12 @@ static void launch_sm(const FwdPlan& pl, const void* Q, const void* Kc, const vo
     dim3 grid(pl.L / SM_BM, pl.BHG);
     if (pl.d == 64)
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 64>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
-                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
+                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK ? pl.RC : 0, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
                            pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
     else
         hipLaunchKernelGGL((softmax_fp32_kernel<T, 128>), grid, dim3(SM_THREADS), 0, st, (const T*)Q,
-                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK, cnt,
+                           (const T*)Kc, (const T*)Vc, (const T*)K, (const T*)V, pl.routing == NATS_ROUTE_CHUNK ? pl.RC : 0, cnt,
                            O_la, w_nla, w_la, (T*)O, O_nla_out, lse_out,
                            pl.L, pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
 }

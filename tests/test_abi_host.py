@@ -195,6 +195,9 @@ def test_backward_validation(lib):
     ptrs[7] = ptrs[0]                                  # dQ aliases Q
     assert call(p, ptrs) == E_SHAPE
     assert call(p, ws_bytes=need - 1) == E_WS
+    # routing chunks of 128 tokens: the forward takes them, the backward covers 64
+    assert nb.fwd_workspace_bytes(good_params(C=128, routing=nb.NATS_ROUTE_CHUNK)) > 0
+    assert call(good_params(C=128, routing=nb.NATS_ROUTE_CHUNK)) == E_UNSUP
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

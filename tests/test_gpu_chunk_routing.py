@@ -58,6 +58,37 @@ def test_chunk_routing_eq21_initial_state_and_scales(dtype):
     check_all(x, dtype, r, ref)
 
 
+@pytest.mark.parametrize("kind", ["bernoulli", "alternate", "all_softmax"])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 128)])
+def test_routing_chunks_of_128_tokens(dtype, d, kind):
+    """One routing decision per 128 tokens (the chunk-size ablation of Section 5): the mask holds L / 128 bytes, a
+    softmax chunk's provisional state lives for 128 tokens, its queries see all 128 of its own keys causally.  Runs on
+    the token-by-token kernels (for bf16 tensors as well)."""
+    B, H, L = 2, 2, 640
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.1, seed=60 + d)
+    x["mask"] = make_chunk_mask(B, H, L // 128, 0.4, 67 + d, kind)
+    g = to_dev(x, dtype)
+    S0 = (np.random.default_rng(61).standard_normal((B, H, d, d)) * 0.05).astype(np.float32)
+    r = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 128, routing=nb.NATS_ROUTE_CHUNK,
+                                want=ALL_OUT, initial_state=torch.from_numpy(S0).cuda())
+    torch.cuda.synchronize()
+    ref = c_oracle.fwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], chunk_routing=128, S0=S0.astype(np.float64))
+    check_all(x, dtype, r, ref)
+
+
+def test_routing_chunks_of_128_tokens_inner_part_by_one_operation():
+    x = make_fwd_inputs(1, 2, 512, 64, "f32", 0.1, seed=62)
+    x["mask"] = make_chunk_mask(1, 2, 4, 0.5, 63, "bernoulli")
+    g = to_dev(x, "f32")
+    from oracle import nats_oracle as no
+    for inner in (1, 2):
+        O = nats.hybrid_attn_fwd_ex(g["Q"], g["K"], g["V"], g["alpha"], g["beta"], g["mask"], 128,
+                                    routing=nb.NATS_ROUTE_CHUNK, inner_chunk=inner, want=())["O"]
+        torch.cuda.synchronize()
+        ref = no.hybrid_fwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 128, inner=inner)["O"]
+        assert rel_err(host(O), ref, stored("f32")) <= TOL["f32"], inner
+
+
 def test_chunk_routing_fp32_math_on_bf16_tensors():
     x = inputs(1, 2, 256, 64, "bf16", 0.4, seed=53)
     check_all(x, "bf16", run_ex(x, "bf16", math=nb.NATS_MATH_FP32), oracle(x))
