@@ -274,7 +274,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 109; }
+int nats_abi_version(void) { return 110; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
