@@ -308,42 +308,61 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_split_kernel(
     float m_run = -INFINITY, l_run = 0.f;
     const T* Kb = k_cache + (size_t)bh * cap * D + lk * EPL;
     const T* Vb = v_cache + (size_t)bh * cap * D + lk * EPL;
-    for (int c0 = c_lo + sg; c0 < c_hi; c0 += NSG * UNROLL) {
-        float kf[UNROLL][EPL], vf[UNROLL][EPL], sc[UNROLL];
+    // Rows as they come from memory (16 bytes of a row per lane); the next group of rows is asked for before the
+    // current one is used, so that a wavefront always has loads in flight.
+    typedef uint4 raw_t;
+    static_assert(sizeof(T) * EPL == 16, "one 16-byte word per lane and row");
+    auto load_rows = [&](int c0, raw_t (&kr)[UNROLL], raw_t (&vr)[UNROLL]) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int c = c0 + u * NSG;
-            if (c < c_hi) {
-                Vec16<T>::load(Kb + (size_t)c * D, kf[u]);
-                Vec16<T>::load(Vb + (size_t)c * D, vf[u]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < EPL; ++j) { kf[u][j] = 0.f; vf[u][j] = 0.f; }
-            }
+            const int c = min(c0 + u * NSG, c_hi - 1);   // rows past the end repeat the last one; masked below
+            kr[u] = *reinterpret_cast<const raw_t*>(Kb + (size_t)c * D);
+            vr[u] = *reinterpret_cast<const raw_t*>(Vb + (size_t)c * D);
         }
-        float bm = -INFINITY;
+    };
+    auto use_rows = [&](int c0, const raw_t (&kr)[UNROLL], const raw_t (&vr)[UNROLL]) {
+        float sc[UNROLL], bm = -INFINITY;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            float kf[EPL];
+            Vec16<T>::unpack(kr[u], kf);
             float dot = 0.f;
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) dot += qf[j] * kf[u][j];
+            for (int j = 0; j < EPL; ++j) dot += qf[j] * kf[j];
             dot = lane_group_sum<LPK>(dot);
             sc[u] = (c0 + u * NSG < c_hi) ? dot : -INFINITY;
             bm = fmaxf(bm, sc[u]);
         }
         const float m_new = fmaxf(m_run, bm);   // finite: row c0 exists
-        const float corr = expf(m_run - m_new);
+        const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * 1.44269504088896341f);   // exp2(-inf) = 0
         l_run *= corr;
 #pragma unroll
         for (int j = 0; j < EPL; ++j) acc[j] *= corr;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const float pw = expf(sc[u] - m_new);
+            const float pw = __builtin_amdgcn_exp2f((sc[u] - m_new) * 1.44269504088896341f);
             l_run += pw;
+            float vf[EPL];
+            Vec16<T>::unpack(vr[u], vf);
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) acc[j] += pw * vf[u][j];
+            for (int j = 0; j < EPL; ++j) acc[j] += pw * vf[j];
         }
         m_run = m_new;
+    };
+    {
+        raw_t ka[UNROLL], va[UNROLL], kb2[UNROLL], vb2[UNROLL];
+        constexpr int STEP = NSG * UNROLL;
+        int c0 = c_lo + sg;
+        if (c0 < c_hi) load_rows(c0, ka, va);
+        while (c0 < c_hi) {
+            if (c0 + STEP < c_hi) load_rows(c0 + STEP, kb2, vb2);
+            use_rows(c0, ka, va);
+            c0 += STEP;
+            if (c0 >= c_hi) break;
+            if (c0 + STEP < c_hi) load_rows(c0 + STEP, ka, va);
+            use_rows(c0, kb2, vb2);
+            c0 += STEP;
+        }
     }
     if (lk == 0) { s_m[sg] = m_run; s_l[sg] = l_run; }
 #pragma unroll

@@ -111,6 +111,9 @@ struct Vec16;
 template <>
 struct Vec16<float> {
     static constexpr int N = 4;
+    __device__ __forceinline__ static void unpack(const uint4 v, float* out) {
+        out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y); out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
+    }
     __device__ __forceinline__ static void load(const float* p, float* out) {
         float4 v = *reinterpret_cast<const float4*>(p);
         out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
@@ -122,6 +125,15 @@ struct Vec16<float> {
 template <>
 struct Vec16<bf16_t> {
     static constexpr int N = 8;
+    // a 16-byte word as it came from memory -> floats (for loads that are used later than they are issued)
+    __device__ __forceinline__ static void unpack(const uint4 v, float* out) {
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
     __device__ __forceinline__ static void load(const bf16_t* p, float* out) {
         uint4 v = *reinterpret_cast<const uint4*>(p);
         uint32_t w[4] = {v.x, v.y, v.z, v.w};
