@@ -169,8 +169,9 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
         pl->off_snap = off; off = align_up(off + (size_t)pl->BHG * pl->d * pl->d * 4, 256);
     }
     if (uses_chunk_path(*pl)) {   // per-chunk operands of the chunkwise linear branch
-        pl->off_tf = off;   off = align_up(off + n_tok * pl->C * 2, 256);    // T'' fp16
-        pl->off_p = off;    off = align_up(off + n_tok * pl->C * 2, 256);    // P fp16
+        const size_t tri = n_tok / pl->C * TRI_FRAG_HALFS * 2;               // lower triangular, fp16, per chunk
+        pl->off_tf = off;   off = align_up(off + tri, 256);                  // T''
+        pl->off_p = off;    off = align_up(off + tri, 256);                  // P
         pl->off_gamv = off; off = align_up(off + n_tok * 4, 256);
         pl->off_kdv = off;  off = align_up(off + n_tok * 4, 256);
         pl->off_gam = off;  off = align_up(off + (n_tok / pl->C) * 4, 256);

@@ -18,9 +18,10 @@
 //
 // Output format, fp16, "fragment-major": both matrices are written in the order in which a wavefront of
 // the state-carrying kernel reads them as MFMA operands (row of the lane, 8 contraction slots), so that
-// a fragment is one contiguous 1 KiB.  With lane = 16 lq + l16 and token tile tw = 0..3:
-//   TF [chunk][tw][ks < 2][lane][s < 8] = T''[r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
-//   PF [chunk][tw][ks < 2][lane][s < 8] = P  [r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
+// a fragment is one contiguous 1 KiB.  With lane = 16 lq + l16, token tile tw = 0..3 and fragment number
+// f = tri_frag(tw, ks) (the two fragments above the diagonal, tw < 2 with ks = 1, are left out: 6 per matrix):
+//   TF [chunk][f][lane][s < 8] = T''[r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
+//   PF [chunk][f][lane][s < 8] = P  [r = 16 tw + l16][i = 32 ks + 16 (s / 4) + 4 lq + s % 4]
 //   gamv[chunk][64], kdv[chunk][64], gamC[chunk]   (fp32)
 // The contraction slots of a lane stand for tokens 4 lq .. 4 lq + 3 of two neighbouring 16-token tiles:
 // that is how a lane holds two accumulator tiles of a product over tokens, so the other operand of such a
@@ -60,9 +61,10 @@ struct InvLds {
     static constexpr int bytes = o_gate + 4 * CH * 4;
 };
 
-// offset (in halves) of element (r, i) of a 64 x 64 operand in the fragment-major layout above; i a multiple of 4
+// offset (in halves) of element (r, i) of a 64 x 64 operand in the fragment-major layout above; i a multiple of 4,
+// (r, i) not in the two fragments that are left out
 __device__ __forceinline__ int frag_off(int r, int i) {
-    return ((((r >> 4) * 2 + (i >> 5)) * 64) + 16 * ((i >> 2) & 3) + (r & 15)) * 8 + 4 * ((i >> 4) & 1) + (i & 3);
+    return ((tri_frag(r >> 4, i >> 5) * 64) + 16 * ((i >> 2) & 3) + (r & 15)) * 8 + 4 * ((i >> 4) & 1) + (i & 3);
 }
 
 struct InvArgs {
@@ -194,7 +196,7 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
         constexpr int NJ = 3;
         const int ja[NJ] = {a0, a1, a0};
         const int jb[NJ] = {0, (wave == 3) ? 3 : 1, (wave < 2) ? 2 : 0};
-        half_t* Pc = PF + gc * (CH * CH);
+        half_t* Pc = PF + gc * TRI_FRAG_HALFS;
         f32x4 accK[NJ], accP[NJ];
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj) {
@@ -257,9 +259,9 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
                 *reinterpret_cast<half4*>(Pc + frag_off(r, 16 * b + 4 * lq)) = to_half4(pv);
             }
         }
-        // the 6 tiles of P above the diagonal are zeros: (0,1) (0,2) (0,3) (1,2) (1,3) (2,3)
-        for (int z = wave; z < 6; z += 4) {
-            const int a = (0x211000 >> (4 * z)) & 15, b = (0x332321 >> (4 * z)) & 15;
+        // the tiles of P above the diagonal inside the stored fragments are zeros: (0,1) and (2,3)
+        if (wave < 2) {
+            const int a = 2 * wave, b = a + 1;
             half4 zero = {0, 0, 0, 0};
             *reinterpret_cast<half4*>(Pc + frag_off(16 * a + l16, 16 * b + 4 * lq)) = zero;
         }
@@ -321,14 +323,16 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
     }
     __syncthreads();   // T complete
     // (c) T'' = T diag(b'), fp16, straight to global memory in fragment order: thread e writes the 4-element
-    //     piece e of the chunk's 8 KiB, so a wavefront's store is one contiguous run.
+    //     piece e of the chunk's 6 KiB, so a wavefront's store is one contiguous run.
     {
-        half_t* Tc = TF + gc * (CH * CH);
-        constexpr int QPT = CH * CH / 4 / INV_THREADS;   // pieces of 4 per thread
+        half_t* Tc = TF + gc * TRI_FRAG_HALFS;
+        constexpr int QPT = TRI_FRAG_HALFS / 4 / INV_THREADS;   // pieces of 4 per thread
+        static_assert(QPT * 4 * INV_THREADS == TRI_FRAG_HALFS, "whole pieces");
 #pragma unroll
         for (int k = 0; k < QPT; ++k) {
-            const int e = tid + INV_THREADS * k;         // piece index: ((tw * 2 + ks) * 64 + lane') * 2 + half
-            const int ln = (e >> 1) & 63, ks = (e >> 7) & 1, tw = e >> 8;
+            const int e = tid + INV_THREADS * k;         // piece index: (f * 64 + lane') * 2 + half
+            const int ln = (e >> 1) & 63, f = e >> 7;    // f = tri_frag(tw, ks)
+            const int tw = f < 2 ? f : (f + 2) >> 1, ks = f < 2 ? 0 : f & 1;
             const int r = 16 * tw + (ln & 15), i = 32 * ks + 16 * (e & 1) + 4 * (ln >> 4);
             const int a = r >> 4, b = i >> 4;
             const float4 bp = *reinterpret_cast<const float4*>(s_bp + i);
@@ -358,7 +362,7 @@ __global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(const Inv
     gdn_chunk_inv_block<D>(a, blockIdx.x - scan_blocks);
 }
 
-// per chunk: TF, PF (64 * 64 fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above.
+// per chunk: TF, PF (TRI_FRAG_HALFS fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above.
 // The same launch carries the mask scan and compaction (arguments as launch_scan_compact).
 nats_status launch_gdn_chunk_inv(const FwdPlan& pl, const void* Q, const void* K, const float* alpha,
                                  const float* beta, const uint8_t* mask, void* TF, void* PF, float* gamv,

@@ -52,9 +52,9 @@ struct SegLds {
     // one operand set (halves)
     static constexpr int o_Kt = 0;
     static constexpr int o_Qt = o_Kt + SC * SS;
-    static constexpr int o_T = o_Qt + SC * SS;         // T'' in fragment order, 64 x 64
-    static constexpr int o_P = o_T + SC * SC;          // P in fragment order, times la_scale
-    static constexpr int o_G = o_P + SC * SC;          // fp32: gam[64], gam_C at [64], kd[64] from [68]
+    static constexpr int o_T = o_Qt + SC * SS;         // T'' in fragment order (the 6 fragments on and below the diagonal)
+    static constexpr int o_P = o_T + TRI_FRAG_HALFS;   // P in fragment order, times la_scale
+    static constexpr int o_G = o_P + TRI_FRAG_HALFS;   // fp32: gam[64], gam_C at [64], kd[64] from [68]
     static constexpr int G_KD = 68;
     static constexpr int SET = o_G + 2 * 132;          // 132 floats
     static constexpr int o_Kd = 2 * SET;               // Kd^T [d_k][TS]: written and read inside one step
@@ -317,7 +317,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
                 for (int vt = 0; vt < NVT; ++vt) accU[t2][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks <= kp; ++ks) {
-                    const half8 tf = Tt[(tt * 2 + ks) * 64 + lane];
+                    const half8 tf = Tt[tri_frag(tt, ks) * 64 + lane];
 #pragma unroll
                     for (int vt = 0; vt < NVT; ++vt) accU[t2][vt] = mfma16(tf, rfrag[ks][vt], accU[t2][vt]);   // rows r, col v
                 }
@@ -337,7 +337,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
                     for (int j = 0; j < 4; ++j) accO[vt][tt][j] *= go;
 #pragma unroll
                 for (int ks = 0; ks <= tt / 2; ++ks) {
-                    const half8 pf = Pt[(tt * 2 + ks) * 64 + lane];
+                    const half8 pf = Pt[tri_frag(tt, ks) * 64 + lane];
 #pragma unroll
                     for (int vt = 0; vt < NVT; ++vt) accO[vt][tt] = mfma16(ufrag[ks][vt], pf, accO[vt][tt]);   // rows v, col r
                 }
@@ -416,7 +416,9 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
 template <int D, bool HAS_OUT>
 struct StageRegs {
     static constexpr int NPC = SC * D / 8 / SEG_GROUP;     // 16-byte pieces of a [64][D] tile per thread
-    static constexpr int NTP = SC * SC / 8 / SEG_GROUP;    // ... of a 64 x 64 fp16 matrix
+    static constexpr int NTP = (TRI_FRAG_HALFS / 8 + SEG_GROUP - 1) / SEG_GROUP;   // ... of a chunk's T'' or P
+    // (6 fragments of 64 pieces: the second piece exists for the first half of the group only)
+    static __device__ __forceinline__ bool has_tp(int i, int pt) { return pt + SEG_GROUP * i < TRI_FRAG_HALFS / 8; }
     u32x4 kp[NPC], qp[NPC];        // pieces of the K and Q tiles (contiguous)
     half8 tp[NTP], pp[NTP];        // pieces of T'' and P (already in fragment order)
     float g0, g1;                  // thread t < 64: gam and kd of token t; thread 64: gam_C
@@ -430,10 +432,16 @@ struct StageRegs {
             if (i < NPC) { qp[i] = reinterpret_cast<const u32x4*>(a.Q + cb)[pt + SEG_GROUP * i]; return; }
             i -= NPC;
         }
-        if (i < NTP) { tp[i] = reinterpret_cast<const half8*>(a.TF + ch * (size_t)(SC * SC))[pt + SEG_GROUP * i]; return; }
+        if (i < NTP) {
+            if (has_tp(i, pt)) tp[i] = reinterpret_cast<const half8*>(a.TF + ch * (size_t)TRI_FRAG_HALFS)[pt + SEG_GROUP * i];
+            return;
+        }
         i -= NTP;
         if (HAS_OUT) {
-            if (i < NTP) { pp[i] = reinterpret_cast<const half8*>(a.PF + ch * (size_t)(SC * SC))[pt + SEG_GROUP * i]; return; }
+            if (i < NTP) {
+                if (has_tp(i, pt)) pp[i] = reinterpret_cast<const half8*>(a.PF + ch * (size_t)TRI_FRAG_HALFS)[pt + SEG_GROUP * i];
+                return;
+            }
             i -= NTP;
         }
         if (i == 0) g0 = pt < SC ? a.gamv[ch * SC + pt] : a.gamC[ch];
@@ -483,6 +491,7 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
         }
 #pragma unroll
         for (int k = 0; k < NTP; ++k) {
+            if (!Regs::has_tp(k, pt)) continue;   // uniform per wavefront
             reinterpret_cast<half8*>(set + Lds::o_T)[pt + SEG_GROUP * k] = r.tp[k];
             if (HAS_OUT) reinterpret_cast<half8*>(set + Lds::o_P)[pt + SEG_GROUP * k] = r.pp[k] * la8;
         }

@@ -182,6 +182,15 @@ struct ProfScope {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int BWD_DKV_SEGMENTS = 8;   // blocks that share the queries of one key tile in the softmax branch's dK / dV kernel
+// The lower triangular 64 x 64 fp16 operands of the forward's linear branch (T'' and P of a chunk) travel from the
+// inversion kernel to the state-carrying kernel as matrix-instruction fragments of 16 rows x 32 columns (1 KiB each).
+// Of the 8 fragments of a matrix the two that lie wholly above the diagonal (rows 0..31, columns 32..63) are
+// neither written nor read: a chunk's matrix is 6 fragments, in this order.
+constexpr int TRI_FRAGS = 6;
+constexpr int TRI_FRAG_HALFS = TRI_FRAGS * 64 * 8;   // fp16 elements per chunk and matrix
+// fragment number of row tile tw (16 rows) and contraction step ks (32 columns); (0, 1) and (1, 1) do not exist
+__host__ __device__ constexpr int tri_frag(int tw, int ks) { return tw < 2 ? tw : 2 * tw - 2 + ks; }
+
 constexpr int BWD_SWEEP_ROWS = 16;   // state rows per block of the reverse sweep: d / 16 blocks and partial sums per (batch, head)
 
 // Resolved forward problem handed to the kernel launchers.
