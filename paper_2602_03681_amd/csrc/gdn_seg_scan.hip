@@ -44,6 +44,10 @@ namespace nats {
 constexpr int SEG_THREADS = 512;
 constexpr int SEG_GROUP = 256;   // threads of a group (state / staging)
 constexpr int SC = 64;           // chunk size
+#ifndef NATS_SEG_PAIR
+#define NATS_SEG_PAIR 1
+#endif
+constexpr bool SEG_PAIR_BLOCKS = NATS_SEG_PAIR != 0;   // pass 1: one block for both output-free roles of a segment
 
 template <int D>
 struct SegLds {
@@ -58,8 +62,9 @@ struct SegLds {
     static constexpr int G_KD = 68;
     static constexpr int SET = o_G + 2 * 132;          // 132 floats
     static constexpr int o_Kd = 2 * SET;               // Kd^T [d_k][TS]: written and read inside one step
-    static constexpr int o_Out = o_Kd + D * TS;        // output tile [64][SS], fp16
-    static constexpr int n_half = o_Out + SC * SS;
+    static constexpr int o_Out = o_Kd + D * TS;        // output tile [64][SS], fp16; in a block that runs the two
+                                                       // output-free roles side by side: the second group's Kd^T
+    static constexpr int n_half = o_Out + (SC * SS > D * TS ? SC * SS : D * TS);
     static constexpr int bytes = n_half * 2;
     static_assert(bytes <= 160 * 1024, "one block per CU");
     static_assert(SET % 8 == 0, "sets stay 16-byte aligned");
@@ -119,7 +124,11 @@ __device__ __forceinline__ half8 pack_tiles(f32x4 lo, f32x4 hi) {
 //   operand fragment      : row / column l16, contraction slots s < 8 of step ks:
 //                           index 32 ks + 16 (s / 4) + 4 lq + s % 4   (d_k, or token)
 // ------------------------------------------------------------------------------------------------------------
-template <int D, int ROLE, bool F32OUT>
+// PAIR: the block runs the two output-free roles of a segment side by side, wavefronts 0-3 one, 4-7 the other, and
+// has no staging group: the 512 threads bring in the operand set themselves (K tile, T'', gates: 2-3 loads of 16
+// bytes per thread and chunk, asked for two chunks ahead at the top of a step and written into the set of the
+// next chunk at the top of the following step).  Each group makes its own Kd^T.
+template <int D, int ROLE, bool F32OUT, bool PAIR>
 __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
     using Lds = SegLds<D>;
     constexpr int SS = Lds::SS, TS = Lds::TS;
@@ -129,7 +138,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
     constexpr bool HAS_OUT = ROLE == ROLE_OUT, HAS_V = ROLE != ROLE_ACC_E;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..3
+    const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // 0..3 inside the group
     const int l16 = lane & 15, lq = lane >> 4;
     const int vbase = wave * (D / 4);
     const int n_chunks = a.L / SC;
@@ -192,7 +201,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
     };
     const float gated_off = a.gated ? 0.f : 1.f;   // without the delta rule the state does not enter R
     half_t* OutT = lds + Lds::o_Out;
-    half_t* Kd = lds + Lds::o_Kd;
+    half_t* Kd = lds + Lds::o_Kd + (PAIR ? (tid >> 8) * (D * TS) : 0);
     // Kd^T[d_k][token slots] = kd_tok K[tok][d_k] is made here too, from the K tile: a product with a 0/1 selector
     // hands 16 d_k columns of a token tile's K fragment back as an accumulator tile (rows tok 4 lq + j, col d_k),
     // exactly; those are 4 consecutive slots of a Kd^T row.  The (contraction step, column half) pairs are dealt
@@ -209,12 +218,56 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
             iselp[i][s8] = (lq == (l16 >> 2) && s8 == 4 * tr_hf[i] + (l16 & 3)) ? (half_t)1.f : (half_t)0.f;
     }
 
+    // ---- PAIR: this thread's share of the operand set ----
+    constexpr int NPC8 = SC * D / 8 / SEG_THREADS;   // 16-byte pieces of the K tile per thread
+    constexpr int NTP8 = TRI_FRAG_HALFS / 8;         // pieces of T'': threads below this number take one
+    static_assert(!PAIR || (NPC8 >= 1 && NTP8 <= SEG_THREADS), "shares of the operand set");
+    u32x4 skp[NPC8 > 0 ? NPC8 : 1];
+    half8 stp;
+    float sg0 = 0.f, sg1 = 0.f;
+    const size_t tokl = (size_t)(bh / a.G) * a.L, chb = (size_t)(bh / a.G) * n_chunks;   // the linear head's rows, chunks
+    auto stage_load = [&](int c) __attribute__((always_inline)) {
+        if (!PAIR) return;
+        const u32x4* Kp = reinterpret_cast<const u32x4*>(a.K + (tokl + (size_t)c * SC) * D);
+#pragma unroll
+        for (int i = 0; i < NPC8; ++i) skp[i] = Kp[tid + SEG_THREADS * i];
+        if (tid < NTP8) stp = reinterpret_cast<const half8*>(a.TF + (chb + c) * (size_t)TRI_FRAG_HALFS)[tid];   // wavefronts 0-5
+        if (tid <= SC) sg0 = tid < SC ? a.gamv[(chb + c) * SC + tid] : a.gamC[chb + c];
+        if (tid < SC) sg1 = a.kdv[(chb + c) * SC + tid];
+    };
+    auto stage_write = [&](half_t* set) __attribute__((always_inline)) {
+        if (!PAIR) return;
+#pragma unroll
+        for (int i = 0; i < NPC8; ++i) {   // the K tile in slot order (see the staging group)
+            const int e = tid + SEG_THREADS * i, row = e / (D / 8), c8 = e % (D / 8);
+            const int pos = 32 * (c8 >> 2) + 16 * (c8 & 1) + 4 * ((c8 >> 1) & 1);
+            const half8 hk = cvt_bf16x8(skp[i]);
+            *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos) = half4{hk[0], hk[1], hk[2], hk[3]};
+            *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos + 8) = half4{hk[4], hk[5], hk[6], hk[7]};
+        }
+        if (tid < NTP8) reinterpret_cast<half8*>(set + Lds::o_T)[tid] = stp;
+        float* G = reinterpret_cast<float*>(set + Lds::o_G);
+        if (tid <= SC) G[tid] = sg0;
+        if (tid < SC) G[Lds::G_KD + tid] = sg1;
+    };
+    if (PAIR) {
+        stage_load(c_begin);
+        stage_write(lds);
+        stage_load(min(c_begin + 1, c_end - 1));
+    }
+
     load_v(c_begin);
     __syncthreads();   // the first operand set is complete
 
     for (int c = c_begin; c < c_end; ++c) {
         const int cn = min(c + 1, c_end - 1);   // the tail re-loads the last chunk: loads stay unconditional
         const half_t* set = lds + ((c - c_begin) & 1) * Lds::SET;
+        if (PAIR) {
+            // chunk c + 1 (asked for a step ago) into the set that the previous step has finished with, then the
+            // request for chunk c + 2
+            stage_write(lds + (((c - c_begin) & 1) ^ 1) * Lds::SET);
+            stage_load(min(c + 2, c_end - 1));
+        }
         const half_t* Kt = set + Lds::o_Kt;
         const half_t* Qt = set + Lds::o_Qt;
         const half8* Tt = reinterpret_cast<const half8*>(set + Lds::o_T);
@@ -564,7 +617,7 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     //      the blocks of one (batch, head) are given such ids (the two blocks of a middle segment read the
     //      same K and T'').
     const int n_mid = a.n_seg > 2 ? a.n_seg - 2 : 0;
-    const int per_bh = a.pass == 1 ? 1 + 2 * n_mid : a.n_seg - 1;
+    const int per_bh = a.pass == 1 ? 1 + (SEG_PAIR_BLOCKS ? 1 : 2) * n_mid : a.n_seg - 1;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     // (with head grouping the G output heads of a linear head, which read the same K, Q, T'', P, share it too)
     const int hq = slot / per_bh, grp = (hq / a.G) * 8 + xcd;
@@ -575,16 +628,20 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     int role, seg;
     if (a.pass == 2) { role = ROLE_OUT; seg = 1 + sub; }
     else if (sub == 0) { role = ROLE_OUT; seg = 0; }
+    else if (SEG_PAIR_BLOCKS) { role = ROLE_ACC_S; seg = sub; }   // and ROLE_ACC_E, in the block's second group
     else { role = ((sub - 1) & 1) ? ROLE_ACC_E : ROLE_ACC_S; seg = 1 + ((sub - 1) >> 1); }
     if (role == ROLE_OUT) {
         if (staging) seg_staging_waves<D, ROLE_OUT>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_OUT, F32OUT>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_OUT, F32OUT, false>(a, bh, seg, lds);
+    } else if (SEG_PAIR_BLOCKS) {
+        if (staging) seg_state_waves<D, ROLE_ACC_E, false, true>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_S, false, true>(a, bh, seg, lds);
     } else if (role == ROLE_ACC_S) {
         if (staging) seg_staging_waves<D, ROLE_ACC_S>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_S, false, false>(a, bh, seg, lds);
     } else {
         if (staging) seg_staging_waves<D, ROLE_ACC_E>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_E, false, false>(a, bh, seg, lds);
     }
 }
 
@@ -753,7 +810,7 @@ static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     {
         ProfScope ps("gdn_seg_pass1", st);
         a.pass = 1;
-        hipLaunchKernelGGL(kern, dim3(bh8 * (1 + 2 * n_mid)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
+        hipLaunchKernelGGL(kern, dim3(bh8 * (1 + (SEG_PAIR_BLOCKS ? 1 : 2) * n_mid)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
     }
     nats_status s = check_launch("gdn_seg_scan (pass 1)");
     if (s != NATS_OK || a.n_seg == 1) return s;
