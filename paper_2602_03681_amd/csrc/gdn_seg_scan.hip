@@ -9,14 +9,16 @@
 // The chunk recurrence is affine in the state: S1 = S0 M + N with M (d_k x d_k) and N (d_v x d_k) that do
 // not depend on S0.  So the sequence is cut into segments that run side by side:
 //   pass 1   segment 0 runs the recurrence from the initial state, outputs included.  For every middle
-//            segment two blocks run the same recurrence without outputs: one from the zero state (its end
-//            state is the segment's N), one on the d_k unit rows with V = 0 (its end state is the segment's M);
+//            segment the same recurrence runs twice without outputs: from the zero state (the end state is the
+//            segment's N) and on the d_k unit rows with V = 0 (the end state is the segment's M); the two runs
+//            share one block, which reads K, T'' and the gates once for both;
 //   fix-up   (gdn_seg_fix) S_start[s + 1] = S_start[s] M_s + N_s along the few segments of a (batch, head);
 //   pass 2   every later segment runs the recurrence from its start state, outputs included.
 // A (batch, head) with L / 64 chunks then costs about 2 L / (64 n_seg) dependent steps instead of L / 64, for
 // 2 (n_seg - 2) / n_seg more state products.
 //
-// One block = one (batch, head, segment), 8 wavefronts in two groups.
+// One block = one (batch, head, segment), 8 wavefronts in two groups (a block with outputs: a state group and a
+// staging group; a block of the two output-free runs: a state group for each, see PAIR below).
 //   The four STATE wavefronts each own a quarter of the d_v rows and everything that is indexed by d_v: their
 // slice of the state (S^T tiles in fp32 MFMA accumulators), of R, U and of the output.  The rows of S never mix,
 // so the whole dependent chain  S0 -> K S0^T -> R -> U = T'' R -> S1  of a slice runs inside one wavefront, and
@@ -35,6 +37,7 @@
 //   Two block barriers per chunk: one before the output tile is overwritten, one when the next operand set is
 // complete.
 #include <algorithm>
+#include <type_traits>
 
 #include "mfma_util.h"
 #include "nats_common.h"
@@ -62,11 +65,27 @@ struct SegLds {
     static constexpr int G_KD = 68;
     static constexpr int SET = o_G + 2 * 132;          // 132 floats
     static constexpr int o_Kd = 2 * SET;               // Kd^T [d_k][TS]: written and read inside one step
-    static constexpr int o_Out = o_Kd + D * TS;        // output tile [64][SS], fp16; in a block that runs the two
-                                                       // output-free roles side by side: the second group's Kd^T
-    static constexpr int n_half = o_Out + (SC * SS > D * TS ? SC * SS : D * TS);
+    static constexpr int o_Out = o_Kd + D * TS;        // output tile [64][SS], fp16
+    static constexpr int n_half = o_Out + SC * SS;
     static constexpr int bytes = n_half * 2;
     static_assert(bytes <= 160 * 1024, "one block per CU");
+    static_assert(SET % 8 == 0, "sets stay 16-byte aligned");
+};
+
+// LDS of a block that runs the two output-free roles of a segment side by side (no Q, P, output tile): two operand
+// sets, and Kd^T per group and chunk parity, so that one barrier per chunk is enough.
+template <int D>
+struct PairLds {
+    static constexpr int SS = SegLds<D>::SS, TS = SegLds<D>::TS;
+    static constexpr int o_Kt = 0;
+    static constexpr int o_T = o_Kt + SC * SS;
+    static constexpr int o_G = o_T + TRI_FRAG_HALFS;
+    static constexpr int G_KD = 68;
+    static constexpr int SET = o_G + 2 * 132;
+    static constexpr int o_Kd = 2 * SET;               // Kd^T [group][chunk parity][d_k][TS]
+    static constexpr int n_half = o_Kd + 4 * D * TS;
+    static constexpr int o_Qt = 0, o_P = 0, o_Out = 0; // not present
+    static_assert(n_half <= SegLds<D>::n_half, "inside the kernel's LDS");
     static_assert(SET % 8 == 0, "sets stay 16-byte aligned");
 };
 
@@ -127,10 +146,12 @@ __device__ __forceinline__ half8 pack_tiles(f32x4 lo, f32x4 hi) {
 // PAIR: the block runs the two output-free roles of a segment side by side, wavefronts 0-3 one, 4-7 the other, and
 // has no staging group: the 512 threads bring in the operand set themselves (K tile, T'', gates: 2-3 loads of 16
 // bytes per thread and chunk, asked for two chunks ahead at the top of a step and written into the set of the
-// next chunk at the top of the following step).  Each group makes its own Kd^T.
+// next chunk at the top of the following step).  Each group makes its own Kd^T, in a buffer per chunk parity:
+// with the sets and Kd^T both double-buffered the barrier in the middle of a step is the only one (what a
+// wavefront writes before it in step c + 1 was last read before that barrier in step c, or in step c - 1).
 template <int D, int ROLE, bool F32OUT, bool PAIR>
 __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
-    using Lds = SegLds<D>;
+    using Lds = typename std::conditional<PAIR, PairLds<D>, SegLds<D>>::type;
     constexpr int SS = Lds::SS, TS = Lds::TS;
     constexpr int KS_D = D / 32;      // contraction steps over d_k
     constexpr int NDT = D / 16;       // 16-row d_k tiles of S^T
@@ -201,7 +222,6 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
     };
     const float gated_off = a.gated ? 0.f : 1.f;   // without the delta rule the state does not enter R
     half_t* OutT = lds + Lds::o_Out;
-    half_t* Kd = lds + Lds::o_Kd + (PAIR ? (tid >> 8) * (D * TS) : 0);
     // Kd^T[d_k][token slots] = kd_tok K[tok][d_k] is made here too, from the K tile: a product with a 0/1 selector
     // hands 16 d_k columns of a token tile's K fragment back as an accumulator tile (rows tok 4 lq + j, col d_k),
     // exactly; those are 4 consecutive slots of a Kd^T row.  The (contraction step, column half) pairs are dealt
@@ -268,6 +288,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
             stage_write(lds + (((c - c_begin) & 1) ^ 1) * Lds::SET);
             stage_load(min(c + 2, c_end - 1));
         }
+        half_t* Kd = lds + Lds::o_Kd + (PAIR ? (2 * (tid >> 8) + ((c - c_begin) & 1)) * (D * TS) : 0);
         const half_t* Kt = set + Lds::o_Kt;
         const half_t* Qt = set + Lds::o_Qt;
         const half8* Tt = reinterpret_cast<const half8*>(set + Lds::o_T);
@@ -396,6 +417,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
                 }
             }
         }
+        const float gC = Gt[64];   // (read before the barrier: in a paired block the set may be rewritten after it)
         __syncthreads();   // the staging group has taken the previous chunk's rows out of the output tile; Kd^T complete
         if (HAS_OUT) {
 #pragma unroll
@@ -411,7 +433,6 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
         }
 
         // ---- S1^T = gam_C S0^T + Kd^T U, and its operand form for the next chunk ----
-        const float gC = Gt[64];
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
             half8 af[2];
@@ -429,7 +450,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
         for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
             for (int ks = 0; ks < KS_D; ++ks) sfrag[vt][ks] = pack_tiles(accS[2 * ks][vt], accS[2 * ks + 1][vt]);
-        __syncthreads();   // the next operand set and this chunk's output tile are complete
+        if (!PAIR) __syncthreads();   // the next operand set and this chunk's output tile are complete
     }
 
     // ---- end state ----
