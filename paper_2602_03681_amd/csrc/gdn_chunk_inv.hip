@@ -67,6 +67,45 @@ __device__ __forceinline__ int frag_off(int r, int i) {
     return ((tri_frag(r >> 4, i >> 5) * 64) + 16 * ((i >> 2) & 3) + (r & 15)) * 8 + 4 * ((i >> 4) & 1) + (i & 3);
 }
 
+// Block column B of T = (I + A)^-1 below its diagonal block, by one wavefront: T_aB = -T_aa sum_{B <= k < a} A_ak T_kB.
+// As, Ts: the lower 16x16 tiles in LDS (the diagonal blocks of T are complete).
+template <int B>
+__device__ __forceinline__ void inv_block_column(const float* As, float* Ts, const int l16, const int lq) {
+    f32x4 X[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) X[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 tkb;   // T_kB as the right operand: rows 4 lq + j, column l16
+    {
+        const float* Tbb = Ts + tri_tile(B, B) + (4 * lq) * AT + l16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tkb[j] = Tbb[j * AT];
+    }
+#pragma unroll
+    for (int k = B; k < 3; ++k) {
+#pragma unroll
+        for (int a = k + 1; a < 4; ++a) {
+            const float4 af = *reinterpret_cast<const float4*>(As + tri_tile(a, k) + l16 * AT + 4 * lq);
+            X[a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, tkb[0], X[a], 0, 0, 0);
+            X[a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, tkb[1], X[a], 0, 0, 0);
+            X[a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, tkb[2], X[a], 0, 0, 0);
+            X[a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, tkb[3], X[a], 0, 0, 0);
+        }
+        const int a = k + 1;   // this block's sum is complete
+        const float4 tf = *reinterpret_cast<const float4*>(Ts + tri_tile(a, a) + l16 * AT + 4 * lq);
+        f32x4 Y = {0.f, 0.f, 0.f, 0.f};
+        Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.x, X[a][0], Y, 0, 0, 0);
+        Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.y, X[a][1], Y, 0, 0, 0);
+        Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.z, X[a][2], Y, 0, 0, 0);
+        Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.w, X[a][3], Y, 0, 0, 0);
+        float* Tab = Ts + tri_tile(a, B) + (4 * lq) * AT + l16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            tkb[j] = -Y[j];   // the next step's right operand as it sits in the registers
+            Tab[j * AT] = tkb[j];
+        }
+    }
+}
+
 struct InvArgs {
     const bf16_t *Q, *K;
     const float *alpha, *beta;
@@ -274,18 +313,29 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
     if (lane < 16) {
         const float* At = As + tri_tile(wave, wave);
         float* Tt = Ts + tri_tile(wave, wave);
+        // col[r] = [r == lane] - sum_{i < r} A[r][i] col[i].  The terms are taken oldest first, in two chains, and the
+        // term of col[r - 1] last: only that product and the subtraction wait for the previous row, everything else
+        // of a row is computed while earlier rows finish.
         float col[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) col[r] = 0.f;
-#pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float acc = 0.f;
+            float a_row[16];
 #pragma unroll
-            for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {   // A[r][i] is 0 for i >= r, col[i] is 0 there too
+            for (int i4 = 0; i4 < (r + 3) / 4; ++i4) {
                 const float4 a4 = *reinterpret_cast<const float4*>(At + r * AT + 4 * i4);
-                acc += a4.x * col[4 * i4] + a4.y * col[4 * i4 + 1] + a4.z * col[4 * i4 + 2] +
-                       a4.w * col[4 * i4 + 3];
+                a_row[4 * i4] = a4.x;
+                a_row[4 * i4 + 1] = a4.y;
+                a_row[4 * i4 + 2] = a4.z;
+                a_row[4 * i4 + 3] = a4.w;
             }
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int i = 0; i + 1 < r; ++i) {   // i <= r - 2
+                if (i & 1) s1 = fmaf(a_row[i], col[i], s1);
+                else s0 = fmaf(a_row[i], col[i], s0);
+            }
+            float acc = s0 + s1;
+            if (r > 0) acc = fmaf(a_row[r > 0 ? r - 1 : 0], col[r > 0 ? r - 1 : 0], acc);
             col[r] = ((r == lane) ? 1.f : 0.f) - acc;
         }
 #pragma unroll
@@ -297,30 +347,11 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
     //     product contracts over the indices 4 lq + j (lq: the lane's quarter): then the left operand is one
     //     16-byte read per lane, and a result tile, which a lane holds as rows 4 lq + j, is the right operand
     //     of the next product as it sits in registers.
-    {
-        const int b = wave;
-        for (int a = b + 1; a < 4; ++a) {
-            f32x4 X = {0.f, 0.f, 0.f, 0.f};
-            for (int k = b; k < a; ++k) {
-                const float4 af = *reinterpret_cast<const float4*>(As + tri_tile(a, k) + l16 * AT + 4 * lq);
-                const float* Tkb = Ts + tri_tile(k, b) + (4 * lq) * AT + l16;
-                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, Tkb[0], X, 0, 0, 0);
-                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, Tkb[AT], X, 0, 0, 0);
-                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, Tkb[2 * AT], X, 0, 0, 0);
-                X = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, Tkb[3 * AT], X, 0, 0, 0);
-            }
-            const float4 tf = *reinterpret_cast<const float4*>(Ts + tri_tile(a, a) + l16 * AT + 4 * lq);
-            f32x4 Y = {0.f, 0.f, 0.f, 0.f};
-            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.x, X[0], Y, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.y, X[1], Y, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.z, X[2], Y, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_16x16x4f32(tf.w, X[3], Y, 0, 0, 0);
-            float* Tab = Ts + tri_tile(a, b) + (4 * lq) * AT + l16;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) Tab[j * AT] = -Y[j];
-            __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
-        }
-    }
+    //     The partial sums of the blocks further down take each T_kb as soon as it exists, so that only the two
+    //     products that finish a block (A_{k+1,k} T_kb and T_{k+1,k+1} X) stand between T_kb and T_{k+1,b}.
+    if (wave == 0) inv_block_column<0>(As, Ts, l16, lq);
+    else if (wave == 1) inv_block_column<1>(As, Ts, l16, lq);
+    else if (wave == 2) inv_block_column<2>(As, Ts, l16, lq);
     __syncthreads();   // T complete
     // (c) T'' = T diag(b'), fp16, straight to global memory in fragment order: thread e writes the 4-element
     //     piece e of the chunk's 6 KiB, so a wavefront's store is one contiguous run.
