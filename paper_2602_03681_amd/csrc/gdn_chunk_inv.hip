@@ -118,7 +118,7 @@ struct InvArgs {
 
 // one block of the inversion: block_id counts (chunk, batch*head padded to a multiple of 8)
 template <int D>
-__device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int block_id) {
+__device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int block_id, unsigned char* smem) {
     const bf16_t* __restrict__ Q = a.Q;
     const bf16_t* __restrict__ K = a.K;
     const float* __restrict__ alpha = a.alpha;
@@ -135,7 +135,6 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
     constexpr int RS = Lds::RS;
     constexpr int NPC = CH * D / 8 / INV_THREADS;   // 16-byte pieces of a [64][D] tile per thread
     constexpr int KS_D = D / 32;
-    __shared__ __align__(16) unsigned char smem[Lds::bytes];
     half_t* Ks = reinterpret_cast<half_t*>(smem);              // [64][RS]
     float* Ts = reinterpret_cast<float*>(smem);                // lower tiles   (after Ks)
     float* As = reinterpret_cast<float*>(smem + Lds::o_as);    // lower tiles
@@ -383,14 +382,19 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
 // branch needs: a few hundred blocks, each a chain of memory latencies, that would otherwise stand alone on the
 // stream for as long as a fifth of this kernel), then one block per chunk and (batch, head).
 template <int D>
-__global__ __launch_bounds__(INV_THREADS, 4) void gdn_chunk_inv_kernel(const InvArgs a, const ScanArgs<bf16_t> sc,
+#ifndef NATS_INV_OCC
+#define NATS_INV_OCC 5
+#endif
+__global__ __launch_bounds__(INV_THREADS, NATS_INV_OCC) void gdn_chunk_inv_kernel(const InvArgs a, const ScanArgs<bf16_t> sc,
                                                                        const int scan_segs, const int scan_blocks) {
     static_assert(INV_THREADS == SCAN_THREADS, "the two kinds of block share one launch");
+    static_assert(InvLds<D>::bytes >= SCAN_LDS_INTS * 4, "and one piece of LDS");
+    __shared__ __align__(16) unsigned char smem[InvLds<D>::bytes];
     if ((int)blockIdx.x < scan_blocks) {
-        scan_compact_block<bf16_t>(sc, blockIdx.x % scan_segs, blockIdx.x / scan_segs);
+        scan_compact_block<bf16_t>(sc, blockIdx.x % scan_segs, blockIdx.x / scan_segs, reinterpret_cast<int*>(smem));
         return;
     }
-    gdn_chunk_inv_block<D>(a, blockIdx.x - scan_blocks);
+    gdn_chunk_inv_block<D>(a, blockIdx.x - scan_blocks, smem);
 }
 
 // per chunk: TF, PF (TRI_FRAG_HALFS fp16 each), gamv, kdv (64 fp32 each), gamC (1 fp32); layouts above.

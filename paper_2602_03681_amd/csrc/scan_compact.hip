@@ -14,7 +14,8 @@ namespace nats {
 
 template <typename T>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_compact_kernel(const ScanArgs<T> a) {
-    scan_compact_block<T>(a, blockIdx.x, blockIdx.y);
+    __shared__ int lds[SCAN_LDS_INTS];
+    scan_compact_block<T>(a, blockIdx.x, blockIdx.y, lds);
 }
 
 nats_status launch_scan_compact(const FwdPlan& pl, const uint8_t* mask, const void* K, const void* V,

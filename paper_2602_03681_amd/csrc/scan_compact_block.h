@@ -30,8 +30,11 @@ struct ScanArgs {
 };
 
 // One block: SCAN_SEG tokens (segment number seg_no) of output head bo.  SCAN_THREADS threads.
+// lds: SCAN_LDS_INTS ints of the block's shared memory (the caller's: a kernel that carries other kinds of block
+// too gives every kind the same bytes).
+constexpr int SCAN_LDS_INTS = SCAN_THREADS / 64 + SCAN_SEG;
 template <typename T>
-__device__ __forceinline__ void scan_compact_block(const ScanArgs<T>& a, const int seg_no, const int bo) {
+__device__ __forceinline__ void scan_compact_block(const ScanArgs<T>& a, const int seg_no, const int bo, int* lds) {
     const uint8_t* __restrict__ mask = a.mask;
     const T* __restrict__ K = a.K;
     const T* __restrict__ V = a.V;
@@ -44,8 +47,8 @@ __device__ __forceinline__ void scan_compact_block(const ScanArgs<T>& a, const i
     T* __restrict__ Kc_user = a.Kc_user;
     T* __restrict__ Vc_user = a.Vc_user;
     half_t* __restrict__ VhT = a.VhT;
-    __shared__ int s_wave[SCAN_THREADS / 64];
-    __shared__ int s_pos[SCAN_SEG];
+    int* s_wave = lds;                        // [SCAN_THREADS / 64]
+    int* s_pos = lds + SCAN_THREADS / 64;     // [SCAN_SEG]
     // Head grouping (Section 4.3): G output heads share the mask of linear head bh.  Every output head gathers
     // its own value rows (and its own key rows, if the softmax heads have keys of their own); the integers are
     // the group's and are stored by its first head.
