@@ -146,7 +146,8 @@ __device__ __forceinline__ half8 pack_tiles(f32x4 lo, f32x4 hi) {
 // PAIR: the block runs the two output-free roles of a segment side by side, wavefronts 0-3 one, 4-7 the other, and
 // has no staging group: the 512 threads bring in the operand set themselves (K tile, T'', gates: 2-3 loads of 16
 // bytes per thread and chunk, asked for two chunks ahead at the top of a step and written into the set of the
-// next chunk at the top of the following step).  Each group makes its own Kd^T, in a buffer per chunk parity:
+// next chunk at the top of the following step).  Kd^T (one for both groups at d = 128, each group's own at
+// d = 64) has a buffer per chunk parity:
 // with the sets and Kd^T both double-buffered the barrier in the middle of a step is the only one (what a
 // wavefront writes before it in step c + 1 was last read before that barrier in step c, or in step c - 1).
 template <int D, int ROLE, bool F32OUT, bool PAIR>
@@ -226,13 +227,15 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
     // hands 16 d_k columns of a token tile's K fragment back as an accumulator tile (rows tok 4 lq + j, col d_k),
     // exactly; those are 4 consecutive slots of a Kd^T row.  The (contraction step, column half) pairs are dealt
     // to the four wavefronts: d = 128: step = wavefront, both halves; d = 64: step = wavefront % 2, half = wavefront / 2.
-    constexpr int NTR = KS_D / 2;                   // pairs per wavefront and token tile
+    // In a paired block at d = 128 the two groups make one Kd^T together: step = wavefront, half = group.
+    constexpr bool SHARE_KD = PAIR && KS_D == 4;
+    constexpr int NTR = SHARE_KD ? 1 : KS_D / 2;    // pairs per wavefront and token tile
     const int tr_ks = KS_D == 4 ? wave : (wave & 1);
     half8 iselp[NTR];                               // selector for a fragment in slot order: column n <- d_k 16 hf + n
     int tr_hf[NTR];
 #pragma unroll
     for (int i = 0; i < NTR; ++i) {
-        tr_hf[i] = KS_D == 4 ? i : (wave >> 1);
+        tr_hf[i] = SHARE_KD ? (tid >> 8) : KS_D == 4 ? i : (wave >> 1);
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8)
             iselp[i][s8] = (lq == (l16 >> 2) && s8 == 4 * tr_hf[i] + (l16 & 3)) ? (half_t)1.f : (half_t)0.f;
@@ -288,7 +291,7 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
             stage_write(lds + (((c - c_begin) & 1) ^ 1) * Lds::SET);
             stage_load(min(c + 2, c_end - 1));
         }
-        half_t* Kd = lds + Lds::o_Kd + (PAIR ? (2 * (tid >> 8) + ((c - c_begin) & 1)) * (D * TS) : 0);
+        half_t* Kd = lds + Lds::o_Kd + (PAIR ? ((SHARE_KD ? 0 : 2 * (tid >> 8)) + ((c - c_begin) & 1)) * (D * TS) : 0);
         const half_t* Kt = set + Lds::o_Kt;
         const half_t* Qt = set + Lds::o_Qt;
         const half8* Tt = reinterpret_cast<const half8*>(set + Lds::o_T);
