@@ -41,6 +41,7 @@
 namespace nats {
 
 constexpr int INV_THREADS = 256;
+constexpr int INV_OCC = 5;             // blocks per CU (96 registers, 32 KB of LDS each)
 constexpr int CH = 64;                 // chunk size
 constexpr int AT = 20;                 // fp32 row stride of a 16x16 tile of A or T in LDS (rows stay 16-byte aligned)
 constexpr int AT_TILE = 16 * AT + 16;  // floats per tile; the 16 extra shift the next tile by 16 banks
@@ -382,10 +383,7 @@ __device__ __forceinline__ void gdn_chunk_inv_block(const InvArgs& a, const int 
 // branch needs: a few hundred blocks, each a chain of memory latencies, that would otherwise stand alone on the
 // stream for as long as a fifth of this kernel), then one block per chunk and (batch, head).
 template <int D>
-#ifndef NATS_INV_OCC
-#define NATS_INV_OCC 5
-#endif
-__global__ __launch_bounds__(INV_THREADS, NATS_INV_OCC) void gdn_chunk_inv_kernel(const InvArgs a, const ScanArgs<bf16_t> sc,
+__global__ __launch_bounds__(INV_THREADS, INV_OCC) void gdn_chunk_inv_kernel(const InvArgs a, const ScanArgs<bf16_t> sc,
                                                                        const int scan_segs, const int scan_blocks) {
     static_assert(INV_THREADS == SCAN_THREADS, "the two kinds of block share one launch");
     static_assert(InvLds<D>::bytes >= SCAN_LDS_INTS * 4, "and one piece of LDS");

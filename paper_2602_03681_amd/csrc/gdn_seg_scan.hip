@@ -47,10 +47,6 @@ namespace nats {
 constexpr int SEG_THREADS = 512;
 constexpr int SEG_GROUP = 256;   // threads of a group (state / staging)
 constexpr int SC = 64;           // chunk size
-#ifndef NATS_SEG_PAIR
-#define NATS_SEG_PAIR 1
-#endif
-constexpr bool SEG_PAIR_BLOCKS = NATS_SEG_PAIR != 0;   // pass 1: one block for both output-free roles of a segment
 
 template <int D>
 struct SegLds {
@@ -150,8 +146,9 @@ __device__ __forceinline__ half8 pack_tiles(f32x4 lo, f32x4 hi) {
 // d = 64) has a buffer per chunk parity:
 // with the sets and Kd^T both double-buffered the barrier in the middle of a step is the only one (what a
 // wavefront writes before it in step c + 1 was last read before that barrier in step c, or in step c - 1).
-template <int D, int ROLE, bool F32OUT, bool PAIR>
+template <int D, int ROLE, bool F32OUT>
 __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
+    constexpr bool PAIR = ROLE != ROLE_OUT;   // the output-free roles always run as a pair
     using Lds = typename std::conditional<PAIR, PairLds<D>, SegLds<D>>::type;
     constexpr int SS = Lds::SS, TS = Lds::TS;
     constexpr int KS_D = D / 32;      // contraction steps over d_k
@@ -490,8 +487,9 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
 // STAGING wavefronts: the operand set of the next chunk, and the previous chunk's output rows.
 // ------------------------------------------------------------------------------------------------------------
 // what a staging thread carries from memory to the next operand set
-template <int D, bool HAS_OUT>
+template <int D>
 struct StageRegs {
+    static constexpr bool HAS_OUT = true;   // only blocks with outputs have a staging group
     static constexpr int NPC = SC * D / 8 / SEG_GROUP;     // 16-byte pieces of a [64][D] tile per thread
     static constexpr int NTP = (TRI_FRAG_HALFS / 8 + SEG_GROUP - 1) / SEG_GROUP;   // ... of a chunk's T'' or P
     // (6 fragments of 64 pieces: the second piece exists for the first half of the group only)
@@ -529,12 +527,12 @@ struct StageRegs {
 // ------------------------------------------------------------------------------------------------------------
 // STAGING wavefronts: the operand set of the next chunk, and the current chunk's output rows (fp16).
 // ------------------------------------------------------------------------------------------------------------
-template <int D, int ROLE>
+template <int D>
 __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
     using Lds = SegLds<D>;
     constexpr int SS = Lds::SS;
-    constexpr bool HAS_OUT = ROLE == ROLE_OUT;
-    using Regs = StageRegs<D, HAS_OUT>;
+    constexpr bool HAS_OUT = true;
+    using Regs = StageRegs<D>;
     constexpr int NPC = Regs::NPC, NTP = Regs::NTP;
     const int pt = threadIdx.x - SEG_GROUP;
     const int n_chunks = a.L / SC;
@@ -641,7 +639,7 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     //      the blocks of one (batch, head) are given such ids (the two blocks of a middle segment read the
     //      same K and T'').
     const int n_mid = a.n_seg > 2 ? a.n_seg - 2 : 0;
-    const int per_bh = a.pass == 1 ? 1 + (SEG_PAIR_BLOCKS ? 1 : 2) * n_mid : a.n_seg - 1;
+    const int per_bh = a.pass == 1 ? 1 + n_mid : a.n_seg - 1;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     // (with head grouping the G output heads of a linear head, which read the same K, Q, T'', P, share it too)
     const int hq = slot / per_bh, grp = (hq / a.G) * 8 + xcd;
@@ -649,23 +647,16 @@ __global__ __launch_bounds__(SEG_THREADS) void gdn_seg_scan_kernel(const SegArgs
     const int bh = grp * a.G + hq % a.G;
     const int sub = slot % per_bh;
     const bool staging = threadIdx.x >= SEG_GROUP;   // uniform per wavefront
-    int role, seg;
-    if (a.pass == 2) { role = ROLE_OUT; seg = 1 + sub; }
-    else if (sub == 0) { role = ROLE_OUT; seg = 0; }
-    else if (SEG_PAIR_BLOCKS) { role = ROLE_ACC_S; seg = sub; }   // and ROLE_ACC_E, in the block's second group
-    else { role = ((sub - 1) & 1) ? ROLE_ACC_E : ROLE_ACC_S; seg = 1 + ((sub - 1) >> 1); }
-    if (role == ROLE_OUT) {
-        if (staging) seg_staging_waves<D, ROLE_OUT>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_OUT, F32OUT, false>(a, bh, seg, lds);
-    } else if (SEG_PAIR_BLOCKS) {
-        if (staging) seg_state_waves<D, ROLE_ACC_E, false, true>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_ACC_S, false, true>(a, bh, seg, lds);
-    } else if (role == ROLE_ACC_S) {
-        if (staging) seg_staging_waves<D, ROLE_ACC_S>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_ACC_S, false, false>(a, bh, seg, lds);
+    // pass 2: every later segment with outputs; pass 1: segment 0 with outputs, then one block per middle segment
+    // that runs it from the zero state (wavefronts 0-3) and on the unit rows (wavefronts 4-7)
+    const bool with_out = a.pass == 2 || sub == 0;
+    const int seg = a.pass == 2 ? 1 + sub : sub;
+    if (with_out) {
+        if (staging) seg_staging_waves<D>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_OUT, F32OUT>(a, bh, seg, lds);
     } else {
-        if (staging) seg_staging_waves<D, ROLE_ACC_E>(a, bh, seg, lds);
-        else seg_state_waves<D, ROLE_ACC_E, false, false>(a, bh, seg, lds);
+        if (staging) seg_state_waves<D, ROLE_ACC_E, false>(a, bh, seg, lds);
+        else seg_state_waves<D, ROLE_ACC_S, false>(a, bh, seg, lds);
     }
 }
 
@@ -834,7 +825,7 @@ static nats_status launch_seg_k(const FwdPlan& pl, SegArgs<D> a, hipStream_t st)
     {
         ProfScope ps("gdn_seg_pass1", st);
         a.pass = 1;
-        hipLaunchKernelGGL(kern, dim3(bh8 * (1 + (SEG_PAIR_BLOCKS ? 1 : 2) * n_mid)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
+        hipLaunchKernelGGL(kern, dim3(bh8 * (1 + n_mid)), dim3(SEG_THREADS), SegLds<D>::bytes, st, a);
     }
     nats_status s = check_launch("gdn_seg_scan (pass 1)");
     if (s != NATS_OK || a.n_seg == 1) return s;
