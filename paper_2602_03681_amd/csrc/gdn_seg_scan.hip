@@ -484,12 +484,12 @@ __device__ __forceinline__ void seg_state_waves(const SegArgs<D>& a, const int b
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// STAGING wavefronts: the operand set of the next chunk, and the previous chunk's output rows.
+// STAGING wavefronts (blocks with outputs only): the operand set of the next chunk, and the previous chunk's
+// output rows.
 // ------------------------------------------------------------------------------------------------------------
 // what a staging thread carries from memory to the next operand set
 template <int D>
 struct StageRegs {
-    static constexpr bool HAS_OUT = true;   // only blocks with outputs have a staging group
     static constexpr int NPC = SC * D / 8 / SEG_GROUP;     // 16-byte pieces of a [64][D] tile per thread
     static constexpr int NTP = (TRI_FRAG_HALFS / 8 + SEG_GROUP - 1) / SEG_GROUP;   // ... of a chunk's T'' or P
     // (6 fragments of 64 pieces: the second piece exists for the first half of the group only)
@@ -497,28 +497,24 @@ struct StageRegs {
     u32x4 kp[NPC], qp[NPC];        // pieces of the K and Q tiles (contiguous)
     half8 tp[NTP], pp[NTP];        // pieces of T'' and P (already in fragment order)
     float g0, g1;                  // thread t < 64: gam and kd of token t; thread 64: gam_C
-    static constexpr int N_LOADS = NPC * (HAS_OUT ? 2 : 1) + NTP * (HAS_OUT ? 2 : 1) + 2;
+    static constexpr int N_LOADS = 2 * NPC + 2 * NTP + 2;
     // load number i of chunk c (one at a time, so that a step can spread them between its other work: issued
     // in a burst they queue in the CU's vector-memory path and the wavefront stalls until all are accepted)
     __device__ __forceinline__ void load_piece(int i, const SegArgs<D>& a, size_t cb, size_t ch, int pt) {
         if (i < NPC) { kp[i] = reinterpret_cast<const u32x4*>(a.K + cb)[pt + SEG_GROUP * i]; return; }
         i -= NPC;
-        if (HAS_OUT) {
-            if (i < NPC) { qp[i] = reinterpret_cast<const u32x4*>(a.Q + cb)[pt + SEG_GROUP * i]; return; }
-            i -= NPC;
-        }
+        if (i < NPC) { qp[i] = reinterpret_cast<const u32x4*>(a.Q + cb)[pt + SEG_GROUP * i]; return; }
+        i -= NPC;
         if (i < NTP) {
             if (has_tp(i, pt)) tp[i] = reinterpret_cast<const half8*>(a.TF + ch * (size_t)TRI_FRAG_HALFS)[pt + SEG_GROUP * i];
             return;
         }
         i -= NTP;
-        if (HAS_OUT) {
-            if (i < NTP) {
-                if (has_tp(i, pt)) pp[i] = reinterpret_cast<const half8*>(a.PF + ch * (size_t)TRI_FRAG_HALFS)[pt + SEG_GROUP * i];
-                return;
-            }
-            i -= NTP;
+        if (i < NTP) {
+            if (has_tp(i, pt)) pp[i] = reinterpret_cast<const half8*>(a.PF + ch * (size_t)TRI_FRAG_HALFS)[pt + SEG_GROUP * i];
+            return;
         }
+        i -= NTP;
         if (i == 0) g0 = pt < SC ? a.gamv[ch * SC + pt] : a.gamC[ch];
         else g1 = a.kdv[ch * SC + (pt & (SC - 1))];
     }
@@ -531,7 +527,6 @@ template <int D>
 __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int bh, const int seg, half_t* lds) {
     using Lds = SegLds<D>;
     constexpr int SS = Lds::SS;
-    constexpr bool HAS_OUT = true;
     using Regs = StageRegs<D>;
     constexpr int NPC = Regs::NPC, NTP = Regs::NTP;
     const int pt = threadIdx.x - SEG_GROUP;
@@ -557,18 +552,16 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
             const half8 hk = cvt_bf16x8(r.kp[i]);
             *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos) = half4{hk[0], hk[1], hk[2], hk[3]};
             *reinterpret_cast<half4*>(set + Lds::o_Kt + row * SS + pos + 8) = half4{hk[4], hk[5], hk[6], hk[7]};
-            if (HAS_OUT) {
-                const half8 hq = cvt_bf16x8(r.qp[i]);
-                *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos) = half4{hq[0], hq[1], hq[2], hq[3]};
-                *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos + 8) = half4{hq[4], hq[5], hq[6], hq[7]};
-            }
+            const half8 hq = cvt_bf16x8(r.qp[i]);
+            *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos) = half4{hq[0], hq[1], hq[2], hq[3]};
+            *reinterpret_cast<half4*>(set + Lds::o_Qt + row * SS + pos + 8) = half4{hq[4], hq[5], hq[6], hq[7]};
             return;
         }
 #pragma unroll
         for (int k = 0; k < NTP; ++k) {
             if (!Regs::has_tp(k, pt)) continue;   // uniform per wavefront
             reinterpret_cast<half8*>(set + Lds::o_T)[pt + SEG_GROUP * k] = r.tp[k];
-            if (HAS_OUT) reinterpret_cast<half8*>(set + Lds::o_P)[pt + SEG_GROUP * k] = r.pp[k] * la8;
+            reinterpret_cast<half8*>(set + Lds::o_P)[pt + SEG_GROUP * k] = r.pp[k] * la8;
         }
         float* G = reinterpret_cast<float*>(set + Lds::o_G);
         if (pt <= SC) G[pt] = r.g0;
@@ -581,7 +574,6 @@ __device__ __forceinline__ void seg_staging_waves(const SegArgs<D>& a, const int
     // rows of chunk c out of the output tile, as fp16 for the softmax kernel's merge epilogue: 16 bytes per lane,
     // whole rows contiguous
     auto store_rows = [&](int c) __attribute__((always_inline)) {
-        if (!HAS_OUT) return;
         const size_t ob = (tokb + (size_t)c * SC) * D;
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
