@@ -237,7 +237,7 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  * the adjoint of the recurrence of Eq. 19 / 14 / 20 (or of the gated operation) for the linear branch, and the
  * attention backward over the softmax columns of Eq. 12 with the mask gradients of Eq. 15.  k and v of a
  * softmax token get nothing from the linear branch and vice versa (Section 4.2).
- *   Q, K, V, alpha, beta, mask : as in the forward (either routing; p->combine_mode must be 0, p->group 1).
+ *   Q, K, V, alpha, beta, mask : as in the forward (either routing; p->combine_mode must be 0).
  *             With routing per chunk the function differentiated is the one the
  *             forward computes there: both operations compute every chunk's inner part, the masks act between
  *             chunks, a softmax chunk hands on (its decay) x (the state at its start).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.
@@ -252,6 +252,11 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  *   dO      : in  [B,H,L,d] dtype p->dtype
  *   dQ, dK, dV : out [B,H,L,d] f32 (whatever p->dtype);  dalpha, dbeta : out [B,H,L] f32
  *   extra   : optional, may be NULL
+ *   head grouping (p->group = G > 1, Section 4.3; the softmax heads of a group use the linear head's Q and K):
+ *             V, dO, dV are [B,H*G,L,d] and initial_state, d_initial_state [B,H*G,d,d], head h*G + g the member g
+ *             of linear head h as in the forward; Q, K, alpha, beta, mask and their gradients, g_nla, g_la and the
+ *             score gradients stay [B,H,...]: a shared input's gradient is the sum over the G heads that read it.
+ *             The pass runs once per member (G times the work and a workspace larger by one member's tensors)
  *   workspace : at least nats_hybrid_attn_bwd_workspace_bytes(p); nothing is kept from the forward call, the
  *             backward recomputes what it needs (the state is checkpointed once per 64 tokens)
  * Sums over (batch, head)-internal blocks are taken in a fixed order: results are deterministic. */

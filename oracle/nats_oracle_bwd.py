@@ -254,3 +254,41 @@ def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=N
             for key in out:
                 out[key][b, h] = r[key]
     return out
+
+
+# --------------------------------------------------------------------------- #
+# head grouping (Section 4.3)
+# --------------------------------------------------------------------------- #
+def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=None, la_scale=1.0, S0=None,
+                       linear_op=0, decay_on_softmax=True):
+    """Backward of nats_oracle.hybrid_fwd_grouped (plain-sum merge, the softmax heads of a group use the linear
+    head's queries and keys).  Output head h G + g reads Q, K, alpha, beta, mask of linear head h and its own V
+    (its block of the wide state's rows never mixes with the other blocks, and its softmax head attends with the
+    same Q, K): it is a head of the ungrouped operator.  A shared input's gradient is therefore the sum over g of the
+    ungrouped gradients, and dV, dS0 are the members' own.
+    Shapes: Q, K [B,H,L,d]; alpha, beta [B,H,L]; mask [B,H,L] (or [B,H,L/C] with C given: routing per chunk);
+    V, dO [B,H G,L,d]; S0 [B,H G,d,d].  Returns dQ, dK, dalpha, dbeta and the score gradients per linear head,
+    dV [B,H G,L,d], dS0 [B,H G,d,d]."""
+    Q, K, V, dO = (np.asarray(a, dtype=np.float64) for a in (Q, K, V, dO))
+    B, H, L, d = Q.shape
+    assert V.shape == (B, H * G, L, d) and dO.shape == V.shape
+    out = None
+    dV = np.zeros_like(V)
+    dS0 = np.zeros((B, H * G, d, d))
+    for g in range(G):
+        Vg, dOg = V[:, g::G], dO[:, g::G]                    # heads h G + g, h = 0 .. H - 1
+        S0g = None if S0 is None else np.asarray(S0, dtype=np.float64)[:, g::G]
+        if C is None:
+            r = hybrid_bwd(Q, K, Vg, alpha, beta, mask, dOg, softmax_scale, la_scale, S0g, linear_op, decay_on_softmax)
+        else:
+            r = hybrid_bwd_chunk_routed(Q, K, Vg, alpha, beta, mask, C, dOg, softmax_scale, la_scale, S0g, linear_op,
+                                        decay_on_softmax)
+        dV[:, g::G] = r.pop("dV")
+        dS0[:, g::G] = r.pop("dS0")
+        if out is None:
+            out = {k: np.array(v, dtype=np.float64) for k, v in r.items()}
+        else:
+            for k, v in r.items():
+                out[k] += v
+    out["dV"], out["dS0"] = dV, dS0
+    return out

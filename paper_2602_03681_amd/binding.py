@@ -295,35 +295,39 @@ def hybrid_attn_fwd_noalloc(Q, K, V, alpha, beta, mask, out, C: int = 64, *, sof
 def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
                     linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False, initial_state=None,
                     want=(), workspace=None, routing: int = NATS_ROUTE_TOKEN,
-                    math: int = NATS_MATH_AUTO) -> Dict[str, torch.Tensor]:
+                    math: int = NATS_MATH_AUTO, group: int = 1) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla given dO.  Returns dQ, dK, dV [B,H,L,d] f32, dalpha,
     dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla, g_la [B,H,L] (routing per token),
     dscore_nla, dscore_la [B,H,L/C] (Eq. 16, Eq. 17).  math = NATS_MATH_FP32: the linear branch's adjoint token by
-    token instead of by chunks."""
+    token instead of by chunks.  group = G > 1 (head grouping): V, dO, dV [B,H*G,L,d], the states [B,H*G,d,d]."""
     lib = load_library()
     B, H, L, d = Q.shape
     dt = Q.dtype
-    for name, t in (("Q", Q), ("K", K), ("V", V), ("dO", dO)):
+    G = max(int(group), 1)
+    for name, t in (("Q", Q), ("K", K)):
         _require(t, name, (B, H, L, d), dt)
+    for name, t in (("V", V), ("dO", dO)):
+        _require(t, name, (B, H * G, L, d), dt)
     _require(alpha, "alpha", (B, H, L), torch.float32)
     _require(beta, "beta", (B, H, L), torch.float32)
     _require(mask, "mask", (B, H, L // C if routing == NATS_ROUTE_CHUNK else L), torch.uint8)
-    _require(initial_state, "initial_state", (B, H, d, d), torch.float32)
+    _require(initial_state, "initial_state", (B, H * G, d, d), torch.float32)
     unknown = set(want) - {"d_initial_state", "g_nla", "g_la", "dscore_nla", "dscore_la"}
     if unknown:
         raise ValueError(f"unknown outputs {sorted(unknown)}")
     params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, math,
-                             routing, linear_op, freeze_on_softmax)
+                             routing, linear_op, freeze_on_softmax, group=G)
     need = int(lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(params)))
     if need == 0:   # let the library say what is wrong with the parameters
         _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), *([None] * 12), None, None, 0, None))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     dev = Q.device
-    res = {k: torch.empty((B, H, L, d), dtype=torch.float32, device=dev) for k in ("dQ", "dK", "dV")}
+    res = {k: torch.empty((B, H, L, d), dtype=torch.float32, device=dev) for k in ("dQ", "dK")}
+    res["dV"] = torch.empty((B, H * G, L, d), dtype=torch.float32, device=dev)
     res["dalpha"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
     res["dbeta"] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
-    if "d_initial_state" in want: res["d_initial_state"] = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    if "d_initial_state" in want: res["d_initial_state"] = torch.empty((B, H * G, d, d), dtype=torch.float32, device=dev)
     for key in ("g_nla", "g_la"):
         if key in want: res[key] = torch.empty((B, H, L), dtype=torch.float32, device=dev)
     for key in ("dscore_nla", "dscore_la"):

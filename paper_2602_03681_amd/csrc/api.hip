@@ -190,6 +190,11 @@ static nats_status validate_fwd_params(const nats_fwd_params* p, FwdPlan* pl) {
 struct BwdPlan {
     size_t off_onla, off_lse, off_dvec, off_ckpt, off_scratch, off_dqp, off_dkp, off_dap, off_dbp, off_skp, off_svp, off_sgp,
         off_gnla, off_vis, off_dslap, off_ops, off_ug, off_uh, off_dck, off_vht, total;
+    // head grouping: the pass runs once per member of the groups on `total` bytes; behind them, one member's heads
+    // of V, dO, the initial state (gathered) and the member's gradients before they are added or scattered
+    int G;
+    size_t off_gv, off_gdo, off_gdv, off_gdq, off_gdk, off_gda, off_gdb, off_gs0, off_gds0, off_ggn, off_ggl, off_gsn,
+        off_gsl, total_grouped;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -221,22 +226,53 @@ static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     bp->off_dck = off;     off = align_up(off + ch * (1 - tk) * pl.BH * (pl.L / 64) * pl.d * pl.d * 4, 256);
     bp->off_vht = off;     off = align_up(off + n_tok * pl.d * 2, 256);   // fp16 V^T tiles of the compacted values (bf16 tensors)
     bp->total = off;
+    bp->G = 1;
+    bp->total_grouped = off;
 }
 
+// the buffers of one member of the groups, behind the workspace of the pass itself (pl: the plan of one member, G = 1)
+static void plan_bwd_group(const FwdPlan& pl, int G, BwdPlan* bp) {
+    const size_t n_tok = (size_t)pl.BH * pl.L, esz = pl.dtype == NATS_BF16 ? 2 : 4;
+    const size_t nd = n_tok * pl.d, st = (size_t)pl.BH * pl.d * pl.d;
+    size_t off = bp->total;
+    bp->G = G;
+    bp->off_gv = off;   off = align_up(off + nd * esz, 256);
+    bp->off_gdo = off;  off = align_up(off + nd * esz, 256);
+    bp->off_gdv = off;  off = align_up(off + nd * 4, 256);
+    bp->off_gdq = off;  off = align_up(off + nd * 4, 256);
+    bp->off_gdk = off;  off = align_up(off + nd * 4, 256);
+    bp->off_gda = off;  off = align_up(off + n_tok * 4, 256);
+    bp->off_gdb = off;  off = align_up(off + n_tok * 4, 256);
+    bp->off_gs0 = off;  off = align_up(off + st * 4, 256);
+    bp->off_gds0 = off; off = align_up(off + st * 4, 256);
+    bp->off_ggn = off;  off = align_up(off + n_tok * 4, 256);
+    bp->off_ggl = off;  off = align_up(off + n_tok * 4, 256);
+    bp->off_gsn = off;  off = align_up(off + (n_tok / pl.C) * 4, 256);
+    bp->off_gsl = off;  off = align_up(off + (n_tok / pl.C) * 4, 256);
+    bp->total_grouped = off;
+}
+
+// pl: the plan of the pass itself.  With head grouping (p->group = G > 1) that is the plan of one member of the groups,
+// B x H heads with G = 1, and bp->G = G.
 static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, BwdPlan* bp) {
-    nats_status st = validate_fwd_params(p, pl);
+    if (p == nullptr) { set_error("params is NULL"); return NATS_ERR_NULL; }
+    nats_fwd_params one = *p;
+    const int G = p->group > 1 ? p->group : 1;
+    if (G > 8) { set_error("group must be at most 8 (got %d)", p->group); return NATS_ERR_SHAPE; }
+    one.group = 1;
+    nats_status st = validate_fwd_params(&one, pl);
     if (st != NATS_OK) return st;
     if (pl->combine_mode != 0) {
         set_error("the backward pass covers the plain-sum merge (combine_mode %d given)", pl->combine_mode);
         return NATS_ERR_UNSUPPORTED;
     }
-    if (pl->G != 1) { set_error("the backward pass has no head grouping (group %d given)", pl->G); return NATS_ERR_UNSUPPORTED; }
     if (pl->inner_chunk != 0) { set_error("the backward pass covers inner_chunk 0 only (got %d)", pl->inner_chunk); return NATS_ERR_UNSUPPORTED; }
     if (pl->routing == NATS_ROUTE_CHUNK && pl->RC != 64) {
         set_error("the backward pass with routing per chunk covers chunks of 64 tokens (C=%d given)", pl->RC);
         return NATS_ERR_UNSUPPORTED;
     }
     plan_bwd(*pl, bp);
+    if (G > 1) plan_bwd_group(*pl, G, bp);
     return NATS_OK;
 }
 
@@ -275,7 +311,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 110; }
+int nats_abi_version(void) { return 111; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -450,42 +486,15 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p) {
     FwdPlan pl;
     BwdPlan bp;
     if (validate_bwd_params(p, &pl, &bp) != NATS_OK) return 0;
-    return bp.total;
+    return bp.total_grouped;
 }
 
-nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
-                                 const float* alpha, const float* beta, const uint8_t* mask, const void* dO,
-                                 float* dQ, float* dK, float* dV, float* dalpha, float* dbeta,
-                                 const nats_bwd_extra* extra, void* workspace, size_t workspace_bytes,
-                                 void* hip_stream) {
-    FwdPlan pl;
-    BwdPlan bp;
-    nats_status st = validate_bwd_params(p, &pl, &bp);
-    if (st != NATS_OK) return st;
-    if (!Q || !K || !V || !alpha || !beta || !mask || !dO || !dQ || !dK || !dV || !dalpha || !dbeta) {
-        set_error("Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha and dbeta must all be non-NULL");
-        return NATS_ERR_NULL;
-    }
-    if (workspace == nullptr || workspace_bytes < bp.total) {
-        set_error("workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, bp.total);
-        return NATS_ERR_WORKSPACE;
-    }
-    nats_bwd_extra ex;
-    memset(&ex, 0, sizeof(ex));
-    if (extra) ex = *extra;
-    const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
-                          ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la};
-    for (const void* ptr : ptrs)
-        if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
-    const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
-    for (const void* o : outs)
-        if (o == Q || o == K || o == V || o == dO || o == alpha || o == beta) {
-            set_error("a gradient output must not alias an input");
-            return NATS_ERR_SHAPE;
-        }
-
-    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    char* ws = static_cast<char*>(workspace);
+// The backward pass on B x H heads without grouping (pl.G = 1).  ex by value: the optional outputs may be redirected.
+static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q, const void* K, const void* V,
+                            const float* alpha, const float* beta, const uint8_t* mask, const void* dO, float* dQ,
+                            float* dK, float* dV, float* dalpha, float* dbeta, nats_bwd_extra ex, char* ws,
+                            hipStream_t stream) {
+    nats_status st = NATS_OK;
     int32_t* cnt = reinterpret_cast<int32_t*>(ws + pl.off_cnt);
     int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
     int32_t* n_s = reinterpret_cast<int32_t*>(ws + pl.off_ns);
@@ -597,6 +606,99 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         ProfScope ps("score_gradients", stream);
         st = chunk ? launch_score_gradients_chunk(pl, ex.g_nla, dslap, ex.dscore_nla, ex.dscore_la, stream)
                    : launch_score_gradients(pl, beta, mask, dbeta, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, stream);
+    }
+    return st;
+}
+
+
+nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const void* K, const void* V,
+                                 const float* alpha, const float* beta, const uint8_t* mask, const void* dO,
+                                 float* dQ, float* dK, float* dV, float* dalpha, float* dbeta,
+                                 const nats_bwd_extra* extra, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+    FwdPlan pl;
+    BwdPlan bp;
+    nats_status st = validate_bwd_params(p, &pl, &bp);
+    if (st != NATS_OK) return st;
+    if (!Q || !K || !V || !alpha || !beta || !mask || !dO || !dQ || !dK || !dV || !dalpha || !dbeta) {
+        set_error("Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha and dbeta must all be non-NULL");
+        return NATS_ERR_NULL;
+    }
+    if (workspace == nullptr || workspace_bytes < bp.total_grouped) {
+        set_error("workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, bp.total_grouped);
+        return NATS_ERR_WORKSPACE;
+    }
+    nats_bwd_extra ex;
+    memset(&ex, 0, sizeof(ex));
+    if (extra) ex = *extra;
+    const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
+                          ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la};
+    for (const void* ptr : ptrs)
+        if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
+    const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
+    for (const void* o : outs)
+        if (o == Q || o == K || o == V || o == dO || o == alpha || o == beta) {
+            set_error("a gradient output must not alias an input");
+            return NATS_ERR_SHAPE;
+        }
+
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (bp.G == 1) return bwd_core(pl, bp, Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, ex, ws, stream);
+
+    // Head grouping (Section 4.3): member g of every group, i.e. the output heads bh G + g, is a problem of B x H heads
+    // with the linear heads' Q, K, alpha, beta and mask.  Its V, dO and initial state are gathered, the pass runs on
+    // them, its dV and state gradient go back to its heads, and what it sends to the shared inputs (dQ, dK, dalpha,
+    // dbeta, the score gradients) is added up over the members.
+    const int G = bp.G;
+    const size_t n_tok = (size_t)pl.BH * pl.L, nd = n_tok * pl.d, esz = pl.dtype == NATS_BF16 ? 2 : 4;
+    const size_t row = (size_t)pl.L * pl.d, srow = (size_t)pl.d * pl.d;
+    void* Vg = ws + bp.off_gv;
+    void* dOg = ws + bp.off_gdo;
+    float* dVg = reinterpret_cast<float*>(ws + bp.off_gdv);
+    float* S0g = reinterpret_cast<float*>(ws + bp.off_gs0);
+    float* dS0g = reinterpret_cast<float*>(ws + bp.off_gds0);
+    for (int g = 0; g < G; ++g) {
+        const bool first = g == 0;
+        st = launch_copy_rows(static_cast<const char*>(V) + g * row * esz, G * row * esz, Vg, row * esz, row * esz, pl.BH, stream);
+        if (st != NATS_OK) return st;
+        st = launch_copy_rows(static_cast<const char*>(dO) + g * row * esz, G * row * esz, dOg, row * esz, row * esz, pl.BH, stream);
+        if (st != NATS_OK) return st;
+        nats_bwd_extra e1;
+        memset(&e1, 0, sizeof(e1));
+        if (ex.initial_state) {
+            st = launch_copy_rows(ex.initial_state + g * srow, G * srow * 4, S0g, srow * 4, srow * 4, pl.BH, stream);
+            if (st != NATS_OK) return st;
+            e1.initial_state = S0g;
+        }
+        if (ex.d_initial_state) e1.d_initial_state = dS0g;
+        // the first member writes the sums' buffers themselves, the others a buffer of their own that is then added
+        if (ex.g_nla) e1.g_nla = first ? ex.g_nla : reinterpret_cast<float*>(ws + bp.off_ggn);
+        if (ex.g_la) e1.g_la = first ? ex.g_la : reinterpret_cast<float*>(ws + bp.off_ggl);
+        if (ex.dscore_nla) e1.dscore_nla = first ? ex.dscore_nla : reinterpret_cast<float*>(ws + bp.off_gsn);
+        if (ex.dscore_la) e1.dscore_la = first ? ex.dscore_la : reinterpret_cast<float*>(ws + bp.off_gsl);
+        float* dQg = first ? dQ : reinterpret_cast<float*>(ws + bp.off_gdq);
+        float* dKg = first ? dK : reinterpret_cast<float*>(ws + bp.off_gdk);
+        float* dag = first ? dalpha : reinterpret_cast<float*>(ws + bp.off_gda);
+        float* dbg = first ? dbeta : reinterpret_cast<float*>(ws + bp.off_gdb);
+        st = bwd_core(pl, bp, Q, K, Vg, alpha, beta, mask, dOg, dQg, dKg, dVg, dag, dbg, e1, ws, stream);
+        if (st != NATS_OK) return st;
+        st = launch_copy_rows(dVg, row * 4, dV + g * row, G * row * 4, row * 4, pl.BH, stream);
+        if (st != NATS_OK) return st;
+        if (ex.d_initial_state) {
+            st = launch_copy_rows(dS0g, srow * 4, ex.d_initial_state + g * srow, G * srow * 4, srow * 4, pl.BH, stream);
+            if (st != NATS_OK) return st;
+        }
+        if (first) continue;
+        struct { float* sum; const float* part; size_t n; } adds[] = {
+            {dQ, dQg, nd}, {dK, dKg, nd}, {dalpha, dag, n_tok}, {dbeta, dbg, n_tok},
+            {ex.g_nla, e1.g_nla, n_tok}, {ex.g_la, e1.g_la, n_tok},
+            {ex.dscore_nla, e1.dscore_nla, n_tok / pl.C}, {ex.dscore_la, e1.dscore_la, n_tok / pl.C}};
+        for (const auto& a : adds) {
+            if (a.sum == nullptr) continue;
+            st = launch_add_f32(a.sum, a.part, a.n, stream);
+            if (st != NATS_OK) return st;
+        }
     }
     return st;
 }

@@ -297,6 +297,10 @@ nats_status launch_visible_rows(const FwdPlan& pl, const int32_t* cnt, int32_t* 
 nats_status launch_softmax_bwd_own_chunk(const FwdPlan& pl, const void* Q, const void* K, const void* V, const void* dO,
                                          const float* lse, const float* Dvec, float* dQ, float* dK, float* dV,
                                          hipStream_t st);
+// head grouping in the backward pass (head_group.hip)
+nats_status launch_copy_rows(const void* src, size_t src_stride_bytes, void* dst, size_t dst_stride_bytes,
+                             size_t row_bytes, size_t n_rows, hipStream_t st);
+nats_status launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);
 nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
                                          float* dscore_la, hipStream_t st);   // ds_la_part NULL: dscore_la is left as it is
 nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,

@@ -37,9 +37,10 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 110   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    assert lib.nats_abi_version() == 111   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
     # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group, decode workspace;
-    # 110: p->math selects the form of the backward's linear adjoint, C = 128 with routing per chunk
+    # 110: p->math selects the form of the backward's linear adjoint, C = 128 with routing per chunk; 111: the backward
+    # pass takes p->group
 
 
 def good_params(**over):
@@ -234,7 +235,12 @@ def test_head_grouping_is_validated_on_the_host(lib):
     one, three = nb.fwd_workspace_bytes(good_params(group=0)), nb.fwd_workspace_bytes(good_params(group=3))
     assert one == nb.fwd_workspace_bytes(good_params(group=1))
     assert one < three < 3 * one     # rows per output head grow with the group, the integers do not
-    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=2))) == 0
+    # the backward pass runs once per member of the groups: its own workspace plus one member's tensors
+    b1 = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=1)))
+    b2 = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=2)))
+    b3 = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=3)))
+    assert 0 < b1 < b2 == b3
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(group=9))) == 0
     assert b"group" in lib.nats_last_error()
 
 

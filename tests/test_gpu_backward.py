@@ -228,3 +228,43 @@ def test_backward_with_routing_per_chunk_degenerate_masks(kind, math):
     r = run_bwd(x, dO, "f32", routing=nb.NATS_ROUTE_CHUNK, want=("dscore_nla", "dscore_la"), math=math)
     ref = nbw.hybrid_bwd_chunk_routed(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], 64, dO)
     check(r, ref, extra=CHUNK_KEYS[1:])
+
+
+# ---- head grouping (Section 4.3): G output heads share the Q, K, alpha, beta and mask of a linear head ----------------
+@pytest.mark.parametrize("dtype,B,H,G,L,d", [("f32", 1, 2, 2, 256, 64), ("bf16", 2, 1, 3, 320, 128),
+                                             ("bf16", 1, 2, 2, 512, 64)])
+@pytest.mark.parametrize("routing", ["token", "chunk"])
+def test_backward_with_head_grouping(dtype, B, H, G, L, d, routing):
+    """V, dO, dV and the states have H G heads; the gradients of the shared inputs (and the score gradients) are sums
+    over the heads of a group."""
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=900 + L + G)
+    xv = make_fwd_inputs(B, H * G, L, d, dtype, 0.15, seed=901 + L + G)
+    x["V"] = xv["V"]
+    dO = make_grad_output(B, H * G, L, d, dtype, seed=902 + L)
+    S0 = (0.05 * np.random.default_rng(L + G).standard_normal((B, H * G, d, d))).astype(np.float32)
+    if routing == "chunk":
+        x["mask"] = make_chunk_mask(B, H, L // 64, 0.35, 903 + L, "bernoulli")
+        want = ("d_initial_state", "dscore_nla", "dscore_la")
+        r = run_bwd(x, dO, dtype, S0=S0, routing=nb.NATS_ROUTE_CHUNK, want=want, group=G)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=64, S0=S0)
+        extra = CHUNK_KEYS
+    else:
+        want = ("d_initial_state", "g_nla", "g_la", "dscore_nla", "dscore_la")
+        r = run_bwd(x, dO, dtype, S0=S0, want=want, group=G)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, S0=S0)
+        ref["dscore_nla"], ref["dscore_la"] = nbw.score_gradients(ref["g_nla"], ref["g_la"], 64)
+        extra = (("d_initial_state", "dS0"), ("g_nla", "g_nla"), ("g_la", "g_la"), ("dscore_nla", "dscore_nla"),
+                 ("dscore_la", "dscore_la"))
+    assert tuple(r["dV"].shape) == (B, H * G, L, d) and tuple(r["dQ"].shape) == (B, H, L, d)
+    errs = check(r, ref, extra=extra)
+    print(dtype, G, routing, errs)
+
+
+def test_head_grouping_of_one_is_the_plain_backward():
+    B, H, L, d = 1, 2, 256, 64
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.2, seed=950)
+    dO = make_grad_output(B, H, L, d, "bf16", seed=951)
+    r1 = run_bwd(x, dO, "bf16")
+    r2 = run_bwd(x, dO, "bf16", group=1)
+    for k in ("dQ", "dK", "dV", "dalpha", "dbeta"):
+        assert torch.equal(r1[k], r2[k]), k

@@ -88,3 +88,50 @@ def test_wide_linear_head_against_transition_matrices():
     for g in range(G):
         np.testing.assert_allclose(got["O_la"][0, g], o[:, g * d:(g + 1) * d], rtol=1e-10, atol=1e-12)
         np.testing.assert_allclose(got["S"][0, g], S[g * d:(g + 1) * d], rtol=1e-10, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- #
+# backward with head grouping
+# --------------------------------------------------------------------------- #
+def _grouped_loss(x, G, dO, S0, C=None):
+    r = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], G, C=C, S0=S0)
+    return float((r["O"] * dO).sum())
+
+
+@pytest.mark.parametrize("G,routing_chunk", [(2, False), (3, False), (2, True)])
+def test_grouped_backward_against_finite_differences_of_the_grouped_forward(G, routing_chunk):
+    """The gradient of a shared input is the sum over the heads of its group: single entries of every gradient
+    against central differences of sum(dO . O) of the grouped forward oracle (an independent function: the wide
+    state of a linear head, one recurrence for the whole group)."""
+    from oracle import nats_oracle_bwd as ob
+    from nats_inputs import make_chunk_mask
+    B, H, L, d, C = 1, 2, 16, 4, 4
+    x = grouped_inputs(B, H, G, L, d, 0.3, seed=40 + G, own_qk=False)
+    x = {k: np.asarray(v, dtype=np.float64) for k, v in x.items() if v is not None}
+    x["mask"] = x["mask"].astype(np.uint8)
+    Cc = None
+    if routing_chunk:
+        Cc = C
+        x["mask"] = make_chunk_mask(B, H, L // C, 0.4, 77)
+        x["mask"][:, :, 0] = 1
+    rng = np.random.default_rng(5)
+    dO = rng.standard_normal((B, H * G, L, d))
+    S0 = 0.3 * rng.standard_normal((B, H * G, d, d))
+    got = ob.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=Cc, S0=S0)
+    eps = 1e-6
+    for key, name in (("Q", "dQ"), ("K", "dK"), ("V", "dV"), ("alpha", "dalpha"), ("beta", "dbeta")):
+        for _ in range(4):
+            pos = tuple(int(rng.integers(0, n)) for n in x[key].shape)
+            xp = {k: v.copy() for k, v in x.items()}
+            xm = {k: v.copy() for k, v in x.items()}
+            xp[key][pos] += eps
+            xm[key][pos] -= eps
+            fd = (_grouped_loss(xp, G, dO, S0, Cc) - _grouped_loss(xm, G, dO, S0, Cc)) / (2 * eps)
+            assert abs(fd - got[name][pos]) <= 2e-6 * max(1.0, abs(fd)), (key, pos, fd, got[name][pos])
+    for _ in range(4):
+        pos = tuple(int(rng.integers(0, n)) for n in S0.shape)
+        Sp, Sm = S0.copy(), S0.copy()
+        Sp[pos] += eps
+        Sm[pos] -= eps
+        fd = (_grouped_loss(x, G, dO, Sp, Cc) - _grouped_loss(x, G, dO, Sm, Cc)) / (2 * eps)
+        assert abs(fd - got["dS0"][pos]) <= 2e-6 * max(1.0, abs(fd)), (pos, fd, got["dS0"][pos])
