@@ -440,7 +440,13 @@ def main():
     out["algorithmic_TFLOPs"] = round(flop_total / (ms_per_step * 1e-3) / 1e12, 2)
     out["mfma_frac_whole_forward"] = round(flop_total / (ms_per_step * 1e-3) / 1e12 / PEAK["mfma"][0], 4)
     tr = [measured_traffic_bytes(k) for k in per_step]
-    out["hbm_bytes"] = {"compulsory": compulsory, "measured": sum(tr) if tr and all(t is not None for t in tr) else None}
+    measured = sum(tr) if tr and all(t is not None for t in tr) else None
+    out["hbm_bytes"] = {"compulsory": compulsory, "measured": measured}
+    # HBM rate of the whole step: the bytes the counters saw per call (committed summary) over this run's step time,
+    # against the published 8 TB/s
+    if measured is not None:
+        gbps = measured / (ms_per_step * 1e-3) / 1e9
+        out["hbm_GBps"] = {"achieved": round(gbps, 1), "peak": PEAK["hbm"][0], "frac": round(gbps / PEAK["hbm"][0], 4)}
     print(json.dumps(out))
 
 
