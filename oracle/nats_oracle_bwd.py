@@ -113,28 +113,42 @@ def softmax_branch_bwd(q, k, v, mask, scale, do):
 
 
 def hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-                    decay_on_softmax=True):
-    """Backward of nats_oracle.hybrid_head with the plain-sum merge: dO goes to both branches as it is."""
+                    decay_on_softmax=True, q_nla=None, k_nla=None):
+    """Backward of nats_oracle.hybrid_head with the plain-sum merge: dO goes to both branches as it is.
+    q_nla, k_nla (both or neither; Section 4.3: the two operations normalise the shared projections differently): the
+    softmax branch's own queries and keys.  Their gradients are then returned apart as dQ_nla, dK_nla, and dQ, dK are
+    the linear branch's alone; V is shared, dV stays the sum."""
     d_k = np.asarray(q).shape[-1]
     scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
     la = gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, la_scale, linear_op, decay_on_softmax)
-    nla = softmax_branch_bwd(q, k, v, mask, scale, do)
-    return {"dQ": la["dq"] + nla["dq"], "dK": la["dk"] + nla["dk"], "dV": la["dv"] + nla["dv"],
-            "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_nla": nla["g"], "g_la": la["g_la"]}
+    out = {"dV": None, "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_la": la["g_la"]}
+    if q_nla is None:
+        nla = softmax_branch_bwd(q, k, v, mask, scale, do)
+        out.update(dQ=la["dq"] + nla["dq"], dK=la["dk"] + nla["dk"])
+    else:
+        nla = softmax_branch_bwd(q_nla, k_nla, v, mask, scale, do)
+        out.update(dQ=la["dq"], dK=la["dk"], dQ_nla=nla["dq"], dK_nla=nla["dk"])
+    out["dV"] = la["dv"] + nla["dv"]
+    out["g_nla"] = nla["g"]
+    return out
 
 
 def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-               decay_on_softmax=True):
-    """All (b,h) of [B,H,L,d] inputs; returns a dict of stacked fp64 arrays."""
+               decay_on_softmax=True, Q_nla=None, K_nla=None):
+    """All (b,h) of [B,H,L,d] inputs; returns a dict of stacked fp64 arrays (with Q_nla, K_nla [B,H,L,d] also
+    dQ_nla, dK_nla)."""
     B, H, L, d = np.asarray(Q).shape
     out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
            "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
            "g_nla": np.zeros((B, H, L)), "g_la": np.zeros((B, H, L))}
+    if Q_nla is not None:
+        out.update(dQ_nla=np.zeros((B, H, L, d)), dK_nla=np.zeros((B, H, L, d)))
     for b in range(B):
         for h in range(H):
             r = hybrid_head_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask[b, h], dO[b, h],
                                 softmax_scale, la_scale, None if S0 is None else S0[b, h], linear_op,
-                                decay_on_softmax)
+                                decay_on_softmax, None if Q_nla is None else Q_nla[b, h],
+                                None if K_nla is None else K_nla[b, h])
             for key in out:
                 out[key][b, h] = r[key]
     return out
@@ -144,7 +158,7 @@ def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0,
 # routing per chunk (Section 4.1 as stated; Section 4.2 for the score gradients)
 # --------------------------------------------------------------------------- #
 def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_scale=None, la_scale=1.0, S0=None,
-                                 linear_op=0, decay_on_softmax=True):
+                                 linear_op=0, decay_on_softmax=True, q_nla=None, k_nla=None):
     """Adjoint of nats_oracle.hybrid_head_chunk_routed (plain-sum merge).
 
     Forward being differentiated, per chunk c with carried state S_c: inside the chunk Eq. 19 runs on every token
@@ -155,8 +169,13 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
     later chunks of dM_ij (Eq. 15-16; the inner part of a chunk is computed whatever its type, no mask stands on
     it); dscore_la[c] = sum(dS_{c+1} . (S_{c+1} - decay_c S_c)) for a linear chunk (Eq. 17); zero where the chunk is
     inactive for the operation.
+    q_nla, k_nla (both or neither): the softmax branch's own queries and keys; their gradients come back apart as
+    dQ_nla, dK_nla and dQ, dK are the linear branch's alone.
     Returns dict(dQ, dK, dV [L,d], dalpha, dbeta [L], dS0, dscore_nla, dscore_la [L/C])."""
     q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
+    own_qk = q_nla is not None
+    qn = np.asarray(q_nla, dtype=np.float64) if own_qk else q
+    kn = np.asarray(k_nla, dtype=np.float64) if own_qk else k
     alpha = np.asarray(alpha, dtype=np.float64)
     beta = np.asarray(beta, dtype=np.float64)
     mask_c = np.asarray(mask_c).reshape(-1) != 0
@@ -165,6 +184,7 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
     n_c = L // C
     scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    dqn, dkn = (np.zeros_like(q), np.zeros_like(k)) if own_qk else (dq, dk)   # shared: both branches add to dq, dk
     dalpha, dbeta = np.zeros(L), np.zeros(L)
     ds_nla, ds_la = np.zeros(n_c), np.zeros(n_c)
 
@@ -174,7 +194,7 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
         for i in range(c * C, (c + 1) * C):
             own = list(range(c * C, i + 1))
             J = np.asarray(earlier + own, dtype=np.int64)
-            s = scale * (k[J] @ q[i])
+            s = scale * (kn[J] @ qn[i])
             p = np.exp(s - s.max())
             p /= p.sum()
             o = p @ v[J]
@@ -182,8 +202,8 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
             for jj, j in enumerate(J[:len(earlier)]):      # only these columns stand behind the mask
                 ds_nla[j // C] += dm[jj]
             dv[J] += np.outer(p, do[i])
-            dq[i] += scale * (dm @ k[J])
-            dk[J] += scale * np.outer(dm, q[i])
+            dqn[i] += scale * (dm @ kn[J])
+            dkn[J] += scale * np.outer(dm, qn[i])
         if mask_c[c]:
             earlier += list(range(c * C, (c + 1) * C))
 
@@ -235,22 +255,29 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
             else:
                 dS = dS + dS_next
         dS_next = dS
-    return {"dQ": dq, "dK": dk, "dV": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS_next,
-            "dscore_nla": ds_nla, "dscore_la": ds_la}
+    out = {"dQ": dq, "dK": dk, "dV": dv, "dalpha": dalpha, "dbeta": dbeta, "dS0": dS_next,
+           "dscore_nla": ds_nla, "dscore_la": ds_la}
+    if own_qk:
+        out.update(dQ_nla=dqn, dK_nla=dkn)
+    return out
 
 
 def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-                            decay_on_softmax=True):
-    """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; returns a dict of stacked fp64 arrays."""
+                            decay_on_softmax=True, Q_nla=None, K_nla=None):
+    """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; returns a dict of stacked fp64 arrays (with Q_nla, K_nla
+    [B,H,L,d] also dQ_nla, dK_nla)."""
     B, H, L, d = np.asarray(Q).shape
     out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
            "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
            "dscore_nla": np.zeros((B, H, L // C)), "dscore_la": np.zeros((B, H, L // C))}
+    if Q_nla is not None:
+        out.update(dQ_nla=np.zeros((B, H, L, d)), dK_nla=np.zeros((B, H, L, d)))
     for b in range(B):
         for h in range(H):
             r = hybrid_head_chunk_routed_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask_c[b, h], C,
                                              dO[b, h], softmax_scale, la_scale, None if S0 is None else S0[b, h],
-                                             linear_op, decay_on_softmax)
+                                             linear_op, decay_on_softmax, None if Q_nla is None else Q_nla[b, h],
+                                             None if K_nla is None else K_nla[b, h])
             for key in out:
                 out[key][b, h] = r[key]
     return out
@@ -260,7 +287,7 @@ def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=N
 # head grouping (Section 4.3)
 # --------------------------------------------------------------------------- #
 def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=None, la_scale=1.0, S0=None,
-                       linear_op=0, decay_on_softmax=True):
+                       linear_op=0, decay_on_softmax=True, Q_nla=None, K_nla=None):
     """Backward of nats_oracle.hybrid_fwd_grouped (plain-sum merge, the softmax heads of a group use the linear
     head's queries and keys).  Output head h G + g reads Q, K, alpha, beta, mask of linear head h and its own V
     (its block of the wide state's rows never mixes with the other blocks, and its softmax head attends with the
@@ -268,27 +295,38 @@ def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=
     ungrouped gradients, and dV, dS0 are the members' own.
     Shapes: Q, K [B,H,L,d]; alpha, beta [B,H,L]; mask [B,H,L] (or [B,H,L/C] with C given: routing per chunk);
     V, dO [B,H G,L,d]; S0 [B,H G,d,d].  Returns dQ, dK, dalpha, dbeta and the score gradients per linear head,
-    dV [B,H G,L,d], dS0 [B,H G,d,d]."""
+    dV [B,H G,L,d], dS0 [B,H G,d,d].  Q_nla, K_nla [B,H G,L,d]: the softmax heads' own queries and keys; their
+    gradients dQ_nla, dK_nla [B,H G,L,d] are each member's own, and dQ, dK are the linear branch's, summed over g."""
     Q, K, V, dO = (np.asarray(a, dtype=np.float64) for a in (Q, K, V, dO))
     B, H, L, d = Q.shape
     assert V.shape == (B, H * G, L, d) and dO.shape == V.shape
     out = None
     dV = np.zeros_like(V)
     dS0 = np.zeros((B, H * G, d, d))
+    own = {}
+    if Q_nla is not None:
+        Q_nla, K_nla = np.asarray(Q_nla, dtype=np.float64), np.asarray(K_nla, dtype=np.float64)
+        own = {"dQ_nla": np.zeros_like(V), "dK_nla": np.zeros_like(V)}
     for g in range(G):
         Vg, dOg = V[:, g::G], dO[:, g::G]                    # heads h G + g, h = 0 .. H - 1
         S0g = None if S0 is None else np.asarray(S0, dtype=np.float64)[:, g::G]
+        Qn = None if Q_nla is None else Q_nla[:, g::G]
+        Kn = None if K_nla is None else K_nla[:, g::G]
         if C is None:
-            r = hybrid_bwd(Q, K, Vg, alpha, beta, mask, dOg, softmax_scale, la_scale, S0g, linear_op, decay_on_softmax)
+            r = hybrid_bwd(Q, K, Vg, alpha, beta, mask, dOg, softmax_scale, la_scale, S0g, linear_op, decay_on_softmax,
+                           Qn, Kn)
         else:
             r = hybrid_bwd_chunk_routed(Q, K, Vg, alpha, beta, mask, C, dOg, softmax_scale, la_scale, S0g, linear_op,
-                                        decay_on_softmax)
+                                        decay_on_softmax, Qn, Kn)
         dV[:, g::G] = r.pop("dV")
         dS0[:, g::G] = r.pop("dS0")
+        for key in own:
+            own[key][:, g::G] = r.pop(key)
         if out is None:
             out = {k: np.array(v, dtype=np.float64) for k, v in r.items()}
         else:
             for k, v in r.items():
                 out[k] += v
     out["dV"], out["dS0"] = dV, dS0
+    out.update(own)
     return out

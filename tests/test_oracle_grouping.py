@@ -135,3 +135,50 @@ def test_grouped_backward_against_finite_differences_of_the_grouped_forward(G, r
         Sm[pos] -= eps
         fd = (_grouped_loss(x, G, dO, Sp, Cc) - _grouped_loss(x, G, dO, Sm, Cc)) / (2 * eps)
         assert abs(fd - got["dS0"][pos]) <= 2e-6 * max(1.0, abs(fd)), (pos, fd, got["dS0"][pos])
+
+
+def _own_qk_loss(x, G, dO, S0, C=None):
+    r = npo.hybrid_fwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], G, C=C, S0=S0,
+                               Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    return float((r["O"] * dO).sum())
+
+
+@pytest.mark.parametrize("G,routing_chunk", [(1, False), (1, True), (2, False), (3, True)])
+def test_backward_with_own_softmax_queries_and_keys_against_finite_differences(G, routing_chunk):
+    """Softmax heads with queries and keys of their own (Section 4.3): dQ_nla, dK_nla are the softmax branch's
+    gradients, dQ, dK the linear branch's alone, dV the sum.  Single entries of each against central differences of
+    sum(dO . O) of the forward oracle called with Q_nla, K_nla."""
+    from oracle import nats_oracle_bwd as ob
+    B, H, L, d, C = 1, 2, 16, 4, 4
+    x = grouped_inputs(B, H, G, L, d, 0.3, seed=60 + G, own_qk=True)
+    x = {k: np.asarray(v, dtype=np.float64) for k, v in x.items() if v is not None}
+    x["mask"] = x["mask"].astype(np.uint8)
+    Cc = None
+    if routing_chunk:
+        Cc = C
+        x["mask"] = make_chunk_mask(B, H, L // C, 0.4, 78)
+        x["mask"][:, :, 0] = 1
+    rng = np.random.default_rng(6)
+    dO = rng.standard_normal((B, H * G, L, d))
+    S0 = 0.3 * rng.standard_normal((B, H * G, d, d))
+    got = ob.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=Cc, S0=S0,
+                                Q_nla=x["Q_nla"], K_nla=x["K_nla"])
+    assert got["dQ_nla"].shape == (B, H * G, L, d) and got["dK_nla"].shape == (B, H * G, L, d)
+    eps = 1e-6
+    for key, name in (("Q", "dQ"), ("K", "dK"), ("V", "dV"), ("Q_nla", "dQ_nla"), ("K_nla", "dK_nla"),
+                      ("alpha", "dalpha"), ("beta", "dbeta")):
+        for _ in range(5):
+            pos = tuple(int(rng.integers(0, n)) for n in x[key].shape)
+            xp = {k: v.copy() for k, v in x.items()}
+            xm = {k: v.copy() for k, v in x.items()}
+            xp[key][pos] += eps
+            xm[key][pos] -= eps
+            fd = (_own_qk_loss(xp, G, dO, S0, Cc) - _own_qk_loss(xm, G, dO, S0, Cc)) / (2 * eps)
+            assert abs(fd - got[name][pos]) <= 2e-6 * max(1.0, abs(fd)), (key, pos, fd, got[name][pos])
+    # with the same tensors given twice the split gradients add up to the shared ones
+    if G == 1:
+        both = ob.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=Cc, S0=S0)
+        same = ob.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=Cc, S0=S0,
+                                     Q_nla=x["Q"], K_nla=x["K"])
+        np.testing.assert_allclose(same["dQ"] + same["dQ_nla"], both["dQ"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(same["dK"] + same["dK_nla"], both["dK"], rtol=1e-12, atol=1e-13)
