@@ -229,6 +229,10 @@ typedef struct nats_bwd_extra {
                                    the mask gradients between chunks (the inner part of a chunk is computed by
                                    both operations whatever its type, no mask stands on it); a chunk gets no
                                    gradient for the operation it is inactive for (Section 4.2)                   */
+    const void* Q_nla;          /* in  [B,H*G,L,d] dtype p->dtype: queries and keys of the softmax branch given apart */
+    const void* K_nla;          /*     (as nats_fwd_extra.Q_nla, K_nla; both or neither, NULL = the branch uses Q, K) */
+    float* dQ_nla;              /* out [B,H*G,L,d] f32: their gradients (required with Q_nla, K_nla).  dQ and dK are     */
+    float* dK_nla;              /*     then the linear branch's gradients alone                                        */
 } nats_bwd_extra;
 
 size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
@@ -252,7 +256,8 @@ size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
  *   dO      : in  [B,H,L,d] dtype p->dtype
  *   dQ, dK, dV : out [B,H,L,d] f32 (whatever p->dtype);  dalpha, dbeta : out [B,H,L] f32
  *   extra   : optional, may be NULL
- *   head grouping (p->group = G > 1, Section 4.3; the softmax heads of a group use the linear head's Q and K):
+ *   head grouping (p->group = G > 1, Section 4.3; the softmax heads of a group use the linear head's Q and K, or
+ *             their own, extra->Q_nla, K_nla with H*G heads):
  *             V, dO, dV are [B,H*G,L,d] and initial_state, d_initial_state [B,H*G,d,d], head h*G + g the member g
  *             of linear head h as in the forward; Q, K, alpha, beta, mask and their gradients, g_nla, g_la and the
  *             score gradients stay [B,H,...]: a shared input's gradient is the sum over the G heads that read it.

@@ -194,7 +194,7 @@ struct BwdPlan {
     // of V, dO, the initial state (gathered) and the member's gradients before they are added or scattered
     int G;
     size_t off_gv, off_gdo, off_gdv, off_gdq, off_gdk, off_gda, off_gdb, off_gs0, off_gds0, off_ggn, off_ggl, off_gsn,
-        off_gsl, total_grouped;
+        off_gsl, off_gqn, off_gkn, off_gdqn, off_gdkn, total_grouped;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -249,6 +249,11 @@ static void plan_bwd_group(const FwdPlan& pl, int G, BwdPlan* bp) {
     bp->off_ggl = off;  off = align_up(off + n_tok * 4, 256);
     bp->off_gsn = off;  off = align_up(off + (n_tok / pl.C) * 4, 256);
     bp->off_gsl = off;  off = align_up(off + (n_tok / pl.C) * 4, 256);
+    // the member's own queries and keys of the softmax branch and their gradients (used if Q_nla, K_nla are given)
+    bp->off_gqn = off;  off = align_up(off + nd * esz, 256);
+    bp->off_gkn = off;  off = align_up(off + nd * esz, 256);
+    bp->off_gdqn = off; off = align_up(off + nd * 4, 256);
+    bp->off_gdkn = off; off = align_up(off + nd * 4, 256);
     bp->total_grouped = off;
 }
 
@@ -311,7 +316,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 111; }
+int nats_abi_version(void) { return 112; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -518,21 +523,30 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     // routing per chunk, token by token: the sweep's partials of Eq. 17 (by chunks the gradient kernel writes dscore_la)
     float* dslap = (chunk && ex.dscore_la != nullptr && pl.math == NATS_MATH_FP32)
                        ? reinterpret_cast<float*>(ws + bp.off_dslap) : nullptr;
+    // The softmax branch's queries and keys, and where their gradients go: with tensors of their own (Section 4.3:
+    // the two operations normalise the shared projections differently) dQs / dKs are separate outputs, start from zero,
+    // and dQ, dK hold the linear branch's gradients alone.
+    const bool own_qk = ex.Q_nla != nullptr;
+    const void* Qs = own_qk ? ex.Q_nla : Q;
+    const void* Ks = own_qk ? ex.K_nla : K;
+    float* dQs = own_qk ? ex.dQ_nla : dQ;
+    float* dKs = own_qk ? ex.dK_nla : dK;
+    const size_t n_qk = (size_t)pl.BH * pl.L * pl.d;
     ProfChain prof_chain;   // the kernels below follow each other on one stream
     const bool mfma_stats = pl.dtype == NATS_BF16;   // the softmax branch's forward on the matrix cores
     void* VhT = mfma_stats ? ws + bp.off_vht : nullptr;
     {   // what the softmax branch's backward needs from its forward: the compacted cache, lse, the branch output
         ProfScope ps("scan_compact", stream);
-        st = launch_scan_compact(pl, mask, K, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, VhT, stream);
+        st = launch_scan_compact(pl, mask, Ks, V, cnt, idx, n_s, Kc, Vc, nullptr, nullptr, 0, VhT, stream);
         if (st != NATS_OK) return st;
     }
     if (mfma_stats) {
         ProfScope ps("flash_softmax", stream);
-        st = launch_flash_softmax(pl, Q, Kc, VhT, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
+        st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;
     } else {
         ProfScope ps("softmax_fp32", stream);
-        st = launch_softmax_fp32(pl, Q, Kc, Vc, K, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
+        st = launch_softmax_fp32(pl, Qs, Kc, Vc, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;
     }
     const int32_t* vis = cnt;   // compacted rows visible to a query
@@ -545,7 +559,13 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     }
     {   // dQ = the softmax branch's share over the compacted rows (written); also D_i
         ProfScope ps("softmax_bwd_dq", stream);
-        st = launch_softmax_bwd_dq(pl, Q, Kc, Vc, dO, vis, O_nla, lse, Dvec, dQ, stream);
+        st = launch_softmax_bwd_dq(pl, Qs, Kc, Vc, dO, vis, O_nla, lse, Dvec, dQs, stream);
+        if (st != NATS_OK) return st;
+    }
+    if (own_qk) {   // the linear branch adds onto dQ, the softmax branch's key gradients scatter into dKs
+        ProfScope ps("zero_fill", stream);
+        st = launch_zero_f32(dQ, n_qk, stream);
+        if (st == NATS_OK) st = launch_zero_f32(dKs, n_qk, stream);
         if (st != NATS_OK) return st;
     }
     float* ops = reinterpret_cast<float*>(ws + bp.off_ops);
@@ -592,12 +612,12 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     }
     if (chunk) {   // every chunk's inner part of the softmax branch: added to dQ, dK, dV
         ProfScope ps("softmax_bwd_own_chunk", stream);
-        st = launch_softmax_bwd_own_chunk(pl, Q, K, V, dO, lse, Dvec, dQ, dK, dV, stream);
+        st = launch_softmax_bwd_own_chunk(pl, Qs, Ks, V, dO, lse, Dvec, dQs, dKs, dV, stream);
         if (st != NATS_OK) return st;
     }
     {   // rows of the softmax tokens in dK, dV (routing per token: their linear share is zero; per chunk: added) and g_nla
         ProfScope ps("softmax_bwd_dkv", stream);
-        st = launch_softmax_bwd_dkv(pl, Q, Kc, Vc, dO, vis, idx, n_s, lse, Dvec, dK, dV, ex.g_nla,
+        st = launch_softmax_bwd_dkv(pl, Qs, Kc, Vc, dO, vis, idx, n_s, lse, Dvec, dKs, dV, ex.g_nla,
                                     reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
                                     reinterpret_cast<float*>(ws + bp.off_sgp), stream);
         if (st != NATS_OK) return st;
@@ -631,8 +651,14 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
     nats_bwd_extra ex;
     memset(&ex, 0, sizeof(ex));
     if (extra) ex = *extra;
+    if ((ex.Q_nla == nullptr) != (ex.K_nla == nullptr)) { set_error("Q_nla and K_nla: both or neither"); return NATS_ERR_NULL; }
+    if (ex.Q_nla != nullptr && (ex.dQ_nla == nullptr || ex.dK_nla == nullptr)) {
+        set_error("with Q_nla and K_nla the gradients dQ_nla and dK_nla must be given");
+        return NATS_ERR_NULL;
+    }
     const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
-                          ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la};
+                          ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, ex.Q_nla, ex.K_nla,
+                          ex.dQ_nla, ex.dK_nla};
     for (const void* ptr : ptrs)
         if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
     const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
@@ -672,6 +698,18 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
             e1.initial_state = S0g;
         }
         if (ex.d_initial_state) e1.d_initial_state = dS0g;
+        if (ex.Q_nla) {   // the member's own queries and keys of the softmax branch; its gradients go straight back
+            st = launch_copy_rows(static_cast<const char*>(ex.Q_nla) + g * row * esz, G * row * esz, ws + bp.off_gqn, row * esz,
+                                  row * esz, pl.BH, stream);
+            if (st == NATS_OK)
+                st = launch_copy_rows(static_cast<const char*>(ex.K_nla) + g * row * esz, G * row * esz, ws + bp.off_gkn,
+                                      row * esz, row * esz, pl.BH, stream);
+            if (st != NATS_OK) return st;
+            e1.Q_nla = ws + bp.off_gqn;
+            e1.K_nla = ws + bp.off_gkn;
+            e1.dQ_nla = reinterpret_cast<float*>(ws + bp.off_gdqn);
+            e1.dK_nla = reinterpret_cast<float*>(ws + bp.off_gdkn);
+        }
         // the first member writes the sums' buffers themselves, the others a buffer of their own that is then added
         if (ex.g_nla) e1.g_nla = first ? ex.g_nla : reinterpret_cast<float*>(ws + bp.off_ggn);
         if (ex.g_la) e1.g_la = first ? ex.g_la : reinterpret_cast<float*>(ws + bp.off_ggl);
@@ -687,6 +725,11 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         if (st != NATS_OK) return st;
         if (ex.d_initial_state) {
             st = launch_copy_rows(dS0g, srow * 4, ex.d_initial_state + g * srow, G * srow * 4, srow * 4, pl.BH, stream);
+            if (st != NATS_OK) return st;
+        }
+        if (ex.Q_nla) {
+            st = launch_copy_rows(e1.dQ_nla, row * 4, ex.dQ_nla + g * row, G * row * 4, row * 4, pl.BH, stream);
+            if (st == NATS_OK) st = launch_copy_rows(e1.dK_nla, row * 4, ex.dK_nla + g * row, G * row * 4, row * 4, pl.BH, stream);
             if (st != NATS_OK) return st;
         }
         if (first) continue;

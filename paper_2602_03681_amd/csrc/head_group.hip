@@ -2,7 +2,8 @@
 // and mask of one linear head, so the gradient of a shared input is the sum of what each of the G heads sends back.
 // The backward pass runs once per member of the groups on that member's heads, gathered into contiguous tensors;
 // the two kernels here move a member's rows in and out of the [B, H G, ...] tensors and add a member's share onto
-// the sums.  Both only stream memory.
+// the sums.  Both only stream memory.  (Also here: the zero fill the pass needs when the softmax branch has queries
+// and keys of its own, whose gradients are then tensors of their own.)
 #include "nats_common.h"
 
 namespace nats {
@@ -41,6 +42,11 @@ __global__ __launch_bounds__(HG_THREADS) void add_f32_scalar_kernel(float* __res
         dst[e] += src[e];
 }
 
+// dst[i] = 0 (a kernel, not a memset: the call may be part of a captured graph)
+__global__ __launch_bounds__(HG_THREADS) void zero_f32_kernel(float* __restrict__ dst, size_t n) {
+    for (size_t e = (size_t)blockIdx.x * HG_THREADS + threadIdx.x; e < n; e += (size_t)gridDim.x * HG_THREADS) dst[e] = 0.f;
+}
+
 static int hg_grid(size_t n) {
     const size_t blocks = (n + HG_THREADS - 1) / HG_THREADS;
     return (int)(blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks));
@@ -68,6 +74,12 @@ nats_status launch_add_f32(float* dst, const float* src, size_t n, hipStream_t s
     else
         hipLaunchKernelGGL(add_f32_scalar_kernel, dim3(hg_grid(n)), dim3(HG_THREADS), 0, st, dst, src, n);
     return check_launch("add_f32");
+}
+
+nats_status launch_zero_f32(float* dst, size_t n, hipStream_t st) {
+    if (n == 0) return NATS_OK;
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(hg_grid(n)), dim3(HG_THREADS), 0, st, dst, n);
+    return check_launch("zero_f32");
 }
 
 }  // namespace nats

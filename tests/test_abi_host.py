@@ -37,10 +37,10 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 111   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    assert lib.nats_abi_version() == 112   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
     # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group, decode workspace;
     # 110: p->math selects the form of the backward's linear adjoint, C = 128 with routing per chunk; 111: the backward
-    # pass takes p->group
+    # pass takes p->group; 112: nats_bwd_extra gained Q_nla, K_nla, dQ_nla, dK_nla
 
 
 def good_params(**over):

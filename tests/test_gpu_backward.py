@@ -268,3 +268,36 @@ def test_head_grouping_of_one_is_the_plain_backward():
     r2 = run_bwd(x, dO, "bf16", group=1)
     for k in ("dQ", "dK", "dV", "dalpha", "dbeta"):
         assert torch.equal(r1[k], r2[k]), k
+
+
+# ---- softmax heads with queries and keys of their own (Section 4.3: shared projections, different normalisation) ------
+@pytest.mark.parametrize("dtype,B,H,G,L,d", [("f32", 1, 2, 1, 320, 64), ("bf16", 1, 2, 1, 448, 128),
+                                             ("bf16", 1, 2, 2, 512, 64), ("f32", 1, 1, 3, 256, 128)])
+@pytest.mark.parametrize("routing", ["token", "chunk"])
+@pytest.mark.parametrize("math", [nb.NATS_MATH_AUTO, nb.NATS_MATH_FP32], ids=["by_chunks", "by_tokens"])
+def test_backward_with_own_softmax_queries_and_keys(dtype, B, H, G, L, d, routing, math):
+    """dQ_nla, dK_nla [B,H G,L,d] are the softmax branch's gradients; dQ, dK then hold the linear branch's alone."""
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=960 + L + G)
+    xs = make_fwd_inputs(B, H * G, L, d, dtype, 0.15, seed=961 + L + G)
+    x["V"] = xs["V"]
+    Qn, Kn = xs["Q"], xs["K"]
+    dO = make_grad_output(B, H * G, L, d, dtype, seed=962 + L)
+    S0 = (0.05 * np.random.default_rng(L + G).standard_normal((B, H * G, d, d))).astype(np.float32)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    kw = dict(S0=S0, group=G, math=math, Q_nla=torch.from_numpy(Qn).to(tdt).cuda(),
+              K_nla=torch.from_numpy(Kn).to(tdt).cuda())
+    own = (("dQ_nla", "dQ_nla"), ("dK_nla", "dK_nla"))
+    if routing == "chunk":
+        x["mask"] = make_chunk_mask(B, H, L // 64, 0.35, 963 + L, "bernoulli")
+        r = run_bwd(x, dO, dtype, routing=nb.NATS_ROUTE_CHUNK, want=("d_initial_state", "dscore_nla", "dscore_la"), **kw)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=64, S0=S0,
+                                     Q_nla=Qn, K_nla=Kn)
+        extra = CHUNK_KEYS + own
+    else:
+        r = run_bwd(x, dO, dtype, want=("d_initial_state", "g_nla", "g_la"), **kw)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, S0=S0,
+                                     Q_nla=Qn, K_nla=Kn)
+        extra = (("d_initial_state", "dS0"), ("g_nla", "g_nla"), ("g_la", "g_la")) + own
+    assert tuple(r["dQ_nla"].shape) == (B, H * G, L, d) and tuple(r["dQ"].shape) == (B, H, L, d)
+    errs = check(r, ref, extra=extra)
+    print(dtype, G, routing, errs)
