@@ -18,6 +18,10 @@ Given dO = dLoss/dO for the plain-sum merge O = O_la + O_nla (Section 4.1), per 
     inactive for an operation gets no score gradient for it (Section 4.2, last paragraph).
   * routing per chunk (hybrid_head_chunk_routed_bwd): the adjoint of nats_oracle.hybrid_head_chunk_routed, in
     which both operations compute every chunk's inner part and the masks act between chunks.
+  * the normalised, weighted merges (Eq. 21 and its single-normalisation ablation; combine_bwd): the merge acts on
+    the two branches' output rows, so its adjoint turns dO into one gradient per branch (and the gradients of the
+    two weights), and each branch's adjoint then runs on its own; the branch outputs it needs are taken from the
+    forward oracle.
 
 Parity pins: tests/test_oracle_bwd_pins.py checks every output against automatic differentiation of an
 independently written forward (plain PyTorch fp64 on the CPU), the column sums against the derivative with
@@ -27,6 +31,36 @@ entries against central finite differences of the forward oracle.
 from __future__ import annotations
 
 import numpy as np
+
+from . import nats_oracle as _fwd   # the forward oracle's branch outputs, needed by the adjoint of the merge
+
+
+def combine_bwd(o_la, o_nla, do, mode, w_nla=None, w_la=None, eps=1e-6):
+    """Adjoint of nats_oracle.combine for rows o_la, o_nla, do [L,d] and weights [L] (None: the forward's defaults).
+    mode 0: the plain sum; 1: Eq. 21, O = w_nla RMSNorm(o_nla) + w_la RMSNorm(o_la); 2: RMSNorm(w_nla o_nla + w_la o_la).
+    RMSNorm(x) = x / sqrt(mean(x^2) + eps) without a gain, so for y = x r, r = (mean(x^2) + eps)^(-1/2):
+        dx = r (dy - y (y . dy) / d).
+    Returns (do_la, do_nla, dw_nla, dw_la); the weight gradients are zero arrays for mode 0."""
+    o_la, o_nla, do = (np.asarray(a, dtype=np.float64) for a in (o_la, o_nla, do))
+    L, d = o_la.shape
+    if mode == 0:
+        return do, do, np.zeros(L), np.zeros(L)
+    default = 1.0 if mode == 2 else 0.5
+    wn = np.full(L, default) if w_nla is None else np.asarray(w_nla, dtype=np.float64)
+    wl = np.full(L, default) if w_la is None else np.asarray(w_la, dtype=np.float64)
+
+    def norm_bwd(x, dy):                       # rows: y = x r;  returns (y, dx)
+        r = 1.0 / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + eps)
+        y = x * r
+        return y, r * (dy - y * np.sum(y * dy, axis=1, keepdims=True) / d)
+
+    if mode == 2:
+        z = wn[:, None] * o_nla + wl[:, None] * o_la
+        _, dz = norm_bwd(z, do)
+        return wl[:, None] * dz, wn[:, None] * dz, np.sum(dz * o_nla, axis=1), np.sum(dz * o_la, axis=1)
+    y_n, dx_n = norm_bwd(o_nla, wn[:, None] * do)
+    y_l, dx_l = norm_bwd(o_la, wl[:, None] * do)
+    return dx_l, dx_n, np.sum(do * y_n, axis=1), np.sum(do * y_l, axis=1)
 
 
 def gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0=None, la_scale=1.0, linear_op=0, decay_on_softmax=True):
@@ -113,20 +147,30 @@ def softmax_branch_bwd(q, k, v, mask, scale, do):
 
 
 def hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-                    decay_on_softmax=True, q_nla=None, k_nla=None):
-    """Backward of nats_oracle.hybrid_head with the plain-sum merge: dO goes to both branches as it is.
+                    decay_on_softmax=True, q_nla=None, k_nla=None, mode=0, w_nla=None, w_la=None, eps=1e-6):
+    """Backward of nats_oracle.hybrid_head.  With the plain-sum merge (mode 0) dO goes to both branches as it is; with
+    the merges of Eq. 21 (mode 1) and its ablation (mode 2) each branch receives the merge's gradient for its own
+    output rows (combine_bwd), and dw_nla, dw_la [L] are returned as well.
     q_nla, k_nla (both or neither; Section 4.3: the two operations normalise the shared projections differently): the
     softmax branch's own queries and keys.  Their gradients are then returned apart as dQ_nla, dK_nla, and dQ, dK are
     the linear branch's alone; V is shared, dV stays the sum."""
     d_k = np.asarray(q).shape[-1]
     scale = (1.0 / np.sqrt(d_k)) if softmax_scale is None else softmax_scale
-    la = gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do, S0, la_scale, linear_op, decay_on_softmax)
+    do_la = do_nla = do
+    merged = {}
+    if mode != 0:
+        fw = _fwd.hybrid_head(q, k, v, alpha, beta, mask, softmax_scale, la_scale, 0, S0=S0, linear_op=linear_op,
+                              decay_on_softmax=decay_on_softmax, q_nla=q_nla, k_nla=k_nla)
+        do_la, do_nla, dwn, dwl = combine_bwd(fw["O_la"], fw["O_nla"], do, mode, w_nla, w_la, eps)
+        merged = {"dw_nla": dwn, "dw_la": dwl}
+    la = gdn_recurrent_bwd(q, k, v, alpha, beta, mask, do_la, S0, la_scale, linear_op, decay_on_softmax)
     out = {"dV": None, "dalpha": la["dalpha"], "dbeta": la["dbeta"], "dS0": la["dS0"], "g_la": la["g_la"]}
+    out.update(merged)
     if q_nla is None:
-        nla = softmax_branch_bwd(q, k, v, mask, scale, do)
+        nla = softmax_branch_bwd(q, k, v, mask, scale, do_nla)
         out.update(dQ=la["dq"] + nla["dq"], dK=la["dk"] + nla["dk"])
     else:
-        nla = softmax_branch_bwd(q_nla, k_nla, v, mask, scale, do)
+        nla = softmax_branch_bwd(q_nla, k_nla, v, mask, scale, do_nla)
         out.update(dQ=la["dq"], dK=la["dk"], dQ_nla=nla["dq"], dK_nla=nla["dk"])
     out["dV"] = la["dv"] + nla["dv"]
     out["g_nla"] = nla["g"]
@@ -134,21 +178,24 @@ def hybrid_head_bwd(q, k, v, alpha, beta, mask, do, softmax_scale=None, la_scale
 
 
 def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-               decay_on_softmax=True, Q_nla=None, K_nla=None):
+               decay_on_softmax=True, Q_nla=None, K_nla=None, mode=0, w_nla=None, w_la=None, eps=1e-6):
     """All (b,h) of [B,H,L,d] inputs; returns a dict of stacked fp64 arrays (with Q_nla, K_nla [B,H,L,d] also
-    dQ_nla, dK_nla)."""
+    dQ_nla, dK_nla; with mode 1 or 2 and weights [B,H,L] or None also dw_nla, dw_la [B,H,L])."""
     B, H, L, d = np.asarray(Q).shape
     out = {"dQ": np.zeros((B, H, L, d)), "dK": np.zeros((B, H, L, d)), "dV": np.zeros((B, H, L, d)),
            "dalpha": np.zeros((B, H, L)), "dbeta": np.zeros((B, H, L)), "dS0": np.zeros((B, H, d, d)),
            "g_nla": np.zeros((B, H, L)), "g_la": np.zeros((B, H, L))}
     if Q_nla is not None:
         out.update(dQ_nla=np.zeros((B, H, L, d)), dK_nla=np.zeros((B, H, L, d)))
+    if mode != 0:
+        out.update(dw_nla=np.zeros((B, H, L)), dw_la=np.zeros((B, H, L)))
     for b in range(B):
         for h in range(H):
             r = hybrid_head_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask[b, h], dO[b, h],
                                 softmax_scale, la_scale, None if S0 is None else S0[b, h], linear_op,
                                 decay_on_softmax, None if Q_nla is None else Q_nla[b, h],
-                                None if K_nla is None else K_nla[b, h])
+                                None if K_nla is None else K_nla[b, h], mode,
+                                None if w_nla is None else w_nla[b, h], None if w_la is None else w_la[b, h], eps)
             for key in out:
                 out[key][b, h] = r[key]
     return out
@@ -158,7 +205,8 @@ def hybrid_bwd(Q, K, V, alpha, beta, mask, dO, softmax_scale=None, la_scale=1.0,
 # routing per chunk (Section 4.1 as stated; Section 4.2 for the score gradients)
 # --------------------------------------------------------------------------- #
 def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_scale=None, la_scale=1.0, S0=None,
-                                 linear_op=0, decay_on_softmax=True, q_nla=None, k_nla=None):
+                                 linear_op=0, decay_on_softmax=True, q_nla=None, k_nla=None, mode=0, w_nla=None,
+                                 w_la=None, eps=1e-6):
     """Adjoint of nats_oracle.hybrid_head_chunk_routed (plain-sum merge).
 
     Forward being differentiated, per chunk c with carried state S_c: inside the chunk Eq. 19 runs on every token
@@ -171,8 +219,18 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
     inactive for the operation.
     q_nla, k_nla (both or neither): the softmax branch's own queries and keys; their gradients come back apart as
     dQ_nla, dK_nla and dQ, dK are the linear branch's alone.
+    mode 1, 2 (the merges of Eq. 21 and its ablation, weights w_nla, w_la [L] or None): each branch runs on the
+    merge's gradient for its own rows (combine_bwd); dw_nla, dw_la [L] are returned as well.
     Returns dict(dQ, dK, dV [L,d], dalpha, dbeta [L], dS0, dscore_nla, dscore_la [L/C])."""
     q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
+    do_la = do_nla = do
+    merged = {}
+    if mode != 0:
+        fw = _fwd.hybrid_head_chunk_routed(q, k, v, alpha, beta, mask_c, C, softmax_scale, la_scale, 0, S0=S0,
+                                           linear_op=linear_op, decay_on_softmax=decay_on_softmax, q_nla=q_nla,
+                                           k_nla=k_nla)
+        do_la, do_nla, dwn, dwl = combine_bwd(fw["O_la"], fw["O_nla"], do, mode, w_nla, w_la, eps)
+        merged = {"dw_nla": dwn, "dw_la": dwl}
     own_qk = q_nla is not None
     qn = np.asarray(q_nla, dtype=np.float64) if own_qk else q
     kn = np.asarray(k_nla, dtype=np.float64) if own_qk else k
@@ -198,10 +256,10 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
             p = np.exp(s - s.max())
             p /= p.sum()
             o = p @ v[J]
-            dm = p * (v[J] @ do[i] - do[i] @ o)           # Eq. 15 (also dLoss/ds_ij)
+            dm = p * (v[J] @ do_nla[i] - do_nla[i] @ o)   # Eq. 15 (also dLoss/ds_ij)
             for jj, j in enumerate(J[:len(earlier)]):      # only these columns stand behind the mask
                 ds_nla[j // C] += dm[jj]
-            dv[J] += np.outer(p, do[i])
+            dv[J] += np.outer(p, do_nla[i])
             dqn[i] += scale * (dm @ kn[J])
             dkn[J] += scale * np.outer(dm, qn[i])
         if mask_c[c]:
@@ -233,8 +291,8 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
             dS = dS_next
             ds_la[c] = np.sum(dS_next * (S_new[last] - decay[c] * S_start[c]))
         for t in range(last, c * C - 1, -1):
-            dq[t] += la_scale * (S_new[t].T @ do[t])
-            dS = dS + la_scale * np.outer(do[t], q[t])
+            dq[t] += la_scale * (S_new[t].T @ do_la[t])
+            dS = dS + la_scale * np.outer(do_la[t], q[t])
             r = resid[t]
             dSk = dS @ k[t]
             dbeta[t] += r @ dSk
@@ -259,11 +317,12 @@ def hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, softmax_sc
            "dscore_nla": ds_nla, "dscore_la": ds_la}
     if own_qk:
         out.update(dQ_nla=dqn, dK_nla=dkn)
+    out.update(merged)
     return out
 
 
 def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=None, la_scale=1.0, S0=None, linear_op=0,
-                            decay_on_softmax=True, Q_nla=None, K_nla=None):
+                            decay_on_softmax=True, Q_nla=None, K_nla=None, mode=0, w_nla=None, w_la=None, eps=1e-6):
     """All (b,h) of [B,H,L,d] inputs with mask_c [B,H,L/C]; returns a dict of stacked fp64 arrays (with Q_nla, K_nla
     [B,H,L,d] also dQ_nla, dK_nla)."""
     B, H, L, d = np.asarray(Q).shape
@@ -272,12 +331,16 @@ def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=N
            "dscore_nla": np.zeros((B, H, L // C)), "dscore_la": np.zeros((B, H, L // C))}
     if Q_nla is not None:
         out.update(dQ_nla=np.zeros((B, H, L, d)), dK_nla=np.zeros((B, H, L, d)))
+    if mode != 0:
+        out.update(dw_nla=np.zeros((B, H, L)), dw_la=np.zeros((B, H, L)))
     for b in range(B):
         for h in range(H):
             r = hybrid_head_chunk_routed_bwd(Q[b, h], K[b, h], V[b, h], alpha[b, h], beta[b, h], mask_c[b, h], C,
                                              dO[b, h], softmax_scale, la_scale, None if S0 is None else S0[b, h],
                                              linear_op, decay_on_softmax, None if Q_nla is None else Q_nla[b, h],
-                                             None if K_nla is None else K_nla[b, h])
+                                             None if K_nla is None else K_nla[b, h], mode,
+                                             None if w_nla is None else w_nla[b, h],
+                                             None if w_la is None else w_la[b, h], eps)
             for key in out:
                 out[key][b, h] = r[key]
     return out
@@ -287,8 +350,9 @@ def hybrid_bwd_chunk_routed(Q, K, V, alpha, beta, mask_c, C, dO, softmax_scale=N
 # head grouping (Section 4.3)
 # --------------------------------------------------------------------------- #
 def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=None, la_scale=1.0, S0=None,
-                       linear_op=0, decay_on_softmax=True, Q_nla=None, K_nla=None):
-    """Backward of nats_oracle.hybrid_fwd_grouped (plain-sum merge, the softmax heads of a group use the linear
+                       linear_op=0, decay_on_softmax=True, Q_nla=None, K_nla=None, mode=0, w_nla=None, w_la=None,
+                       eps=1e-6):
+    """Backward of nats_oracle.hybrid_fwd_grouped (the softmax heads of a group use the linear
     head's queries and keys).  Output head h G + g reads Q, K, alpha, beta, mask of linear head h and its own V
     (its block of the wide state's rows never mixes with the other blocks, and its softmax head attends with the
     same Q, K): it is a head of the ungrouped operator.  A shared input's gradient is therefore the sum over g of the
@@ -296,7 +360,9 @@ def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=
     Shapes: Q, K [B,H,L,d]; alpha, beta [B,H,L]; mask [B,H,L] (or [B,H,L/C] with C given: routing per chunk);
     V, dO [B,H G,L,d]; S0 [B,H G,d,d].  Returns dQ, dK, dalpha, dbeta and the score gradients per linear head,
     dV [B,H G,L,d], dS0 [B,H G,d,d].  Q_nla, K_nla [B,H G,L,d]: the softmax heads' own queries and keys; their
-    gradients dQ_nla, dK_nla [B,H G,L,d] are each member's own, and dQ, dK are the linear branch's, summed over g."""
+    gradients dQ_nla, dK_nla [B,H G,L,d] are each member's own, and dQ, dK are the linear branch's, summed over g.
+    mode 1, 2: the merges of Eq. 21 and its ablation per output head, weights w_nla, w_la [B,H G,L] (or None); their
+    gradients dw_nla, dw_la [B,H G,L] are each member's own."""
     Q, K, V, dO = (np.asarray(a, dtype=np.float64) for a in (Q, K, V, dO))
     B, H, L, d = Q.shape
     assert V.shape == (B, H * G, L, d) and dO.shape == V.shape
@@ -307,17 +373,22 @@ def hybrid_bwd_grouped(Q, K, V, alpha, beta, mask, dO, G, C=None, softmax_scale=
     if Q_nla is not None:
         Q_nla, K_nla = np.asarray(Q_nla, dtype=np.float64), np.asarray(K_nla, dtype=np.float64)
         own = {"dQ_nla": np.zeros_like(V), "dK_nla": np.zeros_like(V)}
+    if mode != 0:
+        own.update(dw_nla=np.zeros((B, H * G, L)), dw_la=np.zeros((B, H * G, L)))
+    mw = dict(mode=mode, eps=eps)
     for g in range(G):
+        mw["w_nla"] = None if w_nla is None else np.asarray(w_nla, dtype=np.float64)[:, g::G]
+        mw["w_la"] = None if w_la is None else np.asarray(w_la, dtype=np.float64)[:, g::G]
         Vg, dOg = V[:, g::G], dO[:, g::G]                    # heads h G + g, h = 0 .. H - 1
         S0g = None if S0 is None else np.asarray(S0, dtype=np.float64)[:, g::G]
         Qn = None if Q_nla is None else Q_nla[:, g::G]
         Kn = None if K_nla is None else K_nla[:, g::G]
         if C is None:
             r = hybrid_bwd(Q, K, Vg, alpha, beta, mask, dOg, softmax_scale, la_scale, S0g, linear_op, decay_on_softmax,
-                           Qn, Kn)
+                           Qn, Kn, **mw)
         else:
             r = hybrid_bwd_chunk_routed(Q, K, Vg, alpha, beta, mask, C, dOg, softmax_scale, la_scale, S0g, linear_op,
-                                        decay_on_softmax, Qn, Kn)
+                                        decay_on_softmax, Qn, Kn, **mw)
         dV[:, g::G] = r.pop("dV")
         dS0[:, g::G] = r.pop("dS0")
         for key in own:

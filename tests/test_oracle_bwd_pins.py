@@ -251,3 +251,70 @@ def test_chunk_routed_backward_single_entries_against_finite_differences():
         dn[pos] -= h
         fd = (loss(**{name: up}) - loss(**{name: dn})) / (2 * h)
         assert abs(fd - r[key][pos]) <= 1e-6 * max(1.0, abs(fd)), (name, pos, fd, r[key][pos])
+
+
+# --------------------------------------------------------------------------- #
+# the normalised, weighted merges (Eq. 21; Section 5, ablation (iii))
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("with_weights", [True, False])
+def test_merge_adjoint_against_autograd_of_a_library_rms_norm(mode, with_weights):
+    rng = np.random.default_rng(31 + mode)
+    L, d, eps = 9, 6, 1e-6
+    o_la, o_nla, do = (rng.standard_normal((L, d)) for _ in range(3))
+    o_nla[2] = 0.0                                     # a query that sees no softmax token
+    wn, wl = (rng.random(L) + 0.1, rng.random(L) + 0.1) if with_weights else (None, None)
+    default = 1.0 if mode == 2 else 0.5
+    t_la, t_nla = (torch.tensor(a, requires_grad=True) for a in (o_la, o_nla))
+    t_wn = torch.tensor(wn if with_weights else np.full(L, default), requires_grad=True)
+    t_wl = torch.tensor(wl if with_weights else np.full(L, default), requires_grad=True)
+    norm = lambda x: torch.nn.functional.rms_norm(x, (d,), eps=eps)
+    if mode == 1:
+        o = t_wn[:, None] * norm(t_nla) + t_wl[:, None] * norm(t_la)
+    else:
+        o = norm(t_wn[:, None] * t_nla + t_wl[:, None] * t_la)
+    np.testing.assert_allclose(o.detach().numpy(), npo.combine(o_la, o_nla, mode, wn, wl, eps), rtol=1e-12, atol=1e-13)
+    (o * torch.tensor(do)).sum().backward()
+    do_la, do_nla, dwn, dwl = nbw.combine_bwd(o_la, o_nla, do, mode, wn, wl, eps)
+    for got, want in ((do_la, t_la.grad), (do_nla, t_nla.grad), (dwn, t_wn.grad), (dwl, t_wl.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-9, atol=1e-9 * float(want.abs().max()))
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("routing_chunk", [False, True])
+def test_backward_through_the_merges_against_finite_differences(mode, routing_chunk):
+    """Every gradient (the two weights' included) against central differences of sum(dO . O) of the forward oracle
+    run with the same merge; softmax heads with queries and keys of their own in one of the cases."""
+    L, d, C = 16, 4, 4
+    q, k, v, alpha, beta, mask, do, S0 = inputs(L=L, d=d, seed=50 + mode)
+    rng = np.random.default_rng(60 + mode)
+    x = dict(q=q, k=k, v=v, alpha=alpha, beta=beta, w_nla=rng.random(L) + 0.2, w_la=rng.random(L) + 0.2)
+    own = mode == 2
+    if own:
+        x["q_nla"], x["k_nla"] = rng.standard_normal((L, d)), rng.standard_normal((L, d))
+    mask_c = np.array([1, 0, 1, 0], dtype=np.uint8)
+
+    def forward(a):
+        kw = dict(mode=mode, w_nla=a["w_nla"], w_la=a["w_la"], S0=S0, la_scale=1.3, q_nla=a.get("q_nla"),
+                  k_nla=a.get("k_nla"))
+        if routing_chunk:
+            return npo.hybrid_head_chunk_routed(a["q"], a["k"], a["v"], a["alpha"], a["beta"], mask_c, C, **kw)["O"]
+        return npo.hybrid_head(a["q"], a["k"], a["v"], a["alpha"], a["beta"], mask, **kw)["O"]
+
+    kw = dict(S0=S0, la_scale=1.3, q_nla=x.get("q_nla"), k_nla=x.get("k_nla"), mode=mode, w_nla=x["w_nla"],
+              w_la=x["w_la"])
+    if routing_chunk:
+        r = nbw.hybrid_head_chunk_routed_bwd(q, k, v, alpha, beta, mask_c, C, do, **kw)
+    else:
+        r = nbw.hybrid_head_bwd(q, k, v, alpha, beta, mask, do, **kw)
+    names = [("q", "dQ"), ("k", "dK"), ("v", "dV"), ("alpha", "dalpha"), ("beta", "dbeta"), ("w_nla", "dw_nla"),
+             ("w_la", "dw_la")] + ([("q_nla", "dQ_nla"), ("k_nla", "dK_nla")] if own else [])
+    h = 1e-6
+    for name, key in names:
+        for _ in range(4):
+            pos = tuple(int(rng.integers(0, n)) for n in x[name].shape)
+            up, dn = {**x, name: x[name].copy()}, {**x, name: x[name].copy()}
+            up[name][pos] += h
+            dn[name][pos] -= h
+            fd = float(np.sum((forward(up) - forward(dn)) * do)) / (2 * h)
+            assert abs(fd - r[key][pos]) <= 3e-6 * max(1.0, abs(fd)), (name, pos, fd, r[key][pos])

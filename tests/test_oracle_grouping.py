@@ -182,3 +182,40 @@ def test_backward_with_own_softmax_queries_and_keys_against_finite_differences(G
                                      Q_nla=x["Q"], K_nla=x["K"])
         np.testing.assert_allclose(same["dQ"] + same["dQ_nla"], both["dQ"], rtol=1e-12, atol=1e-13)
         np.testing.assert_allclose(same["dK"] + same["dK_nla"], both["dK"], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("G,mode,routing_chunk", [(2, 1, False), (3, 2, True)])
+def test_grouped_backward_through_the_merges_against_finite_differences(G, mode, routing_chunk):
+    """Eq. 21 (and its ablation) per output head, weights [B,H G,L]: gradients against central differences of the
+    grouped forward oracle run with the same merge."""
+    from oracle import nats_oracle_bwd as ob
+    B, H, L, d, C = 1, 2, 16, 4, 4
+    x = grouped_inputs(B, H, G, L, d, 0.3, seed=70 + G, own_qk=False)
+    x = {k: np.asarray(v, dtype=np.float64) for k, v in x.items() if v is not None}
+    x["mask"] = x["mask"].astype(np.uint8)
+    Cc = None
+    if routing_chunk:
+        Cc = C
+        x["mask"] = make_chunk_mask(B, H, L // C, 0.4, 79)
+        x["mask"][:, :, 0] = 1
+    rng = np.random.default_rng(8)
+    x["w_nla"], x["w_la"] = rng.random((B, H * G, L)) + 0.2, rng.random((B, H * G, L)) + 0.2
+    dO = rng.standard_normal((B, H * G, L, d))
+
+    def loss(a):
+        r = npo.hybrid_fwd_grouped(a["Q"], a["K"], a["V"], a["alpha"], a["beta"], a["mask"], G, C=Cc, mode=mode,
+                                   w_nla=a["w_nla"], w_la=a["w_la"])
+        return float((r["O"] * dO).sum())
+
+    got = ob.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=Cc, mode=mode,
+                                w_nla=x["w_nla"], w_la=x["w_la"])
+    eps = 1e-6
+    for key, name in (("Q", "dQ"), ("K", "dK"), ("V", "dV"), ("alpha", "dalpha"), ("beta", "dbeta"),
+                      ("w_nla", "dw_nla"), ("w_la", "dw_la")):
+        for _ in range(4):
+            pos = tuple(int(rng.integers(0, n)) for n in x[key].shape)
+            xp, xm = {**x, key: x[key].copy()}, {**x, key: x[key].copy()}
+            xp[key][pos] += eps
+            xm[key][pos] -= eps
+            fd = (loss(xp) - loss(xm)) / (2 * eps)
+            assert abs(fd - got[name][pos]) <= 3e-6 * max(1.0, abs(fd)), (key, pos, fd, got[name][pos])
