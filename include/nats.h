@@ -210,7 +210,7 @@ nats_status nats_hybrid_attn_fwd_noalloc(const nats_fwd_params* p, const void* Q
                                          void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
- * Backward pass (Section 4.2), plain-sum merge, fp32 results
+ * Backward pass (Section 4.2), any of the three merges, fp32 results
  * ------------------------------------------------------------------------- */
 typedef struct nats_bwd_extra {
     const float* initial_state; /* in  [B,H,d,d] f32, the state the forward started from (NULL -> 0)         */
@@ -233,15 +233,25 @@ typedef struct nats_bwd_extra {
     const void* K_nla;          /*     (as nats_fwd_extra.Q_nla, K_nla; both or neither, NULL = the branch uses Q, K) */
     float* dQ_nla;              /* out [B,H*G,L,d] f32: their gradients (required with Q_nla, K_nla).  dQ and dK are     */
     float* dK_nla;              /*     then the linear branch's gradients alone                                        */
+    const float* w_nla;         /* in  [B,H*G,L] f32: the weights of the merge, p->combine_mode 1 (Eq. 21) and 2 (its      */
+    const float* w_la;          /*     ablation with one normalisation); NULL: 0.5 (mode 1) or 1 (mode 2) as in the forward */
+    float* dw_nla;              /* out [B,H*G,L] f32: their gradients (each optional); the caller takes them through        */
+    float* dw_la;               /*     Eq. 22 (or whatever made the weights).  All four must be NULL with combine_mode 0    */
 } nats_bwd_extra;
 
 size_t nats_hybrid_attn_bwd_workspace_bytes(const nats_fwd_params* p);
 
-/* Gradients of nats_hybrid_attn_fwd's O = O_la + O_nla with respect to its inputs, given dO = dLoss/dO:
+/* Gradients of nats_hybrid_attn_fwd's O with respect to its inputs, given dO = dLoss/dO.  For O = O_la + O_nla:
  * the adjoint of the recurrence of Eq. 19 / 14 / 20 (or of the gated operation) for the linear branch, and the
  * attention backward over the softmax columns of Eq. 12 with the mask gradients of Eq. 15.  k and v of a
  * softmax token get nothing from the linear branch and vice versa (Section 4.2).
- *   Q, K, V, alpha, beta, mask : as in the forward (either routing; p->combine_mode must be 0).
+ *   p->combine_mode 1 (Eq. 21) and 2 (Section 5, the ablation with one normalisation): the merge acts on the two
+ *             branches' output rows, so its adjoint turns dO into one gradient per branch, and each branch then runs
+ *             as for the plain sum.  The pass recomputes both branches' rows in fp32 (the linear branch's token by
+ *             token), takes p->rms_eps and extra->w_nla, w_la, and returns extra->dw_nla, dw_la.  These per-branch
+ *             gradients are fp32, so bf16 tensors are widened first and the whole pass runs on fp32 tensors
+ *             (slower than combine_mode 0, and a workspace larger by the fp32 copies).
+ *   Q, K, V, alpha, beta, mask : as in the forward (either routing).
  *             With routing per chunk the function differentiated is the one the
  *             forward computes there: both operations compute every chunk's inner part, the masks act between
  *             chunks, a softmax chunk hands on (its decay) x (the state at its start).  Every sum is fp32 and the recurrence's adjoint is fp32 throughout.

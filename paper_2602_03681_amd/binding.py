@@ -52,7 +52,8 @@ class BwdExtra(ctypes.Structure):
     _fields_ = [("initial_state", ctypes.c_void_p), ("d_initial_state", ctypes.c_void_p), ("g_nla", ctypes.c_void_p),
                 ("g_la", ctypes.c_void_p), ("dscore_nla", ctypes.c_void_p), ("dscore_la", ctypes.c_void_p),
                 ("Q_nla", ctypes.c_void_p), ("K_nla", ctypes.c_void_p), ("dQ_nla", ctypes.c_void_p),
-                ("dK_nla", ctypes.c_void_p)]
+                ("dK_nla", ctypes.c_void_p), ("w_nla", ctypes.c_void_p), ("w_la", ctypes.c_void_p),
+                ("dw_nla", ctypes.c_void_p), ("dw_la", ctypes.c_void_p)]
 
 
 class DecChunkState(ctypes.Structure):
@@ -297,13 +298,15 @@ def hybrid_attn_fwd_noalloc(Q, K, V, alpha, beta, mask, out, C: int = 64, *, sof
 def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scale: float = 0.0, la_scale: float = 0.0,
                     linear_op: int = NATS_LINEAR_GDN, freeze_on_softmax: bool = False, initial_state=None,
                     want=(), workspace=None, routing: int = NATS_ROUTE_TOKEN,
-                    math: int = NATS_MATH_AUTO, group: int = 1, Q_nla=None, K_nla=None) -> Dict[str, torch.Tensor]:
+                    math: int = NATS_MATH_AUTO, group: int = 1, Q_nla=None, K_nla=None, combine_mode: int = 0,
+                    rms_eps: float = 0.0, w_nla=None, w_la=None) -> Dict[str, torch.Tensor]:
     """nats_hybrid_attn_bwd: gradients of O = O_la + O_nla given dO.  Returns dQ, dK, dV [B,H,L,d] f32, dalpha,
     dbeta [B,H,L] f32 and, if named in `want`, d_initial_state [B,H,d,d], g_nla, g_la [B,H,L] (routing per token),
     dscore_nla, dscore_la [B,H,L/C] (Eq. 16, Eq. 17).  math = NATS_MATH_FP32: the linear branch's adjoint token by
     token instead of by chunks.  group = G > 1 (head grouping): V, dO, dV [B,H*G,L,d], the states [B,H*G,d,d].
     Q_nla, K_nla [B,H*G,L,d] (both or neither): the softmax branch's own queries and keys; their gradients come back
-    as dQ_nla, dK_nla, and dQ, dK are then the linear branch's alone."""
+    as dQ_nla, dK_nla, and dQ, dK are then the linear branch's alone.  combine_mode 1, 2 (Eq. 21 and its ablation
+    with one normalisation) with the weights w_nla, w_la [B,H*G,L] f32 (or None): also returns dw_nla, dw_la."""
     lib = load_library()
     B, H, L, d = Q.shape
     dt = Q.dtype
@@ -320,10 +323,12 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
         raise ValueError("Q_nla and K_nla: both or neither")
     _require(Q_nla, "Q_nla", (B, H * G, L, d), dt)
     _require(K_nla, "K_nla", (B, H * G, L, d), dt)
+    _require(w_nla, "w_nla", (B, H * G, L), torch.float32)
+    _require(w_la, "w_la", (B, H * G, L), torch.float32)
     unknown = set(want) - {"d_initial_state", "g_nla", "g_la", "dscore_nla", "dscore_la"}
     if unknown:
         raise ValueError(f"unknown outputs {sorted(unknown)}")
-    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, 0, 0.0, math,
+    params = make_fwd_params(B, H, L, d, C, _dtype_code(Q), softmax_scale, la_scale, combine_mode, rms_eps, math,
                              routing, linear_op, freeze_on_softmax, group=G)
     need = int(lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(params)))
     if need == 0:   # let the library say what is wrong with the parameters
@@ -343,10 +348,15 @@ def hybrid_attn_bwd(Q, K, V, alpha, beta, mask, dO, C: int = 64, *, softmax_scal
     if Q_nla is not None:
         res["dQ_nla"] = torch.empty((B, H * G, L, d), dtype=torch.float32, device=dev)
         res["dK_nla"] = torch.empty((B, H * G, L, d), dtype=torch.float32, device=dev)
+    if combine_mode != 0:
+        res["dw_nla"] = torch.empty((B, H * G, L), dtype=torch.float32, device=dev)
+        res["dw_la"] = torch.empty((B, H * G, L), dtype=torch.float32, device=dev)
     g = lambda k: res[k].data_ptr() if k in res else None
     extra = BwdExtra(initial_state.data_ptr() if initial_state is not None else None, g("d_initial_state"), g("g_nla"),
                      g("g_la"), g("dscore_nla"), g("dscore_la"), Q_nla.data_ptr() if Q_nla is not None else None,
-                     K_nla.data_ptr() if K_nla is not None else None, g("dQ_nla"), g("dK_nla"))
+                     K_nla.data_ptr() if K_nla is not None else None, g("dQ_nla"), g("dK_nla"),
+                     w_nla.data_ptr() if w_nla is not None else None, w_la.data_ptr() if w_la is not None else None,
+                     g("dw_nla"), g("dw_la"))
     _check(lib.nats_hybrid_attn_bwd(ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha), _ptr(beta), _ptr(mask),
                                     _ptr(dO), _ptr(res["dQ"]), _ptr(res["dK"]), _ptr(res["dV"]), _ptr(res["dalpha"]),
                                     _ptr(res["dbeta"]), ctypes.byref(extra), _ptr(workspace), workspace.numel(),

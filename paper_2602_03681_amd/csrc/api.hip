@@ -195,6 +195,13 @@ struct BwdPlan {
     int G;
     size_t off_gv, off_gdo, off_gdv, off_gdq, off_gdk, off_gda, off_gdb, off_gs0, off_gds0, off_ggn, off_ggl, off_gsn,
         off_gsl, off_gqn, off_gkn, off_gdqn, off_gdkn, total_grouped;
+    // the merges of Eq. 21 and its ablation (merge_mode 1, 2; 0: the plain sum): the linear branch's output rows, the
+    // two branches' gradients of their rows, the snapshot rows of the token-by-token forward (routing per chunk), a
+    // member's weights and their gradients (head grouping), and fp32 copies of bf16 tensors (the pass then runs on fp32
+    // tensors: pl.dtype is NATS_F32 whatever src_dtype is)
+    int merge_mode, src_dtype;
+    size_t off_mola, off_mdol, off_mdon, off_msnap, off_mwn, off_mwl, off_mdwn, off_mdwl, off_cq, off_ck, off_cv, off_cdo,
+        off_cqn, off_ckn;
 };
 static void plan_bwd(const FwdPlan& pl, BwdPlan* bp) {
     const size_t n_tok = (size_t)pl.BH * pl.L, ns = (size_t)pl.d / BWD_SWEEP_ROWS;
@@ -257,6 +264,28 @@ static void plan_bwd_group(const FwdPlan& pl, int G, BwdPlan* bp) {
     bp->total_grouped = off;
 }
 
+// the buffers of the backward through Eq. 21's merge, behind everything else (pl: the fp32 plan of one member)
+static void plan_bwd_merge(const FwdPlan& pl, int G, BwdPlan* bp) {
+    const size_t n_tok = (size_t)pl.BH * pl.L, nd = n_tok * pl.d;
+    size_t off = bp->total_grouped;
+    bp->off_mola = off;  off = align_up(off + nd * 4, 256);
+    bp->off_mdol = off;  off = align_up(off + nd * 4, 256);
+    bp->off_mdon = off;  off = align_up(off + nd * 4, 256);
+    bp->off_msnap = off; off = align_up(off + (size_t)pl.BH * pl.d * pl.d * 4, 256);
+    bp->off_mwn = off;   off = align_up(off + n_tok * 4, 256);
+    bp->off_mwl = off;   off = align_up(off + n_tok * 4, 256);
+    bp->off_mdwn = off;  off = align_up(off + n_tok * 4, 256);
+    bp->off_mdwl = off;  off = align_up(off + n_tok * 4, 256);
+    const size_t cv = bp->src_dtype == NATS_BF16 ? 1 : 0;
+    bp->off_cq = off;    off = align_up(off + cv * nd * 4, 256);
+    bp->off_ck = off;    off = align_up(off + cv * nd * 4, 256);
+    bp->off_cv = off;    off = align_up(off + cv * nd * G * 4, 256);
+    bp->off_cdo = off;   off = align_up(off + cv * nd * G * 4, 256);
+    bp->off_cqn = off;   off = align_up(off + cv * nd * G * 4, 256);
+    bp->off_ckn = off;   off = align_up(off + cv * nd * G * 4, 256);
+    bp->total_grouped = off;
+}
+
 // pl: the plan of the pass itself.  With head grouping (p->group = G > 1) that is the plan of one member of the groups,
 // B x H heads with G = 1, and bp->G = G.
 static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, BwdPlan* bp) {
@@ -265,12 +294,18 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
     const int G = p->group > 1 ? p->group : 1;
     if (G > 8) { set_error("group must be at most 8 (got %d)", p->group); return NATS_ERR_SHAPE; }
     one.group = 1;
+    // Eq. 21's merge (and its ablation): each branch's backward runs as for the plain sum, on its own gradient of its
+    // output rows; these gradients are fp32, so the pass runs on fp32 tensors (bf16 ones are widened first)
+    bp->merge_mode = p->combine_mode;
+    bp->src_dtype = p->dtype;
+    if (p->combine_mode < 0 || p->combine_mode > 2) { set_error("combine_mode must be 0, 1 or 2 (got %d)", p->combine_mode); return NATS_ERR_SHAPE; }
+    if (p->combine_mode != 0) {
+        if (p->dtype != NATS_BF16 && p->dtype != NATS_F32) { set_error("dtype must be NATS_BF16 or NATS_F32"); return NATS_ERR_SHAPE; }
+        one.combine_mode = 0;
+        one.dtype = NATS_F32;
+    }
     nats_status st = validate_fwd_params(&one, pl);
     if (st != NATS_OK) return st;
-    if (pl->combine_mode != 0) {
-        set_error("the backward pass covers the plain-sum merge (combine_mode %d given)", pl->combine_mode);
-        return NATS_ERR_UNSUPPORTED;
-    }
     if (pl->inner_chunk != 0) { set_error("the backward pass covers inner_chunk 0 only (got %d)", pl->inner_chunk); return NATS_ERR_UNSUPPORTED; }
     if (pl->routing == NATS_ROUTE_CHUNK && pl->RC != 64) {
         set_error("the backward pass with routing per chunk covers chunks of 64 tokens (C=%d given)", pl->RC);
@@ -278,6 +313,7 @@ static nats_status validate_bwd_params(const nats_fwd_params* p, FwdPlan* pl, Bw
     }
     plan_bwd(*pl, bp);
     if (G > 1) plan_bwd_group(*pl, G, bp);
+    if (bp->merge_mode != 0) plan_bwd_merge(*pl, G, bp);
     return NATS_OK;
 }
 
@@ -316,7 +352,7 @@ extern "C" {
 
 const char* nats_last_error(void) { return g_err; }
 
-int nats_abi_version(void) { return 112; }
+int nats_abi_version(void) { return 113; }
 
 nats_status nats_profile_begin(int max_records) {
     if (max_records <= 0 || max_records > (1 << 20)) { set_error("max_records out of range"); return NATS_ERR_SHAPE; }
@@ -549,6 +585,27 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
         st = launch_softmax_fp32(pl, Qs, Kc, Vc, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;
     }
+    // The merges of Eq. 21 and its ablation: the linear branch's rows once more, token by token in fp32, then the merge's
+    // adjoint turns dO into one gradient per branch; from here on each branch runs as for the plain sum.
+    const void* dO_s = dO;   // gradient of the softmax branch's rows
+    const void* dO_l = dO;   // ... of the linear branch's
+    if (bp.merge_mode != 0) {
+        float* O_la = reinterpret_cast<float*>(ws + bp.off_mola);
+        {
+            ProfScope ps("gdn_recurrent", stream);
+            st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, nullptr, O_la,
+                                      chunk ? reinterpret_cast<float*>(ws + bp.off_msnap) : nullptr, stream);
+            if (st != NATS_OK) return st;
+        }
+        ProfScope ps("merge_bwd", stream);
+        float* dol = reinterpret_cast<float*>(ws + bp.off_mdol);
+        float* don = reinterpret_cast<float*>(ws + bp.off_mdon);
+        st = launch_merge_bwd(pl, bp.merge_mode, pl.rms_eps, O_la, O_nla, static_cast<const float*>(dO), ex.w_nla,
+                              ex.w_la, dol, don, ex.dw_nla, ex.dw_la, stream);
+        if (st != NATS_OK) return st;
+        dO_s = don;
+        dO_l = dol;
+    }
     const int32_t* vis = cnt;   // compacted rows visible to a query
     if (chunk) {
         ProfScope ps("visible_rows", stream);
@@ -559,7 +616,7 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     }
     {   // dQ = the softmax branch's share over the compacted rows (written); also D_i
         ProfScope ps("softmax_bwd_dq", stream);
-        st = launch_softmax_bwd_dq(pl, Qs, Kc, Vc, dO, vis, O_nla, lse, Dvec, dQs, stream);
+        st = launch_softmax_bwd_dq(pl, Qs, Kc, Vc, dO_s, vis, O_nla, lse, Dvec, dQs, stream);
         if (st != NATS_OK) return st;
     }
     if (own_qk) {   // the linear branch adds onto dQ, the softmax branch's key gradients scatter into dKs
@@ -590,18 +647,18 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     if (by_chunks) {
         {   // backwards along the sequence: the state gradient behind every chunk, dV, the partials of dbeta
             ProfScope ps("gdn_chunk_state_grads", stream);
-            st = launch_gdn_chunk_state_grads(pl, Q, K, dO, mask, ops, dck, Uh, dV, dbp, ex.d_initial_state, stream);
+            st = launch_gdn_chunk_state_grads(pl, Q, K, dO_l, mask, ops, dck, Uh, dV, dbp, ex.d_initial_state, stream);
             if (st != NATS_OK) return st;
         }
         // dQ += linear share; dK, dalpha, dbeta = linear share; g_nla cleared
         ProfScope ps("gdn_chunk_grads", stream);
-        st = launch_gdn_chunk_grads(pl, Q, K, dO, alpha, mask, ops, ckpt, dck, Ug, dV, dbp, dQ, dK, dalpha, dbeta, ex.g_nla,
+        st = launch_gdn_chunk_grads(pl, Q, K, dO_l, alpha, mask, ops, ckpt, dck, Ug, dV, dbp, dQ, dK, dalpha, dbeta, ex.g_nla,
                                     chunk ? ex.dscore_la : nullptr, stream);
         if (st != NATS_OK) return st;
     } else {
         {
             ProfScope ps("gdn_recurrent_bwd", stream);
-            st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
+            st = launch_gdn_recurrent_bwd(pl, Q, K, V, dO_l, alpha, beta, mask, ckpt, scratch, dqp, dkp, dap, dbp, dV,
                                           ex.d_initial_state, dslap, stream);
             if (st != NATS_OK) return st;
         }
@@ -612,12 +669,12 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
     }
     if (chunk) {   // every chunk's inner part of the softmax branch: added to dQ, dK, dV
         ProfScope ps("softmax_bwd_own_chunk", stream);
-        st = launch_softmax_bwd_own_chunk(pl, Qs, Ks, V, dO, lse, Dvec, dQs, dKs, dV, stream);
+        st = launch_softmax_bwd_own_chunk(pl, Qs, Ks, V, dO_s, lse, Dvec, dQs, dKs, dV, stream);
         if (st != NATS_OK) return st;
     }
     {   // rows of the softmax tokens in dK, dV (routing per token: their linear share is zero; per chunk: added) and g_nla
         ProfScope ps("softmax_bwd_dkv", stream);
-        st = launch_softmax_bwd_dkv(pl, Qs, Kc, Vc, dO, vis, idx, n_s, lse, Dvec, dKs, dV, ex.g_nla,
+        st = launch_softmax_bwd_dkv(pl, Qs, Kc, Vc, dO_s, vis, idx, n_s, lse, Dvec, dKs, dV, ex.g_nla,
                                     reinterpret_cast<float*>(ws + bp.off_skp), reinterpret_cast<float*>(ws + bp.off_svp),
                                     reinterpret_cast<float*>(ws + bp.off_sgp), stream);
         if (st != NATS_OK) return st;
@@ -656,9 +713,13 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         set_error("with Q_nla and K_nla the gradients dQ_nla and dK_nla must be given");
         return NATS_ERR_NULL;
     }
+    if (bp.merge_mode == 0 && (ex.w_nla || ex.w_la || ex.dw_nla || ex.dw_la)) {
+        set_error("w_nla, w_la, dw_nla, dw_la belong to combine_mode 1 and 2 (the plain sum has no weights)");
+        return NATS_ERR_SHAPE;
+    }
     const void* ptrs[] = {Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, workspace, ex.initial_state,
                           ex.d_initial_state, ex.g_nla, ex.g_la, ex.dscore_nla, ex.dscore_la, ex.Q_nla, ex.K_nla,
-                          ex.dQ_nla, ex.dK_nla};
+                          ex.dQ_nla, ex.dK_nla, ex.w_nla, ex.w_la, ex.dw_nla, ex.dw_la};
     for (const void* ptr : ptrs)
         if (ptr != nullptr && !aligned16(ptr)) { set_error("pointer %p is not 16-byte aligned", ptr); return NATS_ERR_ALIGN; }
     const void* outs[] = {dQ, dK, dV, dalpha, dbeta};
@@ -670,6 +731,20 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
 
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
+    if (bp.merge_mode != 0 && bp.src_dtype == NATS_BF16) {   // the pass runs on fp32 copies (pl.dtype is NATS_F32)
+        ProfScope ps("widen_bf16", stream);
+        const size_t nd = (size_t)pl.BH * pl.L * pl.d;
+        struct { const void** src; size_t off, n; } conv[] = {
+            {&Q, bp.off_cq, nd}, {&K, bp.off_ck, nd}, {&V, bp.off_cv, nd * bp.G}, {&dO, bp.off_cdo, nd * bp.G},
+            {&ex.Q_nla, bp.off_cqn, nd * bp.G}, {&ex.K_nla, bp.off_ckn, nd * bp.G}};
+        for (const auto& c : conv) {
+            if (*c.src == nullptr) continue;
+            float* dst = reinterpret_cast<float*>(ws + c.off);
+            st = launch_widen_bf16(*c.src, dst, c.n, stream);
+            if (st != NATS_OK) return st;
+            *c.src = dst;
+        }
+    }
     if (bp.G == 1) return bwd_core(pl, bp, Q, K, V, alpha, beta, mask, dO, dQ, dK, dV, dalpha, dbeta, ex, ws, stream);
 
     // Head grouping (Section 4.3): member g of every group, i.e. the output heads bh G + g, is a problem of B x H heads
@@ -710,6 +785,23 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
             e1.dQ_nla = reinterpret_cast<float*>(ws + bp.off_gdqn);
             e1.dK_nla = reinterpret_cast<float*>(ws + bp.off_gdkn);
         }
+        if (bp.merge_mode != 0) {   // the member's weights of the merge (per output head) and their gradients
+            const size_t lrow = (size_t)pl.L * 4;
+            float* wn = reinterpret_cast<float*>(ws + bp.off_mwn);
+            float* wl = reinterpret_cast<float*>(ws + bp.off_mwl);
+            if (ex.w_nla) {
+                st = launch_copy_rows(ex.w_nla + g * pl.L, G * lrow, wn, lrow, lrow, pl.BH, stream);
+                if (st != NATS_OK) return st;
+                e1.w_nla = wn;
+            }
+            if (ex.w_la) {
+                st = launch_copy_rows(ex.w_la + g * pl.L, G * lrow, wl, lrow, lrow, pl.BH, stream);
+                if (st != NATS_OK) return st;
+                e1.w_la = wl;
+            }
+            if (ex.dw_nla) e1.dw_nla = reinterpret_cast<float*>(ws + bp.off_mdwn);
+            if (ex.dw_la) e1.dw_la = reinterpret_cast<float*>(ws + bp.off_mdwl);
+        }
         // the first member writes the sums' buffers themselves, the others a buffer of their own that is then added
         if (ex.g_nla) e1.g_nla = first ? ex.g_nla : reinterpret_cast<float*>(ws + bp.off_ggn);
         if (ex.g_la) e1.g_la = first ? ex.g_la : reinterpret_cast<float*>(ws + bp.off_ggl);
@@ -725,6 +817,14 @@ nats_status nats_hybrid_attn_bwd(const nats_fwd_params* p, const void* Q, const 
         if (st != NATS_OK) return st;
         if (ex.d_initial_state) {
             st = launch_copy_rows(dS0g, srow * 4, ex.d_initial_state + g * srow, G * srow * 4, srow * 4, pl.BH, stream);
+            if (st != NATS_OK) return st;
+        }
+        if (e1.dw_nla) {
+            st = launch_copy_rows(e1.dw_nla, (size_t)pl.L * 4, ex.dw_nla + g * pl.L, (size_t)G * pl.L * 4, (size_t)pl.L * 4, pl.BH, stream);
+            if (st != NATS_OK) return st;
+        }
+        if (e1.dw_la) {
+            st = launch_copy_rows(e1.dw_la, (size_t)pl.L * 4, ex.dw_la + g * pl.L, (size_t)G * pl.L * 4, (size_t)pl.L * 4, pl.BH, stream);
             if (st != NATS_OK) return st;
         }
         if (ex.Q_nla) {

@@ -302,6 +302,10 @@ nats_status launch_copy_rows(const void* src, size_t src_stride_bytes, void* dst
                              size_t row_bytes, size_t n_rows, hipStream_t st);
 nats_status launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);
 nats_status launch_zero_f32(float* dst, size_t n, hipStream_t st);
+nats_status launch_merge_bwd(const FwdPlan& pl, int mode, float eps, const float* O_la, const float* O_nla,
+                             const float* dO, const float* w_nla, const float* w_la, float* dO_la, float* dO_nla,
+                             float* dw_nla, float* dw_la, hipStream_t st);
+nats_status launch_widen_bf16(const void* src, float* dst, size_t n, hipStream_t st);
 nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
                                          float* dscore_la, hipStream_t st);   // ds_la_part NULL: dscore_la is left as it is
 nats_status launch_score_gradients(const FwdPlan& pl, const float* beta, const uint8_t* mask, const float* dbeta,

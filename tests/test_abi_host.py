@@ -37,10 +37,11 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_abi_version(lib):
-    assert lib.nats_abi_version() == 112   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
+    assert lib.nats_abi_version() == 113   # 101: nats_fwd_params gained `routing`; 102: nats_fwd_extra gained `W_out`;
     # 103: nats_fwd_params and nats_dec_params gained `linear_op` and `freeze_on_softmax`; 104: backward entry points; 105: Q_nla / K_nla; 106: weight_act; 107: combine_mode 2; 108: gdn_segments, nats_hybrid_attn_fwd_noalloc; 109: group, decode workspace;
     # 110: p->math selects the form of the backward's linear adjoint, C = 128 with routing per chunk; 111: the backward
-    # pass takes p->group; 112: nats_bwd_extra gained Q_nla, K_nla, dQ_nla, dK_nla
+    # pass takes p->group; 112: nats_bwd_extra gained Q_nla, K_nla, dQ_nla, dK_nla;
+    # 113: the backward takes combine_mode 1 and 2 (nats_bwd_extra gained w_nla, w_la, dw_nla, dw_la)
 
 
 def good_params(**over):
@@ -174,7 +175,9 @@ def test_backward_validation(lib):
     need_tok = lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(math=nb.NATS_MATH_FP32)))
     assert need_tok > need
     assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK))) > 0
-    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(combine_mode=1))) == 0
+    # the merges of Eq. 21 run on fp32 copies and keep both branches' rows: a larger workspace
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(combine_mode=1))) > need
+    assert lib.nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(good_params(combine_mode=3))) == 0
 
     def call(prm, ptrs=None, ws=FAKE, ws_bytes=1 << 40):
         ptrs = [FAKE + 16 * i for i in range(12)] if ptrs is None else ptrs
@@ -185,7 +188,10 @@ def test_backward_validation(lib):
     ptrs0 = [FAKE + 16 * i for i in range(12)]
     assert lib.nats_hybrid_attn_bwd(ctypes.byref(good_params(routing=nb.NATS_ROUTE_CHUNK)), *ptrs0, ctypes.byref(ex), FAKE,
                                     1 << 40, None) == E_UNSUP
-    assert call(good_params(combine_mode=1)) == E_UNSUP
+    assert call(good_params(combine_mode=3)) == E_SHAPE
+    # weights of the merge belong to combine_mode 1 and 2
+    exw = nb.BwdExtra(None, None, None, None, None, None, None, None, None, None, FAKE, None, None, None)
+    assert lib.nats_hybrid_attn_bwd(ctypes.byref(p), *ptrs0, ctypes.byref(exw), FAKE, 1 << 40, None) == E_SHAPE
     assert call(good_params(L=100)) == E_SHAPE
     ptrs = [FAKE + 16 * i for i in range(12)]
     ptrs[6] = None                                     # dO

@@ -301,3 +301,53 @@ def test_backward_with_own_softmax_queries_and_keys(dtype, B, H, G, L, d, routin
     assert tuple(r["dQ_nla"].shape) == (B, H * G, L, d) and tuple(r["dQ"].shape) == (B, H, L, d)
     errs = check(r, ref, extra=extra)
     print(dtype, G, routing, errs)
+
+
+# ---- the normalised, weighted merges (Eq. 21; Section 5, ablation (iii)) ------------------------------------------------
+@pytest.mark.parametrize("dtype,B,H,G,L,d,own_qk,weights", [
+    ("f32", 1, 2, 1, 320, 64, False, True), ("bf16", 1, 2, 1, 448, 128, False, True),
+    ("bf16", 1, 2, 2, 256, 64, True, True), ("f32", 2, 1, 3, 256, 128, False, False)])
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("routing", ["token", "chunk"])
+def test_backward_through_the_normalised_merges(dtype, B, H, G, L, d, own_qk, weights, mode, routing):
+    """combine_mode 1 (Eq. 21) and 2 (one normalisation): every gradient, those of the two weights included, against
+    the oracle's adjoint of the same merge; bf16 tensors are widened and the pass runs in fp32."""
+    x = make_fwd_inputs(B, H, L, d, dtype, 0.15, seed=980 + L + G)
+    xs = make_fwd_inputs(B, H * G, L, d, dtype, 0.15, seed=981 + L + G)
+    x["V"] = xs["V"]
+    dO = make_grad_output(B, H * G, L, d, dtype, seed=982 + L)
+    rng = np.random.default_rng(983 + L + mode)
+    S0 = (0.05 * rng.standard_normal((B, H * G, d, d))).astype(np.float32)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    kw, okw = dict(S0=S0, group=G, combine_mode=mode, rms_eps=1e-5), dict(S0=S0, mode=mode, eps=1e-5)
+    if own_qk:
+        kw.update(Q_nla=torch.from_numpy(xs["Q"]).to(tdt).cuda(), K_nla=torch.from_numpy(xs["K"]).to(tdt).cuda())
+        okw.update(Q_nla=xs["Q"], K_nla=xs["K"])
+    if weights:
+        wn = (rng.random((B, H * G, L)) + 0.1).astype(np.float32)
+        wl = (rng.random((B, H * G, L)) + 0.1).astype(np.float32)
+        kw.update(w_nla=torch.from_numpy(wn).cuda(), w_la=torch.from_numpy(wl).cuda())
+        okw.update(w_nla=wn, w_la=wl)
+    extra = (("dw_nla", "dw_nla"), ("dw_la", "dw_la")) + ((("dQ_nla", "dQ_nla"), ("dK_nla", "dK_nla")) if own_qk else ())
+    if routing == "chunk":
+        x["mask"] = make_chunk_mask(B, H, L // 64, 0.35, 984 + L, "bernoulli")
+        r = run_bwd(x, dO, dtype, routing=nb.NATS_ROUTE_CHUNK, want=("d_initial_state", "dscore_nla", "dscore_la"), **kw)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, C=64, **okw)
+        extra = CHUNK_KEYS + extra
+    else:
+        r = run_bwd(x, dO, dtype, want=("d_initial_state", "g_nla", "g_la"), **kw)
+        ref = nbw.hybrid_bwd_grouped(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, G, **okw)
+        extra = (("d_initial_state", "dS0"), ("g_nla", "g_nla"), ("g_la", "g_la")) + extra
+    assert tuple(r["dw_nla"].shape) == (B, H * G, L)
+    errs = check(r, ref, extra=extra)
+    print(dtype, G, mode, routing, errs)
+
+
+def test_backward_through_the_merge_token_by_token_adjoint():
+    """The same with the linear branch's adjoint token by token (math = NATS_MATH_FP32)."""
+    B, H, L, d = 1, 2, 256, 64
+    x = make_fwd_inputs(B, H, L, d, "bf16", 0.2, seed=990)
+    dO = make_grad_output(B, H, L, d, "bf16", seed=991)
+    r = run_bwd(x, dO, "bf16", want=("d_initial_state",), combine_mode=1, math=nb.NATS_MATH_FP32)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, mode=1)
+    check(r, ref, extra=(("d_initial_state", "dS0"), ("dw_nla", "dw_nla"), ("dw_la", "dw_la")))
