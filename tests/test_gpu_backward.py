@@ -351,3 +351,27 @@ def test_backward_through_the_merge_token_by_token_adjoint():
     r = run_bwd(x, dO, "bf16", want=("d_initial_state",), combine_mode=1, math=nb.NATS_MATH_FP32)
     ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, mode=1)
     check(r, ref, extra=(("d_initial_state", "dS0"), ("dw_nla", "dw_nla"), ("dw_la", "dw_la")))
+
+
+@pytest.mark.parametrize("kind", ["all_softmax", "all_linear"])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_backward_through_the_merges_degenerate_masks(kind, mode):
+    """A branch whose rows are all zero (no softmax token at all; no linear token and no initial state): its
+    normalised rows are zero and so is its weight's gradient; the normalisation's derivative at zero is 1/sqrt(eps)."""
+    B, H, L, d = 1, 2, 192, 64
+    x = make_fwd_inputs(B, H, L, d, "f32", 0.1, seed=995)
+    x["mask"] = np.full((B, H, L), 1 if kind == "all_softmax" else 0, dtype=np.uint8)
+    dO = make_grad_output(B, H, L, d, "f32", seed=996)
+    r = run_bwd(x, dO, "f32", want=(), combine_mode=mode)
+    ref = nbw.hybrid_bwd(x["Q"], x["K"], x["V"], x["alpha"], x["beta"], x["mask"], dO, mode=mode)
+    if mode == 1:
+        check(r, ref, extra=(("dw_nla", "dw_nla"), ("dw_la", "dw_la")))
+        return
+    # One normalisation of the weighted sum, one branch zero: the output does not depend on the scale of the other
+    # branch's weight, whose gradient is the difference of two equal terms (exactly eps / (mean square + eps) of
+    # one of them).  It is held to 1e-4 of those terms' size (|dO row| x |normalised row| = |dO row| sqrt(d)),
+    # not of its own.
+    check(r, ref)
+    scale = float(np.sqrt(np.mean(np.sum(dO.astype(np.float64) ** 2, axis=-1)) * d))
+    for key in ("dw_nla", "dw_la"):
+        assert np.max(np.abs(host(r[key]) - ref[key])) <= TOL_BWD * scale, key
