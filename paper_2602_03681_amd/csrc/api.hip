@@ -585,16 +585,40 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
         st = launch_softmax_fp32(pl, Qs, Kc, Vc, Ks, V, cnt, nullptr, nullptr, nullptr, nullptr, O_nla, lse, stream);
         if (st != NATS_OK) return st;
     }
-    // The merges of Eq. 21 and its ablation: the linear branch's rows once more, token by token in fp32, then the merge's
-    // adjoint turns dO into one gradient per branch; from here on each branch runs as for the plain sum.
+    float* ops = reinterpret_cast<float*>(ws + bp.off_ops);
+    float* Ug = reinterpret_cast<float*>(ws + bp.off_ug);
+    float* Uh = reinterpret_cast<float*>(ws + bp.off_uh);
+    float* dck = reinterpret_cast<float*>(ws + bp.off_dck);
+    const bool by_chunks = pl.math != NATS_MATH_FP32;   // the linear branch's backward by chunks of 64 tokens
+    if (by_chunks || !chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
+        {
+            ProfScope ps("gdn_bwd_prep", stream);
+            st = launch_gdn_bwd_prep(pl, Q, K, alpha, beta, mask, ops, stream);
+            if (st != NATS_OK) return st;
+        }
+        ProfScope ps("gdn_chunk_states", stream);
+        st = launch_gdn_chunk_states(pl, K, V, ops, ex.initial_state, ckpt, Ug, Uh, stream);
+        if (st != NATS_OK) return st;
+    } else {   // ... token by token
+        ProfScope ps("gdn_checkpoints", stream);
+        st = launch_gdn_checkpoints(pl, K, V, alpha, beta, mask, ex.initial_state, ckpt, stream);
+        if (st != NATS_OK) return st;
+    }
+    // The merges of Eq. 21 and its ablation: the linear branch's rows once more in fp32 (from the chunk-start states and
+    // U just made, or token by token where the states were made token by token), then the merge's adjoint turns dO into
+    // one gradient per branch; from here on each branch runs as for the plain sum.
     const void* dO_s = dO;   // gradient of the softmax branch's rows
     const void* dO_l = dO;   // ... of the linear branch's
     if (bp.merge_mode != 0) {
         float* O_la = reinterpret_cast<float*>(ws + bp.off_mola);
-        {
+        if (by_chunks || !chunk) {
+            ProfScope ps("gdn_chunk_out", stream);
+            st = launch_gdn_chunk_out(pl, Q, ops, ckpt, Ug, O_la, stream);
+            if (st != NATS_OK) return st;
+        } else {
             ProfScope ps("gdn_recurrent", stream);
             st = launch_gdn_recurrent(pl, Q, K, V, alpha, beta, mask, ex.initial_state, nullptr, O_la,
-                                      chunk ? reinterpret_cast<float*>(ws + bp.off_msnap) : nullptr, stream);
+                                      reinterpret_cast<float*>(ws + bp.off_msnap), stream);
             if (st != NATS_OK) return st;
         }
         ProfScope ps("merge_bwd", stream);
@@ -623,25 +647,6 @@ static nats_status bwd_core(const FwdPlan& pl, const BwdPlan& bp, const void* Q,
         ProfScope ps("zero_fill", stream);
         st = launch_zero_f32(dQ, n_qk, stream);
         if (st == NATS_OK) st = launch_zero_f32(dKs, n_qk, stream);
-        if (st != NATS_OK) return st;
-    }
-    float* ops = reinterpret_cast<float*>(ws + bp.off_ops);
-    float* Ug = reinterpret_cast<float*>(ws + bp.off_ug);
-    float* Uh = reinterpret_cast<float*>(ws + bp.off_uh);
-    float* dck = reinterpret_cast<float*>(ws + bp.off_dck);
-    const bool by_chunks = pl.math != NATS_MATH_FP32;   // the linear branch's backward by chunks of 64 tokens
-    if (by_chunks || !chunk) {   // the linear branch forwards once more by chunks, leaving the state at the start of every chunk
-        {
-            ProfScope ps("gdn_bwd_prep", stream);
-            st = launch_gdn_bwd_prep(pl, Q, K, alpha, beta, mask, ops, stream);
-            if (st != NATS_OK) return st;
-        }
-        ProfScope ps("gdn_chunk_states", stream);
-        st = launch_gdn_chunk_states(pl, K, V, ops, ex.initial_state, ckpt, Ug, Uh, stream);
-        if (st != NATS_OK) return st;
-    } else {   // ... token by token
-        ProfScope ps("gdn_checkpoints", stream);
-        st = launch_gdn_checkpoints(pl, K, V, alpha, beta, mask, ex.initial_state, ckpt, stream);
         if (st != NATS_OK) return st;
     }
     if (by_chunks) {

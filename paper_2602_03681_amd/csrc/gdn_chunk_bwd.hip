@@ -875,6 +875,88 @@ constexpr size_t grads_lds_bytes() {
 }
 
 
+// ---- the linear branch's output rows from what the forward-by-chunks leaves ---------------------------------------------
+// O = la (diag(gamma) Q S0^T + P U) for every chunk at once, fp32: S0 the state at the chunk's start (ck), U the rows
+// gdn_chunk_seq_kernel<.., 0> wrote, P and gamma from the chunk's operands.  Needed where the backward pass must know
+// the branch's rows (the merges that normalise them, Eq. 21).  One block per (chunk, batch*head); wavefront w owns a
+// quarter of the value columns for all 64 tokens, so every element of S0 and U is read once per block, straight
+// from memory as the right operand; Q and P, which every wavefront reads whole, go through LDS.
+template <int D>
+__global__ __launch_bounds__(256) void gdn_chunk_out_kernel(const float* __restrict__ Q, const ChunkOps o,
+                                                           const float* __restrict__ ck, const float* __restrict__ Ug,
+                                                           float* __restrict__ O_la, const int L, const int BH,
+                                                           const float la_scale) {
+    constexpr int KS = D + 4, MS = CB_MS, VW = D / 4, VT = VW / 16;   // value columns per wavefront, in tiles of 16
+    __shared__ __align__(16) float Qs[CB_C * KS];
+    __shared__ __align__(16) float Ps[CB_C * MS];
+    __shared__ float s_gam[CB_C];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int n_chunks = L / CB_C;
+    const int bh = blockIdx.x % BH, chunk = blockIdx.x / BH;
+    const size_t gc = (size_t)bh * n_chunks + chunk, tok0 = (size_t)bh * L + (size_t)chunk * CB_C;
+    for (int e = tid; e < CB_C * D / 4; e += 256) {
+        const int row = e / (D / 4), c4 = (e % (D / 4)) * 4;
+        *reinterpret_cast<float4*>(Qs + row * KS + c4) = ld4(Q + (tok0 + row) * D + c4);
+    }
+    for (int e = tid; e < CB_C * CB_C / 4; e += 256) {
+        const int row = e / 16, c4 = (e % 16) * 4;
+        *reinterpret_cast<float4*>(Ps + row * MS + c4) = ld4(o.Pm + gc * (CB_C * CB_C) + row * CB_C + c4);
+    }
+    if (tid < CB_C) s_gam[tid] = o.gam[tok0 + tid];
+    __syncthreads();
+    const float* S0 = ck + gc * (size_t)D * D;
+    f32x4 acc[4][VT];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int vt = 0; vt < VT; ++vt) acc[tt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Q S0^T: A = Q[token l16 of tile tt][k], B = S0[v = l16 of tile vt][k]
+#pragma unroll 2
+    for (int kt = 0; kt < D / 16; ++kt) {
+        float4 b[VT];
+#pragma unroll
+        for (int vt = 0; vt < VT; ++vt) b[vt] = ld4(S0 + (size_t)(VW * w + 16 * vt + l16) * D + 16 * kt + 4 * lq);
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const float4 a = ld4(Qs + (16 * tt + l16) * KS + 16 * kt + 4 * lq);
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) acc[tt][vt] = mac16(a, b[vt], acc[tt][vt]);
+        }
+    }
+    // rows scaled by gamma (a lane holds tokens 16 tt + 4 lq + j of value column l16)
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+        const float4 g4 = ld4(s_gam + 16 * tt + 4 * lq);
+        const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+        for (int vt = 0; vt < VT; ++vt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[tt][vt][j] *= g[j];
+    }
+    // + P U: A = P[token][i], B = U[i = 16 tb + 4 lq + j][v]; P is lower triangular: tiles tb <= tt
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+        float4 b[VT];
+#pragma unroll
+        for (int vt = 0; vt < VT; ++vt)
+            b[vt] = ld4col(Ug + (tok0 + 16 * tb + 4 * lq) * D + VW * w + 16 * vt + l16, D);
+#pragma unroll
+        for (int tt = tb; tt < 4; ++tt) {
+            const float4 a = ld4(Ps + (16 * tt + l16) * MS + 16 * tb + 4 * lq);
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) acc[tt][vt] = mac16(a, b[vt], acc[tt][vt]);
+        }
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int vt = 0; vt < VT; ++vt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                O_la[(tok0 + 16 * tt + 4 * lq + j) * D + VW * w + 16 * vt + l16] = la_scale * acc[tt][vt][j];
+}
+
 static ChunkOps chunk_ops(const FwdPlan& pl, float* base) {
     const size_t n_tok = (size_t)pl.BH * pl.L, n_ch = n_tok / CB_C;
     ChunkOps o;
@@ -948,6 +1030,21 @@ nats_status launch_gdn_chunk_states(const FwdPlan& pl, const void* K, const void
     }
     if (!ok) { set_error("gdn_chunk_states: the kernel's LDS size was refused"); return NATS_ERR_HIP; }
     return check_launch("gdn_chunk_states");
+}
+
+// O_la [BH][L][d] f32 from ops (after launch_gdn_bwd_prep), ck and Ug (after launch_gdn_chunk_states).  fp32 tensors.
+nats_status launch_gdn_chunk_out(const FwdPlan& pl, const void* Q, float* ops, const float* ck, const float* Ug,
+                                 float* O_la, hipStream_t st) {
+    if (pl.dtype != NATS_F32) { set_error("gdn_chunk_out: fp32 tensors only"); return NATS_ERR_UNSUPPORTED; }
+    const ChunkOps o = chunk_ops(pl, ops);
+    const dim3 grid((unsigned)(pl.BH * (pl.L / CB_C)));
+    if (pl.d == 64)
+        hipLaunchKernelGGL(gdn_chunk_out_kernel<64>, grid, dim3(256), 0, st, (const float*)Q, o, ck, Ug, O_la, pl.L, pl.BH,
+                           pl.la_scale);
+    else
+        hipLaunchKernelGGL(gdn_chunk_out_kernel<128>, grid, dim3(256), 0, st, (const float*)Q, o, ck, Ug, O_la, pl.L, pl.BH,
+                           pl.la_scale);
+    return check_launch("gdn_chunk_out");
 }
 
 // The state gradients behind every chunk, dck [BH][L/64][d][d]; dV (every row), dbeta_part [d/16][BH][L], dS0 (or NULL).

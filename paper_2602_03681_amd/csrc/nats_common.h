@@ -305,6 +305,8 @@ nats_status launch_zero_f32(float* dst, size_t n, hipStream_t st);
 nats_status launch_merge_bwd(const FwdPlan& pl, int mode, float eps, const float* O_la, const float* O_nla,
                              const float* dO, const float* w_nla, const float* w_la, float* dO_la, float* dO_nla,
                              float* dw_nla, float* dw_la, hipStream_t st);
+nats_status launch_gdn_chunk_out(const FwdPlan& pl, const void* Q, float* ops, const float* ck, const float* Ug,
+                                 float* O_la, hipStream_t st);
 nats_status launch_widen_bf16(const void* src, float* dst, size_t n, hipStream_t st);
 nats_status launch_score_gradients_chunk(const FwdPlan& pl, const float* g_nla, const float* ds_la_part, float* dscore_nla,
                                          float* dscore_la, hipStream_t st);   // ds_la_part NULL: dscore_la is left as it is
