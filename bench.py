@@ -147,15 +147,16 @@ def bench_decode(args):
 
 
 def bench_backward(args):
-    print(json.dumps(measure_backward(args.steps, args.warmup, args.routing, args.backward_by_tokens)))
+    print(json.dumps(measure_backward(args.steps, args.warmup, args.routing, args.backward_by_tokens, args.combine_mode)))
 
 
-def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False):
+def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False, combine_mode=0):
     """Backward pass on workload 2's shapes (bf16 tensors, fp32 gradients): a step is one nats_hybrid_attn_bwd call.
     The linear branch's adjoint runs by chunks on fp32 matrix instructions (operands per chunk, states forwards,
     state gradients backwards, then every chunk's gradients); the softmax branch's products run on fp16 / bf16 matrix
     instructions with two-term fp16 weights.  Roofline: fp32 matrix peak for the chunk kernels, counted per chunk of
-    64 tokens with triangular products at 10 of 16 tiles."""
+    64 tokens with triangular products at 10 of 16 tiles.  combine_mode 1, 2: the backward through the merge of Eq. 21
+    (its single-normalisation ablation), which widens the tensors and runs the fp32 kernels."""
     import torch
 
     import paper_2602_03681_amd as nats
@@ -177,24 +178,26 @@ def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False)
         mask_c = make_chunk_mask(cfg.B, cfg.H, cfg.L // cfg.C, cfg.p_softmax, cfg.seed + 1)
         mask_c[:, :, 0] = 1
         g["mask"] = torch.from_numpy(mask_c).to(dev)
-    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, math=math, routing=routing)
+    prm = nb.make_fwd_params(cfg.B, cfg.H, cfg.L, cfg.d, cfg.C, nb.NATS_BF16, math=math, routing=routing,
+                             combine_mode=combine_mode)
     ws = torch.empty(int(nb.load_library().nats_hybrid_attn_bwd_workspace_bytes(ctypes.byref(prm))), dtype=torch.uint8,
                      device=dev)
 
     def step():
-        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math, routing=routing)
+        return nats.hybrid_attn_bwd(Q, K, V, g["alpha"], g["beta"], g["mask"], dO, workspace=ws, math=math, routing=routing,
+                                    combine_mode=combine_mode)
 
     steps = max(1, min(steps_in, 20))
     for _ in range(max(1, min(warmup_in, 3))):
         step()
     torch.cuda.synchronize()
-    nb.profile_begin(16 * steps)
+    nb.profile_begin(32 * steps)
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    kern = nb.profile_end()
+    kern = nb.profile_end(32)
     n_tok = cfg.B * cfg.H * cfg.L
     n_chunks, d = n_tok // 64, cfg.d
     tri = 10.0 / 16.0   # tiles of a 64 x 64 triangular operand that are multiplied
@@ -204,6 +207,7 @@ def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False)
         "gdn_chunk_states": 2 * sq + 2 * tri * st,          # K S^T, the state update; T and At products
         "gdn_chunk_state_grads": 3 * sq + 2 * tri * st,     # K dS^T, two state updates; P^T and T^T products
         "gdn_chunk_grads": 3 * sq + 4 * tri * st + st,      # dO' S0, dR S0, U dS1; dP, dAt, (dP.G) K, (dP.G)^T Q; symmetric . K
+        "gdn_chunk_out": sq + tri * st,                     # Q S0^T, P U (the branch's rows for the merge's adjoint)
         # token by token: about 25 d_k flops per state row and token (re-run of the chunk, then the adjoint)
         "gdn_recurrent_bwd": 25.0 * 64 * d * d,
     }
@@ -221,7 +225,8 @@ def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False)
            "config": {"workload": "backward of cfg2_headline_bf16" + (", routing per chunk" if routing_name == "chunk" else "")
                                   + " (bf16 tensors, fp32 gradients; linear branch "
                                   + ("token by token in fp32" if by_tokens else "by chunks on fp32 MFMA")
-                                  + ", softmax-branch products on MFMA with two-term fp16 weights)"},
+                                  + (", softmax-branch products on MFMA with two-term fp16 weights)" if combine_mode == 0 else
+                                     f", through the merge combine_mode {combine_mode}: tensors widened, fp32 kernels)")},
            "kernels_ms": {k: round(v["avg_ms"], 4) for k, v in kern.items()}, "dominant": dom,
            "roofline": dict(kernel=lead, traffic=None, **roofs[lead]), "kernel_rooflines": roofs,
            "cpu_baseline": None}
@@ -254,6 +259,8 @@ def main():
     ap.add_argument("--no-backward-line", action="store_true",
                     help="leave the short backward measurement out of the forward's JSON line")
     ap.add_argument("--backward", action="store_true", help="measure the backward pass instead")
+    ap.add_argument("--combine-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="--backward only: the merge the backward runs through (0 plain sum, 1 Eq. 21, 2 one normalisation)")
     ap.add_argument("--backward-by-tokens", action="store_true",
                     help="with --backward: the linear branch's adjoint token by token (math = NATS_MATH_FP32)")
     args = ap.parse_args()
