@@ -4,7 +4,7 @@
 //   dx = r (dy - y (y . dy) / d).
 // The merge acts row by row, so the kernel turns dO into one gradient per branch (each branch's backward then runs on
 // its own, as for the plain sum) and gives the gradients of the two weights.  fp32 throughout; a row is held by d / 4
-// adjacent lanes, four columns each.  Streams five rows in and two out: HBM-bound.
+// adjacent lanes, four columns each.  Streams three rows in and two out: HBM-bound.
 // Also here: the widening copy bf16 -> fp32 that the backward pass with these merges runs on its inputs (the
 // branches then receive fp32 gradients of their outputs, which the kernels for bf16 tensors do not take).
 #include "nats_common.h"
