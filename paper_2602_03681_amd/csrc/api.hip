@@ -464,7 +464,13 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
     if (ex.n_s) n_s = ex.n_s;
 
     ProfChain prof_chain;   // the kernels below follow each other on one stream
-    if (ex.W_out != nullptr && pl.combine_mode != 0) {   // Eq. 22: the merge weights from Q
+    // Eq. 22: the merge weights from Q.  On the matrix-core path the softmax kernel makes them itself from the query rows
+    // it holds (when those are Q, not queries of the softmax branch's own, and no fp32 side output takes the kernel's
+    // other epilogue); otherwise a kernel of its own writes them to the workspace.
+    const float* W_fused = nullptr;
+    if (ex.W_out != nullptr && pl.combine_mode != 0 && uses_chunk_path(pl) && ex.Q_nla == nullptr && ex.O_nla == nullptr)
+        W_fused = ex.W_out;
+    else if (ex.W_out != nullptr && pl.combine_mode != 0) {
         float* w = reinterpret_cast<float*>(ws + pl.off_wout);
         ProfScope ps("merge_weights", stream);
         st = launch_merge_weights(pl.B, pl.H * pl.G, pl.L, pl.d, pl.dtype, Q, ex.W_out, w, w + (size_t)pl.BHG * pl.L,
@@ -507,7 +513,7 @@ nats_status nats_hybrid_attn_fwd_ex(const nats_fwd_params* p, const void* Q, con
         if (st != NATS_OK) return st;
         {
             ProfScope ps("flash_softmax", stream);
-            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, Oh, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream);
+            st = launch_flash_softmax(pl, Qs, Kc, VhT, Ks, V, cnt, Oh, ex.w_nla, ex.w_la, O, ex.O_nla, ex.lse, stream, W_fused);
         }
     } else {
         {

@@ -51,6 +51,13 @@ __device__ __forceinline__ float quad_max(float x) {
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
+__device__ __forceinline__ float quad_sum(float x) {
+    const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // The epilogue reads the linear branch's output (fp16), merges (Section 4.1 sum, Eq. 21 or its ablation) and
 // stores O.
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
@@ -63,7 +70,8 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O,
     float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
-    float eps, int BH, int G, int qk_per_out_head, int own_chunk) {
+    float eps, int BH, int G, int qk_per_out_head, int own_chunk, const float* __restrict__ W_out, int weight_act,
+    int heads_out) {
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -362,20 +370,81 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     }
     __syncthreads();   // tiles are dead: the region becomes the output staging
 
-    if (!STATS && combine_mode == 0 && O_nla_out == nullptr) {
-        // The plain sum (no row statistics needed) and no fp32 copy asked for: the
-        // normalised rows are staged as fp16, both 16-query groups of the wavefront at once, so that all LDS
-        // writes, then all LDS reads, then all stores (16 bytes per lane, full rows) are in flight together.
+    if (!STATS && O_nla_out == nullptr) {
+        // No fp32 copy of the branch's rows asked for: the normalised rows are staged as fp16, both 16-query groups
+        // of the wavefront at once, so that all LDS writes, then all LDS reads, then all stores (16 bytes per lane,
+        // full rows) are in flight together.  Read back, a row lies in D / 8 adjacent lanes beside the linear
+        // branch's row (fp16 as well): the plain sum adds them; Eq. 21 and its ablation take the rows' mean squares
+        // with sums over those lanes.
         constexpr int HS = D + 8;                 // staged row, fp16 elements
         constexpr int LPR_H = D / 8;              // lanes per row
         constexpr int RPP_H = 64 / LPR_H;         // rows per pass
         static_assert(4 * FL_NQ * 16 * HS * 2 <= LDS_BYTES, "fp16 output staging must fit the tile region");
         half_t* Oh = reinterpret_cast<half_t*>(smem) + wave * (FL_NQ * 16 * HS);
+        // Eq. 22 here (W_out given: [heads_out][2][D] f32): the two logits of a query are dot products of its row with
+        // the head's two weight vectors, and the query's row is still in this lane group's registers as the first
+        // product's operand (lane (l16, lq) holds columns 32 ks + 8 lq .. + 7 of query l16): 8 D / 16 multiply-adds per
+        // lane, a sum over the four lanes of the query, the activation; the weights go through LDS to the lanes that
+        // merge the row.
+        __shared__ float s_w[2][FL_BM];
+        const bool fused_w = combine_mode != 0 && W_out != nullptr;
+        if (fused_w) {
+            const float* w0 = W_out + (size_t)(bh % heads_out) * 2 * D;
+            float lg[FL_NQ][2];
+#pragma unroll
+            for (int nq = 0; nq < FL_NQ; ++nq) lg[nq][0] = lg[nq][1] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS_D; ++ks) {
+                float wv[2][8];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const float4 x = *reinterpret_cast<const float4*>(w0 + k * D + 32 * ks + 8 * lq);
+                    const float4 y = *reinterpret_cast<const float4*>(w0 + k * D + 32 * ks + 8 * lq + 4);
+                    wv[k][0] = x.x; wv[k][1] = x.y; wv[k][2] = x.z; wv[k][3] = x.w;
+                    wv[k][4] = y.x; wv[k][5] = y.y; wv[k][6] = y.z; wv[k][7] = y.w;
+                }
+#pragma unroll
+                for (int nq = 0; nq < FL_NQ; ++nq)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float qa = __uint_as_float(qf[nq][ks][j] << 16), qb = __uint_as_float(qf[nq][ks][j] & 0xffff0000u);
+                        lg[nq][0] += qa * wv[0][2 * j] + qb * wv[0][2 * j + 1];
+                        lg[nq][1] += qa * wv[1][2 * j] + qb * wv[1][2 * j + 1];
+                    }
+            }
+#pragma unroll
+            for (int nq = 0; nq < FL_NQ; ++nq) {
+                const float a = quad_sum(lg[nq][0]), b = quad_sum(lg[nq][1]);
+                float wa, wb;
+                if (weight_act == 0) {          // Eq. 22: softmax over the two logits
+                    const float m = fmaxf(a, b);
+                    const float ea = expf(a - m), eb = expf(b - m);
+                    const float inv = 1.f / (ea + eb);
+                    wa = ea * inv;
+                    wb = eb * inv;
+                } else if (weight_act == 1) {   // sigmoid weights
+                    wa = 1.f / (1.f + expf(-a));
+                    wb = 1.f / (1.f + expf(-b));
+                } else {                        // linear weights
+                    wa = a;
+                    wb = b;
+                }
+                if (lq == 0) {
+                    s_w[0][(wave * FL_NQ + nq) * 16 + l16] = wa;
+                    s_w[1][(wave * FL_NQ + nq) * 16 + l16] = wb;
+                }
+            }
+        }
         u32x4 la_rows[FL_NQ * 16 / RPP_H];   // the linear branch's rows (fp16), asked for up front
+        float wn_row[FL_NQ * 16 / RPP_H], wl_row[FL_NQ * 16 / RPP_H];   // the rows' weights (Eq. 21 and its ablation)
+        const float w_default = combine_mode == 1 ? 0.5f : 1.f;
 #pragma unroll
         for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
             const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
-            la_rows[pass] = *reinterpret_cast<const u32x4*>(O_la + (tokbase + (q < L ? q : 0)) * D + 8 * (lane % LPR_H));
+            const size_t tok = tokbase + (q < L ? q : 0);
+            la_rows[pass] = *reinterpret_cast<const u32x4*>(O_la + tok * D + 8 * (lane % LPR_H));
+            wn_row[pass] = (combine_mode != 0 && !fused_w && w_nla != nullptr) ? w_nla[tok] : w_default;
+            wl_row[pass] = (combine_mode != 0 && !fused_w && w_la != nullptr) ? w_la[tok] : w_default;
         }
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
@@ -393,18 +462,49 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
         __builtin_amdgcn_wave_barrier();   // LDS operations of one wavefront complete in order
         u32x4 rows[FL_NQ * 16 / RPP_H];
 #pragma unroll
-        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass)
+        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
             rows[pass] = *reinterpret_cast<const u32x4*>(Oh + (pass * RPP_H + lane / LPR_H) * HS + 8 * (lane % LPR_H));
+            if (fused_w) {   // this wavefront's own queries: written above by this wavefront
+                wn_row[pass] = s_w[0][wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H];
+                wl_row[pass] = s_w[1][wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H];
+            }
+        }
 #pragma unroll
         for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
             const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
-            if (q >= L) continue;
-            // O = O_la + O_nla (Section 4.1), rounded to bf16 once
             const half8 a = __builtin_bit_cast(half8, rows[pass]), b = __builtin_bit_cast(half8, la_rows[pass]);
+            float o[8];
+            if (combine_mode == 0) {   // O = O_la + O_nla (Section 4.1), rounded to bf16 once
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] = (float)a[j] + (float)b[j];
+            } else {                   // (every lane of a row takes part in the row's sums: no lane leaves before them)
+                float ssn = 0.f, ssl = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    ssn += (float)a[j] * (float)a[j];
+                    ssl += (float)b[j] * (float)b[j];
+                }
+                float wn = wn_row[pass], wl = wl_row[pass];
+                if (combine_mode == 1) {   // Eq. 21: each branch normalised, then weighted
+                    wn /= sqrtf(lane_group_sum<LPR_H>(ssn) / D + eps);
+                    wl /= sqrtf(lane_group_sum<LPR_H>(ssl) / D + eps);
+                }
+                float ss = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    o[j] = wn * (float)a[j] + wl * (float)b[j];
+                    ss += o[j] * o[j];
+                }
+                if (combine_mode == 2) {   // one normalisation of the weighted sum
+                    const float inv = 1.f / sqrtf(lane_group_sum<LPR_H>(ss) / D + eps);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] *= inv;
+                }
+            }
+            if (q >= L) continue;
             u32x4 w;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                w[j] = pack_bf16x2((float)a[2 * j] + (float)b[2 * j], (float)a[2 * j + 1] + (float)b[2 * j + 1]);
+            for (int j = 0; j < 4; ++j) w[j] = pack_bf16x2(o[2 * j], o[2 * j + 1]);
             *reinterpret_cast<u32x4*>(O + (tokbase + q) * D + 8 * (lane % LPR_H)) = w;
         }
         return;
@@ -486,40 +586,48 @@ template <int D>
 static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT, const void* K,
                       const void* V, const int32_t* cnt,
                       const void* O_la, const float* w_nla, const float* w_la, void* O,
-                      float* O_nla_out, float* lse_out, hipStream_t st) {
+                      float* O_nla_out, float* lse_out, const float* W_out, hipStream_t st) {
     dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BHG + 7) & ~7)));
     if (O == nullptr) {   // the backward pass's call: branch output and log-sum-exp only
         if (pl.routing == NATS_ROUTE_CHUNK)
             hipLaunchKernelGGL((flash_softmax_kernel<D, true, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                                (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
                                nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
-                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2, nullptr, 0, 1);
         else
             hipLaunchKernelGGL((flash_softmax_kernel<D, false, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                                (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
                                nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
-                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+                               pl.G, pl.qk_per_out_head, pl.inner_chunk != 2, nullptr, 0, 1);
         return;
     }
     if (pl.routing == NATS_ROUTE_CHUNK)
         hipLaunchKernelGGL((flash_softmax_kernel<D, true, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
+                           W_out, pl.weight_act, pl.H * pl.G);
     else
         hipLaunchKernelGGL((flash_softmax_kernel<D, false, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
-                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2);
+                           pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
+                           W_out, pl.weight_act, pl.H * pl.G);
 }
 
 // reads O_la (fp16, the linear branch's rows), merges, writes O.  O = NULL: no merge, O_nla_out and lse_out (both
-// required then) to fp32 accuracy
+// required then) to fp32 accuracy.  W_out (or NULL): the merge weights made here from the kernel's queries by
+// Eq. 22 instead of read from w_nla, w_la; only with O_nla_out = NULL, and Q must be the tensor Eq. 22 reads.
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const void* K, const void* V, const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st) {
-    if (pl.d == 64) launch_fl<64>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
-    else launch_fl<128>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, st);
+                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st,
+                                 const float* W_out) {
+    if (W_out != nullptr && (O_nla_out != nullptr || O == nullptr)) {
+        set_error("flash_softmax: weights by Eq. 22 inside the kernel need the merge without the fp32 side output");
+        return NATS_ERR_UNSUPPORTED;
+    }
+    if (pl.d == 64) launch_fl<64>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, W_out, st);
+    else launch_fl<128>(pl, Q, Kc, VhT, K, V, cnt, O_la, w_nla, w_la, O, O_nla_out, lse_out, W_out, st);
     return check_launch("flash_softmax");
 }
 

@@ -241,7 +241,8 @@ nats_status launch_softmax_fp32(const FwdPlan& pl, const void* Q, const void* Kc
 nats_status launch_flash_softmax(const FwdPlan& pl, const void* Q, const void* Kc, const void* VhT,
                                  const void* K, const void* V,
                                  const int32_t* cnt, const void* O_la, const float* w_nla,
-                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st);
+                                 const float* w_la, void* O, float* O_nla_out, float* lse_out, hipStream_t st,
+                                 const float* W_out = nullptr);   // W_out: Eq. 22 inside the kernel (see the launcher)
 nats_status launch_decode(const nats_dec_params& p, float softmax_scale, float la_scale, float eps,
                           float* state, void* k_cache, void* v_cache, int32_t* cache_len, const void* q,
                           const void* k, const void* v, const float* alpha, const float* beta,
