@@ -63,15 +63,18 @@ __device__ __forceinline__ float quad_sum(float x) {
 // chunk_routing: routing per chunk (a template parameter: the per-token kernel carries none of its code)
 // STATS: what the backward pass needs from this branch's forward, to fp32 accuracy: the weights enter the second
 // product (and their sum) as the sum of two fp16 terms, and only O_nla_out (fp32) and lse_out are written; no merge.
-template <int D, bool chunk_routing, bool STATS>
+// MERGED: the merges other than the plain sum (combine_mode 1, 2) and Eq. 22; the plain sum's instantiation carries
+// none of their code.
+template <int D, bool chunk_routing, bool STATS, bool MERGED>
 __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kc, const half_t* __restrict__ VhT,
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ cnt, const half_t* __restrict__ O_la, const float* __restrict__ w_nla,
     const float* __restrict__ w_la, bf16_t* __restrict__ O,
-    float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode,
+    float* __restrict__ O_nla_out, float* __restrict__ lse_out, int L, float scale, int combine_mode_arg,
     float eps, int BH, int G, int qk_per_out_head, int own_chunk, const float* __restrict__ W_out, int weight_act,
     int heads_out) {
+    const int combine_mode = MERGED ? combine_mode_arg : 0;
     constexpr int RS = D + LDS_PAD;      // K / Q tile rows (bf16 elements)
     constexpr int TS = FL_BN + LDS_PAD;  // V^T tile rows (fp16 elements)
     constexpr int OS = D + 4;            // output staging rows (fp32 elements)
@@ -386,8 +389,8 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
         // product's operand (lane (l16, lq) holds columns 32 ks + 8 lq .. + 7 of query l16): 8 D / 16 multiply-adds per
         // lane, a sum over the four lanes of the query, the activation; the weights go through LDS to the lanes that
         // merge the row.
-        __shared__ float s_w[2][FL_BM];
-        const bool fused_w = combine_mode != 0 && W_out != nullptr;
+        __shared__ float s_w[MERGED ? 2 : 1][MERGED ? FL_BM : 1];
+        const bool fused_w = MERGED && combine_mode != 0 && W_out != nullptr;
         if (fused_w) {
             const float* w0 = W_out + (size_t)(bh % heads_out) * 2 * D;
             float lg[FL_NQ][2];
@@ -590,25 +593,40 @@ static void launch_fl(const FwdPlan& pl, const void* Q, const void* Kc, const vo
     dim3 grid((unsigned)(((pl.L + FL_BM - 1) / FL_BM) * ((pl.BHG + 7) & ~7)));
     if (O == nullptr) {   // the backward pass's call: branch output and log-sum-exp only
         if (pl.routing == NATS_ROUTE_CHUNK)
-            hipLaunchKernelGGL((flash_softmax_kernel<D, true, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+            hipLaunchKernelGGL((flash_softmax_kernel<D, true, true, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                                (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
                                nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
                                pl.G, pl.qk_per_out_head, pl.inner_chunk != 2, nullptr, 0, 1);
         else
-            hipLaunchKernelGGL((flash_softmax_kernel<D, false, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+            hipLaunchKernelGGL((flash_softmax_kernel<D, false, true, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                                (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt, nullptr,
                                nullptr, nullptr, nullptr, O_nla_out, lse_out, pl.L, pl.softmax_scale, 0, pl.rms_eps, pl.BHG,
                                pl.G, pl.qk_per_out_head, pl.inner_chunk != 2, nullptr, 0, 1);
         return;
     }
+    if (pl.combine_mode != 0) {   // Eq. 21, its ablation, Eq. 22: the instantiation with their code
+        if (pl.routing == NATS_ROUTE_CHUNK)
+            hipLaunchKernelGGL((flash_softmax_kernel<D, true, false, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                               (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
+                               (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
+                               pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
+                               W_out, pl.weight_act, pl.H * pl.G);
+        else
+            hipLaunchKernelGGL((flash_softmax_kernel<D, false, false, true>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+                               (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
+                               (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
+                               pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
+                               W_out, pl.weight_act, pl.H * pl.G);
+        return;
+    }
     if (pl.routing == NATS_ROUTE_CHUNK)
-        hipLaunchKernelGGL((flash_softmax_kernel<D, true, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, true, false, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
                            W_out, pl.weight_act, pl.H * pl.G);
     else
-        hipLaunchKernelGGL((flash_softmax_kernel<D, false, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
+        hipLaunchKernelGGL((flash_softmax_kernel<D, false, false, false>), grid, dim3(FL_THREADS), 0, st, (const bf16_t*)Q,
                            (const bf16_t*)Kc, (const half_t*)VhT, (const bf16_t*)K, (const bf16_t*)V, cnt,
                            (const half_t*)O_la, w_nla, w_la, (bf16_t*)O, O_nla_out, lse_out, pl.L,
                            pl.softmax_scale, pl.combine_mode, pl.rms_eps, pl.BHG, pl.G, pl.qk_per_out_head, pl.inner_chunk != 2,
