@@ -240,6 +240,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--preheat-kind", choices=("copy", "mfma", "mix"), default="mfma",
+                    help="what keeps the chip busy: device copies, the matrix-instruction probe, or both in turn")
+    ap.add_argument("--preheat-ms", type=float, default=200.0,
+                    help="keep the chip busy with work that is no part of the path for about this long before the "
+                         "warm-up steps, so that they start at operating clocks (0: off)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy: the known-size dispatch against which "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -308,6 +313,29 @@ def main():
         nats.hybrid_attn_fwd(Q, K, V, alpha, beta, mask, cfg.C, routing=routing, out=O, workspace=ws,
                              gdn_segments=args.gdn_segments)
 
+    preheat_ms = 0.0
+    if args.preheat_ms > 0:
+        # A GPU that has been idle (a fresh box, the seconds of input generation above) runs its first tens of
+        # milliseconds of work below its operating clocks: measured here, 20 steps after 5 warm-up steps take 0.27 ms
+        # each from idle and 0.238 ms after 200 ms of any matrix-core load, the same as after 200 or 1000 warm-up steps
+        # of the path itself.  So before the warm-up steps the chip is kept busy for about preheat_ms with work that is
+        # no part of the path (the matrix-instruction probe of nats_measure.h, a chip-filling loop of independent MFMA;
+        # or device copies, which bring the clocks up only part of the way: 0.249 ms), and the W + K steps run at the
+        # clocks a running service sees.  The line reports "preheat_ms" and "preheat_kind"; --preheat-ms 0 turns it off.
+        if args.preheat_kind in ("copy", "mix"):
+            src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+            dst = torch.empty_like(src)
+        scratch = torch.empty(4096, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        while (time.perf_counter() - p0) * 1e3 < args.preheat_ms:
+            if args.preheat_kind in ("copy", "mix"):
+                for _ in range(20):
+                    dst.copy_(src)
+            if args.preheat_kind in ("mfma", "mix"):
+                nb.probe_mfma(4000, scratch)
+            torch.cuda.synchronize()
+        preheat_ms = (time.perf_counter() - p0) * 1e3
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -445,6 +473,8 @@ def main():
         out["graph_replay_ms_per_step"] = round(graph_ms, 4)
     flop_total = 4.0 * cfg.d * sum_cnt + (10.0 * cfg.C * cfg.d + 6.0 * cfg.d ** 2 + cfg.C ** 2 / 3.0) * cfg.B * cfg.H * cfg.L
     out["algorithmic_TFLOPs"] = round(flop_total / (ms_per_step * 1e-3) / 1e12, 2)
+    out["preheat_ms"] = round(preheat_ms, 1)
+    out["preheat_kind"] = args.preheat_kind if preheat_ms > 0 else None
     out["mfma_frac_whole_forward"] = round(flop_total / (ms_per_step * 1e-3) / 1e12 / PEAK["mfma"][0], 4)
     tr = [measured_traffic_bytes(k) for k in per_step]
     measured = sum(tr) if tr and all(t is not None for t in tr) else None
