@@ -81,7 +81,32 @@ def measured_mfma_busy(kernel):
         return None
 
 
-def measure_decode(steps, warmup, split=True):
+def preheat_chip(ms, kind="mfma"):
+    """Keeps the chip busy for about `ms` with work that is no part of the path, so that what follows starts at
+    operating clocks (see the note where the forward's steps are timed).  Returns the milliseconds it took."""
+    import torch
+
+    from paper_2602_03681_amd import binding as nb
+    if ms <= 0:
+        return 0.0
+    dev = torch.device("cuda:0")
+    if kind in ("copy", "mix"):
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+    scratch = torch.empty(4096, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    p0 = time.perf_counter()
+    while (time.perf_counter() - p0) * 1e3 < ms:
+        if kind in ("copy", "mix"):
+            for _ in range(20):
+                dst.copy_(src)
+        if kind in ("mfma", "mix"):
+            nb.probe_mfma(4000, scratch)
+        torch.cuda.synchronize()
+    return (time.perf_counter() - p0) * 1e3
+
+
+def measure_decode(steps, warmup, split=True, preheat_ms=200.0):
     """Decode workload (B=64, H=16, d=128, bf16, cache length U{64..2048}): HBM-bound streaming of the
     fp32 state (read + write) and the live cache rows, one call per token.  split: the step runs on a caller
     workspace as many blocks of equal size (two launches) instead of one block per (batch, head)."""
@@ -112,6 +137,7 @@ def measure_decode(steps, warmup, split=True):
         nats.hybrid_attn_decode(g["state"], g["k_cache"], g["v_cache"], g["cache_len"], g["q"][i], g["k"][i],
                                 g["v"][i], g["alpha"][i], g["beta"][i], g["mask"][i], out=o, workspace=ws)
 
+    preheat_chip(preheat_ms)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -142,15 +168,16 @@ def measure_decode(steps, warmup, split=True):
 
 
 def bench_decode(args):
-    out = measure_decode(args.steps, args.warmup, split=not args.decode_one_block)
+    out = measure_decode(args.steps, args.warmup, split=not args.decode_one_block, preheat_ms=args.preheat_ms)
     print(json.dumps(out))
 
 
 def bench_backward(args):
-    print(json.dumps(measure_backward(args.steps, args.warmup, args.routing, args.backward_by_tokens, args.combine_mode)))
+    print(json.dumps(measure_backward(args.steps, args.warmup, args.routing, args.backward_by_tokens, args.combine_mode,
+                                      preheat_ms=args.preheat_ms)))
 
 
-def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False, combine_mode=0):
+def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False, combine_mode=0, preheat_ms=200.0):
     """Backward pass on workload 2's shapes (bf16 tensors, fp32 gradients): a step is one nats_hybrid_attn_bwd call.
     The linear branch's adjoint runs by chunks on fp32 matrix instructions (operands per chunk, states forwards,
     state gradients backwards, then every chunk's gradients); the softmax branch's products run on fp16 / bf16 matrix
@@ -188,6 +215,7 @@ def measure_backward(steps_in, warmup_in, routing_name="token", by_tokens=False,
                                     combine_mode=combine_mode)
 
     steps = max(1, min(steps_in, 20))
+    preheat_chip(preheat_ms)
     for _ in range(max(1, min(warmup_in, 3))):
         step()
     torch.cuda.synchronize()
@@ -322,20 +350,7 @@ def main():
         # no part of the path (the matrix-instruction probe of nats_measure.h, a chip-filling loop of independent MFMA;
         # or device copies, which bring the clocks up only part of the way: 0.249 ms), and the W + K steps run at the
         # clocks a running service sees.  The line reports "preheat_ms" and "preheat_kind"; --preheat-ms 0 turns it off.
-        if args.preheat_kind in ("copy", "mix"):
-            src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
-            dst = torch.empty_like(src)
-        scratch = torch.empty(4096, dtype=torch.float32, device=dev)
-        torch.cuda.synchronize()
-        p0 = time.perf_counter()
-        while (time.perf_counter() - p0) * 1e3 < args.preheat_ms:
-            if args.preheat_kind in ("copy", "mix"):
-                for _ in range(20):
-                    dst.copy_(src)
-            if args.preheat_kind in ("mfma", "mix"):
-                nb.probe_mfma(4000, scratch)
-            torch.cuda.synchronize()
-        preheat_ms = (time.perf_counter() - p0) * 1e3
+        preheat_ms = preheat_chip(args.preheat_ms, args.preheat_kind)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -460,12 +475,12 @@ def main():
         # the decode workload beside the headline figure (30 steps after 5): tokens/s and its HBM roofline
         del Q, K, V, O, ws
         torch.cuda.empty_cache()
-        dec = measure_decode(30, 5)
+        dec = measure_decode(30, 5, preheat_ms=args.preheat_ms)
         out["decode"] = {k: dec[k] for k in ("metric", "value", "unit", "ms_per_step", "config", "kernels_ms", "roofline")}
     if not args.no_backward_line:
         # ... and the backward pass on the headline shapes (10 calls after 2)
         torch.cuda.empty_cache()
-        bw = measure_backward(10, 2, args.routing)
+        bw = measure_backward(10, 2, args.routing, preheat_ms=args.preheat_ms)
         out["backward"] = {k: bw[k] for k in ("metric", "value", "unit", "ms_per_step", "config", "kernels_ms", "roofline")}
     if measured_peaks is not None:
         out["measured_peaks"] = measured_peaks
