@@ -224,6 +224,17 @@ def test_binding_refuses_cpu_tensors():
         nb.hybrid_attn_fwd(x, x, x, a, a, m)
 
 
+def test_autograd_wrapper_has_no_cpu_path():
+    """The differentiable function is the same two library calls: CPU tensors are refused, nothing is computed here."""
+    import torch
+    import paper_2602_03681_amd as nats
+    x = torch.zeros((1, 1, 64, 64), requires_grad=True)
+    a = torch.zeros((1, 1, 64))
+    m = torch.zeros((1, 1, 64), dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        nats.hybrid_attn(x, x, x, a, a, m)
+
+
 def test_noalloc_forward_rejects_large_problems_on_the_host(lib):
     """The entry point without allocation checks the size against its built-in buffer before anything touches a
     device: too large a problem is an error, and so are bad parameters."""
