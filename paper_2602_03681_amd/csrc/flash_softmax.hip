@@ -488,9 +488,10 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                     ssl += (float)b[j] * (float)b[j];
                 }
                 float wn = wn_row[pass], wl = wl_row[pass];
+                // (the hardware's reciprocal square root, one ulp: the rows are rounded to bf16 right after)
                 if (combine_mode == 1) {   // Eq. 21: each branch normalised, then weighted
-                    wn /= sqrtf(lane_group_sum<LPR_H>(ssn) / D + eps);
-                    wl /= sqrtf(lane_group_sum<LPR_H>(ssl) / D + eps);
+                    wn *= __builtin_amdgcn_rsqf(lane_group_sum<LPR_H>(ssn) * (1.f / D) + eps);
+                    wl *= __builtin_amdgcn_rsqf(lane_group_sum<LPR_H>(ssl) * (1.f / D) + eps);
                 }
                 float ss = 0.f;
 #pragma unroll
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                     ss += o[j] * o[j];
                 }
                 if (combine_mode == 2) {   // one normalisation of the weighted sum
-                    const float inv = 1.f / sqrtf(lane_group_sum<LPR_H>(ss) / D + eps);
+                    const float inv = __builtin_amdgcn_rsqf(lane_group_sum<LPR_H>(ss) * (1.f / D) + eps);
 #pragma unroll
                     for (int j = 0; j < 8; ++j) o[j] *= inv;
                 }
