@@ -391,6 +391,18 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
         // merge the row.
         __shared__ float s_w[MERGED ? 2 : 1][MERGED ? FL_BM : 1];
         const bool fused_w = MERGED && combine_mode != 0 && W_out != nullptr;
+        u32x4 la_rows[FL_NQ * 16 / RPP_H];   // the linear branch's rows (fp16), asked for up front (before the
+        // weights' dot products below, which cover part of their latency)
+        float wn_row[FL_NQ * 16 / RPP_H], wl_row[FL_NQ * 16 / RPP_H];   // the rows' weights (Eq. 21 and its ablation)
+        const float w_default = combine_mode == 1 ? 0.5f : 1.f;
+#pragma unroll
+        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
+            const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
+            const size_t tok = tokbase + (q < L ? q : 0);
+            la_rows[pass] = *reinterpret_cast<const u32x4*>(O_la + tok * D + 8 * (lane % LPR_H));
+            wn_row[pass] = (combine_mode != 0 && !fused_w && w_nla != nullptr) ? w_nla[tok] : w_default;
+            wl_row[pass] = (combine_mode != 0 && !fused_w && w_la != nullptr) ? w_la[tok] : w_default;
+        }
         if (fused_w) {
             const float* w0 = W_out + (size_t)(bh % heads_out) * 2 * D;
             float lg[FL_NQ][2];
@@ -437,17 +449,6 @@ __global__ __launch_bounds__(FL_THREADS, FL_OCC) void flash_softmax_kernel(
                     s_w[1][(wave * FL_NQ + nq) * 16 + l16] = wb;
                 }
             }
-        }
-        u32x4 la_rows[FL_NQ * 16 / RPP_H];   // the linear branch's rows (fp16), asked for up front
-        float wn_row[FL_NQ * 16 / RPP_H], wl_row[FL_NQ * 16 / RPP_H];   // the rows' weights (Eq. 21 and its ablation)
-        const float w_default = combine_mode == 1 ? 0.5f : 1.f;
-#pragma unroll
-        for (int pass = 0; pass < FL_NQ * 16 / RPP_H; ++pass) {
-            const int q = q0 + wave * FL_NQ * 16 + pass * RPP_H + lane / LPR_H;
-            const size_t tok = tokbase + (q < L ? q : 0);
-            la_rows[pass] = *reinterpret_cast<const u32x4*>(O_la + tok * D + 8 * (lane % LPR_H));
-            wn_row[pass] = (combine_mode != 0 && !fused_w && w_nla != nullptr) ? w_nla[tok] : w_default;
-            wl_row[pass] = (combine_mode != 0 && !fused_w && w_la != nullptr) ? w_la[tok] : w_default;
         }
 #pragma unroll
         for (int nq = 0; nq < FL_NQ; ++nq) {
