@@ -375,23 +375,3 @@ def test_backward_through_the_merges_degenerate_masks(kind, mode):
     scale = float(np.sqrt(np.mean(np.sum(dO.astype(np.float64) ** 2, axis=-1)) * d))
     for key in ("dw_nla", "dw_la"):
         assert np.max(np.abs(host(r[key]) - ref[key])) <= TOL_BWD * scale, key
-
-
-def test_backward_cfg2_headline_size_sampled_heads():
-    """The backward pass at the headline size, in the configuration bench.py --backward times (B=2, H=16, L=8192,
-    d=128, bf16 tensors, plain sum, routing per token, the linear adjoint by chunks): every gradient of three
-    (batch, head) pairs spread over the launch, the first and the last among them, against the oracle run on those
-    heads (heads are independent; the oracle takes about 12 s per head)."""
-    from nats_inputs import CONFIGS, make_config_inputs
-    cfg = CONFIGS["cfg2_headline_bf16"]
-    x = make_config_inputs(cfg)
-    dO = make_grad_output(cfg.B, cfg.H, cfg.L, cfg.d, "bf16", seed=cfg.seed + 7)
-    r = run_bwd(x, dO, "bf16", want=("g_nla", "g_la"))
-    got = {k: host(v) for k, v in r.items()}
-    for b, h in ((0, 0), (0, 9), (cfg.B - 1, cfg.H - 1)):
-        ref = nbw.hybrid_head_bwd(x["Q"][b, h], x["K"][b, h], x["V"][b, h], x["alpha"][b, h], x["beta"][b, h],
-                                  x["mask"][b, h], dO[b, h])
-        errs = {k: rel_err(got[k][b, h], ref[k]) for k in ("dQ", "dK", "dV", "dalpha", "dbeta", "g_nla", "g_la")}
-        print((b, h), errs, flush=True)
-        for k, e in errs.items():
-            assert e <= TOL_BWD, f"head {(b, h)} {k}: {e:.3e}"
